@@ -1,0 +1,95 @@
+"""ctypes loader for the C oracle (oracle/nimble_oracle.c) plus a numpy congestion evaluator.
+
+Test infrastructure only: see the header of nimble_oracle.c.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "nimble_oracle.c")
+_LIB = os.path.join(_HERE, "libnimble_oracle.so")
+_lib = None
+
+
+def build(force: bool = True) -> str:
+    """Compile the oracle with gcc.  -ffp-contract=off keeps every statement one IEEE op."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared",
+               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build(force=False)
+        lib = ctypes.CDLL(_LIB)
+        lib.nimble_oracle_solve.restype = ctypes.c_int
+        lib.nimble_oracle_solve.argtypes = [
+            ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_double, ctypes.c_int32,
+            ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p]
+        lib.nimble_oracle_max_threads.restype = ctypes.c_int
+        lib.nimble_oracle_set_threads.argtypes = [ctypes.c_int]
+        _lib = lib
+    return _lib
+
+
+def max_threads() -> int:
+    return int(_load().nimble_oracle_max_threads())
+
+
+def set_threads(n: int) -> None:
+    _load().nimble_oracle_set_threads(int(n))
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def solve(n_links, cap, n_comm, comm_path_ptr, n_paths, path_link_ptr, path_links, demand,
+          eps, iters, flags=0, want_lb=False):
+    """Run the oracle.  Returns dict(splits, lam, count, sumload[, lb])."""
+    cap = np.ascontiguousarray(cap, dtype=np.float64)
+    cp = np.ascontiguousarray(comm_path_ptr, dtype=np.int32)
+    lp = np.ascontiguousarray(path_link_ptr, dtype=np.int32)
+    pl = np.ascontiguousarray(path_links, dtype=np.int32)
+    d = np.ascontiguousarray(demand, dtype=np.float64)
+    assert cap.shape == (n_links,) and cp.shape == (n_comm + 1,) and lp.shape == (n_paths + 1,)
+    assert d.shape == (n_comm,) and pl.shape == (int(lp[-1]),)
+    splits = np.empty(n_paths, dtype=np.float64)
+    lam = np.zeros(1, dtype=np.float64)
+    count = np.empty(n_paths, dtype=np.uint32)
+    sumload = np.empty(n_links, dtype=np.float64)
+    lb = np.empty(iters, dtype=np.float64) if want_lb else None
+    rc = _load().nimble_oracle_solve(n_links, _p(cap), n_comm, _p(cp), n_paths, _p(lp), _p(pl),
+                                     _p(d), float(eps), int(iters), int(flags), _p(splits),
+                                     _p(lam), _p(count), _p(sumload), _p(lb))
+    if rc != 0:
+        raise ValueError(f"nimble_oracle_solve failed with code {rc}")
+    out = dict(splits=splits, lam=float(lam[0]), count=count, sumload=sumload)
+    if want_lb:
+        out["lb"] = lb
+    return out
+
+
+def congestion(n_links, cap, comm_path_ptr, path_link_ptr, path_links, demand, splits):
+    """max_e (1/cap_e) * sum_{p through e} d_k(p) * x_p  -- the objective of Eq. (1)-(3) in
+    capacity-normalized path form, evaluated for given split fractions."""
+    cp = np.asarray(comm_path_ptr, dtype=np.int64)
+    lp = np.asarray(path_link_ptr, dtype=np.int64)
+    path_comm = np.repeat(np.arange(len(cp) - 1), np.diff(cp))
+    flow = np.asarray(demand, dtype=np.float64)[path_comm] * np.asarray(splits, dtype=np.float64)
+    inc_path = np.repeat(np.arange(len(lp) - 1), np.diff(lp))
+    load = np.bincount(np.asarray(path_links, dtype=np.int64), weights=flow[inc_path],
+                       minlength=n_links)
+    util = load / np.asarray(cap, dtype=np.float64)
+    return float(util.max()), util
