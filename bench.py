@@ -1,0 +1,201 @@
+#!/usr/bin/env python3
+"""Planner benchmark on one MI355X.
+
+A step is one complete plan (prologue, all Jacobi MWU iterations, epilogue) of the largest
+benchmark configuration -- 64 modeled nodes x 8 GPUs, 261 632 commodities, 8.3 M candidate
+paths, 39.3 M path-link incidences, 1000 iterations -- with topology and traffic resident in
+HBM before the timed region.  Prints one JSON line: MWU iterations/s (value), plans/s, the
+roofline of the dominant kernel from HIP-event timing, and the CPU oracle timed on the host
+cores on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+
+def phase_bytes(topo_np, lib_topo):
+    """Stored bytes each streaming-regime kernel has to move per launch (indices as stored:
+    int32 link ids and pointers, 32-bit packed reverse entries padded to 16 B per row)."""
+    K, P, E, nnz = topo_np.n_comm, topo_np.n_paths, topo_np.n_links, topo_np.nnz
+    total = lib_topo.bytes_per_iter
+    argmin = 4 * (K + 1) + 4 * (P + 1) + 4 * nnz + 9 * K
+    update_fixed = 4 * (E + 1) + 56 * E
+    # what is left is the reverse stream with its chunk table and partials
+    reduce_ = total - argmin - update_fixed
+    return dict(argmin=argmin, load_reduce=reduce_, update=update_fixed, total=total)
+
+
+def time_phase(B, torch, h, phase, reps, d_traffic):
+    start = torch.cuda.Event(enable_timing=True)
+    stop = torch.cuda.Event(enable_timing=True)
+    B.nimble_debug_run_phase(h, phase, 3, d_traffic)
+    torch.cuda.synchronize()
+    start.record()
+    B.nimble_debug_run_phase(h, phase, reps, d_traffic)
+    stop.record()
+    torch.cuda.synchronize()
+    return start.elapsed_time(stop) * 1e-3 / reps
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=1)
+    ap.add_argument("--config", type=int, default=4, help="benchmark configuration 0..4")
+    ap.add_argument("--regime", type=int, default=0, help="0 auto, 1 resident, 2 stream, 3 persistent")
+    ap.add_argument("--cpu-iters", type=int, default=-1,
+                    help="oracle iterations for the CPU baseline (-1: sized to ~10-30 s, 0: skip)")
+    ap.add_argument("--batch", type=int, default=4096)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (the planner models the whole "
+              "fabric on one device); --gpus must be 1", file=sys.stderr)
+        return 2
+
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    from paper_2604_00317_amd import binding as B
+    from paper_2604_00317_amd import workloads as W
+    B.load_library(build_if_missing=True)
+
+    t_gen = time.perf_counter()
+    w = W.make_config(args.config, batch=args.batch if args.config == 2 else None)
+    topo = w.topo
+    t_gen = time.perf_counter() - t_gen
+    dev = "cuda:0"
+    t_create = time.perf_counter()
+    h = B.nimble_topo_create(*topo.csr())
+    t_create = time.perf_counter() - t_create
+    B.nimble_topo_set_regime(h, args.regime)
+
+    batch = max(w.batch, 1)
+    d_traffic = torch.as_tensor(np.ascontiguousarray(w.traffic).reshape(-1)).to(dev)
+    d_splits = torch.empty(batch * topo.n_paths, dtype=torch.float64, device=dev)
+    d_lambda = torch.empty(batch, dtype=torch.float64, device=dev)
+
+    def step():
+        if w.batch:
+            B.nimble_plan_solve_batch(h, batch, d_traffic, w.eps, w.iters, d_splits, d_lambda)
+        else:
+            B.nimble_plan_solve(h, d_traffic, w.eps, w.iters, d_splits, d_lambda)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(args.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ev_ms = ev0.elapsed_time(ev1)
+    regime = h.regime
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    iters_per_s = w.iters * batch * args.steps / elapsed
+    plans_per_s = batch * args.steps / elapsed
+    lam = d_lambda.cpu().numpy()
+
+    # ---- roofline of the dominant kernel ------------------------------------------------
+    bytes_ = phase_bytes(topo, h)
+    roofline = None
+    kernels = {}
+    if regime == B.NIMBLE_REGIME_STREAM:
+        names = ["argmin", "load_reduce", "update"]
+        for ph, name in enumerate(names):
+            sec = time_phase(B, torch, h, ph, 200, d_traffic)
+            kernels[name] = dict(avg_us=sec * 1e6, bytes=bytes_[name],
+                                 gbs=bytes_[name] / sec / 1e9)
+        dom = max(names, key=lambda n: kernels[n]["avg_us"])
+        roofline = dict(bound="hbm", kernel=dom, achieved=kernels[dom]["gbs"],
+                        peak=HBM_PEAK_GBS, unit="GB/s",
+                        frac=kernels[dom]["gbs"] / HBM_PEAK_GBS, traffic=None,
+                        whole_iteration_gbs=bytes_["total"] * w.iters * args.steps / elapsed / 1e9)
+    else:
+        # one kernel per step: its duration is the step time measured with HIP events
+        sec = ev_ms * 1e-3 / args.steps
+        total = bytes_["total"] * w.iters * batch
+        roofline = dict(bound="hbm", kernel="resident" if regime == 1 else "persistent",
+                        achieved=total / sec / 1e9, peak=HBM_PEAK_GBS, unit="GB/s",
+                        frac=total / sec / 1e9 / HBM_PEAK_GBS, traffic=None)
+
+    # ---- CPU baseline: the oracle on a bounded sample -------------------------------------
+    cpu = None
+    if args.cpu_iters != 0:
+        import oracle
+        cores = oracle.max_threads()
+        if w.batch:
+            n_plans = 64 if args.cpu_iters < 0 else max(1, args.cpu_iters)
+            t1 = time.perf_counter()
+            worst = 0.0
+            for b in range(n_plans):
+                ref = oracle.solve(*topo.csr(), w.traffic[b], w.eps, w.iters)
+                worst = max(worst, abs(lam[b] - ref["lam"]) / max(ref["lam"], 1e-300))
+            dt = time.perf_counter() - t1
+            cpu = dict(value=w.iters * n_plans / dt, unit="iterations/s", cores=cores,
+                       kind="oracle", plans_per_s=n_plans / dt,
+                       sample=f"first {n_plans} of {batch} plans, all {w.iters} iterations",
+                       max_rel_diff_lambda=worst)
+        else:
+            n_it = args.cpu_iters
+            if n_it < 0:
+                t1 = time.perf_counter()
+                oracle.solve(*topo.csr(), w.traffic, w.eps, 2)
+                per_it = (time.perf_counter() - t1) / 2
+                n_it = int(max(4, min(w.iters, 15.0 / max(per_it, 1e-6))))
+            t1 = time.perf_counter()
+            ref = oracle.solve(*topo.csr(), w.traffic, w.eps, n_it)
+            dt = time.perf_counter() - t1
+            # parity of the same shortened run on the GPU
+            B.nimble_plan_solve(h, d_traffic, w.eps, n_it, d_splits, d_lambda)
+            torch.cuda.synchronize()
+            g_s = d_splits.cpu().numpy()
+            g_l = float(d_lambda.item())
+            cpu = dict(value=n_it / dt, unit="iterations/s", cores=cores, kind="oracle",
+                       plans_per_s=1.0 / (dt * w.iters / n_it),
+                       sample=f"first {n_it} of {w.iters} iterations, all commodities",
+                       max_abs_diff_splits=float(np.abs(g_s - ref["splits"]).max()),
+                       max_rel_diff_lambda=abs(g_l - ref["lam"]) / max(ref["lam"], 1e-300))
+
+    out = {
+        "metric": "mwu_iterations_per_s", "value": iters_per_s, "unit": "iterations/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64",
+        "data": "synthetic",
+        "config": {"workload": f"configs[{args.config}] {w.name}", "commodities": topo.n_comm,
+                   "paths": topo.n_paths, "incidences": topo.nnz, "links": topo.n_links,
+                   "eps": w.eps, "iters": w.iters, "batch": batch,
+                   "regime": {1: "resident", 2: "stream", 3: "persistent"}.get(regime, "auto")},
+        "plans_per_s": plans_per_s,
+        "lambda": float(lam[0]),
+        "bytes_per_iter": bytes_["total"],
+        "roofline": roofline,
+        "kernels": kernels,
+        "cpu_baseline": cpu,
+        "setup_s": {"generate": t_gen, "topo_create": t_create},
+    }
+    h.close()
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -1,0 +1,164 @@
+/*
+ * nimble_plan.h -- C ABI of the MI355X execution-time planner.
+ *
+ * The planner solves the minimum-congestion routing problem of Eq. (1)-(5) (Sec. IV-B,
+ * "Hop-Adaptive MCF load balancing") in its fractional, path-based, capacity-normalized form
+ * with a Jacobi multiplicative-weights iteration (the Garg-Koenemann scheme the section
+ * cites): every iteration routes each commodity on its currently cheapest candidate path
+ * (strict `<` in list order, as the candidate scan of Algorithm 1), accumulates link loads
+ * (Algorithm 1, L_e <- L_e + f), and multiplies the length of every link by
+ * (1 + eps * u_e / rho), u_e = load_e / cap_e.  Outputs are the fraction of iterations each
+ * candidate was chosen and the maximum link congestion lambda of that split.
+ *
+ * All arithmetic is IEEE binary64 without fused multiply-add.  Index arrays are int32.
+ * "host" pointers are ordinary CPU memory; "device" pointers are HIP device memory on the
+ * GPU that was current when the topology was created.  The library never frees or keeps a
+ * pointer the caller passed; nimble_topo_create copies what it needs.
+ *
+ * Threading: a nimble_topo_t owns one workspace, so at most ONE solve may be in flight per
+ * topology at a time (enqueue the next solve on the same stream, or synchronise first).
+ * nimble_last_error() is thread-local.
+ */
+#ifndef NIMBLE_PLAN_H
+#define NIMBLE_PLAN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct nimble_topo nimble_topo_t; /* opaque, owned by the library */
+
+typedef enum {
+    NIMBLE_OK = 0,
+    NIMBLE_ERR_INVALID = 1, /* bad argument: null pointer, malformed CSR, eps/iters out of domain */
+    NIMBLE_ERR_ALLOC = 2,   /* host or device allocation failed */
+    NIMBLE_ERR_HIP = 3,     /* a HIP runtime call failed (message in nimble_last_error) */
+    NIMBLE_ERR_RANGE = 4    /* valid input beyond a documented limit of this build */
+} nimble_status_t;
+
+/* flags of nimble_topo_create */
+enum {
+    NIMBLE_COST_SUM = 0u, /* path cost = sum of link prices, price = len/cap (default) */
+    NIMBLE_COST_MAX = 1u  /* path cost = max of link prices, price = len: the bottleneck
+                             rule of Sec. IV-B (intra-node 2-hop and inter-node path costs) */
+};
+
+/* kernel regimes, for nimble_topo_set_regime (testing and benchmarking) */
+enum {
+    NIMBLE_REGIME_AUTO = 0,     /* chosen from the problem size */
+    NIMBLE_REGIME_RESIDENT = 1, /* one workgroup per plan, whole iteration loop in one kernel,
+                                   state in LDS */
+    NIMBLE_REGIME_STREAM = 2,   /* three kernels per iteration streaming the two CSRs */
+    NIMBLE_REGIME_PERSISTENT = 3 /* one persistent kernel per solve with grid-wide barriers */
+};
+
+/*
+ * Build a topology: links with capacities and, per commodity, the ordered list of candidate
+ * paths as a two-level CSR (the sets E, K and the candidate paths of Sec. IV-B / Algorithm 1).
+ *
+ *   n_links        number of directed links, >= 1
+ *   cap            host [n_links], bytes/s, finite and > 0
+ *   n_comm         number of commodities (source-destination pairs), 1 <= n_comm < 2^24 - 1
+ *   comm_path_ptr  host [n_comm+1], comm_path_ptr[0] = 0, strictly increasing,
+ *                  comm_path_ptr[n_comm] = n_paths; commodity k owns candidate paths
+ *                  comm_path_ptr[k] .. comm_path_ptr[k+1]-1, in tie-break order; at most 127
+ *                  candidates per commodity
+ *   n_paths        total number of candidate paths
+ *   path_link_ptr  host [n_paths+1], path_link_ptr[0] = 0, strictly increasing
+ *   path_links     host [path_link_ptr[n_paths]], link ids in [0, n_links), no link twice in
+ *                  one path; the order inside a path is the order costs are added in
+ *   flags          NIMBLE_COST_SUM or NIMBLE_COST_MAX
+ *   out            receives the handle; release it with nimble_topo_destroy
+ *
+ * Validation happens here, on the host, before any device call: malformed input returns
+ * NIMBLE_ERR_INVALID, sizes beyond the limits above NIMBLE_ERR_RANGE.  The reverse
+ * link -> (commodity, path) CSR is built here (stable counting sort, ascending
+ * (commodity, path) inside every link) and uploaded with the forward CSR.
+ */
+nimble_status_t nimble_topo_create(int32_t n_links, const double *cap,
+                                   int32_t n_comm, const int32_t *comm_path_ptr,
+                                   int32_t n_paths, const int32_t *path_link_ptr,
+                                   const int32_t *path_links,
+                                   uint32_t flags, nimble_topo_t **out);
+
+/* Frees device and host memory of the topology.  NULL is ignored.  The caller must make sure
+ * no solve on this topology is still running. */
+void nimble_topo_destroy(nimble_topo_t *topo);
+
+/*
+ * One plan: split fractions and maximum congestion for one demand vector (the All-to-Allv
+ * byte matrix of Sec. III-A flattened to commodity order).
+ *
+ *   d_traffic   device [n_comm], bytes, finite and >= 0 (not checked: checking would need a
+ *               host synchronisation).  Results are bit-identical to the sequential
+ *               definition when demands are integer-valued with total < 2^53; otherwise they
+ *               are still identical from run to run, with loads summed in a fixed tree order.
+ *   eps         step size, 0 < eps <= 0.5
+ *   iters       number of Jacobi iterations, >= 1, iters * log1p(eps) <= 700 (else lengths
+ *               could overflow: NIMBLE_ERR_RANGE)
+ *   d_splits    device [n_paths] out: times chosen / iters; sums to 1 per commodity
+ *   d_lambda    device [1] out: max_e (1/cap_e) * sum_p d_k(p) splits_p, in seconds
+ *   hip_stream  hipStream_t (NULL = default stream).  The call only enqueues work; outputs are
+ *               valid after the stream is synchronised.  No host synchronisation inside.
+ */
+nimble_status_t nimble_plan_solve(nimble_topo_t *topo, const double *d_traffic, double eps,
+                                  int32_t iters, double *d_splits, double *d_lambda,
+                                  void *hip_stream);
+
+/*
+ * `batch` independent plans on the same topology (one per MoE layer x micro-batch), solved
+ * concurrently.  d_traffic is device [batch][n_comm], d_splits device [batch][n_paths],
+ * d_lambda device [batch]; the rest as nimble_plan_solve.  batch >= 1.  Topologies whose
+ * per-plan state does not fit in LDS are solved one plan after another on the stream.
+ */
+nimble_status_t nimble_plan_solve_batch(nimble_topo_t *topo, int32_t batch,
+                                        const double *d_traffic, double eps, int32_t iters,
+                                        double *d_splits, double *d_lambda, void *hip_stream);
+
+/* Last error message of the calling thread ("" if none). Never NULL. */
+const char *nimble_last_error(void);
+
+/* Size queries. */
+int32_t nimble_topo_num_links(const nimble_topo_t *topo);
+int32_t nimble_topo_num_comm(const nimble_topo_t *topo);
+int32_t nimble_topo_num_paths(const nimble_topo_t *topo);
+int64_t nimble_topo_nnz(const nimble_topo_t *topo);
+
+/* Bytes of the stored (device) representation that one iteration has to read or write:
+ * forward CSR, reverse CSR, and the per-link / per-commodity state.  This is the numerator
+ * of the bandwidth figure the benchmark reports. */
+int64_t nimble_topo_bytes_per_iter(const nimble_topo_t *topo);
+
+/* Force a kernel regime (NIMBLE_REGIME_*) for later solves; NIMBLE_ERR_RANGE if the topology
+ * does not fit that regime.  The regime actually used is returned by nimble_topo_regime. */
+nimble_status_t nimble_topo_set_regime(nimble_topo_t *topo, int32_t regime);
+int32_t nimble_topo_regime(const nimble_topo_t *topo);
+
+/*
+ * Benchmark helper: enqueue `reps` back-to-back launches of one phase of the streaming regime
+ * on `hip_stream`, without changing the plan state another solve depends on
+ * (phase 0: path-cost gather + argmin, 1: link-load reduce, 2: length update).  The state
+ * must have been initialised by a previous nimble_plan_solve on this topology with the same
+ * d_traffic.  Used to time a kernel's average launch with HIP events.
+ */
+nimble_status_t nimble_debug_run_phase(nimble_topo_t *topo, int32_t phase, int32_t reps,
+                                       const double *d_traffic, void *hip_stream);
+
+/*
+ * Host-only helper (no device call): the reverse CSR exactly as nimble_topo_create builds it,
+ * unpadded.  rev_ptr is host [n_links+1] out; rev_comm / rev_path are host [nnz] out (the
+ * commodity and the candidate index inside that commodity of every incidence).  Returns the
+ * same validation codes as nimble_topo_create.
+ */
+nimble_status_t nimble_host_build_reverse(int32_t n_links, int32_t n_comm,
+                                          const int32_t *comm_path_ptr, int32_t n_paths,
+                                          const int32_t *path_link_ptr,
+                                          const int32_t *path_links, int32_t *rev_ptr,
+                                          int32_t *rev_comm, int32_t *rev_path);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NIMBLE_PLAN_H */

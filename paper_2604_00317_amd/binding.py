@@ -1,0 +1,238 @@
+"""ctypes binding of libnimble_plan.so: argument marshalling only.
+
+The functions carry the names of the C ABI (include/nimble_plan.h).  Device buffers are torch
+tensors (torch is used for device memory and streams, nothing else); every step of a plan runs
+in the library's HIP kernels.  If the library is missing this module raises -- there is no
+fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libnimble_plan.so")
+
+NIMBLE_OK, NIMBLE_ERR_INVALID, NIMBLE_ERR_ALLOC, NIMBLE_ERR_HIP, NIMBLE_ERR_RANGE = range(5)
+NIMBLE_COST_SUM, NIMBLE_COST_MAX = 0, 1
+NIMBLE_REGIME_AUTO, NIMBLE_REGIME_RESIDENT, NIMBLE_REGIME_STREAM, NIMBLE_REGIME_PERSISTENT = \
+    range(4)
+
+EXPORTS = [
+    "nimble_topo_create", "nimble_topo_destroy", "nimble_plan_solve", "nimble_plan_solve_batch",
+    "nimble_last_error", "nimble_topo_num_links", "nimble_topo_num_comm",
+    "nimble_topo_num_paths", "nimble_topo_nnz", "nimble_topo_bytes_per_iter",
+    "nimble_topo_set_regime", "nimble_topo_regime", "nimble_debug_run_phase",
+    "nimble_host_build_reverse",
+]
+
+_lib = None
+
+
+class NimbleError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"nimble status {status}: {message}")
+        self.status = status
+
+
+def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
+    """Loads the in-tree library; builds it first only when no built library exists."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        if not build_if_missing:
+            raise FileNotFoundError(LIB_PATH)
+        from . import build as _build
+        _build.build()
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, u32, dbl = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32,
+                              ctypes.c_double)
+    lib.nimble_topo_create.restype = ctypes.c_int
+    lib.nimble_topo_create.argtypes = [i32, vp, i32, vp, i32, vp, vp, u32, ctypes.POINTER(vp)]
+    lib.nimble_topo_destroy.restype = None
+    lib.nimble_topo_destroy.argtypes = [vp]
+    lib.nimble_plan_solve.restype = ctypes.c_int
+    lib.nimble_plan_solve.argtypes = [vp, vp, dbl, i32, vp, vp, vp]
+    lib.nimble_plan_solve_batch.restype = ctypes.c_int
+    lib.nimble_plan_solve_batch.argtypes = [vp, i32, vp, dbl, i32, vp, vp, vp]
+    lib.nimble_last_error.restype = ctypes.c_char_p
+    lib.nimble_last_error.argtypes = []
+    for name in ("nimble_topo_num_links", "nimble_topo_num_comm", "nimble_topo_num_paths",
+                 "nimble_topo_regime"):
+        getattr(lib, name).restype = i32
+        getattr(lib, name).argtypes = [vp]
+    for name in ("nimble_topo_nnz", "nimble_topo_bytes_per_iter"):
+        getattr(lib, name).restype = i64
+        getattr(lib, name).argtypes = [vp]
+    lib.nimble_topo_set_regime.restype = ctypes.c_int
+    lib.nimble_topo_set_regime.argtypes = [vp, i32]
+    lib.nimble_debug_run_phase.restype = ctypes.c_int
+    lib.nimble_debug_run_phase.argtypes = [vp, i32, i32, vp, vp]
+    lib.nimble_host_build_reverse.restype = ctypes.c_int
+    lib.nimble_host_build_reverse.argtypes = [i32, i32, vp, i32, vp, vp, vp, vp, vp]
+    _lib = lib
+    return lib
+
+
+def nimble_last_error() -> str:
+    return load_library().nimble_last_error().decode()
+
+
+def _check(status: int) -> None:
+    if status != NIMBLE_OK:
+        raise NimbleError(status, nimble_last_error())
+
+
+def _host(a, dtype) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def _hp(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _dev_ptr(t, dtype_name: str, numel: int, what: str):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{what} must be a device tensor")
+    if t.dtype != getattr(torch, dtype_name) or not t.is_contiguous() or t.numel() != numel:
+        raise ValueError(f"{what} must be contiguous {dtype_name} with {numel} elements")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_ptr(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+class Topo:
+    """Owner of a nimble_topo_t handle."""
+
+    def __init__(self, handle: int):
+        self.handle = ctypes.c_void_p(handle)
+
+    @property
+    def n_links(self) -> int:
+        return load_library().nimble_topo_num_links(self.handle)
+
+    @property
+    def n_comm(self) -> int:
+        return load_library().nimble_topo_num_comm(self.handle)
+
+    @property
+    def n_paths(self) -> int:
+        return load_library().nimble_topo_num_paths(self.handle)
+
+    @property
+    def nnz(self) -> int:
+        return load_library().nimble_topo_nnz(self.handle)
+
+    @property
+    def bytes_per_iter(self) -> int:
+        return load_library().nimble_topo_bytes_per_iter(self.handle)
+
+    @property
+    def regime(self) -> int:
+        return load_library().nimble_topo_regime(self.handle)
+
+    def close(self) -> None:
+        if self.handle is not None and self.handle.value:
+            load_library().nimble_topo_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def nimble_topo_create(n_links, cap, n_comm, comm_path_ptr, n_paths, path_link_ptr, path_links,
+                       flags: int = NIMBLE_COST_SUM) -> Topo:
+    lib = load_library()
+    cap = _host(cap, np.float64)
+    cp = _host(comm_path_ptr, np.int32)
+    lp = _host(path_link_ptr, np.int32)
+    pl = _host(path_links, np.int32)
+    if cap.shape != (n_links,) or cp.shape != (n_comm + 1,) or lp.shape != (n_paths + 1,):
+        raise ValueError("array lengths do not match n_links / n_comm / n_paths")
+    if n_paths >= 0 and lp.size and pl.shape != (max(int(lp[-1]), 0),):
+        raise ValueError("path_links length must equal path_link_ptr[n_paths]")
+    out = ctypes.c_void_p()
+    _check(lib.nimble_topo_create(n_links, _hp(cap), n_comm, _hp(cp), n_paths, _hp(lp), _hp(pl),
+                                  flags, ctypes.byref(out)))
+    return Topo(out.value)
+
+
+def nimble_topo_destroy(topo: Topo) -> None:
+    topo.close()
+
+
+def nimble_topo_set_regime(topo: Topo, regime: int) -> None:
+    _check(load_library().nimble_topo_set_regime(topo.handle, regime))
+
+
+def nimble_plan_solve(topo: Topo, d_traffic, eps: float, iters: int, d_splits, d_lambda,
+                      stream=None) -> None:
+    """Enqueues one plan on `stream` (torch stream; None = current)."""
+    _check(load_library().nimble_plan_solve(
+        topo.handle, _dev_ptr(d_traffic, "float64", topo.n_comm, "d_traffic"), float(eps),
+        int(iters), _dev_ptr(d_splits, "float64", topo.n_paths, "d_splits"),
+        _dev_ptr(d_lambda, "float64", 1, "d_lambda"), _stream_ptr(stream)))
+
+
+def nimble_plan_solve_batch(topo: Topo, batch: int, d_traffic, eps: float, iters: int, d_splits,
+                            d_lambda, stream=None) -> None:
+    _check(load_library().nimble_plan_solve_batch(
+        topo.handle, int(batch),
+        _dev_ptr(d_traffic, "float64", batch * topo.n_comm, "d_traffic"), float(eps), int(iters),
+        _dev_ptr(d_splits, "float64", batch * topo.n_paths, "d_splits"),
+        _dev_ptr(d_lambda, "float64", batch, "d_lambda"), _stream_ptr(stream)))
+
+
+def nimble_debug_run_phase(topo: Topo, phase: int, reps: int, d_traffic, stream=None) -> None:
+    _check(load_library().nimble_debug_run_phase(
+        topo.handle, int(phase), int(reps),
+        _dev_ptr(d_traffic, "float64", topo.n_comm, "d_traffic"), _stream_ptr(stream)))
+
+
+def nimble_host_build_reverse(n_links, n_comm, comm_path_ptr, n_paths, path_link_ptr,
+                              path_links):
+    """Host-only: the reverse link -> (commodity, path) CSR as the library builds it."""
+    cp = _host(comm_path_ptr, np.int32)
+    lp = _host(path_link_ptr, np.int32)
+    pl = _host(path_links, np.int32)
+    nnz = int(lp[-1]) if lp.size else 0
+    rev_ptr = np.zeros(n_links + 1, dtype=np.int32)
+    rev_comm = np.zeros(max(nnz, 1), dtype=np.int32)
+    rev_path = np.zeros(max(nnz, 1), dtype=np.int32)
+    st = load_library().nimble_host_build_reverse(n_links, n_comm, _hp(cp), n_paths, _hp(lp),
+                                                  _hp(pl), _hp(rev_ptr), _hp(rev_comm),
+                                                  _hp(rev_path))
+    if st != NIMBLE_OK:
+        raise NimbleError(st, "invalid CSR")
+    return rev_ptr, rev_comm[:nnz], rev_path[:nnz]
+
+
+def plan(topo: Topo, traffic, eps: float, iters: int, device: str = "cuda:0"):
+    """Convenience wrapper: host demand vector in, (splits, lambda) as numpy out."""
+    import torch
+    d = torch.as_tensor(np.ascontiguousarray(traffic, dtype=np.float64)).to(device)
+    if d.dim() == 1:
+        splits = torch.empty(topo.n_paths, dtype=torch.float64, device=device)
+        lam = torch.empty(1, dtype=torch.float64, device=device)
+        nimble_plan_solve(topo, d, eps, iters, splits, lam)
+        torch.cuda.synchronize()
+        return splits.cpu().numpy(), float(lam.item())
+    b = d.shape[0]
+    splits = torch.empty(b * topo.n_paths, dtype=torch.float64, device=device)
+    lam = torch.empty(b, dtype=torch.float64, device=device)
+    nimble_plan_solve_batch(topo, b, d.reshape(-1), eps, iters, splits, lam)
+    torch.cuda.synchronize()
+    return splits.cpu().numpy().reshape(b, topo.n_paths), lam.cpu().numpy()

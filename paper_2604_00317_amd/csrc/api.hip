@@ -1,0 +1,327 @@
+// C ABI of the planner library: argument checking, device memory ownership, regime choice and
+// kernel sequencing.  Every step of the plan runs in the HIP kernels; there is no CPU
+// fallback -- without a usable GPU the device calls fail and the status says so.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/nimble_plan.h"
+#include "host_topo.hpp"
+#include "kernels.hpp"
+
+namespace {
+
+thread_local std::string g_last_error;
+
+nimble_status_t fail(nimble_status_t st, const std::string &msg)
+{
+    g_last_error = msg;
+    return st;
+}
+
+nimble_status_t fail_hip(hipError_t e, const char *what)
+{
+    g_last_error = std::string(what) + ": " + hipGetErrorString(e);
+    return NIMBLE_ERR_HIP;
+}
+
+}  // namespace
+
+struct nimble_topo {
+    nimble::DeviceTopo d{};
+    std::vector<void *> allocs;
+    int device = -1;
+    int32_t forced_regime = NIMBLE_REGIME_AUTO;
+    int32_t last_regime = NIMBLE_REGIME_AUTO;
+    int64_t bytes_per_iter = 0;
+    bool state_ready = false;   // a stream-regime solve has initialised the workspace
+};
+
+namespace {
+
+template <typename T>
+hipError_t upload(nimble_topo *t, const T *host, size_t n, const T **dev)
+{
+    void *p = nullptr;
+    hipError_t e = hipMalloc(&p, (n ? n : 1) * sizeof(T));
+    if (e != hipSuccess) return e;
+    t->allocs.push_back(p);
+    if (n) {
+        e = hipMemcpy(p, host, n * sizeof(T), hipMemcpyHostToDevice);
+        if (e != hipSuccess) return e;
+    }
+    *dev = static_cast<const T *>(p);
+    return hipSuccess;
+}
+
+template <typename T>
+hipError_t allocate(nimble_topo *t, size_t n, T **dev)
+{
+    void *p = nullptr;
+    hipError_t e = hipMalloc(&p, (n ? n : 1) * sizeof(T));
+    if (e != hipSuccess) return e;
+    t->allocs.push_back(p);
+    *dev = static_cast<T *>(p);
+    return hipSuccess;
+}
+
+void release(nimble_topo *t)
+{
+    for (void *p : t->allocs) (void)hipFree(p);
+    t->allocs.clear();
+}
+
+nimble_status_t check_solve_args(const nimble_topo *topo, const double *d_traffic, double eps,
+                                 int32_t iters, const double *d_splits, const double *d_lambda)
+{
+    if (!topo) return fail(NIMBLE_ERR_INVALID, "topology handle is NULL");
+    if (!d_traffic || !d_splits || !d_lambda)
+        return fail(NIMBLE_ERR_INVALID, "traffic, splits and lambda pointers must not be NULL");
+    if (!(eps > 0.0) || !(eps <= 0.5)) return fail(NIMBLE_ERR_INVALID, "eps must be in (0, 0.5]");
+    if (iters < 1) return fail(NIMBLE_ERR_INVALID, "iters must be >= 1");
+    if (static_cast<double>(iters) * std::log1p(eps) > 700.0)
+        return fail(NIMBLE_ERR_RANGE, "iters * log1p(eps) > 700: link lengths could overflow");
+    return NIMBLE_OK;
+}
+
+nimble_status_t check_device(const nimble_topo *topo)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+    if (dev != topo->device)
+        return fail(NIMBLE_ERR_INVALID, "current device differs from the topology's device");
+    return NIMBLE_OK;
+}
+
+int32_t pick_regime(const nimble_topo *topo)
+{
+    if (topo->forced_regime != NIMBLE_REGIME_AUTO) return topo->forced_regime;
+    return nimble::resident_fits(topo->d) ? NIMBLE_REGIME_RESIDENT : NIMBLE_REGIME_STREAM;
+}
+
+nimble_status_t solve_stream(nimble_topo *topo, const double *d_traffic, double eps,
+                             int32_t iters, double *d_splits, double *d_lambda, hipStream_t s)
+{
+    const nimble::DeviceTopo &d = topo->d;
+    nimble::launch_init(d, s);
+    nimble::launch_width(d, d_traffic, s);
+    for (int32_t it = 0; it < iters; ++it) {
+        nimble::launch_argmin(d, s);
+        nimble::launch_load_reduce(d, d_traffic, s);
+        nimble::launch_update(d, eps, s);
+    }
+    nimble::launch_epilogue(d, iters, d_splits, d_lambda, s);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(e, "kernel launch (streaming regime)");
+    topo->state_ready = true;
+    return NIMBLE_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *nimble_last_error(void) { return g_last_error.c_str(); }
+
+nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n_comm,
+                                   const int32_t *comm_path_ptr, int32_t n_paths,
+                                   const int32_t *path_link_ptr, const int32_t *path_links,
+                                   uint32_t flags, nimble_topo_t **out)
+{
+    g_last_error.clear();
+    if (!out) return fail(NIMBLE_ERR_INVALID, "out is NULL");
+    *out = nullptr;
+    if (!cap) return fail(NIMBLE_ERR_INVALID, "cap is NULL");
+    if (flags & ~static_cast<uint32_t>(NIMBLE_COST_MAX))
+        return fail(NIMBLE_ERR_INVALID, "unknown flag bits");
+    std::string why;
+    nimble_status_t st = nimble::validate_csr(n_links, cap, n_comm, comm_path_ptr, n_paths,
+                                              path_link_ptr, path_links, why);
+    if (st != NIMBLE_OK) return fail(st, why);
+    const int64_t nnz = path_link_ptr[n_paths];
+    if (nnz + 3LL * n_links >= (1LL << 31))
+        return fail(NIMBLE_ERR_RANGE, "padded reverse CSR exceeds 2^31 entries");
+
+    nimble_topo *t = nullptr;
+    nimble::HostTopo h;
+    try {
+        t = new nimble_topo();
+        nimble::build_host_topo(n_links, cap, n_comm, comm_path_ptr, n_paths, path_link_ptr,
+                                path_links, h);
+    } catch (const std::bad_alloc &) {
+        delete t;
+        return fail(NIMBLE_ERR_ALLOC, "host allocation failed");
+    }
+
+    hipError_t e = hipGetDevice(&t->device);
+    if (e != hipSuccess) {
+        delete t;
+        return fail_hip(e, "hipGetDevice (is a GPU visible?)");
+    }
+
+    nimble::DeviceTopo &d = t->d;
+    d.E = h.E;
+    d.K = h.K;
+    d.P = h.P;
+    d.nnz = h.nnz;
+    d.rev_len = static_cast<int64_t>(h.rev_entry.size());
+    d.pmax = h.pmax;
+    d.lmax = h.lmax;
+    d.n_chunks = static_cast<int32_t>(h.chunk_begin.size());
+    d.cost_max = (flags & NIMBLE_COST_MAX) != 0u;
+    d.n_update_blocks = (h.E + 255) / 256;
+
+#define NIMBLE_TRY(call, what)                        \
+    do {                                              \
+        e = (call);                                   \
+        if (e != hipSuccess) {                        \
+            release(t);                               \
+            delete t;                                 \
+            return e == hipErrorOutOfMemory           \
+                       ? fail(NIMBLE_ERR_ALLOC, what) \
+                       : fail_hip(e, what);           \
+        }                                             \
+    } while (0)
+
+    NIMBLE_TRY(upload(t, comm_path_ptr, static_cast<size_t>(h.K) + 1, &d.comm_ptr), "comm_ptr");
+    NIMBLE_TRY(upload(t, path_link_ptr, static_cast<size_t>(h.P) + 1, &d.path_ptr), "path_ptr");
+    NIMBLE_TRY(upload(t, path_links, static_cast<size_t>(h.nnz), &d.path_links), "path_links");
+    NIMBLE_TRY(upload(t, h.rev_ptr.data(), h.rev_ptr.size(), &d.rev_ptr), "rev_ptr");
+    NIMBLE_TRY(upload(t, h.rev_entry.data(), h.rev_entry.size(), &d.rev_entry), "rev_entry");
+    NIMBLE_TRY(upload(t, h.chunk_begin.data(), h.chunk_begin.size(), &d.chunk_begin),
+               "chunk_begin");
+    NIMBLE_TRY(upload(t, h.chunk_end.data(), h.chunk_end.size(), &d.chunk_end), "chunk_end");
+    NIMBLE_TRY(upload(t, h.link_chunk_ptr.data(), h.link_chunk_ptr.size(), &d.link_chunk_ptr),
+               "link_chunk_ptr");
+    NIMBLE_TRY(upload(t, h.invcap.data(), h.invcap.size(), &d.invcap), "invcap");
+    NIMBLE_TRY(allocate(t, static_cast<size_t>(h.E), &d.len), "len");
+    NIMBLE_TRY(allocate(t, static_cast<size_t>(h.E), &d.price), "price");
+    NIMBLE_TRY(allocate(t, static_cast<size_t>(h.E), &d.S), "S");
+    NIMBLE_TRY(allocate(t, static_cast<size_t>(h.K) + 1, &d.choice), "choice");
+    NIMBLE_TRY(allocate(t, static_cast<size_t>(h.P), &d.count), "count");
+    NIMBLE_TRY(allocate(t, static_cast<size_t>(d.n_chunks), &d.partial), "partial");
+    NIMBLE_TRY(allocate(t, static_cast<size_t>(d.n_update_blocks) + 1, &d.scalars), "scalars");
+#undef NIMBLE_TRY
+
+    // stored bytes one iteration streams: forward CSR, reverse CSR with its chunk table and
+    // partials (written, then read), per-commodity outputs, per-link state
+    t->bytes_per_iter = 4LL * (h.K + 1) + 4LL * (h.P + 1) + 4LL * h.nnz       // argmin reads
+                        + 9LL * h.K                                           // choice w, count rw
+                        + 4LL * d.rev_len + 8LL * d.n_chunks + 8LL * d.n_chunks  // reduce
+                        + 8LL * d.n_chunks + 4LL * (h.E + 1) + 56LL * h.E;    // update
+    *out = t;
+    return NIMBLE_OK;
+}
+
+void nimble_topo_destroy(nimble_topo_t *topo)
+{
+    if (!topo) return;
+    release(topo);
+    delete topo;
+}
+
+int32_t nimble_topo_num_links(const nimble_topo_t *t) { return t ? t->d.E : -1; }
+int32_t nimble_topo_num_comm(const nimble_topo_t *t) { return t ? t->d.K : -1; }
+int32_t nimble_topo_num_paths(const nimble_topo_t *t) { return t ? t->d.P : -1; }
+int64_t nimble_topo_nnz(const nimble_topo_t *t) { return t ? t->d.nnz : -1; }
+int64_t nimble_topo_bytes_per_iter(const nimble_topo_t *t) { return t ? t->bytes_per_iter : -1; }
+int32_t nimble_topo_regime(const nimble_topo_t *t) { return t ? t->last_regime : -1; }
+
+nimble_status_t nimble_topo_set_regime(nimble_topo_t *topo, int32_t regime)
+{
+    g_last_error.clear();
+    if (!topo) return fail(NIMBLE_ERR_INVALID, "topology handle is NULL");
+    switch (regime) {
+    case NIMBLE_REGIME_AUTO:
+    case NIMBLE_REGIME_STREAM:
+        break;
+    case NIMBLE_REGIME_RESIDENT:
+        if (!nimble::resident_fits(topo->d))
+            return fail(NIMBLE_ERR_RANGE, "per-plan state does not fit in LDS");
+        break;
+    case NIMBLE_REGIME_PERSISTENT:
+        return fail(NIMBLE_ERR_RANGE, "persistent regime is not available in this build");
+    default:
+        return fail(NIMBLE_ERR_INVALID, "unknown regime");
+    }
+    topo->forced_regime = regime;
+    return NIMBLE_OK;
+}
+
+nimble_status_t nimble_plan_solve(nimble_topo_t *topo, const double *d_traffic, double eps,
+                                  int32_t iters, double *d_splits, double *d_lambda,
+                                  void *hip_stream)
+{
+    g_last_error.clear();
+    nimble_status_t st = check_solve_args(topo, d_traffic, eps, iters, d_splits, d_lambda);
+    if (st != NIMBLE_OK) return st;
+    st = check_device(topo);
+    if (st != NIMBLE_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const int32_t regime = pick_regime(topo);
+    topo->last_regime = regime;
+    if (regime == NIMBLE_REGIME_RESIDENT) {
+        hipError_t e = nimble::launch_resident(topo->d, 1, d_traffic, eps, iters, d_splits,
+                                               d_lambda, s);
+        if (e != hipSuccess) return fail_hip(e, "kernel launch (resident regime)");
+        return NIMBLE_OK;
+    }
+    return solve_stream(topo, d_traffic, eps, iters, d_splits, d_lambda, s);
+}
+
+nimble_status_t nimble_plan_solve_batch(nimble_topo_t *topo, int32_t batch,
+                                        const double *d_traffic, double eps, int32_t iters,
+                                        double *d_splits, double *d_lambda, void *hip_stream)
+{
+    g_last_error.clear();
+    nimble_status_t st = check_solve_args(topo, d_traffic, eps, iters, d_splits, d_lambda);
+    if (st != NIMBLE_OK) return st;
+    if (batch < 1) return fail(NIMBLE_ERR_INVALID, "batch must be >= 1");
+    st = check_device(topo);
+    if (st != NIMBLE_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const int32_t regime = pick_regime(topo);
+    topo->last_regime = regime;
+    if (regime == NIMBLE_REGIME_RESIDENT) {
+        hipError_t e = nimble::launch_resident(topo->d, batch, d_traffic, eps, iters, d_splits,
+                                               d_lambda, s);
+        if (e != hipSuccess) return fail_hip(e, "kernel launch (resident regime)");
+        return NIMBLE_OK;
+    }
+    for (int32_t b = 0; b < batch; ++b) {
+        st = solve_stream(topo, d_traffic + static_cast<size_t>(b) * topo->d.K, eps, iters,
+                          d_splits + static_cast<size_t>(b) * topo->d.P, d_lambda + b, s);
+        if (st != NIMBLE_OK) return st;
+    }
+    return NIMBLE_OK;
+}
+
+nimble_status_t nimble_debug_run_phase(nimble_topo_t *topo, int32_t phase, int32_t reps,
+                                       const double *d_traffic, void *hip_stream)
+{
+    g_last_error.clear();
+    if (!topo || !d_traffic) return fail(NIMBLE_ERR_INVALID, "NULL argument");
+    if (phase < 0 || phase > 2 || reps < 1) return fail(NIMBLE_ERR_INVALID, "bad phase or reps");
+    if (!topo->state_ready)
+        return fail(NIMBLE_ERR_INVALID, "run a streaming-regime solve on this topology first");
+    nimble_status_t st = check_device(topo);
+    if (st != NIMBLE_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    for (int32_t r = 0; r < reps; ++r) {
+        if (phase == 0) nimble::launch_argmin(topo->d, s);
+        else if (phase == 1) nimble::launch_load_reduce(topo->d, d_traffic, s);
+        else nimble::launch_update(topo->d, 0.0, s);   // eps 0: lengths stay as they are
+    }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(e, "kernel launch (phase timing)");
+    return NIMBLE_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,117 @@
+// Wave64 cross-lane helpers for gfx950: butterfly reductions built from DPP row operations
+// (quad_perm, row_half_mirror, row_mirror) for distances below 16 and ds_bpermute for 16/32.
+// Every helper must be called with all 64 lanes of the wave active.
+#pragma once
+#include <hip/hip_runtime.h>
+
+namespace nimble {
+
+constexpr int kWave = 64;
+
+// DPP controls (CDNA ISA): quad_perm [1,0,3,2] / [2,3,0,1], row_half_mirror, row_mirror.
+constexpr int kDppXor1 = 0xB1;
+constexpr int kDppXor2 = 0x4E;
+constexpr int kDppHalfMirror = 0x141;
+constexpr int kDppMirror = 0x140;
+
+template <int CTRL>
+__device__ __forceinline__ int dpp_i32(int v)
+{
+    return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xF, 0xF, false);
+}
+
+template <int CTRL>
+__device__ __forceinline__ double dpp_f64(double v)
+{
+    int lo = dpp_i32<CTRL>(__double2loint(v));
+    int hi = dpp_i32<CTRL>(__double2hiint(v));
+    return __hiloint2double(hi, lo);
+}
+
+// Value of the partner lane at butterfly stage STEP (1,2,4,8,16,32).  Stages 4 and 8 use the
+// mirror permutations: after stages 1..STEP/2 every aligned group of STEP lanes already holds
+// one common value, so any lane of the neighbouring group is a valid partner.
+template <int STEP>
+__device__ __forceinline__ double partner_f64(double v)
+{
+    if constexpr (STEP == 1) return dpp_f64<kDppXor1>(v);
+    else if constexpr (STEP == 2) return dpp_f64<kDppXor2>(v);
+    else if constexpr (STEP == 4) return dpp_f64<kDppHalfMirror>(v);
+    else if constexpr (STEP == 8) return dpp_f64<kDppMirror>(v);
+    else return __shfl_xor(v, STEP, kWave);
+}
+
+template <int STEP>
+__device__ __forceinline__ int partner_i32(int v)
+{
+    if constexpr (STEP == 1) return dpp_i32<kDppXor1>(v);
+    else if constexpr (STEP == 2) return dpp_i32<kDppXor2>(v);
+    else if constexpr (STEP == 4) return dpp_i32<kDppHalfMirror>(v);
+    else if constexpr (STEP == 8) return dpp_i32<kDppMirror>(v);
+    else return __shfl_xor(v, STEP, kWave);
+}
+
+// (cost, index) argmin over aligned groups of L lanes; ties go to the lower index, so the
+// pair order is total and the result does not depend on the reduction tree.  All lanes of a
+// group end with the group's result.
+template <int STEP>
+__device__ __forceinline__ void argmin_stage(double &c, int &j)
+{
+    double oc = partner_f64<STEP>(c);
+    int oj = partner_i32<STEP>(j);
+    bool take = (oc < c) || (oc == c && oj < j);
+    c = take ? oc : c;
+    j = take ? oj : j;
+}
+
+template <int L>
+__device__ __forceinline__ void group_argmin(double &c, int &j)
+{
+    if constexpr (L > 1) argmin_stage<1>(c, j);
+    if constexpr (L > 2) argmin_stage<2>(c, j);
+    if constexpr (L > 4) argmin_stage<4>(c, j);
+    if constexpr (L > 8) argmin_stage<8>(c, j);
+    if constexpr (L > 16) argmin_stage<16>(c, j);
+    if constexpr (L > 32) argmin_stage<32>(c, j);
+}
+
+// Sum over the 64 lanes in a fixed butterfly order (the same tree on every run).
+__device__ __forceinline__ double wave_sum(double v)
+{
+    v = v + partner_f64<1>(v);
+    v = v + partner_f64<2>(v);
+    v = v + partner_f64<4>(v);
+    v = v + partner_f64<8>(v);
+    v = v + partner_f64<16>(v);
+    v = v + partner_f64<32>(v);
+    return v;
+}
+
+__device__ __forceinline__ double wave_max(double v)
+{
+    v = fmax(v, partner_f64<1>(v));
+    v = fmax(v, partner_f64<2>(v));
+    v = fmax(v, partner_f64<4>(v));
+    v = fmax(v, partner_f64<8>(v));
+    v = fmax(v, partner_f64<16>(v));
+    v = fmax(v, partner_f64<32>(v));
+    return v;
+}
+
+// Block-wide max for blocks of up to 1024 threads; `red` is shared scratch of >= 16 doubles.
+// Returns the maximum in every thread.
+__device__ __forceinline__ double block_max(double v, double *red)
+{
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wid = threadIdx.x >> 6;
+    const int nw = (blockDim.x + kWave - 1) >> 6;
+    v = wave_max(v);
+    __syncthreads();
+    if (lane == 0) red[wid] = v;
+    __syncthreads();
+    double r = red[0];
+    for (int w = 1; w < nw; ++w) r = fmax(r, red[w]);
+    return r;
+}
+
+}  // namespace nimble

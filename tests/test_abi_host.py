@@ -1,0 +1,113 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every declared
+symbol, validates its arguments before touching a device, and builds the reverse CSR in
+ascending (commodity, path) order."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2604_00317_amd import binding as B
+from paper_2604_00317_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = B.load_library()
+    header = open(os.path.join(ROOT, "include", "nimble_plan.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(nimble_[a-z_]+)\s*\(", header))
+    assert declared, "no declarations found"
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert declared == set(B.EXPORTS)
+
+
+def _create_status(lib, n_links, cap, n_comm, cp, n_paths, lp, pl, flags=0):
+    out = ctypes.c_void_p()
+    def p(a, dt):
+        if a is None:
+            return None
+        arr = np.ascontiguousarray(a, dtype=dt)
+        keep.append(arr)
+        return arr.ctypes.data_as(ctypes.c_void_p)
+    keep = []
+    st = lib.nimble_topo_create(n_links, p(cap, np.float64), n_comm, p(cp, np.int32), n_paths,
+                                p(lp, np.int32), p(pl, np.int32), flags, ctypes.byref(out))
+    assert out.value is None or st == B.NIMBLE_OK
+    if out.value:
+        lib.nimble_topo_destroy(out)
+    return st, lib.nimble_last_error().decode()
+
+
+def test_create_rejects_malformed_input_before_any_device_call():
+    lib = B.load_library()
+    good = dict(n_links=2, cap=[1e9, 2e9], n_comm=1, cp=[0, 2], n_paths=2, lp=[0, 1, 2],
+                pl=[0, 1])
+    bad = [
+        dict(good, cap=[1e9, 0.0]),
+        dict(good, cap=[1e9, float("inf")]),
+        dict(good, cap=[1e9, float("nan")]),
+        dict(good, cap=None),
+        dict(good, cp=[0, 1]),                # does not end at n_paths
+        dict(good, cp=[1, 2]),                # does not start at 0
+        dict(good, lp=[0, 0, 2]),             # empty path
+        dict(good, pl=[0, 2]),                # link id out of range
+        dict(good, pl=[0, -1]),
+        dict(good, n_paths=1, cp=[0, 1], lp=[0, 2], pl=[1, 1]),   # link twice in a path
+        dict(good, n_comm=0, cp=[0]),
+        dict(good, cp=None),
+    ]
+    for case in bad:
+        st, msg = _create_status(lib, case["n_links"], case["cap"], case["n_comm"], case["cp"],
+                                 case["n_paths"], case["lp"], case["pl"])
+        assert st == B.NIMBLE_ERR_INVALID, (case, st, msg)
+        assert msg
+    st, _ = _create_status(lib, 2, [1e9, 2e9], 1, [0, 2], 2, [0, 1, 2], [0, 1], flags=8)
+    assert st == B.NIMBLE_ERR_INVALID
+    # more than 127 candidates for one commodity is a documented limit
+    n = 128
+    st, msg = _create_status(lib, 1, [1e9], 1, [0, n], n, list(range(n + 1)), [0] * n)
+    assert st == B.NIMBLE_ERR_RANGE, msg
+
+
+def test_solve_argument_checks_without_device():
+    lib = B.load_library()
+    assert lib.nimble_plan_solve(None, None, 0.1, 10, None, None, None) == B.NIMBLE_ERR_INVALID
+    assert lib.nimble_plan_solve_batch(None, 1, None, 0.1, 10, None, None, None) == \
+        B.NIMBLE_ERR_INVALID
+    assert lib.nimble_topo_set_regime(None, 0) == B.NIMBLE_ERR_INVALID
+    assert lib.nimble_topo_num_paths(None) == -1
+    lib.nimble_topo_destroy(None)            # ignored
+
+
+@pytest.mark.parametrize("cfg", [0, 1])
+def test_reverse_csr_matches_numpy(cfg):
+    t = W.config_topology(cfg)
+    rev_ptr, rev_comm, rev_path = B.nimble_host_build_reverse(
+        t.n_links, t.n_comm, t.comm_path_ptr, t.n_paths, t.path_link_ptr, t.path_links)
+    inc_path = np.repeat(np.arange(t.n_paths), np.diff(t.path_link_ptr))
+    path_comm = np.repeat(np.arange(t.n_comm), np.diff(t.comm_path_ptr))
+    inc_comm = path_comm[inc_path]
+    inc_j = inc_path - t.comm_path_ptr[inc_comm]
+    order = np.lexsort((inc_j, inc_comm, t.path_links))       # by link, then (comm, path)
+    assert np.array_equal(rev_ptr, np.concatenate([[0], np.cumsum(np.bincount(
+        t.path_links, minlength=t.n_links))]))
+    assert np.array_equal(rev_comm, inc_comm[order])
+    assert np.array_equal(rev_path, inc_j[order])
+
+
+def test_reverse_csr_random_ragged():
+    rng = np.random.default_rng(9)
+    t = W.random_topology(rng, n_links=23, n_comm=40, max_paths=9, max_len=5)
+    rev_ptr, rev_comm, rev_path = B.nimble_host_build_reverse(
+        t.n_links, t.n_comm, t.comm_path_ptr, t.n_paths, t.path_link_ptr, t.path_links)
+    for e in range(t.n_links):
+        rows = list(zip(rev_comm[rev_ptr[e]:rev_ptr[e + 1]], rev_path[rev_ptr[e]:rev_ptr[e + 1]]))
+        assert rows == sorted(rows)
+        for k, j in rows:
+            p = t.comm_path_ptr[k] + j
+            assert e in t.path_links[t.path_link_ptr[p]:t.path_link_ptr[p + 1]]
+    assert rev_ptr[-1] == t.nnz

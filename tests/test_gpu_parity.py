@@ -1,0 +1,186 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element.
+
+Bar: splits and lambda within 1e-9 relative (binary64 on both sides).  The arithmetic of both
+sides is the same sequence of IEEE operations, so for the integer-valued byte demands of every
+benchmark configuration the test also demands the stronger property, exact equality.
+"""
+import numpy as np
+import pytest
+
+from paper_2604_00317_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+RTOL = 1e-9
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a visible MI355X; no fallback path exists")
+    from paper_2604_00317_amd import binding
+    binding.load_library(build_if_missing=False)
+    return binding
+
+
+def gpu_plan(B, topo, traffic, eps, iters, regime=0, flags=0):
+    print(f"[gpu_plan] K={topo.n_comm} P={topo.n_paths} nnz={topo.nnz} E={topo.n_links} "
+          f"iters={iters} regime={regime} flags={flags}", flush=True)
+    h = B.nimble_topo_create(*topo.csr(), flags=flags)
+    try:
+        B.nimble_topo_set_regime(h, regime)
+        splits, lam = B.plan(h, traffic, eps, iters)
+        used = h.regime
+    finally:
+        h.close()
+    return splits, lam, used
+
+
+def check(oracle_mod, B, topo, traffic, eps, iters, regime=0, flags=0, exact=True):
+    ref = oracle_mod.solve(*topo.csr(), traffic, eps, iters, flags=flags)
+    splits, lam, used = gpu_plan(B, topo, traffic, eps, iters, regime, flags)
+    if regime:
+        assert used == regime
+    np.testing.assert_allclose(splits, ref["splits"], rtol=RTOL, atol=0)
+    assert abs(lam - ref["lam"]) <= RTOL * abs(ref["lam"])
+    if exact:
+        assert np.array_equal(splits, ref["splits"])
+        assert lam == ref["lam"]
+    return splits, lam
+
+
+@pytest.mark.parametrize("regime", [1, 2])
+@pytest.mark.parametrize("cfg", [0, 1])
+def test_small_configs_full_iterations(oracle_mod, B, cfg, regime):
+    w = W.make_config(cfg)
+    check(oracle_mod, B, w.topo, w.traffic, w.eps, w.iters, regime)
+
+
+def test_config3_stream(oracle_mod, B):
+    w = W.make_config(3)
+    check(oracle_mod, B, w.topo, w.traffic, w.eps, 250, regime=2)
+
+
+@pytest.mark.parametrize("batch", [1, 5, 67])
+def test_batched_single_node(oracle_mod, B, batch):
+    w = W.make_config(2, batch=batch)
+    t = w.topo
+    print(f"[batch] batch={batch}", flush=True)
+    h = B.nimble_topo_create(*t.csr())
+    try:
+        splits, lam = B.plan(h, w.traffic, w.eps, w.iters)
+        assert h.regime == B.NIMBLE_REGIME_RESIDENT
+    finally:
+        h.close()
+    for b in range(batch):
+        ref = oracle_mod.solve(*t.csr(), w.traffic[b], w.eps, w.iters)
+        assert np.array_equal(splits[b], ref["splits"]), b
+        assert lam[b] == ref["lam"], b
+
+
+@pytest.mark.parametrize("regime", [1, 2])
+@pytest.mark.parametrize("flags", [0, 1])
+@pytest.mark.parametrize("seed,E,K,pm,lm", [(1, 7, 3, 4, 3), (2, 40, 130, 9, 5),
+                                            (3, 300, 1000, 20, 6), (4, 64, 65, 33, 4),
+                                            (5, 90, 17, 100, 7), (6, 1, 5, 1, 1)])
+def test_random_ragged_topologies(oracle_mod, B, seed, E, K, pm, lm, flags, regime):
+    rng = np.random.default_rng(seed)
+    t = W.random_topology(rng, E, K, pm, lm)
+    d = np.floor(rng.pareto(1.1, K) * 1e6)
+    d[rng.integers(0, K)] = 0.0
+    if regime == 1 and (E, K) == (300, 1000):
+        pytest.skip("per-plan state exceeds the LDS budget of the resident regime")
+    check(oracle_mod, B, t, d, 0.07, 60, regime, flags)
+
+
+@pytest.mark.parametrize("regime", [1, 2])
+def test_edge_cases(oracle_mod, B, regime):
+    t = W.build_fabric(1, 4)
+    check(oracle_mod, B, t, np.zeros(t.n_comm), 0.1, 10, regime)          # all-zero traffic
+    d = np.zeros(t.n_comm)
+    d[5] = 123456789.0
+    check(oracle_mod, B, t, d, 0.5, 1, regime)                             # one iteration
+    check(oracle_mod, B, t, d, 0.5, 1000, regime)                          # largest step
+    big = np.full(t.n_comm, float(2 ** 40))
+    check(oracle_mod, B, t, big, 0.1, 40, regime)
+    # bottleneck cost on the structured fabric
+    w = W.make_config(1)
+    check(oracle_mod, B, w.topo, w.traffic, w.eps, 120, regime, flags=1)
+
+
+def test_non_integer_demands(oracle_mod, B):
+    """The resident regime adds loads in the sequential order, so it is exact for any demands;
+    the streaming regime sums in a fixed tree: run-to-run identical, equal to the oracle up to
+    the rounding of the load sums."""
+    w = W.make_config(1)
+    d = w.traffic * (1.0 + np.random.default_rng(0).random(w.topo.n_comm))
+    check(oracle_mod, B, w.topo, d, w.eps, 100, regime=1, exact=True)
+    a = gpu_plan(B, w.topo, d, w.eps, 100, regime=2)
+    b = gpu_plan(B, w.topo, d, w.eps, 100, regime=2)
+    assert np.array_equal(a[0], b[0]) and a[1] == b[1]
+    ref = oracle_mod.solve(*w.topo.csr(), d, w.eps, 100)
+    assert abs(a[1] - ref["lam"]) <= 1e-6 * ref["lam"]
+
+
+def test_argument_errors_on_device(B):
+    import torch
+    t = W.build_fabric(1, 4)
+    h = B.nimble_topo_create(*t.csr())
+    try:
+        d = torch.zeros(t.n_comm, dtype=torch.float64, device="cuda:0")
+        s = torch.zeros(t.n_paths, dtype=torch.float64, device="cuda:0")
+        lam = torch.zeros(1, dtype=torch.float64, device="cuda:0")
+        for eps, iters, status in [(0.0, 10, B.NIMBLE_ERR_INVALID), (0.6, 10, B.NIMBLE_ERR_INVALID),
+                                   (float("nan"), 10, B.NIMBLE_ERR_INVALID),
+                                   (0.1, 0, B.NIMBLE_ERR_INVALID), (0.5, 2000, B.NIMBLE_ERR_RANGE)]:
+            with pytest.raises(B.NimbleError) as ei:
+                B.nimble_plan_solve(h, d, eps, iters, s, lam)
+            assert ei.value.status == status
+        import ctypes
+        st = B.load_library().nimble_plan_solve_batch(
+            h.handle, 0, ctypes.c_void_p(d.data_ptr()), 0.1, 10, ctypes.c_void_p(s.data_ptr()),
+            ctypes.c_void_p(lam.data_ptr()), None)
+        assert st == B.NIMBLE_ERR_INVALID
+        B.nimble_plan_solve(h, d, 0.1, 10, s, lam)       # still usable after errors
+        torch.cuda.synchronize()
+        assert float(lam.item()) == 0.0
+    finally:
+        h.close()
+
+
+def test_solve_on_side_stream_and_reuse(oracle_mod, B):
+    import torch
+    w = W.make_config(1)
+    t = w.topo
+    h = B.nimble_topo_create(*t.csr())
+    try:
+        B.nimble_topo_set_regime(h, B.NIMBLE_REGIME_STREAM)
+        stream = torch.cuda.Stream()
+        d = torch.as_tensor(w.traffic).to("cuda:0")
+        s = torch.empty(t.n_paths, dtype=torch.float64, device="cuda:0")
+        lam = torch.empty(1, dtype=torch.float64, device="cuda:0")
+        torch.cuda.synchronize()
+        for iters in (50, 20):                      # second solve re-initialises the workspace
+            B.nimble_plan_solve(h, d, w.eps, iters, s, lam, stream=stream)
+            stream.synchronize()
+            ref = oracle_mod.solve(*t.csr(), w.traffic, w.eps, iters)
+            assert np.array_equal(s.cpu().numpy(), ref["splits"])
+            assert float(lam.item()) == ref["lam"]
+    finally:
+        h.close()
+
+
+def test_full_size_config4_against_oracle(oracle_mod, B):
+    """Largest configuration in the regime the benchmark times, compared element by element for
+    a shortened run (the oracle's trajectory cannot be sampled output by output), plus the
+    size-independent properties on the result."""
+    w = W.make_config(4)
+    t = w.topo
+    iters = 24
+    splits, lam = check(oracle_mod, B, t, w.traffic, w.eps, iters, regime=0)
+    np.testing.assert_allclose(np.add.reduceat(splits, t.comm_path_ptr[:-1]), 1.0, rtol=0,
+                               atol=1e-12)
+    lam2, _ = oracle_mod.congestion(t.n_links, t.cap, t.comm_path_ptr, t.path_link_ptr,
+                                    t.path_links, w.traffic, splits)
+    assert abs(lam2 - lam) <= 1e-10 * lam
