@@ -26,15 +26,10 @@ HBM_PEAK_GBS = 8000.0
 
 
 def phase_bytes(topo_np, lib_topo):
-    """Stored bytes each streaming-regime kernel has to move per launch (indices as stored:
-    int32 link ids and pointers, 32-bit packed reverse entries padded to 16 B per row)."""
-    K, P, E, nnz = topo_np.n_comm, topo_np.n_paths, topo_np.n_links, topo_np.nnz
-    total = lib_topo.bytes_per_iter
-    argmin = 4 * (K + 1) + 4 * (P + 1) + 4 * nnz + 9 * K
-    update_fixed = 4 * (E + 1) + 56 * E
-    # what is left is the reverse stream with its chunk table and partials
-    reduce_ = total - argmin - update_fixed
-    return dict(argmin=argmin, load_reduce=reduce_, update=update_fixed, total=total)
+    """Stored bytes each streaming-regime kernel has to move per launch, as the library lays
+    the topology out (16-bit tile-local link indices and path offsets, 8-byte reverse pairs)."""
+    return dict(argmin=lib_topo.phase_bytes(0), load_reduce=lib_topo.phase_bytes(1),
+                update=lib_topo.phase_bytes(2), total=lib_topo.bytes_per_iter)
 
 
 def time_phase(B, torch, h, phase, reps, d_traffic):
@@ -59,6 +54,10 @@ def main() -> int:
     ap.add_argument("--cpu-iters", type=int, default=-1,
                     help="oracle iterations for the CPU baseline (-1: sized to ~10-30 s, 0: skip)")
     ap.add_argument("--batch", type=int, default=4096)
+    ap.add_argument("--iters", type=int, default=0,
+                    help="override the configuration's iteration count (profiling runs only)")
+    ap.add_argument("--copy-calib", type=int, default=0,
+                    help="also run N plain device copies of 1 GiB (counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the planner models the whole "
@@ -76,6 +75,8 @@ def main() -> int:
     t_gen = time.perf_counter()
     w = W.make_config(args.config, batch=args.batch if args.config == 2 else None)
     topo = w.topo
+    if args.iters > 0:
+        w.iters = args.iters
     t_gen = time.perf_counter() - t_gen
     dev = "cuda:0"
     t_create = time.perf_counter()
@@ -93,6 +94,14 @@ def main() -> int:
             B.nimble_plan_solve_batch(h, batch, d_traffic, w.eps, w.iters, d_splits, d_lambda)
         else:
             B.nimble_plan_solve(h, d_traffic, w.eps, w.iters, d_splits, d_lambda)
+
+    if args.copy_calib > 0:
+        src = torch.empty(1 << 27, dtype=torch.float64, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        for _ in range(args.copy_calib):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()

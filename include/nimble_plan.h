@@ -100,6 +100,8 @@ void nimble_topo_destroy(nimble_topo_t *topo);
  *               could overflow: NIMBLE_ERR_RANGE)
  *   d_splits    device [n_paths] out: times chosen / iters; sums to 1 per commodity
  *   d_lambda    device [1] out: max_e (1/cap_e) * sum_p d_k(p) splits_p, in seconds
+ *               (NaN if the persistent regime abandoned the solve, see
+ *               nimble_debug_set_spin_limit)
  *   hip_stream  hipStream_t (NULL = default stream).  The call only enqueues work; outputs are
  *               valid after the stream is synchronised.  No host synchronisation inside.
  */
@@ -131,6 +133,10 @@ int64_t nimble_topo_nnz(const nimble_topo_t *topo);
  * of the bandwidth figure the benchmark reports. */
 int64_t nimble_topo_bytes_per_iter(const nimble_topo_t *topo);
 
+/* The same figure for one phase of the streaming regime (0: path-cost gather + argmin over
+ * the forward CSR, 1: link-load reduce over the reverse CSR, 2: length update). */
+int64_t nimble_topo_phase_bytes(const nimble_topo_t *topo, int32_t phase);
+
 /* Force a kernel regime (NIMBLE_REGIME_*) for later solves; NIMBLE_ERR_RANGE if the topology
  * does not fit that regime.  The regime actually used is returned by nimble_topo_regime. */
 nimble_status_t nimble_topo_set_regime(nimble_topo_t *topo, int32_t regime);
@@ -147,6 +153,16 @@ nimble_status_t nimble_debug_run_phase(nimble_topo_t *topo, int32_t phase, int32
                                        const double *d_traffic, void *hip_stream);
 
 /*
+ * Test helper for the persistent regime: every grid-wide barrier of that kernel waits at most
+ * `polls` polls of its arrival counter (default 2^22, about a second).  When a wait expires the
+ * solve is abandoned -- every workgroup leaves the kernel at its next poll, d_splits is left
+ * undefined and d_lambda[0] is written as NaN.  With polls = 0 the first barrier that is not
+ * already complete gives up, which lets a test exercise the abandon path without hanging
+ * anything.
+ */
+nimble_status_t nimble_debug_set_spin_limit(nimble_topo_t *topo, uint32_t polls);
+
+/*
  * Host-only helper (no device call): the reverse CSR exactly as nimble_topo_create builds it,
  * unpadded.  rev_ptr is host [n_links+1] out; rev_comm / rev_path are host [nnz] out (the
  * commodity and the candidate index inside that commodity of every incidence).  Returns the
@@ -157,6 +173,23 @@ nimble_status_t nimble_host_build_reverse(int32_t n_links, int32_t n_comm,
                                           const int32_t *path_link_ptr,
                                           const int32_t *path_links, int32_t *rev_ptr,
                                           int32_t *rev_comm, int32_t *rev_path);
+
+/*
+ * Host-only helper (no device call): repacks the forward CSR into the self-contained 4 KiB
+ * records the path-cost kernel streams (a run of consecutive commodities, the record's own
+ * link table, and a fixed number of 16-bit link-table indices per candidate) exactly as
+ * nimble_topo_create does, and reads every incidence back through them.  links_out is host
+ * [nnz] out and must equal path_links; path_record is host [n_paths] out, the record of every
+ * path; n_records_out receives the number of records, or 0 when the topology does not fit
+ * records (a path longer than 8 links, padding above 1.5x, more than 255 distinct links or
+ * 4 KiB for a single commodity) -- then the untiled kernel is used and the other outputs are
+ * not written.
+ */
+nimble_status_t nimble_host_records_roundtrip(int32_t n_links, int32_t n_comm,
+                                            const int32_t *comm_path_ptr, int32_t n_paths,
+                                            const int32_t *path_link_ptr,
+                                            const int32_t *path_links, int32_t *links_out,
+                                              int32_t *path_record, int32_t *n_records_out);
 
 #ifdef __cplusplus
 }

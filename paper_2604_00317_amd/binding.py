@@ -26,7 +26,8 @@ EXPORTS = [
     "nimble_last_error", "nimble_topo_num_links", "nimble_topo_num_comm",
     "nimble_topo_num_paths", "nimble_topo_nnz", "nimble_topo_bytes_per_iter",
     "nimble_topo_set_regime", "nimble_topo_regime", "nimble_debug_run_phase",
-    "nimble_host_build_reverse",
+    "nimble_host_build_reverse", "nimble_debug_set_spin_limit", "nimble_topo_phase_bytes",
+    "nimble_host_records_roundtrip",
 ]
 
 _lib = None
@@ -68,10 +69,16 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     for name in ("nimble_topo_nnz", "nimble_topo_bytes_per_iter"):
         getattr(lib, name).restype = i64
         getattr(lib, name).argtypes = [vp]
+    lib.nimble_topo_phase_bytes.restype = i64
+    lib.nimble_topo_phase_bytes.argtypes = [vp, i32]
     lib.nimble_topo_set_regime.restype = ctypes.c_int
     lib.nimble_topo_set_regime.argtypes = [vp, i32]
     lib.nimble_debug_run_phase.restype = ctypes.c_int
     lib.nimble_debug_run_phase.argtypes = [vp, i32, i32, vp, vp]
+    lib.nimble_debug_set_spin_limit.restype = ctypes.c_int
+    lib.nimble_debug_set_spin_limit.argtypes = [vp, u32]
+    lib.nimble_host_records_roundtrip.restype = ctypes.c_int
+    lib.nimble_host_records_roundtrip.argtypes = [i32, i32, vp, i32, vp, vp, vp, vp, vp]
     lib.nimble_host_build_reverse.restype = ctypes.c_int
     lib.nimble_host_build_reverse.argtypes = [i32, i32, vp, i32, vp, vp, vp, vp, vp]
     _lib = lib
@@ -136,6 +143,9 @@ class Topo:
     @property
     def bytes_per_iter(self) -> int:
         return load_library().nimble_topo_bytes_per_iter(self.handle)
+
+    def phase_bytes(self, phase: int) -> int:
+        return load_library().nimble_topo_phase_bytes(self.handle, int(phase))
 
     @property
     def regime(self) -> int:
@@ -202,6 +212,10 @@ def nimble_debug_run_phase(topo: Topo, phase: int, reps: int, d_traffic, stream=
         _dev_ptr(d_traffic, "float64", topo.n_comm, "d_traffic"), _stream_ptr(stream)))
 
 
+def nimble_debug_set_spin_limit(topo: Topo, polls: int) -> None:
+    _check(load_library().nimble_debug_set_spin_limit(topo.handle, int(polls)))
+
+
 def nimble_host_build_reverse(n_links, n_comm, comm_path_ptr, n_paths, path_link_ptr,
                               path_links):
     """Host-only: the reverse link -> (commodity, path) CSR as the library builds it."""
@@ -220,19 +234,37 @@ def nimble_host_build_reverse(n_links, n_comm, comm_path_ptr, n_paths, path_link
     return rev_ptr, rev_comm[:nnz], rev_path[:nnz]
 
 
+def nimble_host_records_roundtrip(n_links, n_comm, comm_path_ptr, n_paths, path_link_ptr,
+                                path_links):
+    """Host-only: (links read back through the tiles, tile of every path, number of tiles)."""
+    cp = _host(comm_path_ptr, np.int32)
+    lp = _host(path_link_ptr, np.int32)
+    pl = _host(path_links, np.int32)
+    links_out = np.full(max(int(lp[-1]), 1), -1, dtype=np.int32)
+    path_tile = np.full(max(n_paths, 1), -1, dtype=np.int32)
+    n_tiles = ctypes.c_int32(0)
+    st = load_library().nimble_host_records_roundtrip(n_links, n_comm, _hp(cp), n_paths, _hp(lp),
+                                                    _hp(pl), _hp(links_out), _hp(path_tile),
+                                                    ctypes.byref(n_tiles))
+    if st != NIMBLE_OK:
+        raise NimbleError(st, "tile round trip failed")
+    return links_out[:int(lp[-1])], path_tile[:n_paths], int(n_tiles.value)
+
+
 def plan(topo: Topo, traffic, eps: float, iters: int, device: str = "cuda:0"):
     """Convenience wrapper: host demand vector in, (splits, lambda) as numpy out."""
     import torch
     d = torch.as_tensor(np.ascontiguousarray(traffic, dtype=np.float64)).to(device)
+    nan = float("nan")     # outputs start poisoned so that stale memory can never pass a check
     if d.dim() == 1:
-        splits = torch.empty(topo.n_paths, dtype=torch.float64, device=device)
-        lam = torch.empty(1, dtype=torch.float64, device=device)
+        splits = torch.full((topo.n_paths,), nan, dtype=torch.float64, device=device)
+        lam = torch.full((1,), nan, dtype=torch.float64, device=device)
         nimble_plan_solve(topo, d, eps, iters, splits, lam)
         torch.cuda.synchronize()
         return splits.cpu().numpy(), float(lam.item())
     b = d.shape[0]
-    splits = torch.empty(b * topo.n_paths, dtype=torch.float64, device=device)
-    lam = torch.empty(b, dtype=torch.float64, device=device)
+    splits = torch.full((b * topo.n_paths,), nan, dtype=torch.float64, device=device)
+    lam = torch.full((b,), nan, dtype=torch.float64, device=device)
     nimble_plan_solve_batch(topo, b, d.reshape(-1), eps, iters, splits, lam)
     torch.cuda.synchronize()
     return splits.cpu().numpy().reshape(b, topo.n_paths), lam.cpu().numpy()

@@ -15,6 +15,7 @@
 #include "host_topo.hpp"
 #include "kernels.hpp"
 
+
 namespace {
 
 thread_local std::string g_last_error;
@@ -39,8 +40,11 @@ struct nimble_topo {
     int device = -1;
     int32_t forced_regime = NIMBLE_REGIME_AUTO;
     int32_t last_regime = NIMBLE_REGIME_AUTO;
-    int64_t bytes_per_iter = 0;
+    int64_t bytes_per_iter = 0, bytes_argmin = 0, bytes_reduce = 0, bytes_update = 0;
     bool state_ready = false;   // a stream-regime solve has initialised the workspace
+    void *sync_words = nullptr; // barrier counter and reductions of the persistent kernel
+    int n_cu = 0;
+    unsigned int spin_limit = 1u << 22;   // barrier polls before a solve is abandoned
 };
 
 namespace {
@@ -124,6 +128,17 @@ nimble_status_t solve_stream(nimble_topo *topo, const double *d_traffic, double 
     return NIMBLE_OK;
 }
 
+nimble_status_t solve_persistent(nimble_topo *topo, const double *d_traffic, double eps,
+                                 int32_t iters, double *d_splits, double *d_lambda,
+                                 hipStream_t s)
+{
+    hipError_t e = nimble::launch_persistent(topo->d, topo->sync_words, topo->n_cu,
+                                             topo->spin_limit, d_traffic, eps, iters, d_splits,
+                                             d_lambda, s);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch (persistent regime)");
+    return NIMBLE_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -153,8 +168,11 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     nimble::HostTopo h;
     try {
         t = new nimble_topo();
+        int ppl = 8;
+        if (const char *env = std::getenv("NIMBLE_TUNE_PAIRS_PER_LANE"))
+            if (std::atoi(env) == 16) ppl = 16;
         nimble::build_host_topo(n_links, cap, n_comm, comm_path_ptr, n_paths, path_link_ptr,
-                                path_links, h);
+                                path_links, ppl, h);
     } catch (const std::bad_alloc &) {
         delete t;
         return fail(NIMBLE_ERR_ALLOC, "host allocation failed");
@@ -171,12 +189,16 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     d.K = h.K;
     d.P = h.P;
     d.nnz = h.nnz;
-    d.rev_len = static_cast<int64_t>(h.rev_entry.size());
+    d.rev_pairs = static_cast<int64_t>(h.rev_pair.size() / 2);
+    d.pairs_per_lane = h.chunk_pairs / nimble::kRowLanesHost;
+    d.n_records = h.n_records;
+    d.rec_stride = h.rec_stride;
+    if (std::getenv("NIMBLE_TUNE_NO_RECORDS")) d.n_records = 0;
     d.pmax = h.pmax;
     d.lmax = h.lmax;
     d.n_chunks = static_cast<int32_t>(h.chunk_begin.size());
     d.cost_max = (flags & NIMBLE_COST_MAX) != 0u;
-    d.n_update_blocks = (h.E + 255) / 256;
+    d.n_update_blocks = (h.E + 15) / 16;   // 256-thread blocks, one 16-lane row per link
 
 #define NIMBLE_TRY(call, what)                        \
     do {                                              \
@@ -194,7 +216,9 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     NIMBLE_TRY(upload(t, path_link_ptr, static_cast<size_t>(h.P) + 1, &d.path_ptr), "path_ptr");
     NIMBLE_TRY(upload(t, path_links, static_cast<size_t>(h.nnz), &d.path_links), "path_links");
     NIMBLE_TRY(upload(t, h.rev_ptr.data(), h.rev_ptr.size(), &d.rev_ptr), "rev_ptr");
-    NIMBLE_TRY(upload(t, h.rev_entry.data(), h.rev_entry.size(), &d.rev_entry), "rev_entry");
+    NIMBLE_TRY(upload(t, h.rev_pair.data(), h.rev_pair.size(), &d.rev_pair), "rev_pair");
+    if (d.n_records > 0)
+        NIMBLE_TRY(upload(t, h.records.data(), h.records.size(), &d.records), "records");
     NIMBLE_TRY(upload(t, h.chunk_begin.data(), h.chunk_begin.size(), &d.chunk_begin),
                "chunk_begin");
     NIMBLE_TRY(upload(t, h.chunk_end.data(), h.chunk_end.size(), &d.chunk_end), "chunk_end");
@@ -208,14 +232,24 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     NIMBLE_TRY(allocate(t, static_cast<size_t>(h.P), &d.count), "count");
     NIMBLE_TRY(allocate(t, static_cast<size_t>(d.n_chunks), &d.partial), "partial");
     NIMBLE_TRY(allocate(t, static_cast<size_t>(d.n_update_blocks) + 1, &d.scalars), "scalars");
+    {
+        unsigned char *sw = nullptr;
+        NIMBLE_TRY(allocate(t, nimble::persistent_sync_bytes(), &sw), "sync words");
+        t->sync_words = sw;
+        NIMBLE_TRY(hipDeviceGetAttribute(&t->n_cu, hipDeviceAttributeMultiprocessorCount,
+                                         t->device),
+                   "hipDeviceGetAttribute");
+    }
 #undef NIMBLE_TRY
 
-    // stored bytes one iteration streams: forward CSR, reverse CSR with its chunk table and
-    // partials (written, then read), per-commodity outputs, per-link state
-    t->bytes_per_iter = 4LL * (h.K + 1) + 4LL * (h.P + 1) + 4LL * h.nnz       // argmin reads
-                        + 9LL * h.K                                           // choice w, count rw
-                        + 4LL * d.rev_len + 8LL * d.n_chunks + 8LL * d.n_chunks  // reduce
-                        + 8LL * d.n_chunks + 4LL * (h.E + 1) + 56LL * h.E;    // update
+    // stored bytes one iteration streams, phase by phase
+    if (d.n_records > 0)
+        t->bytes_argmin = static_cast<int64_t>(nimble::kRecBytes) * d.n_records + 9LL * h.K;
+    else
+        t->bytes_argmin = 4LL * (h.K + 1) + 4LL * (h.P + 1) + 4LL * h.nnz + 9LL * h.K;
+    t->bytes_reduce = 8LL * d.rev_pairs + 8LL * d.n_chunks + 8LL * d.n_chunks;
+    t->bytes_update = 8LL * d.n_chunks + 4LL * (h.E + 1) + 56LL * h.E;
+    t->bytes_per_iter = t->bytes_argmin + t->bytes_reduce + t->bytes_update;
     *out = t;
     return NIMBLE_OK;
 }
@@ -234,6 +268,17 @@ int64_t nimble_topo_nnz(const nimble_topo_t *t) { return t ? t->d.nnz : -1; }
 int64_t nimble_topo_bytes_per_iter(const nimble_topo_t *t) { return t ? t->bytes_per_iter : -1; }
 int32_t nimble_topo_regime(const nimble_topo_t *t) { return t ? t->last_regime : -1; }
 
+int64_t nimble_topo_phase_bytes(const nimble_topo_t *t, int32_t phase)
+{
+    if (!t) return -1;
+    switch (phase) {
+    case 0: return t->bytes_argmin;
+    case 1: return t->bytes_reduce;
+    case 2: return t->bytes_update;
+    default: return -1;
+    }
+}
+
 nimble_status_t nimble_topo_set_regime(nimble_topo_t *topo, int32_t regime)
 {
     g_last_error.clear();
@@ -241,13 +286,12 @@ nimble_status_t nimble_topo_set_regime(nimble_topo_t *topo, int32_t regime)
     switch (regime) {
     case NIMBLE_REGIME_AUTO:
     case NIMBLE_REGIME_STREAM:
+    case NIMBLE_REGIME_PERSISTENT:
         break;
     case NIMBLE_REGIME_RESIDENT:
         if (!nimble::resident_fits(topo->d))
             return fail(NIMBLE_ERR_RANGE, "per-plan state does not fit in LDS");
         break;
-    case NIMBLE_REGIME_PERSISTENT:
-        return fail(NIMBLE_ERR_RANGE, "persistent regime is not available in this build");
     default:
         return fail(NIMBLE_ERR_INVALID, "unknown regime");
     }
@@ -273,6 +317,8 @@ nimble_status_t nimble_plan_solve(nimble_topo_t *topo, const double *d_traffic, 
         if (e != hipSuccess) return fail_hip(e, "kernel launch (resident regime)");
         return NIMBLE_OK;
     }
+    if (regime == NIMBLE_REGIME_PERSISTENT)
+        return solve_persistent(topo, d_traffic, eps, iters, d_splits, d_lambda, s);
     return solve_stream(topo, d_traffic, eps, iters, d_splits, d_lambda, s);
 }
 
@@ -296,10 +342,21 @@ nimble_status_t nimble_plan_solve_batch(nimble_topo_t *topo, int32_t batch,
         return NIMBLE_OK;
     }
     for (int32_t b = 0; b < batch; ++b) {
-        st = solve_stream(topo, d_traffic + static_cast<size_t>(b) * topo->d.K, eps, iters,
-                          d_splits + static_cast<size_t>(b) * topo->d.P, d_lambda + b, s);
+        const double *tr = d_traffic + static_cast<size_t>(b) * topo->d.K;
+        double *sp = d_splits + static_cast<size_t>(b) * topo->d.P;
+        st = regime == NIMBLE_REGIME_PERSISTENT
+                 ? solve_persistent(topo, tr, eps, iters, sp, d_lambda + b, s)
+                 : solve_stream(topo, tr, eps, iters, sp, d_lambda + b, s);
         if (st != NIMBLE_OK) return st;
     }
+    return NIMBLE_OK;
+}
+
+nimble_status_t nimble_debug_set_spin_limit(nimble_topo_t *topo, uint32_t polls)
+{
+    g_last_error.clear();
+    if (!topo) return fail(NIMBLE_ERR_INVALID, "topology handle is NULL");
+    topo->spin_limit = polls;
     return NIMBLE_OK;
 }
 

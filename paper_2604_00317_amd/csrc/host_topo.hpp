@@ -1,5 +1,6 @@
 // Host-side preparation of a topology: validation of the two-level CSR, the reverse
-// link -> (commodity, path) CSR, and its split into fixed-size chunks.  No HIP calls here.
+// link -> (commodity, path set) CSR cut into fixed-size chunks, and the tiling of the forward
+// CSR with per-tile link tables.  No HIP calls here.
 #pragma once
 #include <cstdint>
 #include <string>
@@ -9,21 +10,42 @@
 
 namespace nimble {
 
-// Packed reverse entry: bit 31 = first entry of this commodity in this link's row,
-// bits 30..7 = commodity, bits 6..0 = candidate index inside the commodity.
-constexpr int kPathBits = 7;
-constexpr uint32_t kPathMask = (1u << kPathBits) - 1u;
+// ---- reverse CSR ------------------------------------------------------------------------
+// One 8-byte pair per (link, commodity, window of 32 candidates) that has at least one
+// candidate through the link:
+//   word A: bits 0..23 commodity, bits 24..25 window (candidates 32w .. 32w+31),
+//           bit 31 = first pair of this commodity in this link's row
+//   word B: bit j = candidate 32w+j of the commodity uses the link
+// Inside a row pairs ascend by (commodity, window); since a commodity routes on exactly one
+// candidate per iteration, at most one pair of a commodity hits, so summing the demands of
+// the hit pairs in row order is the sequential order of Algorithm 1's L_e += f.
 constexpr uint32_t kCommMask = (1u << 24) - 1u;
+constexpr int kWindowShift = 24;
 constexpr uint32_t kFirstFlag = 1u << 31;
 constexpr int32_t kMaxComm = (1 << 24) - 2;   // one id is kept as the padding sentinel
-constexpr int32_t kMaxPathsPerComm = 127;     // 0xFF in the choice array marks "no path"
-constexpr int32_t kRevChunk = 1024;           // reverse entries per reduction chunk
-constexpr int32_t kRevAlign = 4;              // rows are padded to 16 bytes
+constexpr int32_t kMaxPathsPerComm = 127;     // four windows of 32, index 255 never occurs
+constexpr int32_t kRowLanesHost = 16;         // lanes of one DPP row reduce one chunk
+constexpr int32_t kPairAlign = 2;             // rows are padded to 16 bytes (2 pairs)
 
-inline uint32_t pack_entry(uint32_t comm, uint32_t path, bool first)
-{
-    return (first ? kFirstFlag : 0u) | (comm << kPathBits) | path;
-}
+// ---- forward CSR records ------------------------------------------------------------------
+// The forward CSR is repacked into self-contained records of kRecBytes bytes, each holding a
+// run of consecutive commodities: a wave fetches one record with four 16-byte loads per lane
+// (no pointer chasing), finds in it the global ids of the record's distinct links (whose
+// prices it gathers into LDS), the first candidate of every commodity, and for every candidate
+// exactly `stride` 16-bit indices into the record's link table.  Paths shorter than the stride
+// are padded with the index n_links, whose price slot holds +0.0 (neutral for sum and for max
+// of positive prices).  Layout, offsets in bytes from the start of the record:
+//   0   int32 k0        first commodity
+//   4   int32 p0        first candidate path (global id)
+//   8   uint16 nk, np, n_links, off_cp, off_loc, reserved[3]
+//   24  int32 links[n_links]
+//   off_cp   uint16 cp16[nk+1]    first candidate of commodity i, relative to p0
+//   off_loc  uint16 loc16[np*stride]
+constexpr int32_t kRecBytes = 4096;
+constexpr int32_t kRecHeader = 24;
+constexpr int32_t kRecMaxLinks = 255;     // link table entries; slot n_links holds +0.0
+constexpr int32_t kRecMaxStride = 8;      // longest path a record can hold
+constexpr int32_t kRecMaxComm = 64;
 
 struct HostTopo {
     int32_t E = 0, K = 0, P = 0;
@@ -31,14 +53,20 @@ struct HostTopo {
     int32_t pmax = 0;       // most candidates of any commodity
     int32_t lmax = 0;       // most links of any path
     std::vector<double> invcap;
-    // reverse CSR, rows padded to kRevAlign entries with the sentinel commodity K
-    std::vector<int32_t> rev_ptr;        // [E+1], padded offsets
-    std::vector<uint32_t> rev_entry;     // [rev_ptr[E]]
-    std::vector<int32_t> rev_rowlen;     // [E], unpadded row lengths
-    // chunks of at most kRevChunk entries, never crossing a row
-    std::vector<int32_t> chunk_begin;    // [n_chunks]
+    // reverse CSR in pair units, rows padded to kPairAlign pairs with (commodity K, mask 0)
+    int32_t chunk_pairs = 128;           // pairs per reduction chunk (16 lanes x pairs per lane)
+    std::vector<int32_t> rev_ptr;        // [E+1], padded offsets in pairs
+    std::vector<uint32_t> rev_pair;      // [2 * rev_ptr[E]], words A,B interleaved
+    std::vector<int32_t> rev_rowlen;     // [E], unpadded row lengths in pairs
+    int64_t n_pairs = 0;                 // unpadded total
+    std::vector<int32_t> chunk_begin;    // [n_chunks], pair offsets
     std::vector<int32_t> chunk_end;      // [n_chunks]
     std::vector<int32_t> link_chunk_ptr; // [E+1]
+    // forward records (n_records = 0 when the topology does not fit them: a path longer than
+    // kRecMaxStride links, padding above 1.5x, or a commodity that alone overflows a record)
+    int32_t rec_stride = 0;              // indices per candidate = lmax
+    int32_t n_records = 0;
+    std::vector<uint8_t> records;        // [n_records * kRecBytes]
 };
 
 // Checks every documented precondition.  Returns NIMBLE_OK or the error; `why` gets the text.
@@ -47,9 +75,10 @@ nimble_status_t validate_csr(int32_t n_links, const double *cap, int32_t n_comm,
                              const int32_t *path_link_ptr, const int32_t *path_links,
                              std::string &why);
 
-// Builds everything in HostTopo from validated input.
+// Builds everything in HostTopo from validated input.  pairs_per_lane is 8 or 16.
 void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                      const int32_t *comm_path_ptr, int32_t n_paths,
-                     const int32_t *path_link_ptr, const int32_t *path_links, HostTopo &out);
+                     const int32_t *path_link_ptr, const int32_t *path_links,
+                     int32_t pairs_per_lane, HostTopo &out);
 
 }  // namespace nimble

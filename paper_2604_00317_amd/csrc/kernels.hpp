@@ -10,28 +10,35 @@ namespace nimble {
 struct DeviceTopo {
     int32_t E, K, P;
     int64_t nnz;
-    int64_t rev_len;   // padded length of rev_entry
     int32_t pmax, lmax;
-    int32_t n_chunks;
     bool cost_max;
     // forward CSR
     const int32_t *comm_ptr;   // [K+1]
     const int32_t *path_ptr;   // [P+1]
     const int32_t *path_links; // [nnz]
-    // reverse CSR (rows padded to 4 entries)
-    const int32_t *rev_ptr;    // [E+1]
-    const uint32_t *rev_entry; // [rev_ptr[E]]
-    const int32_t *chunk_begin, *chunk_end; // [n_chunks]
+    // forward CSR repacked into self-contained 4 KiB records (n_records = 0: not available)
+    int32_t n_records;
+    int32_t rec_stride;        // 16-bit link indices per candidate path
+    const uint8_t *records;
+    // reverse CSR of 8-byte (commodity, window | mask) pairs, rows padded to 2 pairs
+    int64_t rev_pairs;         // padded number of pairs
+    const int32_t *rev_ptr;    // [E+1], in pairs
+    const uint32_t *rev_pair;  // [2 * rev_pairs]
+    int32_t pairs_per_lane;    // 8 or 16: a chunk holds 16 * pairs_per_lane pairs
+    int32_t n_chunks;
+    const int32_t *chunk_begin, *chunk_end; // [n_chunks], in pairs
     const int32_t *link_chunk_ptr;          // [E+1]
     const double *invcap;      // [E]
     // state of the plan in flight
     double *len, *price, *S;   // [E]
-    uint8_t *choice;           // [K+1], choice[K] = 0xFF (padding sentinel)
+    uint8_t *choice;           // [K+1] (slot K is only ever read by padding pairs)
     uint32_t *count;           // [P]
     double *partial;           // [n_chunks]
     double *scalars;           // [0] = 1/rho, [1..] = per-block maxima of S
     int32_t n_update_blocks;
 };
+
+int lanes_per_commodity(int pmax);   // power of two >= pmax, at most 64
 
 // ---- streaming regime: one launch per phase ------------------------------------------------
 void launch_init(const DeviceTopo &t, hipStream_t s);
@@ -49,5 +56,14 @@ size_t resident_topo_bytes(const DeviceTopo &t);
 bool resident_fits(const DeviceTopo &t);
 hipError_t launch_resident(const DeviceTopo &t, int32_t batch, const double *demand, double eps,
                            int32_t iters, double *splits, double *lambda, hipStream_t s);
+
+// ---- persistent regime: one kernel per solve, grid barriers between the phases -------------
+// `sync_words` is device memory of persistent_sync_bytes() bytes owned by the topology.
+// `spin_limit` bounds every barrier wait (polls); when it expires the solve is abandoned and
+// lambda is written as NaN.
+size_t persistent_sync_bytes();
+hipError_t launch_persistent(const DeviceTopo &t, void *sync_words, int n_cu,
+                             unsigned int spin_limit, const double *demand, double eps,
+                             int32_t iters, double *splits, double *lambda, hipStream_t s);
 
 }  // namespace nimble

@@ -1,0 +1,246 @@
+// Persistent regime: the whole solve in ONE kernel.  The grid is sized to be co-resident
+// (blocks per CU from the occupancy query times the CU count) and the three phases of every
+// iteration are separated by grid-wide barriers instead of kernel boundaries.
+//
+// Barrier: one monotonically increasing arrival counter in device memory.  Thread 0 of every
+// block publishes the block's writes (agent-scope release fence), adds 1, and waits until the
+// counter reaches the next multiple of the grid size, then an acquire fence makes the other
+// blocks' writes visible.  The wait is bounded: after `spin_limit` polls a block raises the
+// abort word, every block sees it at its next poll and leaves the kernel, and the epilogue is
+// skipped (lambda is set to NaN by the block that gave up), so no wave can wait forever.
+#include "host_topo.hpp"
+#include "kernels.hpp"
+#include "phases.hpp"
+#include "wave_ops.hpp"
+
+namespace nimble {
+
+namespace {
+
+constexpr int kPBlock = 1024;
+constexpr int kPersistentPPL = 8;   // the reverse chunks must have been built for this
+
+struct SyncWords {
+    unsigned int arrivals;   // barrier counter
+    unsigned int abort;      // set when a bounded wait expired
+    unsigned long long rho_bits;    // max_e reach_e/cap_e as an ordered bit pattern (values >= 0)
+    unsigned long long smax_bits;   // max_e S_e likewise
+};
+
+__global__ void k_sync_reset(SyncWords *w)
+{
+    if (threadIdx.x == 0) {
+        w->arrivals = 0u;
+        w->abort = 0u;
+        w->rho_bits = 0ull;
+        w->smax_bits = 0ull;
+    }
+}
+
+// Returns false when the solve must be abandoned (bounded wait expired somewhere).
+__device__ __forceinline__ bool grid_barrier(SyncWords *w, unsigned int n_blocks,
+                                             unsigned int spin_limit, int *s_flag)
+{
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __threadfence();
+        const unsigned int old = __hip_atomic_fetch_add(&w->arrivals, 1u, __ATOMIC_RELAXED,
+                                                        __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned int target = (old / n_blocks + 1u) * n_blocks;
+        int ok = 1;
+        unsigned int polls = 0;
+        while (__hip_atomic_load(&w->arrivals, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) <
+               target) {
+            if (__hip_atomic_load(&w->abort, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) {
+                ok = 0;
+                break;
+            }
+            if (++polls > spin_limit) {
+                __hip_atomic_store(&w->abort, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                ok = 0;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        __threadfence();
+        *s_flag = ok;
+    }
+    __syncthreads();
+    return *s_flag != 0;
+}
+
+struct PersistentArgs {
+    int E, K, P, n_chunks;
+    uint32_t pad_comm;
+    const int32_t *cp, *lp, *pl;
+    const uint32_t *rev;
+    const int32_t *chunk_begin, *chunk_end, *link_chunk_ptr;
+    const double *invcap;
+    double *len, *price, *S;
+    uint8_t *choice;
+    uint32_t *count;
+    double *partial;
+    SyncWords *sync;
+    const double *demand;
+    double eps;
+    int iters;
+    double *splits, *lambda;
+    unsigned int spin_limit;
+};
+
+__device__ __forceinline__ void atomic_max_bits(unsigned long long *addr, double v)
+{
+    // v >= 0: the IEEE bit pattern is monotone in the value, so an integer max is exact
+    __hip_atomic_fetch_max(addr, static_cast<unsigned long long>(__double_as_longlong(v)),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+template <int L, int LMAX, bool MAXC>
+__global__ __launch_bounds__(kPBlock) void k_persistent(PersistentArgs a)
+{
+    __shared__ double red[16];
+    __shared__ int s_flag;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int n_waves = (gridDim.x * blockDim.x) >> 6;
+    const int tid = blockIdx.x * blockDim.x + threadIdx.x;
+    const int n_threads = gridDim.x * blockDim.x;
+    const unsigned int nb = gridDim.x;
+
+    // prologue: state and the width rho
+    for (int e = tid; e < a.E; e += n_threads) {
+        a.len[e] = 1.0;
+        a.price[e] = MAXC ? 1.0 : a.invcap[e];
+        a.S[e] = 0.0;
+    }
+    for (int p = tid; p < a.P; p += n_threads) a.count[p] = 0u;
+    reduce_phase<1, kPersistentPPL>(a.n_chunks, a.chunk_begin, a.chunk_end, a.rev, a.pad_comm, a.choice,
+                    a.demand, a.partial, wave, n_waves, lane);
+    if (!grid_barrier(a.sync, nb, a.spin_limit, &s_flag)) goto abandoned;
+    {
+        double m = width_phase(a.E, a.link_chunk_ptr, a.partial, a.invcap, wave, n_waves, lane);
+        m = block_max(m, red);
+        if (threadIdx.x == 0) atomic_max_bits(&a.sync->rho_bits, m);
+    }
+    if (!grid_barrier(a.sync, nb, a.spin_limit, &s_flag)) goto abandoned;
+    {
+        const double rho = __longlong_as_double(static_cast<long long>(__hip_atomic_load(
+            &a.sync->rho_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)));
+        const double invrho = (rho > 0.0) ? 1.0 / rho : 0.0;
+
+        for (int it = 0; it < a.iters; ++it) {
+            argmin_phase<L, LMAX, MAXC>(a.K, a.cp, a.lp, a.pl, a.price, a.choice, a.count, wave,
+                                        n_waves, lane);
+            if (!grid_barrier(a.sync, nb, a.spin_limit, &s_flag)) goto abandoned;
+            reduce_phase<0, kPersistentPPL>(a.n_chunks, a.chunk_begin, a.chunk_end, a.rev, a.pad_comm,
+                            a.choice,
+                            a.demand, a.partial, wave, n_waves, lane);
+            if (!grid_barrier(a.sync, nb, a.spin_limit, &s_flag)) goto abandoned;
+            update_phase<MAXC>(a.E, a.eps, invrho, a.link_chunk_ptr, a.partial, a.invcap, a.len,
+                               a.price, a.S, wave, n_waves, lane);
+            if (!grid_barrier(a.sync, nb, a.spin_limit, &s_flag)) goto abandoned;
+        }
+    }
+    // epilogue: split fractions and lambda = max_e S_e / iters
+    {
+        const double T = static_cast<double>(a.iters);
+        for (int p = tid; p < a.P; p += n_threads)
+            a.splits[p] = static_cast<double>(a.count[p]) / T;
+        double m = 0.0;
+        for (int e = tid; e < a.E; e += n_threads) m = fmax(m, a.S[e]);
+        m = block_max(m, red);
+        if (threadIdx.x == 0) atomic_max_bits(&a.sync->smax_bits, m);
+        if (!grid_barrier(a.sync, nb, a.spin_limit, &s_flag)) goto abandoned;
+        if (tid == 0) {
+            const double smax = __longlong_as_double(static_cast<long long>(__hip_atomic_load(
+                &a.sync->smax_bits, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)));
+            a.lambda[0] = smax / T;
+        }
+    }
+    return;
+abandoned:
+    if (tid == 0) a.lambda[0] = __builtin_nan("");
+}
+
+template <int L, int LMAX, bool MAXC>
+hipError_t launch_one(const PersistentArgs &a, int n_cu, hipStream_t s, int *grid_out)
+{
+    int per_cu = 0;
+    hipError_t e = hipOccupancyMaxActiveBlocksPerMultiprocessor(
+        &per_cu, reinterpret_cast<const void *>(&k_persistent<L, LMAX, MAXC>), kPBlock, 0);
+    if (e != hipSuccess) return e;
+    if (per_cu < 1) return hipErrorLaunchOutOfResources;
+    // one 1024-thread workgroup per CU: co-residency of the whole grid then only needs the
+    // kernel to fit a CU at all, whatever else the occupancy query assumes
+    const int grid = n_cu;
+    if (grid_out) *grid_out = grid;
+    hipLaunchKernelGGL((k_persistent<L, LMAX, MAXC>), dim3(grid), dim3(kPBlock), 0, s, a);
+    return hipGetLastError();
+}
+
+template <int L, bool MAXC>
+hipError_t launch_lmax(const PersistentArgs &a, int lmax, int n_cu, hipStream_t s, int *grid_out)
+{
+    if (lmax <= 2) return launch_one<L, 2, MAXC>(a, n_cu, s, grid_out);
+    if (lmax <= 4) return launch_one<L, 4, MAXC>(a, n_cu, s, grid_out);
+    return launch_one<L, 8, MAXC>(a, n_cu, s, grid_out);
+}
+
+template <bool MAXC>
+hipError_t launch_l(const PersistentArgs &a, int L, int lmax, int n_cu, hipStream_t s,
+                    int *grid_out)
+{
+    switch (L) {
+    case 1: return launch_lmax<1, MAXC>(a, lmax, n_cu, s, grid_out);
+    case 2: return launch_lmax<2, MAXC>(a, lmax, n_cu, s, grid_out);
+    case 4: return launch_lmax<4, MAXC>(a, lmax, n_cu, s, grid_out);
+    case 8: return launch_lmax<8, MAXC>(a, lmax, n_cu, s, grid_out);
+    case 16: return launch_lmax<16, MAXC>(a, lmax, n_cu, s, grid_out);
+    case 32: return launch_lmax<32, MAXC>(a, lmax, n_cu, s, grid_out);
+    default: return launch_lmax<64, MAXC>(a, lmax, n_cu, s, grid_out);
+    }
+}
+
+}  // namespace
+
+size_t persistent_sync_bytes() { return sizeof(SyncWords); }
+
+hipError_t launch_persistent(const DeviceTopo &t, void *sync_words, int n_cu,
+                             unsigned int spin_limit, const double *demand, double eps,
+                             int32_t iters, double *splits, double *lambda, hipStream_t s)
+{
+    if (t.pairs_per_lane != kPersistentPPL) return hipErrorInvalidValue;
+    PersistentArgs a;
+    a.E = t.E;
+    a.K = t.K;
+    a.P = t.P;
+    a.n_chunks = t.n_chunks;
+    a.pad_comm = static_cast<uint32_t>(t.K);
+    a.cp = t.comm_ptr;
+    a.lp = t.path_ptr;
+    a.pl = t.path_links;
+    a.rev = t.rev_pair;
+    a.chunk_begin = t.chunk_begin;
+    a.chunk_end = t.chunk_end;
+    a.link_chunk_ptr = t.link_chunk_ptr;
+    a.invcap = t.invcap;
+    a.len = t.len;
+    a.price = t.price;
+    a.S = t.S;
+    a.choice = t.choice;
+    a.count = t.count;
+    a.partial = t.partial;
+    a.sync = static_cast<SyncWords *>(sync_words);
+    a.demand = demand;
+    a.eps = eps;
+    a.iters = iters;
+    a.splits = splits;
+    a.lambda = lambda;
+    a.spin_limit = spin_limit;
+    hipLaunchKernelGGL(k_sync_reset, dim3(1), dim3(64), 0, s, a.sync);
+    const int L = lanes_per_commodity(t.pmax);
+    if (t.cost_max) return launch_l<true>(a, L, t.lmax, n_cu, s, nullptr);
+    return launch_l<false>(a, L, t.lmax, n_cu, s, nullptr);
+}
+
+}  // namespace nimble

@@ -6,7 +6,8 @@
 // Per iteration: each thread scans the candidates of its commodities in list order with a
 // strict `<` (Algorithm 1's scan), then each thread walks the reverse rows of its links in
 // ascending (commodity, path) order -- the sequential order of Algorithm 1's L_e += f -- and
-// applies the multiplicative length update.  Two workgroup barriers per iteration.
+// applies the multiplicative length update.  Reverse rows hold (commodity, window | mask) pairs,
+// ascending by commodity, of which at most one per commodity can hit.  Two workgroup barriers per iteration.
 #include "host_topo.hpp"
 #include "kernels.hpp"
 #include "wave_ops.hpp"
@@ -27,7 +28,7 @@ struct ResidentLayout {
 __host__ __device__ inline size_t align8(size_t x) { return (x + 7) & ~size_t(7); }
 
 __host__ __device__ inline ResidentLayout make_layout(int E, int K, int P, int64_t nnz,
-                                                      int64_t rev_len)
+                                                      int64_t rev_len /* pairs */)
 {
     ResidentLayout l;
     size_t o = 0;
@@ -40,7 +41,7 @@ __host__ __device__ inline ResidentLayout make_layout(int E, int K, int P, int64
     l.plan_bytes = o;
     l.topo_bytes = align8(sizeof(int32_t) * (K + 1)) + align8(sizeof(int32_t) * (P + 1)) +
                    align8(sizeof(int32_t) * nnz) + align8(sizeof(int32_t) * (E + 1)) +
-                   align8(sizeof(uint32_t) * rev_len) + sizeof(double) * E;
+                   align8(sizeof(uint32_t) * 2 * rev_len) + sizeof(double) * E;
     return l;
 }
 
@@ -86,13 +87,13 @@ __global__ __launch_bounds__(1024) void k_resident(
         int32_t *s_rp = reinterpret_cast<int32_t *>(tb);
         tb += align8(sizeof(int32_t) * (E + 1));
         uint32_t *s_rev = reinterpret_cast<uint32_t *>(tb);
-        tb += align8(sizeof(uint32_t) * rev_len);
+        tb += align8(sizeof(uint32_t) * 2 * rev_len);
         double *s_ic = reinterpret_cast<double *>(tb);
         for (int i = threadIdx.x; i <= K; i += blockDim.x) s_cp[i] = g_cp[i];
         for (int i = threadIdx.x; i <= P; i += blockDim.x) s_lp[i] = g_lp[i];
         for (int i = threadIdx.x; i < nnz; i += blockDim.x) s_pl[i] = g_pl[i];
         for (int i = threadIdx.x; i <= E; i += blockDim.x) s_rp[i] = g_rp[i];
-        for (int i = threadIdx.x; i < rev_len; i += blockDim.x) s_rev[i] = g_rev[i];
+        for (int i = threadIdx.x; i < 2 * rev_len; i += blockDim.x) s_rev[i] = g_rev[i];
         for (int i = threadIdx.x; i < E; i += blockDim.x) s_ic[i] = g_invcap[i];
         cp = s_cp; lp = s_lp; pl = s_pl; rp = s_rp; rev = s_rev; invcap = s_ic;
     }
@@ -100,7 +101,7 @@ __global__ __launch_bounds__(1024) void k_resident(
     const double *d_in = demand_all + static_cast<size_t>(live ? plan : 0) * K;
     for (int k = t; k < K; k += nt) demand[k] = d_in[k];
     for (int p = t; p < P; p += nt) count[p] = 0u;
-    if (t == 0) choice[K] = 0xFFu;
+    if (t == 0) choice[K] = 0u;   // slot K is read (never used) by padding pairs
     __syncthreads();
 
     // width rho: every commodity that can reach a link counts once (first-of-commodity flag)
@@ -108,8 +109,8 @@ __global__ __launch_bounds__(1024) void k_resident(
     for (int e = t; e < E; e += nt) {
         double reach = 0.0;
         for (int i = rp[e]; i < rp[e + 1]; ++i) {
-            const uint32_t ent = rev[i];
-            if (ent & kFirstFlag) reach = reach + demand[(ent >> kPathBits) & kCommMask];
+            const uint32_t wa = rev[2 * i];
+            if (wa & kFirstFlag) reach = reach + demand[wa & kCommMask];
         }
         const double ic = invcap[e];
         wmax = fmax(wmax, reach * ic);
@@ -161,9 +162,11 @@ __global__ __launch_bounds__(1024) void k_resident(
         for (int e = t; e < E; e += nt) {
             double load = 0.0;
             for (int i = rp[e]; i < rp[e + 1]; ++i) {
-                const uint32_t ent = rev[i];
-                const uint32_t k = (ent >> kPathBits) & kCommMask;
-                if (choice[k] == (ent & kPathMask)) load = load + demand[k];
+                const uint32_t wa = rev[2 * i], wb = rev[2 * i + 1];
+                const uint32_t k = wa & kCommMask;
+                const uint32_t ch = choice[k];
+                if ((ch >> 5) == ((wa >> kWindowShift) & 3u) && ((wb >> (ch & 31u)) & 1u))
+                    load = load + demand[k];
             }
             const double ic = invcap[e];
             const double u = load * ic;
@@ -205,7 +208,7 @@ struct ResidentPlan {
 
 bool plan_resident(const DeviceTopo &t, int batch, ResidentPlan &rp)
 {
-    const ResidentLayout lay = make_layout(t.E, t.K, t.P, t.nnz, t.rev_len);
+    const ResidentLayout lay = make_layout(t.E, t.K, t.P, t.nnz, t.rev_pairs);
     if (lay.plan_bytes + 256 > kLdsBudget) return false;
     int need = t.K > t.E ? t.K : t.E;
     int nt = kWave;
@@ -228,12 +231,12 @@ bool plan_resident(const DeviceTopo &t, int batch, ResidentPlan &rp)
 
 size_t resident_state_bytes(const DeviceTopo &t)
 {
-    return make_layout(t.E, t.K, t.P, t.nnz, t.rev_len).plan_bytes;
+    return make_layout(t.E, t.K, t.P, t.nnz, t.rev_pairs).plan_bytes;
 }
 
 size_t resident_topo_bytes(const DeviceTopo &t)
 {
-    return make_layout(t.E, t.K, t.P, t.nnz, t.rev_len).topo_bytes;
+    return make_layout(t.E, t.K, t.P, t.nnz, t.rev_pairs).topo_bytes;
 }
 
 bool resident_fits(const DeviceTopo &t)
@@ -251,9 +254,9 @@ hipError_t launch_resident(const DeviceTopo &t, int32_t batch, const double *dem
     const int block = rp.nt * rp.plans_per_block;
 #define NIMBLE_RES_LAUNCH(MAXC, TL)                                                            \
     hipLaunchKernelGGL((k_resident<MAXC, TL>), dim3(grid), dim3(block), rp.lds_bytes, s, t.E,  \
-                       t.K, t.P, static_cast<int>(t.nnz), static_cast<int>(t.rev_len), batch,  \
+                       t.K, t.P, static_cast<int>(t.nnz), static_cast<int>(t.rev_pairs), batch,  \
                        rp.nt, rp.plans_per_block, eps, iters, t.comm_ptr, t.path_ptr,          \
-                       t.path_links, t.rev_ptr, t.rev_entry, t.invcap, demand, splits, lambda)
+                       t.path_links, t.rev_ptr, t.rev_pair, t.invcap, demand, splits, lambda)
     if (t.cost_max) {
         if (rp.topo_lds) NIMBLE_RES_LAUNCH(true, true);
         else NIMBLE_RES_LAUNCH(true, false);

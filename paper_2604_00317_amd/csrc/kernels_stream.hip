@@ -1,13 +1,8 @@
-// Streaming regime: three kernels per Jacobi iteration.
-//   argmin       path-cost gather over the path->link CSR + per-commodity argmin
-//                (lowest index wins ties, the strict `<` scan of Algorithm 1)
-//   load_reduce  link loads over the reverse link->(commodity,path) CSR in fixed-size chunks,
-//                fixed reduction tree, no floating-point atomics (Algorithm 1: L_e += f)
-//   update       chunk partials -> load, congestion sum S_e, multiplicative length update
-//                len_e *= 1 + eps*u_e/rho, new price, per-block max of S (lambda)
-// All arithmetic is binary64 with one IEEE operation per statement (no contraction).
+// Streaming regime: three kernels per Jacobi iteration (path-cost gather + argmin, link-load
+// reduce, length update), each a thin wrapper over the phase code in phases.hpp.
 #include "host_topo.hpp"
 #include "kernels.hpp"
+#include "phases.hpp"
 #include "wave_ops.hpp"
 
 namespace nimble {
@@ -32,11 +27,10 @@ __global__ __launch_bounds__(kBlock) void k_init(int E, int K, int P, bool cost_
         S[e] = 0.0;
     }
     for (int p = tid; p < P; p += stride) count[p] = 0u;
-    if (tid == 0) choice[K] = 0xFFu;
+    if (tid == 0) choice[K] = 0u;   // slot K is read (never used) by padding pairs
 }
 
-// L lanes cooperate on one commodity: lane j evaluates candidates j, j+L, ...
-template <int L, bool MAXC>
+template <int L, int LMAX, bool MAXC>
 __global__ __launch_bounds__(kBlock) void k_argmin(int K, const int32_t *__restrict__ cp,
                                                    const int32_t *__restrict__ lp,
                                                    const int32_t *__restrict__ pl,
@@ -44,52 +38,101 @@ __global__ __launch_bounds__(kBlock) void k_argmin(int K, const int32_t *__restr
                                                    uint8_t *__restrict__ choice,
                                                    uint32_t *__restrict__ count)
 {
-    constexpr int kPerWave = kWave / L;
     const int lane = threadIdx.x & (kWave - 1);
-    const int sub = lane / L;          // commodity slot inside the wave
-    const int j0 = lane % L;           // first candidate of this lane
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
-    // wave-uniform loop so that every lane reaches the cross-lane reduction
-    for (int base = wave * kPerWave; base < K; base += n_waves * kPerWave) {
-        const int k = base + sub;
+    argmin_phase<L, LMAX, MAXC>(K, cp, lp, pl, price, choice, count, wave, n_waves, lane);
+}
+
+// Record path-cost gather + argmin: one wave (a 64-thread workgroup) per 4 KiB record of the
+// forward CSR.  The wave copies its record into LDS with four 16-byte loads per lane, gathers
+// the prices of the record's link table (the only access that leaves the record), and then L
+// lanes per commodity add S prices per candidate from LDS in CSR order -- padding slots read
+// +0.0 -- and reduce (cost, index) across the group.  The sums are the same IEEE operations in
+// the same order as in the untiled kernel.
+template <int L, int S, bool MAXC>
+__global__ __launch_bounds__(kWave) void k_argmin_rec(int n_records,
+                                                      const uint8_t *__restrict__ records,
+                                                      const double *__restrict__ price,
+                                                      uint8_t *__restrict__ choice,
+                                                      uint32_t *__restrict__ count)
+{
+    __shared__ __align__(16) uint8_t s_rec[kRecBytes];
+    __shared__ double s_price[kRecMaxLinks + 1];
+    constexpr int kGroups = kWave / L;
+    const int lane = threadIdx.x;
+    const int g = lane / L;
+    const int j = lane % L;
+    const int rec = blockIdx.x;
+    if (rec >= n_records) return;
+    {
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(records + size_t(rec) * kRecBytes);
+        u32x4 v[4];
+#pragma unroll
+        for (int it = 0; it < 4; ++it) v[it] = stream_load(src + it * kWave + lane);
+#pragma unroll
+        for (int it = 0; it < 4; ++it)
+            reinterpret_cast<u32x4 *>(s_rec)[it * kWave + lane] = v[it];
+    }
+    __syncthreads();
+    const int k0 = *reinterpret_cast<const int32_t *>(s_rec);
+    const int p0 = *reinterpret_cast<const int32_t *>(s_rec + 4);
+    const uint16_t *h16 = reinterpret_cast<const uint16_t *>(s_rec + 8);
+    const int nk = h16[0], nl = h16[2];
+    const int32_t *links = reinterpret_cast<const int32_t *>(s_rec + kRecHeader);
+    const uint16_t *cp16 = reinterpret_cast<const uint16_t *>(s_rec + h16[3]);
+    const uint16_t *loc16 = reinterpret_cast<const uint16_t *>(s_rec + h16[4]);
+    for (int i = lane; i < nl; i += kWave) s_price[i] = price[links[i]];
+    if (lane == 0) s_price[nl] = 0.0;
+    __syncthreads();
+    const int rounds = (nk + kGroups - 1) / kGroups;
+    for (int r = 0; r < rounds; ++r) {            // wave-uniform: all lanes reach the reduction
+        const int c = r * kGroups + g;
         double best = __builtin_inf();
         int bj = 0x7FFFFFFF;
-        int p0 = 0;
-        if (k < K) {
-            p0 = cp[k];
-            const int np = cp[k + 1] - p0;
-            if (j0 < np) bj = j0;      // an all-infinite commodity still resolves to candidate 0
-            for (int j = j0; j < np; j += L) {
-                const int a = lp[p0 + j], b = lp[p0 + j + 1];
-                double c = 0.0;
-                for (int i = a; i < b; ++i) {
-                    const double pe = price[pl[i]];
-                    if constexpr (MAXC) c = (pe > c) ? pe : c;
-                    else c = c + pe;
+        int p_lo = 0;
+        bool valid = false;
+        if (c < nk) {
+            p_lo = cp16[c];
+            const int np = cp16[c + 1] - p_lo;
+            valid = j < np;
+            if (valid) bj = j;
+            for (int jj = j; jj < np; jj += L) {
+                const uint16_t *lp = loc16 + (p_lo + jj) * S;
+                int idx[S];
+#pragma unroll
+                for (int i = 0; i < S; ++i) idx[i] = lp[i];
+                double cst = 0.0;
+#pragma unroll
+                for (int i = 0; i < S; ++i) {
+                    const double pe = s_price[idx[i]];
+                    if constexpr (MAXC) cst = (pe > cst) ? pe : cst;
+                    else cst = cst + pe;
                 }
-                if (c < best) {
-                    best = c;
-                    bj = j;
+                if (cst < best) {
+                    best = cst;
+                    bj = jj;
                 }
             }
         }
-        group_argmin<L>(best, bj);
-        if (k < K && j0 == 0) {
-            choice[k] = static_cast<uint8_t>(bj);
-            count[p0 + bj] += 1u;
+        if constexpr (L < kWave) {
+            bj = group_argmin_ballot<L>(best, valid);     // np <= pmax <= L: one per lane
+        } else {
+            group_argmin<L>(best, bj);
+        }
+        if (c < nk && j == 0) {
+            choice[k0 + c] = static_cast<uint8_t>(bj);
+            count[p0 + p_lo + bj] += 1u;
         }
     }
 }
 
-// One wave per chunk of the reverse CSR.  MODE 0: an entry contributes d_k when candidate j is
-// the chosen one.  MODE 1 (width rho): an entry contributes when it is the first of its
-// commodity in the row, i.e. every commodity that can reach the link counts once.
-template <int MODE>
+template <int MODE, int PPL>
 __global__ __launch_bounds__(kBlock) void k_load_reduce(int n_chunks,
                                                         const int32_t *__restrict__ chunk_begin,
                                                         const int32_t *__restrict__ chunk_end,
                                                         const uint32_t *__restrict__ rev,
+                                                        uint32_t pad_comm,
                                                         const uint8_t *__restrict__ choice,
                                                         const double *__restrict__ demand,
                                                         double *__restrict__ partial)
@@ -97,44 +140,24 @@ __global__ __launch_bounds__(kBlock) void k_load_reduce(int n_chunks,
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
-    for (int c = wave; c < n_chunks; c += n_waves) {
-        const int b = chunk_begin[c], e = chunk_end[c];
-        double acc = 0.0;
-        for (int i = b + lane * 4; i < e; i += kWave * 4) {
-            const uint4 v = *reinterpret_cast<const uint4 *>(rev + i);
-            const uint32_t ent[4] = {v.x, v.y, v.z, v.w};
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t k = (ent[q] >> kPathBits) & kCommMask;
-                bool hit;
-                if constexpr (MODE == 0) hit = choice[k] == (ent[q] & kPathMask);
-                else hit = (ent[q] & kFirstFlag) != 0u;
-                if (hit) acc = acc + demand[k];
-            }
-        }
-        acc = wave_sum(acc);
-        if (lane == 0) partial[c] = acc;
-    }
+    reduce_phase<MODE, PPL>(n_chunks, chunk_begin, chunk_end, rev, pad_comm, choice, demand,
+                            partial, wave, n_waves, lane);
 }
 
-// reach_e = sum of chunk partials, rho = max_e reach_e / cap_e, scalars[0] = 1/rho (0 if rho=0)
+// rho = max_e (demand that can reach e) / cap_e; scalars[0] = 1/rho (0 when rho = 0)
 __global__ __launch_bounds__(1024) void k_width(int E, const int32_t *__restrict__ link_chunk_ptr,
                                                 const double *__restrict__ partial,
                                                 const double *__restrict__ invcap,
                                                 double *__restrict__ scalars)
 {
     __shared__ double red[16];
-    double m = 0.0;
-    for (int e = threadIdx.x; e < E; e += blockDim.x) {
-        double reach = 0.0;
-        for (int c = link_chunk_ptr[e]; c < link_chunk_ptr[e + 1]; ++c) reach = reach + partial[c];
-        const double w = reach * invcap[e];
-        m = fmax(m, w);
-    }
+    double m = width_phase(E, link_chunk_ptr, partial, invcap, threadIdx.x >> 6, blockDim.x >> 6,
+                           threadIdx.x & (kWave - 1));
     m = block_max(m, red);
     if (threadIdx.x == 0) scalars[0] = (m > 0.0) ? 1.0 / m : 0.0;
 }
 
+// length update fused with the per-block maximum of the congestion sums (lambda = max / iters)
 template <bool MAXC>
 __global__ __launch_bounds__(kBlock) void k_update(int E, double eps,
                                                    const int32_t *__restrict__ link_chunk_ptr,
@@ -146,23 +169,11 @@ __global__ __launch_bounds__(kBlock) void k_update(int E, double eps,
                                                    double *__restrict__ scalars)
 {
     __shared__ double red[16];
-    const int e = blockIdx.x * blockDim.x + threadIdx.x;
-    double s_new = 0.0;
-    if (e < E) {
-        const double invrho = scalars[0];
-        double load = 0.0;
-        for (int c = link_chunk_ptr[e]; c < link_chunk_ptr[e + 1]; ++c) load = load + partial[c];
-        const double ic = invcap[e];
-        const double u = load * ic;
-        s_new = S[e] + u;
-        S[e] = s_new;
-        const double g = u * invrho;
-        const double t1 = eps * g;
-        const double t2 = 1.0 + t1;
-        const double l = len[e] * t2;
-        len[e] = l;
-        price[e] = MAXC ? l : l * ic;
-    }
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int n_waves = (gridDim.x * blockDim.x) >> 6;
+    const double s_new = update_phase<MAXC>(E, eps, scalars[0], link_chunk_ptr, partial, invcap,
+                                            len, price, S, wave, n_waves, lane);
     const double m = block_max(s_new, red);
     if (threadIdx.x == 0) scalars[1 + blockIdx.x] = m;
 }
@@ -195,30 +206,76 @@ inline int blocks_for(int64_t threads, int block, int cap)
     return static_cast<int>(b);
 }
 
+template <int L, bool MAXC>
+void launch_argmin_lmax(const DeviceTopo &t, int grid, hipStream_t s)
+{
+    if (t.n_records > 0) {
+#define NIMBLE_REC_LAUNCH(SS)                                                                  \
+    case SS:                                                                                   \
+        hipLaunchKernelGGL((k_argmin_rec<L, SS, MAXC>), dim3(t.n_records), dim3(kWave), 0, s,  \
+                           t.n_records, t.records, t.price, t.choice, t.count);                \
+        return;
+        switch (t.rec_stride) {
+            NIMBLE_REC_LAUNCH(1)
+            NIMBLE_REC_LAUNCH(2)
+            NIMBLE_REC_LAUNCH(3)
+            NIMBLE_REC_LAUNCH(4)
+            NIMBLE_REC_LAUNCH(5)
+            NIMBLE_REC_LAUNCH(6)
+            NIMBLE_REC_LAUNCH(7)
+            NIMBLE_REC_LAUNCH(8)
+        }
+#undef NIMBLE_REC_LAUNCH
+    }
+#define NIMBLE_ARGMIN_LAUNCH(LM)                                                              \
+    hipLaunchKernelGGL((k_argmin<L, LM, MAXC>), dim3(grid), dim3(kBlock), 0, s, t.K,          \
+                       t.comm_ptr, t.path_ptr, t.path_links, t.price, t.choice, t.count)
+    if (t.lmax <= 2) NIMBLE_ARGMIN_LAUNCH(2);
+    else if (t.lmax <= 4) NIMBLE_ARGMIN_LAUNCH(4);
+    else NIMBLE_ARGMIN_LAUNCH(8);
+#undef NIMBLE_ARGMIN_LAUNCH
+}
+
 template <bool MAXC>
 void launch_argmin_l(const DeviceTopo &t, hipStream_t s)
 {
-    int L = 1;
-    while (L < t.pmax && L < kWave) L <<= 1;
+    const int L = lanes_per_commodity(t.pmax);
     const int grid = blocks_for(static_cast<int64_t>(t.K) * L, kBlock, 1 << 20);
-#define NIMBLE_ARGMIN_CASE(LL)                                                                 \
-    case LL:                                                                                   \
-        hipLaunchKernelGGL((k_argmin<LL, MAXC>), dim3(grid), dim3(kBlock), 0, s, t.K,          \
-                           t.comm_ptr, t.path_ptr, t.path_links, t.price, t.choice, t.count);  \
-        break;
     switch (L) {
-        NIMBLE_ARGMIN_CASE(1)
-        NIMBLE_ARGMIN_CASE(2)
-        NIMBLE_ARGMIN_CASE(4)
-        NIMBLE_ARGMIN_CASE(8)
-        NIMBLE_ARGMIN_CASE(16)
-        NIMBLE_ARGMIN_CASE(32)
-        NIMBLE_ARGMIN_CASE(64)
+    case 1: launch_argmin_lmax<1, MAXC>(t, grid, s); break;
+    case 2: launch_argmin_lmax<2, MAXC>(t, grid, s); break;
+    case 4: launch_argmin_lmax<4, MAXC>(t, grid, s); break;
+    case 8: launch_argmin_lmax<8, MAXC>(t, grid, s); break;
+    case 16: launch_argmin_lmax<16, MAXC>(t, grid, s); break;
+    case 32: launch_argmin_lmax<32, MAXC>(t, grid, s); break;
+    default: launch_argmin_lmax<64, MAXC>(t, grid, s); break;
     }
-#undef NIMBLE_ARGMIN_CASE
+}
+
+template <int MODE>
+void launch_reduce_mode(const DeviceTopo &t, const double *demand, hipStream_t s)
+{
+    const int64_t waves = (static_cast<int64_t>(t.n_chunks) + kRowsPerWave - 1) / kRowsPerWave;
+    const int grid = blocks_for(waves * kWave, kBlock, 1 << 20);
+    const uint32_t pad_comm = static_cast<uint32_t>(t.K);
+    if (t.pairs_per_lane == 16)
+        hipLaunchKernelGGL((k_load_reduce<MODE, 16>), dim3(grid), dim3(kBlock), 0, s, t.n_chunks,
+                           t.chunk_begin, t.chunk_end, t.rev_pair, pad_comm, t.choice, demand,
+                           t.partial);
+    else
+        hipLaunchKernelGGL((k_load_reduce<MODE, 8>), dim3(grid), dim3(kBlock), 0, s, t.n_chunks,
+                           t.chunk_begin, t.chunk_end, t.rev_pair, pad_comm, t.choice, demand,
+                           t.partial);
 }
 
 }  // namespace
+
+int lanes_per_commodity(int pmax)
+{
+    int L = 1;
+    while (L < pmax && L < kWave) L <<= 1;
+    return L;
+}
 
 void launch_init(const DeviceTopo &t, hipStream_t s)
 {
@@ -229,12 +286,7 @@ void launch_init(const DeviceTopo &t, hipStream_t s)
 
 void launch_width(const DeviceTopo &t, const double *demand, hipStream_t s)
 {
-    if (t.n_chunks > 0)
-        hipLaunchKernelGGL(k_load_reduce<1>,
-                           dim3(blocks_for(static_cast<int64_t>(t.n_chunks) * kWave, kBlock,
-                                           1 << 20)),
-                           dim3(kBlock), 0, s, t.n_chunks, t.chunk_begin, t.chunk_end,
-                           t.rev_entry, t.choice, demand, t.partial);
+    launch_reduce_mode<1>(t, demand, s);
     hipLaunchKernelGGL(k_width, dim3(1), dim3(1024), 0, s, t.E, t.link_chunk_ptr, t.partial,
                        t.invcap, t.scalars);
 }
@@ -247,10 +299,7 @@ void launch_argmin(const DeviceTopo &t, hipStream_t s)
 
 void launch_load_reduce(const DeviceTopo &t, const double *demand, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_load_reduce<0>,
-                       dim3(blocks_for(static_cast<int64_t>(t.n_chunks) * kWave, kBlock, 1 << 20)),
-                       dim3(kBlock), 0, s, t.n_chunks, t.chunk_begin, t.chunk_end, t.rev_entry,
-                       t.choice, demand, t.partial);
+    launch_reduce_mode<0>(t, demand, s);
 }
 
 void launch_update(const DeviceTopo &t, double eps, hipStream_t s)

@@ -75,6 +75,28 @@ __device__ __forceinline__ void group_argmin(double &c, int &j)
     if constexpr (L > 32) argmin_stage<32>(c, j);
 }
 
+// Argmin over aligned groups of L < 64 lanes when every lane holds at most one candidate and
+// the candidate index equals the lane's position in its group: min-reduce the costs, then the
+// lowest lane whose cost equals the minimum wins (the tie rule "lowest index").  `valid` marks
+// lanes that hold a candidate; a group whose costs are all +inf resolves to its first lane.
+// Returns the winning position in every lane of the group.
+template <int L>
+__device__ __forceinline__ int group_argmin_ballot(double c, bool valid)
+{
+    static_assert(L < 64, "one candidate per lane only");
+    double m = c;
+    if constexpr (L > 1) m = fmin(m, partner_f64<1>(m));
+    if constexpr (L > 2) m = fmin(m, partner_f64<2>(m));
+    if constexpr (L > 4) m = fmin(m, partner_f64<4>(m));
+    if constexpr (L > 8) m = fmin(m, partner_f64<8>(m));
+    if constexpr (L > 16) m = fmin(m, partner_f64<16>(m));
+    const unsigned long long win = __ballot(valid && c == m);
+    const int lane = threadIdx.x & (kWave - 1);
+    const unsigned int mine =
+        static_cast<unsigned int>(win >> (lane & ~(L - 1))) & ((L == 32) ? 0xFFFFFFFFu : ((1u << L) - 1u));
+    return __ffs(mine) - 1;
+}
+
 // Sum over the 64 lanes in a fixed butterfly order (the same tree on every run).
 __device__ __forceinline__ double wave_sum(double v)
 {

@@ -111,3 +111,39 @@ def test_reverse_csr_random_ragged():
             p = t.comm_path_ptr[k] + j
             assert e in t.path_links[t.path_link_ptr[p]:t.path_link_ptr[p + 1]]
     assert rev_ptr[-1] == t.nnz
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 3])
+def test_forward_records_round_trip(cfg):
+    t = W.config_topology(cfg)
+    links, path_rec, n_rec = B.nimble_host_records_roundtrip(
+        t.n_links, t.n_comm, t.comm_path_ptr, t.n_paths, t.path_link_ptr, t.path_links)
+    assert n_rec >= 1
+    assert np.array_equal(links, t.path_links)
+    # records are runs of whole commodities, in order
+    assert np.all(np.diff(path_rec) >= 0) and path_rec[-1] == n_rec - 1
+    assert np.array_equal(path_rec[t.comm_path_ptr[:-1]], path_rec[t.comm_path_ptr[1:] - 1])
+    # a 4 KiB record cannot hold more 16-bit indices than fit it
+    stride = int(np.diff(t.path_link_ptr).max())
+    assert np.bincount(path_rec).max() * stride * 2 <= 4096
+
+
+def test_forward_records_ragged_and_unfit():
+    rng = np.random.default_rng(21)
+    t = W.random_topology(rng, n_links=300, n_comm=700, max_paths=20, max_len=2)
+    links, path_rec, n_rec = B.nimble_host_records_roundtrip(
+        t.n_links, t.n_comm, t.comm_path_ptr, t.n_paths, t.path_link_ptr, t.path_links)
+    assert n_rec > 1 and np.array_equal(links, t.path_links)
+    # paths of 70 links exceed the record stride: no records, the untiled kernel is used
+    E, npth, ln = 80, 100, 70
+    pl = np.concatenate([rng.choice(E, size=ln, replace=False) for _ in range(npth)])
+    _, _, n_rec = B.nimble_host_records_roundtrip(E, 1, [0, npth], npth,
+                                                  np.arange(npth + 1) * ln, pl)
+    assert n_rec == 0
+    # one commodity with 127 candidates of 8 links needs 2032 indices + its links: fits;
+    # with 300 distinct links it exceeds the 255-entry link table: no records
+    E, npth, ln = 400, 127, 8
+    pl = np.concatenate([rng.choice(E, size=ln, replace=False) for _ in range(npth)])
+    _, _, n_rec = B.nimble_host_records_roundtrip(E, 1, [0, npth], npth,
+                                                  np.arange(npth + 1) * ln, pl)
+    assert n_rec == 0
