@@ -191,6 +191,17 @@ nimble_status_t nimble_host_records_roundtrip(int32_t n_links, int32_t n_comm,
                                             const int32_t *path_links, int32_t *links_out,
                                               int32_t *path_record, int32_t *n_records_out);
 
+/*
+ * Host-only helper (no device call): sizes of the device layout nimble_topo_create would build.
+ * out is host int64 [8]: (commodity, window) pairs of the reverse CSR; octets; single pairs;
+ * octet chunks; single-pair chunks; partial-sum slots; forward records; indices per candidate
+ * in a record.
+ */
+nimble_status_t nimble_host_layout_stats(int32_t n_links, int32_t n_comm,
+                                         const int32_t *comm_path_ptr, int32_t n_paths,
+                                         const int32_t *path_link_ptr,
+                                         const int32_t *path_links, int64_t *out);
+
 #ifdef __cplusplus
 }
 #endif

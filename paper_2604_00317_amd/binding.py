@@ -27,7 +27,7 @@ EXPORTS = [
     "nimble_topo_num_paths", "nimble_topo_nnz", "nimble_topo_bytes_per_iter",
     "nimble_topo_set_regime", "nimble_topo_regime", "nimble_debug_run_phase",
     "nimble_host_build_reverse", "nimble_debug_set_spin_limit", "nimble_topo_phase_bytes",
-    "nimble_host_records_roundtrip",
+    "nimble_host_records_roundtrip", "nimble_host_layout_stats",
 ]
 
 _lib = None
@@ -79,6 +79,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.nimble_debug_set_spin_limit.argtypes = [vp, u32]
     lib.nimble_host_records_roundtrip.restype = ctypes.c_int
     lib.nimble_host_records_roundtrip.argtypes = [i32, i32, vp, i32, vp, vp, vp, vp, vp]
+    lib.nimble_host_layout_stats.restype = ctypes.c_int
+    lib.nimble_host_layout_stats.argtypes = [i32, i32, vp, i32, vp, vp, vp]
     lib.nimble_host_build_reverse.restype = ctypes.c_int
     lib.nimble_host_build_reverse.argtypes = [i32, i32, vp, i32, vp, vp, vp, vp, vp]
     _lib = lib
@@ -249,6 +251,21 @@ def nimble_host_records_roundtrip(n_links, n_comm, comm_path_ptr, n_paths, path_
     if st != NIMBLE_OK:
         raise NimbleError(st, "tile round trip failed")
     return links_out[:int(lp[-1])], path_tile[:n_paths], int(n_tiles.value)
+
+
+def nimble_host_layout_stats(n_links, n_comm, comm_path_ptr, n_paths, path_link_ptr, path_links):
+    """Host-only: dict of the sizes of the device layout (see include/nimble_plan.h)."""
+    cp = _host(comm_path_ptr, np.int32)
+    lp = _host(path_link_ptr, np.int32)
+    pl = _host(path_links, np.int32)
+    out = np.zeros(8, dtype=np.int64)
+    st = load_library().nimble_host_layout_stats(n_links, n_comm, _hp(cp), n_paths, _hp(lp),
+                                                 _hp(pl), _hp(out))
+    if st != NIMBLE_OK:
+        raise NimbleError(st, "invalid CSR")
+    keys = ["pairs", "octets", "singles", "octet_chunks", "single_chunks", "slots", "records",
+            "record_stride"]
+    return dict(zip(keys, (int(v) for v in out)))
 
 
 def plan(topo: Topo, traffic, eps: float, iters: int, device: str = "cuda:0"):

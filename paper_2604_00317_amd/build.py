@@ -18,7 +18,8 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=o
 
 def build(verbose: bool = False) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *FLAGS, "-shared", "-o", LIB]
+    extra = os.environ.get("NIMBLE_EXTRA_HIPCC_FLAGS", "").split()
+    cmd = [hipcc, *FLAGS, *extra, "-shared", "-o", LIB]
     for s in SOURCES:
         src = os.path.join(CSRC, s)
         if s.endswith(".cpp"):

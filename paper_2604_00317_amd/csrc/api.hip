@@ -114,7 +114,7 @@ nimble_status_t solve_stream(nimble_topo *topo, const double *d_traffic, double 
                              int32_t iters, double *d_splits, double *d_lambda, hipStream_t s)
 {
     const nimble::DeviceTopo &d = topo->d;
-    nimble::launch_init(d, s);
+    nimble::launch_init(d, d_traffic, s);
     nimble::launch_width(d, d_traffic, s);
     for (int32_t it = 0; it < iters; ++it) {
         nimble::launch_argmin(d, s);
@@ -168,11 +168,13 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     nimble::HostTopo h;
     try {
         t = new nimble_topo();
-        int ppl = 8;
-        if (const char *env = std::getenv("NIMBLE_TUNE_PAIRS_PER_LANE"))
-            if (std::atoi(env) == 16) ppl = 16;
+        int opl = nimble::kOctetsPerLane;
+        if (const char *env = std::getenv("NIMBLE_TUNE_OCTETS_PER_LANE")) {
+            const int v = std::atoi(env);
+            if (v == 1 || v == 2 || v == 4) opl = v;
+        }
         nimble::build_host_topo(n_links, cap, n_comm, comm_path_ptr, n_paths, path_link_ptr,
-                                path_links, ppl, h);
+                                path_links, opl, h);
     } catch (const std::bad_alloc &) {
         delete t;
         return fail(NIMBLE_ERR_ALLOC, "host allocation failed");
@@ -190,13 +192,15 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     d.P = h.P;
     d.nnz = h.nnz;
     d.rev_pairs = static_cast<int64_t>(h.rev_pair.size() / 2);
-    d.pairs_per_lane = h.chunk_pairs / nimble::kRowLanesHost;
     d.n_records = h.n_records;
     d.rec_stride = h.rec_stride;
     if (std::getenv("NIMBLE_TUNE_NO_RECORDS")) d.n_records = 0;
     d.pmax = h.pmax;
     d.lmax = h.lmax;
-    d.n_chunks = static_cast<int32_t>(h.chunk_begin.size());
+    d.n_ochunks = static_cast<int32_t>(h.ochunk_begin.size());
+    d.n_schunks = static_cast<int32_t>(h.schunk_begin.size());
+    d.n_slots = h.n_slots;
+    d.octets_per_lane = h.octets_per_lane;
     d.cost_max = (flags & NIMBLE_COST_MAX) != 0u;
     d.n_update_blocks = (h.E + 15) / 16;   // 256-thread blocks, one 16-lane row per link
 
@@ -219,18 +223,32 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     NIMBLE_TRY(upload(t, h.rev_pair.data(), h.rev_pair.size(), &d.rev_pair), "rev_pair");
     if (d.n_records > 0)
         NIMBLE_TRY(upload(t, h.records.data(), h.records.size(), &d.records), "records");
-    NIMBLE_TRY(upload(t, h.chunk_begin.data(), h.chunk_begin.size(), &d.chunk_begin),
-               "chunk_begin");
-    NIMBLE_TRY(upload(t, h.chunk_end.data(), h.chunk_end.size(), &d.chunk_end), "chunk_end");
-    NIMBLE_TRY(upload(t, h.link_chunk_ptr.data(), h.link_chunk_ptr.size(), &d.link_chunk_ptr),
-               "link_chunk_ptr");
+    NIMBLE_TRY(upload(t, h.oct_base.data(), h.oct_base.size(), &d.oct_base), "oct_base");
+    NIMBLE_TRY(upload(t, h.oct_mask.data(), h.oct_mask.size(), &d.oct_mask), "oct_mask");
+    NIMBLE_TRY(upload(t, h.single_pair.data(), h.single_pair.size(), &d.single_pair),
+               "single_pair");
+    NIMBLE_TRY(upload(t, h.ochunk_begin.data(), h.ochunk_begin.size(), &d.ochunk_begin), "ochunk");
+    NIMBLE_TRY(upload(t, h.ochunk_end.data(), h.ochunk_end.size(), &d.ochunk_end), "ochunk");
+    NIMBLE_TRY(upload(t, h.ochunk_slot.data(), h.ochunk_slot.size(), &d.ochunk_slot), "ochunk");
+    NIMBLE_TRY(upload(t, h.schunk_begin.data(), h.schunk_begin.size(), &d.schunk_begin), "schunk");
+    NIMBLE_TRY(upload(t, h.schunk_end.data(), h.schunk_end.size(), &d.schunk_end), "schunk");
+    NIMBLE_TRY(upload(t, h.schunk_slot.data(), h.schunk_slot.size(), &d.schunk_slot), "schunk");
+    NIMBLE_TRY(upload(t, h.link_slot_ptr.data(), h.link_slot_ptr.size(), &d.link_slot_ptr),
+               "link_slot_ptr");
+    NIMBLE_TRY(upload(t, h.sigma.data(), h.sigma.size(), &d.sigma), "sigma");
+    d.sigma_size = h.sigma_size;
+    NIMBLE_TRY(allocate(t, static_cast<size_t>(h.sigma_size), &d.choice2), "choice2");
+    NIMBLE_TRY(allocate(t, static_cast<size_t>(h.sigma_size), &d.demand2), "demand2");
+    NIMBLE_TRY(hipMemset(d.choice2, 0, static_cast<size_t>(h.sigma_size)), "choice2 clear");
+    NIMBLE_TRY(hipMemset(d.demand2, 0, sizeof(double) * static_cast<size_t>(h.sigma_size)),
+               "demand2 clear");
     NIMBLE_TRY(upload(t, h.invcap.data(), h.invcap.size(), &d.invcap), "invcap");
     NIMBLE_TRY(allocate(t, static_cast<size_t>(h.E), &d.len), "len");
     NIMBLE_TRY(allocate(t, static_cast<size_t>(h.E), &d.price), "price");
     NIMBLE_TRY(allocate(t, static_cast<size_t>(h.E), &d.S), "S");
     NIMBLE_TRY(allocate(t, static_cast<size_t>(h.K) + 1, &d.choice), "choice");
     NIMBLE_TRY(allocate(t, static_cast<size_t>(h.P), &d.count), "count");
-    NIMBLE_TRY(allocate(t, static_cast<size_t>(d.n_chunks), &d.partial), "partial");
+    NIMBLE_TRY(allocate(t, static_cast<size_t>(d.n_slots), &d.partial), "partial");
     NIMBLE_TRY(allocate(t, static_cast<size_t>(d.n_update_blocks) + 1, &d.scalars), "scalars");
     {
         unsigned char *sw = nullptr;
@@ -239,16 +257,22 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
         NIMBLE_TRY(hipDeviceGetAttribute(&t->n_cu, hipDeviceAttributeMultiprocessorCount,
                                          t->device),
                    "hipDeviceGetAttribute");
+        int per_cu = 6;
+        if (const char *env = std::getenv("NIMBLE_TUNE_REDUCE_BLOCKS_PER_CU"))
+            if (std::atoi(env) > 0) per_cu = std::atoi(env);
+        d.reduce_blocks = t->n_cu * per_cu;
     }
 #undef NIMBLE_TRY
 
     // stored bytes one iteration streams, phase by phase
     if (d.n_records > 0)
-        t->bytes_argmin = static_cast<int64_t>(nimble::kRecBytes) * d.n_records + 9LL * h.K;
+        t->bytes_argmin = static_cast<int64_t>(nimble::kRecBytes) * d.n_records + 10LL * h.K;
     else
-        t->bytes_argmin = 4LL * (h.K + 1) + 4LL * (h.P + 1) + 4LL * h.nnz + 9LL * h.K;
-    t->bytes_reduce = 8LL * d.rev_pairs + 8LL * d.n_chunks + 8LL * d.n_chunks;
-    t->bytes_update = 8LL * d.n_chunks + 4LL * (h.E + 1) + 56LL * h.E;
+        t->bytes_argmin = 4LL * (h.K + 1) + 4LL * (h.P + 1) + 4LL * h.nnz + 14LL * h.K;
+    t->bytes_reduce = 36LL * static_cast<int64_t>(h.oct_base.size()) +
+                      4LL * static_cast<int64_t>(h.single_pair.size()) +
+                      12LL * (d.n_ochunks + d.n_schunks) + 8LL * d.n_slots;
+    t->bytes_update = 8LL * d.n_slots + 4LL * (h.E + 1) + 56LL * h.E;
     t->bytes_per_iter = t->bytes_argmin + t->bytes_reduce + t->bytes_update;
     *out = t;
     return NIMBLE_OK;

@@ -1,5 +1,7 @@
 #include "host_topo.hpp"
 
+#include <algorithm>
+#include <climits>
 #include <cmath>
 #include <cstring>
 
@@ -75,8 +77,9 @@ nimble_status_t validate_csr(int32_t n_links, const double *cap, int32_t n_comm,
 void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                      const int32_t *comm_path_ptr, int32_t n_paths,
                      const int32_t *path_link_ptr, const int32_t *path_links,
-                     int32_t pairs_per_lane, HostTopo &t)
+                     int32_t octets_per_lane, HostTopo &t)
 {
+    t.octets_per_lane = octets_per_lane;
     t.E = n_links;
     t.K = n_comm;
     t.P = n_paths;
@@ -146,7 +149,7 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
         }
 
     // fixed-size chunks; a link with an empty row gets no chunk (its load is 0)
-    t.chunk_pairs = kRowLanesHost * pairs_per_lane;
+    t.chunk_pairs = kRowLanesHost * 8;
     t.link_chunk_ptr.assign(n_links + 1, 0);
     t.chunk_begin.clear();
     t.chunk_end.clear();
@@ -157,6 +160,155 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                                                                       : t.rev_ptr[e + 1]);
         }
         t.link_chunk_ptr[e + 1] = static_cast<int32_t>(t.chunk_begin.size());
+    }
+
+    // ---- streaming layout of the reverse rows: octets (two numberings) + single pairs -----
+    t.oct_base.clear();
+    t.oct_mask.clear();
+    t.single_pair.clear();
+    t.n_single_pairs = 0;
+    t.ochunk_begin.clear(); t.ochunk_end.clear(); t.ochunk_slot.clear();
+    t.schunk_begin.clear(); t.schunk_end.clear(); t.schunk_slot.clear();
+    t.link_slot_ptr.assign(n_links + 1, 0);
+    t.n_slots = 0;
+    t.sigma.assign(n_comm, -1);
+    const int32_t oct_chunk = kRowLanesHost * t.octets_per_lane;
+    const int32_t sgl_chunk = kRowLanesHost * kSinglesPerLane;
+    auto one_window = [&](int32_t kk) { return comm_path_ptr[kk + 1] - comm_path_ptr[kk] <= 32; };
+    struct Item { int32_t key; uint32_t a, b; };       // key: commodity id or sigma
+    // greedy octet packing of items sorted by key; appends octets, returns the left-overs
+    auto pack = [&](const std::vector<Item> &items, int32_t key_limit, std::vector<int32_t> &obase,
+                    std::vector<uint32_t> &omask, std::vector<Item> &left) {
+        size_t i = 0;
+        while (i < items.size()) {
+            const int32_t base = items[i].key & ~3;
+            size_t cnt = 0;
+            if (items[i].key >= 0)
+                while (i + cnt < items.size() && items[i + cnt].key >= 0 &&
+                       items[i + cnt].key < base + 8)
+                    ++cnt;
+            if (static_cast<int32_t>(cnt) >= kOctetMinFill && base + 8 <= key_limit) {
+                obase.push_back(base);
+                const size_t m0 = omask.size();
+                omask.resize(m0 + 8, 0u);
+                for (size_t q = 0; q < cnt; ++q) omask[m0 + (items[i + q].key - base)] = items[i + q].b;
+                i += cnt;
+            } else {
+                left.push_back(items[i]);
+                i += 1;
+            }
+        }
+    };
+    // pass 1: octets over commodity ids, row by row; left-overs kept per row
+    std::vector<std::vector<Item>> left1(n_links);
+    std::vector<std::vector<int32_t>> rowA_base(n_links);
+    std::vector<std::vector<uint32_t>> rowA_mask(n_links);
+    for (int32_t e = 0; e < n_links; ++e) {
+        std::vector<Item> items;
+        for (int32_t i = 0; i < t.rev_rowlen[e]; ++i) {
+            const uint32_t a = t.rev_pair[2 * static_cast<size_t>(t.rev_ptr[e] + i)];
+            const uint32_t b = t.rev_pair[2 * static_cast<size_t>(t.rev_ptr[e] + i) + 1];
+            const int32_t kk = static_cast<int32_t>(a & kCommMask);
+            items.push_back({one_window(kk) ? kk : -1, a, b});    // -1: never in an octet
+        }
+        pack(items, n_comm, rowA_base[e], rowA_mask[e], left1[e]);
+    }
+    // second numbering: left-over commodities in order of first appearance, every row's new
+    // run starting at a multiple of 8
+    int32_t next_sigma = 0;
+    for (int32_t e = 0; e < n_links; ++e) {
+        bool started = false;
+        for (const Item &it : left1[e]) {
+            if (it.key < 0) continue;
+            const int32_t kk = static_cast<int32_t>(it.a & kCommMask);
+            if (t.sigma[kk] < 0) {
+                if (!started) {
+                    next_sigma = (next_sigma + 7) & ~7;
+                    started = true;
+                }
+                t.sigma[kk] = next_sigma++;
+            }
+        }
+    }
+    t.sigma_size = ((next_sigma + 7) & ~7) + 8;
+    // pass 2: octets over sigma from the left-overs, then the final layout row by row
+    std::vector<int32_t> octB_base;
+    std::vector<uint32_t> octB_mask;
+    std::vector<std::vector<int32_t>> rowB_base(n_links);
+    std::vector<std::vector<uint32_t>> rowB_mask(n_links);
+    std::vector<std::vector<Item>> left2(n_links);
+    for (int32_t e = 0; e < n_links; ++e) {
+        std::vector<Item> items;
+        for (const Item &it : left1[e]) {
+            Item x = it;
+            x.key = it.key < 0 ? -1 : t.sigma[it.a & kCommMask];
+            items.push_back(x);
+        }
+        std::stable_sort(items.begin(), items.end(), [](const Item &x, const Item &y) {
+            return (x.key < 0 ? INT32_MAX : x.key) < (y.key < 0 ? INT32_MAX : y.key);
+        });
+        pack(items, t.sigma_size, rowB_base[e], rowB_mask[e], left2[e]);
+        // single pairs back in (commodity, window) order
+        std::stable_sort(left2[e].begin(), left2[e].end(), [](const Item &x, const Item &y) {
+            const uint32_t kx = x.a & kCommMask, ky = y.a & kCommMask;
+            return kx != ky ? kx < ky : ((x.a >> kWindowShift) & 3u) < ((y.a >> kWindowShift) & 3u);
+        });
+    }
+    // octets over ids of all rows first, then octets over sigma, so that a chunk is of one kind
+    std::vector<int32_t> rowA_first(n_links + 1, 0), rowB_first(n_links + 1, 0);
+    for (int32_t e = 0; e < n_links; ++e) {
+        rowA_first[e] = static_cast<int32_t>(t.oct_base.size());
+        t.oct_base.insert(t.oct_base.end(), rowA_base[e].begin(), rowA_base[e].end());
+        t.oct_mask.insert(t.oct_mask.end(), rowA_mask[e].begin(), rowA_mask[e].end());
+    }
+    rowA_first[n_links] = static_cast<int32_t>(t.oct_base.size());
+    t.n_octets_id = static_cast<int64_t>(t.oct_base.size());
+    for (int32_t e = 0; e < n_links; ++e) {
+        rowB_first[e] = static_cast<int32_t>(t.oct_base.size());
+        t.oct_base.insert(t.oct_base.end(), rowB_base[e].begin(), rowB_base[e].end());
+        t.oct_mask.insert(t.oct_mask.end(), rowB_mask[e].begin(), rowB_mask[e].end());
+    }
+    rowB_first[n_links] = static_cast<int32_t>(t.oct_base.size());
+    for (int32_t e = 0; e < n_links; ++e) {
+        for (int32_t b = rowA_first[e]; b < rowA_first[e + 1]; b += oct_chunk) {
+            t.ochunk_begin.push_back(b);
+            t.ochunk_end.push_back(b + oct_chunk < rowA_first[e + 1] ? b + oct_chunk
+                                                                    : rowA_first[e + 1]);
+            t.ochunk_slot.push_back(t.n_slots++);
+        }
+        for (int32_t b = rowB_first[e]; b < rowB_first[e + 1]; b += oct_chunk) {
+            t.ochunk_begin.push_back(b);
+            t.ochunk_end.push_back(b + oct_chunk < rowB_first[e + 1] ? b + oct_chunk
+                                                                    : rowB_first[e + 1]);
+            t.ochunk_slot.push_back(static_cast<int32_t>(0x80000000u | static_cast<uint32_t>(t.n_slots++)));
+        }
+        const int32_t s_first = static_cast<int32_t>(t.single_pair.size() / 2);
+        for (const Item &it : left2[e]) {
+            t.single_pair.push_back(it.a);
+            t.single_pair.push_back(it.b);
+            t.n_single_pairs += 1;
+        }
+        if ((t.single_pair.size() / 2) % kPairAlign) {       // pad the row to 16 bytes
+            t.single_pair.push_back(static_cast<uint32_t>(n_comm));
+            t.single_pair.push_back(0u);
+        }
+        const int32_t s_last = static_cast<int32_t>(t.single_pair.size() / 2);
+        for (int32_t b = s_first; b < s_last; b += sgl_chunk) {
+            t.schunk_begin.push_back(b);
+            t.schunk_end.push_back(b + sgl_chunk < s_last ? b + sgl_chunk : s_last);
+            t.schunk_slot.push_back(t.n_slots++);
+        }
+        t.link_slot_ptr[e + 1] = t.n_slots;
+    }
+    if (t.single_pair.empty()) {          // keep the array loadable
+        t.single_pair.push_back(static_cast<uint32_t>(n_comm));
+        t.single_pair.push_back(0u);
+        t.single_pair.push_back(static_cast<uint32_t>(n_comm));
+        t.single_pair.push_back(0u);
+    }
+    if (t.oct_base.empty()) {
+        t.oct_base.push_back(0);
+        t.oct_mask.resize(8, 0u);
     }
 
     // ---- forward records ------------------------------------------------------------------
@@ -172,7 +324,7 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
         std::vector<uint16_t> cp16, loc16;
         auto align4 = [](int32_t x) { return (x + 3) & ~3; };
         auto bytes_needed = [&](int32_t nl, int32_t nk, int32_t np) {
-            return kRecHeader + 4 * nl + align4(2 * (nk + 1)) + 2 * np * S;
+            return kRecHeader + 4 * nl + 4 * nk + align4(2 * (nk + 1)) + 2 * np * S;
         };
         bool ok = true;
         int32_t k = 0;
@@ -228,15 +380,18 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                 if (v == 0xFFFFu) v = static_cast<uint16_t>(nl);     // the +0.0 price slot
             t.records.resize(static_cast<size_t>(t.n_records + 1) * kRecBytes, 0);
             uint8_t *r = t.records.data() + static_cast<size_t>(t.n_records) * kRecBytes;
-            const int32_t off_cp = kRecHeader + 4 * nl;
+            const int32_t off_sig = kRecHeader + 4 * nl;
+            const int32_t off_cp = off_sig + 4 * nk;
             const int32_t off_loc = off_cp + align4(2 * (nk + 1));
             const uint16_t h16[8] = {static_cast<uint16_t>(nk), static_cast<uint16_t>(np),
                                      static_cast<uint16_t>(nl), static_cast<uint16_t>(off_cp),
-                                     static_cast<uint16_t>(off_loc), 0, 0, 0};
+                                     static_cast<uint16_t>(off_loc),
+                                     static_cast<uint16_t>(off_sig), 0, 0};
             std::memcpy(r + 0, &k0, 4);
             std::memcpy(r + 4, &p0, 4);
             std::memcpy(r + 8, h16, 16);
             std::memcpy(r + kRecHeader, links.data(), 4 * static_cast<size_t>(nl));
+            std::memcpy(r + off_sig, t.sigma.data() + k0, 4 * static_cast<size_t>(nk));
             std::memcpy(r + off_cp, cp16.data(), 2 * cp16.size());
             std::memcpy(r + off_loc, loc16.data(), 2 * loc16.size());
             t.n_records += 1;
@@ -266,7 +421,7 @@ extern "C" nimble_status_t nimble_host_build_reverse(int32_t n_links, int32_t n_
     std::vector<double> cap(n_links, 1.0);
     nimble::HostTopo t;
     nimble::build_host_topo(n_links, cap.data(), n_comm, comm_path_ptr, n_paths, path_link_ptr,
-                            path_links, 8, t);
+                            path_links, nimble::kOctetsPerLane, t);
     // expand the (commodity, window, mask) pairs back into one entry per incidence
     int32_t w = 0;
     for (int32_t e = 0; e < n_links; ++e) {
@@ -303,7 +458,7 @@ extern "C" nimble_status_t nimble_host_records_roundtrip(int32_t n_links, int32_
     std::vector<double> cap(n_links, 1.0);
     nimble::HostTopo t;
     nimble::build_host_topo(n_links, cap.data(), n_comm, comm_path_ptr, n_paths, path_link_ptr,
-                            path_links, 8, t);
+                            path_links, nimble::kOctetsPerLane, t);
     *n_records_out = t.n_records;
     if (t.n_records == 0) return NIMBLE_OK;
     // read every incidence back the way the kernel does: header -> first candidate of each
@@ -339,4 +494,30 @@ extern "C" nimble_status_t nimble_host_records_roundtrip(int32_t n_links, int32_
         }
     }
     return (w == t.nnz && next_comm == n_comm) ? NIMBLE_OK : NIMBLE_ERR_INVALID;
+}
+
+extern "C" nimble_status_t nimble_host_layout_stats(int32_t n_links, int32_t n_comm,
+                                                    const int32_t *comm_path_ptr,
+                                                    int32_t n_paths,
+                                                    const int32_t *path_link_ptr,
+                                                    const int32_t *path_links, int64_t *out)
+{
+    std::string why;
+    nimble_status_t st = nimble::validate_csr(n_links, nullptr, n_comm, comm_path_ptr, n_paths,
+                                              path_link_ptr, path_links, why);
+    if (st != NIMBLE_OK) return st;
+    if (!out) return NIMBLE_ERR_INVALID;
+    std::vector<double> cap(n_links, 1.0);
+    nimble::HostTopo t;
+    nimble::build_host_topo(n_links, cap.data(), n_comm, comm_path_ptr, n_paths, path_link_ptr,
+                            path_links, nimble::kOctetsPerLane, t);
+    out[0] = t.n_pairs;
+    out[1] = static_cast<int64_t>(t.oct_base.size());
+    out[2] = t.n_single_pairs;
+    out[3] = static_cast<int64_t>(t.ochunk_begin.size());
+    out[4] = static_cast<int64_t>(t.schunk_begin.size());
+    out[5] = t.n_slots;
+    out[6] = t.n_records;
+    out[7] = t.rec_stride;
+    return NIMBLE_OK;
 }

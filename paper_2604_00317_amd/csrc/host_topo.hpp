@@ -27,6 +27,21 @@ constexpr int32_t kMaxPathsPerComm = 127;     // four windows of 32, index 255 n
 constexpr int32_t kRowLanesHost = 16;         // lanes of one DPP row reduce one chunk
 constexpr int32_t kPairAlign = 2;             // rows are padded to 16 bytes (2 pairs)
 
+// Streaming layout of the same rows.  Commodity ids that fall into one aligned-by-4 window of 8
+// consecutive ids are packed into an OCTET: one base id and eight masks (0 for commodities
+// that do not use the link), so that one 8-byte load fetches all eight choices; an octet is
+// emitted when it holds at least kOctetMinFill pairs.  Pairs left over (rows whose commodities
+// are far apart in id order, e.g. "all sources towards one destination") get a second chance
+// under a second numbering sigma of the commodities: walking the rows in order, every
+// left-over commodity that has no sigma yet receives the next one, so the left-overs of the
+// first row that lists them become consecutive, and rows with the same left-overs are dense
+// under sigma.  Octets over sigma read a second copy of the choices (and demands) stored in
+// sigma order.  What is still left stays SINGLE pairs as above.  A link's load is the sum over
+// its chunks of all three kinds.
+constexpr int32_t kOctetMinFill = 3;
+constexpr int32_t kOctetsPerLane = 1;         // default: an octet chunk holds 16 * 1 octets
+constexpr int32_t kSinglesPerLane = 8;        // a single chunk holds 16 * 8 pairs
+
 // ---- forward CSR records ------------------------------------------------------------------
 // The forward CSR is repacked into self-contained records of kRecBytes bytes, each holding a
 // run of consecutive commodities: a wave fetches one record with four 16-byte loads per lane
@@ -37,8 +52,9 @@ constexpr int32_t kPairAlign = 2;             // rows are padded to 16 bytes (2 
 // of positive prices).  Layout, offsets in bytes from the start of the record:
 //   0   int32 k0        first commodity
 //   4   int32 p0        first candidate path (global id)
-//   8   uint16 nk, np, n_links, off_cp, off_loc, reserved[3]
+//   8   uint16 nk, np, n_links, off_cp, off_loc, off_sig, reserved[2]
 //   24  int32 links[n_links]
+//   off_sig  int32 sigma[nk]      second numbering of the commodity (-1: none)
 //   off_cp   uint16 cp16[nk+1]    first candidate of commodity i, relative to p0
 //   off_loc  uint16 loc16[np*stride]
 constexpr int32_t kRecBytes = 4096;
@@ -62,6 +78,21 @@ struct HostTopo {
     std::vector<int32_t> chunk_begin;    // [n_chunks], pair offsets
     std::vector<int32_t> chunk_end;      // [n_chunks]
     std::vector<int32_t> link_chunk_ptr; // [E+1]
+    // streaming layout: octets and single pairs, each cut into chunks that write one partial
+    // sum into `slot`; the slots of a link are contiguous: link_slot_ptr[e] .. link_slot_ptr[e+1]
+    std::vector<int32_t> oct_base;       // [n_octets]: octets over ids first, then over sigma
+    std::vector<uint32_t> oct_mask;      // [8 * n_octets]
+    int64_t n_octets_id = 0;             // octets over commodity ids
+    std::vector<int32_t> sigma;          // [K] second numbering, -1 = none
+    int32_t sigma_size = 0;              // length of the sigma-ordered copies (multiple of 8)
+    std::vector<uint32_t> single_pair;   // [2 * n_singles_padded], rows padded to 2 pairs
+    int64_t n_single_pairs = 0;          // unpadded
+    // octet units; bit 31 of the slot word marks a chunk of sigma octets
+    std::vector<int32_t> ochunk_begin, ochunk_end, ochunk_slot;
+    std::vector<int32_t> schunk_begin, schunk_end, schunk_slot;   // pair units
+    std::vector<int32_t> link_slot_ptr;  // [E+1]
+    int32_t n_slots = 0;
+    int32_t octets_per_lane = kOctetsPerLane;
     // forward records (n_records = 0 when the topology does not fit them: a path longer than
     // kRecMaxStride links, padding above 1.5x, or a commodity that alone overflows a record)
     int32_t rec_stride = 0;              // indices per candidate = lmax
@@ -75,10 +106,10 @@ nimble_status_t validate_csr(int32_t n_links, const double *cap, int32_t n_comm,
                              const int32_t *path_link_ptr, const int32_t *path_links,
                              std::string &why);
 
-// Builds everything in HostTopo from validated input.  pairs_per_lane is 8 or 16.
+// Builds everything in HostTopo from validated input.  octets_per_lane is 1, 2 or 4.
 void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                      const int32_t *comm_path_ptr, int32_t n_paths,
                      const int32_t *path_link_ptr, const int32_t *path_links,
-                     int32_t pairs_per_lane, HostTopo &out);
+                     int32_t octets_per_lane, HostTopo &out);
 
 }  // namespace nimble

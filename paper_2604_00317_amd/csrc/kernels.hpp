@@ -24,24 +24,37 @@ struct DeviceTopo {
     int64_t rev_pairs;         // padded number of pairs
     const int32_t *rev_ptr;    // [E+1], in pairs
     const uint32_t *rev_pair;  // [2 * rev_pairs]
-    int32_t pairs_per_lane;    // 8 or 16: a chunk holds 16 * pairs_per_lane pairs
-    int32_t n_chunks;
-    const int32_t *chunk_begin, *chunk_end; // [n_chunks], in pairs
-    const int32_t *link_chunk_ptr;          // [E+1]
+    // streaming layout of the reverse rows: octets (base id + 8 masks) and single pairs, cut
+    // into chunks that each write one partial sum into partial[slot]
+    int32_t n_ochunks, n_schunks, n_slots;
+    int32_t octets_per_lane;    // 1, 2 or 4: an octet chunk holds 16 * octets_per_lane octets
+    const int32_t *oct_base;    // [n_octets]
+    const uint32_t *oct_mask;   // [8 * n_octets]
+    const uint32_t *single_pair; // [2 * padded singles]
+    const int32_t *ochunk_begin, *ochunk_end, *ochunk_slot;   // [n_ochunks], octet units
+    const int32_t *schunk_begin, *schunk_end, *schunk_slot;   // [n_schunks], pair units
+    const int32_t *link_slot_ptr;                             // [E+1]
+    // second numbering of the commodities for the sigma octets, with sigma-ordered copies of
+    // the choices and the demands
+    int32_t sigma_size;
+    const int32_t *sigma;      // [K], -1 = none
+    uint8_t *choice2;          // [sigma_size]
+    double *demand2;           // [sigma_size]
     const double *invcap;      // [E]
     // state of the plan in flight
     double *len, *price, *S;   // [E]
     uint8_t *choice;           // [K+1] (slot K is only ever read by padding pairs)
     uint32_t *count;           // [P]
-    double *partial;           // [n_chunks]
+    double *partial;           // [n_slots]
     double *scalars;           // [0] = 1/rho, [1..] = per-block maxima of S
     int32_t n_update_blocks;
+    int32_t reduce_blocks;     // 256-thread blocks of the link-load reduce (fills the chip once)
 };
 
 int lanes_per_commodity(int pmax);   // power of two >= pmax, at most 64
 
 // ---- streaming regime: one launch per phase ------------------------------------------------
-void launch_init(const DeviceTopo &t, hipStream_t s);
+void launch_init(const DeviceTopo &t, const double *demand, hipStream_t s);
 void launch_width(const DeviceTopo &t, const double *demand, hipStream_t s);
 void launch_argmin(const DeviceTopo &t, hipStream_t s);
 void launch_load_reduce(const DeviceTopo &t, const double *demand, hipStream_t s);

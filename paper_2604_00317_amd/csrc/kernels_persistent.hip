@@ -18,7 +18,6 @@ namespace nimble {
 namespace {
 
 constexpr int kPBlock = 1024;
-constexpr int kPersistentPPL = 8;   // the reverse chunks must have been built for this
 
 struct SyncWords {
     unsigned int arrivals;   // barrier counter
@@ -70,11 +69,17 @@ __device__ __forceinline__ bool grid_barrier(SyncWords *w, unsigned int n_blocks
 }
 
 struct PersistentArgs {
-    int E, K, P, n_chunks;
+    int E, K, P, n_ochunks, n_schunks;
     uint32_t pad_comm;
     const int32_t *cp, *lp, *pl;
-    const uint32_t *rev;
-    const int32_t *chunk_begin, *chunk_end, *link_chunk_ptr;
+    const int32_t *ochunk_begin, *ochunk_end, *ochunk_slot, *oct_base;
+    const uint32_t *oct_mask;
+    const int32_t *schunk_begin, *schunk_end, *schunk_slot;
+    const uint32_t *single_pair;
+    const int32_t *link_slot_ptr;
+    const int32_t *sigma;
+    uint8_t *choice2;
+    double *demand2;
     const double *invcap;
     double *len, *price, *S;
     uint8_t *choice;
@@ -87,6 +92,19 @@ struct PersistentArgs {
     double *splits, *lambda;
     unsigned int spin_limit;
 };
+
+template <int MODE>
+__device__ __forceinline__ void reduce_both(const PersistentArgs &a, int wave, int n_waves,
+                                            int lane)
+{
+    reduce_oct_phase<MODE, kOctetsPerLane>(a.n_ochunks, a.ochunk_begin, a.ochunk_end,
+                                           a.ochunk_slot, a.oct_base, a.oct_mask, a.choice,
+                                           a.demand, a.choice2, a.demand2, a.partial, wave,
+                                           n_waves, lane);
+    reduce_phase<MODE, kSinglesPerLane>(a.n_schunks, a.schunk_begin, a.schunk_end, a.schunk_slot,
+                                        a.single_pair, a.pad_comm, a.choice, a.demand, a.partial,
+                                        n_waves - 1 - wave, n_waves, lane);
+}
 
 __device__ __forceinline__ void atomic_max_bits(unsigned long long *addr, double v)
 {
@@ -114,11 +132,15 @@ __global__ __launch_bounds__(kPBlock) void k_persistent(PersistentArgs a)
         a.S[e] = 0.0;
     }
     for (int p = tid; p < a.P; p += n_threads) a.count[p] = 0u;
-    reduce_phase<1, kPersistentPPL>(a.n_chunks, a.chunk_begin, a.chunk_end, a.rev, a.pad_comm, a.choice,
-                    a.demand, a.partial, wave, n_waves, lane);
+    for (int k = tid; k < a.K; k += n_threads) {
+        const int sg = a.sigma[k];
+        if (sg >= 0) a.demand2[sg] = a.demand[k];
+    }
+    if (!grid_barrier(a.sync, nb, a.spin_limit, &s_flag)) goto abandoned;
+    reduce_both<1>(a, wave, n_waves, lane);
     if (!grid_barrier(a.sync, nb, a.spin_limit, &s_flag)) goto abandoned;
     {
-        double m = width_phase(a.E, a.link_chunk_ptr, a.partial, a.invcap, wave, n_waves, lane);
+        double m = width_phase(a.E, a.link_slot_ptr, a.partial, a.invcap, wave, n_waves, lane);
         m = block_max(m, red);
         if (threadIdx.x == 0) atomic_max_bits(&a.sync->rho_bits, m);
     }
@@ -129,14 +151,12 @@ __global__ __launch_bounds__(kPBlock) void k_persistent(PersistentArgs a)
         const double invrho = (rho > 0.0) ? 1.0 / rho : 0.0;
 
         for (int it = 0; it < a.iters; ++it) {
-            argmin_phase<L, LMAX, MAXC>(a.K, a.cp, a.lp, a.pl, a.price, a.choice, a.count, wave,
-                                        n_waves, lane);
+            argmin_phase<L, LMAX, MAXC>(a.K, a.cp, a.lp, a.pl, a.price, a.choice, a.count, a.sigma,
+                                        a.choice2, wave, n_waves, lane);
             if (!grid_barrier(a.sync, nb, a.spin_limit, &s_flag)) goto abandoned;
-            reduce_phase<0, kPersistentPPL>(a.n_chunks, a.chunk_begin, a.chunk_end, a.rev, a.pad_comm,
-                            a.choice,
-                            a.demand, a.partial, wave, n_waves, lane);
+            reduce_both<0>(a, wave, n_waves, lane);
             if (!grid_barrier(a.sync, nb, a.spin_limit, &s_flag)) goto abandoned;
-            update_phase<MAXC>(a.E, a.eps, invrho, a.link_chunk_ptr, a.partial, a.invcap, a.len,
+            update_phase<MAXC>(a.E, a.eps, invrho, a.link_slot_ptr, a.partial, a.invcap, a.len,
                                a.price, a.S, wave, n_waves, lane);
             if (!grid_barrier(a.sync, nb, a.spin_limit, &s_flag)) goto abandoned;
         }
@@ -209,20 +229,30 @@ hipError_t launch_persistent(const DeviceTopo &t, void *sync_words, int n_cu,
                              unsigned int spin_limit, const double *demand, double eps,
                              int32_t iters, double *splits, double *lambda, hipStream_t s)
 {
-    if (t.pairs_per_lane != kPersistentPPL) return hipErrorInvalidValue;
+    if (t.octets_per_lane != kOctetsPerLane) return hipErrorInvalidValue;
     PersistentArgs a;
     a.E = t.E;
     a.K = t.K;
     a.P = t.P;
-    a.n_chunks = t.n_chunks;
+    a.n_ochunks = t.n_ochunks;
+    a.n_schunks = t.n_schunks;
     a.pad_comm = static_cast<uint32_t>(t.K);
     a.cp = t.comm_ptr;
     a.lp = t.path_ptr;
     a.pl = t.path_links;
-    a.rev = t.rev_pair;
-    a.chunk_begin = t.chunk_begin;
-    a.chunk_end = t.chunk_end;
-    a.link_chunk_ptr = t.link_chunk_ptr;
+    a.ochunk_begin = t.ochunk_begin;
+    a.ochunk_end = t.ochunk_end;
+    a.ochunk_slot = t.ochunk_slot;
+    a.oct_base = t.oct_base;
+    a.oct_mask = t.oct_mask;
+    a.schunk_begin = t.schunk_begin;
+    a.schunk_end = t.schunk_end;
+    a.schunk_slot = t.schunk_slot;
+    a.single_pair = t.single_pair;
+    a.link_slot_ptr = t.link_slot_ptr;
+    a.sigma = t.sigma;
+    a.choice2 = t.choice2;
+    a.demand2 = t.demand2;
     a.invcap = t.invcap;
     a.len = t.len;
     a.price = t.price;

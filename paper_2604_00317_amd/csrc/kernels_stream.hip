@@ -17,10 +17,17 @@ __global__ __launch_bounds__(kBlock) void k_init(int E, int K, int P, bool cost_
                                                  double *__restrict__ price,
                                                  double *__restrict__ S,
                                                  uint8_t *__restrict__ choice,
-                                                 uint32_t *__restrict__ count)
+                                                 uint32_t *__restrict__ count,
+                                                 const int32_t *__restrict__ sigma,
+                                                 const double *__restrict__ demand,
+                                                 double *__restrict__ demand2)
 {
     const int stride = gridDim.x * blockDim.x;
     const int tid = blockIdx.x * blockDim.x + threadIdx.x;
+    for (int k = tid; k < K; k += stride) {      // demands in sigma order for the sigma octets
+        const int sg = sigma[k];
+        if (sg >= 0) demand2[sg] = demand[k];
+    }
     for (int e = tid; e < E; e += stride) {
         len[e] = 1.0;
         price[e] = cost_max ? 1.0 : invcap[e];
@@ -36,12 +43,15 @@ __global__ __launch_bounds__(kBlock) void k_argmin(int K, const int32_t *__restr
                                                    const int32_t *__restrict__ pl,
                                                    const double *__restrict__ price,
                                                    uint8_t *__restrict__ choice,
-                                                   uint32_t *__restrict__ count)
+                                                   uint32_t *__restrict__ count,
+                                                   const int32_t *__restrict__ sigma,
+                                                   uint8_t *__restrict__ choice2)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
-    argmin_phase<L, LMAX, MAXC>(K, cp, lp, pl, price, choice, count, wave, n_waves, lane);
+    argmin_phase<L, LMAX, MAXC>(K, cp, lp, pl, price, choice, count, sigma, choice2, wave,
+                                n_waves, lane);
 }
 
 // Record path-cost gather + argmin: one wave (a 64-thread workgroup) per 4 KiB record of the
@@ -55,7 +65,8 @@ __global__ __launch_bounds__(kWave) void k_argmin_rec(int n_records,
                                                       const uint8_t *__restrict__ records,
                                                       const double *__restrict__ price,
                                                       uint8_t *__restrict__ choice,
-                                                      uint32_t *__restrict__ count)
+                                                      uint32_t *__restrict__ count,
+                                                      uint8_t *__restrict__ choice2)
 {
     __shared__ __align__(16) uint8_t s_rec[kRecBytes];
     __shared__ double s_price[kRecMaxLinks + 1];
@@ -82,6 +93,7 @@ __global__ __launch_bounds__(kWave) void k_argmin_rec(int n_records,
     const int32_t *links = reinterpret_cast<const int32_t *>(s_rec + kRecHeader);
     const uint16_t *cp16 = reinterpret_cast<const uint16_t *>(s_rec + h16[3]);
     const uint16_t *loc16 = reinterpret_cast<const uint16_t *>(s_rec + h16[4]);
+    const int32_t *sig = reinterpret_cast<const int32_t *>(s_rec + h16[5]);
     for (int i = lane; i < nl; i += kWave) s_price[i] = price[links[i]];
     if (lane == 0) s_price[nl] = 0.0;
     __syncthreads();
@@ -122,26 +134,40 @@ __global__ __launch_bounds__(kWave) void k_argmin_rec(int n_records,
         }
         if (c < nk && j == 0) {
             choice[k0 + c] = static_cast<uint8_t>(bj);
+            const int sg = sig[c];
+            if (sg >= 0) choice2[sg] = static_cast<uint8_t>(bj);   // copy in sigma order
             count[p0 + p_lo + bj] += 1u;
         }
     }
 }
 
-template <int MODE, int PPL>
-__global__ __launch_bounds__(kBlock) void k_load_reduce(int n_chunks,
-                                                        const int32_t *__restrict__ chunk_begin,
-                                                        const int32_t *__restrict__ chunk_end,
-                                                        const uint32_t *__restrict__ rev,
-                                                        uint32_t pad_comm,
-                                                        const uint8_t *__restrict__ choice,
-                                                        const double *__restrict__ demand,
-                                                        double *__restrict__ partial)
+struct ReduceArgs {
+    int n_ochunks, n_schunks;
+    const int32_t *ochunk_begin, *ochunk_end, *ochunk_slot, *oct_base;
+    const uint32_t *oct_mask;
+    const int32_t *schunk_begin, *schunk_end, *schunk_slot;
+    const uint32_t *single_pair;
+    uint32_t pad_comm;
+    const uint8_t *choice, *choice2;
+    const double *demand, *demand2;
+    double *partial;
+};
+
+template <int MODE, int OPL>
+__global__ __launch_bounds__(kBlock) void k_load_reduce(ReduceArgs a)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
-    reduce_phase<MODE, PPL>(n_chunks, chunk_begin, chunk_end, rev, pad_comm, choice, demand,
-                            partial, wave, n_waves, lane);
+    reduce_oct_phase<MODE, OPL>(a.n_ochunks, a.ochunk_begin, a.ochunk_end,
+                                           a.ochunk_slot, a.oct_base, a.oct_mask, a.choice,
+                                           a.demand, a.choice2, a.demand2, a.partial, wave,
+                                           n_waves, lane);
+    // the single pairs are walked from the other end of the wave pool, so that the waves that
+    // got no octet chunk start on them at once
+    reduce_phase<MODE, kSinglesPerLane>(a.n_schunks, a.schunk_begin, a.schunk_end, a.schunk_slot,
+                                        a.single_pair, a.pad_comm, a.choice, a.demand, a.partial,
+                                        n_waves - 1 - wave, n_waves, lane);
 }
 
 // rho = max_e (demand that can reach e) / cap_e; scalars[0] = 1/rho (0 when rho = 0)
@@ -213,7 +239,7 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, hipStream_t s)
 #define NIMBLE_REC_LAUNCH(SS)                                                                  \
     case SS:                                                                                   \
         hipLaunchKernelGGL((k_argmin_rec<L, SS, MAXC>), dim3(t.n_records), dim3(kWave), 0, s,  \
-                           t.n_records, t.records, t.price, t.choice, t.count);                \
+                           t.n_records, t.records, t.price, t.choice, t.count, t.choice2);     \
         return;
         switch (t.rec_stride) {
             NIMBLE_REC_LAUNCH(1)
@@ -229,7 +255,8 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, hipStream_t s)
     }
 #define NIMBLE_ARGMIN_LAUNCH(LM)                                                              \
     hipLaunchKernelGGL((k_argmin<L, LM, MAXC>), dim3(grid), dim3(kBlock), 0, s, t.K,          \
-                       t.comm_ptr, t.path_ptr, t.path_links, t.price, t.choice, t.count)
+                       t.comm_ptr, t.path_ptr, t.path_links, t.price, t.choice, t.count,      \
+                       t.sigma, t.choice2)
     if (t.lmax <= 2) NIMBLE_ARGMIN_LAUNCH(2);
     else if (t.lmax <= 4) NIMBLE_ARGMIN_LAUNCH(4);
     else NIMBLE_ARGMIN_LAUNCH(8);
@@ -255,17 +282,34 @@ void launch_argmin_l(const DeviceTopo &t, hipStream_t s)
 template <int MODE>
 void launch_reduce_mode(const DeviceTopo &t, const double *demand, hipStream_t s)
 {
-    const int64_t waves = (static_cast<int64_t>(t.n_chunks) + kRowsPerWave - 1) / kRowsPerWave;
-    const int grid = blocks_for(waves * kWave, kBlock, 1 << 20);
-    const uint32_t pad_comm = static_cast<uint32_t>(t.K);
-    if (t.pairs_per_lane == 16)
-        hipLaunchKernelGGL((k_load_reduce<MODE, 16>), dim3(grid), dim3(kBlock), 0, s, t.n_chunks,
-                           t.chunk_begin, t.chunk_end, t.rev_pair, pad_comm, t.choice, demand,
-                           t.partial);
+    // a fixed pool of waves, each walking its chunks with the loads pipelined
+    const int64_t rows = static_cast<int64_t>(t.n_ochunks) + t.n_schunks;
+    const int64_t waves = (rows + kRowsPerWave - 1) / kRowsPerWave;
+    const int grid = blocks_for(waves * kWave, kBlock, t.reduce_blocks);
+    ReduceArgs a;
+    a.n_ochunks = t.n_ochunks;
+    a.n_schunks = t.n_schunks;
+    a.ochunk_begin = t.ochunk_begin;
+    a.ochunk_end = t.ochunk_end;
+    a.ochunk_slot = t.ochunk_slot;
+    a.oct_base = t.oct_base;
+    a.oct_mask = t.oct_mask;
+    a.schunk_begin = t.schunk_begin;
+    a.schunk_end = t.schunk_end;
+    a.schunk_slot = t.schunk_slot;
+    a.single_pair = t.single_pair;
+    a.pad_comm = static_cast<uint32_t>(t.K);
+    a.choice = t.choice;
+    a.choice2 = t.choice2;
+    a.demand = demand;
+    a.demand2 = t.demand2;
+    a.partial = t.partial;
+    if (t.octets_per_lane == 1)
+        hipLaunchKernelGGL((k_load_reduce<MODE, 1>), dim3(grid), dim3(kBlock), 0, s, a);
+    else if (t.octets_per_lane == 2)
+        hipLaunchKernelGGL((k_load_reduce<MODE, 2>), dim3(grid), dim3(kBlock), 0, s, a);
     else
-        hipLaunchKernelGGL((k_load_reduce<MODE, 8>), dim3(grid), dim3(kBlock), 0, s, t.n_chunks,
-                           t.chunk_begin, t.chunk_end, t.rev_pair, pad_comm, t.choice, demand,
-                           t.partial);
+        hipLaunchKernelGGL((k_load_reduce<MODE, 4>), dim3(grid), dim3(kBlock), 0, s, a);
 }
 
 }  // namespace
@@ -277,17 +321,18 @@ int lanes_per_commodity(int pmax)
     return L;
 }
 
-void launch_init(const DeviceTopo &t, hipStream_t s)
+void launch_init(const DeviceTopo &t, const double *demand, hipStream_t s)
 {
     const int n = t.E > t.P ? t.E : t.P;
     hipLaunchKernelGGL(k_init, dim3(blocks_for(n, kBlock, 4096)), dim3(kBlock), 0, s, t.E, t.K,
-                       t.P, t.cost_max, t.invcap, t.len, t.price, t.S, t.choice, t.count);
+                       t.P, t.cost_max, t.invcap, t.len, t.price, t.S, t.choice, t.count, t.sigma,
+                       demand, t.demand2);
 }
 
 void launch_width(const DeviceTopo &t, const double *demand, hipStream_t s)
 {
     launch_reduce_mode<1>(t, demand, s);
-    hipLaunchKernelGGL(k_width, dim3(1), dim3(1024), 0, s, t.E, t.link_chunk_ptr, t.partial,
+    hipLaunchKernelGGL(k_width, dim3(1), dim3(1024), 0, s, t.E, t.link_slot_ptr, t.partial,
                        t.invcap, t.scalars);
 }
 
@@ -306,10 +351,10 @@ void launch_update(const DeviceTopo &t, double eps, hipStream_t s)
 {
     if (t.cost_max)
         hipLaunchKernelGGL(k_update<true>, dim3(t.n_update_blocks), dim3(kBlock), 0, s, t.E, eps,
-                           t.link_chunk_ptr, t.partial, t.invcap, t.len, t.price, t.S, t.scalars);
+                           t.link_slot_ptr, t.partial, t.invcap, t.len, t.price, t.S, t.scalars);
     else
         hipLaunchKernelGGL(k_update<false>, dim3(t.n_update_blocks), dim3(kBlock), 0, s, t.E, eps,
-                           t.link_chunk_ptr, t.partial, t.invcap, t.len, t.price, t.S, t.scalars);
+                           t.link_slot_ptr, t.partial, t.invcap, t.len, t.price, t.S, t.scalars);
 }
 
 void launch_epilogue(const DeviceTopo &t, int32_t iters, double *splits, double *lambda,

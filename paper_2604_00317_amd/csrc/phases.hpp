@@ -43,7 +43,9 @@ __device__ __forceinline__ void argmin_phase(int K, const int32_t *__restrict__ 
                                              const int32_t *__restrict__ pl,
                                              const double *__restrict__ price,
                                              uint8_t *__restrict__ choice,
-                                             uint32_t *__restrict__ count, int wave,
+                                             uint32_t *__restrict__ count,
+                                             const int32_t *__restrict__ sigma,
+                                             uint8_t *__restrict__ choice2, int wave,
                                              int n_waves, int lane)
 {
     constexpr int kPerWave = kWave / L;
@@ -88,6 +90,8 @@ __device__ __forceinline__ void argmin_phase(int K, const int32_t *__restrict__ 
         group_argmin<L>(best, bj);
         if (k < K && j0 == 0) {
             choice[k] = static_cast<uint8_t>(bj);
+            const int sg = sigma[k];
+            if (sg >= 0) choice2[sg] = static_cast<uint8_t>(bj);   // copy in sigma order
             count[p0 + bj] += 1u;
         }
     }
@@ -105,42 +109,76 @@ __device__ __forceinline__ void argmin_phase(int K, const int32_t *__restrict__ 
 constexpr int kRowLanes = 16;
 constexpr int kRowsPerWave = kWave / kRowLanes;
 
+template <int PPL>
+__device__ __forceinline__ void load_pairs(u32x4 (&v)[PPL / 2], const uint32_t *__restrict__ rev,
+                                           int b, int e, int l, uint32_t pad_comm)
+{
+#pragma unroll
+    for (int it = 0; it < PPL / 2; ++it) {
+        // every lane always loads (lanes past the end re-read the chunk's first group and
+        // discard it): an unconditional load keeps the number of outstanding requests known to
+        // the compiler, which is what lets it wait for the older gathers only
+        const int i = b + it * (kRowLanes * 2) + l * 2;      // pair index
+        const u32x4 pad = {pad_comm, 0u, pad_comm, 0u};
+        const u32x4 x = stream_load(reinterpret_cast<const u32x4 *>(rev + 2 * size_t(i < e ? i : b)));
+        v[it] = (i < e) ? x : pad;
+    }
+}
+
+// Software-pipelined over the chunks a DPP row visits: while the choices of the current chunk
+// are being gathered, the pairs of the next chunk and the bounds of the one after are already
+// requested, and because they are requested AFTER the gathers the in-order return of vector
+// loads lets the gathers be consumed while the stream loads are in flight.  The demands of the
+// few hits are fetched last, one per loop turn, in pair order.
 template <int MODE, int PPL>
 __device__ __forceinline__ void reduce_phase(int n_chunks, const int32_t *__restrict__ chunk_begin,
                                              const int32_t *__restrict__ chunk_end,
+                                             const int32_t *__restrict__ chunk_slot,
                                              const uint32_t *__restrict__ rev, uint32_t pad_comm,
                                              const uint8_t *__restrict__ choice,
                                              const double *__restrict__ demand,
                                              double *__restrict__ partial, int wave, int n_waves,
                                              int lane)
 {
+    if (n_chunks <= 0) return;
     const int row = lane / kRowLanes;
     const int l = lane % kRowLanes;
-    for (int cbase = wave * kRowsPerWave; cbase < n_chunks; cbase += n_waves * kRowsPerWave) {
-        const int c = cbase + row;
-        int b = 0, e = 0;
-        if (c < n_chunks) {
-            b = stream_load(chunk_begin + c);
-            e = stream_load(chunk_end + c);
-        }
+    const int stride = n_waves * kRowsPerWave;
+    const int last = n_chunks - 1;
+    int c = wave * kRowsPerWave + row;
+    int b1, e1;
+    u32x4 cur[PPL / 2];
+    {
+        // bounds of chunks past the end are read from the last chunk and replaced by an empty
+        // range, again so that every load is unconditional
+        int b0 = chunk_begin[c < last ? c : last], e0 = chunk_end[c < last ? c : last];
+        if (c > last) b0 = e0 = 0;
+        const int cn = c + stride;
+        b1 = chunk_begin[cn < last ? cn : last];
+        e1 = chunk_end[cn < last ? cn : last];
+        if (cn > last) b1 = e1 = 0;
+        load_pairs<PPL>(cur, rev, b0, e0, l, pad_comm);
+    }
+    for (; c - row < n_chunks; c += stride) {          // wave-uniform bound
         uint32_t wa[PPL], wb[PPL];
 #pragma unroll
         for (int it = 0; it < PPL / 2; ++it) {
-            const int i = b + it * (kRowLanes * 2) + l * 2;      // pair index
-            u32x4 v = {pad_comm, 0u, pad_comm, 0u};
-            if (i < e) v = stream_load(reinterpret_cast<const u32x4 *>(rev + 2 * size_t(i)));
-            wa[it * 2 + 0] = v.x;
-            wb[it * 2 + 0] = v.y;
-            wa[it * 2 + 1] = v.z;
-            wb[it * 2 + 1] = v.w;
+            wa[it * 2 + 0] = cur[it].x;
+            wb[it * 2 + 0] = cur[it].y;
+            wa[it * 2 + 1] = cur[it].z;
+            wb[it * 2 + 1] = cur[it].w;
         }
-        // gathers are issued in batches before anything waits on them: PPL choice bytes, then
-        // the demands of the hits; absent demands are +0.0, which adds exactly
         uint32_t ch[PPL];
 #pragma unroll
         for (int q = 0; q < PPL; ++q)
             if constexpr (MODE == 0) ch[q] = choice[wa[q] & kCommMask];
-        double dq[PPL];
+        // requests for later chunks, issued after the gathers
+        const int c2 = c + 2 * stride;
+        const int b2 = chunk_begin[c2 < last ? c2 : last], e2 = chunk_end[c2 < last ? c2 : last];
+        const int slot = chunk_slot[c < last ? c : last];
+        u32x4 nxt[PPL / 2];
+        load_pairs<PPL>(nxt, rev, b1, e1, l, pad_comm);
+        uint32_t hits = 0u;
 #pragma unroll
         for (int q = 0; q < PPL; ++q) {
             bool hit;
@@ -149,17 +187,170 @@ __device__ __forceinline__ void reduce_phase(int n_chunks, const int32_t *__rest
                       (((wb[q] >> (ch[q] & 31u)) & 1u) != 0u);
             else
                 hit = (wa[q] & kFirstFlag) != 0u;
-            dq[q] = 0.0;
-            if (hit) dq[q] = demand[wa[q] & kCommMask];
+            hits |= static_cast<uint32_t>(hit) << q;
         }
+        // demands of the hits in pair order
         double acc = 0.0;
+        while (hits != 0u) {                 // four hits per turn, their loads side by side
+            uint32_t idx[4];
+            bool ok[4];
 #pragma unroll
-        for (int q = 0; q < PPL; ++q) acc = acc + dq[q];
+            for (int u = 0; u < 4; ++u) {
+                ok[u] = hits != 0u;
+                const int t = ok[u] ? __ffs(hits) - 1 : 0;
+                hits &= hits - 1u;           // 0 stays 0
+                uint32_t ksel = wa[0];
+#pragma unroll
+                for (int q = 1; q < PPL; ++q) ksel = (t == q) ? wa[q] : ksel;
+                idx[u] = ok[u] ? (ksel & kCommMask) : idx[0];
+            }
+            double d[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) d[u] = demand[idx[u]];
+            // an absent hit re-reads the first one and is masked to +0.0 (masked, not selected:
+            // a select would let the compiler move the load under the condition)
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int mk = -static_cast<int>(ok[u]);
+                acc = acc + __hiloint2double(__double2hiint(d[u]) & mk, __double2loint(d[u]) & mk);
+            }
+        }
         acc = acc + partner_f64<1>(acc);
         acc = acc + partner_f64<2>(acc);
         acc = acc + partner_f64<4>(acc);
         acc = acc + partner_f64<8>(acc);
-        if (c < n_chunks && l == 0) partial[c] = acc;
+        if (c < n_chunks && l == 0) partial[slot] = acc;
+#pragma unroll
+        for (int it = 0; it < PPL / 2; ++it) cur[it] = nxt[it];
+        b1 = (c2 > last) ? 0 : b2;
+        e1 = (c2 > last) ? 0 : e2;
+    }
+}
+
+// ---- phase B, octet part --------------------------------------------------------------------
+// An octet is one base commodity id (a multiple of 4) and eight masks for the commodities
+// base .. base+7 (0 where the commodity does not use the link).  One 8-byte load fetches the
+// eight choices.  A chunk holds up to 16*OPL octets and is reduced by one 16-lane DPP row: the
+// demands of the hits are added in (octet, slot) order per lane, then the fixed butterfly.
+// MODE 1 (width rho): every commodity with a non-zero mask counts once.
+template <int OPL>
+__device__ __forceinline__ void load_octets(int (&base)[OPL], u32x4 (&m)[OPL][2],
+                                            const int32_t *__restrict__ oct_base,
+                                            const uint32_t *__restrict__ oct_mask, int b, int e,
+                                            int l)
+{
+#pragma unroll
+    for (int it = 0; it < OPL; ++it) {
+        const int i = b + it * kRowLanes + l;
+        const int ii = i < e ? i : b;                 // unconditional loads, see load_pairs
+        base[it] = stream_load(oct_base + ii);
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(oct_mask + 8 * size_t(ii));
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        const u32x4 x0 = stream_load(src), x1 = stream_load(src + 1);
+        m[it][0] = (i < e) ? x0 : z;
+        m[it][1] = (i < e) ? x1 : z;
+    }
+}
+
+template <int MODE, int OPL>
+__device__ __forceinline__ void reduce_oct_phase(
+    int n_chunks, const int32_t *__restrict__ chunk_begin, const int32_t *__restrict__ chunk_end,
+    const int32_t *__restrict__ chunk_slot, const int32_t *__restrict__ oct_base,
+    const uint32_t *__restrict__ oct_mask, const uint8_t *__restrict__ choice,
+    const double *__restrict__ demand, const uint8_t *__restrict__ choice2,
+    const double *__restrict__ demand2, double *__restrict__ partial, int wave, int n_waves,
+    int lane)
+{
+    if (n_chunks <= 0) return;
+    const int row = lane / kRowLanes;
+    const int l = lane % kRowLanes;
+    const int stride = n_waves * kRowsPerWave;
+    const int last = n_chunks - 1;
+    int c = wave * kRowsPerWave + row;
+    int b1, e1;
+    int base[OPL];
+    u32x4 m[OPL][2];
+    {
+        int b0 = chunk_begin[c < last ? c : last], e0 = chunk_end[c < last ? c : last];
+        if (c > last) b0 = e0 = 0;
+        const int cn = c + stride;
+        b1 = chunk_begin[cn < last ? cn : last];
+        e1 = chunk_end[cn < last ? cn : last];
+        if (cn > last) b1 = e1 = 0;
+        load_octets<OPL>(base, m, oct_base, oct_mask, b0, e0, l);
+    }
+    for (; c - row < n_chunks; c += stride) {          // wave-uniform bound
+        // the eight choices of every octet (base is a multiple of 4: an aligned 8-byte load)
+        // (bit 31 of the slot word: the octets of this chunk are numbered by sigma)
+        const int slot_word = chunk_slot[c < last ? c : last];
+        const uint8_t *ch_src = slot_word < 0 ? choice2 : choice;
+        const double *dm_src = slot_word < 0 ? demand2 : demand;
+        const int slot = slot_word & 0x7FFFFFFF;
+        uint2 ch[OPL];
+#pragma unroll
+        for (int it = 0; it < OPL; ++it)
+            if constexpr (MODE == 0) ch[it] = *reinterpret_cast<const uint2 *>(ch_src + base[it]);
+        // requests for later chunks, issued after the gathers
+        const int c2 = c + 2 * stride;
+        const int b2 = chunk_begin[c2 < last ? c2 : last], e2 = chunk_end[c2 < last ? c2 : last];
+        int nbase[OPL];
+        u32x4 nm[OPL][2];
+        load_octets<OPL>(nbase, nm, oct_base, oct_mask, b1, e1, l);
+        // hit bits, 8 per octet
+        uint32_t hits = 0u;
+#pragma unroll
+        for (int it = 0; it < OPL; ++it) {
+            const uint32_t mk[8] = {m[it][0].x, m[it][0].y, m[it][0].z, m[it][0].w,
+                                    m[it][1].x, m[it][1].y, m[it][1].z, m[it][1].w};
+#pragma unroll
+            for (int sl = 0; sl < 8; ++sl) {
+                bool hit;
+                if constexpr (MODE == 0) {
+                    const uint32_t c8 = ((sl < 4 ? ch[it].x : ch[it].y) >> (8 * (sl & 3))) & 0xFFu;
+                    hit = c8 < 32u && ((mk[sl] >> c8) & 1u) != 0u;
+                } else {
+                    hit = mk[sl] != 0u;
+                }
+                hits |= static_cast<uint32_t>(hit) << (it * 8 + sl);
+            }
+        }
+        // demands of the hits in ascending (octet, slot) order; hits are rare in MODE 0
+        double acc = 0.0;
+        while (hits != 0u) {                 // four hits per turn, their loads side by side
+            int idx[4];
+            bool ok[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                ok[u] = hits != 0u;
+                const int t = ok[u] ? __ffs(hits) - 1 : 0;
+                hits &= hits - 1u;           // 0 stays 0
+                int bsel = base[0];
+#pragma unroll
+                for (int it = 1; it < OPL; ++it) bsel = ((t >> 3) == it) ? base[it] : bsel;
+                idx[u] = ok[u] ? bsel + (t & 7) : idx[0];
+            }
+            double d[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) d[u] = dm_src[idx[u]];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int mk = -static_cast<int>(ok[u]);      // masked, see the single pairs
+                acc = acc + __hiloint2double(__double2hiint(d[u]) & mk, __double2loint(d[u]) & mk);
+            }
+        }
+        acc = acc + partner_f64<1>(acc);
+        acc = acc + partner_f64<2>(acc);
+        acc = acc + partner_f64<4>(acc);
+        acc = acc + partner_f64<8>(acc);
+        if (c < n_chunks && l == 0) partial[slot] = acc;
+#pragma unroll
+        for (int it = 0; it < OPL; ++it) {
+            base[it] = nbase[it];
+            m[it][0] = nm[it][0];
+            m[it][1] = nm[it][1];
+        }
+        b1 = (c2 > last) ? 0 : b2;
+        e1 = (c2 > last) ? 0 : e2;
     }
 }
 
