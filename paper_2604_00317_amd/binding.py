@@ -263,7 +263,7 @@ def nimble_host_layout_stats(n_links, n_comm, comm_path_ptr, n_paths, path_link_
                                                  _hp(pl), _hp(out))
     if st != NIMBLE_OK:
         raise NimbleError(st, "invalid CSR")
-    keys = ["pairs", "octets", "singles", "octet_chunks", "single_chunks", "slots", "records",
+    keys = ["pairs", "octets", "singles", "octets_sigma", "single_chunks", "slots", "records",
             "record_stride"]
     return dict(zip(keys, (int(v) for v in out)))
 

@@ -168,13 +168,8 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     nimble::HostTopo h;
     try {
         t = new nimble_topo();
-        int opl = nimble::kOctetsPerLane;
-        if (const char *env = std::getenv("NIMBLE_TUNE_OCTETS_PER_LANE")) {
-            const int v = std::atoi(env);
-            if (v == 1 || v == 2 || v == 4) opl = v;
-        }
         nimble::build_host_topo(n_links, cap, n_comm, comm_path_ptr, n_paths, path_link_ptr,
-                                path_links, opl, h);
+                                path_links, h);
     } catch (const std::bad_alloc &) {
         delete t;
         return fail(NIMBLE_ERR_ALLOC, "host allocation failed");
@@ -197,10 +192,9 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     if (std::getenv("NIMBLE_TUNE_NO_RECORDS")) d.n_records = 0;
     d.pmax = h.pmax;
     d.lmax = h.lmax;
-    d.n_ochunks = static_cast<int32_t>(h.ochunk_begin.size());
+    d.n_passes = static_cast<int32_t>(h.oct_base.size() / 64);
     d.n_schunks = static_cast<int32_t>(h.schunk_begin.size());
     d.n_slots = h.n_slots;
-    d.octets_per_lane = h.octets_per_lane;
     d.cost_max = (flags & NIMBLE_COST_MAX) != 0u;
     d.n_update_blocks = (h.E + 15) / 16;   // 256-thread blocks, one 16-lane row per link
 
@@ -227,9 +221,10 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     NIMBLE_TRY(upload(t, h.oct_mask.data(), h.oct_mask.size(), &d.oct_mask), "oct_mask");
     NIMBLE_TRY(upload(t, h.single_pair.data(), h.single_pair.size(), &d.single_pair),
                "single_pair");
-    NIMBLE_TRY(upload(t, h.ochunk_begin.data(), h.ochunk_begin.size(), &d.ochunk_begin), "ochunk");
-    NIMBLE_TRY(upload(t, h.ochunk_end.data(), h.ochunk_end.size(), &d.ochunk_end), "ochunk");
-    NIMBLE_TRY(upload(t, h.ochunk_slot.data(), h.ochunk_slot.size(), &d.ochunk_slot), "ochunk");
+    NIMBLE_TRY(upload(t, h.pass_first_slot.data(), h.pass_first_slot.size(), &d.pass_first_slot),
+               "pass_first_slot");
+    NIMBLE_TRY(upload(t, h.link_sslot_ptr.data(), h.link_sslot_ptr.size(), &d.link_sslot_ptr),
+               "link_sslot_ptr");
     NIMBLE_TRY(upload(t, h.schunk_begin.data(), h.schunk_begin.size(), &d.schunk_begin), "schunk");
     NIMBLE_TRY(upload(t, h.schunk_end.data(), h.schunk_end.size(), &d.schunk_end), "schunk");
     NIMBLE_TRY(upload(t, h.schunk_slot.data(), h.schunk_slot.size(), &d.schunk_slot), "schunk");
@@ -269,10 +264,10 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
         t->bytes_argmin = static_cast<int64_t>(nimble::kRecBytes) * d.n_records + 10LL * h.K;
     else
         t->bytes_argmin = 4LL * (h.K + 1) + 4LL * (h.P + 1) + 4LL * h.nnz + 14LL * h.K;
-    t->bytes_reduce = 36LL * static_cast<int64_t>(h.oct_base.size()) +
-                      4LL * static_cast<int64_t>(h.single_pair.size()) +
-                      12LL * (d.n_ochunks + d.n_schunks) + 8LL * d.n_slots;
-    t->bytes_update = 8LL * d.n_slots + 4LL * (h.E + 1) + 56LL * h.E;
+    t->bytes_reduce = 36LL * static_cast<int64_t>(h.oct_base.size()) + 4LL * d.n_passes +
+                      4LL * static_cast<int64_t>(h.single_pair.size()) + 12LL * d.n_schunks +
+                      8LL * d.n_slots;
+    t->bytes_update = 8LL * d.n_slots + 8LL * (h.E + 1) + 56LL * h.E;
     t->bytes_per_iter = t->bytes_argmin + t->bytes_reduce + t->bytes_update;
     *out = t;
     return NIMBLE_OK;

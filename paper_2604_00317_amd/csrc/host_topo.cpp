@@ -77,9 +77,8 @@ nimble_status_t validate_csr(int32_t n_links, const double *cap, int32_t n_comm,
 void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                      const int32_t *comm_path_ptr, int32_t n_paths,
                      const int32_t *path_link_ptr, const int32_t *path_links,
-                     int32_t octets_per_lane, HostTopo &t)
+                     HostTopo &t)
 {
-    t.octets_per_lane = octets_per_lane;
     t.E = n_links;
     t.K = n_comm;
     t.P = n_paths;
@@ -162,23 +161,23 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
         t.link_chunk_ptr[e + 1] = static_cast<int32_t>(t.chunk_begin.size());
     }
 
-    // ---- streaming layout of the reverse rows: octets (two numberings) + single pairs -----
+    // ---- streaming layout of the reverse rows: flat octets (two numberings) + single pairs --
     t.oct_base.clear();
     t.oct_mask.clear();
+    t.pass_first_slot.clear();
     t.single_pair.clear();
     t.n_single_pairs = 0;
-    t.ochunk_begin.clear(); t.ochunk_end.clear(); t.ochunk_slot.clear();
     t.schunk_begin.clear(); t.schunk_end.clear(); t.schunk_slot.clear();
     t.link_slot_ptr.assign(n_links + 1, 0);
-    t.n_slots = 0;
+    t.link_sslot_ptr.assign(n_links + 1, 0);
     t.sigma.assign(n_comm, -1);
-    const int32_t oct_chunk = kRowLanesHost * t.octets_per_lane;
     const int32_t sgl_chunk = kRowLanesHost * kSinglesPerLane;
     auto one_window = [&](int32_t kk) { return comm_path_ptr[kk + 1] - comm_path_ptr[kk] <= 32; };
-    struct Item { int32_t key; uint32_t a, b; };       // key: commodity id or sigma
+    struct Item { int32_t key; uint32_t a, b; };       // key: commodity id or sigma, -1: single
     // greedy octet packing of items sorted by key; appends octets, returns the left-overs
-    auto pack = [&](const std::vector<Item> &items, int32_t key_limit, std::vector<int32_t> &obase,
-                    std::vector<uint32_t> &omask, std::vector<Item> &left) {
+    auto pack = [&](const std::vector<Item> &items, int32_t key_limit, int32_t min_fill,
+                    uint32_t flags, std::vector<uint32_t> &obase, std::vector<uint32_t> &omask,
+                    std::vector<Item> &left) {
         size_t i = 0;
         while (i < items.size()) {
             const int32_t base = items[i].key & ~3;
@@ -187,11 +186,15 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                 while (i + cnt < items.size() && items[i + cnt].key >= 0 &&
                        items[i + cnt].key < base + 8)
                     ++cnt;
-            if (static_cast<int32_t>(cnt) >= kOctetMinFill && base + 8 <= key_limit) {
-                obase.push_back(base);
+            // an octet must not read past its choice array: slide the window back at the end
+            const int32_t b8 = base + 8 <= key_limit ? base : ((key_limit - 8) & ~3);
+            const bool fits = cnt > 0 && b8 >= 0 && items[i].key >= b8 &&
+                              items[i + cnt - 1].key < b8 + 8;
+            if (static_cast<int32_t>(cnt) >= min_fill && fits) {
+                obase.push_back(static_cast<uint32_t>(b8) | flags);
                 const size_t m0 = omask.size();
                 omask.resize(m0 + 8, 0u);
-                for (size_t q = 0; q < cnt; ++q) omask[m0 + (items[i + q].key - base)] = items[i + q].b;
+                for (size_t q = 0; q < cnt; ++q) omask[m0 + (items[i + q].key - b8)] = items[i + q].b;
                 i += cnt;
             } else {
                 left.push_back(items[i]);
@@ -201,8 +204,7 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
     };
     // pass 1: octets over commodity ids, row by row; left-overs kept per row
     std::vector<std::vector<Item>> left1(n_links);
-    std::vector<std::vector<int32_t>> rowA_base(n_links);
-    std::vector<std::vector<uint32_t>> rowA_mask(n_links);
+    std::vector<std::vector<uint32_t>> row_base(n_links), row_mask(n_links);
     for (int32_t e = 0; e < n_links; ++e) {
         std::vector<Item> items;
         for (int32_t i = 0; i < t.rev_rowlen[e]; ++i) {
@@ -211,7 +213,7 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
             const int32_t kk = static_cast<int32_t>(a & kCommMask);
             items.push_back({one_window(kk) ? kk : -1, a, b});    // -1: never in an octet
         }
-        pack(items, n_comm, rowA_base[e], rowA_mask[e], left1[e]);
+        pack(items, n_comm, kOctetMinFill, 0u, row_base[e], row_mask[e], left1[e]);
     }
     // second numbering: left-over commodities in order of first appearance, every row's new
     // run starting at a multiple of 8
@@ -231,14 +233,11 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
         }
     }
     t.sigma_size = ((next_sigma + 7) & ~7) + 8;
-    // pass 2: octets over sigma from the left-overs, then the final layout row by row
-    std::vector<int32_t> octB_base;
-    std::vector<uint32_t> octB_mask;
-    std::vector<std::vector<int32_t>> rowB_base(n_links);
-    std::vector<std::vector<uint32_t>> rowB_mask(n_links);
-    std::vector<std::vector<Item>> left2(n_links);
+    // passes 2 and 3 and the flat arrays
+    t.n_octets_sigma = 0;
+    int32_t slot = 0;
     for (int32_t e = 0; e < n_links; ++e) {
-        std::vector<Item> items;
+        std::vector<Item> items, left2, left3;
         for (const Item &it : left1[e]) {
             Item x = it;
             x.key = it.key < 0 ? -1 : t.sigma[it.a & kCommMask];
@@ -247,43 +246,36 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
         std::stable_sort(items.begin(), items.end(), [](const Item &x, const Item &y) {
             return (x.key < 0 ? INT32_MAX : x.key) < (y.key < 0 ? INT32_MAX : y.key);
         });
-        pack(items, t.sigma_size, rowB_base[e], rowB_mask[e], left2[e]);
-        // single pairs back in (commodity, window) order
-        std::stable_sort(left2[e].begin(), left2[e].end(), [](const Item &x, const Item &y) {
+        const size_t before = row_base[e].size();
+        pack(items, t.sigma_size, kOctetMinFill, kOctSigma, row_base[e], row_mask[e], left2);
+        t.n_octets_sigma += static_cast<int64_t>(row_base[e].size() - before);
+        // back to (commodity, window) order; eligible ones become octets of any fill
+        for (Item &x : left2) x.key = x.key < 0 ? -1 : static_cast<int32_t>(x.a & kCommMask);
+        std::stable_sort(left2.begin(), left2.end(), [](const Item &x, const Item &y) {
             const uint32_t kx = x.a & kCommMask, ky = y.a & kCommMask;
             return kx != ky ? kx < ky : ((x.a >> kWindowShift) & 3u) < ((y.a >> kWindowShift) & 3u);
         });
-    }
-    // octets over ids of all rows first, then octets over sigma, so that a chunk is of one kind
-    std::vector<int32_t> rowA_first(n_links + 1, 0), rowB_first(n_links + 1, 0);
-    for (int32_t e = 0; e < n_links; ++e) {
-        rowA_first[e] = static_cast<int32_t>(t.oct_base.size());
-        t.oct_base.insert(t.oct_base.end(), rowA_base[e].begin(), rowA_base[e].end());
-        t.oct_mask.insert(t.oct_mask.end(), rowA_mask[e].begin(), rowA_mask[e].end());
-    }
-    rowA_first[n_links] = static_cast<int32_t>(t.oct_base.size());
-    t.n_octets_id = static_cast<int64_t>(t.oct_base.size());
-    for (int32_t e = 0; e < n_links; ++e) {
-        rowB_first[e] = static_cast<int32_t>(t.oct_base.size());
-        t.oct_base.insert(t.oct_base.end(), rowB_base[e].begin(), rowB_base[e].end());
-        t.oct_mask.insert(t.oct_mask.end(), rowB_mask[e].begin(), rowB_mask[e].end());
-    }
-    rowB_first[n_links] = static_cast<int32_t>(t.oct_base.size());
-    for (int32_t e = 0; e < n_links; ++e) {
-        for (int32_t b = rowA_first[e]; b < rowA_first[e + 1]; b += oct_chunk) {
-            t.ochunk_begin.push_back(b);
-            t.ochunk_end.push_back(b + oct_chunk < rowA_first[e + 1] ? b + oct_chunk
-                                                                    : rowA_first[e + 1]);
-            t.ochunk_slot.push_back(t.n_slots++);
+        pack(left2, n_comm, 1, 0u, row_base[e], row_mask[e], left3);
+        // append the row to the flat arrays; a new slot at the row's first octet and at
+        // every pass boundary
+        t.link_slot_ptr[e] = slot;
+        for (size_t q = 0; q < row_base[e].size(); ++q) {
+            const size_t pos = t.oct_base.size();
+            uint32_t w = row_base[e][q];
+            if (q == 0 || pos % 64 == 0) {
+                w |= kOctNewSlot;
+                if (pos % 64 == 0) t.pass_first_slot.push_back(slot);
+                ++slot;
+            }
+            t.oct_base.push_back(w);
+            t.oct_mask.insert(t.oct_mask.end(), row_mask[e].begin() + 8 * q,
+                              row_mask[e].begin() + 8 * q + 8);
         }
-        for (int32_t b = rowB_first[e]; b < rowB_first[e + 1]; b += oct_chunk) {
-            t.ochunk_begin.push_back(b);
-            t.ochunk_end.push_back(b + oct_chunk < rowB_first[e + 1] ? b + oct_chunk
-                                                                    : rowB_first[e + 1]);
-            t.ochunk_slot.push_back(static_cast<int32_t>(0x80000000u | static_cast<uint32_t>(t.n_slots++)));
-        }
+        row_base[e].clear(); row_base[e].shrink_to_fit();
+        row_mask[e].clear(); row_mask[e].shrink_to_fit();
+        // single pairs (commodities with several windows)
         const int32_t s_first = static_cast<int32_t>(t.single_pair.size() / 2);
-        for (const Item &it : left2[e]) {
+        for (const Item &it : left3) {
             t.single_pair.push_back(it.a);
             t.single_pair.push_back(it.b);
             t.n_single_pairs += 1;
@@ -293,22 +285,41 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
             t.single_pair.push_back(0u);
         }
         const int32_t s_last = static_cast<int32_t>(t.single_pair.size() / 2);
+        t.link_sslot_ptr[e] = static_cast<int32_t>(t.schunk_begin.size());
         for (int32_t b = s_first; b < s_last; b += sgl_chunk) {
             t.schunk_begin.push_back(b);
             t.schunk_end.push_back(b + sgl_chunk < s_last ? b + sgl_chunk : s_last);
-            t.schunk_slot.push_back(t.n_slots++);
         }
-        t.link_slot_ptr[e + 1] = t.n_slots;
     }
+    t.link_slot_ptr[n_links] = slot;
+    t.n_oct_slots = slot;
+    t.n_octets = static_cast<int64_t>(t.oct_base.size());
+    // pad the flat array to whole passes: padding octets have no masks and start a slot of
+    // their own that no link owns
+    while (t.oct_base.size() % 64) {
+        if (t.oct_base.size() % 64 == 0) t.pass_first_slot.push_back(slot);
+        t.oct_base.push_back(kOctNewSlot);
+        t.oct_mask.resize(t.oct_mask.size() + 8, 0u);
+    }
+    if (t.oct_base.empty()) {             // keep one (empty) pass
+        t.pass_first_slot.push_back(slot);
+        t.oct_base.assign(64, kOctNewSlot);
+        t.oct_mask.assign(8 * 64, 0u);
+    }
+    // padding octets may each open a slot: reserve one slot per padding octet
+    const int32_t pad_slots = 64;
+    const int32_t single_slot0 = t.n_oct_slots + pad_slots;
+    t.link_sslot_ptr[n_links] = static_cast<int32_t>(t.schunk_begin.size());
+    t.schunk_slot.resize(t.schunk_begin.size());
+    for (size_t c = 0; c < t.schunk_begin.size(); ++c)
+        t.schunk_slot[c] = single_slot0 + static_cast<int32_t>(c);
+    for (int32_t e = 0; e <= n_links; ++e) t.link_sslot_ptr[e] += single_slot0;
+    t.n_slots = single_slot0 + static_cast<int32_t>(t.schunk_begin.size());
     if (t.single_pair.empty()) {          // keep the array loadable
-        t.single_pair.push_back(static_cast<uint32_t>(n_comm));
-        t.single_pair.push_back(0u);
-        t.single_pair.push_back(static_cast<uint32_t>(n_comm));
-        t.single_pair.push_back(0u);
-    }
-    if (t.oct_base.empty()) {
-        t.oct_base.push_back(0);
-        t.oct_mask.resize(8, 0u);
+        for (int q = 0; q < 2; ++q) {
+            t.single_pair.push_back(static_cast<uint32_t>(n_comm));
+            t.single_pair.push_back(0u);
+        }
     }
 
     // ---- forward records ------------------------------------------------------------------
@@ -421,7 +432,7 @@ extern "C" nimble_status_t nimble_host_build_reverse(int32_t n_links, int32_t n_
     std::vector<double> cap(n_links, 1.0);
     nimble::HostTopo t;
     nimble::build_host_topo(n_links, cap.data(), n_comm, comm_path_ptr, n_paths, path_link_ptr,
-                            path_links, nimble::kOctetsPerLane, t);
+                            path_links, t);
     // expand the (commodity, window, mask) pairs back into one entry per incidence
     int32_t w = 0;
     for (int32_t e = 0; e < n_links; ++e) {
@@ -458,7 +469,7 @@ extern "C" nimble_status_t nimble_host_records_roundtrip(int32_t n_links, int32_
     std::vector<double> cap(n_links, 1.0);
     nimble::HostTopo t;
     nimble::build_host_topo(n_links, cap.data(), n_comm, comm_path_ptr, n_paths, path_link_ptr,
-                            path_links, nimble::kOctetsPerLane, t);
+                            path_links, t);
     *n_records_out = t.n_records;
     if (t.n_records == 0) return NIMBLE_OK;
     // read every incidence back the way the kernel does: header -> first candidate of each
@@ -510,11 +521,11 @@ extern "C" nimble_status_t nimble_host_layout_stats(int32_t n_links, int32_t n_c
     std::vector<double> cap(n_links, 1.0);
     nimble::HostTopo t;
     nimble::build_host_topo(n_links, cap.data(), n_comm, comm_path_ptr, n_paths, path_link_ptr,
-                            path_links, nimble::kOctetsPerLane, t);
+                            path_links, t);
     out[0] = t.n_pairs;
-    out[1] = static_cast<int64_t>(t.oct_base.size());
+    out[1] = t.n_octets;
     out[2] = t.n_single_pairs;
-    out[3] = static_cast<int64_t>(t.ochunk_begin.size());
+    out[3] = t.n_octets_sigma;
     out[4] = static_cast<int64_t>(t.schunk_begin.size());
     out[5] = t.n_slots;
     out[6] = t.n_records;

@@ -24,23 +24,30 @@ constexpr int kWindowShift = 24;
 constexpr uint32_t kFirstFlag = 1u << 31;
 constexpr int32_t kMaxComm = (1 << 24) - 2;   // one id is kept as the padding sentinel
 constexpr int32_t kMaxPathsPerComm = 127;     // four windows of 32, index 255 never occurs
-constexpr int32_t kRowLanesHost = 16;         // lanes of one DPP row reduce one chunk
+constexpr int32_t kRowLanesHost = 16;         // lanes of one DPP row reduce one single-pair chunk
 constexpr int32_t kPairAlign = 2;             // rows are padded to 16 bytes (2 pairs)
 
 // Streaming layout of the same rows.  Commodity ids that fall into one aligned-by-4 window of 8
 // consecutive ids are packed into an OCTET: one base id and eight masks (0 for commodities
-// that do not use the link), so that one 8-byte load fetches all eight choices; an octet is
-// emitted when it holds at least kOctetMinFill pairs.  Pairs left over (rows whose commodities
-// are far apart in id order, e.g. "all sources towards one destination") get a second chance
-// under a second numbering sigma of the commodities: walking the rows in order, every
-// left-over commodity that has no sigma yet receives the next one, so the left-overs of the
-// first row that lists them become consecutive, and rows with the same left-overs are dense
-// under sigma.  Octets over sigma read a second copy of the choices (and demands) stored in
-// sigma order.  What is still left stays SINGLE pairs as above.  A link's load is the sum over
-// its chunks of all three kinds.
+// that do not use the link), so that one 8-byte load fetches all eight choices.  A row is
+// packed in three passes: (1) octets over commodity ids that hold at least kOctetMinFill
+// pairs; (2) the left-overs (rows whose commodities are far apart in id order, e.g. "all
+// sources towards one destination") get a second chance under a second numbering sigma of the
+// commodities -- walking the rows in order, every left-over commodity that has no sigma yet
+// receives the next one, so the left-overs of the first row that lists them become
+// consecutive and rows with the same left-overs are dense under sigma; octets over sigma read
+// a second copy of the choices (and demands) stored in sigma order; (3) what is still left
+// becomes octets over ids of any fill.  Only commodities with more than 32 candidates
+// (several windows) stay SINGLE pairs.
+//
+// All octets of all rows form one flat array, row after row, processed 64 at a time (one per
+// lane, a "pass").  The low bits of the base word carry two flags: bit 0 = this octet starts a
+// new partial-sum slot (first octet of a row, or of a pass), bit 1 = numbered by sigma.  The
+// slots of a row are consecutive; pass_first_slot gives the slot of the first octet of a pass.
 constexpr int32_t kOctetMinFill = 3;
-constexpr int32_t kOctetsPerLane = 1;         // default: an octet chunk holds 16 * 1 octets
-constexpr int32_t kSinglesPerLane = 8;        // a single chunk holds 16 * 8 pairs
+constexpr uint32_t kOctNewSlot = 1u;
+constexpr uint32_t kOctSigma = 2u;
+constexpr int32_t kSinglesPerLane = 8;        // a single-pair chunk holds 16 * 8 pairs
 
 // ---- forward CSR records ------------------------------------------------------------------
 // The forward CSR is repacked into self-contained records of kRecBytes bytes, each holding a
@@ -78,21 +85,21 @@ struct HostTopo {
     std::vector<int32_t> chunk_begin;    // [n_chunks], pair offsets
     std::vector<int32_t> chunk_end;      // [n_chunks]
     std::vector<int32_t> link_chunk_ptr; // [E+1]
-    // streaming layout: octets and single pairs, each cut into chunks that write one partial
-    // sum into `slot`; the slots of a link are contiguous: link_slot_ptr[e] .. link_slot_ptr[e+1]
-    std::vector<int32_t> oct_base;       // [n_octets]: octets over ids first, then over sigma
-    std::vector<uint32_t> oct_mask;      // [8 * n_octets]
-    int64_t n_octets_id = 0;             // octets over commodity ids
+    // streaming layout
+    std::vector<uint32_t> oct_base;      // [n_oct_padded]: base id | flags, padded to 64
+    std::vector<uint32_t> oct_mask;      // [8 * n_oct_padded]
+    int64_t n_octets = 0;                // unpadded
+    int64_t n_octets_sigma = 0;          // of which numbered by sigma
+    std::vector<int32_t> pass_first_slot; // [n_oct_padded / 64]
+    int32_t n_oct_slots = 0;
+    std::vector<int32_t> link_slot_ptr;  // [E+1] octet slots of a link
     std::vector<int32_t> sigma;          // [K] second numbering, -1 = none
     int32_t sigma_size = 0;              // length of the sigma-ordered copies (multiple of 8)
     std::vector<uint32_t> single_pair;   // [2 * n_singles_padded], rows padded to 2 pairs
     int64_t n_single_pairs = 0;          // unpadded
-    // octet units; bit 31 of the slot word marks a chunk of sigma octets
-    std::vector<int32_t> ochunk_begin, ochunk_end, ochunk_slot;
     std::vector<int32_t> schunk_begin, schunk_end, schunk_slot;   // pair units
-    std::vector<int32_t> link_slot_ptr;  // [E+1]
-    int32_t n_slots = 0;
-    int32_t octets_per_lane = kOctetsPerLane;
+    std::vector<int32_t> link_sslot_ptr; // [E+1] single-chunk slots of a link (after the octet slots)
+    int32_t n_slots = 0;                 // octet slots + single-chunk slots
     // forward records (n_records = 0 when the topology does not fit them: a path longer than
     // kRecMaxStride links, padding above 1.5x, or a commodity that alone overflows a record)
     int32_t rec_stride = 0;              // indices per candidate = lmax
@@ -106,10 +113,10 @@ nimble_status_t validate_csr(int32_t n_links, const double *cap, int32_t n_comm,
                              const int32_t *path_link_ptr, const int32_t *path_links,
                              std::string &why);
 
-// Builds everything in HostTopo from validated input.  octets_per_lane is 1, 2 or 4.
+// Builds everything in HostTopo from validated input.
 void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                      const int32_t *comm_path_ptr, int32_t n_paths,
                      const int32_t *path_link_ptr, const int32_t *path_links,
-                     int32_t octets_per_lane, HostTopo &out);
+                     HostTopo &out);
 
 }  // namespace nimble

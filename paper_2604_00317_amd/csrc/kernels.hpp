@@ -24,16 +24,18 @@ struct DeviceTopo {
     int64_t rev_pairs;         // padded number of pairs
     const int32_t *rev_ptr;    // [E+1], in pairs
     const uint32_t *rev_pair;  // [2 * rev_pairs]
-    // streaming layout of the reverse rows: octets (base id + 8 masks) and single pairs, cut
-    // into chunks that each write one partial sum into partial[slot]
-    int32_t n_ochunks, n_schunks, n_slots;
-    int32_t octets_per_lane;    // 1, 2 or 4: an octet chunk holds 16 * octets_per_lane octets
-    const int32_t *oct_base;    // [n_octets]
-    const uint32_t *oct_mask;   // [8 * n_octets]
-    const uint32_t *single_pair; // [2 * padded singles]
-    const int32_t *ochunk_begin, *ochunk_end, *ochunk_slot;   // [n_ochunks], octet units
+    // streaming layout of the reverse rows: one flat array of octets (base id | flags, 8
+    // masks) walked 64 at a time, plus chunked single pairs for commodities with > 32
+    // candidates; every slot of partial[] receives one partial sum
+    int32_t n_passes;           // flat octets / 64
+    int32_t n_schunks, n_slots;
+    const uint32_t *oct_base;   // [64 * n_passes]
+    const uint32_t *oct_mask;   // [8 * 64 * n_passes]
+    const int32_t *pass_first_slot;   // [n_passes]
+    const int32_t *link_slot_ptr;     // [E+1] octet slots of a link
+    const uint32_t *single_pair;      // [2 * padded singles]
     const int32_t *schunk_begin, *schunk_end, *schunk_slot;   // [n_schunks], pair units
-    const int32_t *link_slot_ptr;                             // [E+1]
+    const int32_t *link_sslot_ptr;    // [E+1] single-chunk slots of a link
     // second numbering of the commodities for the sigma octets, with sigma-ordered copies of
     // the choices and the demands
     int32_t sigma_size;

@@ -69,14 +69,14 @@ __device__ __forceinline__ bool grid_barrier(SyncWords *w, unsigned int n_blocks
 }
 
 struct PersistentArgs {
-    int E, K, P, n_ochunks, n_schunks;
+    int E, K, P, n_passes, n_schunks;
     uint32_t pad_comm;
     const int32_t *cp, *lp, *pl;
-    const int32_t *ochunk_begin, *ochunk_end, *ochunk_slot, *oct_base;
-    const uint32_t *oct_mask;
+    const int32_t *pass_first_slot;
+    const uint32_t *oct_base, *oct_mask;
     const int32_t *schunk_begin, *schunk_end, *schunk_slot;
     const uint32_t *single_pair;
-    const int32_t *link_slot_ptr;
+    const int32_t *link_slot_ptr, *link_sslot_ptr;
     const int32_t *sigma;
     uint8_t *choice2;
     double *demand2;
@@ -97,10 +97,8 @@ template <int MODE>
 __device__ __forceinline__ void reduce_both(const PersistentArgs &a, int wave, int n_waves,
                                             int lane)
 {
-    reduce_oct_phase<MODE, kOctetsPerLane>(a.n_ochunks, a.ochunk_begin, a.ochunk_end,
-                                           a.ochunk_slot, a.oct_base, a.oct_mask, a.choice,
-                                           a.demand, a.choice2, a.demand2, a.partial, wave,
-                                           n_waves, lane);
+    reduce_flat_phase<MODE>(a.n_passes, a.pass_first_slot, a.oct_base, a.oct_mask, a.choice,
+                            a.demand, a.choice2, a.demand2, a.partial, wave, n_waves, lane);
     reduce_phase<MODE, kSinglesPerLane>(a.n_schunks, a.schunk_begin, a.schunk_end, a.schunk_slot,
                                         a.single_pair, a.pad_comm, a.choice, a.demand, a.partial,
                                         n_waves - 1 - wave, n_waves, lane);
@@ -140,7 +138,8 @@ __global__ __launch_bounds__(kPBlock) void k_persistent(PersistentArgs a)
     reduce_both<1>(a, wave, n_waves, lane);
     if (!grid_barrier(a.sync, nb, a.spin_limit, &s_flag)) goto abandoned;
     {
-        double m = width_phase(a.E, a.link_slot_ptr, a.partial, a.invcap, wave, n_waves, lane);
+        double m = width_phase(a.E, a.link_slot_ptr, a.link_sslot_ptr, a.partial, a.invcap, wave,
+                               n_waves, lane);
         m = block_max(m, red);
         if (threadIdx.x == 0) atomic_max_bits(&a.sync->rho_bits, m);
     }
@@ -156,8 +155,8 @@ __global__ __launch_bounds__(kPBlock) void k_persistent(PersistentArgs a)
             if (!grid_barrier(a.sync, nb, a.spin_limit, &s_flag)) goto abandoned;
             reduce_both<0>(a, wave, n_waves, lane);
             if (!grid_barrier(a.sync, nb, a.spin_limit, &s_flag)) goto abandoned;
-            update_phase<MAXC>(a.E, a.eps, invrho, a.link_slot_ptr, a.partial, a.invcap, a.len,
-                               a.price, a.S, wave, n_waves, lane);
+            update_phase<MAXC>(a.E, a.eps, invrho, a.link_slot_ptr, a.link_sslot_ptr, a.partial,
+                               a.invcap, a.len, a.price, a.S, wave, n_waves, lane);
             if (!grid_barrier(a.sync, nb, a.spin_limit, &s_flag)) goto abandoned;
         }
     }
@@ -229,20 +228,17 @@ hipError_t launch_persistent(const DeviceTopo &t, void *sync_words, int n_cu,
                              unsigned int spin_limit, const double *demand, double eps,
                              int32_t iters, double *splits, double *lambda, hipStream_t s)
 {
-    if (t.octets_per_lane != kOctetsPerLane) return hipErrorInvalidValue;
     PersistentArgs a;
     a.E = t.E;
     a.K = t.K;
     a.P = t.P;
-    a.n_ochunks = t.n_ochunks;
+    a.n_passes = t.n_passes;
     a.n_schunks = t.n_schunks;
     a.pad_comm = static_cast<uint32_t>(t.K);
     a.cp = t.comm_ptr;
     a.lp = t.path_ptr;
     a.pl = t.path_links;
-    a.ochunk_begin = t.ochunk_begin;
-    a.ochunk_end = t.ochunk_end;
-    a.ochunk_slot = t.ochunk_slot;
+    a.pass_first_slot = t.pass_first_slot;
     a.oct_base = t.oct_base;
     a.oct_mask = t.oct_mask;
     a.schunk_begin = t.schunk_begin;
@@ -250,6 +246,7 @@ hipError_t launch_persistent(const DeviceTopo &t, void *sync_words, int n_cu,
     a.schunk_slot = t.schunk_slot;
     a.single_pair = t.single_pair;
     a.link_slot_ptr = t.link_slot_ptr;
+    a.link_sslot_ptr = t.link_sslot_ptr;
     a.sigma = t.sigma;
     a.choice2 = t.choice2;
     a.demand2 = t.demand2;

@@ -142,9 +142,9 @@ __global__ __launch_bounds__(kWave) void k_argmin_rec(int n_records,
 }
 
 struct ReduceArgs {
-    int n_ochunks, n_schunks;
-    const int32_t *ochunk_begin, *ochunk_end, *ochunk_slot, *oct_base;
-    const uint32_t *oct_mask;
+    int n_passes, n_schunks;
+    const int32_t *pass_first_slot;
+    const uint32_t *oct_base, *oct_mask;
     const int32_t *schunk_begin, *schunk_end, *schunk_slot;
     const uint32_t *single_pair;
     uint32_t pad_comm;
@@ -153,32 +153,31 @@ struct ReduceArgs {
     double *partial;
 };
 
-template <int MODE, int OPL>
+template <int MODE>
 __global__ __launch_bounds__(kBlock) void k_load_reduce(ReduceArgs a)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
-    reduce_oct_phase<MODE, OPL>(a.n_ochunks, a.ochunk_begin, a.ochunk_end,
-                                           a.ochunk_slot, a.oct_base, a.oct_mask, a.choice,
-                                           a.demand, a.choice2, a.demand2, a.partial, wave,
-                                           n_waves, lane);
-    // the single pairs are walked from the other end of the wave pool, so that the waves that
-    // got no octet chunk start on them at once
+    reduce_flat_phase<MODE>(a.n_passes, a.pass_first_slot, a.oct_base, a.oct_mask, a.choice,
+                            a.demand, a.choice2, a.demand2, a.partial, wave, n_waves, lane);
+    // single pairs (commodities with more than 32 candidates) are walked from the other end of
+    // the wave pool
     reduce_phase<MODE, kSinglesPerLane>(a.n_schunks, a.schunk_begin, a.schunk_end, a.schunk_slot,
                                         a.single_pair, a.pad_comm, a.choice, a.demand, a.partial,
                                         n_waves - 1 - wave, n_waves, lane);
 }
 
 // rho = max_e (demand that can reach e) / cap_e; scalars[0] = 1/rho (0 when rho = 0)
-__global__ __launch_bounds__(1024) void k_width(int E, const int32_t *__restrict__ link_chunk_ptr,
+__global__ __launch_bounds__(1024) void k_width(int E, const int32_t *__restrict__ link_slot_ptr,
+                                                const int32_t *__restrict__ link_sslot_ptr,
                                                 const double *__restrict__ partial,
                                                 const double *__restrict__ invcap,
                                                 double *__restrict__ scalars)
 {
     __shared__ double red[16];
-    double m = width_phase(E, link_chunk_ptr, partial, invcap, threadIdx.x >> 6, blockDim.x >> 6,
-                           threadIdx.x & (kWave - 1));
+    double m = width_phase(E, link_slot_ptr, link_sslot_ptr, partial, invcap, threadIdx.x >> 6,
+                           blockDim.x >> 6, threadIdx.x & (kWave - 1));
     m = block_max(m, red);
     if (threadIdx.x == 0) scalars[0] = (m > 0.0) ? 1.0 / m : 0.0;
 }
@@ -186,7 +185,8 @@ __global__ __launch_bounds__(1024) void k_width(int E, const int32_t *__restrict
 // length update fused with the per-block maximum of the congestion sums (lambda = max / iters)
 template <bool MAXC>
 __global__ __launch_bounds__(kBlock) void k_update(int E, double eps,
-                                                   const int32_t *__restrict__ link_chunk_ptr,
+                                                   const int32_t *__restrict__ link_slot_ptr,
+                                                   const int32_t *__restrict__ link_sslot_ptr,
                                                    const double *__restrict__ partial,
                                                    const double *__restrict__ invcap,
                                                    double *__restrict__ len,
@@ -198,8 +198,8 @@ __global__ __launch_bounds__(kBlock) void k_update(int E, double eps,
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
-    const double s_new = update_phase<MAXC>(E, eps, scalars[0], link_chunk_ptr, partial, invcap,
-                                            len, price, S, wave, n_waves, lane);
+    const double s_new = update_phase<MAXC>(E, eps, scalars[0], link_slot_ptr, link_sslot_ptr,
+                                            partial, invcap, len, price, S, wave, n_waves, lane);
     const double m = block_max(s_new, red);
     if (threadIdx.x == 0) scalars[1 + blockIdx.x] = m;
 }
@@ -282,16 +282,15 @@ void launch_argmin_l(const DeviceTopo &t, hipStream_t s)
 template <int MODE>
 void launch_reduce_mode(const DeviceTopo &t, const double *demand, hipStream_t s)
 {
-    // a fixed pool of waves, each walking its chunks with the loads pipelined
-    const int64_t rows = static_cast<int64_t>(t.n_ochunks) + t.n_schunks;
-    const int64_t waves = (rows + kRowsPerWave - 1) / kRowsPerWave;
+    // a fixed pool of waves, each walking its passes with the loads pipelined
+    const int64_t waves = static_cast<int64_t>(t.n_passes) > (t.n_schunks + 3) / 4
+                              ? static_cast<int64_t>(t.n_passes)
+                              : (t.n_schunks + 3) / 4;
     const int grid = blocks_for(waves * kWave, kBlock, t.reduce_blocks);
     ReduceArgs a;
-    a.n_ochunks = t.n_ochunks;
+    a.n_passes = t.n_passes;
     a.n_schunks = t.n_schunks;
-    a.ochunk_begin = t.ochunk_begin;
-    a.ochunk_end = t.ochunk_end;
-    a.ochunk_slot = t.ochunk_slot;
+    a.pass_first_slot = t.pass_first_slot;
     a.oct_base = t.oct_base;
     a.oct_mask = t.oct_mask;
     a.schunk_begin = t.schunk_begin;
@@ -304,12 +303,7 @@ void launch_reduce_mode(const DeviceTopo &t, const double *demand, hipStream_t s
     a.demand = demand;
     a.demand2 = t.demand2;
     a.partial = t.partial;
-    if (t.octets_per_lane == 1)
-        hipLaunchKernelGGL((k_load_reduce<MODE, 1>), dim3(grid), dim3(kBlock), 0, s, a);
-    else if (t.octets_per_lane == 2)
-        hipLaunchKernelGGL((k_load_reduce<MODE, 2>), dim3(grid), dim3(kBlock), 0, s, a);
-    else
-        hipLaunchKernelGGL((k_load_reduce<MODE, 4>), dim3(grid), dim3(kBlock), 0, s, a);
+    hipLaunchKernelGGL(k_load_reduce<MODE>, dim3(grid), dim3(kBlock), 0, s, a);
 }
 
 }  // namespace
@@ -332,8 +326,8 @@ void launch_init(const DeviceTopo &t, const double *demand, hipStream_t s)
 void launch_width(const DeviceTopo &t, const double *demand, hipStream_t s)
 {
     launch_reduce_mode<1>(t, demand, s);
-    hipLaunchKernelGGL(k_width, dim3(1), dim3(1024), 0, s, t.E, t.link_slot_ptr, t.partial,
-                       t.invcap, t.scalars);
+    hipLaunchKernelGGL(k_width, dim3(1), dim3(1024), 0, s, t.E, t.link_slot_ptr,
+                       t.link_sslot_ptr, t.partial, t.invcap, t.scalars);
 }
 
 void launch_argmin(const DeviceTopo &t, hipStream_t s)
@@ -351,10 +345,12 @@ void launch_update(const DeviceTopo &t, double eps, hipStream_t s)
 {
     if (t.cost_max)
         hipLaunchKernelGGL(k_update<true>, dim3(t.n_update_blocks), dim3(kBlock), 0, s, t.E, eps,
-                           t.link_slot_ptr, t.partial, t.invcap, t.len, t.price, t.S, t.scalars);
+                           t.link_slot_ptr, t.link_sslot_ptr, t.partial, t.invcap, t.len, t.price,
+                           t.S, t.scalars);
     else
         hipLaunchKernelGGL(k_update<false>, dim3(t.n_update_blocks), dim3(kBlock), 0, s, t.E, eps,
-                           t.link_slot_ptr, t.partial, t.invcap, t.len, t.price, t.S, t.scalars);
+                           t.link_slot_ptr, t.link_sslot_ptr, t.partial, t.invcap, t.len, t.price,
+                           t.S, t.scalars);
 }
 
 void launch_epilogue(const DeviceTopo &t, int32_t iters, double *splits, double *lambda,

@@ -229,94 +229,70 @@ __device__ __forceinline__ void reduce_phase(int n_chunks, const int32_t *__rest
 
 // ---- phase B, octet part --------------------------------------------------------------------
 // An octet is one base commodity id (a multiple of 4) and eight masks for the commodities
-// base .. base+7 (0 where the commodity does not use the link).  One 8-byte load fetches the
-// eight choices.  A chunk holds up to 16*OPL octets and is reduced by one 16-lane DPP row: the
-// demands of the hits are added in (octet, slot) order per lane, then the fixed butterfly.
+// base .. base+7 (0 where the commodity does not use the link); one 8-byte load fetches the
+// eight choices.  The octets of all links form one flat array that the waves walk 64 at a time
+// (one octet per lane).  Flag bits in the base word: kOctNewSlot = this octet starts a new
+// partial-sum slot (first octet of a link's row, or of a pass), kOctSigma = base is in the
+// second commodity numbering (choices and demands are read from the sigma-ordered copies).
+// Per lane the demands of the hits are added in slot order; the lanes of one slot are then
+// combined by a segmented inclusive scan (fixed distances 1,2,..,32: the same tree on every
+// run) and the last lane of the segment stores the sum.  No floating-point atomics.
 // MODE 1 (width rho): every commodity with a non-zero mask counts once.
-template <int OPL>
-__device__ __forceinline__ void load_octets(int (&base)[OPL], u32x4 (&m)[OPL][2],
-                                            const int32_t *__restrict__ oct_base,
-                                            const uint32_t *__restrict__ oct_mask, int b, int e,
-                                            int l)
+template <int MODE>
+__device__ __forceinline__ void reduce_flat_phase(
+    int n_passes, const int32_t *__restrict__ pass_first_slot,
+    const uint32_t *__restrict__ oct_base, const uint32_t *__restrict__ oct_mask,
+    const uint8_t *__restrict__ choice, const double *__restrict__ demand,
+    const uint8_t *__restrict__ choice2, const double *__restrict__ demand2,
+    double *__restrict__ partial, int wave, int n_waves, int lane)
 {
-#pragma unroll
-    for (int it = 0; it < OPL; ++it) {
-        const int i = b + it * kRowLanes + l;
-        const int ii = i < e ? i : b;                 // unconditional loads, see load_pairs
-        base[it] = stream_load(oct_base + ii);
-        const u32x4 *src = reinterpret_cast<const u32x4 *>(oct_mask + 8 * size_t(ii));
-        const u32x4 z = {0u, 0u, 0u, 0u};
-        const u32x4 x0 = stream_load(src), x1 = stream_load(src + 1);
-        m[it][0] = (i < e) ? x0 : z;
-        m[it][1] = (i < e) ? x1 : z;
-    }
-}
-
-template <int MODE, int OPL>
-__device__ __forceinline__ void reduce_oct_phase(
-    int n_chunks, const int32_t *__restrict__ chunk_begin, const int32_t *__restrict__ chunk_end,
-    const int32_t *__restrict__ chunk_slot, const int32_t *__restrict__ oct_base,
-    const uint32_t *__restrict__ oct_mask, const uint8_t *__restrict__ choice,
-    const double *__restrict__ demand, const uint8_t *__restrict__ choice2,
-    const double *__restrict__ demand2, double *__restrict__ partial, int wave, int n_waves,
-    int lane)
-{
-    if (n_chunks <= 0) return;
-    const int row = lane / kRowLanes;
-    const int l = lane % kRowLanes;
-    const int stride = n_waves * kRowsPerWave;
-    const int last = n_chunks - 1;
-    int c = wave * kRowsPerWave + row;
-    int b1, e1;
-    int base[OPL];
-    u32x4 m[OPL][2];
+    if (wave >= n_passes) return;
+    const int last = n_passes - 1;
+    // pipeline: the octets of the next pass are requested before the gathers of the current
+    // one are consumed; loads past the end re-read the last pass and are ignored
+    uint32_t bw;
+    u32x4 m0, m1;
     {
-        int b0 = chunk_begin[c < last ? c : last], e0 = chunk_end[c < last ? c : last];
-        if (c > last) b0 = e0 = 0;
-        const int cn = c + stride;
-        b1 = chunk_begin[cn < last ? cn : last];
-        e1 = chunk_end[cn < last ? cn : last];
-        if (cn > last) b1 = e1 = 0;
-        load_octets<OPL>(base, m, oct_base, oct_mask, b0, e0, l);
+        const size_t i = size_t(wave) * kWave + lane;
+        bw = stream_load(oct_base + i);
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(oct_mask + 8 * i);
+        m0 = stream_load(src);
+        m1 = stream_load(src + 1);
     }
-    for (; c - row < n_chunks; c += stride) {          // wave-uniform bound
-        // the eight choices of every octet (base is a multiple of 4: an aligned 8-byte load)
-        // (bit 31 of the slot word: the octets of this chunk are numbered by sigma)
-        const int slot_word = chunk_slot[c < last ? c : last];
-        const uint8_t *ch_src = slot_word < 0 ? choice2 : choice;
-        const double *dm_src = slot_word < 0 ? demand2 : demand;
-        const int slot = slot_word & 0x7FFFFFFF;
-        uint2 ch[OPL];
-#pragma unroll
-        for (int it = 0; it < OPL; ++it)
-            if constexpr (MODE == 0) ch[it] = *reinterpret_cast<const uint2 *>(ch_src + base[it]);
-        // requests for later chunks, issued after the gathers
-        const int c2 = c + 2 * stride;
-        const int b2 = chunk_begin[c2 < last ? c2 : last], e2 = chunk_end[c2 < last ? c2 : last];
-        int nbase[OPL];
-        u32x4 nm[OPL][2];
-        load_octets<OPL>(nbase, nm, oct_base, oct_mask, b1, e1, l);
-        // hit bits, 8 per octet
+    for (int pass = wave; pass < n_passes; pass += n_waves) {      // wave-uniform
+        const bool sig = (bw & kOctSigma) != 0u;
+        const int base = static_cast<int>(bw & ~3u);
+        const uint8_t *ch_src = sig ? choice2 : choice;
+        const double *dm_src = sig ? demand2 : demand;
+        uint2 ch = make_uint2(0u, 0u);
+        if constexpr (MODE == 0) ch = *reinterpret_cast<const uint2 *>(ch_src + base);
+        const int first_slot = pass_first_slot[pass];
+        // requests for the next pass, issued after the gather
+        const int np = pass + n_waves < last ? pass + n_waves : last;
+        const size_t ni = size_t(np) * kWave + lane;
+        const uint32_t nbw = stream_load(oct_base + ni);
+        const u32x4 *nsrc = reinterpret_cast<const u32x4 *>(oct_mask + 8 * ni);
+        const u32x4 nm0 = stream_load(nsrc), nm1 = stream_load(nsrc + 1);
+        // hit bits of the eight slots
+        const uint32_t mk[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
         uint32_t hits = 0u;
 #pragma unroll
-        for (int it = 0; it < OPL; ++it) {
-            const uint32_t mk[8] = {m[it][0].x, m[it][0].y, m[it][0].z, m[it][0].w,
-                                    m[it][1].x, m[it][1].y, m[it][1].z, m[it][1].w};
-#pragma unroll
-            for (int sl = 0; sl < 8; ++sl) {
-                bool hit;
-                if constexpr (MODE == 0) {
-                    const uint32_t c8 = ((sl < 4 ? ch[it].x : ch[it].y) >> (8 * (sl & 3))) & 0xFFu;
-                    hit = c8 < 32u && ((mk[sl] >> c8) & 1u) != 0u;
-                } else {
-                    hit = mk[sl] != 0u;
-                }
-                hits |= static_cast<uint32_t>(hit) << (it * 8 + sl);
+        for (int sl = 0; sl < 8; ++sl) {
+            uint32_t h;
+            if constexpr (MODE == 0) {
+                // commodities in octets have at most 32 candidates, so the choice is < 32
+                const uint32_t c8 = ((sl < 4 ? ch.x : ch.y) >> (8 * (sl & 3))) & 31u;
+                h = (mk[sl] >> c8) & 1u;
+            } else {
+                h = mk[sl] != 0u ? 1u : 0u;
             }
+            hits |= h << sl;
         }
-        // demands of the hits in ascending (octet, slot) order; hits are rare in MODE 0
+        // demands of the hits in slot order, four loads side by side; an absent hit re-reads
+        // the first one and is masked to +0.0 (masked, not selected: a select would let the
+        // compiler move the load under the condition and wait for it on its own)
         double acc = 0.0;
-        while (hits != 0u) {                 // four hits per turn, their loads side by side
+        while (hits != 0u) {
             int idx[4];
             bool ok[4];
 #pragma unroll
@@ -324,39 +300,37 @@ __device__ __forceinline__ void reduce_oct_phase(
                 ok[u] = hits != 0u;
                 const int t = ok[u] ? __ffs(hits) - 1 : 0;
                 hits &= hits - 1u;           // 0 stays 0
-                int bsel = base[0];
-#pragma unroll
-                for (int it = 1; it < OPL; ++it) bsel = ((t >> 3) == it) ? base[it] : bsel;
-                idx[u] = ok[u] ? bsel + (t & 7) : idx[0];
+                idx[u] = ok[u] ? base + t : idx[0];
             }
             double d[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) d[u] = dm_src[idx[u]];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int mk = -static_cast<int>(ok[u]);      // masked, see the single pairs
-                acc = acc + __hiloint2double(__double2hiint(d[u]) & mk, __double2loint(d[u]) & mk);
+                const int mkk = -static_cast<int>(ok[u]);
+                acc = acc + __hiloint2double(__double2hiint(d[u]) & mkk, __double2loint(d[u]) & mkk);
             }
         }
-        acc = acc + partner_f64<1>(acc);
-        acc = acc + partner_f64<2>(acc);
-        acc = acc + partner_f64<4>(acc);
-        acc = acc + partner_f64<8>(acc);
-        if (c < n_chunks && l == 0) partial[slot] = acc;
+        // segmented inclusive scan over the lanes of one slot
+        const unsigned long long heads = __ballot((bw & kOctNewSlot) != 0u);   // bit 0 is set
+        const unsigned long long upto = heads & (~0ull >> (63 - lane));       // heads at lanes <= lane
+        const int start = 63 - __clzll(static_cast<long long>(upto));
 #pragma unroll
-        for (int it = 0; it < OPL; ++it) {
-            base[it] = nbase[it];
-            m[it][0] = nm[it][0];
-            m[it][1] = nm[it][1];
+        for (int dist = 1; dist < kWave; dist <<= 1) {
+            const double v = __shfl_up(acc, dist, kWave);
+            if (lane - dist >= start) acc = acc + v;
         }
-        b1 = (c2 > last) ? 0 : b2;
-        e1 = (c2 > last) ? 0 : e2;
+        const bool tail = lane == kWave - 1 || ((heads >> (lane + 1)) & 1ull) != 0ull;
+        if (tail) partial[first_slot + __popcll(upto) - 1] = acc;
+        bw = nbw;
+        m0 = nm0;
+        m1 = nm1;
     }
 }
 
-// ---- phase C: chunk partials -> load, congestion sum, multiplicative length update ---------
-// One 16-lane DPP row per link: the lanes fetch the link's chunk partials side by side (16 per
-// step), add their own in ascending chunk order, and a fixed butterfly combines the 16 lane
+// ---- phase C: slot partials -> load, congestion sum, multiplicative length update ----------
+// One 16-lane DPP row per link: the lanes fetch the link's slot partials side by side (16 per
+// step), add their own in ascending slot order, and a fixed butterfly combines the 16 lane
 // sums; lane 0 of the row then applies  S_e += u_e,  len_e *= 1 + eps*u_e/rho,  price_e.
 // Returns, in lane 0 of every row, the new S_e (0 elsewhere) for the lambda max-reduce.
 __device__ __forceinline__ double row_partial_sum(int c0, int c1, int l,
@@ -373,7 +347,8 @@ __device__ __forceinline__ double row_partial_sum(int c0, int c1, int l,
 
 template <bool MAXC>
 __device__ __forceinline__ double update_phase(int E, double eps, double invrho,
-                                               const int32_t *__restrict__ link_chunk_ptr,
+                                               const int32_t *__restrict__ link_slot_ptr,
+                                               const int32_t *__restrict__ link_sslot_ptr,
                                                const double *__restrict__ partial,
                                                const double *__restrict__ invcap,
                                                double *__restrict__ len,
@@ -385,12 +360,15 @@ __device__ __forceinline__ double update_phase(int E, double eps, double invrho,
     double smax = 0.0;
     for (int ebase = wave * kRowsPerWave; ebase < E; ebase += n_waves * kRowsPerWave) {
         const int e = ebase + row;
-        int c0 = 0, c1 = 0;
+        int c0 = 0, c1 = 0, s0 = 0, s1 = 0;
         if (e < E) {
-            c0 = link_chunk_ptr[e];
-            c1 = link_chunk_ptr[e + 1];
+            c0 = link_slot_ptr[e];
+            c1 = link_slot_ptr[e + 1];
+            s0 = link_sslot_ptr[e];
+            s1 = link_sslot_ptr[e + 1];
         }
-        const double load = row_partial_sum(c0, c1, l, partial);
+        // octet slots, then (rarely any) single-pair slots
+        const double load = row_partial_sum(c0, c1, l, partial) + row_partial_sum(s0, s1, l, partial);
         if (e < E && l == 0) {
             const double ic = invcap[e];
             const double u = load * ic;
@@ -409,7 +387,8 @@ __device__ __forceinline__ double update_phase(int E, double eps, double invrho,
 }
 
 // max over this wave's links of (demand that can reach the link) / capacity: terms of rho
-__device__ __forceinline__ double width_phase(int E, const int32_t *__restrict__ link_chunk_ptr,
+__device__ __forceinline__ double width_phase(int E, const int32_t *__restrict__ link_slot_ptr,
+                                              const int32_t *__restrict__ link_sslot_ptr,
                                               const double *__restrict__ partial,
                                               const double *__restrict__ invcap, int wave,
                                               int n_waves, int lane)
@@ -419,12 +398,14 @@ __device__ __forceinline__ double width_phase(int E, const int32_t *__restrict__
     double m = 0.0;
     for (int ebase = wave * kRowsPerWave; ebase < E; ebase += n_waves * kRowsPerWave) {
         const int e = ebase + row;
-        int c0 = 0, c1 = 0;
+        int c0 = 0, c1 = 0, s0 = 0, s1 = 0;
         if (e < E) {
-            c0 = link_chunk_ptr[e];
-            c1 = link_chunk_ptr[e + 1];
+            c0 = link_slot_ptr[e];
+            c1 = link_slot_ptr[e + 1];
+            s0 = link_sslot_ptr[e];
+            s1 = link_sslot_ptr[e + 1];
         }
-        const double reach = row_partial_sum(c0, c1, l, partial);
+        const double reach = row_partial_sum(c0, c1, l, partial) + row_partial_sum(s0, s1, l, partial);
         if (e < E) m = fmax(m, reach * invcap[e]);
     }
     return m;
