@@ -189,6 +189,12 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     d.rev_pairs = static_cast<int64_t>(h.rev_pair.size() / 2);
     d.n_records = h.n_records;
     d.rec_stride = h.rec_stride;
+    d.rec_max_links = h.rec_max_links;
+    d.rec_lanes = 0;
+    if (const char *env = std::getenv("NIMBLE_TUNE_RECORD_LANES")) {
+        const int v = std::atoi(env);
+        if (v == 1 || v == 2 || v == 4 || v == 8 || v == 16 || v == 32 || v == 64) d.rec_lanes = v;
+    }
     if (std::getenv("NIMBLE_TUNE_NO_RECORDS")) d.n_records = 0;
     d.pmax = h.pmax;
     d.lmax = h.lmax;

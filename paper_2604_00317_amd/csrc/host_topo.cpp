@@ -324,6 +324,7 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
 
     // ---- forward records ------------------------------------------------------------------
     t.n_records = 0;
+    t.rec_max_links = 0;
     t.records.clear();
     t.rec_stride = t.lmax;
     const bool shape_ok = t.lmax <= kRecMaxStride &&
@@ -387,6 +388,22 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                 break;
             }
             const int32_t nk = k - k0, nl = static_cast<int32_t>(links.size());
+            // the link table in ascending id order: neighbouring lanes then gather neighbouring
+            // prices (fewer cache lines per gather)
+            {
+                std::vector<int32_t> order(nl), rank(nl);
+                for (int32_t i = 0; i < nl; ++i) order[i] = i;
+                std::sort(order.begin(), order.end(),
+                          [&](int32_t x, int32_t y) { return links[x] < links[y]; });
+                std::vector<int32_t> sorted(nl);
+                for (int32_t i = 0; i < nl; ++i) {
+                    sorted[i] = links[order[i]];
+                    rank[order[i]] = i;
+                }
+                links.swap(sorted);
+                for (auto &v : loc16)
+                    if (v != 0xFFFFu) v = static_cast<uint16_t>(rank[v]);
+            }
             for (auto &v : loc16)
                 if (v == 0xFFFFu) v = static_cast<uint16_t>(nl);     // the +0.0 price slot
             t.records.resize(static_cast<size_t>(t.n_records + 1) * kRecBytes, 0);
@@ -404,8 +421,16 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
             std::memcpy(r + kRecHeader, links.data(), 4 * static_cast<size_t>(nl));
             std::memcpy(r + off_sig, t.sigma.data() + k0, 4 * static_cast<size_t>(nk));
             std::memcpy(r + off_cp, cp16.data(), 2 * cp16.size());
-            std::memcpy(r + off_loc, loc16.data(), 2 * loc16.size());
+            // step-major: index i of every path, then index i+1, ... so that the lanes of a
+            // wave (consecutive paths) read consecutive 16-bit words
+            {
+                std::vector<uint16_t> soa(loc16.size());
+                for (int32_t p = 0; p < np; ++p)
+                    for (int32_t i = 0; i < S; ++i) soa[static_cast<size_t>(i) * np + p] = loc16[static_cast<size_t>(p) * S + i];
+                std::memcpy(r + off_loc, soa.data(), 2 * soa.size());
+            }
             t.n_records += 1;
+            if (nl > t.rec_max_links) t.rec_max_links = nl;
         }
         if (!ok) {
             t.n_records = 0;
@@ -496,7 +521,7 @@ extern "C" nimble_status_t nimble_host_records_roundtrip(int32_t n_links, int32_
             for (int32_t p = cp16[c]; p < cp16[c + 1]; ++p) {
                 path_record[p0 + p] = ri;
                 for (int32_t i = 0; i < t.rec_stride; ++i) {
-                    const int32_t li = loc16[p * t.rec_stride + i];
+                    const int32_t li = loc16[i * np + p];
                     if (li == nl) continue;
                     if (li > nl) return NIMBLE_ERR_INVALID;
                     links_out[w++] = links[li];

@@ -63,7 +63,7 @@ constexpr int32_t kSinglesPerLane = 8;        // a single-pair chunk holds 16 * 
 //   24  int32 links[n_links]
 //   off_sig  int32 sigma[nk]      second numbering of the commodity (-1: none)
 //   off_cp   uint16 cp16[nk+1]    first candidate of commodity i, relative to p0
-//   off_loc  uint16 loc16[np*stride]
+//   off_loc  uint16 loc16[stride][np]   (index i of every path, then index i+1, ...)
 constexpr int32_t kRecBytes = 4096;
 constexpr int32_t kRecHeader = 24;
 constexpr int32_t kRecMaxLinks = 255;     // link table entries; slot n_links holds +0.0
@@ -104,6 +104,7 @@ struct HostTopo {
     // kRecMaxStride links, padding above 1.5x, or a commodity that alone overflows a record)
     int32_t rec_stride = 0;              // indices per candidate = lmax
     int32_t n_records = 0;
+    int32_t rec_max_links = 0;           // largest link table of any record
     std::vector<uint8_t> records;        // [n_records * kRecBytes]
 };
 

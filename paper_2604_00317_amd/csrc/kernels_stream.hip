@@ -60,22 +60,30 @@ __global__ __launch_bounds__(kBlock) void k_argmin(int K, const int32_t *__restr
 // lanes per commodity add S prices per candidate from LDS in CSR order -- padding slots read
 // +0.0 -- and reduce (cost, index) across the group.  The sums are the same IEEE operations in
 // the same order as in the untiled kernel.
+constexpr int kRecWaves = 4;     // records (waves) per workgroup
+
 template <int L, int S, bool MAXC>
-__global__ __launch_bounds__(kWave) void k_argmin_rec(int n_records,
+__global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records, int lds_per_wave,
                                                       const uint8_t *__restrict__ records,
                                                       const double *__restrict__ price,
                                                       uint8_t *__restrict__ choice,
                                                       uint32_t *__restrict__ count,
                                                       uint8_t *__restrict__ choice2)
 {
-    __shared__ __align__(16) uint8_t s_rec[kRecBytes];
-    __shared__ double s_price[kRecMaxLinks + 1];
+    // dynamic LDS: the record (kRecBytes) followed by the price table, sized by the launcher
+    // for the largest link table of the topology
+    extern __shared__ __align__(16) uint8_t s_all[];
+    uint8_t *s_rec = s_all + (threadIdx.x >> 6) * lds_per_wave;     // this wave's slice
+    double *s_price = reinterpret_cast<double *>(s_rec + kRecBytes);
     constexpr int kGroups = kWave / L;
-    const int lane = threadIdx.x;
+    const int lane = threadIdx.x & (kWave - 1);
     const int g = lane / L;
     const int j = lane % L;
-    const int rec = blockIdx.x;
-    if (rec >= n_records) return;
+    // waves past the last record work on it again (idempotent up to the count, which they
+    // skip) so that every wave reaches the workgroup barriers
+    const int rec_raw = blockIdx.x * kRecWaves + (threadIdx.x >> 6);
+    const bool live = rec_raw < n_records;
+    const int rec = live ? rec_raw : n_records - 1;
     {
         const u32x4 *src = reinterpret_cast<const u32x4 *>(records + size_t(rec) * kRecBytes);
         u32x4 v[4];
@@ -89,35 +97,47 @@ __global__ __launch_bounds__(kWave) void k_argmin_rec(int n_records,
     const int k0 = *reinterpret_cast<const int32_t *>(s_rec);
     const int p0 = *reinterpret_cast<const int32_t *>(s_rec + 4);
     const uint16_t *h16 = reinterpret_cast<const uint16_t *>(s_rec + 8);
-    const int nk = h16[0], nl = h16[2];
+    const int nk = h16[0], np_rec = h16[1], nl = h16[2];
     const int32_t *links = reinterpret_cast<const int32_t *>(s_rec + kRecHeader);
     const uint16_t *cp16 = reinterpret_cast<const uint16_t *>(s_rec + h16[3]);
     const uint16_t *loc16 = reinterpret_cast<const uint16_t *>(s_rec + h16[4]);
     const int32_t *sig = reinterpret_cast<const int32_t *>(s_rec + h16[5]);
+#if defined(NIMBLE_EXP_ARGMIN) && NIMBLE_EXP_ARGMIN == 3
+    for (int i = lane; i < nl; i += kWave) s_price[i] = 1.0 + links[i];   // experiment: no gather
+#else
     for (int i = lane; i < nl; i += kWave) s_price[i] = price[links[i]];
+#endif
     if (lane == 0) s_price[nl] = 0.0;
     __syncthreads();
+#if defined(NIMBLE_EXP_ARGMIN) && NIMBLE_EXP_ARGMIN == 1
+    const int rounds = 0;       // experiment: staging only
+#elif defined(NIMBLE_EXP_ARGMIN) && NIMBLE_EXP_ARGMIN == 2
+    const int rounds = 1;       // experiment: one round
+#else
     const int rounds = (nk + kGroups - 1) / kGroups;
+#endif
     for (int r = 0; r < rounds; ++r) {            // wave-uniform: all lanes reach the reduction
         const int c = r * kGroups + g;
         double best = __builtin_inf();
         int bj = 0x7FFFFFFF;
         int p_lo = 0;
-        bool valid = false;
         if (c < nk) {
             p_lo = cp16[c];
             const int np = cp16[c + 1] - p_lo;
-            valid = j < np;
-            if (valid) bj = j;
+            if (j < np) bj = j;
             for (int jj = j; jj < np; jj += L) {
-                const uint16_t *lp = loc16 + (p_lo + jj) * S;
+                const uint16_t *lp = loc16 + (p_lo + jj);
                 int idx[S];
 #pragma unroll
-                for (int i = 0; i < S; ++i) idx[i] = lp[i];
+                for (int i = 0; i < S; ++i) idx[i] = lp[i * np_rec];
                 double cst = 0.0;
 #pragma unroll
                 for (int i = 0; i < S; ++i) {
+#if defined(NIMBLE_EXP_ARGMIN) && NIMBLE_EXP_ARGMIN == 4
+                    const double pe = static_cast<double>(idx[i]);
+#else
                     const double pe = s_price[idx[i]];
+#endif
                     if constexpr (MAXC) cst = (pe > cst) ? pe : cst;
                     else cst = cst + pe;
                 }
@@ -127,12 +147,8 @@ __global__ __launch_bounds__(kWave) void k_argmin_rec(int n_records,
                 }
             }
         }
-        if constexpr (L < kWave) {
-            bj = group_argmin_ballot<L>(best, valid);     // np <= pmax <= L: one per lane
-        } else {
-            group_argmin<L>(best, bj);
-        }
-        if (c < nk && j == 0) {
+        bj = group_argmin_two_pass<L>(best, bj);
+        if (live && c < nk && j == 0) {
             choice[k0 + c] = static_cast<uint8_t>(bj);
             const int sg = sig[c];
             if (sg >= 0) choice2[sg] = static_cast<uint8_t>(bj);   // copy in sigma order
@@ -236,10 +252,13 @@ template <int L, bool MAXC>
 void launch_argmin_lmax(const DeviceTopo &t, int grid, hipStream_t s)
 {
     if (t.n_records > 0) {
+        const int rec_lds = (kRecBytes + 8 * (t.rec_max_links + 1) + 15) & ~15;
 #define NIMBLE_REC_LAUNCH(SS)                                                                  \
     case SS:                                                                                   \
-        hipLaunchKernelGGL((k_argmin_rec<L, SS, MAXC>), dim3(t.n_records), dim3(kWave), 0, s,  \
-                           t.n_records, t.records, t.price, t.choice, t.count, t.choice2);     \
+        hipLaunchKernelGGL((k_argmin_rec<L, SS, MAXC>),                                        \
+                           dim3((t.n_records + kRecWaves - 1) / kRecWaves),                    \
+                           dim3(kWave * kRecWaves), kRecWaves * rec_lds, s, t.n_records,       \
+                           rec_lds, t.records, t.price, t.choice, t.count, t.choice2);         \
         return;
         switch (t.rec_stride) {
             NIMBLE_REC_LAUNCH(1)
@@ -266,7 +285,17 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, hipStream_t s)
 template <bool MAXC>
 void launch_argmin_l(const DeviceTopo &t, hipStream_t s)
 {
-    const int L = lanes_per_commodity(t.pmax);
+    // untiled kernel: one candidate per lane; record kernel: as many commodities side by side
+    // as a record typically holds, each lane scanning several candidates
+    int L = lanes_per_commodity(t.pmax);
+    if (t.n_records > 0) {
+        const int per_rec = (t.K + t.n_records - 1) / t.n_records;     // average, rounded up
+        int groups = 1;
+        while (groups < per_rec && groups < kWave) groups <<= 1;
+        const int l_rec = kWave / groups;
+        if (l_rec < L) L = l_rec;
+        if (t.rec_lanes > 0) L = t.rec_lanes;
+    }
     const int grid = blocks_for(static_cast<int64_t>(t.K) * L, kBlock, 1 << 20);
     switch (L) {
     case 1: launch_argmin_lmax<1, MAXC>(t, grid, s); break;

@@ -75,26 +75,38 @@ __device__ __forceinline__ void group_argmin(double &c, int &j)
     if constexpr (L > 32) argmin_stage<32>(c, j);
 }
 
-// Argmin over aligned groups of L < 64 lanes when every lane holds at most one candidate and
-// the candidate index equals the lane's position in its group: min-reduce the costs, then the
-// lowest lane whose cost equals the minimum wins (the tie rule "lowest index").  `valid` marks
-// lanes that hold a candidate; a group whose costs are all +inf resolves to its first lane.
-// Returns the winning position in every lane of the group.
-template <int L>
-__device__ __forceinline__ int group_argmin_ballot(double c, bool valid)
+// Minimum of two doubles without the NaN canonicalisation the C library semantics would add
+// (costs are never NaN here).
+__device__ __forceinline__ double fast_min_f64(double a, double b)
 {
-    static_assert(L < 64, "one candidate per lane only");
+    double r;
+    asm("v_min_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
+// Argmin over aligned groups of L lanes, every lane holding its own best (cost, index) with
+// index = 0x7FFFFFFF when it has no candidate: the costs are min-reduced, then the indices of
+// the lanes whose cost equals the minimum are min-reduced, which is the tie rule "lowest
+// index".  A group whose costs are all +inf resolves to its lowest candidate index.  Returns
+// the winning index in every lane of the group.
+template <int L>
+__device__ __forceinline__ int group_argmin_two_pass(double c, int j)
+{
     double m = c;
-    if constexpr (L > 1) m = fmin(m, partner_f64<1>(m));
-    if constexpr (L > 2) m = fmin(m, partner_f64<2>(m));
-    if constexpr (L > 4) m = fmin(m, partner_f64<4>(m));
-    if constexpr (L > 8) m = fmin(m, partner_f64<8>(m));
-    if constexpr (L > 16) m = fmin(m, partner_f64<16>(m));
-    const unsigned long long win = __ballot(valid && c == m);
-    const int lane = threadIdx.x & (kWave - 1);
-    const unsigned int mine =
-        static_cast<unsigned int>(win >> (lane & ~(L - 1))) & ((L == 32) ? 0xFFFFFFFFu : ((1u << L) - 1u));
-    return __ffs(mine) - 1;
+    if constexpr (L > 1) m = fast_min_f64(m, partner_f64<1>(m));
+    if constexpr (L > 2) m = fast_min_f64(m, partner_f64<2>(m));
+    if constexpr (L > 4) m = fast_min_f64(m, partner_f64<4>(m));
+    if constexpr (L > 8) m = fast_min_f64(m, partner_f64<8>(m));
+    if constexpr (L > 16) m = fast_min_f64(m, partner_f64<16>(m));
+    if constexpr (L > 32) m = fast_min_f64(m, partner_f64<32>(m));
+    int t = (c == m) ? j : 0x7FFFFFFF;
+    if constexpr (L > 1) t = min(t, partner_i32<1>(t));
+    if constexpr (L > 2) t = min(t, partner_i32<2>(t));
+    if constexpr (L > 4) t = min(t, partner_i32<4>(t));
+    if constexpr (L > 8) t = min(t, partner_i32<8>(t));
+    if constexpr (L > 16) t = min(t, partner_i32<16>(t));
+    if constexpr (L > 32) t = min(t, partner_i32<32>(t));
+    return t;
 }
 
 // Sum over the 64 lanes in a fixed butterfly order (the same tree on every run).
