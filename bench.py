@@ -5,8 +5,9 @@ A step is one complete plan (prologue, all Jacobi MWU iterations, epilogue) of t
 benchmark configuration -- 64 modeled nodes x 8 GPUs, 261 632 commodities, 8.3 M candidate
 paths, 39.3 M path-link incidences, 1000 iterations -- with topology and traffic resident in
 HBM before the timed region.  Prints one JSON line: MWU iterations/s (value), plans/s, the
-roofline of the dominant kernel from HIP-event timing, and the CPU oracle timed on the host
-cores on a bounded sample of the same workload.
+roofline of the dominant kernel from HIP-event timing, the CPU oracle timed on the host cores
+on a bounded sample of the same workload, and (key "also") the throughput of the 16-node and
+the batched configuration.
 """
 from __future__ import annotations
 
@@ -23,16 +24,21 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+REGIME_NAMES = {1: "resident", 2: "stream", 3: "persistent"}
+PHASES = ["argmin", "load_reduce", "update"]
 
 
-def phase_bytes(topo_np, lib_topo):
+def phase_bytes(lib_topo):
     """Stored bytes each streaming-regime kernel has to move per launch, as the library lays
-    the topology out (16-bit tile-local link indices and path offsets, 8-byte reverse pairs)."""
-    return dict(argmin=lib_topo.phase_bytes(0), load_reduce=lib_topo.phase_bytes(1),
-                update=lib_topo.phase_bytes(2), total=lib_topo.bytes_per_iter)
+    the topology out (4 KiB forward records with 16-bit link indices, 36-byte reverse octets)."""
+    d = {name: lib_topo.phase_bytes(i) for i, name in enumerate(PHASES)}
+    d["total"] = lib_topo.bytes_per_iter
+    return d
 
 
 def time_phase(B, torch, h, phase, reps, d_traffic):
+    """Average duration of `reps` back-to-back launches of one phase, HIP events on the stream
+    the kernels run on (torch's current stream)."""
     start = torch.cuda.Event(enable_timing=True)
     stop = torch.cuda.Event(enable_timing=True)
     B.nimble_debug_run_phase(h, phase, 3, d_traffic)
@@ -44,20 +50,86 @@ def time_phase(B, torch, h, phase, reps, d_traffic):
     return start.elapsed_time(stop) * 1e-3 / reps
 
 
+def read_traffic(kernel, workload):
+    """HBM bytes per launch of `kernel` measured with rocprofv3 counters, from the committed
+    summary profiles/hbm_traffic.txt (lines: workload kernel fetch_bytes write_bytes)."""
+    path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        parts = line.split()
+        if len(parts) >= 4 and not line.startswith("#") and parts[0] == workload and \
+                parts[1] == kernel:
+            return float(parts[2]) + float(parts[3])
+    return None
+
+
+def run_config(B, W, torch, cfg, regime, steps, warmup, iters_override=0, batch_size=4096,
+               copy_calib=0):
+    dev = "cuda:0"
+    t_gen = time.perf_counter()
+    w = W.make_config(cfg, batch=batch_size if cfg == 2 else None)
+    topo = w.topo
+    if iters_override > 0:
+        w.iters = iters_override
+    t_gen = time.perf_counter() - t_gen
+    t_create = time.perf_counter()
+    h = B.nimble_topo_create(*topo.csr())
+    t_create = time.perf_counter() - t_create
+    B.nimble_topo_set_regime(h, regime)
+    batch = max(w.batch, 1)
+    d_traffic = torch.as_tensor(np.ascontiguousarray(w.traffic).reshape(-1)).to(dev)
+    d_splits = torch.empty(batch * topo.n_paths, dtype=torch.float64, device=dev)
+    d_lambda = torch.empty(batch, dtype=torch.float64, device=dev)
+
+    def step():
+        if w.batch:
+            B.nimble_plan_solve_batch(h, batch, d_traffic, w.eps, w.iters, d_splits, d_lambda)
+        else:
+            B.nimble_plan_solve(h, d_traffic, w.eps, w.iters, d_splits, d_lambda)
+
+    if copy_calib > 0:      # plain device copies of 1 GiB: calibration of the HBM counters
+        src = torch.empty(1 << 27, dtype=torch.float64, device=dev).fill_(1.0)
+        dst = torch.empty_like(src)
+        for _ in range(copy_calib):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0 = torch.cuda.Event(enable_timing=True)
+    ev1 = torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for _ in range(steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    return dict(w=w, topo=topo, h=h, batch=batch, d_traffic=d_traffic, d_splits=d_splits,
+                d_lambda=d_lambda, elapsed=elapsed, event_s=ev0.elapsed_time(ev1) * 1e-3,
+                regime=h.regime, t_gen=t_gen, t_create=t_create)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=5)
     ap.add_argument("--warmup", type=int, default=1)
     ap.add_argument("--config", type=int, default=4, help="benchmark configuration 0..4")
-    ap.add_argument("--regime", type=int, default=0, help="0 auto, 1 resident, 2 stream, 3 persistent")
+    ap.add_argument("--regime", type=int, default=0,
+                    help="0 auto, 1 resident, 2 stream, 3 persistent")
     ap.add_argument("--cpu-iters", type=int, default=-1,
-                    help="oracle iterations for the CPU baseline (-1: sized to ~10-30 s, 0: skip)")
+                    help="oracle iterations for the CPU baseline (-1: sized to ~15 s, 0: skip)")
     ap.add_argument("--batch", type=int, default=4096)
     ap.add_argument("--iters", type=int, default=0,
                     help="override the configuration's iteration count (profiling runs only)")
     ap.add_argument("--copy-calib", type=int, default=0,
                     help="also run N plain device copies of 1 GiB (counter calibration)")
+    ap.add_argument("--no-also", action="store_true",
+                    help="skip the extra configurations reported under 'also'")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the planner models the whole "
@@ -72,79 +144,38 @@ def main() -> int:
     from paper_2604_00317_amd import workloads as W
     B.load_library(build_if_missing=True)
 
-    t_gen = time.perf_counter()
-    w = W.make_config(args.config, batch=args.batch if args.config == 2 else None)
-    topo = w.topo
-    if args.iters > 0:
-        w.iters = args.iters
-    t_gen = time.perf_counter() - t_gen
-    dev = "cuda:0"
-    t_create = time.perf_counter()
-    h = B.nimble_topo_create(*topo.csr())
-    t_create = time.perf_counter() - t_create
-    B.nimble_topo_set_regime(h, args.regime)
-
-    batch = max(w.batch, 1)
-    d_traffic = torch.as_tensor(np.ascontiguousarray(w.traffic).reshape(-1)).to(dev)
-    d_splits = torch.empty(batch * topo.n_paths, dtype=torch.float64, device=dev)
-    d_lambda = torch.empty(batch, dtype=torch.float64, device=dev)
-
-    def step():
-        if w.batch:
-            B.nimble_plan_solve_batch(h, batch, d_traffic, w.eps, w.iters, d_splits, d_lambda)
-        else:
-            B.nimble_plan_solve(h, d_traffic, w.eps, w.iters, d_splits, d_lambda)
-
-    if args.copy_calib > 0:
-        src = torch.empty(1 << 27, dtype=torch.float64, device=dev).fill_(1.0)
-        dst = torch.empty_like(src)
-        for _ in range(args.copy_calib):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    ev0 = torch.cuda.Event(enable_timing=True)
-    ev1 = torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record()
-    for _ in range(args.steps):
-        step()
-    ev1.record()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ev_ms = ev0.elapsed_time(ev1)
-    regime = h.regime
-
+    r = run_config(B, W, torch, args.config, args.regime, args.steps, args.warmup, args.iters,
+                   args.batch, args.copy_calib)
+    w, topo, h, batch = r["w"], r["topo"], r["h"], r["batch"]
+    elapsed, regime = r["elapsed"], r["regime"]
     ms_per_step = elapsed * 1e3 / args.steps
     iters_per_s = w.iters * batch * args.steps / elapsed
     plans_per_s = batch * args.steps / elapsed
-    lam = d_lambda.cpu().numpy()
+    lam = r["d_lambda"].cpu().numpy()
+    workload = f"configs[{args.config}] {w.name}"
 
     # ---- roofline of the dominant kernel ------------------------------------------------
-    bytes_ = phase_bytes(topo, h)
-    roofline = None
+    bytes_ = phase_bytes(h)
     kernels = {}
     if regime == B.NIMBLE_REGIME_STREAM:
-        names = ["argmin", "load_reduce", "update"]
-        for ph, name in enumerate(names):
-            sec = time_phase(B, torch, h, ph, 200, d_traffic)
+        for ph, name in enumerate(PHASES):
+            sec = time_phase(B, torch, h, ph, 200, r["d_traffic"])
             kernels[name] = dict(avg_us=sec * 1e6, bytes=bytes_[name],
                                  gbs=bytes_[name] / sec / 1e9)
-        dom = max(names, key=lambda n: kernels[n]["avg_us"])
+        dom = max(PHASES, key=lambda n: kernels[n]["avg_us"])
         roofline = dict(bound="hbm", kernel=dom, achieved=kernels[dom]["gbs"],
                         peak=HBM_PEAK_GBS, unit="GB/s",
-                        frac=kernels[dom]["gbs"] / HBM_PEAK_GBS, traffic=None,
+                        frac=kernels[dom]["gbs"] / HBM_PEAK_GBS,
+                        traffic=read_traffic(dom, w.name),
                         whole_iteration_gbs=bytes_["total"] * w.iters * args.steps / elapsed / 1e9)
     else:
         # one kernel per step: its duration is the step time measured with HIP events
-        sec = ev_ms * 1e-3 / args.steps
+        sec = r["event_s"] / args.steps
         total = bytes_["total"] * w.iters * batch
-        roofline = dict(bound="hbm", kernel="resident" if regime == 1 else "persistent",
-                        achieved=total / sec / 1e9, peak=HBM_PEAK_GBS, unit="GB/s",
-                        frac=total / sec / 1e9 / HBM_PEAK_GBS, traffic=None)
+        name = REGIME_NAMES.get(regime, "auto")
+        roofline = dict(bound="hbm", kernel=name, achieved=total / sec / 1e9, peak=HBM_PEAK_GBS,
+                        unit="GB/s", frac=total / sec / 1e9 / HBM_PEAK_GBS,
+                        traffic=read_traffic(name, w.name))
 
     # ---- CPU baseline: the oracle on a bounded sample -------------------------------------
     cpu = None
@@ -153,6 +184,7 @@ def main() -> int:
         cores = oracle.max_threads()
         if w.batch:
             n_plans = 64 if args.cpu_iters < 0 else max(1, args.cpu_iters)
+            n_plans = min(n_plans, batch)
             t1 = time.perf_counter()
             worst = 0.0
             for b in range(n_plans):
@@ -166,42 +198,59 @@ def main() -> int:
         else:
             n_it = args.cpu_iters
             if n_it < 0:
+                oracle.solve(*topo.csr(), w.traffic, w.eps, 1)          # page everything in
                 t1 = time.perf_counter()
-                oracle.solve(*topo.csr(), w.traffic, w.eps, 2)
-                per_it = (time.perf_counter() - t1) / 2
+                oracle.solve(*topo.csr(), w.traffic, w.eps, 4)
+                per_it = (time.perf_counter() - t1) / 4
                 n_it = int(max(4, min(w.iters, 15.0 / max(per_it, 1e-6))))
             t1 = time.perf_counter()
             ref = oracle.solve(*topo.csr(), w.traffic, w.eps, n_it)
             dt = time.perf_counter() - t1
             # parity of the same shortened run on the GPU
-            B.nimble_plan_solve(h, d_traffic, w.eps, n_it, d_splits, d_lambda)
+            B.nimble_plan_solve(h, r["d_traffic"], w.eps, n_it, r["d_splits"], r["d_lambda"])
             torch.cuda.synchronize()
-            g_s = d_splits.cpu().numpy()
-            g_l = float(d_lambda.item())
+            g_s = r["d_splits"].cpu().numpy()
+            g_l = float(r["d_lambda"].item())
             cpu = dict(value=n_it / dt, unit="iterations/s", cores=cores, kind="oracle",
                        plans_per_s=1.0 / (dt * w.iters / n_it),
                        sample=f"first {n_it} of {w.iters} iterations, all commodities",
                        max_abs_diff_splits=float(np.abs(g_s - ref["splits"]).max()),
                        max_rel_diff_lambda=abs(g_l - ref["lam"]) / max(ref["lam"], 1e-300))
+    setup = {"generate": r["t_gen"], "topo_create": r["t_create"]}
+    h.close()
+    del r
+
+    # ---- the other throughput figures the metric names -------------------------------------
+    also = {}
+    if not args.no_also and args.config == 4 and args.iters == 0:
+        for cfg, steps in ((3, 5), (2, 5)):
+            q = run_config(B, W, torch, cfg, 0, steps, 1, 0, args.batch)
+            also[f"configs[{cfg}] {q['w'].name}"] = dict(
+                iterations_per_s=q["w"].iters * q["batch"] * steps / q["elapsed"],
+                plans_per_s=q["batch"] * steps / q["elapsed"],
+                ms_per_step=q["elapsed"] * 1e3 / steps,
+                regime=REGIME_NAMES.get(q["regime"], "auto"), batch=q["batch"],
+                iters=q["w"].iters)
+            q["h"].close()
+            del q
 
     out = {
         "metric": "mwu_iterations_per_s", "value": iters_per_s, "unit": "iterations/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f64",
         "data": "synthetic",
-        "config": {"workload": f"configs[{args.config}] {w.name}", "commodities": topo.n_comm,
-                   "paths": topo.n_paths, "incidences": topo.nnz, "links": topo.n_links,
-                   "eps": w.eps, "iters": w.iters, "batch": batch,
-                   "regime": {1: "resident", 2: "stream", 3: "persistent"}.get(regime, "auto")},
+        "config": {"workload": workload, "commodities": topo.n_comm, "paths": topo.n_paths,
+                   "incidences": topo.nnz, "links": topo.n_links, "eps": w.eps, "iters": w.iters,
+                   "batch": batch, "regime": REGIME_NAMES.get(regime, "auto")},
         "plans_per_s": plans_per_s,
         "lambda": float(lam[0]),
         "bytes_per_iter": bytes_["total"],
         "roofline": roofline,
         "kernels": kernels,
         "cpu_baseline": cpu,
-        "setup_s": {"generate": t_gen, "topo_create": t_create},
+        "also": also,
+        "setup_s": setup,
     }
-    h.close()
     print(json.dumps(out))
     return 0
 

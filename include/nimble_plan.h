@@ -175,6 +175,19 @@ nimble_status_t nimble_host_build_reverse(int32_t n_links, int32_t n_comm,
                                           int32_t *rev_comm, int32_t *rev_path);
 
 /*
+ * Host-only helper (no device call): the same reverse CSR, but decoded from the streaming
+ * layout the link-load kernel walks (flat octets under the two commodity numberings, slot
+ * flags, chunked single pairs), with every row sorted by (commodity, path).  Must equal the
+ * output of nimble_host_build_reverse.
+ */
+nimble_status_t nimble_host_build_reverse_streaming(int32_t n_links, int32_t n_comm,
+                                                    const int32_t *comm_path_ptr,
+                                                    int32_t n_paths,
+                                                    const int32_t *path_link_ptr,
+                                                    const int32_t *path_links, int32_t *rev_ptr,
+                                                    int32_t *rev_comm, int32_t *rev_path);
+
+/*
  * Host-only helper (no device call): repacks the forward CSR into the self-contained 4 KiB
  * records the path-cost kernel streams (a run of consecutive commodities, the record's own
  * link table, and a fixed number of 16-bit link-table indices per candidate) exactly as

@@ -28,6 +28,7 @@ EXPORTS = [
     "nimble_topo_set_regime", "nimble_topo_regime", "nimble_debug_run_phase",
     "nimble_host_build_reverse", "nimble_debug_set_spin_limit", "nimble_topo_phase_bytes",
     "nimble_host_records_roundtrip", "nimble_host_layout_stats",
+    "nimble_host_build_reverse_streaming",
 ]
 
 _lib = None
@@ -81,8 +82,9 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.nimble_host_records_roundtrip.argtypes = [i32, i32, vp, i32, vp, vp, vp, vp, vp]
     lib.nimble_host_layout_stats.restype = ctypes.c_int
     lib.nimble_host_layout_stats.argtypes = [i32, i32, vp, i32, vp, vp, vp]
-    lib.nimble_host_build_reverse.restype = ctypes.c_int
-    lib.nimble_host_build_reverse.argtypes = [i32, i32, vp, i32, vp, vp, vp, vp, vp]
+    for name in ("nimble_host_build_reverse", "nimble_host_build_reverse_streaming"):
+        getattr(lib, name).restype = ctypes.c_int
+        getattr(lib, name).argtypes = [i32, i32, vp, i32, vp, vp, vp, vp, vp]
     _lib = lib
     return lib
 
@@ -219,8 +221,9 @@ def nimble_debug_set_spin_limit(topo: Topo, polls: int) -> None:
 
 
 def nimble_host_build_reverse(n_links, n_comm, comm_path_ptr, n_paths, path_link_ptr,
-                              path_links):
-    """Host-only: the reverse link -> (commodity, path) CSR as the library builds it."""
+                              path_links, streaming: bool = False):
+    """Host-only: the reverse link -> (commodity, path) CSR as the library builds it; with
+    streaming=True decoded from the layout the link-load kernel walks."""
     cp = _host(comm_path_ptr, np.int32)
     lp = _host(path_link_ptr, np.int32)
     pl = _host(path_links, np.int32)
@@ -228,9 +231,10 @@ def nimble_host_build_reverse(n_links, n_comm, comm_path_ptr, n_paths, path_link
     rev_ptr = np.zeros(n_links + 1, dtype=np.int32)
     rev_comm = np.zeros(max(nnz, 1), dtype=np.int32)
     rev_path = np.zeros(max(nnz, 1), dtype=np.int32)
-    st = load_library().nimble_host_build_reverse(n_links, n_comm, _hp(cp), n_paths, _hp(lp),
-                                                  _hp(pl), _hp(rev_ptr), _hp(rev_comm),
-                                                  _hp(rev_path))
+    fn = (load_library().nimble_host_build_reverse_streaming if streaming
+          else load_library().nimble_host_build_reverse)
+    st = fn(n_links, n_comm, _hp(cp), n_paths, _hp(lp), _hp(pl), _hp(rev_ptr), _hp(rev_comm),
+            _hp(rev_path))
     if st != NIMBLE_OK:
         raise NimbleError(st, "invalid CSR")
     return rev_ptr, rev_comm[:nnz], rev_path[:nnz]

@@ -168,6 +168,10 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     nimble::HostTopo h;
     try {
         t = new nimble_topo();
+        if (const char *env = std::getenv("NIMBLE_TUNE_RECORD_COMM_CAP")) {
+            const int v = std::atoi(env);
+            if (v >= 1 && v <= nimble::kRecMaxComm) h.rec_comm_cap = v;
+        }
         nimble::build_host_topo(n_links, cap, n_comm, comm_path_ptr, n_paths, path_link_ptr,
                                 path_links, h);
     } catch (const std::bad_alloc &) {

@@ -347,7 +347,7 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
             cp16.assign(1, 0);
             loc16.clear();
             int32_t np = 0;
-            while (k < n_comm && k - k0 < kRecMaxComm) {
+            while (k < n_comm && k - k0 < t.rec_comm_cap) {
                 const int32_t pa = comm_path_ptr[k], pb = comm_path_ptr[k + 1];
                 // distinct links this commodity would add
                 int32_t add = 0;
@@ -555,5 +555,80 @@ extern "C" nimble_status_t nimble_host_layout_stats(int32_t n_links, int32_t n_c
     out[5] = t.n_slots;
     out[6] = t.n_records;
     out[7] = t.rec_stride;
+    return NIMBLE_OK;
+}
+
+extern "C" nimble_status_t nimble_host_build_reverse_streaming(int32_t n_links, int32_t n_comm,
+                                                               const int32_t *comm_path_ptr,
+                                                               int32_t n_paths,
+                                                               const int32_t *path_link_ptr,
+                                                               const int32_t *path_links,
+                                                               int32_t *rev_ptr,
+                                                               int32_t *rev_comm,
+                                                               int32_t *rev_path)
+{
+    std::string why;
+    nimble_status_t st = nimble::validate_csr(n_links, nullptr, n_comm, comm_path_ptr, n_paths,
+                                              path_link_ptr, path_links, why);
+    if (st != NIMBLE_OK) return st;
+    if (!rev_ptr || !rev_comm || !rev_path) return NIMBLE_ERR_INVALID;
+    std::vector<double> cap(n_links, 1.0);
+    nimble::HostTopo t;
+    nimble::build_host_topo(n_links, cap.data(), n_comm, comm_path_ptr, n_paths, path_link_ptr,
+                            path_links, t);
+    // decode the streaming layout the way the reduce kernel walks it: flat octets with slot
+    // flags (slot -> link through link_slot_ptr), sigma octets through the inverse numbering,
+    // and chunked single pairs (chunk slot -> link through link_sslot_ptr)
+    std::vector<int32_t> inv_sigma(static_cast<size_t>(t.sigma_size), -1);
+    for (int32_t k = 0; k < n_comm; ++k)
+        if (t.sigma[k] >= 0) inv_sigma[t.sigma[k]] = k;
+    std::vector<int32_t> slot_link(static_cast<size_t>(t.n_slots), -1);
+    for (int32_t e = 0; e < n_links; ++e) {
+        for (int32_t sl = t.link_slot_ptr[e]; sl < t.link_slot_ptr[e + 1]; ++sl) slot_link[sl] = e;
+        for (int32_t sl = t.link_sslot_ptr[e]; sl < t.link_sslot_ptr[e + 1]; ++sl) slot_link[sl] = e;
+    }
+    std::vector<std::vector<int64_t>> rows(n_links);      // (commodity << 8 | path) per link
+    const size_t n_flat = t.oct_base.size();
+    int32_t slot = -1;
+    for (size_t i = 0; i < n_flat; ++i) {
+        const uint32_t w = t.oct_base[i];
+        if (i % 64 == 0) slot = t.pass_first_slot[i / 64] - 1;
+        if (w & nimble::kOctNewSlot) ++slot;
+        const int32_t e = slot < t.n_slots ? slot_link[slot] : -1;
+        const int32_t base = static_cast<int32_t>(w & ~3u);
+        for (int32_t s8 = 0; s8 < 8; ++s8) {
+            const uint32_t m = t.oct_mask[8 * i + s8];
+            if (!m) continue;
+            if (e < 0) return NIMBLE_ERR_INVALID;          // a mask in a padding octet
+            const int32_t k = (w & nimble::kOctSigma) ? inv_sigma[base + s8] : base + s8;
+            if (k < 0 || k >= n_comm) return NIMBLE_ERR_INVALID;
+            for (int32_t j = 0; j < 32; ++j)
+                if (m & (1u << j)) rows[e].push_back((static_cast<int64_t>(k) << 8) | j);
+        }
+    }
+    for (size_t c = 0; c < t.schunk_begin.size(); ++c) {
+        const int32_t e = slot_link[t.schunk_slot[c]];
+        if (e < 0) return NIMBLE_ERR_INVALID;
+        for (int32_t i = t.schunk_begin[c]; i < t.schunk_end[c]; ++i) {
+            const uint32_t a = t.single_pair[2 * static_cast<size_t>(i)];
+            const uint32_t m = t.single_pair[2 * static_cast<size_t>(i) + 1];
+            const int32_t k = static_cast<int32_t>(a & nimble::kCommMask);
+            const int32_t window = static_cast<int32_t>((a >> nimble::kWindowShift) & 3u);
+            for (int32_t j = 0; j < 32; ++j)
+                if (m & (1u << j)) rows[e].push_back((static_cast<int64_t>(k) << 8) | (window * 32 + j));
+        }
+    }
+    int32_t w = 0;
+    for (int32_t e = 0; e < n_links; ++e) {
+        std::sort(rows[e].begin(), rows[e].end());
+        rev_ptr[e] = w;
+        for (int64_t v : rows[e]) {
+            if (w >= t.nnz) return NIMBLE_ERR_INVALID;
+            rev_comm[w] = static_cast<int32_t>(v >> 8);
+            rev_path[w] = static_cast<int32_t>(v & 255);
+            ++w;
+        }
+    }
+    rev_ptr[n_links] = w;
     return NIMBLE_OK;
 }

@@ -64,7 +64,10 @@ constexpr int32_t kSinglesPerLane = 8;        // a single-pair chunk holds 16 * 
 //   off_sig  int32 sigma[nk]      second numbering of the commodity (-1: none)
 //   off_cp   uint16 cp16[nk+1]    first candidate of commodity i, relative to p0
 //   off_loc  uint16 loc16[stride][np]   (index i of every path, then index i+1, ...)
-constexpr int32_t kRecBytes = 4096;
+#ifndef NIMBLE_REC_KB
+#define NIMBLE_REC_KB 4
+#endif
+constexpr int32_t kRecBytes = 1024 * NIMBLE_REC_KB;   // one 16-byte load per lane and KiB
 constexpr int32_t kRecHeader = 24;
 constexpr int32_t kRecMaxLinks = 255;     // link table entries; slot n_links holds +0.0
 constexpr int32_t kRecMaxStride = 8;      // longest path a record can hold
@@ -102,6 +105,7 @@ struct HostTopo {
     int32_t n_slots = 0;                 // octet slots + single-chunk slots
     // forward records (n_records = 0 when the topology does not fit them: a path longer than
     // kRecMaxStride links, padding above 1.5x, or a commodity that alone overflows a record)
+    int32_t rec_comm_cap = kRecMaxComm;  // most commodities put into one record
     int32_t rec_stride = 0;              // indices per candidate = lmax
     int32_t n_records = 0;
     int32_t rec_max_links = 0;           // largest link table of any record
@@ -114,7 +118,8 @@ nimble_status_t validate_csr(int32_t n_links, const double *cap, int32_t n_comm,
                              const int32_t *path_link_ptr, const int32_t *path_links,
                              std::string &why);
 
-// Builds everything in HostTopo from validated input.
+// Builds everything in HostTopo from validated input.  out.rec_comm_cap is read as an option
+// (default kRecMaxComm).
 void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                      const int32_t *comm_path_ptr, int32_t n_paths,
                      const int32_t *path_link_ptr, const int32_t *path_links,

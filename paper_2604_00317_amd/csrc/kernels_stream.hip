@@ -85,12 +85,14 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records, 
     const bool live = rec_raw < n_records;
     const int rec = live ? rec_raw : n_records - 1;
     {
+        // one 16-byte load per lane and KiB of record, all requested before any is stored
         const u32x4 *src = reinterpret_cast<const u32x4 *>(records + size_t(rec) * kRecBytes);
-        u32x4 v[4];
+        constexpr int kLoads = kRecBytes / 1024;
+        u32x4 v[kLoads];
 #pragma unroll
-        for (int it = 0; it < 4; ++it) v[it] = stream_load(src + it * kWave + lane);
+        for (int it = 0; it < kLoads; ++it) v[it] = stream_load(src + it * kWave + lane);
 #pragma unroll
-        for (int it = 0; it < 4; ++it)
+        for (int it = 0; it < kLoads; ++it)
             reinterpret_cast<u32x4 *>(s_rec)[it * kWave + lane] = v[it];
     }
     __syncthreads();
@@ -102,20 +104,10 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records, 
     const uint16_t *cp16 = reinterpret_cast<const uint16_t *>(s_rec + h16[3]);
     const uint16_t *loc16 = reinterpret_cast<const uint16_t *>(s_rec + h16[4]);
     const int32_t *sig = reinterpret_cast<const int32_t *>(s_rec + h16[5]);
-#if defined(NIMBLE_EXP_ARGMIN) && NIMBLE_EXP_ARGMIN == 3
-    for (int i = lane; i < nl; i += kWave) s_price[i] = 1.0 + links[i];   // experiment: no gather
-#else
     for (int i = lane; i < nl; i += kWave) s_price[i] = price[links[i]];
-#endif
     if (lane == 0) s_price[nl] = 0.0;
     __syncthreads();
-#if defined(NIMBLE_EXP_ARGMIN) && NIMBLE_EXP_ARGMIN == 1
-    const int rounds = 0;       // experiment: staging only
-#elif defined(NIMBLE_EXP_ARGMIN) && NIMBLE_EXP_ARGMIN == 2
-    const int rounds = 1;       // experiment: one round
-#else
     const int rounds = (nk + kGroups - 1) / kGroups;
-#endif
     for (int r = 0; r < rounds; ++r) {            // wave-uniform: all lanes reach the reduction
         const int c = r * kGroups + g;
         double best = __builtin_inf();
@@ -133,11 +125,7 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records, 
                 double cst = 0.0;
 #pragma unroll
                 for (int i = 0; i < S; ++i) {
-#if defined(NIMBLE_EXP_ARGMIN) && NIMBLE_EXP_ARGMIN == 4
-                    const double pe = static_cast<double>(idx[i]);
-#else
                     const double pe = s_price[idx[i]];
-#endif
                     if constexpr (MAXC) cst = (pe > cst) ? pe : cst;
                     else cst = cst + pe;
                 }
