@@ -336,7 +336,7 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
         std::vector<uint16_t> cp16, loc16;
         auto align4 = [](int32_t x) { return (x + 3) & ~3; };
         auto bytes_needed = [&](int32_t nl, int32_t nk, int32_t np) {
-            return kRecHeader + 4 * nl + 4 * nk + align4(2 * (nk + 1)) + 2 * np * S;
+            return kRecHeader + 4 * nl + 4 * nk + align4(2 * (nk + 1)) + np * S;
         };
         bool ok = true;
         int32_t k = 0;
@@ -424,10 +424,12 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
             // step-major: index i of every path, then index i+1, ... so that the lanes of a
             // wave (consecutive paths) read consecutive 16-bit words
             {
-                std::vector<uint16_t> soa(loc16.size());
+                std::vector<uint8_t> soa(loc16.size());
                 for (int32_t p = 0; p < np; ++p)
-                    for (int32_t i = 0; i < S; ++i) soa[static_cast<size_t>(i) * np + p] = loc16[static_cast<size_t>(p) * S + i];
-                std::memcpy(r + off_loc, soa.data(), 2 * soa.size());
+                    for (int32_t i = 0; i < S; ++i)
+                        soa[static_cast<size_t>(i) * np + p] =
+                            static_cast<uint8_t>(loc16[static_cast<size_t>(p) * S + i]);
+                std::memcpy(r + off_loc, soa.data(), soa.size());
             }
             t.n_records += 1;
             if (nl > t.rec_max_links) t.rec_max_links = nl;
@@ -514,7 +516,7 @@ extern "C" nimble_status_t nimble_host_records_roundtrip(int32_t n_links, int32_
         next_comm = k0 + nk;
         const int32_t *links = reinterpret_cast<const int32_t *>(r + nimble::kRecHeader);
         const uint16_t *cp16 = reinterpret_cast<const uint16_t *>(r + off_cp);
-        const uint16_t *loc16 = reinterpret_cast<const uint16_t *>(r + off_loc);
+        const uint8_t *loc16 = r + off_loc;
         if (cp16[nk] != np) return NIMBLE_ERR_INVALID;
         for (int32_t c = 0; c < nk; ++c) {
             if (p0 + cp16[c] != comm_path_ptr[k0 + c]) return NIMBLE_ERR_INVALID;

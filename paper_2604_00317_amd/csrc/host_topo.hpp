@@ -54,7 +54,7 @@ constexpr int32_t kSinglesPerLane = 8;        // a single-pair chunk holds 16 * 
 // run of consecutive commodities: a wave fetches one record with four 16-byte loads per lane
 // (no pointer chasing), finds in it the global ids of the record's distinct links (whose
 // prices it gathers into LDS), the first candidate of every commodity, and for every candidate
-// exactly `stride` 16-bit indices into the record's link table.  Paths shorter than the stride
+// exactly `stride` 8-bit indices into the record's link table.  Paths shorter than the stride
 // are padded with the index n_links, whose price slot holds +0.0 (neutral for sum and for max
 // of positive prices).  Layout, offsets in bytes from the start of the record:
 //   0   int32 k0        first commodity
@@ -63,13 +63,13 @@ constexpr int32_t kSinglesPerLane = 8;        // a single-pair chunk holds 16 * 
 //   24  int32 links[n_links]
 //   off_sig  int32 sigma[nk]      second numbering of the commodity (-1: none)
 //   off_cp   uint16 cp16[nk+1]    first candidate of commodity i, relative to p0
-//   off_loc  uint16 loc16[stride][np]   (index i of every path, then index i+1, ...)
+//   off_loc  uint8  loc8[stride][np]    (index i of every path, then index i+1, ...)
 #ifndef NIMBLE_REC_KB
 #define NIMBLE_REC_KB 4
 #endif
 constexpr int32_t kRecBytes = 1024 * NIMBLE_REC_KB;   // one 16-byte load per lane and KiB
 constexpr int32_t kRecHeader = 24;
-constexpr int32_t kRecMaxLinks = 255;     // link table entries; slot n_links holds +0.0
+constexpr int32_t kRecMaxLinks = 254;     // link table entries (8-bit indices); slot n_links holds +0.0
 constexpr int32_t kRecMaxStride = 8;      // longest path a record can hold
 constexpr int32_t kRecMaxComm = 64;
 

@@ -57,7 +57,7 @@ __global__ __launch_bounds__(kBlock) void k_argmin(int K, const int32_t *__restr
 // Record path-cost gather + argmin: one wave (a 64-thread workgroup) per 4 KiB record of the
 // forward CSR.  The wave copies its record into LDS with four 16-byte loads per lane, gathers
 // the prices of the record's link table (the only access that leaves the record), and then L
-// lanes per commodity add S prices per candidate from LDS in CSR order -- padding slots read
+// lanes per commodity add S prices per candidate (8-bit table indices) from LDS in CSR order -- padding slots read
 // +0.0 -- and reduce (cost, index) across the group.  The sums are the same IEEE operations in
 // the same order as in the untiled kernel.
 constexpr int kRecWaves = 4;     // records (waves) per workgroup
@@ -102,7 +102,7 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records, 
     const int nk = h16[0], np_rec = h16[1], nl = h16[2];
     const int32_t *links = reinterpret_cast<const int32_t *>(s_rec + kRecHeader);
     const uint16_t *cp16 = reinterpret_cast<const uint16_t *>(s_rec + h16[3]);
-    const uint16_t *loc16 = reinterpret_cast<const uint16_t *>(s_rec + h16[4]);
+    const uint8_t *loc8 = s_rec + h16[4];
     const int32_t *sig = reinterpret_cast<const int32_t *>(s_rec + h16[5]);
     for (int i = lane; i < nl; i += kWave) s_price[i] = price[links[i]];
     if (lane == 0) s_price[nl] = 0.0;
@@ -118,7 +118,7 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records, 
             const int np = cp16[c + 1] - p_lo;
             if (j < np) bj = j;
             for (int jj = j; jj < np; jj += L) {
-                const uint16_t *lp = loc16 + (p_lo + jj);
+                const uint8_t *lp = loc8 + (p_lo + jj);
                 int idx[S];
 #pragma unroll
                 for (int i = 0; i < S; ++i) idx[i] = lp[i * np_rec];

@@ -123,9 +123,9 @@ def test_forward_records_round_trip(cfg):
     # records are runs of whole commodities, in order
     assert np.all(np.diff(path_rec) >= 0) and path_rec[-1] == n_rec - 1
     assert np.array_equal(path_rec[t.comm_path_ptr[:-1]], path_rec[t.comm_path_ptr[1:] - 1])
-    # a 4 KiB record cannot hold more 16-bit indices than fit it
+    # a 4 KiB record cannot hold more 8-bit indices than fit it
     stride = int(np.diff(t.path_link_ptr).max())
-    assert np.bincount(path_rec).max() * stride * 2 <= 4096
+    assert np.bincount(path_rec).max() * stride <= 4096
 
 
 def test_forward_records_ragged_and_unfit():
@@ -140,8 +140,8 @@ def test_forward_records_ragged_and_unfit():
     _, _, n_rec = B.nimble_host_records_roundtrip(E, 1, [0, npth], npth,
                                                   np.arange(npth + 1) * ln, pl)
     assert n_rec == 0
-    # one commodity with 127 candidates of 8 links needs 2032 indices + its links: fits;
-    # with 300 distinct links it exceeds the 255-entry link table: no records
+    # one commodity with 127 candidates of 8 links over 300 distinct links exceeds the
+    # 254-entry link table of a record: no records
     E, npth, ln = 400, 127, 8
     pl = np.concatenate([rng.choice(E, size=ln, replace=False) for _ in range(npth)])
     _, _, n_rec = B.nimble_host_records_roundtrip(E, 1, [0, npth], npth,
