@@ -306,6 +306,18 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
         t.oct_base.assign(64, kOctNewSlot);
         t.oct_mask.assign(8 * 64, 0u);
     }
+    // masks lane-contiguous inside a pass: words 0..3 of the 64 octets, then words 4..7, so
+    // that each of the two 16-byte loads of a lane is part of one contiguous KiB
+    {
+        std::vector<uint32_t> tmp(t.oct_mask.size());
+        const size_t n_pass = t.oct_base.size() / 64;
+        for (size_t ps = 0; ps < n_pass; ++ps)
+            for (size_t ln = 0; ln < 64; ++ln)
+                for (size_t w8 = 0; w8 < 8; ++w8)
+                    tmp[ps * 512 + (w8 / 4) * 256 + ln * 4 + (w8 % 4)] =
+                        t.oct_mask[(ps * 64 + ln) * 8 + w8];
+        t.oct_mask.swap(tmp);
+    }
     // padding octets may each open a slot: reserve one slot per padding octet
     const int32_t pad_slots = 64;
     const int32_t single_slot0 = t.n_oct_slots + pad_slots;
@@ -599,7 +611,7 @@ extern "C" nimble_status_t nimble_host_build_reverse_streaming(int32_t n_links, 
         const int32_t e = slot < t.n_slots ? slot_link[slot] : -1;
         const int32_t base = static_cast<int32_t>(w & ~3u);
         for (int32_t s8 = 0; s8 < 8; ++s8) {
-            const uint32_t m = t.oct_mask[8 * i + s8];
+            const uint32_t m = t.oct_mask[(i / 64) * 512 + (s8 / 4) * 256 + (i % 64) * 4 + (s8 % 4)];
             if (!m) continue;
             if (e < 0) return NIMBLE_ERR_INVALID;          // a mask in a padding octet
             const int32_t k = (w & nimble::kOctSigma) ? inv_sigma[base + s8] : base + s8;

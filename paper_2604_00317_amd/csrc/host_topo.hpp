@@ -90,7 +90,8 @@ struct HostTopo {
     std::vector<int32_t> link_chunk_ptr; // [E+1]
     // streaming layout
     std::vector<uint32_t> oct_base;      // [n_oct_padded]: base id | flags, padded to 64
-    std::vector<uint32_t> oct_mask;      // [8 * n_oct_padded]
+    std::vector<uint32_t> oct_mask;      // [8 * n_oct_padded]; per pass: words 0..3 of its 64
+                                         // octets lane after lane, then words 4..7
     int64_t n_octets = 0;                // unpadded
     int64_t n_octets_sigma = 0;          // of which numbered by sigma
     std::vector<int32_t> pass_first_slot; // [n_oct_padded / 64]

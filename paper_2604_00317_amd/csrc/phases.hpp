@@ -255,9 +255,10 @@ __device__ __forceinline__ void reduce_flat_phase(
     {
         const size_t i = size_t(wave) * kWave + lane;
         bw = stream_load(oct_base + i);
-        const u32x4 *src = reinterpret_cast<const u32x4 *>(oct_mask + 8 * i);
+        // masks of a pass: words 0..3 of the 64 octets lane after lane, then words 4..7
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(oct_mask) + size_t(wave) * 128 + lane;
         m0 = stream_load(src);
-        m1 = stream_load(src + 1);
+        m1 = stream_load(src + 64);
     }
     for (int pass = wave; pass < n_passes; pass += n_waves) {      // wave-uniform
         const bool sig = (bw & kOctSigma) != 0u;
@@ -271,8 +272,8 @@ __device__ __forceinline__ void reduce_flat_phase(
         const int np = pass + n_waves < last ? pass + n_waves : last;
         const size_t ni = size_t(np) * kWave + lane;
         const uint32_t nbw = stream_load(oct_base + ni);
-        const u32x4 *nsrc = reinterpret_cast<const u32x4 *>(oct_mask + 8 * ni);
-        const u32x4 nm0 = stream_load(nsrc), nm1 = stream_load(nsrc + 1);
+        const u32x4 *nsrc = reinterpret_cast<const u32x4 *>(oct_mask) + size_t(np) * 128 + lane;
+        const u32x4 nm0 = stream_load(nsrc), nm1 = stream_load(nsrc + 64);
         // hit bits of the eight slots
         const uint32_t mk[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
         uint32_t hits = 0u;
