@@ -42,6 +42,11 @@ struct nimble_topo {
     int32_t last_regime = NIMBLE_REGIME_AUTO;
     int64_t bytes_per_iter = 0, bytes_argmin = 0, bytes_reduce = 0, bytes_update = 0;
     bool state_ready = false;   // a stream-regime solve has initialised the workspace
+    // per-iteration choice log of the streaming regime (rows of log_stride bytes); grows on
+    // demand, so the first solve with more iterations than any before allocates
+    uint8_t *choice_log = nullptr;
+    int64_t log_rows = 0;
+    size_t log_stride = 0;
     void *sync_words = nullptr; // barrier counter and reductions of the persistent kernel
     int n_cu = 0;
     unsigned int spin_limit = 1u << 22;   // barrier polls before a solve is abandoned
@@ -79,6 +84,32 @@ void release(nimble_topo *t)
 {
     for (void *p : t->allocs) (void)hipFree(p);
     t->allocs.clear();
+    if (t->choice_log) (void)hipFree(t->choice_log);
+    t->choice_log = nullptr;
+    t->log_rows = 0;
+}
+
+// Makes sure the choice log holds `iters` rows; false when it cannot (too large or out of
+// memory), in which case the solve keeps per-path counts instead.
+bool ensure_choice_log(nimble_topo *t, int32_t iters)
+{
+    if (std::getenv("NIMBLE_TUNE_NO_CHOICE_LOG")) return false;
+    if (t->log_rows >= iters) return true;
+    const size_t stride = (static_cast<size_t>(t->d.K) + 8 + 255) & ~static_cast<size_t>(255);
+    const size_t bytes = stride * static_cast<size_t>(iters);
+    if (bytes > (static_cast<size_t>(4) << 30)) return false;
+    if (t->choice_log) (void)hipFree(t->choice_log);      // waits for work that still uses it
+    t->choice_log = nullptr;
+    t->log_rows = 0;
+    void *p = nullptr;
+    if (hipMalloc(&p, bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    t->choice_log = static_cast<uint8_t *>(p);
+    t->log_rows = iters;
+    t->log_stride = stride;
+    return true;
 }
 
 nimble_status_t check_solve_args(const nimble_topo *topo, const double *d_traffic, double eps,
@@ -114,14 +145,21 @@ nimble_status_t solve_stream(nimble_topo *topo, const double *d_traffic, double 
                              int32_t iters, double *d_splits, double *d_lambda, hipStream_t s)
 {
     const nimble::DeviceTopo &d = topo->d;
+    // choices are logged per iteration when the log fits (the split fractions are then
+    // counted once at the end); otherwise every iteration bumps a per-path counter
+    const bool logged = ensure_choice_log(topo, iters);
     nimble::launch_init(d, d_traffic, s);
     nimble::launch_width(d, d_traffic, s);
     for (int32_t it = 0; it < iters; ++it) {
-        nimble::launch_argmin(d, s);
-        nimble::launch_load_reduce(d, d_traffic, s);
+        uint8_t *row = logged ? topo->choice_log + topo->log_stride * static_cast<size_t>(it)
+                              : d.choice;
+        nimble::launch_argmin(d, row, logged ? nullptr : d.count, s);
+        nimble::launch_load_reduce(d, row, d_traffic, s);
         nimble::launch_update(d, eps, s);
     }
-    nimble::launch_epilogue(d, iters, d_splits, d_lambda, s);
+    nimble::launch_epilogue(d, iters, logged ? nullptr : d.count, d_splits, d_lambda, s);
+    if (logged)
+        nimble::launch_histogram(d, topo->choice_log, topo->log_stride, iters, d_splits, s);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail_hip(e, "kernel launch (streaming regime)");
     topo->state_ready = true;
@@ -271,7 +309,7 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
 
     // stored bytes one iteration streams, phase by phase
     if (d.n_records > 0)
-        t->bytes_argmin = static_cast<int64_t>(nimble::kRecBytes) * d.n_records + 10LL * h.K;
+        t->bytes_argmin = static_cast<int64_t>(nimble::kRecBytes) * d.n_records + 2LL * h.K;
     else
         t->bytes_argmin = 4LL * (h.K + 1) + 4LL * (h.P + 1) + 4LL * h.nnz + 14LL * h.K;
     t->bytes_reduce = 36LL * static_cast<int64_t>(h.oct_base.size()) + 4LL * d.n_passes +
@@ -401,8 +439,9 @@ nimble_status_t nimble_debug_run_phase(nimble_topo_t *topo, int32_t phase, int32
     if (st != NIMBLE_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     for (int32_t r = 0; r < reps; ++r) {
-        if (phase == 0) nimble::launch_argmin(topo->d, s);
-        else if (phase == 1) nimble::launch_load_reduce(topo->d, d_traffic, s);
+        uint8_t *row = topo->log_rows > 0 ? topo->choice_log : topo->d.choice;
+        if (phase == 0) nimble::launch_argmin(topo->d, row, topo->log_rows > 0 ? nullptr : topo->d.count, s);
+        else if (phase == 1) nimble::launch_load_reduce(topo->d, row, d_traffic, s);
         else nimble::launch_update(topo->d, 0.0, s);   // eps 0: lengths stay as they are
     }
     hipError_t e = hipGetLastError();

@@ -60,11 +60,17 @@ int lanes_per_commodity(int pmax);   // power of two >= pmax, at most 64
 // ---- streaming regime: one launch per phase ------------------------------------------------
 void launch_init(const DeviceTopo &t, const double *demand, hipStream_t s);
 void launch_width(const DeviceTopo &t, const double *demand, hipStream_t s);
-void launch_argmin(const DeviceTopo &t, hipStream_t s);
-void launch_load_reduce(const DeviceTopo &t, const double *demand, hipStream_t s);
+// `choice` is the row the choices of this iteration are written to / read from (the
+// topology's own array, or a row of the per-iteration choice log); `count` may be null when
+// the choices are logged.
+void launch_argmin(const DeviceTopo &t, uint8_t *choice, uint32_t *count, hipStream_t s);
+void launch_load_reduce(const DeviceTopo &t, const uint8_t *choice, const double *demand,
+                        hipStream_t s);
+void launch_histogram(const DeviceTopo &t, const uint8_t *log, size_t stride, int32_t iters,
+                      double *splits, hipStream_t s);
 void launch_update(const DeviceTopo &t, double eps, hipStream_t s);
-void launch_epilogue(const DeviceTopo &t, int32_t iters, double *splits, double *lambda,
-                     hipStream_t s);
+void launch_epilogue(const DeviceTopo &t, int32_t iters, const uint32_t *count, double *splits,
+                     double *lambda, hipStream_t s);
 
 // ---- resident regime: one workgroup per plan, all iterations in one kernel ------------------
 // Bytes of LDS one plan needs (state only) and the bytes of the topology copy.

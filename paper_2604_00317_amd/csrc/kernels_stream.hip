@@ -140,8 +140,39 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records, 
             choice[k0 + c] = static_cast<uint8_t>(bj);
             const int sg = sig[c];
             if (sg >= 0) choice2[sg] = static_cast<uint8_t>(bj);   // copy in sigma order
-            count[p0 + p_lo + bj] += 1u;
+            // counts are kept only when the choices are not logged per iteration
+            if (count != nullptr) count[p0 + p_lo + bj] += 1u;
         }
+    }
+}
+
+// Split fractions from the per-iteration choice log: one lane per commodity walks its column
+// of the log and counts in LDS (a padded row per lane, so lanes hit different banks).
+__global__ __launch_bounds__(kWave) void k_histogram(int K, int iters, int pmax, size_t stride,
+                                                     const uint8_t *__restrict__ log,
+                                                     const int32_t *__restrict__ cp,
+                                                     double *__restrict__ splits)
+{
+    extern __shared__ uint32_t s_cnt[];
+    const int lane = threadIdx.x;
+    const int k = blockIdx.x * kWave + lane;
+    const int row = pmax | 1;                      // odd row length: conflict-free columns
+    uint32_t *mine = s_cnt + lane * row;
+    for (int j = 0; j < pmax; ++j) mine[j] = 0u;
+    if (k < K) {
+        const uint8_t *col = log + k;
+        int t = 0;
+        for (; t + 8 <= iters; t += 8) {
+            uint8_t c[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) c[u] = col[size_t(t + u) * stride];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) mine[c[u]] += 1u;
+        }
+        for (; t < iters; ++t) mine[col[size_t(t) * stride]] += 1u;
+        const int p0 = cp[k], np = cp[k + 1] - p0;
+        const double T = static_cast<double>(iters);
+        for (int j = 0; j < np; ++j) splits[p0 + j] = static_cast<double>(mine[j]) / T;
     }
 }
 
@@ -163,7 +194,7 @@ __global__ __launch_bounds__(kBlock) void k_load_reduce(ReduceArgs a)
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
-    reduce_flat_phase<MODE>(a.n_passes, a.pass_first_slot, a.oct_base, a.oct_mask, a.choice,
+    reduce_flat_phase<MODE, kFlatUnroll>(a.n_passes, a.pass_first_slot, a.oct_base, a.oct_mask, a.choice,
                             a.demand, a.choice2, a.demand2, a.partial, wave, n_waves, lane);
     // single pairs (commodities with more than 32 candidates) are walked from the other end of
     // the wave pool
@@ -217,8 +248,9 @@ __global__ __launch_bounds__(kBlock) void k_epilogue(int P, int iters, int n_upd
     __shared__ double red[16];
     const double T = static_cast<double>(iters);
     const int stride = gridDim.x * blockDim.x;
-    for (int p = blockIdx.x * blockDim.x + threadIdx.x; p < P; p += stride)
-        splits[p] = static_cast<double>(count[p]) / T;
+    if (count != nullptr)         // otherwise the splits come from the choice log
+        for (int p = blockIdx.x * blockDim.x + threadIdx.x; p < P; p += stride)
+            splits[p] = static_cast<double>(count[p]) / T;
     if (blockIdx.x == 0) {
         double m = 0.0;
         for (int b = threadIdx.x; b < n_update_blocks; b += blockDim.x)
@@ -237,7 +269,8 @@ inline int blocks_for(int64_t threads, int block, int cap)
 }
 
 template <int L, bool MAXC>
-void launch_argmin_lmax(const DeviceTopo &t, int grid, hipStream_t s)
+void launch_argmin_lmax(const DeviceTopo &t, int grid, uint8_t *choice, uint32_t *count,
+                        hipStream_t s)
 {
     if (t.n_records > 0) {
         const int rec_lds = (kRecBytes + 8 * (t.rec_max_links + 1) + 15) & ~15;
@@ -246,7 +279,7 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, hipStream_t s)
         hipLaunchKernelGGL((k_argmin_rec<L, SS, MAXC>),                                        \
                            dim3((t.n_records + kRecWaves - 1) / kRecWaves),                    \
                            dim3(kWave * kRecWaves), kRecWaves * rec_lds, s, t.n_records,       \
-                           rec_lds, t.records, t.price, t.choice, t.count, t.choice2);         \
+                           rec_lds, t.records, t.price, choice, count, t.choice2);             \
         return;
         switch (t.rec_stride) {
             NIMBLE_REC_LAUNCH(1)
@@ -262,8 +295,8 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, hipStream_t s)
     }
 #define NIMBLE_ARGMIN_LAUNCH(LM)                                                              \
     hipLaunchKernelGGL((k_argmin<L, LM, MAXC>), dim3(grid), dim3(kBlock), 0, s, t.K,          \
-                       t.comm_ptr, t.path_ptr, t.path_links, t.price, t.choice, t.count,      \
-                       t.sigma, t.choice2)
+                       t.comm_ptr, t.path_ptr, t.path_links, t.price, choice, count, t.sigma, \
+                       t.choice2)
     if (t.lmax <= 2) NIMBLE_ARGMIN_LAUNCH(2);
     else if (t.lmax <= 4) NIMBLE_ARGMIN_LAUNCH(4);
     else NIMBLE_ARGMIN_LAUNCH(8);
@@ -271,7 +304,7 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, hipStream_t s)
 }
 
 template <bool MAXC>
-void launch_argmin_l(const DeviceTopo &t, hipStream_t s)
+void launch_argmin_l(const DeviceTopo &t, uint8_t *choice, uint32_t *count, hipStream_t s)
 {
     // untiled kernel: one candidate per lane; record kernel: as many commodities side by side
     // as a record typically holds, each lane scanning several candidates
@@ -286,18 +319,19 @@ void launch_argmin_l(const DeviceTopo &t, hipStream_t s)
     }
     const int grid = blocks_for(static_cast<int64_t>(t.K) * L, kBlock, 1 << 20);
     switch (L) {
-    case 1: launch_argmin_lmax<1, MAXC>(t, grid, s); break;
-    case 2: launch_argmin_lmax<2, MAXC>(t, grid, s); break;
-    case 4: launch_argmin_lmax<4, MAXC>(t, grid, s); break;
-    case 8: launch_argmin_lmax<8, MAXC>(t, grid, s); break;
-    case 16: launch_argmin_lmax<16, MAXC>(t, grid, s); break;
-    case 32: launch_argmin_lmax<32, MAXC>(t, grid, s); break;
-    default: launch_argmin_lmax<64, MAXC>(t, grid, s); break;
+    case 1: launch_argmin_lmax<1, MAXC>(t, grid, choice, count, s); break;
+    case 2: launch_argmin_lmax<2, MAXC>(t, grid, choice, count, s); break;
+    case 4: launch_argmin_lmax<4, MAXC>(t, grid, choice, count, s); break;
+    case 8: launch_argmin_lmax<8, MAXC>(t, grid, choice, count, s); break;
+    case 16: launch_argmin_lmax<16, MAXC>(t, grid, choice, count, s); break;
+    case 32: launch_argmin_lmax<32, MAXC>(t, grid, choice, count, s); break;
+    default: launch_argmin_lmax<64, MAXC>(t, grid, choice, count, s); break;
     }
 }
 
 template <int MODE>
-void launch_reduce_mode(const DeviceTopo &t, const double *demand, hipStream_t s)
+void launch_reduce_mode(const DeviceTopo &t, const uint8_t *choice, const double *demand,
+                        hipStream_t s)
 {
     // a fixed pool of waves, each walking its passes with the loads pipelined
     const int64_t waves = static_cast<int64_t>(t.n_passes) > (t.n_schunks + 3) / 4
@@ -315,7 +349,7 @@ void launch_reduce_mode(const DeviceTopo &t, const double *demand, hipStream_t s
     a.schunk_slot = t.schunk_slot;
     a.single_pair = t.single_pair;
     a.pad_comm = static_cast<uint32_t>(t.K);
-    a.choice = t.choice;
+    a.choice = choice;
     a.choice2 = t.choice2;
     a.demand = demand;
     a.demand2 = t.demand2;
@@ -342,20 +376,29 @@ void launch_init(const DeviceTopo &t, const double *demand, hipStream_t s)
 
 void launch_width(const DeviceTopo &t, const double *demand, hipStream_t s)
 {
-    launch_reduce_mode<1>(t, demand, s);
+    launch_reduce_mode<1>(t, t.choice, demand, s);
     hipLaunchKernelGGL(k_width, dim3(1), dim3(1024), 0, s, t.E, t.link_slot_ptr,
                        t.link_sslot_ptr, t.partial, t.invcap, t.scalars);
 }
 
-void launch_argmin(const DeviceTopo &t, hipStream_t s)
+void launch_argmin(const DeviceTopo &t, uint8_t *choice, uint32_t *count, hipStream_t s)
 {
-    if (t.cost_max) launch_argmin_l<true>(t, s);
-    else launch_argmin_l<false>(t, s);
+    if (t.cost_max) launch_argmin_l<true>(t, choice, count, s);
+    else launch_argmin_l<false>(t, choice, count, s);
 }
 
-void launch_load_reduce(const DeviceTopo &t, const double *demand, hipStream_t s)
+void launch_load_reduce(const DeviceTopo &t, const uint8_t *choice, const double *demand,
+                        hipStream_t s)
 {
-    launch_reduce_mode<0>(t, demand, s);
+    launch_reduce_mode<0>(t, choice, demand, s);
+}
+
+void launch_histogram(const DeviceTopo &t, const uint8_t *log, size_t stride, int32_t iters,
+                      double *splits, hipStream_t s)
+{
+    const size_t lds = sizeof(uint32_t) * kWave * static_cast<size_t>(t.pmax | 1);
+    hipLaunchKernelGGL(k_histogram, dim3((t.K + kWave - 1) / kWave), dim3(kWave), lds, s, t.K,
+                       iters, t.pmax, stride, log, t.comm_ptr, splits);
 }
 
 void launch_update(const DeviceTopo &t, double eps, hipStream_t s)
@@ -370,11 +413,12 @@ void launch_update(const DeviceTopo &t, double eps, hipStream_t s)
                            t.S, t.scalars);
 }
 
-void launch_epilogue(const DeviceTopo &t, int32_t iters, double *splits, double *lambda,
-                     hipStream_t s)
+void launch_epilogue(const DeviceTopo &t, int32_t iters, const uint32_t *count, double *splits,
+                     double *lambda, hipStream_t s)
 {
-    hipLaunchKernelGGL(k_epilogue, dim3(blocks_for(t.P, kBlock, 4096)), dim3(kBlock), 0, s, t.P,
-                       iters, t.n_update_blocks, t.count, t.scalars, splits, lambda);
+    const int grid = count ? blocks_for(t.P, kBlock, 4096) : 1;
+    hipLaunchKernelGGL(k_epilogue, dim3(grid), dim3(kBlock), 0, s, t.P, iters, t.n_update_blocks,
+                       count, t.scalars, splits, lambda);
 }
 
 }  // namespace nimble

@@ -92,7 +92,7 @@ __device__ __forceinline__ void argmin_phase(int K, const int32_t *__restrict__ 
             choice[k] = static_cast<uint8_t>(bj);
             const int sg = sigma[k];
             if (sg >= 0) choice2[sg] = static_cast<uint8_t>(bj);   // copy in sigma order
-            count[p0 + bj] += 1u;
+            if (count != nullptr) count[p0 + bj] += 1u;            // absent: choices are logged
         }
     }
 }
@@ -238,7 +238,12 @@ __device__ __forceinline__ void reduce_phase(int n_chunks, const int32_t *__rest
 // combined by a segmented inclusive scan (fixed distances 1,2,..,32: the same tree on every
 // run) and the last lane of the segment stores the sum.  No floating-point atomics.
 // MODE 1 (width rho): every commodity with a non-zero mask counts once.
-template <int MODE>
+#ifndef NIMBLE_FLAT_UNROLL
+#define NIMBLE_FLAT_UNROLL 1
+#endif
+constexpr int kFlatUnroll = NIMBLE_FLAT_UNROLL;   // passes a wave works on at a time
+
+template <int MODE, int U>
 __device__ __forceinline__ void reduce_flat_phase(
     int n_passes, const int32_t *__restrict__ pass_first_slot,
     const uint32_t *__restrict__ oct_base, const uint32_t *__restrict__ oct_mask,
@@ -246,86 +251,133 @@ __device__ __forceinline__ void reduce_flat_phase(
     const uint8_t *__restrict__ choice2, const double *__restrict__ demand2,
     double *__restrict__ partial, int wave, int n_waves, int lane)
 {
+    // a wave works on U passes at a time (passes wave, wave + n_waves, ...): their gathers
+    // and scans are independent, so their latencies overlap
     if (wave >= n_passes) return;
     const int last = n_passes - 1;
-    // pipeline: the octets of the next pass are requested before the gathers of the current
-    // one are consumed; loads past the end re-read the last pass and are ignored
-    uint32_t bw;
-    u32x4 m0, m1;
-    {
-        const size_t i = size_t(wave) * kWave + lane;
-        bw = stream_load(oct_base + i);
+    const u32x4 *masks = reinterpret_cast<const u32x4 *>(oct_mask);
+    // pipeline: the octets of the next U passes are requested before the gathers of the
+    // current ones are consumed; loads past the end re-read the last pass and are ignored
+    uint32_t bw[U];
+    u32x4 m0[U], m1[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int ps = wave + u * n_waves < last ? wave + u * n_waves : last;
+        bw[u] = stream_load(oct_base + size_t(ps) * kWave + lane);
         // masks of a pass: words 0..3 of the 64 octets lane after lane, then words 4..7
-        const u32x4 *src = reinterpret_cast<const u32x4 *>(oct_mask) + size_t(wave) * 128 + lane;
-        m0 = stream_load(src);
-        m1 = stream_load(src + 64);
+        m0[u] = stream_load(masks + size_t(ps) * 128 + lane);
+        m1[u] = stream_load(masks + size_t(ps) * 128 + 64 + lane);
     }
-    for (int pass = wave; pass < n_passes; pass += n_waves) {      // wave-uniform
-        const bool sig = (bw & kOctSigma) != 0u;
-        const int base = static_cast<int>(bw & ~3u);
-        const uint8_t *ch_src = sig ? choice2 : choice;
-        const double *dm_src = sig ? demand2 : demand;
-        uint2 ch = make_uint2(0u, 0u);
-        if constexpr (MODE == 0) ch = *reinterpret_cast<const uint2 *>(ch_src + base);
-        const int first_slot = pass_first_slot[pass];
-        // requests for the next pass, issued after the gather
-        const int np = pass + n_waves < last ? pass + n_waves : last;
-        const size_t ni = size_t(np) * kWave + lane;
-        const uint32_t nbw = stream_load(oct_base + ni);
-        const u32x4 *nsrc = reinterpret_cast<const u32x4 *>(oct_mask) + size_t(np) * 128 + lane;
-        const u32x4 nm0 = stream_load(nsrc), nm1 = stream_load(nsrc + 64);
-        // hit bits of the eight slots
-        const uint32_t mk[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
-        uint32_t hits = 0u;
+    for (int pass0 = wave; pass0 < n_passes; pass0 += U * n_waves) {      // wave-uniform
+        uint2 ch[U];
+        int base[U];
+        const double *dm_src[U];
 #pragma unroll
-        for (int sl = 0; sl < 8; ++sl) {
-            uint32_t h;
-            if constexpr (MODE == 0) {
-                // commodities in octets have at most 32 candidates, so the choice is < 32
-                const uint32_t c8 = ((sl < 4 ? ch.x : ch.y) >> (8 * (sl & 3))) & 31u;
-                h = (mk[sl] >> c8) & 1u;
-            } else {
-                h = mk[sl] != 0u ? 1u : 0u;
-            }
-            hits |= h << sl;
+        for (int u = 0; u < U; ++u) {
+            const bool sig = (bw[u] & kOctSigma) != 0u;
+            base[u] = static_cast<int>(bw[u] & ~3u);
+            const uint8_t *ch_src = sig ? choice2 : choice;
+            dm_src[u] = sig ? demand2 : demand;
+            ch[u] = make_uint2(0u, 0u);
+            if constexpr (MODE == 0) ch[u] = *reinterpret_cast<const uint2 *>(ch_src + base[u]);
         }
-        // demands of the hits in slot order, four loads side by side; an absent hit re-reads
-        // the first one and is masked to +0.0 (masked, not selected: a select would let the
-        // compiler move the load under the condition and wait for it on its own)
-        double acc = 0.0;
-        while (hits != 0u) {
-            int idx[4];
-            bool ok[4];
+        int first_slot[U];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                ok[u] = hits != 0u;
-                const int t = ok[u] ? __ffs(hits) - 1 : 0;
-                hits &= hits - 1u;           // 0 stays 0
-                idx[u] = ok[u] ? base + t : idx[0];
+        for (int u = 0; u < U; ++u) {
+            const int ps = pass0 + u * n_waves;
+            first_slot[u] = pass_first_slot[ps < last ? ps : last];
+        }
+        // requests for the next passes, issued after the gathers
+        uint32_t nbw[U];
+        u32x4 nm0[U], nm1[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int ps = pass0 + (U + u) * n_waves;
+            const int np = ps < last ? ps : last;
+            nbw[u] = stream_load(oct_base + size_t(np) * kWave + lane);
+            nm0[u] = stream_load(masks + size_t(np) * 128 + lane);
+            nm1[u] = stream_load(masks + size_t(np) * 128 + 64 + lane);
+        }
+        // hit bits of the eight slots of each octet
+        uint32_t hits[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint32_t mk[8] = {m0[u].x, m0[u].y, m0[u].z, m0[u].w,
+                                    m1[u].x, m1[u].y, m1[u].z, m1[u].w};
+            hits[u] = 0u;
+#pragma unroll
+            for (int sl = 0; sl < 8; ++sl) {
+                uint32_t h;
+                if constexpr (MODE == 0) {
+                    // commodities in octets have at most 32 candidates, so the choice is < 32
+                    const uint32_t c8 = ((sl < 4 ? ch[u].x : ch[u].y) >> (8 * (sl & 3))) & 31u;
+                    h = (mk[sl] >> c8) & 1u;
+                } else {
+                    h = mk[sl] != 0u ? 1u : 0u;
+                }
+                hits[u] |= h << sl;
             }
-            double d[4];
+            if (pass0 + u * n_waves > last) hits[u] = 0u;      // no such pass
+        }
+        // demands of the hits in slot order, two loads per pass side by side; an absent hit
+        // re-reads the first one and is masked to +0.0 (masked, not selected: a select would
+        // let the compiler move the load under the condition and wait for it on its own)
+        double acc[U];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) d[u] = dm_src[idx[u]];
+        for (int u = 0; u < U; ++u) acc[u] = 0.0;
+        bool more = false;
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int mkk = -static_cast<int>(ok[u]);
-                acc = acc + __hiloint2double(__double2hiint(d[u]) & mkk, __double2loint(d[u]) & mkk);
+        for (int u = 0; u < U; ++u) more = more || hits[u] != 0u;
+        while (more) {
+            int idx[U][2];
+            bool ok[U][2];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int v = 0; v < 2; ++v) {
+                    ok[u][v] = hits[u] != 0u;
+                    const int t = ok[u][v] ? __ffs(hits[u]) - 1 : 0;
+                    hits[u] &= hits[u] - 1u;           // 0 stays 0
+                    idx[u][v] = base[u] + t;           // an absent hit reads slot 0: in range
+                }
+            double d[U][2];
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+#pragma unroll
+                for (int v = 0; v < 2; ++v) d[u][v] = dm_src[u][idx[u][v]];
+            more = false;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+#pragma unroll
+                for (int v = 0; v < 2; ++v) {
+                    const int mkk = -static_cast<int>(ok[u][v]);
+                    acc[u] = acc[u] + __hiloint2double(__double2hiint(d[u][v]) & mkk,
+                                                       __double2loint(d[u][v]) & mkk);
+                }
+                more = more || hits[u] != 0u;
             }
         }
-        // segmented inclusive scan over the lanes of one slot
-        const unsigned long long heads = __ballot((bw & kOctNewSlot) != 0u);   // bit 0 is set
-        const unsigned long long upto = heads & (~0ull >> (63 - lane));       // heads at lanes <= lane
-        const int start = 63 - __clzll(static_cast<long long>(upto));
+        // segmented inclusive scans over the lanes of one slot
 #pragma unroll
-        for (int dist = 1; dist < kWave; dist <<= 1) {
-            const double v = __shfl_up(acc, dist, kWave);
-            if (lane - dist >= start) acc = acc + v;
+        for (int u = 0; u < U; ++u) {
+            const unsigned long long heads = __ballot((bw[u] & kOctNewSlot) != 0u);   // bit 0 set
+            const unsigned long long upto = heads & (~0ull >> (63 - lane));   // heads at lanes <= lane
+            const int start = 63 - __clzll(static_cast<long long>(upto));
+#pragma unroll
+            for (int dist = 1; dist < kWave; dist <<= 1) {
+                const double v = __shfl_up(acc[u], dist, kWave);
+                if (lane - dist >= start) acc[u] = acc[u] + v;
+            }
+            const bool tail = lane == kWave - 1 || ((heads >> (lane + 1)) & 1ull) != 0ull;
+            if (tail && pass0 + u * n_waves <= last)
+                partial[first_slot[u] + __popcll(upto) - 1] = acc[u];
         }
-        const bool tail = lane == kWave - 1 || ((heads >> (lane + 1)) & 1ull) != 0ull;
-        if (tail) partial[first_slot + __popcll(upto) - 1] = acc;
-        bw = nbw;
-        m0 = nm0;
-        m1 = nm1;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            bw[u] = nbw[u];
+            m0[u] = nm0[u];
+            m1[u] = nm1[u];
+        }
     }
 }
 

@@ -130,6 +130,15 @@ def test_edge_cases(oracle_mod, B, regime):
     check(oracle_mod, B, w.topo, w.traffic, w.eps, 120, regime, flags=1)
 
 
+def test_streaming_regime_without_choice_log(oracle_mod, B, monkeypatch):
+    """When the per-iteration choice log is unavailable the streaming regime counts per path
+    every iteration instead; both ways must give the same plan."""
+    monkeypatch.setenv("NIMBLE_TUNE_NO_CHOICE_LOG", "1")
+    for cfg, iters in ((1, 300), (3, 120)):
+        w = W.make_config(cfg)
+        check(oracle_mod, B, w.topo, w.traffic, w.eps, iters, regime=2)
+
+
 def test_non_integer_demands(oracle_mod, B):
     """The resident regime adds loads in the sequential order, so it is exact for any demands;
     the streaming regime sums in a fixed tree: run-to-run identical, equal to the oracle up to
