@@ -363,11 +363,7 @@ __device__ __forceinline__ void reduce_flat_phase(
             const unsigned long long heads = __ballot((bw[u] & kOctNewSlot) != 0u);   // bit 0 set
             const unsigned long long upto = heads & (~0ull >> (63 - lane));   // heads at lanes <= lane
             const int start = 63 - __clzll(static_cast<long long>(upto));
-#pragma unroll
-            for (int dist = 1; dist < kWave; dist <<= 1) {
-                const double v = __shfl_up(acc[u], dist, kWave);
-                if (lane - dist >= start) acc[u] = acc[u] + v;
-            }
+            acc[u] = segmented_scan_f64(acc[u], start, lane);
             const bool tail = lane == kWave - 1 || ((heads >> (lane + 1)) & 1ull) != 0ull;
             if (tail && pass0 + u * n_waves <= last)
                 partial[first_slot[u] + __popcll(upto) - 1] = acc[u];

@@ -109,6 +109,43 @@ __device__ __forceinline__ int group_argmin_two_pass(double c, int j)
     return t;
 }
 
+// DPP shifts for scans: value of the lane `D` below inside the 16-lane row (0.0 where there is
+// none), of lane 15 of the previous row (rows 1 and 3 only), and of lane 31 (rows 2 and 3 only).
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ double dpp_shift_f64(double v)
+{
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, ROW_MASK, 0xF, true);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, ROW_MASK, 0xF, true);
+    return __hiloint2double(hi, lo);
+}
+
+// Segmented inclusive scan of `v` over the wave: lanes are grouped into runs that begin at the
+// lanes flagged in `heads` (bit 0 must be set); every lane ends with the sum of its run up to
+// and including itself, added in a fixed order (row-local shifts 1, 2, 4, 8, then the carry of
+// the previous row, then the carry of the lower half).  `start` is the lane at which this
+// lane's run begins.
+__device__ __forceinline__ double segmented_scan_f64(double v, int start, int lane)
+{
+    const int l16 = lane & 15;
+    const int row_base = lane & ~15;
+    // row-local: the source lane must be inside the row and inside the run
+    double t = dpp_shift_f64<0x111, 0xF>(v);            // row_shr:1
+    if (l16 >= 1 && lane - 1 >= start) v = v + t;
+    t = dpp_shift_f64<0x112, 0xF>(v);                   // row_shr:2
+    if (l16 >= 2 && lane - 2 >= start) v = v + t;
+    t = dpp_shift_f64<0x114, 0xF>(v);                   // row_shr:4
+    if (l16 >= 4 && lane - 4 >= start) v = v + t;
+    t = dpp_shift_f64<0x118, 0xF>(v);                   // row_shr:8
+    if (l16 >= 8 && lane - 8 >= start) v = v + t;
+    // carry of the previous row into rows 1 and 3 (their runs may begin in that row)
+    t = dpp_shift_f64<0x142, 0xA>(v);                   // row_bcast:15
+    if ((lane & 16) != 0 && start < row_base) v = v + t;
+    // carry of the lower half into rows 2 and 3
+    t = dpp_shift_f64<0x143, 0xC>(v);                   // row_bcast:31
+    if (lane >= 32 && start < 32) v = v + t;
+    return v;
+}
+
 // Sum over the 64 lanes in a fixed butterfly order (the same tree on every run).
 __device__ __forceinline__ double wave_sum(double v)
 {
