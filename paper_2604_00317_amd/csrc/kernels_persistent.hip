@@ -97,7 +97,7 @@ template <int MODE>
 __device__ __forceinline__ void reduce_both(const PersistentArgs &a, int wave, int n_waves,
                                             int lane)
 {
-    reduce_flat_phase<MODE, kFlatUnroll>(a.n_passes, a.pass_first_slot, a.oct_base, a.oct_mask, a.choice,
+    reduce_flat_phase<MODE>(a.n_passes, a.pass_first_slot, a.oct_base, a.oct_mask, a.choice,
                             a.demand, a.choice2, a.demand2, a.partial, wave, n_waves, lane);
     reduce_phase<MODE, kSinglesPerLane>(a.n_schunks, a.schunk_begin, a.schunk_end, a.schunk_slot,
                                         a.single_pair, a.pad_comm, a.choice, a.demand, a.partial,

@@ -194,7 +194,7 @@ __global__ __launch_bounds__(kBlock) void k_load_reduce(ReduceArgs a)
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
-    reduce_flat_phase<MODE, kFlatUnroll>(a.n_passes, a.pass_first_slot, a.oct_base, a.oct_mask, a.choice,
+    reduce_flat_phase<MODE>(a.n_passes, a.pass_first_slot, a.oct_base, a.oct_mask, a.choice,
                             a.demand, a.choice2, a.demand2, a.partial, wave, n_waves, lane);
     // single pairs (commodities with more than 32 candidates) are walked from the other end of
     // the wave pool

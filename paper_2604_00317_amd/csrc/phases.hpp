@@ -238,12 +238,7 @@ __device__ __forceinline__ void reduce_phase(int n_chunks, const int32_t *__rest
 // combined by a segmented inclusive scan (fixed distances 1,2,..,32: the same tree on every
 // run) and the last lane of the segment stores the sum.  No floating-point atomics.
 // MODE 1 (width rho): every commodity with a non-zero mask counts once.
-#ifndef NIMBLE_FLAT_UNROLL
-#define NIMBLE_FLAT_UNROLL 1
-#endif
-constexpr int kFlatUnroll = NIMBLE_FLAT_UNROLL;   // passes a wave works on at a time
-
-template <int MODE, int U>
+template <int MODE>
 __device__ __forceinline__ void reduce_flat_phase(
     int n_passes, const int32_t *__restrict__ pass_first_slot,
     const uint32_t *__restrict__ oct_base, const uint32_t *__restrict__ oct_mask,
@@ -251,130 +246,104 @@ __device__ __forceinline__ void reduce_flat_phase(
     const uint8_t *__restrict__ choice2, const double *__restrict__ demand2,
     double *__restrict__ partial, int wave, int n_waves, int lane)
 {
-    // a wave works on U passes at a time (passes wave, wave + n_waves, ...): their gathers
-    // and scans are independent, so their latencies overlap
     if (wave >= n_passes) return;
     const int last = n_passes - 1;
     const u32x4 *masks = reinterpret_cast<const u32x4 *>(oct_mask);
-    // pipeline: the octets of the next U passes are requested before the gathers of the
-    // current ones are consumed; loads past the end re-read the last pass and are ignored
-    uint32_t bw[U];
-    u32x4 m0[U], m1[U];
+    // Software pipeline over the passes of this wave, two passes in flight:
+    //   A  gather the choices of pass i            (its octets arrived during pass i-1)
+    //   B  request the octets of pass i+1
+    //   C  finish pass i-1: its demand loads were issued before A and B, so waiting for them
+    //      leaves A and B in flight; segmented scan, store of the partial sums
+    //   D  hit bits of pass i, request the demands of (up to two) hits per lane
+    // Every load on this path is unconditional (absent hits read element 0 and are masked to
+    // +0.0; passes beyond the end re-read the last pass), which keeps the number of
+    // outstanding requests known to the compiler so that it waits for the oldest only.
+    uint32_t bw = stream_load(oct_base + size_t(wave) * kWave + lane);
+    // masks of a pass: words 0..3 of the 64 octets lane after lane, then words 4..7
+    u32x4 m0 = stream_load(masks + size_t(wave) * 128 + lane);
+    u32x4 m1 = stream_load(masks + size_t(wave) * 128 + 64 + lane);
+    // carried state of the pass that is waiting for its demands
+    bool have_prev = false;
+    double pd0 = 0.0, pd1 = 0.0, pextra = 0.0;
+    int pmask0 = 0, pmask1 = 0, pslot = 0;
+    uint32_t pflag = 0u;
+    auto finish = [&](double d0, double d1, int k0, int k1, double extra, uint32_t flagword,
+                      int first_slot) {
+        // masked, not selected: a select would let the compiler move the load under the
+        // condition and wait for it on its own
+        double acc = __hiloint2double(__double2hiint(d0) & k0, __double2loint(d0) & k0);
+        acc = acc + __hiloint2double(__double2hiint(d1) & k1, __double2loint(d1) & k1);
+        acc = acc + extra;
+        const unsigned long long heads = __ballot((flagword & kOctNewSlot) != 0u);   // bit 0 set
+        const unsigned long long upto = heads & (~0ull >> (63 - lane));   // heads at lanes <= lane
+        const int start = 63 - __clzll(static_cast<long long>(upto));
+        acc = segmented_scan_f64(acc, start, lane);
+        const bool tail = lane == kWave - 1 || ((heads >> (lane + 1)) & 1ull) != 0ull;
+        if (tail) partial[first_slot + __popcll(upto) - 1] = acc;
+    };
+    for (int pass = wave; pass < n_passes; pass += n_waves) {      // wave-uniform
+        // A
+        const bool sig = (bw & kOctSigma) != 0u;
+        const int base = static_cast<int>(bw & ~3u);
+        const uint8_t *ch_src = sig ? choice2 : choice;
+        const double *dm_src = sig ? demand2 : demand;
+        uint2 ch = make_uint2(0u, 0u);
+        if constexpr (MODE == 0) ch = *reinterpret_cast<const uint2 *>(ch_src + base);
+        const int first_slot = pass_first_slot[pass];
+        // B
+        const int np = pass + n_waves < last ? pass + n_waves : last;
+        const uint32_t nbw = stream_load(oct_base + size_t(np) * kWave + lane);
+        const u32x4 nm0 = stream_load(masks + size_t(np) * 128 + lane);
+        const u32x4 nm1 = stream_load(masks + size_t(np) * 128 + 64 + lane);
+        // C
+        if (have_prev) finish(pd0, pd1, pmask0, pmask1, pextra, pflag, pslot);
+        // D
+        const uint32_t mk[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
+        uint32_t hits = 0u;
 #pragma unroll
-    for (int u = 0; u < U; ++u) {
-        const int ps = wave + u * n_waves < last ? wave + u * n_waves : last;
-        bw[u] = stream_load(oct_base + size_t(ps) * kWave + lane);
-        // masks of a pass: words 0..3 of the 64 octets lane after lane, then words 4..7
-        m0[u] = stream_load(masks + size_t(ps) * 128 + lane);
-        m1[u] = stream_load(masks + size_t(ps) * 128 + 64 + lane);
-    }
-    for (int pass0 = wave; pass0 < n_passes; pass0 += U * n_waves) {      // wave-uniform
-        uint2 ch[U];
-        int base[U];
-        const double *dm_src[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const bool sig = (bw[u] & kOctSigma) != 0u;
-            base[u] = static_cast<int>(bw[u] & ~3u);
-            const uint8_t *ch_src = sig ? choice2 : choice;
-            dm_src[u] = sig ? demand2 : demand;
-            ch[u] = make_uint2(0u, 0u);
-            if constexpr (MODE == 0) ch[u] = *reinterpret_cast<const uint2 *>(ch_src + base[u]);
-        }
-        int first_slot[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int ps = pass0 + u * n_waves;
-            first_slot[u] = pass_first_slot[ps < last ? ps : last];
-        }
-        // requests for the next passes, issued after the gathers
-        uint32_t nbw[U];
-        u32x4 nm0[U], nm1[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int ps = pass0 + (U + u) * n_waves;
-            const int np = ps < last ? ps : last;
-            nbw[u] = stream_load(oct_base + size_t(np) * kWave + lane);
-            nm0[u] = stream_load(masks + size_t(np) * 128 + lane);
-            nm1[u] = stream_load(masks + size_t(np) * 128 + 64 + lane);
-        }
-        // hit bits of the eight slots of each octet
-        uint32_t hits[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const uint32_t mk[8] = {m0[u].x, m0[u].y, m0[u].z, m0[u].w,
-                                    m1[u].x, m1[u].y, m1[u].z, m1[u].w};
-            hits[u] = 0u;
-#pragma unroll
-            for (int sl = 0; sl < 8; ++sl) {
-                uint32_t h;
-                if constexpr (MODE == 0) {
-                    // commodities in octets have at most 32 candidates, so the choice is < 32
-                    const uint32_t c8 = ((sl < 4 ? ch[u].x : ch[u].y) >> (8 * (sl & 3))) & 31u;
-                    h = (mk[sl] >> c8) & 1u;
-                } else {
-                    h = mk[sl] != 0u ? 1u : 0u;
-                }
-                hits[u] |= h << sl;
+        for (int sl = 0; sl < 8; ++sl) {
+            uint32_t h;
+            if constexpr (MODE == 0) {
+                // commodities in octets have at most 32 candidates, so the choice is < 32
+                const uint32_t c8 = ((sl < 4 ? ch.x : ch.y) >> (8 * (sl & 3))) & 31u;
+                h = (mk[sl] >> c8) & 1u;
+            } else {
+                h = mk[sl] != 0u ? 1u : 0u;
             }
-            if (pass0 + u * n_waves > last) hits[u] = 0u;      // no such pass
+            hits |= h << sl;
         }
-        // demands of the hits in slot order, two loads per pass side by side; an absent hit
-        // re-reads the first one and is masked to +0.0 (masked, not selected: a select would
-        // let the compiler move the load under the condition and wait for it on its own)
-        double acc[U];
-#pragma unroll
-        for (int u = 0; u < U; ++u) acc[u] = 0.0;
-        bool more = false;
-#pragma unroll
-        for (int u = 0; u < U; ++u) more = more || hits[u] != 0u;
-        while (more) {
-            int idx[U][2];
-            bool ok[U][2];
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int v = 0; v < 2; ++v) {
-                    ok[u][v] = hits[u] != 0u;
-                    const int t = ok[u][v] ? __ffs(hits[u]) - 1 : 0;
-                    hits[u] &= hits[u] - 1u;           // 0 stays 0
-                    idx[u][v] = base[u] + t;           // an absent hit reads slot 0: in range
-                }
-            double d[U][2];
-#pragma unroll
-            for (int u = 0; u < U; ++u)
-#pragma unroll
-                for (int v = 0; v < 2; ++v) d[u][v] = dm_src[u][idx[u][v]];
-            more = false;
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-#pragma unroll
-                for (int v = 0; v < 2; ++v) {
-                    const int mkk = -static_cast<int>(ok[u][v]);
-                    acc[u] = acc[u] + __hiloint2double(__double2hiint(d[u][v]) & mkk,
-                                                       __double2loint(d[u][v]) & mkk);
-                }
-                more = more || hits[u] != 0u;
+        // the first two hits of the lane, in slot order; a lane without a hit reads element 0
+        // of the demand array instead (all such lanes share one cache line) and is masked
+        const bool ok0 = hits != 0u;
+        const int i0 = ok0 ? base + __ffs(hits) - 1 : 0;
+        hits &= hits - 1u;
+        const bool ok1 = hits != 0u;
+        const int i1 = ok1 ? base + __ffs(hits) - 1 : 0;
+        hits &= hits - 1u;
+        const double d0 = dm_src[i0];
+        const double d1 = dm_src[i1];
+        // further hits of a lane are rare: fetch them at once (this wait is for everything)
+        double extra = 0.0;
+        if (__any(hits != 0u)) {
+            while (hits != 0u) {
+                const int t = __ffs(hits) - 1;
+                hits &= hits - 1u;
+                extra = extra + dm_src[base + t];
             }
         }
-        // segmented inclusive scans over the lanes of one slot
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const unsigned long long heads = __ballot((bw[u] & kOctNewSlot) != 0u);   // bit 0 set
-            const unsigned long long upto = heads & (~0ull >> (63 - lane));   // heads at lanes <= lane
-            const int start = 63 - __clzll(static_cast<long long>(upto));
-            acc[u] = segmented_scan_f64(acc[u], start, lane);
-            const bool tail = lane == kWave - 1 || ((heads >> (lane + 1)) & 1ull) != 0ull;
-            if (tail && pass0 + u * n_waves <= last)
-                partial[first_slot[u] + __popcll(upto) - 1] = acc[u];
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            bw[u] = nbw[u];
-            m0[u] = nm0[u];
-            m1[u] = nm1[u];
-        }
+        pd0 = d0;
+        pd1 = d1;
+        pmask0 = -static_cast<int>(ok0);
+        pmask1 = -static_cast<int>(ok1);
+        pextra = extra;
+        pflag = bw;
+        pslot = first_slot;
+        have_prev = true;
+        bw = nbw;
+        m0 = nm0;
+        m1 = nm1;
     }
+    if (have_prev) finish(pd0, pd1, pmask0, pmask1, pextra, pflag, pslot);
 }
 
 // ---- phase C: slot partials -> load, congestion sum, multiplicative length update ----------
