@@ -233,6 +233,9 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     d.rec_stride = h.rec_stride;
     d.rec_max_links = h.rec_max_links;
     d.rec_lanes = 0;
+    d.rec_per_wave = 0;
+    if (const char *env = std::getenv("NIMBLE_TUNE_RECORDS_PER_WAVE"))
+        if (std::atoi(env) >= 1 && std::atoi(env) <= 64) d.rec_per_wave = std::atoi(env);
     if (const char *env = std::getenv("NIMBLE_TUNE_RECORD_LANES")) {
         const int v = std::atoi(env);
         if (v == 1 || v == 2 || v == 4 || v == 8 || v == 16 || v == 32 || v == 64) d.rec_lanes = v;

@@ -345,10 +345,10 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
         const int32_t S = t.rec_stride;
         std::vector<int32_t> stamp(n_links, -1), local(n_links, 0);
         std::vector<int32_t> links;
-        std::vector<uint16_t> cp16, loc16;
+        std::vector<uint16_t> cp16, cq16, loc16;
         auto align4 = [](int32_t x) { return (x + 3) & ~3; };
-        auto bytes_needed = [&](int32_t nl, int32_t nk, int32_t np) {
-            return kRecHeader + 4 * nl + 4 * nk + align4(2 * (nk + 1)) + np * S;
+        auto bytes_needed = [&](int32_t nl, int32_t nk, int32_t npad) {
+            return kRecHeader + 4 * nl + 4 * nk + 2 * align4(2 * (nk + 1)) + npad * S;
         };
         bool ok = true;
         int32_t k = 0;
@@ -357,8 +357,9 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
             const int32_t k0 = k, p0 = comm_path_ptr[k];
             links.clear();
             cp16.assign(1, 0);
+            cq16.assign(1, 0);
             loc16.clear();
-            int32_t np = 0;
+            int32_t np = 0, npad = 0;
             while (k < n_comm && k - k0 < t.rec_comm_cap) {
                 const int32_t pa = comm_path_ptr[k], pb = comm_path_ptr[k + 1];
                 // distinct links this commodity would add
@@ -372,7 +373,8 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                 }
                 const int32_t nl_new = static_cast<int32_t>(links.size()) + add;
                 const bool fits = nl_new <= kRecMaxLinks &&
-                                  bytes_needed(nl_new, k - k0 + 1, np + (pb - pa)) <= kRecBytes;
+                                  bytes_needed(nl_new, k - k0 + 1, npad + align4(pb - pa)) <=
+                                      kRecBytes;
                 if (!fits) {
                     for (int32_t i = path_link_ptr[pa]; i < path_link_ptr[pb]; ++i)
                         if (stamp[path_links[i]] == -2 - rec_id) stamp[path_links[i]] = -1;
@@ -391,8 +393,13 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                     }
                     for (int32_t i = lb - la; i < S; ++i) loc16.push_back(0xFFFFu);  // patched below
                 }
+                // candidates are padded to whole quads (the kernel never compares the padding)
+                for (int32_t q = pb - pa; q < align4(pb - pa); ++q)
+                    for (int32_t i = 0; i < S; ++i) loc16.push_back(0xFFFFu);
                 np += pb - pa;
+                npad += align4(pb - pa);
                 cp16.push_back(static_cast<uint16_t>(np));
+                cq16.push_back(static_cast<uint16_t>(npad));
                 ++k;
             }
             if (k == k0) {      // one commodity alone does not fit a record
@@ -422,24 +429,28 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
             uint8_t *r = t.records.data() + static_cast<size_t>(t.n_records) * kRecBytes;
             const int32_t off_sig = kRecHeader + 4 * nl;
             const int32_t off_cp = off_sig + 4 * nk;
-            const int32_t off_loc = off_cp + align4(2 * (nk + 1));
+            const int32_t off_cq = off_cp + align4(2 * (nk + 1));
+            const int32_t off_loc = off_cq + align4(2 * (nk + 1));
             const uint16_t h16[8] = {static_cast<uint16_t>(nk), static_cast<uint16_t>(np),
                                      static_cast<uint16_t>(nl), static_cast<uint16_t>(off_cp),
                                      static_cast<uint16_t>(off_loc),
-                                     static_cast<uint16_t>(off_sig), 0, 0};
+                                     static_cast<uint16_t>(off_sig),
+                                     static_cast<uint16_t>(off_cq),
+                                     static_cast<uint16_t>(npad)};
             std::memcpy(r + 0, &k0, 4);
             std::memcpy(r + 4, &p0, 4);
             std::memcpy(r + 8, h16, 16);
             std::memcpy(r + kRecHeader, links.data(), 4 * static_cast<size_t>(nl));
             std::memcpy(r + off_sig, t.sigma.data() + k0, 4 * static_cast<size_t>(nk));
             std::memcpy(r + off_cp, cp16.data(), 2 * cp16.size());
-            // step-major: index i of every path, then index i+1, ... so that the lanes of a
-            // wave (consecutive paths) read consecutive 16-bit words
+            std::memcpy(r + off_cq, cq16.data(), 2 * cq16.size());
+            // step-major over the padded candidates: index i of every candidate, then index
+            // i+1, ...; four consecutive candidates (a quad) are one aligned 32-bit word
             {
                 std::vector<uint8_t> soa(loc16.size());
-                for (int32_t p = 0; p < np; ++p)
+                for (int32_t p = 0; p < npad; ++p)
                     for (int32_t i = 0; i < S; ++i)
-                        soa[static_cast<size_t>(i) * np + p] =
+                        soa[static_cast<size_t>(i) * npad + p] =
                             static_cast<uint8_t>(loc16[static_cast<size_t>(p) * S + i]);
                 std::memcpy(r + off_loc, soa.data(), soa.size());
             }
@@ -524,18 +535,23 @@ extern "C" nimble_status_t nimble_host_records_roundtrip(int32_t n_links, int32_
         std::memcpy(&p0, r + 4, 4);
         std::memcpy(h16, r + 8, 16);
         const int32_t nk = h16[0], np = h16[1], nl = h16[2], off_cp = h16[3], off_loc = h16[4];
+        const int32_t off_cq = h16[6], npad = h16[7];
         if (k0 != next_comm || p0 != comm_path_ptr[k0]) return NIMBLE_ERR_INVALID;
         next_comm = k0 + nk;
         const int32_t *links = reinterpret_cast<const int32_t *>(r + nimble::kRecHeader);
         const uint16_t *cp16 = reinterpret_cast<const uint16_t *>(r + off_cp);
+        const uint16_t *cq16 = reinterpret_cast<const uint16_t *>(r + off_cq);
+        if (cq16[nk] != npad || npad % 4) return NIMBLE_ERR_INVALID;
         const uint8_t *loc16 = r + off_loc;
         if (cp16[nk] != np) return NIMBLE_ERR_INVALID;
         for (int32_t c = 0; c < nk; ++c) {
             if (p0 + cp16[c] != comm_path_ptr[k0 + c]) return NIMBLE_ERR_INVALID;
+            if (cq16[c] % 4) return NIMBLE_ERR_INVALID;
             for (int32_t p = cp16[c]; p < cp16[c + 1]; ++p) {
                 path_record[p0 + p] = ri;
+                const int32_t pq = cq16[c] + (p - cp16[c]);       // padded position
                 for (int32_t i = 0; i < t.rec_stride; ++i) {
-                    const int32_t li = loc16[i * np + p];
+                    const int32_t li = loc16[i * npad + pq];
                     if (li == nl) continue;
                     if (li > nl) return NIMBLE_ERR_INVALID;
                     links_out[w++] = links[li];

@@ -59,11 +59,13 @@ constexpr int32_t kSinglesPerLane = 8;        // a single-pair chunk holds 16 * 
 // of positive prices).  Layout, offsets in bytes from the start of the record:
 //   0   int32 k0        first commodity
 //   4   int32 p0        first candidate path (global id)
-//   8   uint16 nk, np, n_links, off_cp, off_loc, off_sig, reserved[2]
+//   8   uint16 nk, np, n_links, off_cp, off_loc, off_sig, off_cq, npad
 //   24  int32 links[n_links]
 //   off_sig  int32 sigma[nk]      second numbering of the commodity (-1: none)
 //   off_cp   uint16 cp16[nk+1]    first candidate of commodity i, relative to p0
-//   off_loc  uint8  loc8[stride][np]    (index i of every path, then index i+1, ...)
+//   off_cq   uint16 cq16[nk+1]    the same with every commodity padded to a multiple of 4
+//   off_loc  uint8  loc8[stride][npad]  (index i of every padded candidate, then index i+1,
+//                                        ...): four consecutive candidates are one 32-bit word
 #ifndef NIMBLE_REC_KB
 #define NIMBLE_REC_KB 4
 #endif

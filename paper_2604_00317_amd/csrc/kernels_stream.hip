@@ -60,7 +60,17 @@ __global__ __launch_bounds__(kBlock) void k_argmin(int K, const int32_t *__restr
 // lanes per commodity add S prices per candidate (8-bit table indices) from LDS in CSR order -- padding slots read
 // +0.0 -- and reduce (cost, index) across the group.  The sums are the same IEEE operations in
 // the same order as in the untiled kernel.
-constexpr int kRecWaves = 4;     // records (waves) per workgroup
+constexpr int kRecWaves = 4;     // independent waves per workgroup
+constexpr int kRecPerWave = 1;   // records a wave walks (the next one prefetched into registers)
+
+// Orders the LDS accesses of one wave: a wave's LDS operations execute in issue order, so the
+// lanes of a wave can exchange data through LDS once the compiler keeps the accesses in order.
+__device__ __forceinline__ void wave_lds_sync()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
 
 template <int L, int S, bool MAXC>
 __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records, int lds_per_wave,
@@ -70,78 +80,107 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records, 
                                                       uint32_t *__restrict__ count,
                                                       uint8_t *__restrict__ choice2)
 {
-    // dynamic LDS: the record (kRecBytes) followed by the price table, sized by the launcher
-    // for the largest link table of the topology
+    // dynamic LDS, one private slice per wave: the record (kRecBytes) followed by the price
+    // table, sized by the launcher for the largest link table of the topology.  The waves of a
+    // workgroup never synchronise with each other.
     extern __shared__ __align__(16) uint8_t s_all[];
-    uint8_t *s_rec = s_all + (threadIdx.x >> 6) * lds_per_wave;     // this wave's slice
+    uint8_t *s_rec = s_all + (threadIdx.x >> 6) * lds_per_wave;
     double *s_price = reinterpret_cast<double *>(s_rec + kRecBytes);
     constexpr int kGroups = kWave / L;
+    constexpr int kLoads = kRecBytes / 1024;
     const int lane = threadIdx.x & (kWave - 1);
     const int g = lane / L;
     const int j = lane % L;
-    // waves past the last record work on it again (idempotent up to the count, which they
-    // skip) so that every wave reaches the workgroup barriers
-    const int rec_raw = blockIdx.x * kRecWaves + (threadIdx.x >> 6);
-    const bool live = rec_raw < n_records;
-    const int rec = live ? rec_raw : n_records - 1;
+    const int n_waves = gridDim.x * kRecWaves;
+    int rec = blockIdx.x * kRecWaves + (threadIdx.x >> 6);
+    if (rec >= n_records) return;                       // wave-uniform
+    // one 16-byte load per lane and KiB of record, all requested at once
+    u32x4 v[kLoads];
     {
-        // one 16-byte load per lane and KiB of record, all requested before any is stored
         const u32x4 *src = reinterpret_cast<const u32x4 *>(records + size_t(rec) * kRecBytes);
-        constexpr int kLoads = kRecBytes / 1024;
-        u32x4 v[kLoads];
 #pragma unroll
         for (int it = 0; it < kLoads; ++it) v[it] = stream_load(src + it * kWave + lane);
+    }
+    for (; rec < n_records; rec += n_waves) {           // wave-uniform
+        wave_lds_sync();                                // the previous record is done with LDS
 #pragma unroll
         for (int it = 0; it < kLoads; ++it)
             reinterpret_cast<u32x4 *>(s_rec)[it * kWave + lane] = v[it];
-    }
-    __syncthreads();
-    const int k0 = *reinterpret_cast<const int32_t *>(s_rec);
-    const int p0 = *reinterpret_cast<const int32_t *>(s_rec + 4);
-    const uint16_t *h16 = reinterpret_cast<const uint16_t *>(s_rec + 8);
-    const int nk = h16[0], np_rec = h16[1], nl = h16[2];
-    const int32_t *links = reinterpret_cast<const int32_t *>(s_rec + kRecHeader);
-    const uint16_t *cp16 = reinterpret_cast<const uint16_t *>(s_rec + h16[3]);
-    const uint8_t *loc8 = s_rec + h16[4];
-    const int32_t *sig = reinterpret_cast<const int32_t *>(s_rec + h16[5]);
-    for (int i = lane; i < nl; i += kWave) s_price[i] = price[links[i]];
-    if (lane == 0) s_price[nl] = 0.0;
-    __syncthreads();
-    const int rounds = (nk + kGroups - 1) / kGroups;
-    for (int r = 0; r < rounds; ++r) {            // wave-uniform: all lanes reach the reduction
-        const int c = r * kGroups + g;
-        double best = __builtin_inf();
-        int bj = 0x7FFFFFFF;
-        int p_lo = 0;
-        if (c < nk) {
-            p_lo = cp16[c];
-            const int np = cp16[c + 1] - p_lo;
-            if (j < np) bj = j;
-            for (int jj = j; jj < np; jj += L) {
-                const uint8_t *lp = loc8 + (p_lo + jj);
-                int idx[S];
+        wave_lds_sync();
+        const int k0 = *reinterpret_cast<const int32_t *>(s_rec);
+        const int p0 = *reinterpret_cast<const int32_t *>(s_rec + 4);
+        const uint16_t *h16 = reinterpret_cast<const uint16_t *>(s_rec + 8);
+        const int nk = h16[0], nl = h16[2], npad_rec = h16[7];
+        const int32_t *links = reinterpret_cast<const int32_t *>(s_rec + kRecHeader);
+        const uint16_t *cp16 = reinterpret_cast<const uint16_t *>(s_rec + h16[3]);
+        const uint8_t *loc8 = s_rec + h16[4];
+        const int32_t *sig = reinterpret_cast<const int32_t *>(s_rec + h16[5]);
+        const uint16_t *cq16 = reinterpret_cast<const uint16_t *>(s_rec + h16[6]);
+        // prices of the link table: always four gathers per lane (entries past the table
+        // re-read its last link), so that the record prefetch below, issued after them, can
+        // stay in flight while the gathers are consumed
+        double pr[4];
 #pragma unroll
-                for (int i = 0; i < S; ++i) idx[i] = lp[i * np_rec];
-                double cst = 0.0;
+        for (int q = 0; q < 4; ++q) {
+            const int i = lane + q * kWave;
+            pr[q] = price[links[i < nl ? i : nl - 1]];
+        }
+        // the next record of this wave (the last one re-reads itself)
+        {
+            const int nxt = rec + n_waves < n_records ? rec + n_waves : rec;
+            const u32x4 *src = reinterpret_cast<const u32x4 *>(records + size_t(nxt) * kRecBytes);
 #pragma unroll
-                for (int i = 0; i < S; ++i) {
-                    const double pe = s_price[idx[i]];
-                    if constexpr (MAXC) cst = (pe > cst) ? pe : cst;
-                    else cst = cst + pe;
-                }
-                if (cst < best) {
-                    best = cst;
-                    bj = jj;
+            for (int it = 0; it < kLoads; ++it) v[it] = stream_load(src + it * kWave + lane);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int i = lane + q * kWave;
+            if (i < nl) s_price[i] = pr[q];
+        }
+        if (lane == 0) s_price[nl] = 0.0;
+        wave_lds_sync();
+        const int rounds = (nk + kGroups - 1) / kGroups;
+        for (int r = 0; r < rounds; ++r) {        // wave-uniform: all lanes reach the reduction
+            const int c = r * kGroups + g;
+            double best = __builtin_inf();
+            int bj = 0x7FFFFFFF;
+            int p_lo = 0;
+            if (c < nk) {
+                p_lo = cp16[c];
+                const int np = cp16[c + 1] - p_lo;
+                const int q_lo = cq16[c];
+                if (4 * j < np) bj = 4 * j;
+                // lane j scans the quads j, j+L, ... of the commodity: the S table indices of
+                // four consecutive candidates come as S aligned 32-bit words
+                for (int jq = 4 * j; jq < np; jq += 4 * L) {
+                    const uint32_t *lp = reinterpret_cast<const uint32_t *>(loc8 + q_lo + jq);
+                    uint32_t w[S];
+#pragma unroll
+                    for (int i = 0; i < S; ++i) w[i] = lp[i * (npad_rec >> 2)];
+#pragma unroll
+                    for (int c4 = 0; c4 < 4; ++c4) {
+                        double cst = 0.0;
+#pragma unroll
+                        for (int i = 0; i < S; ++i) {
+                            const double pe = s_price[(w[i] >> (8 * c4)) & 0xFFu];
+                            if constexpr (MAXC) cst = (pe > cst) ? pe : cst;
+                            else cst = cst + pe;
+                        }
+                        if (jq + c4 < np && cst < best) {      // padding never competes
+                            best = cst;
+                            bj = jq + c4;
+                        }
+                    }
                 }
             }
-        }
-        bj = group_argmin_two_pass<L>(best, bj);
-        if (live && c < nk && j == 0) {
-            choice[k0 + c] = static_cast<uint8_t>(bj);
-            const int sg = sig[c];
-            if (sg >= 0) choice2[sg] = static_cast<uint8_t>(bj);   // copy in sigma order
-            // counts are kept only when the choices are not logged per iteration
-            if (count != nullptr) count[p0 + p_lo + bj] += 1u;
+            bj = group_argmin_two_pass<L>(best, bj);
+            if (c < nk && j == 0) {
+                choice[k0 + c] = static_cast<uint8_t>(bj);
+                const int sg = sig[c];
+                if (sg >= 0) choice2[sg] = static_cast<uint8_t>(bj);   // copy in sigma order
+                // counts are kept only when the choices are not logged per iteration
+                if (count != nullptr) count[p0 + p_lo + bj] += 1u;
+            }
         }
     }
 }
@@ -274,10 +313,12 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, uint8_t *choice, uint32_t
 {
     if (t.n_records > 0) {
         const int rec_lds = (kRecBytes + 8 * (t.rec_max_links + 1) + 15) & ~15;
+        const int rpw = t.rec_per_wave > 0 ? t.rec_per_wave : kRecPerWave;
+        const int rec_grid = (t.n_records + kRecWaves * rpw - 1) / (kRecWaves * rpw);
 #define NIMBLE_REC_LAUNCH(SS)                                                                  \
     case SS:                                                                                   \
         hipLaunchKernelGGL((k_argmin_rec<L, SS, MAXC>),                                        \
-                           dim3((t.n_records + kRecWaves - 1) / kRecWaves),                    \
+                           dim3(rec_grid),                                                     \
                            dim3(kWave * kRecWaves), kRecWaves * rec_lds, s, t.n_records,       \
                            rec_lds, t.records, t.price, choice, count, t.choice2);             \
         return;
@@ -310,11 +351,13 @@ void launch_argmin_l(const DeviceTopo &t, uint8_t *choice, uint32_t *count, hipS
     // as a record typically holds, each lane scanning several candidates
     int L = lanes_per_commodity(t.pmax);
     if (t.n_records > 0) {
+        // record kernel: a lane scans quads of four candidates; one lane per quad of the
+        // largest commodity unless that leaves too few commodities side by side
+        const int quads = (t.pmax + 3) / 4;
+        L = 1;
+        while (L < quads && L < kWave) L <<= 1;
         const int per_rec = (t.K + t.n_records - 1) / t.n_records;     // average, rounded up
-        int groups = 1;
-        while (groups < per_rec && groups < kWave) groups <<= 1;
-        const int l_rec = kWave / groups;
-        if (l_rec < L) L = l_rec;
+        while (L > 1 && (kWave / L) * 2 <= per_rec && (kWave / L) < 8) L >>= 1;
         if (t.rec_lanes > 0) L = t.rec_lanes;
     }
     const int grid = blocks_for(static_cast<int64_t>(t.K) * L, kBlock, 1 << 20);
