@@ -385,17 +385,23 @@ __device__ __forceinline__ double update_phase(int E, double eps, double invrho,
             s0 = link_sslot_ptr[e];
             s1 = link_sslot_ptr[e + 1];
         }
+        // the link's own state is requested before the partial sums are waited for
+        double ic = 0.0, s_old = 0.0, l_old = 0.0;
+        if (e < E && l == 0) {
+            ic = invcap[e];
+            s_old = S[e];
+            l_old = len[e];
+        }
         // octet slots, then (rarely any) single-pair slots
         const double load = row_partial_sum(c0, c1, l, partial) + row_partial_sum(s0, s1, l, partial);
         if (e < E && l == 0) {
-            const double ic = invcap[e];
             const double u = load * ic;
-            const double s_new = S[e] + u;
+            const double s_new = s_old + u;
             S[e] = s_new;
             const double g = u * invrho;
             const double t1 = eps * g;
             const double t2 = 1.0 + t1;
-            const double ln = len[e] * t2;
+            const double ln = l_old * t2;
             len[e] = ln;
             price[e] = MAXC ? ln : ln * ic;
             smax = fmax(smax, s_new);
