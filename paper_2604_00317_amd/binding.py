@@ -242,19 +242,19 @@ def nimble_host_build_reverse(n_links, n_comm, comm_path_ptr, n_paths, path_link
 
 def nimble_host_records_roundtrip(n_links, n_comm, comm_path_ptr, n_paths, path_link_ptr,
                                 path_links):
-    """Host-only: (links read back through the tiles, tile of every path, number of tiles)."""
+    """Host-only: (links read back through the records, record of every path, number of records)."""
     cp = _host(comm_path_ptr, np.int32)
     lp = _host(path_link_ptr, np.int32)
     pl = _host(path_links, np.int32)
     links_out = np.full(max(int(lp[-1]), 1), -1, dtype=np.int32)
-    path_tile = np.full(max(n_paths, 1), -1, dtype=np.int32)
-    n_tiles = ctypes.c_int32(0)
+    path_rec = np.full(max(n_paths, 1), -1, dtype=np.int32)
+    n_recs = ctypes.c_int32(0)
     st = load_library().nimble_host_records_roundtrip(n_links, n_comm, _hp(cp), n_paths, _hp(lp),
-                                                    _hp(pl), _hp(links_out), _hp(path_tile),
-                                                    ctypes.byref(n_tiles))
+                                                    _hp(pl), _hp(links_out), _hp(path_rec),
+                                                    ctypes.byref(n_recs))
     if st != NIMBLE_OK:
-        raise NimbleError(st, "tile round trip failed")
-    return links_out[:int(lp[-1])], path_tile[:n_paths], int(n_tiles.value)
+        raise NimbleError(st, "record round trip failed")
+    return links_out[:int(lp[-1])], path_rec[:n_paths], int(n_recs.value)
 
 
 def nimble_host_layout_stats(n_links, n_comm, comm_path_ptr, n_paths, path_link_ptr, path_links):

@@ -147,20 +147,6 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
             }
         }
 
-    // fixed-size chunks; a link with an empty row gets no chunk (its load is 0)
-    t.chunk_pairs = kRowLanesHost * 8;
-    t.link_chunk_ptr.assign(n_links + 1, 0);
-    t.chunk_begin.clear();
-    t.chunk_end.clear();
-    for (int32_t e = 0; e < n_links; ++e) {
-        for (int32_t b = t.rev_ptr[e]; b < t.rev_ptr[e + 1]; b += t.chunk_pairs) {
-            t.chunk_begin.push_back(b);
-            t.chunk_end.push_back(b + t.chunk_pairs < t.rev_ptr[e + 1] ? b + t.chunk_pairs
-                                                                      : t.rev_ptr[e + 1]);
-        }
-        t.link_chunk_ptr[e + 1] = static_cast<int32_t>(t.chunk_begin.size());
-    }
-
     // ---- streaming layout of the reverse rows: flat octets (two numberings) + single pairs --
     t.oct_base.clear();
     t.oct_mask.clear();
@@ -297,7 +283,6 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
     // pad the flat array to whole passes: padding octets have no masks and start a slot of
     // their own that no link owns
     while (t.oct_base.size() % 64) {
-        if (t.oct_base.size() % 64 == 0) t.pass_first_slot.push_back(slot);
         t.oct_base.push_back(kOctNewSlot);
         t.oct_mask.resize(t.oct_mask.size() + 8, 0u);
     }

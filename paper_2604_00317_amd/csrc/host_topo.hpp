@@ -1,6 +1,7 @@
 // Host-side preparation of a topology: validation of the two-level CSR, the reverse
-// link -> (commodity, path set) CSR cut into fixed-size chunks, and the tiling of the forward
-// CSR with per-tile link tables.  No HIP calls here.
+// link -> (commodity, candidate set) CSR in its two device layouts (pairs for the resident
+// kernel, flat octets plus single pairs for the streaming kernels), and the repacking of the
+// forward CSR into self-contained records.  No HIP calls here.
 #pragma once
 #include <cstdint>
 #include <string>
@@ -82,14 +83,10 @@ struct HostTopo {
     int32_t lmax = 0;       // most links of any path
     std::vector<double> invcap;
     // reverse CSR in pair units, rows padded to kPairAlign pairs with (commodity K, mask 0)
-    int32_t chunk_pairs = 128;           // pairs per reduction chunk (16 lanes x pairs per lane)
     std::vector<int32_t> rev_ptr;        // [E+1], padded offsets in pairs
     std::vector<uint32_t> rev_pair;      // [2 * rev_ptr[E]], words A,B interleaved
     std::vector<int32_t> rev_rowlen;     // [E], unpadded row lengths in pairs
     int64_t n_pairs = 0;                 // unpadded total
-    std::vector<int32_t> chunk_begin;    // [n_chunks], pair offsets
-    std::vector<int32_t> chunk_end;      // [n_chunks]
-    std::vector<int32_t> link_chunk_ptr; // [E+1]
     // streaming layout
     std::vector<uint32_t> oct_base;      // [n_oct_padded]: base id | flags, padded to 64
     std::vector<uint32_t> oct_mask;      // [8 * n_oct_padded]; per pass: words 0..3 of its 64

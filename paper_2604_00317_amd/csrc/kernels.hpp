@@ -18,7 +18,7 @@ struct DeviceTopo {
     const int32_t *path_links; // [nnz]
     // forward CSR repacked into self-contained 4 KiB records (n_records = 0: not available)
     int32_t n_records;
-    int32_t rec_stride;        // 16-bit link indices per candidate path
+    int32_t rec_stride;        // 8-bit link indices per candidate path
     int32_t rec_max_links;     // largest link table of any record
     int32_t rec_lanes;         // lanes per commodity in the record kernel (0: automatic)
     int32_t rec_per_wave;      // records a wave walks in the record kernel (0: default)

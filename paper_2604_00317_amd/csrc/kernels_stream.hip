@@ -242,16 +242,29 @@ __global__ __launch_bounds__(kBlock) void k_load_reduce(ReduceArgs a)
                                         n_waves - 1 - wave, n_waves, lane);
 }
 
-// rho = max_e (demand that can reach e) / cap_e; scalars[0] = 1/rho (0 when rho = 0)
-__global__ __launch_bounds__(1024) void k_width(int E, const int32_t *__restrict__ link_slot_ptr,
-                                                const int32_t *__restrict__ link_sslot_ptr,
-                                                const double *__restrict__ partial,
-                                                const double *__restrict__ invcap,
-                                                double *__restrict__ scalars)
+// rho = max_e (demand that can reach e) / cap_e, in two steps: every block leaves the maximum
+// over its links in scalars[1 + block], then one block folds those into scalars[0] = 1/rho
+// (0 when rho = 0).  A maximum does not depend on the order it is taken in.
+__global__ __launch_bounds__(kBlock) void k_width(int E, const int32_t *__restrict__ link_slot_ptr,
+                                                  const int32_t *__restrict__ link_sslot_ptr,
+                                                  const double *__restrict__ partial,
+                                                  const double *__restrict__ invcap,
+                                                  double *__restrict__ scalars)
 {
     __shared__ double red[16];
-    double m = width_phase(E, link_slot_ptr, link_sslot_ptr, partial, invcap, threadIdx.x >> 6,
-                           blockDim.x >> 6, threadIdx.x & (kWave - 1));
+    const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int n_waves = (gridDim.x * blockDim.x) >> 6;
+    double m = width_phase(E, link_slot_ptr, link_sslot_ptr, partial, invcap, wave, n_waves,
+                           threadIdx.x & (kWave - 1));
+    m = block_max(m, red);
+    if (threadIdx.x == 0) scalars[1 + blockIdx.x] = m;
+}
+
+__global__ __launch_bounds__(kBlock) void k_width_fold(int n_blocks, double *__restrict__ scalars)
+{
+    __shared__ double red[16];
+    double m = 0.0;
+    for (int b = threadIdx.x; b < n_blocks; b += blockDim.x) m = fmax(m, scalars[1 + b]);
     m = block_max(m, red);
     if (threadIdx.x == 0) scalars[0] = (m > 0.0) ? 1.0 / m : 0.0;
 }
@@ -420,8 +433,9 @@ void launch_init(const DeviceTopo &t, const double *demand, hipStream_t s)
 void launch_width(const DeviceTopo &t, const double *demand, hipStream_t s)
 {
     launch_reduce_mode<1>(t, t.choice, demand, s);
-    hipLaunchKernelGGL(k_width, dim3(1), dim3(1024), 0, s, t.E, t.link_slot_ptr,
-                       t.link_sslot_ptr, t.partial, t.invcap, t.scalars);
+    hipLaunchKernelGGL(k_width, dim3(t.n_update_blocks), dim3(kBlock), 0, s, t.E,
+                       t.link_slot_ptr, t.link_sslot_ptr, t.partial, t.invcap, t.scalars);
+    hipLaunchKernelGGL(k_width_fold, dim3(1), dim3(kBlock), 0, s, t.n_update_blocks, t.scalars);
 }
 
 void launch_argmin(const DeviceTopo &t, uint8_t *choice, uint32_t *count, hipStream_t s)

@@ -146,18 +146,6 @@ __device__ __forceinline__ double segmented_scan_f64(double v, int start, int la
     return v;
 }
 
-// Sum over the 64 lanes in a fixed butterfly order (the same tree on every run).
-__device__ __forceinline__ double wave_sum(double v)
-{
-    v = v + partner_f64<1>(v);
-    v = v + partner_f64<2>(v);
-    v = v + partner_f64<4>(v);
-    v = v + partner_f64<8>(v);
-    v = v + partner_f64<16>(v);
-    v = v + partner_f64<32>(v);
-    return v;
-}
-
 __device__ __forceinline__ double wave_max(double v)
 {
     v = fmax(v, partner_f64<1>(v));
