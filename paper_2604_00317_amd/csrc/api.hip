@@ -3,6 +3,7 @@
 // fallback -- without a usable GPU the device calls fail and the status says so.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -154,8 +155,12 @@ nimble_status_t solve_stream(nimble_topo *topo, const double *d_traffic, double 
         uint8_t *row = logged ? topo->choice_log + topo->log_stride * static_cast<size_t>(it)
                               : d.choice;
         nimble::launch_argmin(d, row, logged ? nullptr : d.count, s);
-        nimble::launch_load_reduce(d, row, d_traffic, s);
-        nimble::launch_update(d, eps, s);
+        if (d.n_blocks > 0) {
+            nimble::launch_reduce_update(d, row, d_traffic, eps, s);
+        } else {
+            nimble::launch_load_reduce(d, row, d_traffic, s);
+            nimble::launch_update(d, eps, s);
+        }
     }
     nimble::launch_epilogue(d, iters, logged ? nullptr : d.count, d_splits, d_lambda, s);
     if (logged)
@@ -210,6 +215,10 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
             const int v = std::atoi(env);
             if (v >= 1 && v <= nimble::kRecMaxComm) h.rec_comm_cap = v;
         }
+        if (const char *env = std::getenv("NIMBLE_TUNE_BLOCK_PASSES")) {
+            const int v = std::atoi(env);
+            if (v >= 1 && v <= 1024) h.blk_passes = v;
+        }
         nimble::build_host_topo(n_links, cap, n_comm, comm_path_ptr, n_paths, path_link_ptr,
                                 path_links, h);
     } catch (const std::bad_alloc &) {
@@ -248,6 +257,7 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     d.n_slots = h.n_slots;
     d.cost_max = (flags & NIMBLE_COST_MAX) != 0u;
     d.n_update_blocks = (h.E + 15) / 16;   // 256-thread blocks, one 16-lane row per link
+    d.n_blocks = std::getenv("NIMBLE_TUNE_NO_LINK_BLOCKS") ? 0 : h.n_blocks;
 
 #define NIMBLE_TRY(call, what)                        \
     do {                                              \
@@ -279,8 +289,10 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     NIMBLE_TRY(upload(t, h.schunk_begin.data(), h.schunk_begin.size(), &d.schunk_begin), "schunk");
     NIMBLE_TRY(upload(t, h.schunk_end.data(), h.schunk_end.size(), &d.schunk_end), "schunk");
     NIMBLE_TRY(upload(t, h.schunk_slot.data(), h.schunk_slot.size(), &d.schunk_slot), "schunk");
-    NIMBLE_TRY(upload(t, h.link_slot_ptr.data(), h.link_slot_ptr.size(), &d.link_slot_ptr),
-               "link_slot_ptr");
+    NIMBLE_TRY(upload(t, h.pos_link.data(), h.pos_link.size(), &d.pos_link), "pos_link");
+    NIMBLE_TRY(upload(t, h.pos_slot_ptr.data(), h.pos_slot_ptr.size(), &d.pos_slot_ptr),
+               "pos_slot_ptr");
+    NIMBLE_TRY(upload(t, h.blk_desc.data(), h.blk_desc.size(), &d.blk_desc), "blk_desc");
     NIMBLE_TRY(upload(t, h.sigma.data(), h.sigma.size(), &d.sigma), "sigma");
     d.sigma_size = h.sigma_size;
     NIMBLE_TRY(allocate(t, static_cast<size_t>(h.sigma_size), &d.choice2), "choice2");
@@ -289,13 +301,18 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     NIMBLE_TRY(hipMemset(d.demand2, 0, sizeof(double) * static_cast<size_t>(h.sigma_size)),
                "demand2 clear");
     NIMBLE_TRY(upload(t, h.invcap.data(), h.invcap.size(), &d.invcap), "invcap");
+    NIMBLE_TRY(upload(t, h.invcap_pos.data(), h.invcap_pos.size(), &d.invcap_pos), "invcap_pos");
     NIMBLE_TRY(allocate(t, static_cast<size_t>(h.E), &d.len), "len");
     NIMBLE_TRY(allocate(t, static_cast<size_t>(h.E), &d.price), "price");
     NIMBLE_TRY(allocate(t, static_cast<size_t>(h.E), &d.S), "S");
-    NIMBLE_TRY(allocate(t, static_cast<size_t>(h.K) + 1, &d.choice), "choice");
+    // 8 spare entries: the last octet of a row may start at the last multiple of 4 below K
+    NIMBLE_TRY(allocate(t, static_cast<size_t>(h.K) + 8, &d.choice), "choice");
     NIMBLE_TRY(allocate(t, static_cast<size_t>(h.P), &d.count), "count");
     NIMBLE_TRY(allocate(t, static_cast<size_t>(d.n_slots), &d.partial), "partial");
-    NIMBLE_TRY(allocate(t, static_cast<size_t>(d.n_update_blocks) + 1, &d.scalars), "scalars");
+    // one maximum of S per update block, or per wave of the fused kernel's link blocks
+    NIMBLE_TRY(allocate(t, static_cast<size_t>(std::max(d.n_update_blocks, 4 * d.n_blocks)) + 1,
+                        &d.scalars),
+               "scalars");
     {
         unsigned char *sw = nullptr;
         NIMBLE_TRY(allocate(t, nimble::persistent_sync_bytes(), &sw), "sync words");
@@ -319,6 +336,12 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
                       4LL * static_cast<int64_t>(h.single_pair.size()) + 12LL * d.n_schunks +
                       8LL * d.n_slots;
     t->bytes_update = 8LL * d.n_slots + 8LL * (h.E + 1) + 56LL * h.E;
+    if (d.n_blocks > 0) {
+        // one kernel: the slot partials stay in LDS; per block two table entries and one maximum
+        t->bytes_reduce = 36LL * static_cast<int64_t>(h.oct_base.size()) + 4LL * d.n_passes +
+                          8LL * h.E + 56LL * h.E + 64LL * d.n_blocks;
+        t->bytes_update = 0;
+    }
     t->bytes_per_iter = t->bytes_argmin + t->bytes_reduce + t->bytes_update;
     *out = t;
     return NIMBLE_OK;
@@ -436,6 +459,8 @@ nimble_status_t nimble_debug_run_phase(nimble_topo_t *topo, int32_t phase, int32
     g_last_error.clear();
     if (!topo || !d_traffic) return fail(NIMBLE_ERR_INVALID, "NULL argument");
     if (phase < 0 || phase > 2 || reps < 1) return fail(NIMBLE_ERR_INVALID, "bad phase or reps");
+    if (phase == 2 && topo->d.n_blocks > 0)
+        return fail(NIMBLE_ERR_INVALID, "the length update is part of phase 1 on this topology");
     if (!topo->state_ready)
         return fail(NIMBLE_ERR_INVALID, "run a streaming-regime solve on this topology first");
     nimble_status_t st = check_device(topo);
@@ -444,6 +469,8 @@ nimble_status_t nimble_debug_run_phase(nimble_topo_t *topo, int32_t phase, int32
     for (int32_t r = 0; r < reps; ++r) {
         uint8_t *row = topo->log_rows > 0 ? topo->choice_log : topo->d.choice;
         if (phase == 0) nimble::launch_argmin(topo->d, row, topo->log_rows > 0 ? nullptr : topo->d.count, s);
+        else if (phase == 1 && topo->d.n_blocks > 0)
+            nimble::launch_reduce_update(topo->d, row, d_traffic, 0.0, s);
         else if (phase == 1) nimble::launch_load_reduce(topo->d, row, d_traffic, s);
         else nimble::launch_update(topo->d, 0.0, s);   // eps 0: lengths stay as they are
     }

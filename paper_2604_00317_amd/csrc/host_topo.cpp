@@ -4,6 +4,8 @@
 #include <climits>
 #include <cmath>
 #include <cstring>
+#include <functional>
+#include <queue>
 
 namespace nimble {
 
@@ -154,7 +156,6 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
     t.single_pair.clear();
     t.n_single_pairs = 0;
     t.schunk_begin.clear(); t.schunk_end.clear(); t.schunk_slot.clear();
-    t.link_slot_ptr.assign(n_links + 1, 0);
     t.link_sslot_ptr.assign(n_links + 1, 0);
     t.sigma.assign(n_comm, -1);
     const int32_t sgl_chunk = kRowLanesHost * kSinglesPerLane;
@@ -172,7 +173,8 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                 while (i + cnt < items.size() && items[i + cnt].key >= 0 &&
                        items[i + cnt].key < base + 8)
                     ++cnt;
-            // an octet must not read past its choice array: slide the window back at the end
+            // an octet must not read past its choice array (which has 8 spare entries when
+            // indexed by commodity id): slide the window back at the end
             const int32_t b8 = base + 8 <= key_limit ? base : ((key_limit - 8) & ~3);
             const bool fits = cnt > 0 && b8 >= 0 && items[i].key >= b8 &&
                               items[i + cnt - 1].key < b8 + 8;
@@ -199,7 +201,7 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
             const int32_t kk = static_cast<int32_t>(a & kCommMask);
             items.push_back({one_window(kk) ? kk : -1, a, b});    // -1: never in an octet
         }
-        pack(items, n_comm, kOctetMinFill, 0u, row_base[e], row_mask[e], left1[e]);
+        pack(items, n_comm + 8, kOctetMinFill, 0u, row_base[e], row_mask[e], left1[e]);
     }
     // second numbering: left-over commodities in order of first appearance, every row's new
     // run starting at a multiple of 8
@@ -219,9 +221,10 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
         }
     }
     t.sigma_size = ((next_sigma + 7) & ~7) + 8;
-    // passes 2 and 3 and the flat arrays
+    // passes 2 and 3 of every row; single pairs (commodities with several windows) and their
+    // chunks in link order
     t.n_octets_sigma = 0;
-    int32_t slot = 0;
+    t.n_octets = 0;
     for (int32_t e = 0; e < n_links; ++e) {
         std::vector<Item> items, left2, left3;
         for (const Item &it : left1[e]) {
@@ -229,6 +232,7 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
             x.key = it.key < 0 ? -1 : t.sigma[it.a & kCommMask];
             items.push_back(x);
         }
+        left1[e].clear(); left1[e].shrink_to_fit();
         std::stable_sort(items.begin(), items.end(), [](const Item &x, const Item &y) {
             return (x.key < 0 ? INT32_MAX : x.key) < (y.key < 0 ? INT32_MAX : y.key);
         });
@@ -241,25 +245,8 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
             const uint32_t kx = x.a & kCommMask, ky = y.a & kCommMask;
             return kx != ky ? kx < ky : ((x.a >> kWindowShift) & 3u) < ((y.a >> kWindowShift) & 3u);
         });
-        pack(left2, n_comm, 1, 0u, row_base[e], row_mask[e], left3);
-        // append the row to the flat arrays; a new slot at the row's first octet and at
-        // every pass boundary
-        t.link_slot_ptr[e] = slot;
-        for (size_t q = 0; q < row_base[e].size(); ++q) {
-            const size_t pos = t.oct_base.size();
-            uint32_t w = row_base[e][q];
-            if (q == 0 || pos % 64 == 0) {
-                w |= kOctNewSlot;
-                if (pos % 64 == 0) t.pass_first_slot.push_back(slot);
-                ++slot;
-            }
-            t.oct_base.push_back(w);
-            t.oct_mask.insert(t.oct_mask.end(), row_mask[e].begin() + 8 * q,
-                              row_mask[e].begin() + 8 * q + 8);
-        }
-        row_base[e].clear(); row_base[e].shrink_to_fit();
-        row_mask[e].clear(); row_mask[e].shrink_to_fit();
-        // single pairs (commodities with several windows)
+        pack(left2, n_comm + 8, 1, 0u, row_base[e], row_mask[e], left3);
+        t.n_octets += static_cast<int64_t>(row_base[e].size());
         const int32_t s_first = static_cast<int32_t>(t.single_pair.size() / 2);
         for (const Item &it : left3) {
             t.single_pair.push_back(it.a);
@@ -277,19 +264,94 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
             t.schunk_end.push_back(b + sgl_chunk < s_last ? b + sgl_chunk : s_last);
         }
     }
-    t.link_slot_ptr[n_links] = slot;
-    t.n_oct_slots = slot;
-    t.n_octets = static_cast<int64_t>(t.oct_base.size());
-    // pad the flat array to whole passes: padding octets have no masks and start a slot of
-    // their own that no link owns
-    while (t.oct_base.size() % 64) {
-        t.oct_base.push_back(kOctNewSlot);
-        t.oct_mask.resize(t.oct_mask.size() + 8, 0u);
+
+    // ---- link blocks and the order of the rows in the flat array ---------------------------
+    // The rows are dealt to n_blk blocks, largest row first, each to the block that is lightest
+    // so far (a row weighs its octets plus a small constant for the link's update), so that all
+    // blocks carry the same work within one small row.  Inside a block the links ascend by id.
+    // pos_link lists the links in flat order; pos_slot_ptr gives the slots of each position.
+    const int64_t kLinkWeight = 4;
+    const int64_t total_passes = (t.n_octets + 63) / 64;
+    int64_t blk_passes = t.blk_passes;
+    if (blk_passes <= 0) {                       // default: about six blocks per compute unit
+        blk_passes = (total_passes + 1535) / 1536;
+        if (blk_passes < 3) blk_passes = 3;
     }
-    if (t.oct_base.empty()) {             // keep one (empty) pass
+    int64_t n_blk = (total_passes + blk_passes - 1) / blk_passes;
+    const int64_t by_links = (static_cast<int64_t>(n_links) + kBlkMaxLinks / 2 - 1) / (kBlkMaxLinks / 2);
+    if (n_blk < by_links) n_blk = by_links;
+    if (n_blk < 1) n_blk = 1;
+    if (n_blk > n_links) n_blk = n_links;
+    std::vector<std::vector<int32_t>> blk_members(static_cast<size_t>(n_blk));
+    {
+        std::vector<int32_t> by_size(n_links);
+        for (int32_t e = 0; e < n_links; ++e) by_size[e] = e;
+        std::stable_sort(by_size.begin(), by_size.end(), [&](int32_t x, int32_t y) {
+            return row_base[x].size() > row_base[y].size();
+        });
+        using Load = std::pair<int64_t, int32_t>;         // (weight so far, block)
+        std::priority_queue<Load, std::vector<Load>, std::greater<Load>> lightest;
+        for (int32_t b = 0; b < n_blk; ++b) lightest.push({0, b});
+        for (int32_t e : by_size) {
+            Load top = lightest.top();
+            lightest.pop();
+            blk_members[top.second].push_back(e);
+            top.first += static_cast<int64_t>(row_base[e].size()) + kLinkWeight;
+            lightest.push(top);
+        }
+    }
+    bool blocks_fit = true;
+    int32_t slot = 0;
+    t.pos_link.clear();
+    t.pos_slot_ptr.clear();
+    t.blk_pos_ptr.assign(1, 0);
+    t.blk_pass_ptr.assign(1, 0);
+    for (int64_t b = 0; b < n_blk; ++b) {
+        std::vector<int32_t> &members = blk_members[b];
+        std::sort(members.begin(), members.end());
+        const int32_t blk_slot0 = slot;
+        for (int32_t e : members) {
+            // append the row to the flat arrays; a new slot at the row's first octet and at
+            // every pass boundary
+            t.pos_link.push_back(e);
+            t.pos_slot_ptr.push_back(slot);
+            for (size_t q = 0; q < row_base[e].size(); ++q) {
+                const size_t pos = t.oct_base.size();
+                uint32_t w = row_base[e][q];
+                if (q == 0 || pos % 64 == 0) {
+                    w |= kOctNewSlot;
+                    if (pos % 64 == 0) t.pass_first_slot.push_back(slot);
+                    ++slot;
+                }
+                t.oct_base.push_back(w);
+                t.oct_mask.insert(t.oct_mask.end(), row_mask[e].begin() + 8 * q,
+                                  row_mask[e].begin() + 8 * q + 8);
+            }
+            row_base[e].clear(); row_base[e].shrink_to_fit();
+            row_mask[e].clear(); row_mask[e].shrink_to_fit();
+        }
+        // the next block starts at a pass boundary: padding octets have no masks and no flags
+        while (t.oct_base.size() % 64) {
+            t.oct_base.push_back(0u);
+            t.oct_mask.resize(t.oct_mask.size() + 8, 0u);
+        }
+        if (slot - blk_slot0 > kBlkMaxSlots || static_cast<int32_t>(members.size()) > kBlkMaxLinks)
+            blocks_fit = false;
+        t.blk_pos_ptr.push_back(static_cast<int32_t>(t.pos_link.size()));
+        t.blk_pass_ptr.push_back(static_cast<int32_t>(t.oct_base.size() / 64));
+    }
+    t.pos_slot_ptr.push_back(slot);
+    t.invcap_pos.resize(n_links);
+    for (int32_t i = 0; i < n_links; ++i) t.invcap_pos[i] = t.invcap[t.pos_link[i]];
+    t.n_oct_slots = slot;
+    int32_t pad_slots = 0;
+    if (t.oct_base.empty()) {             // keep one (empty) pass with a slot no link owns
         t.pass_first_slot.push_back(slot);
-        t.oct_base.assign(64, kOctNewSlot);
+        t.oct_base.assign(64, 0u);
+        t.oct_base[0] = kOctNewSlot;
         t.oct_mask.assign(8 * 64, 0u);
+        pad_slots = 1;
+        blocks_fit = false;
     }
     // masks lane-contiguous inside a pass: words 0..3 of the 64 octets, then words 4..7, so
     // that each of the two 16-byte loads of a lane is part of one contiguous KiB
@@ -303,8 +365,6 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                         t.oct_mask[(ps * 64 + ln) * 8 + w8];
         t.oct_mask.swap(tmp);
     }
-    // padding octets may each open a slot: reserve one slot per padding octet
-    const int32_t pad_slots = 64;
     const int32_t single_slot0 = t.n_oct_slots + pad_slots;
     t.link_sslot_ptr[n_links] = static_cast<int32_t>(t.schunk_begin.size());
     t.schunk_slot.resize(t.schunk_begin.size());
@@ -312,6 +372,18 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
         t.schunk_slot[c] = single_slot0 + static_cast<int32_t>(c);
     for (int32_t e = 0; e <= n_links; ++e) t.link_sslot_ptr[e] += single_slot0;
     t.n_slots = single_slot0 + static_cast<int32_t>(t.schunk_begin.size());
+    // the fused kernel covers topologies whose reverse rows are octets only
+    t.n_blocks = (blocks_fit && t.n_single_pairs == 0)
+                     ? static_cast<int32_t>(t.blk_pos_ptr.size()) - 1 : 0;
+    t.blk_desc.assign(8 * static_cast<size_t>(t.n_blocks > 0 ? t.n_blocks : 1), 0);
+    for (int32_t b = 0; b < t.n_blocks; ++b) {
+        int32_t *d = &t.blk_desc[8 * static_cast<size_t>(b)];
+        d[0] = t.blk_pos_ptr[b];
+        d[1] = t.blk_pos_ptr[b + 1];
+        d[2] = t.blk_pass_ptr[b];
+        d[3] = t.blk_pass_ptr[b + 1];
+        d[4] = t.pos_slot_ptr[t.blk_pos_ptr[b]];
+    }
     if (t.single_pair.empty()) {          // keep the array loadable
         for (int q = 0; q < 2; ++q) {
             t.single_pair.push_back(static_cast<uint32_t>(n_comm));
@@ -570,6 +642,8 @@ extern "C" nimble_status_t nimble_host_layout_stats(int32_t n_links, int32_t n_c
     out[5] = t.n_slots;
     out[6] = t.n_records;
     out[7] = t.rec_stride;
+    out[8] = t.n_blocks;
+    out[9] = static_cast<int64_t>(t.oct_base.size());
     return NIMBLE_OK;
 }
 
@@ -592,16 +666,44 @@ extern "C" nimble_status_t nimble_host_build_reverse_streaming(int32_t n_links, 
     nimble::build_host_topo(n_links, cap.data(), n_comm, comm_path_ptr, n_paths, path_link_ptr,
                             path_links, t);
     // decode the streaming layout the way the reduce kernel walks it: flat octets with slot
-    // flags (slot -> link through link_slot_ptr), sigma octets through the inverse numbering,
+    // flags (slot -> position -> link through pos_slot_ptr and pos_link), sigma octets through the inverse numbering,
     // and chunked single pairs (chunk slot -> link through link_sslot_ptr)
     std::vector<int32_t> inv_sigma(static_cast<size_t>(t.sigma_size), -1);
     for (int32_t k = 0; k < n_comm; ++k)
         if (t.sigma[k] >= 0) inv_sigma[t.sigma[k]] = k;
-    std::vector<int32_t> slot_link(static_cast<size_t>(t.n_slots), -1);
-    for (int32_t e = 0; e < n_links; ++e) {
-        for (int32_t sl = t.link_slot_ptr[e]; sl < t.link_slot_ptr[e + 1]; ++sl) slot_link[sl] = e;
-        for (int32_t sl = t.link_sslot_ptr[e]; sl < t.link_sslot_ptr[e + 1]; ++sl) slot_link[sl] = e;
+    // pos_link must list every link once
+    if (static_cast<int32_t>(t.pos_link.size()) != n_links ||
+        static_cast<int32_t>(t.pos_slot_ptr.size()) != n_links + 1)
+        return NIMBLE_ERR_INVALID;
+    std::vector<int32_t> link_pos(n_links, -1);
+    for (int32_t i = 0; i < n_links; ++i) {
+        const int32_t e = t.pos_link[i];
+        if (e < 0 || e >= n_links || link_pos[e] >= 0) return NIMBLE_ERR_INVALID;
+        link_pos[e] = i;
     }
+    std::vector<int32_t> slot_link(static_cast<size_t>(t.n_slots), -1);
+    for (int32_t i = 0; i < n_links; ++i)
+        for (int32_t sl = t.pos_slot_ptr[i]; sl < t.pos_slot_ptr[i + 1]; ++sl)
+            slot_link[sl] = t.pos_link[i];
+    for (int32_t e = 0; e < n_links; ++e)
+        for (int32_t sl = t.link_sslot_ptr[e]; sl < t.link_sslot_ptr[e + 1]; ++sl) slot_link[sl] = e;
+    // link blocks: every pass of a block holds slots of the block's own links only, and the
+    // block's slots and links fit its capacity
+    std::vector<int32_t> pass_block(t.oct_base.size() / 64, -1);
+    for (int32_t b = 0; b < t.n_blocks; ++b) {
+        if (t.blk_pos_ptr[b] >= t.blk_pos_ptr[b + 1] || t.blk_pass_ptr[b] > t.blk_pass_ptr[b + 1])
+            return NIMBLE_ERR_INVALID;
+        if (t.blk_pos_ptr[b + 1] - t.blk_pos_ptr[b] > nimble::kBlkMaxLinks) return NIMBLE_ERR_INVALID;
+        if (t.pos_slot_ptr[t.blk_pos_ptr[b + 1]] - t.pos_slot_ptr[t.blk_pos_ptr[b]] >
+            nimble::kBlkMaxSlots)
+            return NIMBLE_ERR_INVALID;
+        for (int32_t ps = t.blk_pass_ptr[b]; ps < t.blk_pass_ptr[b + 1]; ++ps) pass_block[ps] = b;
+    }
+    if (t.n_blocks > 0 &&
+        (t.blk_pos_ptr[0] != 0 || t.blk_pos_ptr[t.n_blocks] != n_links ||
+         t.blk_pass_ptr[0] != 0 ||
+         t.blk_pass_ptr[t.n_blocks] != static_cast<int32_t>(t.oct_base.size() / 64)))
+        return NIMBLE_ERR_INVALID;
     std::vector<std::vector<int64_t>> rows(n_links);      // (commodity << 8 | path) per link
     const size_t n_flat = t.oct_base.size();
     int32_t slot = -1;
@@ -610,6 +712,11 @@ extern "C" nimble_status_t nimble_host_build_reverse_streaming(int32_t n_links, 
         if (i % 64 == 0) slot = t.pass_first_slot[i / 64] - 1;
         if (w & nimble::kOctNewSlot) ++slot;
         const int32_t e = slot < t.n_slots ? slot_link[slot] : -1;
+        if (t.n_blocks > 0 && e >= 0) {
+            const int32_t b = pass_block[i / 64];
+            if (b < 0 || link_pos[e] < t.blk_pos_ptr[b] || link_pos[e] >= t.blk_pos_ptr[b + 1])
+                return NIMBLE_ERR_INVALID;
+        }
         const int32_t base = static_cast<int32_t>(w & ~3u);
         for (int32_t s8 = 0; s8 < 8; ++s8) {
             const uint32_t m = t.oct_mask[(i / 64) * 512 + (s8 / 4) * 256 + (i % 64) * 4 + (s8 % 4)];

@@ -45,10 +45,24 @@ constexpr int32_t kPairAlign = 2;             // rows are padded to 16 bytes (2 
 // lane, a "pass").  The low bits of the base word carry two flags: bit 0 = this octet starts a
 // new partial-sum slot (first octet of a row, or of a pass), bit 1 = numbered by sigma.  The
 // slots of a row are consecutive; pass_first_slot gives the slot of the first octet of a pass.
+// Padding octets (no masks, no flags) extend the last slot of their pass by +0.0.
 constexpr int32_t kOctetMinFill = 3;
 constexpr uint32_t kOctNewSlot = 1u;
 constexpr uint32_t kOctSigma = 2u;
 constexpr int32_t kSinglesPerLane = 8;        // a single-pair chunk holds 16 * 8 pairs
+
+// Link blocks and the order of the rows.  The rows are dealt to blocks of equal weight
+// (largest row first, each to the lightest block so far); the flat octet array holds the rows
+// block after block, inside a block by ascending link id.  pos_link[i] is the link whose row
+// comes i-th, pos_slot_ptr[i] .. pos_slot_ptr[i+1] are its slots.  Every block starts at a pass
+// boundary (the tail of its last pass is filled with padding octets that have no masks and
+// open no slot), so that one workgroup can reduce the rows of a block into LDS and apply the
+// length update of those links right away.  A block holds at most kBlkMaxSlots partial-sum
+// slots and kBlkMaxLinks links; a topology that breaks either bound, or one with single
+// pairs, has no blocks (n_blocks = 0) and runs the separate reduce and update kernels over the
+// same arrays.
+constexpr int32_t kBlkMaxSlots = 1024;
+constexpr int32_t kBlkMaxLinks = 512;
 
 // ---- forward CSR records ------------------------------------------------------------------
 // The forward CSR is repacked into self-contained records of kRecBytes bytes, each holding a
@@ -81,7 +95,8 @@ struct HostTopo {
     int64_t nnz = 0;
     int32_t pmax = 0;       // most candidates of any commodity
     int32_t lmax = 0;       // most links of any path
-    std::vector<double> invcap;
+    std::vector<double> invcap;          // [E] by link id
+    std::vector<double> invcap_pos;      // [E] by position (pos_link)
     // reverse CSR in pair units, rows padded to kPairAlign pairs with (commodity K, mask 0)
     std::vector<int32_t> rev_ptr;        // [E+1], padded offsets in pairs
     std::vector<uint32_t> rev_pair;      // [2 * rev_ptr[E]], words A,B interleaved
@@ -94,8 +109,16 @@ struct HostTopo {
     int64_t n_octets = 0;                // unpadded
     int64_t n_octets_sigma = 0;          // of which numbered by sigma
     std::vector<int32_t> pass_first_slot; // [n_oct_padded / 64]
+    int32_t blk_passes = 0;              // option: target passes per link block (0 = default)
+    int32_t n_blocks = 0;                // 0: the topology does not fit link blocks
+    std::vector<int32_t> pos_link;       // [E] link of every position of the flat order
+    std::vector<int32_t> pos_slot_ptr;   // [E+1] octet slots of a position
+    std::vector<int32_t> blk_pos_ptr;    // [n_blocks+1] first position of a block
+    std::vector<int32_t> blk_pass_ptr;   // [n_blocks+1] first pass of a block
+    std::vector<int32_t> blk_desc;       // [8 * n_blocks] what one workgroup of the fused kernel
+                                         // needs: first and end position, first and end pass,
+                                         // first slot, three zeros
     int32_t n_oct_slots = 0;
-    std::vector<int32_t> link_slot_ptr;  // [E+1] octet slots of a link
     std::vector<int32_t> sigma;          // [K] second numbering, -1 = none
     int32_t sigma_size = 0;              // length of the sigma-ordered copies (multiple of 8)
     std::vector<uint32_t> single_pair;   // [2 * n_singles_padded], rows padded to 2 pairs
@@ -118,8 +141,8 @@ nimble_status_t validate_csr(int32_t n_links, const double *cap, int32_t n_comm,
                              const int32_t *path_link_ptr, const int32_t *path_links,
                              std::string &why);
 
-// Builds everything in HostTopo from validated input.  out.rec_comm_cap is read as an option
-// (default kRecMaxComm).
+// Builds everything in HostTopo from validated input.  out.rec_comm_cap (default kRecMaxComm)
+// and out.blk_passes are read as options.
 void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                      const int32_t *comm_path_ptr, int32_t n_paths,
                      const int32_t *path_link_ptr, const int32_t *path_links,

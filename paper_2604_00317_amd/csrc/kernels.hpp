@@ -35,7 +35,12 @@ struct DeviceTopo {
     const uint32_t *oct_base;   // [64 * n_passes]
     const uint32_t *oct_mask;   // [8 * 64 * n_passes]
     const int32_t *pass_first_slot;   // [n_passes]
-    const int32_t *link_slot_ptr;     // [E+1] octet slots of a link
+    const int32_t *pos_link;          // [E] link whose row comes i-th in the flat array
+    const int32_t *pos_slot_ptr;      // [E+1] octet slots of position i
+    // link blocks of the fused reduce + update kernel (n_blocks = 0: separate kernels)
+    int32_t n_blocks;
+    const int32_t *blk_desc;          // [8 * n_blocks]: first position, end position, first
+                                      // pass, end pass, first slot, 0, 0, 0
     const uint32_t *single_pair;      // [2 * padded singles]
     const int32_t *schunk_begin, *schunk_end, *schunk_slot;   // [n_schunks], pair units
     const int32_t *link_sslot_ptr;    // [E+1] single-chunk slots of a link
@@ -45,13 +50,16 @@ struct DeviceTopo {
     const int32_t *sigma;      // [K], -1 = none
     uint8_t *choice2;          // [sigma_size]
     double *demand2;           // [sigma_size]
-    const double *invcap;      // [E]
-    // state of the plan in flight
+    const double *invcap;      // [E] by link id
+    const double *invcap_pos;  // [E] by position in the flat order of the rows
+    // state of the plan in flight: price by link id (the candidate scan gathers from it);
+    // len and S by position in the streaming and persistent regimes
     double *len, *price, *S;   // [E]
-    uint8_t *choice;           // [K+1] (slot K is only ever read by padding pairs)
+    uint8_t *choice;           // [K+8] (entries from K on are only read for empty masks or
+                               // padding pairs)
     uint32_t *count;           // [P]
     double *partial;           // [n_slots]
-    double *scalars;           // [0] = 1/rho, [1..] = per-block maxima of S
+    double *scalars;           // [0] = 1/rho, [1..] = per-block maxima of S (update or link blocks)
     int32_t n_update_blocks;
     int32_t reduce_blocks;     // 256-thread blocks of the link-load reduce (fills the chip once)
 };
@@ -70,6 +78,9 @@ void launch_load_reduce(const DeviceTopo &t, const uint8_t *choice, const double
 void launch_histogram(const DeviceTopo &t, const uint8_t *log, size_t stride, int32_t iters,
                       double *splits, hipStream_t s);
 void launch_update(const DeviceTopo &t, double eps, hipStream_t s);
+// reduce and update in one launch; only for topologies with link blocks (t.n_blocks > 0)
+void launch_reduce_update(const DeviceTopo &t, const uint8_t *choice, const double *demand,
+                          double eps, hipStream_t s);
 void launch_epilogue(const DeviceTopo &t, int32_t iters, const uint32_t *count, double *splits,
                      double *lambda, hipStream_t s);
 

@@ -76,11 +76,11 @@ struct PersistentArgs {
     const uint32_t *oct_base, *oct_mask;
     const int32_t *schunk_begin, *schunk_end, *schunk_slot;
     const uint32_t *single_pair;
-    const int32_t *link_slot_ptr, *link_sslot_ptr;
+    const int32_t *pos_link, *pos_slot_ptr, *link_sslot_ptr;
     const int32_t *sigma;
     uint8_t *choice2;
     double *demand2;
-    const double *invcap;
+    const double *invcap, *invcap_pos;
     double *len, *price, *S;
     uint8_t *choice;
     uint32_t *count;
@@ -97,8 +97,8 @@ template <int MODE>
 __device__ __forceinline__ void reduce_both(const PersistentArgs &a, int wave, int n_waves,
                                             int lane)
 {
-    reduce_flat_phase<MODE>(a.n_passes, a.pass_first_slot, a.oct_base, a.oct_mask, a.choice,
-                            a.demand, a.choice2, a.demand2, a.partial, wave, n_waves, lane);
+    reduce_flat_phase<MODE>(0, a.n_passes, a.pass_first_slot, a.oct_base, a.oct_mask, a.choice,
+                            a.demand, a.choice2, a.demand2, a.partial, 0, wave, n_waves, lane);
     reduce_phase<MODE, kSinglesPerLane>(a.n_schunks, a.schunk_begin, a.schunk_end, a.schunk_slot,
                                         a.single_pair, a.pad_comm, a.choice, a.demand, a.partial,
                                         n_waves - 1 - wave, n_waves, lane);
@@ -138,7 +138,7 @@ __global__ __launch_bounds__(kPBlock) void k_persistent(PersistentArgs a)
     reduce_both<1>(a, wave, n_waves, lane);
     if (!grid_barrier(a.sync, nb, a.spin_limit, &s_flag)) goto abandoned;
     {
-        double m = width_phase(a.E, a.link_slot_ptr, a.link_sslot_ptr, a.partial, a.invcap, wave,
+        double m = width_phase(a.E, a.pos_link, a.pos_slot_ptr, a.link_sslot_ptr, a.partial, a.invcap_pos, wave,
                                n_waves, lane);
         m = block_max(m, red);
         if (threadIdx.x == 0) atomic_max_bits(&a.sync->rho_bits, m);
@@ -155,8 +155,8 @@ __global__ __launch_bounds__(kPBlock) void k_persistent(PersistentArgs a)
             if (!grid_barrier(a.sync, nb, a.spin_limit, &s_flag)) goto abandoned;
             reduce_both<0>(a, wave, n_waves, lane);
             if (!grid_barrier(a.sync, nb, a.spin_limit, &s_flag)) goto abandoned;
-            update_phase<MAXC>(a.E, a.eps, invrho, a.link_slot_ptr, a.link_sslot_ptr, a.partial,
-                               a.invcap, a.len, a.price, a.S, wave, n_waves, lane);
+            update_phase<MAXC>(a.E, a.eps, invrho, a.pos_link, a.pos_slot_ptr, a.link_sslot_ptr, a.partial,
+                               a.invcap_pos, a.len, a.price, a.S, wave, n_waves, lane);
             if (!grid_barrier(a.sync, nb, a.spin_limit, &s_flag)) goto abandoned;
         }
     }
@@ -245,12 +245,14 @@ hipError_t launch_persistent(const DeviceTopo &t, void *sync_words, int n_cu,
     a.schunk_end = t.schunk_end;
     a.schunk_slot = t.schunk_slot;
     a.single_pair = t.single_pair;
-    a.link_slot_ptr = t.link_slot_ptr;
+    a.pos_link = t.pos_link;
+    a.pos_slot_ptr = t.pos_slot_ptr;
     a.link_sslot_ptr = t.link_sslot_ptr;
     a.sigma = t.sigma;
     a.choice2 = t.choice2;
     a.demand2 = t.demand2;
     a.invcap = t.invcap;
+    a.invcap_pos = t.invcap_pos;
     a.len = t.len;
     a.price = t.price;
     a.S = t.S;

@@ -233,8 +233,8 @@ __global__ __launch_bounds__(kBlock) void k_load_reduce(ReduceArgs a)
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
-    reduce_flat_phase<MODE>(a.n_passes, a.pass_first_slot, a.oct_base, a.oct_mask, a.choice,
-                            a.demand, a.choice2, a.demand2, a.partial, wave, n_waves, lane);
+    reduce_flat_phase<MODE>(0, a.n_passes, a.pass_first_slot, a.oct_base, a.oct_mask, a.choice,
+                            a.demand, a.choice2, a.demand2, a.partial, 0, wave, n_waves, lane);
     // single pairs (commodities with more than 32 candidates) are walked from the other end of
     // the wave pool
     reduce_phase<MODE, kSinglesPerLane>(a.n_schunks, a.schunk_begin, a.schunk_end, a.schunk_slot,
@@ -242,10 +242,92 @@ __global__ __launch_bounds__(kBlock) void k_load_reduce(ReduceArgs a)
                                         n_waves - 1 - wave, n_waves, lane);
 }
 
+// Link-load reduce and length update in one kernel, for topologies cut into link blocks: a
+// workgroup owns the rows of a block, reduces their octets (a contiguous range of passes) into
+// slot partials kept in LDS, and applies  S += u,  len *= 1 + eps*u/rho,  price = len/cap  to
+// exactly those links.  len, S and 1/cap are stored by position, so the state of the block's
+// links is requested with coalesced loads before the octets are walked and has arrived when
+// the partials are complete.  Every wave leaves its maximum of S in scalars[1 + wave id].
+struct FusedArgs {
+    const int32_t *blk_desc;
+    const int32_t *pass_first_slot;
+    const uint32_t *oct_base, *oct_mask;
+    const int32_t *pos_link, *pos_slot_ptr;
+    const uint8_t *choice, *choice2;
+    const double *demand, *demand2;
+    const double *invcap_pos;
+    double *len, *price, *S, *scalars;
+    double eps;
+};
+
+struct LinkState {
+    int e, c0, c1;
+    double ic, s, l;
+};
+
+template <bool MAXC>
+__global__ __launch_bounds__(kBlock) void k_reduce_update(FusedArgs a)
+{
+    __shared__ double s_part[kBlkMaxSlots];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    const int b = blockIdx.x;
+    const int4 d4 = *reinterpret_cast<const int4 *>(a.blk_desc + 8 * b);
+    const int i0 = d4.x, i1 = d4.y;             // positions of the block (at least one)
+    const int p0 = d4.z, p1 = d4.w;             // its passes
+    const int slot0 = a.blk_desc[8 * b + 4];
+    const double invrho = a.scalars[0];
+    const int row = threadIdx.x / kRowLanes;
+    const int l = threadIdx.x % kRowLanes;
+    constexpr int kRows = kBlock / kRowLanes;
+    // positions past the end re-read the last one (so that every load is unconditional) and
+    // are masked out when the update is applied
+    auto fetch = [&](int i) {
+        const int ic = i < i1 ? i : i1 - 1;
+        LinkState st;
+        st.e = a.pos_link[ic];
+        st.c0 = a.pos_slot_ptr[ic] - slot0;
+        st.c1 = a.pos_slot_ptr[ic + 1] - slot0;
+        st.ic = a.invcap_pos[ic];
+        st.s = a.S[ic];
+        st.l = a.len[ic];
+        return st;
+    };
+    double smax = 0.0;
+    auto apply = [&](int i, const LinkState &st) {
+        const bool valid = i < i1;
+        const double load = row_partial_sum(st.c0, valid ? st.c1 : st.c0, l, s_part);
+        if (valid && l == 0) {
+            const double u = load * st.ic;
+            const double s_new = st.s + u;
+            a.S[i] = s_new;
+            const double g = u * invrho;
+            const double t1 = a.eps * g;
+            const double t2 = 1.0 + t1;
+            const double ln = st.l * t2;
+            a.len[i] = ln;
+            a.price[st.e] = MAXC ? ln : ln * st.ic;
+            smax = fmax(smax, s_new);
+        }
+    };
+    const LinkState st0 = fetch(i0 + row);
+    const LinkState st1 = fetch(i0 + row + kRows);
+    reduce_flat_phase<0>(p0, p1, a.pass_first_slot, a.oct_base, a.oct_mask, a.choice, a.demand,
+                         a.choice2, a.demand2, s_part, slot0, wave, kBlock / kWave, lane);
+    __syncthreads();
+    apply(i0 + row, st0);
+    apply(i0 + row + kRows, st1);
+    for (int ibase = i0 + 2 * kRows; ibase < i1; ibase += kRows)         // block-uniform, rare
+        apply(ibase + row, fetch(ibase + row));
+    const double m = wave_max(smax);
+    if (lane == 0) a.scalars[1 + b * (kBlock / kWave) + wave] = m;
+}
+
 // rho = max_e (demand that can reach e) / cap_e, in two steps: every block leaves the maximum
 // over its links in scalars[1 + block], then one block folds those into scalars[0] = 1/rho
 // (0 when rho = 0).  A maximum does not depend on the order it is taken in.
-__global__ __launch_bounds__(kBlock) void k_width(int E, const int32_t *__restrict__ link_slot_ptr,
+__global__ __launch_bounds__(kBlock) void k_width(int E, const int32_t *__restrict__ pos_link,
+                                                  const int32_t *__restrict__ pos_slot_ptr,
                                                   const int32_t *__restrict__ link_sslot_ptr,
                                                   const double *__restrict__ partial,
                                                   const double *__restrict__ invcap,
@@ -254,7 +336,7 @@ __global__ __launch_bounds__(kBlock) void k_width(int E, const int32_t *__restri
     __shared__ double red[16];
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
-    double m = width_phase(E, link_slot_ptr, link_sslot_ptr, partial, invcap, wave, n_waves,
+    double m = width_phase(E, pos_link, pos_slot_ptr, link_sslot_ptr, partial, invcap, wave, n_waves,
                            threadIdx.x & (kWave - 1));
     m = block_max(m, red);
     if (threadIdx.x == 0) scalars[1 + blockIdx.x] = m;
@@ -272,7 +354,8 @@ __global__ __launch_bounds__(kBlock) void k_width_fold(int n_blocks, double *__r
 // length update fused with the per-block maximum of the congestion sums (lambda = max / iters)
 template <bool MAXC>
 __global__ __launch_bounds__(kBlock) void k_update(int E, double eps,
-                                                   const int32_t *__restrict__ link_slot_ptr,
+                                                   const int32_t *__restrict__ pos_link,
+                                                   const int32_t *__restrict__ pos_slot_ptr,
                                                    const int32_t *__restrict__ link_sslot_ptr,
                                                    const double *__restrict__ partial,
                                                    const double *__restrict__ invcap,
@@ -285,7 +368,7 @@ __global__ __launch_bounds__(kBlock) void k_update(int E, double eps,
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
-    const double s_new = update_phase<MAXC>(E, eps, scalars[0], link_slot_ptr, link_sslot_ptr,
+    const double s_new = update_phase<MAXC>(E, eps, scalars[0], pos_link, pos_slot_ptr, link_sslot_ptr,
                                             partial, invcap, len, price, S, wave, n_waves, lane);
     const double m = block_max(s_new, red);
     if (threadIdx.x == 0) scalars[1 + blockIdx.x] = m;
@@ -434,7 +517,7 @@ void launch_width(const DeviceTopo &t, const double *demand, hipStream_t s)
 {
     launch_reduce_mode<1>(t, t.choice, demand, s);
     hipLaunchKernelGGL(k_width, dim3(t.n_update_blocks), dim3(kBlock), 0, s, t.E,
-                       t.link_slot_ptr, t.link_sslot_ptr, t.partial, t.invcap, t.scalars);
+                       t.pos_link, t.pos_slot_ptr, t.link_sslot_ptr, t.partial, t.invcap_pos, t.scalars);
     hipLaunchKernelGGL(k_width_fold, dim3(1), dim3(kBlock), 0, s, t.n_update_blocks, t.scalars);
 }
 
@@ -462,20 +545,49 @@ void launch_update(const DeviceTopo &t, double eps, hipStream_t s)
 {
     if (t.cost_max)
         hipLaunchKernelGGL(k_update<true>, dim3(t.n_update_blocks), dim3(kBlock), 0, s, t.E, eps,
-                           t.link_slot_ptr, t.link_sslot_ptr, t.partial, t.invcap, t.len, t.price,
+                           t.pos_link, t.pos_slot_ptr, t.link_sslot_ptr, t.partial, t.invcap_pos, t.len, t.price,
                            t.S, t.scalars);
     else
         hipLaunchKernelGGL(k_update<false>, dim3(t.n_update_blocks), dim3(kBlock), 0, s, t.E, eps,
-                           t.link_slot_ptr, t.link_sslot_ptr, t.partial, t.invcap, t.len, t.price,
+                           t.pos_link, t.pos_slot_ptr, t.link_sslot_ptr, t.partial, t.invcap_pos, t.len, t.price,
                            t.S, t.scalars);
+}
+
+void launch_reduce_update(const DeviceTopo &t, const uint8_t *choice, const double *demand,
+                          double eps, hipStream_t s)
+{
+    FusedArgs a;
+    a.blk_desc = t.blk_desc;
+    a.pass_first_slot = t.pass_first_slot;
+    a.oct_base = t.oct_base;
+    a.oct_mask = t.oct_mask;
+    a.pos_link = t.pos_link;
+    a.pos_slot_ptr = t.pos_slot_ptr;
+    a.choice = choice;
+    a.choice2 = t.choice2;
+    a.demand = demand;
+    a.demand2 = t.demand2;
+    a.invcap_pos = t.invcap_pos;
+    a.len = t.len;
+    a.price = t.price;
+    a.S = t.S;
+    a.scalars = t.scalars;
+    a.eps = eps;
+    if (t.cost_max)
+        hipLaunchKernelGGL(k_reduce_update<true>, dim3(t.n_blocks), dim3(kBlock), 0, s, a);
+    else
+        hipLaunchKernelGGL(k_reduce_update<false>, dim3(t.n_blocks), dim3(kBlock), 0, s, a);
 }
 
 void launch_epilogue(const DeviceTopo &t, int32_t iters, const uint32_t *count, double *splits,
                      double *lambda, hipStream_t s)
 {
+    // the last length update left one maximum of S per block: link blocks when the fused
+    // kernel ran, update blocks otherwise
+    const int n_max = t.n_blocks > 0 ? t.n_blocks * (kBlock / kWave) : t.n_update_blocks;
     const int grid = count ? blocks_for(t.P, kBlock, 4096) : 1;
-    hipLaunchKernelGGL(k_epilogue, dim3(grid), dim3(kBlock), 0, s, t.P, iters, t.n_update_blocks,
-                       count, t.scalars, splits, lambda);
+    hipLaunchKernelGGL(k_epilogue, dim3(grid), dim3(kBlock), 0, s, t.P, iters, n_max, count,
+                       t.scalars, splits, lambda);
 }
 
 }  // namespace nimble

@@ -240,14 +240,17 @@ __device__ __forceinline__ void reduce_phase(int n_chunks, const int32_t *__rest
 // MODE 1 (width rho): every commodity with a non-zero mask counts once.
 template <int MODE>
 __device__ __forceinline__ void reduce_flat_phase(
-    int n_passes, const int32_t *__restrict__ pass_first_slot,
+    int pass_begin, int pass_end, const int32_t *__restrict__ pass_first_slot,
     const uint32_t *__restrict__ oct_base, const uint32_t *__restrict__ oct_mask,
     const uint8_t *__restrict__ choice, const double *__restrict__ demand,
     const uint8_t *__restrict__ choice2, const double *__restrict__ demand2,
-    double *__restrict__ partial, int wave, int n_waves, int lane)
+    double *__restrict__ partial, int slot_base, int wave, int n_waves, int lane)
 {
-    if (wave >= n_passes) return;
-    const int last = n_passes - 1;
+    // passes pass_begin + wave, + n_waves, ... below pass_end; slot s goes to
+    // partial[s - slot_base] (global memory, or the LDS of a link block)
+    const int first = pass_begin + wave;
+    if (first >= pass_end) return;
+    const int last = pass_end - 1;
     const u32x4 *masks = reinterpret_cast<const u32x4 *>(oct_mask);
     // Software pipeline over the passes of this wave, two passes in flight:
     //   A  gather the choices of pass i            (its octets arrived during pass i-1)
@@ -258,10 +261,10 @@ __device__ __forceinline__ void reduce_flat_phase(
     // Every load on this path is unconditional (absent hits read element 0 and are masked to
     // +0.0; passes beyond the end re-read the last pass), which keeps the number of
     // outstanding requests known to the compiler so that it waits for the oldest only.
-    uint32_t bw = stream_load(oct_base + size_t(wave) * kWave + lane);
+    uint32_t bw = stream_load(oct_base + size_t(first) * kWave + lane);
     // masks of a pass: words 0..3 of the 64 octets lane after lane, then words 4..7
-    u32x4 m0 = stream_load(masks + size_t(wave) * 128 + lane);
-    u32x4 m1 = stream_load(masks + size_t(wave) * 128 + 64 + lane);
+    u32x4 m0 = stream_load(masks + size_t(first) * 128 + lane);
+    u32x4 m1 = stream_load(masks + size_t(first) * 128 + 64 + lane);
     // carried state of the pass that is waiting for its demands
     bool have_prev = false;
     double pd0 = 0.0, pd1 = 0.0, pextra = 0.0;
@@ -279,9 +282,9 @@ __device__ __forceinline__ void reduce_flat_phase(
         const int start = 63 - __clzll(static_cast<long long>(upto));
         acc = segmented_scan_f64(acc, start, lane);
         const bool tail = lane == kWave - 1 || ((heads >> (lane + 1)) & 1ull) != 0ull;
-        if (tail) partial[first_slot + __popcll(upto) - 1] = acc;
+        if (tail) partial[first_slot - slot_base + __popcll(upto) - 1] = acc;
     };
-    for (int pass = wave; pass < n_passes; pass += n_waves) {      // wave-uniform
+    for (int pass = first; pass < pass_end; pass += n_waves) {     // wave-uniform
         // A
         const bool sig = (bw & kOctSigma) != 0u;
         const int base = static_cast<int>(bw & ~3u);
@@ -365,44 +368,48 @@ __device__ __forceinline__ double row_partial_sum(int c0, int c1, int l,
 
 template <bool MAXC>
 __device__ __forceinline__ double update_phase(int E, double eps, double invrho,
-                                               const int32_t *__restrict__ link_slot_ptr,
+                                               const int32_t *__restrict__ pos_link,
+                                               const int32_t *__restrict__ pos_slot_ptr,
                                                const int32_t *__restrict__ link_sslot_ptr,
                                                const double *__restrict__ partial,
-                                               const double *__restrict__ invcap,
+                                               const double *__restrict__ invcap_pos,
                                                double *__restrict__ len,
                                                double *__restrict__ price, double *__restrict__ S,
                                                int wave, int n_waves, int lane)
 {
+    // invcap_pos, len and S are stored in the flat order of the rows (by position); only the
+    // price array, which the candidate scan gathers from, is indexed by link id
     const int row = lane / kRowLanes;
     const int l = lane % kRowLanes;
     double smax = 0.0;
-    for (int ebase = wave * kRowsPerWave; ebase < E; ebase += n_waves * kRowsPerWave) {
-        const int e = ebase + row;
-        int c0 = 0, c1 = 0, s0 = 0, s1 = 0;
-        if (e < E) {
-            c0 = link_slot_ptr[e];
-            c1 = link_slot_ptr[e + 1];
+    for (int ibase = wave * kRowsPerWave; ibase < E; ibase += n_waves * kRowsPerWave) {
+        const int i = ibase + row;          // position in the flat order of the rows
+        int e = 0, c0 = 0, c1 = 0, s0 = 0, s1 = 0;
+        if (i < E) {
+            e = pos_link[i];
+            c0 = pos_slot_ptr[i];
+            c1 = pos_slot_ptr[i + 1];
             s0 = link_sslot_ptr[e];
             s1 = link_sslot_ptr[e + 1];
         }
         // the link's own state is requested before the partial sums are waited for
         double ic = 0.0, s_old = 0.0, l_old = 0.0;
-        if (e < E && l == 0) {
-            ic = invcap[e];
-            s_old = S[e];
-            l_old = len[e];
+        if (i < E && l == 0) {
+            ic = invcap_pos[i];
+            s_old = S[i];
+            l_old = len[i];
         }
         // octet slots, then (rarely any) single-pair slots
         const double load = row_partial_sum(c0, c1, l, partial) + row_partial_sum(s0, s1, l, partial);
-        if (e < E && l == 0) {
+        if (i < E && l == 0) {
             const double u = load * ic;
             const double s_new = s_old + u;
-            S[e] = s_new;
+            S[i] = s_new;
             const double g = u * invrho;
             const double t1 = eps * g;
             const double t2 = 1.0 + t1;
             const double ln = l_old * t2;
-            len[e] = ln;
+            len[i] = ln;
             price[e] = MAXC ? ln : ln * ic;
             smax = fmax(smax, s_new);
         }
@@ -411,26 +418,28 @@ __device__ __forceinline__ double update_phase(int E, double eps, double invrho,
 }
 
 // max over this wave's links of (demand that can reach the link) / capacity: terms of rho
-__device__ __forceinline__ double width_phase(int E, const int32_t *__restrict__ link_slot_ptr,
+__device__ __forceinline__ double width_phase(int E, const int32_t *__restrict__ pos_link,
+                                              const int32_t *__restrict__ pos_slot_ptr,
                                               const int32_t *__restrict__ link_sslot_ptr,
                                               const double *__restrict__ partial,
-                                              const double *__restrict__ invcap, int wave,
+                                              const double *__restrict__ invcap_pos, int wave,
                                               int n_waves, int lane)
 {
     const int row = lane / kRowLanes;
     const int l = lane % kRowLanes;
     double m = 0.0;
-    for (int ebase = wave * kRowsPerWave; ebase < E; ebase += n_waves * kRowsPerWave) {
-        const int e = ebase + row;
-        int c0 = 0, c1 = 0, s0 = 0, s1 = 0;
-        if (e < E) {
-            c0 = link_slot_ptr[e];
-            c1 = link_slot_ptr[e + 1];
+    for (int ibase = wave * kRowsPerWave; ibase < E; ibase += n_waves * kRowsPerWave) {
+        const int i = ibase + row;
+        int e = 0, c0 = 0, c1 = 0, s0 = 0, s1 = 0;
+        if (i < E) {
+            e = pos_link[i];
+            c0 = pos_slot_ptr[i];
+            c1 = pos_slot_ptr[i + 1];
             s0 = link_sslot_ptr[e];
             s1 = link_sslot_ptr[e + 1];
         }
         const double reach = row_partial_sum(c0, c1, l, partial) + row_partial_sum(s0, s1, l, partial);
-        if (e < E) m = fmax(m, reach * invcap[e]);
+        if (i < E) m = fmax(m, reach * invcap_pos[i]);
     }
     return m;
 }

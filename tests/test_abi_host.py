@@ -160,6 +160,28 @@ def test_streaming_reverse_layout_decodes_to_the_same_rows(cfg):
     st = B.nimble_host_layout_stats(*args)
     assert st["pairs"] > 0 and st["octets"] > 0 and st["singles"] == 0
     assert st["octets_sigma"] > 0              # "all sources to one destination" rows exist
+    # octet-only rows: the topology is cut into link blocks (the decode above has checked that
+    # every block holds the slots of its own links only), each padded to whole passes
+    assert st["link_blocks"] > 0
+    assert st["octets_padded"] % 64 == 0
+    assert st["octets"] <= st["octets_padded"] < st["octets"] + 64 * st["link_blocks"]
+
+
+def test_link_blocks_are_dropped_when_a_row_overflows_a_block():
+    """One link that 600 000 single-path commodities share needs more partial-sum slots than a
+    link block holds: the layout must still decode to the same rows, without blocks."""
+    K, E = 600_000, 3
+    cp = np.arange(K + 1, dtype=np.int32)
+    lp = np.arange(K + 1, dtype=np.int32)
+    pl = np.zeros(K, dtype=np.int32)
+    pl[::1000] = 2
+    args = (E, K, cp, K, lp, pl)
+    a = B.nimble_host_build_reverse(*args)
+    b = B.nimble_host_build_reverse(*args, streaming=True)
+    for x, y in zip(a, b):
+        assert np.array_equal(x, y)
+    st = B.nimble_host_layout_stats(*args)
+    assert st["link_blocks"] == 0 and st["singles"] == 0
 
 
 @pytest.mark.parametrize("seed,E,K,pm,lm", [(1, 7, 3, 4, 3), (2, 40, 130, 9, 5), (5, 90, 17, 100, 7),
@@ -171,5 +193,9 @@ def test_streaming_reverse_layout_random(seed, E, K, pm, lm):
     b = B.nimble_host_build_reverse(*args, streaming=True)
     for x, y in zip(a, b):
         assert np.array_equal(x, y)
-    if pm > 32:                                  # several windows: single pairs must appear
-        assert B.nimble_host_layout_stats(*args)["singles"] > 0
+    st = B.nimble_host_layout_stats(*args)
+    if pm > 32:                                  # several windows: single pairs must appear,
+        assert st["singles"] > 0                 # and such topologies have no link blocks
+        assert st["link_blocks"] == 0
+    else:
+        assert st["link_blocks"] > 0

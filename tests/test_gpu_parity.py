@@ -139,6 +139,41 @@ def test_streaming_regime_without_choice_log(oracle_mod, B, monkeypatch):
         check(oracle_mod, B, w.topo, w.traffic, w.eps, iters, regime=2)
 
 
+def test_streaming_regime_with_separate_reduce_and_update(oracle_mod, B, monkeypatch):
+    """Topologies cut into link blocks run the link-load reduce and the length update as one
+    kernel; with the blocks switched off the same topologies take the two separate kernels
+    (the path every topology with single pairs uses).  Both must give the oracle's plan."""
+    monkeypatch.setenv("NIMBLE_TUNE_NO_LINK_BLOCKS", "1")
+    for cfg, iters in ((0, 200), (1, 300), (3, 120)):
+        w = W.make_config(cfg)
+        check(oracle_mod, B, w.topo, w.traffic, w.eps, iters, regime=2)
+
+
+@pytest.mark.parametrize("passes", [1, 2, 64])
+def test_link_block_sizes(oracle_mod, B, monkeypatch, passes):
+    """Link blocks of one pass (a block per large row), two passes and one huge block size."""
+    monkeypatch.setenv("NIMBLE_TUNE_BLOCK_PASSES", str(passes))
+    for cfg, iters in ((1, 300), (3, 60)):
+        w = W.make_config(cfg)
+        check(oracle_mod, B, w.topo, w.traffic, w.eps, iters, regime=2)
+        check(oracle_mod, B, w.topo, w.traffic, w.eps, iters, regime=2, flags=1)
+
+
+def test_row_too_long_for_a_link_block(oracle_mod, B):
+    """600 000 single-path commodities on one link: the row needs more partial-sum slots than a
+    link block holds, so the streaming regime runs the separate reduce and update kernels."""
+    K, E = 600_000, 3
+    cp = np.arange(K + 1, dtype=np.int32)
+    pl = np.zeros(K, dtype=np.int32)
+    pl[::1000] = 2
+    topo = W.Topology(n_links=E, cap=np.array([100e9, 50e9, 25e9]), n_comm=K, comm_path_ptr=cp,
+                      n_paths=K, path_link_ptr=cp.copy(), path_links=pl,
+                      src=np.zeros(K, dtype=np.int32), dst=np.zeros(K, dtype=np.int32),
+                      meta=dict(kind="one hot link"))
+    d = np.random.default_rng(3).integers(1, 1 << 20, size=K).astype(np.float64)
+    check(oracle_mod, B, topo, d, 0.1, 5, regime=2)
+
+
 def test_non_integer_demands(oracle_mod, B):
     """The resident regime adds loads in the sequential order, so it is exact for any demands;
     the streaming regime sums in a fixed tree: run-to-run identical, equal to the oracle up to
