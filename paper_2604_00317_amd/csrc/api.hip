@@ -96,7 +96,8 @@ bool ensure_choice_log(nimble_topo *t, int32_t iters)
 {
     if (std::getenv("NIMBLE_TUNE_NO_CHOICE_LOG")) return false;
     if (t->log_rows >= iters) return true;
-    const size_t stride = (static_cast<size_t>(t->d.K) + 8 + 255) & ~static_cast<size_t>(255);
+    // a row holds whole windows of choices (the tile phase reads them 512 at a time)
+    const size_t stride = (static_cast<size_t>(t->d.K) + 8 + 511) & ~static_cast<size_t>(511);
     const size_t bytes = stride * static_cast<size_t>(iters);
     if (bytes > (static_cast<size_t>(4) << 30)) return false;
     if (t->choice_log) (void)hipFree(t->choice_log);      // waits for work that still uses it
@@ -211,14 +212,7 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     nimble::HostTopo h;
     try {
         t = new nimble_topo();
-        if (const char *env = std::getenv("NIMBLE_TUNE_RECORD_COMM_CAP")) {
-            const int v = std::atoi(env);
-            if (v >= 1 && v <= nimble::kRecMaxComm) h.rec_comm_cap = v;
-        }
-        if (const char *env = std::getenv("NIMBLE_TUNE_BLOCK_PASSES")) {
-            const int v = std::atoi(env);
-            if (v >= 1 && v <= 1024) h.blk_passes = v;
-        }
+        nimble::read_layout_options(h);
         nimble::build_host_topo(n_links, cap, n_comm, comm_path_ptr, n_paths, path_link_ptr,
                                 path_links, h);
     } catch (const std::bad_alloc &) {
@@ -293,6 +287,21 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     NIMBLE_TRY(upload(t, h.pos_slot_ptr.data(), h.pos_slot_ptr.size(), &d.pos_slot_ptr),
                "pos_slot_ptr");
     NIMBLE_TRY(upload(t, h.blk_desc.data(), h.blk_desc.size(), &d.blk_desc), "blk_desc");
+    NIMBLE_TRY(upload(t, h.tile_desc.data(), h.tile_desc.size(), &d.tile_desc), "tile_desc");
+    NIMBLE_TRY(upload(t, h.tile_mask.data(), h.tile_mask.size(), &d.tile_mask), "tile_mask");
+    NIMBLE_TRY(upload(t, h.tile_pres.data(), h.tile_pres.size(), &d.tile_pres), "tile_pres");
+    d.n_tile_items = h.n_tile_items;
+    {
+        const size_t k_pad = (static_cast<size_t>(h.K) + 511) & ~static_cast<size_t>(511);
+        NIMBLE_TRY(allocate(t, k_pad, &d.demand1t), "demand1t");
+        NIMBLE_TRY(hipMemset(d.demand1t, 0, sizeof(double) * k_pad), "demand1t clear");
+        NIMBLE_TRY(allocate(t, static_cast<size_t>(h.sigma_size), &d.demand2t), "demand2t");
+        NIMBLE_TRY(hipMemset(d.demand2t, 0, sizeof(double) * static_cast<size_t>(h.sigma_size)),
+                   "demand2t clear");
+        d.tile_item_cost = 1;
+        if (const char *env = std::getenv("NIMBLE_TUNE_TILE_ITEM_COST"))
+            if (std::atoi(env) >= 1 && std::atoi(env) <= 64) d.tile_item_cost = std::atoi(env);
+    }
     NIMBLE_TRY(upload(t, h.sigma.data(), h.sigma.size(), &d.sigma), "sigma");
     d.sigma_size = h.sigma_size;
     NIMBLE_TRY(allocate(t, static_cast<size_t>(h.sigma_size), &d.choice2), "choice2");
@@ -306,7 +315,9 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     NIMBLE_TRY(allocate(t, static_cast<size_t>(h.E), &d.price), "price");
     NIMBLE_TRY(allocate(t, static_cast<size_t>(h.E), &d.S), "S");
     // 8 spare entries: the last octet of a row may start at the last multiple of 4 below K
-    NIMBLE_TRY(allocate(t, static_cast<size_t>(h.K) + 8, &d.choice), "choice");
+    NIMBLE_TRY(allocate(t, ((static_cast<size_t>(h.K) + 511) & ~static_cast<size_t>(511)) + 8,
+                        &d.choice),
+               "choice");
     NIMBLE_TRY(allocate(t, static_cast<size_t>(h.P), &d.count), "count");
     NIMBLE_TRY(allocate(t, static_cast<size_t>(d.n_slots), &d.partial), "partial");
     // one maximum of S per update block, or per wave of the fused kernel's link blocks
@@ -336,6 +347,11 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
                       4LL * static_cast<int64_t>(h.single_pair.size()) + 12LL * d.n_schunks +
                       8LL * d.n_slots;
     t->bytes_update = 8LL * d.n_slots + 8LL * (h.E + 1) + 56LL * h.E;
+    // tile items: 2 KiB per piece, the descriptor, the window's choices and demands, one slot
+    // per piece
+    t->bytes_reduce += 2048LL * (h.n_pieces - h.n_pieces_uniform) + 8LL * h.n_pieces +
+                       (128LL + 512 + 4096) * h.n_tile_items +
+                       512LL * static_cast<int64_t>(h.tile_pres.size() / 64 - 1);
     if (d.n_blocks > 0) {
         // one kernel: the slot partials stay in LDS; per block two table entries and one maximum
         t->bytes_reduce = 36LL * static_cast<int64_t>(h.oct_base.size()) + 4LL * d.n_passes +

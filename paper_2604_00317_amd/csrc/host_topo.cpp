@@ -3,9 +3,11 @@
 #include <algorithm>
 #include <climits>
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <functional>
 #include <queue>
+#include <unordered_map>
 
 namespace nimble {
 
@@ -74,6 +76,23 @@ nimble_status_t validate_csr(int32_t n_links, const double *cap, int32_t n_comm,
         return NIMBLE_ERR_RANGE;
     }
     return NIMBLE_OK;
+}
+
+void read_layout_options(HostTopo &t)
+{
+    auto number = [](const char *name, int lo, int hi, int32_t &out) {
+        if (const char *env = std::getenv(name)) {
+            const int v = std::atoi(env);
+            if (v >= lo && v <= hi) out = v;
+        }
+    };
+    number("NIMBLE_TUNE_RECORD_COMM_CAP", 1, kRecMaxComm, t.rec_comm_cap);
+    number("NIMBLE_TUNE_BLOCK_PASSES", 1, 1024, t.blk_passes);
+    number("NIMBLE_TUNE_TILES", 0, 1, t.tiles);
+    number("NIMBLE_TUNE_TILE_MIN_ITEMS", 1, kTileIds, t.tile_min_items);
+    int32_t dense_only = 0;
+    number("NIMBLE_TUNE_TILES_DENSE_ONLY", 0, 1, dense_only);
+    t.tiles_dense_only = dense_only != 0;
 }
 
 void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
@@ -190,79 +209,254 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
             }
         }
     };
-    // pass 1: octets over commodity ids, row by row; left-overs kept per row
-    std::vector<std::vector<Item>> left1(n_links);
-    std::vector<std::vector<uint32_t>> row_base(n_links), row_mask(n_links);
-    for (int32_t e = 0; e < n_links; ++e) {
-        std::vector<Item> items;
+    auto row_items = [&](int32_t e, std::vector<Item> &items) {
+        items.clear();
         for (int32_t i = 0; i < t.rev_rowlen[e]; ++i) {
             const uint32_t a = t.rev_pair[2 * static_cast<size_t>(t.rev_ptr[e] + i)];
             const uint32_t b = t.rev_pair[2 * static_cast<size_t>(t.rev_ptr[e] + i) + 1];
             const int32_t kk = static_cast<int32_t>(a & kCommMask);
             items.push_back({one_window(kk) ? kk : -1, a, b});    // -1: never in an octet
         }
-        pack(items, n_comm + 8, kOctetMinFill, 0u, row_base[e], row_mask[e], left1[e]);
-    }
-    // second numbering: left-over commodities in order of first appearance, every row's new
-    // run starting at a multiple of 8
+    };
+    // second numbering: the commodities that octets over ids of fill >= kOctetMinFill leave
+    // over, in order of first appearance, every row's new run starting at a multiple of 8
     int32_t next_sigma = 0;
-    for (int32_t e = 0; e < n_links; ++e) {
-        bool started = false;
-        for (const Item &it : left1[e]) {
-            if (it.key < 0) continue;
-            const int32_t kk = static_cast<int32_t>(it.a & kCommMask);
-            if (t.sigma[kk] < 0) {
-                if (!started) {
-                    next_sigma = (next_sigma + 7) & ~7;
-                    started = true;
+    {
+        std::vector<Item> items, left;
+        std::vector<uint32_t> scratch_base, scratch_mask;
+        for (int32_t e = 0; e < n_links; ++e) {
+            row_items(e, items);
+            left.clear();
+            scratch_base.clear();
+            scratch_mask.clear();
+            pack(items, n_comm + 8, kOctetMinFill, 0u, scratch_base, scratch_mask, left);
+            bool started = false;
+            for (const Item &it : left) {
+                if (it.key < 0) continue;
+                const int32_t kk = static_cast<int32_t>(it.a & kCommMask);
+                if (t.sigma[kk] < 0) {
+                    if (!started) {
+                        next_sigma = (next_sigma + 7) & ~7;
+                        started = true;
+                    }
+                    t.sigma[kk] = next_sigma++;
                 }
-                t.sigma[kk] = next_sigma++;
             }
         }
     }
-    t.sigma_size = ((next_sigma + 7) & ~7) + 8;
-    // passes 2 and 3 of every row; single pairs (commodities with several windows) and their
-    // chunks in link order
+    // the sigma-ordered copies are read in whole windows of kTileIds entries by the tile phase
+    t.sigma_size = (next_sigma + 8 + kTileIds - 1) / kTileIds * kTileIds;
+
+    // ---- tiles: dense (row, window) pieces --------------------------------------------------
+    // A window is kTileIds consecutive commodity numbers (ids, or sigma numbers).  Where a row
+    // holds at least tile_min_items commodities of one window, those commodities leave the
+    // octet stream and become a PIECE: 64 columns x 8 masks, column c = commodities
+    // window*kTileIds + 8c .. + 7, zero masks where the commodity does not use the link.
+    // Pieces of the same window are grouped, up to kTileRows at a time, into one work item.
+    const bool tiles_on = t.tiles > 0 || (t.tiles < 0 && t.n_pairs >= kTileAutoPairs);
+    const int32_t tile_min = t.tile_min_items > 0 ? t.tile_min_items : kTileMinItems;
+    struct Piece { int32_t window; int32_t sig; int32_t link; size_t mask_at; };
+    std::vector<Piece> pieces;
+    std::vector<uint32_t> piece_mask;                     // 512 words per piece, [column][slot]
+    std::vector<std::vector<int32_t>> link_pieces(n_links);
+    std::vector<std::vector<uint32_t>> row_base(n_links), row_mask(n_links);
     t.n_octets_sigma = 0;
     t.n_octets = 0;
-    for (int32_t e = 0; e < n_links; ++e) {
-        std::vector<Item> items, left2, left3;
-        for (const Item &it : left1[e]) {
-            Item x = it;
-            x.key = it.key < 0 ? -1 : t.sigma[it.a & kCommMask];
-            items.push_back(x);
+    t.n_piece_items = 0;
+    int32_t extra_slots = 0;              // slots of pieces and single-pair chunks, link by link
+    std::vector<int32_t> piece_extra;     // per piece (creation order = link order)
+    {
+        std::vector<Item> items, rest, left1, left2, left3;
+        std::unordered_map<int32_t, int32_t> win_count;
+        std::unordered_map<int64_t, int32_t> win_masks;
+        std::unordered_map<int32_t, std::pair<int32_t, uint32_t>> win_major;
+        for (int32_t e = 0; e < n_links; ++e) {
+            row_items(e, items);
+            rest.clear();
+            if (tiles_on) {
+                // id windows first, then sigma windows over what is left
+                for (int sig = 0; sig < 2; ++sig) {
+                    auto number = [&](const Item &it) -> int32_t {
+                        if (it.key < 0) return -1;
+                        return sig ? t.sigma[it.a & kCommMask] : static_cast<int32_t>(it.a & kCommMask);
+                    };
+                    // per window: how many of the row's commodities, and the mask value most
+                    // of them share
+                    win_count.clear();
+                    win_masks.clear();
+                    for (const Item &it : items) {
+                        const int32_t nb = number(it);
+                        if (nb < 0) continue;
+                        win_count[nb / kTileIds] += 1;
+                        win_masks[(static_cast<int64_t>(nb / kTileIds) << 32) | it.b] += 1;
+                    }
+                    win_major.clear();                     // window -> (count, mask) of the top value
+                    for (const auto &kv : win_masks) {
+                        const int32_t w = static_cast<int32_t>(kv.first >> 32);
+                        const uint32_t m = static_cast<uint32_t>(kv.first & 0xFFFFFFFFll);
+                        auto &top = win_major[w];
+                        if (kv.second > top.first || (kv.second == top.first && m < top.second))
+                            top = {kv.second, m};
+                    }
+                    std::unordered_map<int32_t, size_t> win_piece;
+                    rest.clear();
+                    for (const Item &it : items) {
+                        const int32_t nb = number(it);
+                        if (nb < 0 || win_count[nb / kTileIds] < tile_min) {
+                            rest.push_back(it);
+                            continue;
+                        }
+                        const int32_t w = nb / kTileIds;
+                        // a window where one mask value covers most commodities becomes a
+                        // uniform piece of exactly those; the few others stay octets
+                        const auto &top = win_major[w];
+                        const bool mostly_uniform = !t.tiles_dense_only && top.first >= tile_min &&
+                                                    4 * top.first >= 3 * win_count[w];
+                        if (mostly_uniform && it.b != top.second) {
+                            rest.push_back(it);
+                            continue;
+                        }
+                        auto f = win_piece.find(w);
+                        if (f == win_piece.end()) {
+                            f = win_piece.emplace(w, pieces.size()).first;
+                            link_pieces[e].push_back(static_cast<int32_t>(pieces.size()));
+                            pieces.push_back({w, sig, e, piece_mask.size()});
+                            piece_mask.resize(piece_mask.size() + 512, 0u);
+                        }
+                        piece_mask[pieces[f->second].mask_at + static_cast<size_t>(nb % kTileIds)] = it.b;
+                        t.n_piece_items += 1;
+                    }
+                    items.swap(rest);
+                }
+            }
+            // what is left: octets over ids (fill >= kOctetMinFill), octets over sigma (same
+            // fill), octets over ids of any fill, single pairs
+            left1.clear(); left2.clear(); left3.clear();
+            pack(items, n_comm + 8, kOctetMinFill, 0u, row_base[e], row_mask[e], left1);
+            for (Item &x : left1) x.key = x.key < 0 ? -1 : t.sigma[x.a & kCommMask];
+            std::stable_sort(left1.begin(), left1.end(), [](const Item &x, const Item &y) {
+                return (x.key < 0 ? INT32_MAX : x.key) < (y.key < 0 ? INT32_MAX : y.key);
+            });
+            const size_t before = row_base[e].size();
+            pack(left1, t.sigma_size, kOctetMinFill, kOctSigma, row_base[e], row_mask[e], left2);
+            t.n_octets_sigma += static_cast<int64_t>(row_base[e].size() - before);
+            // back to (commodity, window) order; eligible ones become octets of any fill
+            for (Item &x : left2) x.key = x.key < 0 ? -1 : static_cast<int32_t>(x.a & kCommMask);
+            std::stable_sort(left2.begin(), left2.end(), [](const Item &x, const Item &y) {
+                const uint32_t kx = x.a & kCommMask, ky = y.a & kCommMask;
+                return kx != ky ? kx < ky : ((x.a >> kWindowShift) & 3u) < ((y.a >> kWindowShift) & 3u);
+            });
+            pack(left2, n_comm + 8, 1, 0u, row_base[e], row_mask[e], left3);
+            t.n_octets += static_cast<int64_t>(row_base[e].size());
+            // single pairs (commodities with several windows) and their chunks, in link order
+            const int32_t s_first = static_cast<int32_t>(t.single_pair.size() / 2);
+            for (const Item &it : left3) {
+                t.single_pair.push_back(it.a);
+                t.single_pair.push_back(it.b);
+                t.n_single_pairs += 1;
+            }
+            if ((t.single_pair.size() / 2) % kPairAlign) {       // pad the row to 16 bytes
+                t.single_pair.push_back(static_cast<uint32_t>(n_comm));
+                t.single_pair.push_back(0u);
+            }
+            const int32_t s_last = static_cast<int32_t>(t.single_pair.size() / 2);
+            // the link's slots outside the octet range: one per piece, then one per chunk
+            t.link_sslot_ptr[e] = extra_slots;
+            for (size_t q = 0; q < link_pieces[e].size(); ++q) piece_extra.push_back(extra_slots++);
+            for (int32_t b = s_first; b < s_last; b += sgl_chunk) {
+                t.schunk_begin.push_back(b);
+                t.schunk_end.push_back(b + sgl_chunk < s_last ? b + sgl_chunk : s_last);
+                t.schunk_slot.push_back(extra_slots++);
+            }
         }
-        left1[e].clear(); left1[e].shrink_to_fit();
-        std::stable_sort(items.begin(), items.end(), [](const Item &x, const Item &y) {
-            return (x.key < 0 ? INT32_MAX : x.key) < (y.key < 0 ? INT32_MAX : y.key);
+    }
+    // A piece whose non-zero masks are all equal (the usual case when the candidates of a
+    // fabric are enumerated by a product rule) is UNIFORM: it is stored as that one mask plus a
+    // presence bit per commodity.  Work items: pieces sorted by (numbering, window, kind, link),
+    // up to kTileRows pieces of one window and one kind per item.  Dense pieces keep their
+    // 512 masks, lane-contiguous like the masks of a pass; a uniform item stores, per column,
+    // one byte of presence bits for each of its rows.
+    t.n_pieces = static_cast<int32_t>(pieces.size());
+    t.n_pieces_uniform = 0;
+    std::vector<uint32_t> piece_umask(pieces.size(), 0u);     // 0: dense
+    for (size_t i = 0; i < pieces.size(); ++i) {
+        uint32_t m = 0u;
+        bool uniform = !t.tiles_dense_only;
+        for (size_t q = 0; q < 512 && uniform; ++q) {
+            const uint32_t v = piece_mask[pieces[i].mask_at + q];
+            if (v == 0u) continue;
+            if (m == 0u) m = v;
+            else if (m != v) uniform = false;
+        }
+        if (uniform && m != 0u) {
+            piece_umask[i] = m;
+            t.n_pieces_uniform += 1;
+        }
+    }
+    std::vector<int32_t> item_piece;                      // [kTileRows * n_tile_items], -1: none
+    {
+        std::vector<int32_t> ord(pieces.size());
+        for (size_t i = 0; i < ord.size(); ++i) ord[i] = static_cast<int32_t>(i);
+        auto kind = [&](int32_t x) { return piece_umask[x] != 0u ? 1 : 0; };
+        std::sort(ord.begin(), ord.end(), [&](int32_t x, int32_t y) {
+            const Piece &px = pieces[x], &py = pieces[y];
+            if (px.sig != py.sig) return px.sig < py.sig;
+            if (px.window != py.window) return px.window < py.window;
+            if (kind(x) != kind(y)) return kind(x) < kind(y);
+            return px.link < py.link;
         });
-        const size_t before = row_base[e].size();
-        pack(items, t.sigma_size, kOctetMinFill, kOctSigma, row_base[e], row_mask[e], left2);
-        t.n_octets_sigma += static_cast<int64_t>(row_base[e].size() - before);
-        // back to (commodity, window) order; eligible ones become octets of any fill
-        for (Item &x : left2) x.key = x.key < 0 ? -1 : static_cast<int32_t>(x.a & kCommMask);
-        std::stable_sort(left2.begin(), left2.end(), [](const Item &x, const Item &y) {
-            const uint32_t kx = x.a & kCommMask, ky = y.a & kCommMask;
-            return kx != ky ? kx < ky : ((x.a >> kWindowShift) & 3u) < ((y.a >> kWindowShift) & 3u);
-        });
-        pack(left2, n_comm + 8, 1, 0u, row_base[e], row_mask[e], left3);
-        t.n_octets += static_cast<int64_t>(row_base[e].size());
-        const int32_t s_first = static_cast<int32_t>(t.single_pair.size() / 2);
-        for (const Item &it : left3) {
-            t.single_pair.push_back(it.a);
-            t.single_pair.push_back(it.b);
-            t.n_single_pairs += 1;
+        t.tile_mask.clear();
+        t.tile_pres.clear();
+        t.tile_desc.clear();
+        int32_t n_dense = 0, n_uitems = 0;
+        for (size_t i = 0; i < ord.size(); ++i) {
+            const int32_t pi = ord[i];
+            const Piece &pc = pieces[pi];
+            const bool uni = kind(pi) == 1;
+            const bool fresh = i == 0 || pieces[ord[i - 1]].sig != pc.sig ||
+                               pieces[ord[i - 1]].window != pc.window ||
+                               kind(ord[i - 1]) != kind(pi) ||
+                               t.tile_desc[t.tile_desc.size() - kTileDescInts + 2] == kTileRows;
+            if (fresh) {
+                t.tile_desc.resize(t.tile_desc.size() + kTileDescInts, 0);
+                item_piece.resize(item_piece.size() + kTileRows, -1);
+                int32_t *d = &t.tile_desc[t.tile_desc.size() - kTileDescInts];
+                d[0] = pc.window * kTileIds;
+                d[1] = pc.sig | (uni ? 2 : 0);
+                d[2] = 0;
+                d[3] = uni ? n_uitems : n_dense;
+                if (uni) {
+                    n_uitems += 1;
+                    t.tile_pres.resize(t.tile_pres.size() + 64, 0ull);
+                }
+            }
+            int32_t *d = &t.tile_desc[t.tile_desc.size() - kTileDescInts];
+            const int32_t r = d[2]++;
+            item_piece[item_piece.size() - kTileRows + r] = pi;
+            if (uni) {
+                d[16 + r] = static_cast<int32_t>(piece_umask[pi]);
+                uint64_t *pres = &t.tile_pres[t.tile_pres.size() - 64];
+                for (size_t c = 0; c < 64; ++c) {
+                    uint64_t bits = 0;
+                    for (size_t w8 = 0; w8 < 8; ++w8)
+                        if (piece_mask[pc.mask_at + c * 8 + w8] != 0u) bits |= 1ull << w8;
+                    pres[c] |= bits << (8 * r);
+                }
+            } else {
+                const size_t at = t.tile_mask.size();
+                t.tile_mask.resize(at + 512, 0u);
+                for (size_t c = 0; c < 64; ++c)
+                    for (size_t w8 = 0; w8 < 8; ++w8)
+                        t.tile_mask[at + (w8 / 4) * 256 + c * 4 + (w8 % 4)] =
+                            piece_mask[pc.mask_at + c * 8 + w8];
+                n_dense += 1;
+            }
         }
-        if ((t.single_pair.size() / 2) % kPairAlign) {       // pad the row to 16 bytes
-            t.single_pair.push_back(static_cast<uint32_t>(n_comm));
-            t.single_pair.push_back(0u);
-        }
-        const int32_t s_last = static_cast<int32_t>(t.single_pair.size() / 2);
-        t.link_sslot_ptr[e] = static_cast<int32_t>(t.schunk_begin.size());
-        for (int32_t b = s_first; b < s_last; b += sgl_chunk) {
-            t.schunk_begin.push_back(b);
-            t.schunk_end.push_back(b + sgl_chunk < s_last ? b + sgl_chunk : s_last);
-        }
+        t.n_tile_items = static_cast<int32_t>(t.tile_desc.size() / kTileDescInts);
+        if (t.tile_desc.empty()) t.tile_desc.assign(kTileDescInts, 0);
+        t.tile_mask.resize(t.tile_mask.size() + 512, 0u);      // one spare piece keeps it loadable
+        t.tile_pres.resize(t.tile_pres.size() + 64, 0ull);
+        piece_mask.clear(); piece_mask.shrink_to_fit();
     }
 
     // ---- link blocks and the order of the rows in the flat array ---------------------------
@@ -300,7 +494,7 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
             lightest.push(top);
         }
     }
-    bool blocks_fit = true;
+    bool blocks_fit = !tiles_on;          // pieces of one item belong to many links
     int32_t slot = 0;
     t.pos_link.clear();
     t.pos_slot_ptr.clear();
@@ -365,13 +559,19 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                         t.oct_mask[(ps * 64 + ln) * 8 + w8];
         t.oct_mask.swap(tmp);
     }
-    const int32_t single_slot0 = t.n_oct_slots + pad_slots;
-    t.link_sslot_ptr[n_links] = static_cast<int32_t>(t.schunk_begin.size());
-    t.schunk_slot.resize(t.schunk_begin.size());
-    for (size_t c = 0; c < t.schunk_begin.size(); ++c)
-        t.schunk_slot[c] = single_slot0 + static_cast<int32_t>(c);
-    for (int32_t e = 0; e <= n_links; ++e) t.link_sslot_ptr[e] += single_slot0;
-    t.n_slots = single_slot0 + static_cast<int32_t>(t.schunk_begin.size());
+    // the extra slots follow the octet slots
+    const int32_t extra_slot0 = t.n_oct_slots + pad_slots;
+    t.link_sslot_ptr[n_links] = extra_slots;
+    for (int32_t &v : t.schunk_slot) v += extra_slot0;
+    for (int32_t e = 0; e <= n_links; ++e) t.link_sslot_ptr[e] += extra_slot0;
+    t.n_slots = extra_slot0 + extra_slots;
+    for (int32_t it = 0; it < t.n_tile_items; ++it) {
+        int32_t *d = &t.tile_desc[static_cast<size_t>(it) * kTileDescInts];
+        for (int32_t r = 0; r < kTileRows; ++r) {
+            const int32_t pi = item_piece[static_cast<size_t>(it) * kTileRows + r];
+            d[8 + r] = pi >= 0 ? extra_slot0 + piece_extra[pi] : -1;
+        }
+    }
     // the fused kernel covers topologies whose reverse rows are octets only
     t.n_blocks = (blocks_fit && t.n_single_pairs == 0)
                      ? static_cast<int32_t>(t.blk_pos_ptr.size()) - 1 : 0;
@@ -632,6 +832,7 @@ extern "C" nimble_status_t nimble_host_layout_stats(int32_t n_links, int32_t n_c
     if (!out) return NIMBLE_ERR_INVALID;
     std::vector<double> cap(n_links, 1.0);
     nimble::HostTopo t;
+    nimble::read_layout_options(t);
     nimble::build_host_topo(n_links, cap.data(), n_comm, comm_path_ptr, n_paths, path_link_ptr,
                             path_links, t);
     out[0] = t.n_pairs;
@@ -644,6 +845,9 @@ extern "C" nimble_status_t nimble_host_layout_stats(int32_t n_links, int32_t n_c
     out[7] = t.rec_stride;
     out[8] = t.n_blocks;
     out[9] = static_cast<int64_t>(t.oct_base.size());
+    out[10] = t.n_pieces;
+    out[11] = t.n_tile_items;
+    out[12] = t.n_pieces_uniform;
     return NIMBLE_OK;
 }
 
@@ -663,6 +867,7 @@ extern "C" nimble_status_t nimble_host_build_reverse_streaming(int32_t n_links, 
     if (!rev_ptr || !rev_comm || !rev_path) return NIMBLE_ERR_INVALID;
     std::vector<double> cap(n_links, 1.0);
     nimble::HostTopo t;
+    nimble::read_layout_options(t);
     nimble::build_host_topo(n_links, cap.data(), n_comm, comm_path_ptr, n_paths, path_link_ptr,
                             path_links, t);
     // decode the streaming layout the way the reduce kernel walks it: flat octets with slot
@@ -726,6 +931,33 @@ extern "C" nimble_status_t nimble_host_build_reverse_streaming(int32_t n_links, 
             if (k < 0 || k >= n_comm) return NIMBLE_ERR_INVALID;
             for (int32_t j = 0; j < 32; ++j)
                 if (m & (1u << j)) rows[e].push_back((static_cast<int64_t>(k) << 8) | j);
+        }
+    }
+    // tile items: every piece belongs to the link that owns its slot
+    for (int32_t it = 0; it < t.n_tile_items; ++it) {
+        const int32_t *d = &t.tile_desc[static_cast<size_t>(it) * nimble::kTileDescInts];
+        if (d[2] < 1 || d[2] > nimble::kTileRows || d[0] % nimble::kTileIds) return NIMBLE_ERR_INVALID;
+        for (int32_t r = 0; r < d[2]; ++r) {
+            const int32_t sl = d[8 + r];
+            if (sl < 0 || sl >= t.n_slots || slot_link[sl] < 0) return NIMBLE_ERR_INVALID;
+            const int32_t e = slot_link[sl];
+            const bool uni = (d[1] & 2) != 0;
+            const size_t at = 512 * static_cast<size_t>(d[3] + r);      // dense piece
+            for (int32_t c = 0; c < 64; ++c)
+                for (int32_t s8 = 0; s8 < 8; ++s8) {
+                    uint32_t m;
+                    if (uni)
+                        m = ((t.tile_pres[64 * static_cast<size_t>(d[3]) + c] >> (8 * r + s8)) & 1ull)
+                                ? static_cast<uint32_t>(d[16 + r]) : 0u;
+                    else
+                        m = t.tile_mask[at + (s8 / 4) * 256 + c * 4 + (s8 % 4)];
+                    if (!m) continue;
+                    const int32_t nb = d[0] + 8 * c + s8;
+                    const int32_t k = (d[1] & 1) ? (nb < t.sigma_size ? inv_sigma[nb] : -1) : nb;
+                    if (k < 0 || k >= n_comm) return NIMBLE_ERR_INVALID;
+                    for (int32_t j = 0; j < 32; ++j)
+                        if (m & (1u << j)) rows[e].push_back((static_cast<int64_t>(k) << 8) | j);
+                }
         }
     }
     for (size_t c = 0; c < t.schunk_begin.size(); ++c) {

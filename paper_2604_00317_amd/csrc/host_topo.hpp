@@ -51,6 +51,28 @@ constexpr uint32_t kOctNewSlot = 1u;
 constexpr uint32_t kOctSigma = 2u;
 constexpr int32_t kSinglesPerLane = 8;        // a single-pair chunk holds 16 * 8 pairs
 
+// Tiles.  Where a row holds many commodities of one WINDOW (kTileIds consecutive ids, or
+// consecutive sigma numbers), those commodities are stored as a dense piece of 64 columns x 8
+// masks instead of octets: column c covers the commodities window*kTileIds + 8c .. + 7.  One
+// work item holds up to kTileRows pieces of the same window (different links); a wave loads
+// the 512 choices and demands of the window once, coalesced, and uses them for every row of
+// the item, so no per-hit gather is left.  Every piece adds one partial-sum slot to its link.
+// A piece whose non-zero masks are all one value is UNIFORM and shrinks to that value plus
+// one presence bit per commodity; an item holds pieces of one kind.
+// Item descriptor, kTileDescInts int32:
+//   [0] first number of the window   [1] bit 0: sigma numbers, bit 1: uniform pieces
+//   [2] number of pieces             [3] dense: index of the first piece in tile_mask (2 KiB
+//                                        each, lane-contiguous like the masks of a pass);
+//                                        uniform: index of the item's block in tile_pres
+//   [8..15] slot of piece 0..7 (-1: none)      [16..23] uniform: mask of piece 0..7
+// tile_pres holds, per uniform item, 64 words of 64 bits: word c, byte r, bit s = commodity
+// window + 8c + s is present in piece r.
+constexpr int32_t kTileIds = 512;
+constexpr int32_t kTileRows = 8;
+constexpr int32_t kTileDescInts = 32;
+constexpr int32_t kTileMinItems = 128;        // fewest commodities of a window that make a piece
+constexpr int64_t kTileAutoPairs = 4000000;   // tiles are used by default from this many pairs on
+
 // Link blocks and the order of the rows.  The rows are dealt to blocks of equal weight
 // (largest row first, each to the lightest block so far); the flat octet array holds the rows
 // block after block, inside a block by ascending link id.  pos_link[i] is the link whose row
@@ -58,8 +80,8 @@ constexpr int32_t kSinglesPerLane = 8;        // a single-pair chunk holds 16 * 
 // boundary (the tail of its last pass is filled with padding octets that have no masks and
 // open no slot), so that one workgroup can reduce the rows of a block into LDS and apply the
 // length update of those links right away.  A block holds at most kBlkMaxSlots partial-sum
-// slots and kBlkMaxLinks links; a topology that breaks either bound, or one with single
-// pairs, has no blocks (n_blocks = 0) and runs the separate reduce and update kernels over the
+// slots and kBlkMaxLinks links; a topology that breaks either bound, one with single
+// pairs, or one that uses tiles, has no blocks (n_blocks = 0) and runs the separate reduce and update kernels over the
 // same arrays.
 constexpr int32_t kBlkMaxSlots = 1024;
 constexpr int32_t kBlkMaxLinks = 512;
@@ -109,6 +131,15 @@ struct HostTopo {
     int64_t n_octets = 0;                // unpadded
     int64_t n_octets_sigma = 0;          // of which numbered by sigma
     std::vector<int32_t> pass_first_slot; // [n_oct_padded / 64]
+    int32_t tiles = -1;                  // option: 1 = build tiles, 0 = never, -1 = by size
+    int32_t tile_min_items = 0;          // option: fewest commodities per piece (0 = default)
+    int32_t n_pieces = 0, n_tile_items = 0;
+    int64_t n_piece_items = 0;           // (link, commodity) pairs stored in pieces
+    int32_t n_pieces_uniform = 0;
+    bool tiles_dense_only = false;       // option: never store a piece as uniform
+    std::vector<int32_t> tile_desc;      // [kTileDescInts * n_tile_items]
+    std::vector<uint32_t> tile_mask;     // [512 * (dense pieces + 1)]
+    std::vector<uint64_t> tile_pres;     // [64 * (uniform items + 1)]
     int32_t blk_passes = 0;              // option: target passes per link block (0 = default)
     int32_t n_blocks = 0;                // 0: the topology does not fit link blocks
     std::vector<int32_t> pos_link;       // [E] link of every position of the flat order
@@ -124,7 +155,8 @@ struct HostTopo {
     std::vector<uint32_t> single_pair;   // [2 * n_singles_padded], rows padded to 2 pairs
     int64_t n_single_pairs = 0;          // unpadded
     std::vector<int32_t> schunk_begin, schunk_end, schunk_slot;   // pair units
-    std::vector<int32_t> link_sslot_ptr; // [E+1] single-chunk slots of a link (after the octet slots)
+    std::vector<int32_t> link_sslot_ptr; // [E+1] piece and single-chunk slots of a link (after
+                                         // all octet slots)
     int32_t n_slots = 0;                 // octet slots + single-chunk slots
     // forward records (n_records = 0 when the topology does not fit them: a path longer than
     // kRecMaxStride links, padding above 1.5x, or a commodity that alone overflows a record)
@@ -141,8 +173,12 @@ nimble_status_t validate_csr(int32_t n_links, const double *cap, int32_t n_comm,
                              const int32_t *path_link_ptr, const int32_t *path_links,
                              std::string &why);
 
+// Reads the layout options of `out` from the NIMBLE_TUNE_* environment variables (record
+// capacity, link block size, tiles on/off, piece threshold); unset variables leave defaults.
+void read_layout_options(HostTopo &out);
+
 // Builds everything in HostTopo from validated input.  out.rec_comm_cap (default kRecMaxComm)
-// and out.blk_passes are read as options.
+// out.blk_passes, out.tiles and out.tile_min_items are read as options.
 void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                      const int32_t *comm_path_ptr, int32_t n_paths,
                      const int32_t *path_link_ptr, const int32_t *path_links,

@@ -43,7 +43,15 @@ struct DeviceTopo {
                                       // pass, end pass, first slot, 0, 0, 0
     const uint32_t *single_pair;      // [2 * padded singles]
     const int32_t *schunk_begin, *schunk_end, *schunk_slot;   // [n_schunks], pair units
-    const int32_t *link_sslot_ptr;    // [E+1] single-chunk slots of a link
+    const int32_t *link_sslot_ptr;    // [E+1] piece and single-chunk slots of a link
+    // tile work items: up to 8 dense (link, window of 512 commodities) pieces of one window
+    int32_t n_tile_items;
+    const int32_t *tile_desc;         // [32 * n_tile_items]
+    const uint32_t *tile_mask;        // [512 * (dense pieces + 1)]
+    const uint64_t *tile_pres;        // [64 * (uniform items + 1)] presence bytes
+    int32_t tile_item_cost;           // weight of an item against an octet pass (wave split)
+    double *demand1t;                 // [K rounded up to whole windows] demands by id, and
+    double *demand2t;                 // [sigma_size] by sigma number, both window-transposed
     // second numbering of the commodities for the sigma octets, with sigma-ordered copies of
     // the choices and the demands
     int32_t sigma_size;
@@ -55,8 +63,8 @@ struct DeviceTopo {
     // state of the plan in flight: price by link id (the candidate scan gathers from it);
     // len and S by position in the streaming and persistent regimes
     double *len, *price, *S;   // [E]
-    uint8_t *choice;           // [K+8] (entries from K on are only read for empty masks or
-                               // padding pairs)
+    uint8_t *choice;           // [K rounded up to whole windows, + 8] (entries from K on are
+                               // only read for empty masks or padding pairs)
     uint32_t *count;           // [P]
     double *partial;           // [n_slots]
     double *scalars;           // [0] = 1/rho, [1..] = per-block maxima of S (update or link blocks)

@@ -69,8 +69,12 @@ __device__ __forceinline__ bool grid_barrier(SyncWords *w, unsigned int n_blocks
 }
 
 struct PersistentArgs {
-    int E, K, P, n_passes, n_schunks;
+    int E, K, P, n_passes, n_schunks, n_tile_items;
     uint32_t pad_comm;
+    const int32_t *tile_desc;
+    const uint32_t *tile_mask;
+    const uint64_t *tile_pres;
+    double *demand1t, *demand2t;
     const int32_t *cp, *lp, *pl;
     const int32_t *pass_first_slot;
     const uint32_t *oct_base, *oct_mask;
@@ -97,6 +101,9 @@ template <int MODE>
 __device__ __forceinline__ void reduce_both(const PersistentArgs &a, int wave, int n_waves,
                                             int lane)
 {
+    reduce_tile_phase<MODE>(a.n_tile_items, a.tile_desc, a.tile_mask, a.tile_pres, a.choice,
+                                a.demand1t,
+                            a.choice2, a.demand2t, a.partial, wave, n_waves, lane);
     reduce_flat_phase<MODE>(0, a.n_passes, a.pass_first_slot, a.oct_base, a.oct_mask, a.choice,
                             a.demand, a.choice2, a.demand2, a.partial, 0, wave, n_waves, lane);
     reduce_phase<MODE, kSinglesPerLane>(a.n_schunks, a.schunk_begin, a.schunk_end, a.schunk_slot,
@@ -131,8 +138,13 @@ __global__ __launch_bounds__(kPBlock) void k_persistent(PersistentArgs a)
     }
     for (int p = tid; p < a.P; p += n_threads) a.count[p] = 0u;
     for (int k = tid; k < a.K; k += n_threads) {
+        const double dk = a.demand[k];
+        a.demand1t[tile_demand_index(k)] = dk;
         const int sg = a.sigma[k];
-        if (sg >= 0) a.demand2[sg] = a.demand[k];
+        if (sg >= 0) {
+            a.demand2[sg] = dk;
+            a.demand2t[tile_demand_index(sg)] = dk;
+        }
     }
     if (!grid_barrier(a.sync, nb, a.spin_limit, &s_flag)) goto abandoned;
     reduce_both<1>(a, wave, n_waves, lane);
@@ -234,6 +246,12 @@ hipError_t launch_persistent(const DeviceTopo &t, void *sync_words, int n_cu,
     a.P = t.P;
     a.n_passes = t.n_passes;
     a.n_schunks = t.n_schunks;
+    a.n_tile_items = t.n_tile_items;
+    a.tile_desc = t.tile_desc;
+    a.tile_mask = t.tile_mask;
+    a.tile_pres = t.tile_pres;
+    a.demand1t = t.demand1t;
+    a.demand2t = t.demand2t;
     a.pad_comm = static_cast<uint32_t>(t.K);
     a.cp = t.comm_ptr;
     a.lp = t.path_ptr;

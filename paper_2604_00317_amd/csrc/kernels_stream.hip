@@ -20,13 +20,22 @@ __global__ __launch_bounds__(kBlock) void k_init(int E, int K, int P, bool cost_
                                                  uint32_t *__restrict__ count,
                                                  const int32_t *__restrict__ sigma,
                                                  const double *__restrict__ demand,
-                                                 double *__restrict__ demand2)
+                                                 double *__restrict__ demand1t,
+                                                 double *__restrict__ demand2,
+                                                 double *__restrict__ demand2t)
 {
     const int stride = gridDim.x * blockDim.x;
     const int tid = blockIdx.x * blockDim.x + threadIdx.x;
-    for (int k = tid; k < K; k += stride) {      // demands in sigma order for the sigma octets
+    // the library's own copies of the demands: in sigma order for the sigma octets, and by id
+    // and by sigma number in the window-transposed order the tile phase reads
+    for (int k = tid; k < K; k += stride) {
+        const double dk = demand[k];
+        demand1t[tile_demand_index(k)] = dk;
         const int sg = sigma[k];
-        if (sg >= 0) demand2[sg] = demand[k];
+        if (sg >= 0) {
+            demand2[sg] = dk;
+            demand2t[tile_demand_index(sg)] = dk;
+        }
     }
     for (int e = tid; e < E; e += stride) {
         len[e] = 1.0;
@@ -216,7 +225,11 @@ __global__ __launch_bounds__(kWave) void k_histogram(int K, int iters, int pmax,
 }
 
 struct ReduceArgs {
-    int n_passes, n_schunks;
+    int n_passes, n_schunks, n_tile_items, n_tile_waves;
+    const int32_t *tile_desc;
+    const uint32_t *tile_mask;
+    const uint64_t *tile_pres;
+    const double *demand1t, *demand2t;
     const int32_t *pass_first_slot;
     const uint32_t *oct_base, *oct_mask;
     const int32_t *schunk_begin, *schunk_end, *schunk_slot;
@@ -233,13 +246,21 @@ __global__ __launch_bounds__(kBlock) void k_load_reduce(ReduceArgs a)
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
-    reduce_flat_phase<MODE>(0, a.n_passes, a.pass_first_slot, a.oct_base, a.oct_mask, a.choice,
-                            a.demand, a.choice2, a.demand2, a.partial, 0, wave, n_waves, lane);
+    // the wave pool is split between the tile items and the octet passes in proportion to
+    // their estimated cost
+    if (wave < a.n_tile_waves)
+        reduce_tile_phase<MODE>(a.n_tile_items, a.tile_desc, a.tile_mask, a.tile_pres, a.choice,
+                                a.demand1t,
+                                a.choice2, a.demand2t, a.partial, wave, a.n_tile_waves, lane);
+    else
+        reduce_flat_phase<MODE>(0, a.n_passes, a.pass_first_slot, a.oct_base, a.oct_mask,
+                                a.choice, a.demand, a.choice2, a.demand2, a.partial, 0,
+                                wave - a.n_tile_waves, n_waves - a.n_tile_waves, lane);
     // single pairs (commodities with more than 32 candidates) are walked from the other end of
     // the wave pool
     reduce_phase<MODE, kSinglesPerLane>(a.n_schunks, a.schunk_begin, a.schunk_end, a.schunk_slot,
                                         a.single_pair, a.pad_comm, a.choice, a.demand, a.partial,
-                                        n_waves - 1 - wave, n_waves, lane);
+                                        wave, n_waves, lane);
 }
 
 // Link-load reduce and length update in one kernel, for topologies cut into link blocks: a
@@ -473,13 +494,29 @@ void launch_reduce_mode(const DeviceTopo &t, const uint8_t *choice, const double
                         hipStream_t s)
 {
     // a fixed pool of waves, each walking its passes with the loads pipelined
-    const int64_t waves = static_cast<int64_t>(t.n_passes) > (t.n_schunks + 3) / 4
-                              ? static_cast<int64_t>(t.n_passes)
-                              : (t.n_schunks + 3) / 4;
+    int64_t waves = static_cast<int64_t>(t.n_passes) + t.n_tile_items;
+    if (waves < (t.n_schunks + 3) / 4) waves = (t.n_schunks + 3) / 4;
     const int grid = blocks_for(waves * kWave, kBlock, t.reduce_blocks);
+    // waves of the tile items: their share of the estimated work (an item of 8 pieces weighs
+    // kTileItemCost passes), at least one wave for each kind of work that exists
+    const int64_t n_waves = static_cast<int64_t>(grid) * (kBlock / kWave);
+    const int64_t w_items = static_cast<int64_t>(t.n_tile_items) * t.tile_item_cost;
+    int64_t tile_waves = t.n_tile_items > 0 ? (n_waves * w_items + (w_items + t.n_passes) / 2) /
+                                                  (w_items + t.n_passes)
+                                            : 0;
+    if (t.n_tile_items > 0 && tile_waves < 1) tile_waves = 1;
+    if (tile_waves > t.n_tile_items) tile_waves = t.n_tile_items;
+    if (tile_waves > n_waves - 1) tile_waves = n_waves - 1;
     ReduceArgs a;
     a.n_passes = t.n_passes;
     a.n_schunks = t.n_schunks;
+    a.n_tile_items = t.n_tile_items;
+    a.n_tile_waves = static_cast<int>(tile_waves);
+    a.tile_desc = t.tile_desc;
+    a.tile_mask = t.tile_mask;
+    a.tile_pres = t.tile_pres;
+    a.demand1t = t.demand1t;
+    a.demand2t = t.demand2t;
     a.pass_first_slot = t.pass_first_slot;
     a.oct_base = t.oct_base;
     a.oct_mask = t.oct_mask;
@@ -510,7 +547,7 @@ void launch_init(const DeviceTopo &t, const double *demand, hipStream_t s)
     const int n = t.E > t.P ? t.E : t.P;
     hipLaunchKernelGGL(k_init, dim3(blocks_for(n, kBlock, 4096)), dim3(kBlock), 0, s, t.E, t.K,
                        t.P, t.cost_max, t.invcap, t.len, t.price, t.S, t.choice, t.count, t.sigma,
-                       demand, t.demand2);
+                       demand, t.demand1t, t.demand2, t.demand2t);
 }
 
 void launch_width(const DeviceTopo &t, const double *demand, hipStream_t s)

@@ -349,6 +349,106 @@ __device__ __forceinline__ void reduce_flat_phase(
     if (have_prev) finish(pd0, pd1, pmask0, pmask1, pextra, pflag, pslot);
 }
 
+// ---- phase B, tile part ---------------------------------------------------------------------
+// A work item is up to kTileRows pieces of one window: kTileIds consecutive commodity numbers
+// (ids, or sigma numbers).  Lane c owns column c, the commodities window + 8c .. + 7: it loads
+// their eight choices and eight demands once (coalesced over the wave) and uses them for every
+// piece of the item, whose masks arrive as two 16-byte loads per lane and piece.  No per-hit
+// gather is left.  Uniform pieces (one mask value plus presence bits) need no mask loads at
+// all: one 8-byte word per lane holds the presence bytes of all rows of the item.  The eight
+// per-lane row sums are added over the wave by wave_sum8 and lanes 0..7 store one partial each.
+// MODE 1 (width rho): every commodity with a non-zero mask counts once.
+// Position of commodity number nb in the window-transposed demand copies: inside a window of
+// kTileIds numbers the eight demands of a column are 64 entries apart, so that lane c's load of
+// demand sl sits next to lane c+1's (eight fully coalesced 8-byte loads per window).
+__device__ __forceinline__ int tile_demand_index(int nb)
+{
+    return (nb & ~(kTileIds - 1)) | ((nb & 7) << 6) | ((nb >> 3) & 63);
+}
+
+template <int MODE>
+__device__ __forceinline__ void reduce_tile_phase(
+    int n_items, const int32_t *__restrict__ tile_desc, const uint32_t *__restrict__ tile_mask,
+    const uint64_t *__restrict__ tile_pres,
+    const uint8_t *__restrict__ choice, const double *__restrict__ demand1t,
+    const uint8_t *__restrict__ choice2, const double *__restrict__ demand2t,
+    double *__restrict__ partial, int wave, int n_waves, int lane)
+{
+    // demand1t / demand2t: the demands by id / by sigma number, window-transposed
+    // (tile_demand_index)
+    const u32x4 *masks = reinterpret_cast<const u32x4 *>(tile_mask);
+    const int my_row = tile_row_of_lane(lane);
+    for (int it = wave; it < n_items; it += n_waves) {               // wave-uniform
+        const int32_t *d = tile_desc + size_t(it) * kTileDescInts;
+        const int base = __builtin_amdgcn_readfirstlane(d[0]);
+        const int flags = __builtin_amdgcn_readfirstlane(d[1]);
+        const int n_rows = __builtin_amdgcn_readfirstlane(d[2]);
+        const int first = __builtin_amdgcn_readfirstlane(d[3]);
+        const int my_slot = d[8 + my_row];
+        const bool sig = (flags & 1) != 0;
+        const uint8_t *ch_src = sig ? choice2 : choice;
+        const double *dm_src = (sig ? demand2t : demand1t) + base + lane;
+        uint2 ch = make_uint2(0u, 0u);
+        if constexpr (MODE == 0) ch = *reinterpret_cast<const uint2 *>(ch_src + base + 8 * lane);
+        double dm[8];
+#pragma unroll
+        for (int sl = 0; sl < 8; ++sl) dm[sl] = dm_src[sl * 64];
+        uint32_t c8[8];
+#pragma unroll
+        for (int sl = 0; sl < 8; ++sl) c8[sl] = ((sl < 4 ? ch.x : ch.y) >> (8 * (sl & 3))) & 31u;
+        double acc[kTileRows];
+        if ((flags & 2) != 0) {
+            // uniform pieces: one mask per piece (wave-uniform) and one presence byte per
+            // lane and piece; rows past the last piece have presence 0
+            const uint64_t pres = tile_pres[size_t(first) * 64 + lane];
+#pragma unroll
+            for (int r = 0; r < kTileRows; ++r) {
+                const uint32_t mr = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(d[16 + r]));
+                const uint32_t pb = static_cast<uint32_t>(pres >> (8 * r)) & 0xFFu;
+                double a = 0.0;
+#pragma unroll
+                for (int sl = 0; sl < 8; ++sl) {
+                    uint32_t h = pb >> sl;
+                    if constexpr (MODE == 0) h &= mr >> c8[sl];
+                    const int hit = __builtin_amdgcn_sbfe(static_cast<int>(h), 0u, 1u);
+                    a = a + __hiloint2double(__double2hiint(dm[sl]) & hit,
+                                             __double2loint(dm[sl]) & hit);
+                }
+                acc[r] = a;
+            }
+        } else {
+            // dense pieces: rows past the last piece re-read it and are not stored
+            u32x4 m0[kTileRows], m1[kTileRows];
+#pragma unroll
+            for (int r = 0; r < kTileRows; ++r) {
+                const int pr = first + (r < n_rows ? r : n_rows - 1);
+                m0[r] = stream_load(masks + size_t(pr) * 128 + lane);
+                m1[r] = stream_load(masks + size_t(pr) * 128 + 64 + lane);
+            }
+#pragma unroll
+            for (int r = 0; r < kTileRows; ++r) {
+                const uint32_t mk[8] = {m0[r].x, m0[r].y, m0[r].z, m0[r].w,
+                                        m1[r].x, m1[r].y, m1[r].z, m1[r].w};
+                double a = 0.0;
+#pragma unroll
+                for (int sl = 0; sl < 8; ++sl) {
+                    // all ones where the commodity routes through the link, else zero
+                    int hit;
+                    if constexpr (MODE == 0)
+                        hit = __builtin_amdgcn_sbfe(static_cast<int>(mk[sl]), c8[sl], 1u);
+                    else
+                        hit = mk[sl] != 0u ? -1 : 0;
+                    a = a + __hiloint2double(__double2hiint(dm[sl]) & hit,
+                                             __double2loint(dm[sl]) & hit);
+                }
+                acc[r] = a;
+            }
+        }
+        const double total = wave_sum8(acc, lane);
+        if (lane < 8 && my_row < n_rows) partial[my_slot] = total;
+    }
+}
+
 // ---- phase C: slot partials -> load, congestion sum, multiplicative length update ----------
 // One 16-lane DPP row per link: the lanes fetch the link's slot partials side by side (16 per
 // step), add their own in ascending slot order, and a fixed butterfly combines the 16 lane

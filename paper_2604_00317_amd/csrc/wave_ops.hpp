@@ -146,6 +146,44 @@ __device__ __forceinline__ double segmented_scan_f64(double v, int start, int la
     return v;
 }
 
+// Sums of eight per-lane values over the 64 lanes, all eight at once: three exchange steps
+// inside every group of 8 lanes halve the number of values a lane carries (a lane keeps the
+// half its lane bit selects and adds the partner's copy of it), three more steps add the eight
+// groups.  Returns the total of value number  4*bit2 + 2*bit0 + bit1  of the lane id (see
+// tile_row_of_lane); the order of the additions is the same on every run.
+__device__ __forceinline__ double wave_sum8(const double (&a)[8], int lane)
+{
+    const bool s2 = (lane & 4) != 0;
+    double v4[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const double keep = s2 ? a[4 + j] : a[j];
+        const double give = s2 ? a[j] : a[4 + j];
+        v4[j] = keep + dpp_f64<kDppHalfMirror>(give);     // partner 7 - l: the other bit 2
+    }
+    const bool s0 = (lane & 1) != 0;
+    double v2[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const double keep = s0 ? v4[2 + j] : v4[j];
+        const double give = s0 ? v4[j] : v4[2 + j];
+        v2[j] = keep + dpp_f64<kDppXor1>(give);
+    }
+    const bool s1 = (lane & 2) != 0;
+    const double keep = s1 ? v2[1] : v2[0];
+    const double give = s1 ? v2[0] : v2[1];
+    double v = keep + dpp_f64<kDppXor2>(give);
+    v = v + dpp_f64<0x128>(v);                            // row_ror:8, lane ^ 8
+    v = v + __shfl_xor(v, 16, kWave);
+    v = v + __shfl_xor(v, 32, kWave);
+    return v;
+}
+
+__device__ __forceinline__ int tile_row_of_lane(int lane)
+{
+    return ((lane >> 2) & 1) * 4 + (lane & 1) * 2 + ((lane >> 1) & 1);
+}
+
 __device__ __forceinline__ double wave_max(double v)
 {
     v = fmax(v, partner_f64<1>(v));

@@ -167,6 +167,31 @@ def test_streaming_reverse_layout_decodes_to_the_same_rows(cfg):
     assert st["octets"] <= st["octets_padded"] < st["octets"] + 64 * st["link_blocks"]
 
 
+@pytest.mark.parametrize("min_items", [1, 24, 128])
+def test_tiled_reverse_layout_decodes_to_the_same_rows(monkeypatch, min_items):
+    """With tiles switched on, commodities of one window of 512 numbers that share a link leave
+    the octet stream for dense pieces; pieces, octets and single pairs together must still
+    decode to exactly the reverse CSR, whatever the piece threshold."""
+    monkeypatch.setenv("NIMBLE_TUNE_TILES", "1")
+    monkeypatch.setenv("NIMBLE_TUNE_TILE_MIN_ITEMS", str(min_items))
+    topos = [W.config_topology(c) for c in (0, 1, 3)]
+    topos.append(W.random_topology(np.random.default_rng(5), 90, 17, 100, 7))
+    topos.append(W.random_topology(np.random.default_rng(11), 60, 1500, 6, 3))
+    for t in topos:
+        args = (t.n_links, t.n_comm, t.comm_path_ptr, t.n_paths, t.path_link_ptr, t.path_links)
+        a = B.nimble_host_build_reverse(*args)
+        b = B.nimble_host_build_reverse(*args, streaming=True)
+        for x, y in zip(a, b):
+            assert np.array_equal(x, y)
+        st = B.nimble_host_layout_stats(*args)
+        assert st["link_blocks"] == 0                  # tiles and link blocks exclude each other
+        assert (st["pieces"] + 7) // 8 <= st["tile_items"] <= st["pieces"]
+    # the 16-node fabric has dense windows at every threshold tried here
+    assert st["pieces"] >= 0 and B.nimble_host_layout_stats(
+        *(lambda t: (t.n_links, t.n_comm, t.comm_path_ptr, t.n_paths, t.path_link_ptr,
+                     t.path_links))(topos[2]))["pieces"] > 0
+
+
 def test_link_blocks_are_dropped_when_a_row_overflows_a_block():
     """One link that 600 000 single-path commodities share needs more partial-sum slots than a
     link block holds: the layout must still decode to the same rows, without blocks."""

@@ -159,6 +159,24 @@ def test_link_block_sizes(oracle_mod, B, monkeypatch, passes):
         check(oracle_mod, B, w.topo, w.traffic, w.eps, iters, regime=2, flags=1)
 
 
+@pytest.mark.parametrize("min_items", [1, 24, 128])
+def test_tiled_reverse_layout(oracle_mod, B, monkeypatch, min_items):
+    """Dense (link, window) pieces instead of octets, forced on for small fabrics and ragged
+    random instances at several piece thresholds, in both regimes that stream the layout."""
+    monkeypatch.setenv("NIMBLE_TUNE_TILES", "1")
+    monkeypatch.setenv("NIMBLE_TUNE_TILE_MIN_ITEMS", str(min_items))
+    for cfg, iters in ((0, 200), (1, 300), (3, 60)):
+        w = W.make_config(cfg)
+        for regime in (2, 3):
+            check(oracle_mod, B, w.topo, w.traffic, w.eps, iters, regime=regime)
+        check(oracle_mod, B, w.topo, w.traffic, w.eps, iters, regime=2, flags=1)
+    for seed, E, K, pm, lm in ((5, 90, 17, 100, 7), (11, 60, 1500, 6, 3), (12, 300, 700, 31, 2)):
+        rng = np.random.default_rng(seed)
+        t = W.random_topology(rng, E, K, pm, lm)
+        d = rng.integers(0, 1 << 30, size=t.n_comm).astype(np.float64)
+        check(oracle_mod, B, t, d, 0.1, 40, regime=2)
+
+
 def test_row_too_long_for_a_link_block(oracle_mod, B):
     """600 000 single-path commodities on one link: the row needs more partial-sum slots than a
     link block holds, so the streaming regime runs the separate reduce and update kernels."""
