@@ -650,9 +650,10 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                     }
                     for (int32_t i = lb - la; i < S; ++i) loc16.push_back(0xFFFFu);  // patched below
                 }
-                // candidates are padded to whole quads (the kernel never compares the padding)
+                // candidates are padded to whole quads; a padding candidate starts at the
+                // +inf price slot, so it never wins the argmin
                 for (int32_t q = pb - pa; q < align4(pb - pa); ++q)
-                    for (int32_t i = 0; i < S; ++i) loc16.push_back(0xFFFFu);
+                    for (int32_t i = 0; i < S; ++i) loc16.push_back(i == 0 ? 0xFFFEu : 0xFFFFu);
                 np += pb - pa;
                 npad += align4(pb - pa);
                 cp16.push_back(static_cast<uint16_t>(np));
@@ -678,10 +679,12 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                 }
                 links.swap(sorted);
                 for (auto &v : loc16)
-                    if (v != 0xFFFFu) v = static_cast<uint16_t>(rank[v]);
+                    if (v < 0xFFFEu) v = static_cast<uint16_t>(rank[v]);
             }
-            for (auto &v : loc16)
-                if (v == 0xFFFFu) v = static_cast<uint16_t>(nl);     // the +0.0 price slot
+            for (auto &v : loc16) {
+                if (v == 0xFFFFu) v = static_cast<uint16_t>(nl);          // the +0.0 price slot
+                else if (v == 0xFFFEu) v = static_cast<uint16_t>(nl + 1); // the +inf price slot
+            }
             t.records.resize(static_cast<size_t>(t.n_records + 1) * kRecBytes, 0);
             uint8_t *r = t.records.data() + static_cast<size_t>(t.n_records) * kRecBytes;
             const int32_t off_sig = kRecHeader + 4 * nl;

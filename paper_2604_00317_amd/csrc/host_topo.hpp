@@ -93,7 +93,8 @@ constexpr int32_t kBlkMaxLinks = 512;
 // prices it gathers into LDS), the first candidate of every commodity, and for every candidate
 // exactly `stride` 8-bit indices into the record's link table.  Paths shorter than the stride
 // are padded with the index n_links, whose price slot holds +0.0 (neutral for sum and for max
-// of positive prices).  Layout, offsets in bytes from the start of the record:
+// of positive prices); the candidates that pad a commodity to a multiple of 4 start with the
+// index n_links + 1, whose price slot holds +inf, so their cost is +inf.  Layout, offsets in bytes from the start of the record:
 //   0   int32 k0        first commodity
 //   4   int32 p0        first candidate path (global id)
 //   8   uint16 nk, np, n_links, off_cp, off_loc, off_sig, off_cq, npad
@@ -108,7 +109,8 @@ constexpr int32_t kBlkMaxLinks = 512;
 #endif
 constexpr int32_t kRecBytes = 1024 * NIMBLE_REC_KB;   // one 16-byte load per lane and KiB
 constexpr int32_t kRecHeader = 24;
-constexpr int32_t kRecMaxLinks = 254;     // link table entries (8-bit indices); slot n_links holds +0.0
+constexpr int32_t kRecMaxLinks = 254;     // link table entries (8-bit indices); slots n_links and
+                                          // n_links + 1 hold +0.0 and +inf
 constexpr int32_t kRecMaxStride = 8;      // longest path a record can hold
 constexpr int32_t kRecMaxComm = 64;
 

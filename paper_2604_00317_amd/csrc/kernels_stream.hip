@@ -146,7 +146,10 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records, 
             const int i = lane + q * kWave;
             if (i < nl) s_price[i] = pr[q];
         }
-        if (lane == 0) s_price[nl] = 0.0;
+        if (lane == 0) {
+            s_price[nl] = 0.0;                       // pads short paths
+            s_price[nl + 1] = __builtin_inf();       // first step of padding candidates
+        }
         wave_lds_sync();
         const int rounds = (nk + kGroups - 1) / kGroups;
         for (int r = 0; r < rounds; ++r) {        // wave-uniform: all lanes reach the reduction
@@ -166,19 +169,26 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records, 
                     uint32_t w[S];
 #pragma unroll
                     for (int i = 0; i < S; ++i) w[i] = lp[i * (npad_rec >> 2)];
+                    double cst[4];
 #pragma unroll
                     for (int c4 = 0; c4 < 4; ++c4) {
-                        double cst = 0.0;
+                        // 0 + p0 is p0: the sum starts at the first price
+                        cst[c4] = s_price[(w[0] >> (8 * c4)) & 0xFFu];
 #pragma unroll
-                        for (int i = 0; i < S; ++i) {
+                        for (int i = 1; i < S; ++i) {
                             const double pe = s_price[(w[i] >> (8 * c4)) & 0xFFu];
-                            if constexpr (MAXC) cst = (pe > cst) ? pe : cst;
-                            else cst = cst + pe;
+                            if constexpr (MAXC) cst[c4] = (pe > cst[c4]) ? pe : cst[c4];
+                            else cst[c4] = cst[c4] + pe;
                         }
-                        if (jq + c4 < np && cst < best) {      // padding never competes
-                            best = cst;
-                            bj = jq + c4;
-                        }
+                    }
+                    // minimum of the quad (padding candidates cost +inf), then the lowest
+                    // candidate that holds it
+                    const double m4 = fast_min_f64(fast_min_f64(cst[0], cst[1]),
+                                                   fast_min_f64(cst[2], cst[3]));
+                    const int i4 = cst[0] == m4 ? 0 : (cst[1] == m4 ? 1 : (cst[2] == m4 ? 2 : 3));
+                    if (m4 < best) {
+                        best = m4;
+                        bj = jq + i4;
                     }
                 }
             }
@@ -429,7 +439,7 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, uint8_t *choice, uint32_t
                         hipStream_t s)
 {
     if (t.n_records > 0) {
-        const int rec_lds = (kRecBytes + 8 * (t.rec_max_links + 1) + 15) & ~15;
+        const int rec_lds = (kRecBytes + 8 * (t.rec_max_links + 2) + 15) & ~15;
         const int rpw = t.rec_per_wave > 0 ? t.rec_per_wave : kRecPerWave;
         const int rec_grid = (t.n_records + kRecWaves * rpw - 1) / (kRecWaves * rpw);
 #define NIMBLE_REC_LAUNCH(SS)                                                                  \
