@@ -13,15 +13,17 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "nimble_oracle.c")
+_SRC_ALG1 = os.path.join(_HERE, "alg1_oracle.c")
 _LIB = os.path.join(_HERE, "libnimble_oracle.so")
 _lib = None
 
 
 def build(force: bool = True) -> str:
     """Compile the oracle with gcc.  -ffp-contract=off keeps every statement one IEEE op."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_ALG1))
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared",
-               "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+               "-Wall", "-Wextra", "-o", _LIB, _SRC, _SRC_ALG1, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -37,6 +39,11 @@ def _load():
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_double, ctypes.c_int32,
             ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_void_p]
+        lib.nimble_oracle_alg1.restype = ctypes.c_int
+        lib.nimble_oracle_alg1.argtypes = [
+            ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_double, ctypes.c_double,
+            ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         lib.nimble_oracle_max_threads.restype = ctypes.c_int
         lib.nimble_oracle_set_threads.argtypes = [ctypes.c_int]
         _lib = lib
@@ -93,3 +100,26 @@ def congestion(n_links, cap, comm_path_ptr, path_link_ptr, path_links, demand, s
                        minlength=n_links)
     util = load / np.asarray(cap, dtype=np.float64)
     return float(util.max()), util
+
+
+def alg1(n_links, cap, n_comm, comm_path_ptr, n_paths, path_link_ptr, path_links, demand,
+         phi, chi, max_sweeps=1 << 20):
+    """Algorithm 1 (sequential sweep, fraction phi of the remainder in chunks of chi).
+    Returns dict(flows [n_paths] bytes, lam, sweeps, load [n_links])."""
+    cap = np.ascontiguousarray(cap, dtype=np.float64)
+    cp = np.ascontiguousarray(comm_path_ptr, dtype=np.int32)
+    lp = np.ascontiguousarray(path_link_ptr, dtype=np.int32)
+    pl = np.ascontiguousarray(path_links, dtype=np.int32)
+    d = np.ascontiguousarray(demand, dtype=np.float64)
+    assert cap.shape == (n_links,) and cp.shape == (n_comm + 1,) and lp.shape == (n_paths + 1,)
+    assert d.shape == (n_comm,) and pl.shape == (int(lp[-1]),)
+    flows = np.empty(max(n_paths, 1), dtype=np.float64)
+    lam = np.zeros(1, dtype=np.float64)
+    sweeps = np.zeros(1, dtype=np.int32)
+    load = np.empty(n_links, dtype=np.float64)
+    rc = _load().nimble_oracle_alg1(n_links, _p(cap), n_comm, _p(cp), n_paths, _p(lp), _p(pl),
+                                    _p(d), float(phi), float(chi), int(max_sweeps), _p(flows),
+                                    _p(lam), _p(sweeps), _p(load))
+    if rc != 0:
+        raise ValueError(f"nimble_oracle_alg1 failed with code {rc}")
+    return dict(flows=flows[:n_paths], lam=float(lam[0]), sweeps=int(sweeps[0]), load=load)
