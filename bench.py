@@ -241,6 +241,44 @@ def main() -> int:
                 ms_per_step=q["elapsed"] * 1e3 / steps,
                 regime=REGIME_NAMES.get(q["regime"], "auto"), batch=q["batch"],
                 iters=q["w"].iters)
+            if cfg == 2:
+                # the paper's own sequential planner (Algorithm 1) on the same batch: one GPU
+                # thread per problem; lambda against the Jacobi MWU plan of the same problems
+                phi, chi = 0.5, float(1 << 20)
+                nb, P = q["batch"], q["topo"].n_paths
+                d_flows = torch.empty(nb * P, dtype=torch.float64, device="cuda:0")
+                d_lam1 = torch.empty(nb, dtype=torch.float64, device="cuda:0")
+                d_sw = torch.empty(nb, dtype=torch.int32, device="cuda:0")
+
+                def alg1_step():
+                    B.nimble_alg1_solve_batch(q["h"], nb, q["d_traffic"], phi, chi, 1 << 20,
+                                              d_flows, d_lam1, d_sw)
+                alg1_step()
+                torch.cuda.synchronize()
+                t1 = time.perf_counter()
+                for _ in range(steps):
+                    alg1_step()
+                torch.cuda.synchronize()
+                dt = time.perf_counter() - t1
+                ratio = (d_lam1 / q["d_lambda"]).cpu().numpy()
+                entry = dict(plans_per_s=nb * steps / dt, ms_per_step=dt * 1e3 / steps, batch=nb,
+                             phi=phi, chi=chi, mean_sweeps=float(d_sw.float().mean().item()),
+                             lambda_over_mwu_mean=float(ratio.mean()),
+                             lambda_over_mwu_max=float(ratio.max()))
+                if args.cpu_iters != 0:
+                    import oracle
+                    n_cpu = min(nb, 256)
+                    t1 = time.perf_counter()
+                    worst = 0.0
+                    lam1 = d_lam1.cpu().numpy()
+                    for b in range(n_cpu):
+                        ref = oracle.alg1(*q["topo"].csr(), q["w"].traffic[b], phi, chi)
+                        worst = max(worst, abs(lam1[b] - ref["lam"]))
+                    dtc = time.perf_counter() - t1
+                    entry["cpu_oracle_plans_per_s"] = n_cpu / dtc
+                    entry["cpu_sample"] = f"first {n_cpu} of {nb} problems, one core"
+                    entry["max_abs_diff_lambda"] = worst
+                also[f"configs[{cfg}] {q['w'].name} (Algorithm 1)"] = entry
             q["h"].close()
             del q
 

@@ -119,6 +119,36 @@ nimble_status_t nimble_plan_solve_batch(nimble_topo_t *topo, int32_t batch,
                                         const double *d_traffic, double eps, int32_t iters,
                                         double *d_splits, double *d_lambda, void *hip_stream);
 
+/*
+ * The sequential planner of Algorithm 1 ("Link Load Balancing w. Iterative Approximation",
+ * Sec. IV-B), for `batch` independent problems on the same topology.  Per problem: link loads
+ * and costs start at 0 and every pair's remainder at its demand; while any remainder is left
+ * the pairs are swept in order, and a pair with remainder r > 0 takes the candidate with the
+ * lowest bottleneck cost max_e F(L_e) (strict `<` in candidate order), routes f = r if r < chi,
+ * else the largest multiple of chi that is <= r * phi (one chunk when that is 0), and adds f to
+ * the loads of that candidate's links at once (the next pair sees it).  F(L_e) = L_e / cap_e.
+ * One GPU thread runs one problem.
+ *
+ *   d_traffic   device [batch][n_comm], bytes >= 0
+ *   phi         routed fraction of the remainder per visit, 0 < phi <= 1
+ *   chi         chunk granularity in bytes, > 0
+ *   max_sweeps  bound on the sweeps of a problem, >= 1
+ *   d_flows     device [batch][n_paths] out: bytes routed on every candidate path (the
+ *               algorithm's per-pair path and flow lists, summed per path); the flows of a
+ *               pair add up to its demand
+ *   d_lambda    device [batch] out: max_e L_e / cap_e; NaN for a problem that still had
+ *               traffic left after max_sweeps sweeps
+ *   d_sweeps    device int32 [batch] out: sweeps made
+ *   hip_stream  as for nimble_plan_solve: the call only enqueues work.
+ * Errors: NIMBLE_ERR_INVALID for bad arguments; NIMBLE_ERR_RANGE when 8 x (n_links + n_comm)
+ * doubles exceed 150 KB (the per-problem state lives in LDS, 8 to 64 problems per workgroup).
+ * Results are bit-identical to the plain CPU definition for any demands.
+ */
+nimble_status_t nimble_alg1_solve_batch(nimble_topo_t *topo, int32_t batch,
+                                        const double *d_traffic, double phi, double chi,
+                                        int32_t max_sweeps, double *d_flows, double *d_lambda,
+                                        int32_t *d_sweeps, void *hip_stream);
+
 /* Last error message of the calling thread ("" if none). Never NULL. */
 const char *nimble_last_error(void);
 

@@ -27,6 +27,7 @@ EXPORTS = [
     "nimble_topo_num_paths", "nimble_topo_nnz", "nimble_topo_bytes_per_iter",
     "nimble_topo_set_regime", "nimble_topo_regime", "nimble_debug_run_phase",
     "nimble_host_build_reverse", "nimble_debug_set_spin_limit", "nimble_topo_phase_bytes",
+    "nimble_alg1_solve_batch",
     "nimble_host_records_roundtrip", "nimble_host_layout_stats",
     "nimble_host_build_reverse_streaming",
 ]
@@ -80,6 +81,9 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.nimble_debug_set_spin_limit.argtypes = [vp, u32]
     lib.nimble_host_records_roundtrip.restype = ctypes.c_int
     lib.nimble_host_records_roundtrip.argtypes = [i32, i32, vp, i32, vp, vp, vp, vp, vp]
+    lib.nimble_alg1_solve_batch.restype = ctypes.c_int
+    lib.nimble_alg1_solve_batch.argtypes = [vp, i32, vp, ctypes.c_double, ctypes.c_double, i32,
+                                            vp, vp, vp, vp]
     lib.nimble_host_layout_stats.restype = ctypes.c_int
     lib.nimble_host_layout_stats.argtypes = [i32, i32, vp, i32, vp, vp, vp]
     for name in ("nimble_host_build_reverse", "nimble_host_build_reverse_streaming"):
@@ -210,6 +214,16 @@ def nimble_plan_solve_batch(topo: Topo, batch: int, d_traffic, eps: float, iters
         _dev_ptr(d_lambda, "float64", batch, "d_lambda"), _stream_ptr(stream)))
 
 
+def nimble_alg1_solve_batch(topo: Topo, batch: int, d_traffic, phi: float, chi: float,
+                            max_sweeps: int, d_flows, d_lambda, d_sweeps, stream=None) -> None:
+    _check(load_library().nimble_alg1_solve_batch(
+        topo.handle, int(batch),
+        _dev_ptr(d_traffic, "float64", batch * topo.n_comm, "d_traffic"), float(phi), float(chi),
+        int(max_sweeps), _dev_ptr(d_flows, "float64", batch * topo.n_paths, "d_flows"),
+        _dev_ptr(d_lambda, "float64", batch, "d_lambda"),
+        _dev_ptr(d_sweeps, "int32", batch, "d_sweeps"), _stream_ptr(stream)))
+
+
 def nimble_debug_run_phase(topo: Topo, phase: int, reps: int, d_traffic, stream=None) -> None:
     _check(load_library().nimble_debug_run_phase(
         topo.handle, int(phase), int(reps),
@@ -290,3 +304,22 @@ def plan(topo: Topo, traffic, eps: float, iters: int, device: str = "cuda:0"):
     nimble_plan_solve_batch(topo, b, d.reshape(-1), eps, iters, splits, lam)
     torch.cuda.synchronize()
     return splits.cpu().numpy().reshape(b, topo.n_paths), lam.cpu().numpy()
+
+
+def plan_alg1(topo: Topo, traffic, phi: float, chi: float, max_sweeps: int = 1 << 20,
+              device: str = "cuda:0"):
+    """Convenience wrapper of nimble_alg1_solve_batch: host demands [batch][n_comm] (or one
+    vector) in, (flows, lambda, sweeps) as numpy out."""
+    import torch
+    d = torch.as_tensor(np.ascontiguousarray(traffic, dtype=np.float64)).to(device)
+    single = d.dim() == 1
+    b = 1 if single else d.shape[0]
+    flows = torch.full((b * topo.n_paths,), float("nan"), dtype=torch.float64, device=device)
+    lam = torch.full((b,), float("nan"), dtype=torch.float64, device=device)
+    sweeps = torch.full((b,), -1, dtype=torch.int32, device=device)
+    nimble_alg1_solve_batch(topo, b, d.reshape(-1), phi, chi, max_sweeps, flows, lam, sweeps)
+    torch.cuda.synchronize()
+    f = flows.cpu().numpy().reshape(b, topo.n_paths)
+    if single:
+        return f[0], float(lam.item()), int(sweeps.item())
+    return f, lam.cpu().numpy(), sweeps.cpu().numpy()

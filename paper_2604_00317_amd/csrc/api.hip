@@ -461,6 +461,32 @@ nimble_status_t nimble_plan_solve_batch(nimble_topo_t *topo, int32_t batch,
     return NIMBLE_OK;
 }
 
+nimble_status_t nimble_alg1_solve_batch(nimble_topo_t *topo, int32_t batch,
+                                        const double *d_traffic, double phi, double chi,
+                                        int32_t max_sweeps, double *d_flows, double *d_lambda,
+                                        int32_t *d_sweeps, void *hip_stream)
+{
+    g_last_error.clear();
+    if (!topo) return fail(NIMBLE_ERR_INVALID, "topology handle is NULL");
+    if (!d_traffic || !d_flows || !d_lambda || !d_sweeps)
+        return fail(NIMBLE_ERR_INVALID,
+                    "traffic, flows, lambda and sweeps pointers must not be NULL");
+    if (batch < 1) return fail(NIMBLE_ERR_INVALID, "batch must be >= 1");
+    if (!(phi > 0.0) || !(phi <= 1.0)) return fail(NIMBLE_ERR_INVALID, "phi must be in (0, 1]");
+    if (!(chi > 0.0) || !std::isfinite(chi))
+        return fail(NIMBLE_ERR_INVALID, "chi must be positive and finite");
+    if (max_sweeps < 1) return fail(NIMBLE_ERR_INVALID, "max_sweeps must be >= 1");
+    if (!nimble::alg1_fits(topo->d))
+        return fail(NIMBLE_ERR_RANGE,
+                    "8 x (links + commodities) doubles do not fit in the LDS of a compute unit");
+    nimble_status_t st = check_device(topo);
+    if (st != NIMBLE_OK) return st;
+    hipError_t e = nimble::launch_alg1(topo->d, batch, d_traffic, phi, chi, max_sweeps, d_flows,
+                                       d_lambda, d_sweeps, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail_hip(e, "kernel launch (Algorithm 1)");
+    return NIMBLE_OK;
+}
+
 nimble_status_t nimble_debug_set_spin_limit(nimble_topo_t *topo, uint32_t polls)
 {
     g_last_error.clear();

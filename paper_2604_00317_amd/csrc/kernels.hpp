@@ -109,4 +109,14 @@ hipError_t launch_persistent(const DeviceTopo &t, void *sync_words, int n_cu,
                              unsigned int spin_limit, const double *demand, double eps,
                              int32_t iters, double *splits, double *lambda, hipStream_t s);
 
+// ---- Algorithm 1 (sequential sweep), one thread per problem of a batch -----------------------
+// LDS one workgroup (64 problems, down to 8 for larger topologies) needs, and whether it fits
+// the LDS of a compute unit.
+size_t alg1_lds_bytes(const DeviceTopo &t);
+bool alg1_fits(const DeviceTopo &t);
+// lambda[b] is NaN when problem b still had traffic left after max_sweeps sweeps.
+hipError_t launch_alg1(const DeviceTopo &t, int32_t batch, const double *demand, double phi,
+                       double chi, int32_t max_sweeps, double *flows, double *lambda,
+                       int32_t *sweeps, hipStream_t s);
+
 }  // namespace nimble

@@ -18,7 +18,7 @@ def test_library_exports_every_declared_symbol():
     lib = B.load_library()
     header = open(os.path.join(ROOT, "include", "nimble_plan.h")).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(nimble_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(nimble_[a-z0-9_]+)\s*\(", header))
     assert declared, "no declarations found"
     for name in declared:
         assert hasattr(lib, name), name
