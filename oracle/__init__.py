@@ -4,3 +4,4 @@ Nothing in the product path (`paper_2604_00317_amd`) may import this package; on
 `__graft_entry__.smoke()` and the `cpu_baseline` leg of `bench.py` do.
 """
 from .oracle import solve, alg1, build, max_threads, set_threads, congestion  # noqa: F401
+from .quantize_oracle import quantize  # noqa: F401
