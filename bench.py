@@ -227,6 +227,36 @@ def main() -> int:
                        max_abs_diff_splits=float(np.abs(g_s - ref["splits"]).max()),
                        max_rel_diff_lambda=abs(g_l - ref["lam"]) / max(ref["lam"], 1e-300))
     setup = {"generate": r["t_gen"], "topo_create": r["t_create"]}
+
+    # ---- post-processing of the plan into byte flows per path (whole chunks) ----------------
+    post = None
+    if not w.batch and not args.no_also:
+        n_it = w.iters
+        B.nimble_plan_solve(h, r["d_traffic"], w.eps, n_it, r["d_splits"], r["d_lambda"])
+        chi, theta = 1 << 20, float(1 << 20)
+        d_flows = torch.empty(topo.n_paths, dtype=torch.float64, device="cuda:0")
+        B.nimble_plan_quantize(h, r["d_traffic"], r["d_splits"], n_it, chi, theta, d_flows)
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(20):
+            B.nimble_plan_quantize(h, r["d_traffic"], r["d_splits"], n_it, chi, theta, d_flows)
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t1) / 20
+        post = dict(kernel="quantize", us_per_plan=dt * 1e6, chi=chi, small_threshold=theta,
+                    bytes=int(16 * topo.n_paths + 12 * topo.n_comm),
+                    gbs=(16 * topo.n_paths + 12 * topo.n_comm) / dt / 1e9)
+        if args.cpu_iters != 0:
+            import oracle
+            n_k = min(topo.n_comm, 20000)           # the Python oracle on the first pairs
+            cp = topo.comm_path_ptr[:n_k + 1]
+            sp = r["d_splits"].cpu().numpy()
+            t1 = time.perf_counter()
+            ref = oracle.quantize(cp, w.traffic[:n_k], sp[:cp[-1]], n_it, chi, theta)
+            dtc = time.perf_counter() - t1
+            got = d_flows.cpu().numpy()[:cp[-1]]
+            post["cpu_oracle_us_per_plan"] = dtc * 1e6 * topo.n_comm / n_k
+            post["cpu_sample"] = f"first {n_k} of {topo.n_comm} pairs, one core, scaled"
+            post["max_abs_diff_flows"] = float(np.abs(got - ref).max())
     h.close()
     del r
 
@@ -297,6 +327,7 @@ def main() -> int:
         "kernels": kernels,
         "cpu_baseline": cpu,
         "also": also,
+        "post_processing": post,
         "setup_s": setup,
     }
     print(json.dumps(out))

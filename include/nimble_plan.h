@@ -149,6 +149,32 @@ nimble_status_t nimble_alg1_solve_batch(nimble_topo_t *topo, int32_t batch,
                                         int32_t max_sweeps, double *d_flows, double *d_lambda,
                                         int32_t *d_sweeps, void *hip_stream);
 
+/*
+ * Post-processing of a plan into what a dataplane consumes: bytes per candidate path in whole
+ * chunks (the Paths / Flows lists of Algorithm 1), with the practical policies of Sec. I and
+ * Sec. V-A: no fragmentation below the chunk granularity and no multi-hop forwarding of small
+ * messages (1 MB or less in the paper).  Per pair with demand d and counts c_j = splits_j * iters:
+ *   d <= small_threshold: everything on the pair's first candidate;
+ *   otherwise N = floor(d / chi) whole chunks are apportioned by largest remainder (quota
+ *   floor(N * c_j / iters); the chunks left over go to the largest remainders N * c_j mod iters,
+ *   ties to the lower index) and the residual d - N * chi joins the candidate with the largest
+ *   count (ties to the lower index).
+ *
+ *   d_traffic        device [n_comm], the demands the plan was solved for
+ *   d_splits         device [n_paths], the output of nimble_plan_solve with the same iters
+ *   iters            >= 1
+ *   chi              chunk in bytes, 1 <= chi <= 2^40
+ *   small_threshold  bytes, >= 0 (0: no pair is treated as small unless its demand is 0)
+ *   d_flows          device [n_paths] out: bytes per candidate path; the flows of a pair add up
+ *                    to its demand exactly (integer demands below 2^53).  A pair with
+ *                    d / chi >= 2^31 gets NaN flows.
+ * One batch entry per call; only enqueues work on hip_stream.  Bit-identical to the plain CPU
+ * definition.
+ */
+nimble_status_t nimble_plan_quantize(nimble_topo_t *topo, const double *d_traffic,
+                                     const double *d_splits, int32_t iters, int64_t chi,
+                                     double small_threshold, double *d_flows, void *hip_stream);
+
 /* Last error message of the calling thread ("" if none). Never NULL. */
 const char *nimble_last_error(void);
 

@@ -487,6 +487,28 @@ nimble_status_t nimble_alg1_solve_batch(nimble_topo_t *topo, int32_t batch,
     return NIMBLE_OK;
 }
 
+nimble_status_t nimble_plan_quantize(nimble_topo_t *topo, const double *d_traffic,
+                                     const double *d_splits, int32_t iters, int64_t chi,
+                                     double small_threshold, double *d_flows, void *hip_stream)
+{
+    g_last_error.clear();
+    if (!topo) return fail(NIMBLE_ERR_INVALID, "topology handle is NULL");
+    if (!d_traffic || !d_splits || !d_flows)
+        return fail(NIMBLE_ERR_INVALID, "traffic, splits and flows pointers must not be NULL");
+    if (iters < 1) return fail(NIMBLE_ERR_INVALID, "iters must be >= 1");
+    if (chi < 1 || chi > (1LL << 40))
+        return fail(NIMBLE_ERR_INVALID, "chi must be a whole number of bytes in [1, 2^40]");
+    if (!(small_threshold >= 0.0))
+        return fail(NIMBLE_ERR_INVALID, "small_threshold must be >= 0");
+    nimble_status_t st = check_device(topo);
+    if (st != NIMBLE_OK) return st;
+    hipError_t e = nimble::launch_quantize(topo->d, d_traffic, d_splits, iters, chi,
+                                           small_threshold, d_flows,
+                                           static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail_hip(e, "kernel launch (plan quantisation)");
+    return NIMBLE_OK;
+}
+
 nimble_status_t nimble_debug_set_spin_limit(nimble_topo_t *topo, uint32_t polls)
 {
     g_last_error.clear();

@@ -119,4 +119,9 @@ hipError_t launch_alg1(const DeviceTopo &t, int32_t batch, const double *demand,
                        double chi, int32_t max_sweeps, double *flows, double *lambda,
                        int32_t *sweeps, hipStream_t s);
 
+// ---- plan post-processing: fractions -> bytes per path in whole chunks ----------------------
+hipError_t launch_quantize(const DeviceTopo &t, const double *demand, const double *splits,
+                           int32_t iters, int64_t chi, double theta, double *flows,
+                           hipStream_t s);
+
 }  // namespace nimble
