@@ -290,9 +290,17 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     NIMBLE_TRY(upload(t, h.tile_desc.data(), h.tile_desc.size(), &d.tile_desc), "tile_desc");
     NIMBLE_TRY(upload(t, h.tile_mask.data(), h.tile_mask.size(), &d.tile_mask), "tile_mask");
     NIMBLE_TRY(upload(t, h.tile_pres.data(), h.tile_pres.size(), &d.tile_pres), "tile_pres");
+    NIMBLE_TRY(upload(t, h.strip_base.data(), h.strip_base.size(), &d.strip_base), "strip_base");
+    NIMBLE_TRY(upload(t, h.strip_pres.data(), h.strip_pres.size(), &d.strip_pres), "strip_pres");
+    NIMBLE_TRY(upload(t, h.strip_mask.data(), h.strip_mask.size(), &d.strip_mask), "strip_mask");
+    NIMBLE_TRY(upload(t, h.strip_slot.data(), h.strip_slot.size(), &d.strip_slot), "strip_slot");
+    d.n_strip_items = h.n_strip_items;
     d.n_tile_items = h.n_tile_items;
     {
         const size_t k_pad = (static_cast<size_t>(h.K) + 511) & ~static_cast<size_t>(511);
+        // 8 spare entries: an octet may start at the last multiple of 4 below K
+        NIMBLE_TRY(allocate(t, k_pad + 8, &d.demand1n), "demand1n");
+        NIMBLE_TRY(hipMemset(d.demand1n, 0, sizeof(double) * (k_pad + 8)), "demand1n clear");
         NIMBLE_TRY(allocate(t, k_pad, &d.demand1t), "demand1t");
         NIMBLE_TRY(hipMemset(d.demand1t, 0, sizeof(double) * k_pad), "demand1t clear");
         NIMBLE_TRY(allocate(t, static_cast<size_t>(h.sigma_size), &d.demand2t), "demand2t");
@@ -351,7 +359,10 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     // per piece
     t->bytes_reduce += 2048LL * (h.n_pieces - h.n_pieces_uniform) + 8LL * h.n_pieces +
                        (128LL + 512 + 4096) * h.n_tile_items +
-                       512LL * static_cast<int64_t>(h.tile_pres.size() / 64 - 1);
+                       512LL * static_cast<int64_t>(h.tile_pres.size() / 64 - 1) +
+                       // strip items: base, presence, masks and slots per lane (20 B), one line
+                       // of choices and one of demands per column, a partial per unit and row
+                       64LL * (20 + 8 + 64 + 8) * h.n_strip_items;
     if (d.n_blocks > 0) {
         // one kernel: the slot partials stay in LDS; per block two table entries and one maximum
         t->bytes_reduce = 36LL * static_cast<int64_t>(h.oct_base.size()) + 4LL * d.n_passes +

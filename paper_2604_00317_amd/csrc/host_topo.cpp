@@ -263,8 +263,9 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
     t.n_octets_sigma = 0;
     t.n_octets = 0;
     t.n_piece_items = 0;
-    int32_t extra_slots = 0;              // slots of pieces and single-pair chunks, link by link
+    int32_t extra_slots = 0;              // slots of pieces, strip rows and single-pair chunks
     std::vector<int32_t> piece_extra;     // per piece (creation order = link order)
+    std::vector<int32_t> link_chunk_first(n_links + 1, 0);
     {
         std::vector<Item> items, rest, left1, left2, left3;
         std::unordered_map<int32_t, int32_t> win_count;
@@ -347,7 +348,6 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                 return kx != ky ? kx < ky : ((x.a >> kWindowShift) & 3u) < ((y.a >> kWindowShift) & 3u);
             });
             pack(left2, n_comm + 8, 1, 0u, row_base[e], row_mask[e], left3);
-            t.n_octets += static_cast<int64_t>(row_base[e].size());
             // single pairs (commodities with several windows) and their chunks, in link order
             const int32_t s_first = static_cast<int32_t>(t.single_pair.size() / 2);
             for (const Item &it : left3) {
@@ -360,15 +360,117 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                 t.single_pair.push_back(0u);
             }
             const int32_t s_last = static_cast<int32_t>(t.single_pair.size() / 2);
-            // the link's slots outside the octet range: one per piece, then one per chunk
-            t.link_sslot_ptr[e] = extra_slots;
-            for (size_t q = 0; q < link_pieces[e].size(); ++q) piece_extra.push_back(extra_slots++);
+            link_chunk_first[e] = static_cast<int32_t>(t.schunk_begin.size());
             for (int32_t b = s_first; b < s_last; b += sgl_chunk) {
                 t.schunk_begin.push_back(b);
                 t.schunk_end.push_back(b + sgl_chunk < s_last ? b + sgl_chunk : s_last);
-                t.schunk_slot.push_back(extra_slots++);
             }
         }
+        link_chunk_first[n_links] = static_cast<int32_t>(t.schunk_begin.size());
+    }
+
+    // ---- strips: short rows that several links share ---------------------------------------
+    // Rows that are left with the very same octets (the same commodities: e.g. the rail links
+    // between two nodes) and one mask value each are taken out of the octet stream.  A UNIT is
+    // 8 columns (octets) x up to 8 such rows and occupies 8 lanes of a strip item; lane i of
+    // the unit gathers the choices and demands of column i once and uses them for all rows.
+    struct UnitRef { int32_t item, group, row; };
+    std::vector<std::vector<UnitRef>> link_units(n_links);
+    t.strip_base.clear(); t.strip_pres.clear(); t.strip_mask.clear(); t.strip_slot.clear();
+    t.n_strip_rows = 0;
+    if (tiles_on && !t.tiles_dense_only) {
+        std::vector<uint32_t> row_um(n_links, 0u);        // the row's one mask value, 0: none
+        std::unordered_map<uint64_t, std::vector<int32_t>> by_hash;
+        for (int32_t e = 0; e < n_links; ++e) {
+            const size_t n = row_base[e].size();
+            if (n < static_cast<size_t>(kStripMinCols) || n > static_cast<size_t>(kStripMaxCols))
+                continue;
+            uint32_t m = 0u;
+            bool uniform = true;
+            for (uint32_t v : row_mask[e]) {
+                if (v == 0u) continue;
+                if (m == 0u) m = v;
+                else if (m != v) { uniform = false; break; }
+            }
+            if (!uniform || m == 0u) continue;
+            row_um[e] = m;
+            uint64_t h = 1469598103934665603ull;
+            for (uint32_t v : row_base[e]) h = (h ^ v) * 1099511628211ull;
+            by_hash[h ^ (static_cast<uint64_t>(n) << 48)].push_back(e);
+        }
+        std::vector<std::vector<int32_t>> clusters;
+        for (auto &kv : by_hash) {
+            std::vector<int32_t> &cand = kv.second;         // ascending link ids
+            std::vector<bool> used(cand.size(), false);
+            for (size_t i = 0; i < cand.size(); ++i) {
+                if (used[i]) continue;
+                std::vector<int32_t> cl(1, cand[i]);
+                for (size_t j = i + 1; j < cand.size(); ++j)
+                    if (!used[j] && row_base[cand[j]] == row_base[cand[i]]) {
+                        used[j] = true;
+                        cl.push_back(cand[j]);
+                    }
+                if (static_cast<int32_t>(cl.size()) >= kStripMinRows) clusters.push_back(cl);
+            }
+        }
+        std::sort(clusters.begin(), clusters.end());        // by first link: a fixed order
+        int32_t n_units = 0;
+        for (const std::vector<int32_t> &cl : clusters) {
+            const std::vector<uint32_t> &bases = row_base[cl[0]];
+            const int32_t n_cols = static_cast<int32_t>(bases.size());
+            for (size_t r0 = 0; r0 < cl.size(); r0 += 8) {
+                const int32_t n_rows = static_cast<int32_t>(std::min<size_t>(8, cl.size() - r0));
+                for (int32_t c0 = 0; c0 < n_cols; c0 += 8) {
+                    const int32_t item = n_units / 8, group = n_units % 8;
+                    if (group == 0) {
+                        t.strip_base.resize(t.strip_base.size() + 64, 0u);
+                        t.strip_pres.resize(t.strip_pres.size() + 64, 0ull);
+                        t.strip_mask.resize(t.strip_mask.size() + 64, 0u);
+                        t.strip_slot.resize(t.strip_slot.size() + 64, -1);
+                    }
+                    const size_t at = static_cast<size_t>(item) * 64 + static_cast<size_t>(group) * 8;
+                    for (int32_t i = 0; i < 8 && c0 + i < n_cols; ++i) {
+                        t.strip_base[at + i] = bases[c0 + i];
+                        uint64_t pres = 0;
+                        for (int32_t r = 0; r < n_rows; ++r) {
+                            const std::vector<uint32_t> &mk = row_mask[cl[r0 + r]];
+                            for (int32_t s8 = 0; s8 < 8; ++s8)
+                                if (mk[static_cast<size_t>(c0 + i) * 8 + s8] != 0u)
+                                    pres |= 1ull << (8 * r + s8);
+                        }
+                        t.strip_pres[at + i] = pres;
+                    }
+                    for (int32_t r = 0; r < n_rows; ++r) {
+                        t.strip_mask[at + r] = row_um[cl[r0 + r]];
+                        link_units[cl[r0 + r]].push_back({item, group, r});
+                    }
+                    n_units += 1;
+                }
+            }
+            for (int32_t e : cl) {
+                t.n_strip_rows += 1;
+                row_base[e].clear(); row_base[e].shrink_to_fit();
+                row_mask[e].clear(); row_mask[e].shrink_to_fit();
+            }
+        }
+    }
+    t.n_strip_items = static_cast<int32_t>(t.strip_base.size() / 64);
+    t.strip_base.resize(t.strip_base.size() + 64, 0u);          // one spare item keeps the
+    t.strip_pres.resize(t.strip_pres.size() + 64, 0ull);        // arrays loadable
+    t.strip_mask.resize(t.strip_mask.size() + 64, 0u);
+    t.strip_slot.resize(t.strip_slot.size() + 64, -1);
+    for (int32_t e = 0; e < n_links; ++e) t.n_octets += static_cast<int64_t>(row_base[e].size());
+
+    // the link's slots outside the octet range: one per piece, per strip unit it has a row in,
+    // and per single-pair chunk, link by link
+    for (int32_t e = 0; e < n_links; ++e) {
+        t.link_sslot_ptr[e] = extra_slots;
+        for (size_t q = 0; q < link_pieces[e].size(); ++q) piece_extra.push_back(extra_slots++);
+        for (const UnitRef &u : link_units[e])
+            t.strip_slot[static_cast<size_t>(u.item) * 64 + static_cast<size_t>(u.group) * 8 + u.row] =
+                extra_slots++;
+        for (int32_t c = link_chunk_first[e]; c < link_chunk_first[e + 1]; ++c)
+            t.schunk_slot.push_back(extra_slots++);
     }
     // A piece whose non-zero masks are all equal (the usual case when the candidates of a
     // fabric are enumerated by a product rule) is UNIFORM: it is stored as that one mask plus a
@@ -563,6 +665,8 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
     const int32_t extra_slot0 = t.n_oct_slots + pad_slots;
     t.link_sslot_ptr[n_links] = extra_slots;
     for (int32_t &v : t.schunk_slot) v += extra_slot0;
+    for (int32_t &v : t.strip_slot)
+        if (v >= 0) v += extra_slot0;
     for (int32_t e = 0; e <= n_links; ++e) t.link_sslot_ptr[e] += extra_slot0;
     t.n_slots = extra_slot0 + extra_slots;
     for (int32_t it = 0; it < t.n_tile_items; ++it) {
@@ -851,6 +955,8 @@ extern "C" nimble_status_t nimble_host_layout_stats(int32_t n_links, int32_t n_c
     out[10] = t.n_pieces;
     out[11] = t.n_tile_items;
     out[12] = t.n_pieces_uniform;
+    out[13] = t.n_strip_items;
+    out[14] = t.n_strip_rows;
     return NIMBLE_OK;
 }
 
@@ -963,6 +1069,30 @@ extern "C" nimble_status_t nimble_host_build_reverse_streaming(int32_t n_links, 
                 }
         }
     }
+    // strip items: lane = column of a unit, rows through the unit's slots
+    for (int32_t it = 0; it < t.n_strip_items; ++it)
+        for (int32_t lane = 0; lane < 64; ++lane) {
+            const size_t at = static_cast<size_t>(it) * 64 + lane;
+            const uint32_t w = t.strip_base[at];
+            const int32_t base = static_cast<int32_t>(w & ~3u);
+            for (int32_t r = 0; r < 8; ++r) {
+                const uint32_t pb = static_cast<uint32_t>(t.strip_pres[at] >> (8 * r)) & 0xFFu;
+                if (!pb) continue;
+                const size_t ur = static_cast<size_t>(it) * 64 + (lane & ~7) + r;
+                const int32_t sl = t.strip_slot[ur];
+                if (sl < 0 || sl >= t.n_slots || slot_link[sl] < 0) return NIMBLE_ERR_INVALID;
+                const int32_t e = slot_link[sl];
+                const uint32_t m = t.strip_mask[ur];
+                if (!m) return NIMBLE_ERR_INVALID;
+                for (int32_t s8 = 0; s8 < 8; ++s8) {
+                    if (!((pb >> s8) & 1u)) continue;
+                    const int32_t k = (w & nimble::kOctSigma) ? inv_sigma[base + s8] : base + s8;
+                    if (k < 0 || k >= n_comm) return NIMBLE_ERR_INVALID;
+                    for (int32_t j = 0; j < 32; ++j)
+                        if (m & (1u << j)) rows[e].push_back((static_cast<int64_t>(k) << 8) | j);
+                }
+            }
+        }
     for (size_t c = 0; c < t.schunk_begin.size(); ++c) {
         const int32_t e = slot_link[t.schunk_slot[c]];
         if (e < 0) return NIMBLE_ERR_INVALID;

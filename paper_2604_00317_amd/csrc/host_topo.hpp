@@ -73,6 +73,16 @@ constexpr int32_t kTileDescInts = 32;
 constexpr int32_t kTileMinItems = 128;        // fewest commodities of a window that make a piece
 constexpr int64_t kTileAutoPairs = 4000000;   // tiles are used by default from this many pairs on
 
+// Strips.  Short rows that several links share octet for octet (the same commodities, e.g. the
+// rail links between two nodes), each with one mask value, leave the octet stream too.  A unit
+// is 8 columns (octets) x up to 8 such rows; 8 units fill the 64 lanes of a strip item.  Per
+// lane: strip_base (the octet's base word: id | sigma flag), strip_pres (byte r = presence bits
+// of the column's 8 commodities in row r of the lane's unit); per unit and row (index
+// 8 * unit + row): strip_mask (the row's mask value) and strip_slot (-1: no such row).
+constexpr int32_t kStripMinCols = 2;
+constexpr int32_t kStripMaxCols = 64;
+constexpr int32_t kStripMinRows = 3;
+
 // Link blocks and the order of the rows.  The rows are dealt to blocks of equal weight
 // (largest row first, each to the lightest block so far); the flat octet array holds the rows
 // block after block, inside a block by ascending link id.  pos_link[i] is the link whose row
@@ -142,6 +152,11 @@ struct HostTopo {
     std::vector<int32_t> tile_desc;      // [kTileDescInts * n_tile_items]
     std::vector<uint32_t> tile_mask;     // [512 * (dense pieces + 1)]
     std::vector<uint64_t> tile_pres;     // [64 * (uniform items + 1)]
+    int32_t n_strip_items = 0, n_strip_rows = 0;
+    std::vector<uint32_t> strip_base;    // [64 * (n_strip_items + 1)]
+    std::vector<uint64_t> strip_pres;    // [64 * (n_strip_items + 1)]
+    std::vector<uint32_t> strip_mask;    // [64 * (n_strip_items + 1)]
+    std::vector<int32_t> strip_slot;     // [64 * (n_strip_items + 1)]
     int32_t blk_passes = 0;              // option: target passes per link block (0 = default)
     int32_t n_blocks = 0;                // 0: the topology does not fit link blocks
     std::vector<int32_t> pos_link;       // [E] link of every position of the flat order

@@ -50,6 +50,13 @@ struct DeviceTopo {
     const uint32_t *tile_mask;        // [512 * (dense pieces + 1)]
     const uint64_t *tile_pres;        // [64 * (uniform items + 1)] presence bytes
     int32_t tile_item_cost;           // weight of an item against an octet pass (wave split)
+    // strip items: 8 units of 8 octets shared by up to 8 links each
+    int32_t n_strip_items;
+    const uint32_t *strip_base;       // [64 * (items + 1)] per lane
+    const uint64_t *strip_pres;       // [64 * (items + 1)] per lane
+    const uint32_t *strip_mask;       // [64 * (items + 1)] per unit and row
+    const int32_t *strip_slot;        // [64 * (items + 1)] per unit and row
+    double *demand1n;                 // [K rounded up to whole windows] demands by id
     double *demand1t;                 // [K rounded up to whole windows] demands by id, and
     double *demand2t;                 // [sigma_size] by sigma number, both window-transposed
     // second numbering of the commodities for the sigma octets, with sigma-ordered copies of

@@ -74,7 +74,11 @@ struct PersistentArgs {
     const int32_t *tile_desc;
     const uint32_t *tile_mask;
     const uint64_t *tile_pres;
-    double *demand1t, *demand2t;
+    double *demand1n, *demand1t, *demand2t;
+    int n_strip_items;
+    const uint32_t *strip_base, *strip_mask;
+    const uint64_t *strip_pres;
+    const int32_t *strip_slot;
     const int32_t *cp, *lp, *pl;
     const int32_t *pass_first_slot;
     const uint32_t *oct_base, *oct_mask;
@@ -104,6 +108,9 @@ __device__ __forceinline__ void reduce_both(const PersistentArgs &a, int wave, i
     reduce_tile_phase<MODE>(a.n_tile_items, a.tile_desc, a.tile_mask, a.tile_pres, a.choice,
                                 a.demand1t,
                             a.choice2, a.demand2t, a.partial, wave, n_waves, lane);
+    reduce_strip_phase<MODE>(a.n_strip_items, a.strip_base, a.strip_pres, a.strip_mask,
+                             a.strip_slot, a.choice, a.demand1n, a.choice2, a.demand2, a.partial,
+                             wave, n_waves, lane);
     reduce_flat_phase<MODE>(0, a.n_passes, a.pass_first_slot, a.oct_base, a.oct_mask, a.choice,
                             a.demand, a.choice2, a.demand2, a.partial, 0, wave, n_waves, lane);
     reduce_phase<MODE, kSinglesPerLane>(a.n_schunks, a.schunk_begin, a.schunk_end, a.schunk_slot,
@@ -139,6 +146,7 @@ __global__ __launch_bounds__(kPBlock) void k_persistent(PersistentArgs a)
     for (int p = tid; p < a.P; p += n_threads) a.count[p] = 0u;
     for (int k = tid; k < a.K; k += n_threads) {
         const double dk = a.demand[k];
+        a.demand1n[k] = dk;
         a.demand1t[tile_demand_index(k)] = dk;
         const int sg = a.sigma[k];
         if (sg >= 0) {
@@ -250,8 +258,14 @@ hipError_t launch_persistent(const DeviceTopo &t, void *sync_words, int n_cu,
     a.tile_desc = t.tile_desc;
     a.tile_mask = t.tile_mask;
     a.tile_pres = t.tile_pres;
+    a.demand1n = t.demand1n;
     a.demand1t = t.demand1t;
     a.demand2t = t.demand2t;
+    a.n_strip_items = t.n_strip_items;
+    a.strip_base = t.strip_base;
+    a.strip_pres = t.strip_pres;
+    a.strip_mask = t.strip_mask;
+    a.strip_slot = t.strip_slot;
     a.pad_comm = static_cast<uint32_t>(t.K);
     a.cp = t.comm_ptr;
     a.lp = t.path_ptr;

@@ -20,16 +20,19 @@ __global__ __launch_bounds__(kBlock) void k_init(int E, int K, int P, bool cost_
                                                  uint32_t *__restrict__ count,
                                                  const int32_t *__restrict__ sigma,
                                                  const double *__restrict__ demand,
+                                                 double *__restrict__ demand1n,
                                                  double *__restrict__ demand1t,
                                                  double *__restrict__ demand2,
                                                  double *__restrict__ demand2t)
 {
     const int stride = gridDim.x * blockDim.x;
     const int tid = blockIdx.x * blockDim.x + threadIdx.x;
-    // the library's own copies of the demands: in sigma order for the sigma octets, and by id
-    // and by sigma number in the window-transposed order the tile phase reads
+    // the library's own copies of the demands: by id (aligned, padded) and in sigma order for
+    // the octets and strips, and by id and by sigma number in the window-transposed order the
+    // tile phase reads
     for (int k = tid; k < K; k += stride) {
         const double dk = demand[k];
+        demand1n[k] = dk;
         demand1t[tile_demand_index(k)] = dk;
         const int sg = sigma[k];
         if (sg >= 0) {
@@ -235,7 +238,11 @@ __global__ __launch_bounds__(kWave) void k_histogram(int K, int iters, int pmax,
 }
 
 struct ReduceArgs {
-    int n_passes, n_schunks, n_tile_items, n_tile_waves;
+    int n_passes, n_schunks, n_tile_items, n_tile_waves, n_strip_items, n_strip_waves;
+    const uint32_t *strip_base, *strip_mask;
+    const uint64_t *strip_pres;
+    const int32_t *strip_slot;
+    const double *demand1n;
     const int32_t *tile_desc;
     const uint32_t *tile_mask;
     const uint64_t *tile_pres;
@@ -256,16 +263,21 @@ __global__ __launch_bounds__(kBlock) void k_load_reduce(ReduceArgs a)
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
-    // the wave pool is split between the tile items and the octet passes in proportion to
-    // their estimated cost
+    // the wave pool is split between the tile items, the strip items and the octet passes in
+    // proportion to their numbers
     if (wave < a.n_tile_waves)
         reduce_tile_phase<MODE>(a.n_tile_items, a.tile_desc, a.tile_mask, a.tile_pres, a.choice,
-                                a.demand1t,
-                                a.choice2, a.demand2t, a.partial, wave, a.n_tile_waves, lane);
+                                a.demand1t, a.choice2, a.demand2t, a.partial, wave, a.n_tile_waves,
+                                lane);
+    else if (wave < a.n_tile_waves + a.n_strip_waves)
+        reduce_strip_phase<MODE>(a.n_strip_items, a.strip_base, a.strip_pres, a.strip_mask,
+                                 a.strip_slot, a.choice, a.demand1n, a.choice2, a.demand2,
+                                 a.partial, wave - a.n_tile_waves, a.n_strip_waves, lane);
     else
         reduce_flat_phase<MODE>(0, a.n_passes, a.pass_first_slot, a.oct_base, a.oct_mask,
                                 a.choice, a.demand, a.choice2, a.demand2, a.partial, 0,
-                                wave - a.n_tile_waves, n_waves - a.n_tile_waves, lane);
+                                wave - a.n_tile_waves - a.n_strip_waves,
+                                n_waves - a.n_tile_waves - a.n_strip_waves, lane);
     // single pairs (commodities with more than 32 candidates) are walked from the other end of
     // the wave pool
     reduce_phase<MODE, kSinglesPerLane>(a.n_schunks, a.schunk_begin, a.schunk_end, a.schunk_slot,
@@ -504,24 +516,40 @@ void launch_reduce_mode(const DeviceTopo &t, const uint8_t *choice, const double
                         hipStream_t s)
 {
     // a fixed pool of waves, each walking its passes with the loads pipelined
-    int64_t waves = static_cast<int64_t>(t.n_passes) + t.n_tile_items;
+    int64_t waves = static_cast<int64_t>(t.n_passes) + t.n_tile_items + t.n_strip_items;
     if (waves < (t.n_schunks + 3) / 4) waves = (t.n_schunks + 3) / 4;
     const int grid = blocks_for(waves * kWave, kBlock, t.reduce_blocks);
-    // waves of the tile items: their share of the estimated work (an item of 8 pieces weighs
-    // kTileItemCost passes), at least one wave for each kind of work that exists
+    // every kind of work that exists gets at least one wave and at most one wave per item; an
+    // item weighs tile_item_cost octet passes
     const int64_t n_waves = static_cast<int64_t>(grid) * (kBlock / kWave);
-    const int64_t w_items = static_cast<int64_t>(t.n_tile_items) * t.tile_item_cost;
-    int64_t tile_waves = t.n_tile_items > 0 ? (n_waves * w_items + (w_items + t.n_passes) / 2) /
-                                                  (w_items + t.n_passes)
-                                            : 0;
-    if (t.n_tile_items > 0 && tile_waves < 1) tile_waves = 1;
-    if (tile_waves > t.n_tile_items) tile_waves = t.n_tile_items;
-    if (tile_waves > n_waves - 1) tile_waves = n_waves - 1;
+    const int64_t w_tile = static_cast<int64_t>(t.n_tile_items) * t.tile_item_cost;
+    const int64_t w_strip = static_cast<int64_t>(t.n_strip_items) * t.tile_item_cost;
+    const int64_t w_all = w_tile + w_strip + t.n_passes;
+    auto share = [&](int64_t w, int64_t items) -> int64_t {
+        if (items == 0) return 0;
+        int64_t v = (n_waves * w + w_all / 2) / w_all;
+        if (v < 1) v = 1;
+        return v > items ? items : v;
+    };
+    int64_t tile_waves = share(w_tile, t.n_tile_items);
+    int64_t strip_waves = share(w_strip, t.n_strip_items);
+    while (tile_waves + strip_waves > n_waves - 1) {     // the octet passes keep one wave
+        if (tile_waves >= strip_waves && tile_waves > 1) tile_waves -= 1;
+        else if (strip_waves > 1) strip_waves -= 1;
+        else break;
+    }
     ReduceArgs a;
     a.n_passes = t.n_passes;
     a.n_schunks = t.n_schunks;
     a.n_tile_items = t.n_tile_items;
     a.n_tile_waves = static_cast<int>(tile_waves);
+    a.n_strip_items = t.n_strip_items;
+    a.n_strip_waves = static_cast<int>(strip_waves);
+    a.strip_base = t.strip_base;
+    a.strip_pres = t.strip_pres;
+    a.strip_mask = t.strip_mask;
+    a.strip_slot = t.strip_slot;
+    a.demand1n = t.demand1n;
     a.tile_desc = t.tile_desc;
     a.tile_mask = t.tile_mask;
     a.tile_pres = t.tile_pres;
@@ -557,7 +585,7 @@ void launch_init(const DeviceTopo &t, const double *demand, hipStream_t s)
     const int n = t.E > t.P ? t.E : t.P;
     hipLaunchKernelGGL(k_init, dim3(blocks_for(n, kBlock, 4096)), dim3(kBlock), 0, s, t.E, t.K,
                        t.P, t.cost_max, t.invcap, t.len, t.price, t.S, t.choice, t.count, t.sigma,
-                       demand, t.demand1t, t.demand2, t.demand2t);
+                       demand, t.demand1n, t.demand1t, t.demand2, t.demand2t);
 }
 
 void launch_width(const DeviceTopo &t, const double *demand, hipStream_t s)

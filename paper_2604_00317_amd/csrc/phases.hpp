@@ -449,6 +449,64 @@ __device__ __forceinline__ void reduce_tile_phase(
     }
 }
 
+// ---- phase B, strip part --------------------------------------------------------------------
+// A strip item is 8 units of 8 lanes; a unit is 8 columns (octets) shared by up to 8 links
+// whose rows consist of exactly these octets, each row with one mask value.  Lane i of a unit
+// gathers the 8 choices and 8 demands of its column once (the demands with four 16-byte loads
+// from the library's own aligned copies) and uses them for every row; the row sums are added
+// inside the unit's 8 lanes and every lane stores the partial of one row.
+// MODE 1 (width rho): every present commodity counts once.
+template <int MODE>
+__device__ __forceinline__ void reduce_strip_phase(
+    int n_items, const uint32_t *__restrict__ strip_base, const uint64_t *__restrict__ strip_pres,
+    const uint32_t *__restrict__ strip_mask, const int32_t *__restrict__ strip_slot,
+    const uint8_t *__restrict__ choice, const double *__restrict__ demand1n,
+    const uint8_t *__restrict__ choice2, const double *__restrict__ demand2,
+    double *__restrict__ partial, int wave, int n_waves, int lane)
+{
+    const int my_row = tile_row_of_lane(lane);
+    const int unit0 = lane & ~7;
+    for (int it = wave; it < n_items; it += n_waves) {               // wave-uniform
+        const size_t at = size_t(it) * kWave;
+        const uint32_t bw = stream_load(strip_base + at + lane);
+        const uint64_t pres = strip_pres[at + lane];
+        const int my_slot = strip_slot[at + unit0 + my_row];
+        uint32_t mr[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) mr[r] = strip_mask[at + unit0 + r];
+        const bool sig = (bw & kOctSigma) != 0u;
+        const int base = static_cast<int>(bw & ~3u);
+        uint2 ch = make_uint2(0u, 0u);
+        if constexpr (MODE == 0)
+            ch = *reinterpret_cast<const uint2 *>((sig ? choice2 : choice) + base);
+        const u32x4 *dq = reinterpret_cast<const u32x4 *>((sig ? demand2 : demand1n) + base);
+        const u32x4 q0 = dq[0], q1 = dq[1], q2 = dq[2], q3 = dq[3];
+        const int dlo[8] = {int(q0.x), int(q0.z), int(q1.x), int(q1.z),
+                            int(q2.x), int(q2.z), int(q3.x), int(q3.z)};
+        const int dhi[8] = {int(q0.y), int(q0.w), int(q1.y), int(q1.w),
+                            int(q2.y), int(q2.w), int(q3.y), int(q3.w)};
+        uint32_t c8[8];
+#pragma unroll
+        for (int sl = 0; sl < 8; ++sl) c8[sl] = ((sl < 4 ? ch.x : ch.y) >> (8 * (sl & 3))) & 31u;
+        double acc[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            const uint32_t pb = static_cast<uint32_t>(pres >> (8 * r)) & 0xFFu;
+            double a = 0.0;
+#pragma unroll
+            for (int sl = 0; sl < 8; ++sl) {
+                uint32_t h = pb >> sl;
+                if constexpr (MODE == 0) h &= mr[r] >> c8[sl];
+                const int hit = __builtin_amdgcn_sbfe(static_cast<int>(h), 0u, 1u);
+                a = a + __hiloint2double(dhi[sl] & hit, dlo[sl] & hit);
+            }
+            acc[r] = a;
+        }
+        const double total = group8_sum8(acc, lane);
+        if (my_slot >= 0) partial[my_slot] = total;
+    }
+}
+
 // ---- phase C: slot partials -> load, congestion sum, multiplicative length update ----------
 // One 16-lane DPP row per link: the lanes fetch the link's slot partials side by side (16 per
 // step), add their own in ascending slot order, and a fixed butterfly combines the 16 lane

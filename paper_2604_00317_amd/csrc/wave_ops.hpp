@@ -179,6 +179,32 @@ __device__ __forceinline__ double wave_sum8(const double (&a)[8], int lane)
     return v;
 }
 
+// The first three steps of wave_sum8 alone: sums inside every aligned group of 8 lanes.  Lane l
+// ends with the total, over its group, of value number tile_row_of_lane(l).
+__device__ __forceinline__ double group8_sum8(const double (&a)[8], int lane)
+{
+    const bool s2 = (lane & 4) != 0;
+    double v4[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const double keep = s2 ? a[4 + j] : a[j];
+        const double give = s2 ? a[j] : a[4 + j];
+        v4[j] = keep + dpp_f64<kDppHalfMirror>(give);
+    }
+    const bool s0 = (lane & 1) != 0;
+    double v2[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+        const double keep = s0 ? v4[2 + j] : v4[j];
+        const double give = s0 ? v4[j] : v4[2 + j];
+        v2[j] = keep + dpp_f64<kDppXor1>(give);
+    }
+    const bool s1 = (lane & 2) != 0;
+    const double keep = s1 ? v2[1] : v2[0];
+    const double give = s1 ? v2[0] : v2[1];
+    return keep + dpp_f64<kDppXor2>(give);
+}
+
 __device__ __forceinline__ int tile_row_of_lane(int lane)
 {
     return ((lane >> 2) & 1) * 4 + (lane & 1) * 2 + ((lane >> 1) & 1);
