@@ -278,8 +278,13 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
                "single_pair");
     NIMBLE_TRY(upload(t, h.pass_first_slot.data(), h.pass_first_slot.size(), &d.pass_first_slot),
                "pass_first_slot");
-    NIMBLE_TRY(upload(t, h.link_sslot_ptr.data(), h.link_sslot_ptr.size(), &d.link_sslot_ptr),
-               "link_sslot_ptr");
+    {
+        const int2 *px = nullptr;
+        NIMBLE_TRY(upload(t, reinterpret_cast<const int2 *>(h.pos_xslot.data()),
+                          h.pos_xslot.size() / 2, &px),
+                   "pos_xslot");
+        d.pos_xslot = px;
+    }
     NIMBLE_TRY(upload(t, h.schunk_begin.data(), h.schunk_begin.size(), &d.schunk_begin), "schunk");
     NIMBLE_TRY(upload(t, h.schunk_end.data(), h.schunk_end.size(), &d.schunk_end), "schunk");
     NIMBLE_TRY(upload(t, h.schunk_slot.data(), h.schunk_slot.size(), &d.schunk_slot), "schunk");

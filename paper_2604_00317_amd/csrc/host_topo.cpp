@@ -669,6 +669,11 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
         if (v >= 0) v += extra_slot0;
     for (int32_t e = 0; e <= n_links; ++e) t.link_sslot_ptr[e] += extra_slot0;
     t.n_slots = extra_slot0 + extra_slots;
+    t.pos_xslot.resize(2 * static_cast<size_t>(n_links));
+    for (int32_t i = 0; i < n_links; ++i) {
+        t.pos_xslot[2 * static_cast<size_t>(i)] = t.link_sslot_ptr[t.pos_link[i]];
+        t.pos_xslot[2 * static_cast<size_t>(i) + 1] = t.link_sslot_ptr[t.pos_link[i] + 1];
+    }
     for (int32_t it = 0; it < t.n_tile_items; ++it) {
         int32_t *d = &t.tile_desc[static_cast<size_t>(it) * kTileDescInts];
         for (int32_t r = 0; r < kTileRows; ++r) {

@@ -161,6 +161,8 @@ struct HostTopo {
     int32_t n_blocks = 0;                // 0: the topology does not fit link blocks
     std::vector<int32_t> pos_link;       // [E] link of every position of the flat order
     std::vector<int32_t> pos_slot_ptr;   // [E+1] octet slots of a position
+    std::vector<int32_t> pos_xslot;      // [2 * E] first and end of the link's other slots
+                                         // (link_sslot_ptr), by position
     std::vector<int32_t> blk_pos_ptr;    // [n_blocks+1] first position of a block
     std::vector<int32_t> blk_pass_ptr;   // [n_blocks+1] first pass of a block
     std::vector<int32_t> blk_desc;       // [8 * n_blocks] what one workgroup of the fused kernel

@@ -43,7 +43,8 @@ struct DeviceTopo {
                                       // pass, end pass, first slot, 0, 0, 0
     const uint32_t *single_pair;      // [2 * padded singles]
     const int32_t *schunk_begin, *schunk_end, *schunk_slot;   // [n_schunks], pair units
-    const int32_t *link_sslot_ptr;    // [E+1] piece and single-chunk slots of a link
+    const int2 *pos_xslot;            // [E] first and end of the piece, strip and single-chunk
+                                      // slots of the link at position i
     // tile work items: up to 8 dense (link, window of 512 commodities) pieces of one window
     int32_t n_tile_items;
     const int32_t *tile_desc;         // [32 * n_tile_items]

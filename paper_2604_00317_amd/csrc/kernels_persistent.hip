@@ -84,7 +84,8 @@ struct PersistentArgs {
     const uint32_t *oct_base, *oct_mask;
     const int32_t *schunk_begin, *schunk_end, *schunk_slot;
     const uint32_t *single_pair;
-    const int32_t *pos_link, *pos_slot_ptr, *link_sslot_ptr;
+    const int32_t *pos_link, *pos_slot_ptr;
+    const int2 *pos_xslot;
     const int32_t *sigma;
     uint8_t *choice2;
     double *demand2;
@@ -158,7 +159,7 @@ __global__ __launch_bounds__(kPBlock) void k_persistent(PersistentArgs a)
     reduce_both<1>(a, wave, n_waves, lane);
     if (!grid_barrier(a.sync, nb, a.spin_limit, &s_flag)) goto abandoned;
     {
-        double m = width_phase(a.E, a.pos_link, a.pos_slot_ptr, a.link_sslot_ptr, a.partial, a.invcap_pos, wave,
+        double m = width_phase(a.E, a.pos_slot_ptr, a.pos_xslot, a.partial, a.invcap_pos, wave,
                                n_waves, lane);
         m = block_max(m, red);
         if (threadIdx.x == 0) atomic_max_bits(&a.sync->rho_bits, m);
@@ -175,7 +176,7 @@ __global__ __launch_bounds__(kPBlock) void k_persistent(PersistentArgs a)
             if (!grid_barrier(a.sync, nb, a.spin_limit, &s_flag)) goto abandoned;
             reduce_both<0>(a, wave, n_waves, lane);
             if (!grid_barrier(a.sync, nb, a.spin_limit, &s_flag)) goto abandoned;
-            update_phase<MAXC>(a.E, a.eps, invrho, a.pos_link, a.pos_slot_ptr, a.link_sslot_ptr, a.partial,
+            update_phase<MAXC>(a.E, a.eps, invrho, a.pos_link, a.pos_slot_ptr, a.pos_xslot, a.partial,
                                a.invcap_pos, a.len, a.price, a.S, wave, n_waves, lane);
             if (!grid_barrier(a.sync, nb, a.spin_limit, &s_flag)) goto abandoned;
         }
@@ -279,7 +280,7 @@ hipError_t launch_persistent(const DeviceTopo &t, void *sync_words, int n_cu,
     a.single_pair = t.single_pair;
     a.pos_link = t.pos_link;
     a.pos_slot_ptr = t.pos_slot_ptr;
-    a.link_sslot_ptr = t.link_sslot_ptr;
+    a.pos_xslot = t.pos_xslot;
     a.sigma = t.sigma;
     a.choice2 = t.choice2;
     a.demand2 = t.demand2;

@@ -369,9 +369,9 @@ __global__ __launch_bounds__(kBlock) void k_reduce_update(FusedArgs a)
 // rho = max_e (demand that can reach e) / cap_e, in two steps: every block leaves the maximum
 // over its links in scalars[1 + block], then one block folds those into scalars[0] = 1/rho
 // (0 when rho = 0).  A maximum does not depend on the order it is taken in.
-__global__ __launch_bounds__(kBlock) void k_width(int E, const int32_t *__restrict__ pos_link,
+__global__ __launch_bounds__(kBlock) void k_width(int E,
                                                   const int32_t *__restrict__ pos_slot_ptr,
-                                                  const int32_t *__restrict__ link_sslot_ptr,
+                                                  const int2 *__restrict__ pos_xslot,
                                                   const double *__restrict__ partial,
                                                   const double *__restrict__ invcap,
                                                   double *__restrict__ scalars)
@@ -379,7 +379,7 @@ __global__ __launch_bounds__(kBlock) void k_width(int E, const int32_t *__restri
     __shared__ double red[16];
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
-    double m = width_phase(E, pos_link, pos_slot_ptr, link_sslot_ptr, partial, invcap, wave, n_waves,
+    double m = width_phase(E, pos_slot_ptr, pos_xslot, partial, invcap, wave, n_waves,
                            threadIdx.x & (kWave - 1));
     m = block_max(m, red);
     if (threadIdx.x == 0) scalars[1 + blockIdx.x] = m;
@@ -399,7 +399,7 @@ template <bool MAXC>
 __global__ __launch_bounds__(kBlock) void k_update(int E, double eps,
                                                    const int32_t *__restrict__ pos_link,
                                                    const int32_t *__restrict__ pos_slot_ptr,
-                                                   const int32_t *__restrict__ link_sslot_ptr,
+                                                   const int2 *__restrict__ pos_xslot,
                                                    const double *__restrict__ partial,
                                                    const double *__restrict__ invcap,
                                                    double *__restrict__ len,
@@ -411,7 +411,7 @@ __global__ __launch_bounds__(kBlock) void k_update(int E, double eps,
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
-    const double s_new = update_phase<MAXC>(E, eps, scalars[0], pos_link, pos_slot_ptr, link_sslot_ptr,
+    const double s_new = update_phase<MAXC>(E, eps, scalars[0], pos_link, pos_slot_ptr, pos_xslot,
                                             partial, invcap, len, price, S, wave, n_waves, lane);
     const double m = block_max(s_new, red);
     if (threadIdx.x == 0) scalars[1 + blockIdx.x] = m;
@@ -592,7 +592,7 @@ void launch_width(const DeviceTopo &t, const double *demand, hipStream_t s)
 {
     launch_reduce_mode<1>(t, t.choice, demand, s);
     hipLaunchKernelGGL(k_width, dim3(t.n_update_blocks), dim3(kBlock), 0, s, t.E,
-                       t.pos_link, t.pos_slot_ptr, t.link_sslot_ptr, t.partial, t.invcap_pos, t.scalars);
+                       t.pos_slot_ptr, t.pos_xslot, t.partial, t.invcap_pos, t.scalars);
     hipLaunchKernelGGL(k_width_fold, dim3(1), dim3(kBlock), 0, s, t.n_update_blocks, t.scalars);
 }
 
@@ -620,11 +620,11 @@ void launch_update(const DeviceTopo &t, double eps, hipStream_t s)
 {
     if (t.cost_max)
         hipLaunchKernelGGL(k_update<true>, dim3(t.n_update_blocks), dim3(kBlock), 0, s, t.E, eps,
-                           t.pos_link, t.pos_slot_ptr, t.link_sslot_ptr, t.partial, t.invcap_pos, t.len, t.price,
+                           t.pos_link, t.pos_slot_ptr, t.pos_xslot, t.partial, t.invcap_pos, t.len, t.price,
                            t.S, t.scalars);
     else
         hipLaunchKernelGGL(k_update<false>, dim3(t.n_update_blocks), dim3(kBlock), 0, s, t.E, eps,
-                           t.pos_link, t.pos_slot_ptr, t.link_sslot_ptr, t.partial, t.invcap_pos, t.len, t.price,
+                           t.pos_link, t.pos_slot_ptr, t.pos_xslot, t.partial, t.invcap_pos, t.len, t.price,
                            t.S, t.scalars);
 }
 

@@ -528,7 +528,7 @@ template <bool MAXC>
 __device__ __forceinline__ double update_phase(int E, double eps, double invrho,
                                                const int32_t *__restrict__ pos_link,
                                                const int32_t *__restrict__ pos_slot_ptr,
-                                               const int32_t *__restrict__ link_sslot_ptr,
+                                               const int2 *__restrict__ pos_xslot,
                                                const double *__restrict__ partial,
                                                const double *__restrict__ invcap_pos,
                                                double *__restrict__ len,
@@ -547,8 +547,9 @@ __device__ __forceinline__ double update_phase(int E, double eps, double invrho,
             e = pos_link[i];
             c0 = pos_slot_ptr[i];
             c1 = pos_slot_ptr[i + 1];
-            s0 = link_sslot_ptr[e];
-            s1 = link_sslot_ptr[e + 1];
+            const int2 xs = pos_xslot[i];       // the link's piece, strip and single-chunk slots
+            s0 = xs.x;
+            s1 = xs.y;
         }
         // the link's own state is requested before the partial sums are waited for
         double ic = 0.0, s_old = 0.0, l_old = 0.0;
@@ -576,9 +577,9 @@ __device__ __forceinline__ double update_phase(int E, double eps, double invrho,
 }
 
 // max over this wave's links of (demand that can reach the link) / capacity: terms of rho
-__device__ __forceinline__ double width_phase(int E, const int32_t *__restrict__ pos_link,
+__device__ __forceinline__ double width_phase(int E,
                                               const int32_t *__restrict__ pos_slot_ptr,
-                                              const int32_t *__restrict__ link_sslot_ptr,
+                                              const int2 *__restrict__ pos_xslot,
                                               const double *__restrict__ partial,
                                               const double *__restrict__ invcap_pos, int wave,
                                               int n_waves, int lane)
@@ -588,13 +589,13 @@ __device__ __forceinline__ double width_phase(int E, const int32_t *__restrict__
     double m = 0.0;
     for (int ibase = wave * kRowsPerWave; ibase < E; ibase += n_waves * kRowsPerWave) {
         const int i = ibase + row;
-        int e = 0, c0 = 0, c1 = 0, s0 = 0, s1 = 0;
+        int c0 = 0, c1 = 0, s0 = 0, s1 = 0;
         if (i < E) {
-            e = pos_link[i];
             c0 = pos_slot_ptr[i];
             c1 = pos_slot_ptr[i + 1];
-            s0 = link_sslot_ptr[e];
-            s1 = link_sslot_ptr[e + 1];
+            const int2 xs = pos_xslot[i];       // the link's piece, strip and single-chunk slots
+            s0 = xs.x;
+            s1 = xs.y;
         }
         const double reach = row_partial_sum(c0, c1, l, partial) + row_partial_sum(s0, s1, l, partial);
         if (i < E) m = fmax(m, reach * invcap_pos[i]);
