@@ -235,7 +235,7 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     d.n_records = h.n_records;
     d.rec_stride = h.rec_stride;
     d.rec_max_links = h.rec_max_links;
-    d.rec_lanes = 0;
+    d.rec_lanes = h.rec_lanes;
     d.rec_per_wave = 0;
     if (const char *env = std::getenv("NIMBLE_TUNE_RECORDS_PER_WAVE"))
         if (std::atoi(env) >= 1 && std::atoi(env) <= 64) d.rec_per_wave = std::atoi(env);

@@ -716,6 +716,17 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
         auto bytes_needed = [&](int32_t nl, int32_t nk, int32_t npad) {
             return kRecHeader + 4 * nl + 4 * nk + 2 * align4(2 * (nk + 1)) + npad * S;
         };
+        // lanes per commodity in the record kernel: a lane scans two quads of the largest
+        // commodity; a record holds as many commodities as one round of the wave covers
+        // (64 / lanes), unless the caller set the capacity
+        {
+            const int32_t quads = (t.pmax + 3) / 4;
+            int32_t lanes = 1;
+            while (2 * lanes < quads && lanes < 64) lanes <<= 1;
+            t.rec_lanes = lanes;
+            if (t.rec_comm_cap <= 0) t.rec_comm_cap = 64 / lanes;
+            if (t.rec_comm_cap > kRecMaxComm) t.rec_comm_cap = kRecMaxComm;
+        }
         bool ok = true;
         int32_t k = 0;
         while (k < n_comm && ok) {

@@ -179,7 +179,9 @@ struct HostTopo {
     int32_t n_slots = 0;                 // octet slots + single-chunk slots
     // forward records (n_records = 0 when the topology does not fit them: a path longer than
     // kRecMaxStride links, padding above 1.5x, or a commodity that alone overflows a record)
-    int32_t rec_comm_cap = kRecMaxComm;  // most commodities put into one record
+    int32_t rec_comm_cap = 0;            // option: most commodities per record (0: one round of
+                                         // the record kernel, 64 / rec_lanes)
+    int32_t rec_lanes = 0;               // lanes per commodity the record kernel should use
     int32_t rec_stride = 0;              // indices per candidate = lmax
     int32_t n_records = 0;
     int32_t rec_max_links = 0;           // largest link table of any record
@@ -196,7 +198,7 @@ nimble_status_t validate_csr(int32_t n_links, const double *cap, int32_t n_comm,
 // capacity, link block size, tiles on/off, piece threshold); unset variables leave defaults.
 void read_layout_options(HostTopo &out);
 
-// Builds everything in HostTopo from validated input.  out.rec_comm_cap (default kRecMaxComm)
+// Builds everything in HostTopo from validated input.  out.rec_comm_cap,
 // out.blk_passes, out.tiles and out.tile_min_items are read as options.
 void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                      const int32_t *comm_path_ptr, int32_t n_paths,

@@ -73,7 +73,6 @@ __global__ __launch_bounds__(kBlock) void k_argmin(int K, const int32_t *__restr
 // +0.0 -- and reduce (cost, index) across the group.  The sums are the same IEEE operations in
 // the same order as in the untiled kernel.
 constexpr int kRecWaves = 4;     // independent waves per workgroup
-constexpr int kRecPerWave = 1;   // records a wave walks (the next one prefetched into registers)
 
 // Orders the LDS accesses of one wave: a wave's LDS operations execute in issue order, so the
 // lanes of a wave can exchange data through LDS once the compiler keeps the accesses in order.
@@ -452,7 +451,11 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, uint8_t *choice, uint32_t
 {
     if (t.n_records > 0) {
         const int rec_lds = (kRecBytes + 8 * (t.rec_max_links + 2) + 15) & ~15;
-        const int rpw = t.rec_per_wave > 0 ? t.rec_per_wave : kRecPerWave;
+        // records per wave: up to four (the next one is prefetched while one is scanned) once
+        // there are more records than wave slots
+        int rpw = (t.n_records + 4095) / 4096;
+        if (rpw > 4) rpw = 4;
+        if (t.rec_per_wave > 0) rpw = t.rec_per_wave;
         const int rec_grid = (t.n_records + kRecWaves * rpw - 1) / (kRecWaves * rpw);
 #define NIMBLE_REC_LAUNCH(SS)                                                                  \
     case SS:                                                                                   \
@@ -490,13 +493,11 @@ void launch_argmin_l(const DeviceTopo &t, uint8_t *choice, uint32_t *count, hipS
     // as a record typically holds, each lane scanning several candidates
     int L = lanes_per_commodity(t.pmax);
     if (t.n_records > 0) {
-        // record kernel: a lane scans quads of four candidates; one lane per quad of the
-        // largest commodity unless that leaves too few commodities side by side
+        // record kernel: a lane scans quads of four candidates; the layout builder chose the
+        // lanes per commodity together with the record capacity
         const int quads = (t.pmax + 3) / 4;
         L = 1;
-        while (L < quads && L < kWave) L <<= 1;
-        const int per_rec = (t.K + t.n_records - 1) / t.n_records;     // average, rounded up
-        while (L > 1 && (kWave / L) * 2 <= per_rec && (kWave / L) < 8) L >>= 1;
+        while (2 * L < quads && L < kWave) L <<= 1;
         if (t.rec_lanes > 0) L = t.rec_lanes;
     }
     const int grid = blocks_for(static_cast<int64_t>(t.K) * L, kBlock, 1 << 20);
