@@ -67,6 +67,20 @@ void nimble_oracle_set_threads(int n)
  * sumload_out[n_links] = sum over iterations of u_e; lb_out[iters] = weak-duality lower
  * bound on the LP optimum after each iteration's routing step (sum cost only).
  */
+/*
+ * len_io (may be NULL): link lengths to start from and, on return, the lengths after the last
+ * iteration.  NULL starts from len = 1, the plain method.  Starting a solve from the lengths a
+ * previous solve ended with continues that solve's price trajectory: the "hysteresis" policy of
+ * Sec. I (path selection must not oscillate between consecutive plans) read as a warm start.
+ */
+int nimble_oracle_solve_warm(int32_t n_links, const double *cap,
+                             int32_t n_comm, const int32_t *comm_path_ptr,
+                             int32_t n_paths, const int32_t *path_link_ptr,
+                             const int32_t *path_links,
+                             const double *demand, double eps, int32_t iters, uint32_t flags,
+                             double *len_io, double *splits, double *lambda,
+                             uint32_t *count_out, double *sumload_out, double *lb_out);
+
 int nimble_oracle_solve(int32_t n_links, const double *cap,
                         int32_t n_comm, const int32_t *comm_path_ptr,
                         int32_t n_paths, const int32_t *path_link_ptr,
@@ -74,6 +88,19 @@ int nimble_oracle_solve(int32_t n_links, const double *cap,
                         const double *demand, double eps, int32_t iters, uint32_t flags,
                         double *splits, double *lambda,
                         uint32_t *count_out, double *sumload_out, double *lb_out)
+{
+    return nimble_oracle_solve_warm(n_links, cap, n_comm, comm_path_ptr, n_paths, path_link_ptr,
+                                    path_links, demand, eps, iters, flags, NULL, splits, lambda,
+                                    count_out, sumload_out, lb_out);
+}
+
+int nimble_oracle_solve_warm(int32_t n_links, const double *cap,
+                             int32_t n_comm, const int32_t *comm_path_ptr,
+                             int32_t n_paths, const int32_t *path_link_ptr,
+                             const int32_t *path_links,
+                             const double *demand, double eps, int32_t iters, uint32_t flags,
+                             double *len_io, double *splits, double *lambda,
+                             uint32_t *count_out, double *sumload_out, double *lb_out)
 {
     if (n_links < 1 || n_comm < 1 || n_paths < 1 || iters < 1 || !(eps > 0.0) || !cap ||
         !comm_path_ptr || !path_link_ptr || !path_links || !demand || !splits || !lambda)
@@ -121,8 +148,8 @@ int nimble_oracle_solve(int32_t n_links, const double *cap,
     const double invrho = (rho > 0.0) ? 1.0 / rho : 0.0;
 
     for (int e = 0; e < E; ++e) {
-        len[e] = 1.0;
-        price[e] = use_max ? len[e] : invcap[e];
+        len[e] = len_io ? len_io[e] : 1.0;
+        price[e] = use_max ? len[e] : len[e] * invcap[e];
         S[e] = 0.0;
     }
 
@@ -192,6 +219,7 @@ int nimble_oracle_solve(int32_t n_links, const double *cap,
         if (S[e] > smax) smax = S[e];
     *lambda = smax / T;
 
+    if (len_io) memcpy(len_io, len, sizeof(double) * E);
     if (count_out) memcpy(count_out, count, sizeof(uint32_t) * P);
     if (sumload_out) memcpy(sumload_out, S, sizeof(double) * E);
 

@@ -39,6 +39,12 @@ def _load():
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_double, ctypes.c_int32,
             ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_void_p]
+        lib.nimble_oracle_solve_warm.restype = ctypes.c_int
+        lib.nimble_oracle_solve_warm.argtypes = [
+            ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_double, ctypes.c_int32,
+            ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_void_p]
         lib.nimble_oracle_alg1.restype = ctypes.c_int
         lib.nimble_oracle_alg1.argtypes = [
             ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32,
@@ -63,8 +69,10 @@ def _p(a: Optional[np.ndarray]):
 
 
 def solve(n_links, cap, n_comm, comm_path_ptr, n_paths, path_link_ptr, path_links, demand,
-          eps, iters, flags=0, want_lb=False):
-    """Run the oracle.  Returns dict(splits, lam, count, sumload[, lb])."""
+          eps, iters, flags=0, want_lb=False, len0=None):
+    """Run the oracle.  Returns dict(splits, lam, count, sumload[, lb][, len]).  len0: link
+    lengths to start from (warm start); the lengths after the last iteration come back as
+    "len"."""
     cap = np.ascontiguousarray(cap, dtype=np.float64)
     cp = np.ascontiguousarray(comm_path_ptr, dtype=np.int32)
     lp = np.ascontiguousarray(path_link_ptr, dtype=np.int32)
@@ -77,12 +85,19 @@ def solve(n_links, cap, n_comm, comm_path_ptr, n_paths, path_link_ptr, path_link
     count = np.empty(n_paths, dtype=np.uint32)
     sumload = np.empty(n_links, dtype=np.float64)
     lb = np.empty(iters, dtype=np.float64) if want_lb else None
-    rc = _load().nimble_oracle_solve(n_links, _p(cap), n_comm, _p(cp), n_paths, _p(lp), _p(pl),
-                                     _p(d), float(eps), int(iters), int(flags), _p(splits),
-                                     _p(lam), _p(count), _p(sumload), _p(lb))
+    len_io = None
+    if len0 is not None:
+        len_io = np.array(len0, dtype=np.float64)
+        assert len_io.shape == (n_links,)
+    rc = _load().nimble_oracle_solve_warm(n_links, _p(cap), n_comm, _p(cp), n_paths, _p(lp),
+                                          _p(pl), _p(d), float(eps), int(iters), int(flags),
+                                          _p(len_io), _p(splits), _p(lam), _p(count),
+                                          _p(sumload), _p(lb))
     if rc != 0:
         raise ValueError(f"nimble_oracle_solve failed with code {rc}")
     out = dict(splits=splits, lam=float(lam[0]), count=count, sumload=sumload)
+    if len_io is not None:
+        out["len"] = len_io
     if want_lb:
         out["lb"] = lb
     return out

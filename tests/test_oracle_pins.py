@@ -325,3 +325,58 @@ def test_width_counts_a_commodity_once_per_link(oracle_mod):
                          0.1, 16)
     assert r["count"].tolist() == [15, 1]
     assert r["lam"] == pytest.approx(1e6 / 50e9, rel=1e-14)      # the shared link carries all
+
+
+# ---- warm start (the hysteresis policy read as: start from the previous solve's lengths) ----
+
+def test_warm_start_continues_the_trajectory(oracle_mod):
+    """The link lengths are the whole state of the method: T1 iterations followed by T2
+    iterations started from the lengths the first run ended with must make exactly the choices
+    of one uninterrupted run of T1 + T2 iterations (counts add up, final lengths agree)."""
+    for cfg, flags in ((1, 0), (1, 1), (0, 0)):
+        w = W.make_config(cfg)
+        t = w.topo
+        ones = np.ones(t.n_links)
+        full = oracle_mod.solve(*t.csr(), w.traffic, w.eps, 50, flags=flags, len0=ones)
+        a = oracle_mod.solve(*t.csr(), w.traffic, w.eps, 20, flags=flags, len0=ones)
+        b = oracle_mod.solve(*t.csr(), w.traffic, w.eps, 30, flags=flags, len0=a["len"])
+        assert np.array_equal(full["count"], a["count"] + b["count"])
+        assert np.array_equal(full["len"], b["len"])
+        # S restarts at 0 in the second run, so the sums agree up to the rounding of one add
+        assert np.allclose(full["sumload"], a["sumload"] + b["sumload"], rtol=1e-14, atol=0)
+
+
+def test_unit_lengths_are_the_cold_start(oracle_mod):
+    w = W.make_config(1)
+    t = w.topo
+    cold = oracle_mod.solve(*t.csr(), w.traffic, w.eps, 40)
+    warm = oracle_mod.solve(*t.csr(), w.traffic, w.eps, 40, len0=np.ones(t.n_links))
+    assert np.array_equal(cold["count"], warm["count"]) and cold["lam"] == warm["lam"]
+
+
+def test_lengths_scaled_by_a_power_of_two_change_nothing(oracle_mod):
+    """Only price ratios matter to the argmin; a power of two scales every price exactly."""
+    w = W.make_config(1)
+    t = w.topo
+    a = oracle_mod.solve(*t.csr(), w.traffic, w.eps, 25, len0=np.ones(t.n_links))
+    b = oracle_mod.solve(*t.csr(), w.traffic, w.eps, 30, len0=a["len"])
+    c = oracle_mod.solve(*t.csr(), w.traffic, w.eps, 30, len0=a["len"] * 0.125)
+    assert np.array_equal(b["count"], c["count"]) and b["lam"] == c["lam"]
+    assert np.array_equal(b["len"] * 0.125, c["len"])
+
+
+def test_warm_start_on_new_traffic_keeps_the_loaded_links_expensive(oracle_mod):
+    """After a solve for a hot pair the hot pair's direct link is the longest one; a new
+    solve for uniform traffic started from those lengths moves traffic off that link in its
+    first iteration, which a cold start (everything direct) does not."""
+    t = W.build_fabric(1, 8, 0)
+    hot = np.zeros(t.n_comm)
+    hot[0] = 1e9
+    first = oracle_mod.solve(*t.csr(), hot, 0.1, 30, len0=np.ones(t.n_links))
+    direct0 = t.path_links[t.path_link_ptr[t.comm_path_ptr[0]]]
+    assert first["len"][direct0] == first["len"].max()
+    uni = np.full(t.n_comm, 1e6)
+    cold = oracle_mod.solve(*t.csr(), uni, 0.1, 1)
+    warm = oracle_mod.solve(*t.csr(), uni, 0.1, 1, len0=first["len"])
+    assert cold["count"][t.comm_path_ptr[0]] == 1          # direct
+    assert warm["count"][t.comm_path_ptr[0]] == 0          # moved to a relay
