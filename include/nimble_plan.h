@@ -150,6 +150,24 @@ nimble_status_t nimble_alg1_solve_batch(nimble_topo_t *topo, int32_t batch,
                                         int32_t *d_sweeps, void *hip_stream);
 
 /*
+ * nimble_plan_solve started from given link lengths (warm start) instead of len = 1, and
+ * returning the lengths after the last iteration.  Consecutive plans of a changing workload
+ * that hand the lengths on keep the price trajectory: links that were loaded stay expensive,
+ * so path selection does not flip back at every new plan (the hysteresis policy named in
+ * Sec. I, read as a warm start).  T1 iterations followed by T2 iterations from the returned
+ * lengths make exactly the choices of one solve of T1 + T2 iterations.
+ *
+ *   d_len   device [n_links], by link id, in and out; every entry finite and > 0 (1.0
+ *           everywhere is the cold start).  Lengths grow by at most (1 + eps) per iteration:
+ *           the caller rescales them (e.g. by a power of two, which changes nothing else)
+ *           before they can overflow.
+ * The other arguments as for nimble_plan_solve.  Always runs the streaming regime.
+ */
+nimble_status_t nimble_plan_solve_warm(nimble_topo_t *topo, const double *d_traffic, double eps,
+                                       int32_t iters, double *d_len, double *d_splits,
+                                       double *d_lambda, void *hip_stream);
+
+/*
  * Post-processing of a plan into what a dataplane consumes: bytes per candidate path in whole
  * chunks (the Paths / Flows lists of Algorithm 1), with the practical policies of Sec. I and
  * Sec. V-A: no fragmentation below the chunk granularity and no multi-hop forwarding of small

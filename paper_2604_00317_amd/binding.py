@@ -27,7 +27,7 @@ EXPORTS = [
     "nimble_topo_num_paths", "nimble_topo_nnz", "nimble_topo_bytes_per_iter",
     "nimble_topo_set_regime", "nimble_topo_regime", "nimble_debug_run_phase",
     "nimble_host_build_reverse", "nimble_debug_set_spin_limit", "nimble_topo_phase_bytes",
-    "nimble_alg1_solve_batch", "nimble_plan_quantize",
+    "nimble_alg1_solve_batch", "nimble_plan_quantize", "nimble_plan_solve_warm",
     "nimble_host_records_roundtrip", "nimble_host_layout_stats",
     "nimble_host_build_reverse_streaming",
 ]
@@ -84,6 +84,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.nimble_alg1_solve_batch.restype = ctypes.c_int
     lib.nimble_alg1_solve_batch.argtypes = [vp, i32, vp, ctypes.c_double, ctypes.c_double, i32,
                                             vp, vp, vp, vp]
+    lib.nimble_plan_solve_warm.restype = ctypes.c_int
+    lib.nimble_plan_solve_warm.argtypes = [vp, vp, ctypes.c_double, i32, vp, vp, vp, vp]
     lib.nimble_plan_quantize.restype = ctypes.c_int
     lib.nimble_plan_quantize.argtypes = [vp, vp, vp, i32, ctypes.c_int64, ctypes.c_double, vp, vp]
     lib.nimble_host_layout_stats.restype = ctypes.c_int
@@ -224,6 +226,15 @@ def nimble_alg1_solve_batch(topo: Topo, batch: int, d_traffic, phi: float, chi: 
         int(max_sweeps), _dev_ptr(d_flows, "float64", batch * topo.n_paths, "d_flows"),
         _dev_ptr(d_lambda, "float64", batch, "d_lambda"),
         _dev_ptr(d_sweeps, "int32", batch, "d_sweeps"), _stream_ptr(stream)))
+
+
+def nimble_plan_solve_warm(topo: Topo, d_traffic, eps: float, iters: int, d_len, d_splits,
+                           d_lambda, stream=None) -> None:
+    _check(load_library().nimble_plan_solve_warm(
+        topo.handle, _dev_ptr(d_traffic, "float64", topo.n_comm, "d_traffic"), float(eps),
+        int(iters), _dev_ptr(d_len, "float64", topo.n_links, "d_len"),
+        _dev_ptr(d_splits, "float64", topo.n_paths, "d_splits"),
+        _dev_ptr(d_lambda, "float64", 1, "d_lambda"), _stream_ptr(stream)))
 
 
 def nimble_plan_quantize(topo: Topo, d_traffic, d_splits, iters: int, chi: int,

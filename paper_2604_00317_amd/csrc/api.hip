@@ -144,13 +144,14 @@ int32_t pick_regime(const nimble_topo *topo)
 }
 
 nimble_status_t solve_stream(nimble_topo *topo, const double *d_traffic, double eps,
-                             int32_t iters, double *d_splits, double *d_lambda, hipStream_t s)
+                             int32_t iters, double *d_splits, double *d_lambda, hipStream_t s,
+                             double *d_len = nullptr)
 {
     const nimble::DeviceTopo &d = topo->d;
     // choices are logged per iteration when the log fits (the split fractions are then
     // counted once at the end); otherwise every iteration bumps a per-path counter
     const bool logged = ensure_choice_log(topo, iters);
-    nimble::launch_init(d, d_traffic, s);
+    nimble::launch_init(d, d_traffic, d_len, s);
     nimble::launch_width(d, d_traffic, s);
     for (int32_t it = 0; it < iters; ++it) {
         uint8_t *row = logged ? topo->choice_log + topo->log_stride * static_cast<size_t>(it)
@@ -166,6 +167,7 @@ nimble_status_t solve_stream(nimble_topo *topo, const double *d_traffic, double 
     nimble::launch_epilogue(d, iters, logged ? nullptr : d.count, d_splits, d_lambda, s);
     if (logged)
         nimble::launch_histogram(d, topo->choice_log, topo->log_stride, iters, d_splits, s);
+    if (d_len) nimble::launch_export_len(d, d_len, s);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail_hip(e, "kernel launch (streaming regime)");
     topo->state_ready = true;
@@ -501,6 +503,21 @@ nimble_status_t nimble_alg1_solve_batch(nimble_topo_t *topo, int32_t batch,
                                        d_lambda, d_sweeps, static_cast<hipStream_t>(hip_stream));
     if (e != hipSuccess) return fail_hip(e, "kernel launch (Algorithm 1)");
     return NIMBLE_OK;
+}
+
+nimble_status_t nimble_plan_solve_warm(nimble_topo_t *topo, const double *d_traffic, double eps,
+                                       int32_t iters, double *d_len, double *d_splits,
+                                       double *d_lambda, void *hip_stream)
+{
+    g_last_error.clear();
+    nimble_status_t st = check_solve_args(topo, d_traffic, eps, iters, d_splits, d_lambda);
+    if (st != NIMBLE_OK) return st;
+    if (!d_len) return fail(NIMBLE_ERR_INVALID, "the length pointer must not be NULL");
+    st = check_device(topo);
+    if (st != NIMBLE_OK) return st;
+    topo->last_regime = NIMBLE_REGIME_STREAM;
+    return solve_stream(topo, d_traffic, eps, iters, d_splits, d_lambda,
+                        static_cast<hipStream_t>(hip_stream), d_len);
 }
 
 nimble_status_t nimble_plan_quantize(nimble_topo_t *topo, const double *d_traffic,

@@ -83,7 +83,10 @@ struct DeviceTopo {
 int lanes_per_commodity(int pmax);   // power of two >= pmax, at most 64
 
 // ---- streaming regime: one launch per phase ------------------------------------------------
-void launch_init(const DeviceTopo &t, const double *demand, hipStream_t s);
+// len_in: link lengths to start from, by link id (null: all 1)
+void launch_init(const DeviceTopo &t, const double *demand, const double *len_in, hipStream_t s);
+// the lengths after the last iteration, by link id
+void launch_export_len(const DeviceTopo &t, double *len_out, hipStream_t s);
 void launch_width(const DeviceTopo &t, const double *demand, hipStream_t s);
 // `choice` is the row the choices of this iteration are written to / read from (the
 // topology's own array, or a row of the per-iteration choice log); `count` may be null when

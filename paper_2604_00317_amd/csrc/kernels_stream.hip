@@ -12,6 +12,8 @@ namespace {
 constexpr int kBlock = 256;
 
 __global__ __launch_bounds__(kBlock) void k_init(int E, int K, int P, bool cost_max,
+                                                 const double *__restrict__ len_in,
+                                                 const int32_t *__restrict__ pos_link,
                                                  const double *__restrict__ invcap,
                                                  double *__restrict__ len,
                                                  double *__restrict__ price,
@@ -40,13 +42,25 @@ __global__ __launch_bounds__(kBlock) void k_init(int E, int K, int P, bool cost_
             demand2t[tile_demand_index(sg)] = dk;
         }
     }
+    // lengths start at 1, or at the caller's values (warm start; given by link id); len and S
+    // are kept by position in the flat order of the rows, the price by link id
     for (int e = tid; e < E; e += stride) {
-        len[e] = 1.0;
-        price[e] = cost_max ? 1.0 : invcap[e];
+        const double l_e = len_in ? len_in[e] : 1.0;
+        price[e] = cost_max ? l_e : l_e * invcap[e];
+        len[e] = len_in ? len_in[pos_link[e]] : 1.0;      // here e is a position
         S[e] = 0.0;
     }
     for (int p = tid; p < P; p += stride) count[p] = 0u;
     if (tid == 0) choice[K] = 0u;   // slot K is read (never used) by padding pairs
+}
+
+// link lengths after the last iteration, back in link id order
+__global__ __launch_bounds__(kBlock) void k_export_len(int E, const int32_t *__restrict__ pos_link,
+                                                       const double *__restrict__ len,
+                                                       double *__restrict__ len_out)
+{
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < E) len_out[pos_link[i]] = len[i];
 }
 
 template <int L, int LMAX, bool MAXC>
@@ -581,11 +595,17 @@ int lanes_per_commodity(int pmax)
     return L;
 }
 
-void launch_init(const DeviceTopo &t, const double *demand, hipStream_t s)
+void launch_export_len(const DeviceTopo &t, double *len_out, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_export_len, dim3((t.E + kBlock - 1) / kBlock), dim3(kBlock), 0, s, t.E,
+                       t.pos_link, t.len, len_out);
+}
+
+void launch_init(const DeviceTopo &t, const double *demand, const double *len_in, hipStream_t s)
 {
     const int n = t.E > t.P ? t.E : t.P;
     hipLaunchKernelGGL(k_init, dim3(blocks_for(n, kBlock, 4096)), dim3(kBlock), 0, s, t.E, t.K,
-                       t.P, t.cost_max, t.invcap, t.len, t.price, t.S, t.choice, t.count, t.sigma,
+                       t.P, t.cost_max, len_in, t.pos_link, t.invcap, t.len, t.price, t.S, t.choice, t.count, t.sigma,
                        demand, t.demand1n, t.demand1t, t.demand2, t.demand2t);
 }
 
