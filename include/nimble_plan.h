@@ -50,7 +50,8 @@ enum {
     NIMBLE_REGIME_AUTO = 0,     /* chosen from the problem size */
     NIMBLE_REGIME_RESIDENT = 1, /* one workgroup per plan, whole iteration loop in one kernel,
                                    state in LDS */
-    NIMBLE_REGIME_STREAM = 2,   /* three kernels per iteration streaming the two CSRs */
+    NIMBLE_REGIME_STREAM = 2,   /* one kernel per phase: two or three launches per iteration
+                                   streaming the repacked CSRs */
     NIMBLE_REGIME_PERSISTENT = 3 /* one persistent kernel per solve with grid-wide barriers */
 };
 
@@ -208,7 +209,8 @@ int64_t nimble_topo_nnz(const nimble_topo_t *topo);
 int64_t nimble_topo_bytes_per_iter(const nimble_topo_t *topo);
 
 /* The same figure for one phase of the streaming regime (0: path-cost gather + argmin over
- * the forward CSR, 1: link-load reduce over the reverse CSR, 2: length update). */
+ * the forward CSR, 1: link-load reduce over the reverse CSR, 2: length update).  On topologies
+ * whose reduce and update run as one kernel, phase 1 covers both and phase 2 is 0. */
 int64_t nimble_topo_phase_bytes(const nimble_topo_t *topo, int32_t phase);
 
 /* Force a kernel regime (NIMBLE_REGIME_*) for later solves; NIMBLE_ERR_RANGE if the topology
@@ -219,9 +221,11 @@ int32_t nimble_topo_regime(const nimble_topo_t *topo);
 /*
  * Benchmark helper: enqueue `reps` back-to-back launches of one phase of the streaming regime
  * on `hip_stream`, without changing the plan state another solve depends on
- * (phase 0: path-cost gather + argmin, 1: link-load reduce, 2: length update).  The state
- * must have been initialised by a previous nimble_plan_solve on this topology with the same
- * d_traffic.  Used to time a kernel's average launch with HIP events.
+ * (phase 0: path-cost gather + argmin, 1: link-load reduce, 2: length update with step 0; on
+ * topologies whose reduce and update run as one kernel phase 1 is that kernel and phase 2 is
+ * refused with NIMBLE_ERR_INVALID).  The state must have been initialised by a previous
+ * streaming-regime nimble_plan_solve on this topology with the same d_traffic.  Used to time a
+ * kernel's average launch with HIP events.
  */
 nimble_status_t nimble_debug_run_phase(nimble_topo_t *topo, int32_t phase, int32_t reps,
                                        const double *d_traffic, void *hip_stream);

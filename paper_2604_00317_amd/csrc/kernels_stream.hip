@@ -1,5 +1,8 @@
-// Streaming regime: three kernels per Jacobi iteration (path-cost gather + argmin, link-load
-// reduce, length update), each a thin wrapper over the phase code in phases.hpp.
+// Streaming regime: one kernel per phase of a Jacobi iteration.  The path-cost gather + argmin
+// runs over the forward records (k_argmin_rec) or the plain CSR (k_argmin); the link-load
+// reduce and the length update are either one kernel per block of links (k_reduce_update) or
+// two (k_load_reduce over tile items, strip items, octet passes and single pairs, then
+// k_update).  The reduce phases themselves live in phases.hpp.
 #include "host_topo.hpp"
 #include "kernels.hpp"
 #include "phases.hpp"

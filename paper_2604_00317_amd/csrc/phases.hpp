@@ -1,5 +1,7 @@
-// Device code of the three per-iteration phases, shared by the streaming kernels (one launch
-// per phase) and the persistent kernel (one launch per solve, grid barriers between phases).
+// Device code of the per-iteration phases -- candidate scan over the plain CSR, link-load
+// reduce over tile items / strip items / octet passes / single pairs, length update -- shared
+// by the streaming kernels (one launch per phase) and the persistent kernel (one launch per
+// solve, grid barriers between phases).
 // All arithmetic is binary64, one IEEE operation per statement.
 #pragma once
 #include <hip/hip_runtime.h>
@@ -16,11 +18,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 template <typename T>
 __device__ __forceinline__ T stream_load(const T *p)
 {
-#ifdef NIMBLE_NO_NT
-    return *p;
-#else
     return __builtin_nontemporal_load(p);
-#endif
 }
 
 // Forward-CSR loads: neighbouring lanes and the next unrolled load touch the same cache lines,
