@@ -14,16 +14,18 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "nimble_oracle.c")
 _SRC_ALG1 = os.path.join(_HERE, "alg1_oracle.c")
+_SRC_ADAPT = os.path.join(_HERE, "adaptive_oracle.c")
 _LIB = os.path.join(_HERE, "libnimble_oracle.so")
 _lib = None
 
 
 def build(force: bool = True) -> str:
     """Compile the oracle with gcc.  -ffp-contract=off keeps every statement one IEEE op."""
-    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_ALG1))
+    newest = max(os.path.getmtime(_SRC), os.path.getmtime(_SRC_ALG1),
+                 os.path.getmtime(_SRC_ADAPT))
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < newest:
         cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fopenmp", "-fPIC", "-shared",
-               "-Wall", "-Wextra", "-o", _LIB, _SRC, _SRC_ALG1, "-lm"]
+               "-Wall", "-Wextra", "-o", _LIB, _SRC, _SRC_ALG1, _SRC_ADAPT, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 
@@ -45,6 +47,14 @@ def _load():
             ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_double, ctypes.c_int32,
             ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
             ctypes.c_void_p, ctypes.c_void_p]
+        lib.nimble_oracle_solve_adaptive.restype = ctypes.c_int
+        lib.nimble_oracle_solve_adaptive.argtypes = [
+            ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_double, ctypes.c_int32,
+            ctypes.c_int32, ctypes.c_uint32, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p,
+            ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        lib.nimble_oracle_chunked_sum.restype = ctypes.c_double
+        lib.nimble_oracle_chunked_sum.argtypes = [ctypes.c_void_p, ctypes.c_int64]
         lib.nimble_oracle_alg1.restype = ctypes.c_int
         lib.nimble_oracle_alg1.argtypes = [
             ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32,
@@ -138,3 +148,37 @@ def alg1(n_links, cap, n_comm, comm_path_ptr, n_paths, path_link_ptr, path_links
     if rc != 0:
         raise ValueError(f"nimble_oracle_alg1 failed with code {rc}")
     return dict(flows=flows[:n_paths], lam=float(lam[0]), sweeps=int(sweeps[0]), load=load)
+
+
+def solve_adaptive(n_links, cap, n_comm, comm_path_ptr, n_paths, path_link_ptr, path_links,
+                   demand, eps, max_iters, check_every, flags=0):
+    """Adaptive-step variant with early stop.  Returns dict(splits, lam, iters, lb, weight,
+    sigma [iters])."""
+    cap = np.ascontiguousarray(cap, dtype=np.float64)
+    cp = np.ascontiguousarray(comm_path_ptr, dtype=np.int32)
+    lp = np.ascontiguousarray(path_link_ptr, dtype=np.int32)
+    pl = np.ascontiguousarray(path_links, dtype=np.int32)
+    d = np.ascontiguousarray(demand, dtype=np.float64)
+    assert cap.shape == (n_links,) and cp.shape == (n_comm + 1,) and lp.shape == (n_paths + 1,)
+    assert d.shape == (n_comm,) and pl.shape == (int(lp[-1]),)
+    splits = np.empty(n_paths, dtype=np.float64)
+    lam = np.zeros(1, dtype=np.float64)
+    iters = np.zeros(1, dtype=np.int32)
+    lb = np.zeros(1, dtype=np.float64)
+    weight = np.empty(n_paths, dtype=np.float64)
+    sigma = np.zeros(max_iters, dtype=np.float64)
+    rc = _load().nimble_oracle_solve_adaptive(
+        n_links, _p(cap), n_comm, _p(cp), n_paths, _p(lp), _p(pl), _p(d), float(eps),
+        int(max_iters), int(check_every), int(flags), _p(splits), _p(lam), _p(iters), _p(lb),
+        _p(weight), _p(sigma))
+    if rc != 0:
+        raise ValueError(f"nimble_oracle_solve_adaptive failed with code {rc}")
+    n = int(iters[0])
+    return dict(splits=splits, lam=float(lam[0]), iters=n, lb=float(lb[0]), weight=weight,
+                sigma=sigma[:n])
+
+
+def chunked_sum(x) -> float:
+    """The fixed-association sum the adaptive variant uses for its lower bound."""
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    return float(_load().nimble_oracle_chunked_sum(_p(x), x.size))

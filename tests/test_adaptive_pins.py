@@ -1,0 +1,96 @@
+"""Pins of the adaptive-step oracle (oracle/adaptive_oracle.c)."""
+import math
+import os
+
+import numpy as np
+import pytest
+
+from oracle import lp_simplex
+from paper_2604_00317_amd import workloads as W
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def parallel_links(caps):
+    m = len(caps)
+    return (m, np.asarray(caps, dtype=np.float64), 1, np.array([0, m], dtype=np.int32), m,
+            np.arange(m + 1, dtype=np.int32), np.arange(m, dtype=np.int32))
+
+
+def test_switch_iteration_worked_by_hand(oracle_mod):
+    line = [l for l in open(os.path.join(GOLDEN, "adaptive_switch_iteration.txt"))
+            if l[0] != "#"][0].split()
+    first, s_before, s_at = int(line[0]), float(line[1]), float(line[2])
+    r = oracle_mod.solve_adaptive(*parallel_links([100.0, 50.0]), [10.0], 0.1, 12, 1000)
+    assert r["sigma"][:first - 1].tolist() == [s_before] * (first - 1)
+    assert r["sigma"][first - 1] == s_at
+    # weights: eight iterations of sigma 10 on link 0 before the switch
+    r9 = oracle_mod.solve_adaptive(*parallel_links([100.0, 50.0]), [10.0], 0.1, first, 1000)
+    assert r9["weight"].tolist() == [s_before * (first - 1), s_at]
+    assert r9["splits"].tolist() == [80.0 / 85.0, 5.0 / 85.0]
+
+
+def test_parallel_links_reach_the_closed_form(oracle_mod):
+    caps = [100.0, 50.0, 25.0]
+    r = oracle_mod.solve_adaptive(*parallel_links(caps), [70.0], 0.05, 100000, 5)
+    opt = 70.0 / sum(caps)
+    assert r["lb"] <= opt * (1 + 1e-12) <= r["lam"] * (1 + 1e-12)
+    assert r["lam"] <= (1.05 ** 2) * r["lb"]
+    assert r["iters"] < 100000                       # it stopped on the certificate
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_bounds_bracket_the_lp_optimum(oracle_mod, seed):
+    """LB <= lambda* <= lambda on tiny instances, lambda* from an exact simplex."""
+    rng = np.random.default_rng(100 + seed)
+    t = W.random_topology(rng, 8, 5, 3, 3)
+    d = rng.integers(1, 50, size=t.n_comm).astype(np.float64)
+    lam_star, _ = lp_simplex.min_congestion_lp(t.n_links, t.cap, t.comm_path_ptr,
+                                               t.path_link_ptr, t.path_links, d)
+    r = oracle_mod.solve_adaptive(*t.csr(), d, 0.05, 20000, 3)
+    assert r["lb"] <= lam_star * (1 + 1e-9)
+    assert lam_star <= r["lam"] * (1 + 1e-9)
+    assert r["lam"] <= (1.05 ** 2) * r["lb"] * (1 + 1e-12)
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 3])
+def test_plan_invariants_and_fewer_iterations(oracle_mod, cfg):
+    w = W.make_config(cfg)
+    t = w.topo
+    r = oracle_mod.solve_adaptive(*t.csr(), w.traffic, w.eps, 20000, 10)
+    cp = t.comm_path_ptr
+    sums = np.add.reduceat(r["splits"], cp[:-1])
+    assert np.allclose(sums, 1.0, rtol=0, atol=1e-12)
+    # lambda is the congestion of the returned splits
+    lam, _ = oracle_mod.congestion(t.n_links, t.cap, t.comm_path_ptr, t.path_link_ptr,
+                                   t.path_links, w.traffic, r["splits"])
+    assert abs(lam - r["lam"]) <= 1e-9 * r["lam"]
+    assert r["lam"] <= (1 + w.eps) ** 2 * r["lb"]
+    # the fixed-step method needs more iterations for a plan that good (or does not get there
+    # within the configuration's iteration count at all)
+    fixed = oracle_mod.solve(*t.csr(), w.traffic, w.eps, r["iters"])
+    assert fixed["lam"] >= r["lam"] * (1 - 1e-3)
+
+
+def test_zero_traffic(oracle_mod):
+    w = W.make_config(0)
+    r = oracle_mod.solve_adaptive(*w.topo.csr(), np.zeros(w.topo.n_comm), 0.1, 50, 5)
+    assert r["iters"] == 0 and r["lam"] == 0.0
+    assert r["splits"][w.topo.comm_path_ptr[:-1]].tolist() == [1.0] * w.topo.n_comm
+
+
+def test_chunked_sum_is_a_sum(oracle_mod):
+    rng = np.random.default_rng(0)
+    for n in (0, 1, 255, 256, 257, 10000):
+        x = rng.random(n) * 1e6
+        got = oracle_mod.chunked_sum(x)
+        assert abs(got - math.fsum(x)) <= 1e-12 * max(1.0, math.fsum(x))
+    # the association itself: chunks of 256, then the chunk sums, both left to right
+    x = rng.random(700)
+    s = 0.0
+    for c in range(0, 700, 256):
+        part = 0.0
+        for v in x[c:c + 256]:
+            part = part + v
+        s = s + part
+    assert oracle_mod.chunked_sum(x) == s
