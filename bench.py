@@ -257,6 +257,25 @@ def main() -> int:
             post["cpu_oracle_us_per_plan"] = dtc * 1e6 * topo.n_comm / n_k
             post["cpu_sample"] = f"first {n_k} of {topo.n_comm} pairs, one core, scaled"
             post["max_abs_diff_flows"] = float(np.abs(got - ref).max())
+    # ---- adaptive step + early stop on the same workload -------------------------------------
+    adaptive = None
+    if not w.batch and not args.no_also:
+        B.nimble_plan_solve(h, r["d_traffic"], w.eps, w.iters, r["d_splits"], r["d_lambda"])
+        torch.cuda.synchronize()
+        lam_fixed = float(r["d_lambda"].item())
+        check_every = 25
+        B.nimble_plan_solve_adaptive(h, r["d_traffic"], w.eps, 4 * w.iters, check_every,
+                                     r["d_splits"], r["d_lambda"])          # warm-up
+        t1 = time.perf_counter()
+        n_done, lb = B.nimble_plan_solve_adaptive(h, r["d_traffic"], w.eps, 4 * w.iters,
+                                                  check_every, r["d_splits"], r["d_lambda"])
+        dt = time.perf_counter() - t1
+        lam_ad = float(r["d_lambda"].item())
+        adaptive = dict(iterations=n_done, ms_per_plan=dt * 1e3, iterations_per_s=n_done / dt,
+                        check_every=check_every, lambda_=lam_ad, lower_bound=lb,
+                        gap=lam_ad / lb if lb > 0 else None, target_gap=(1 + w.eps) ** 2,
+                        lambda_fixed_step=lam_fixed, fixed_step_iters=w.iters,
+                        fixed_step_ms=ms_per_step)
     h.close()
     del r
 
@@ -328,6 +347,7 @@ def main() -> int:
         "cpu_baseline": cpu,
         "also": also,
         "post_processing": post,
+        "adaptive_step": adaptive,
         "setup_s": setup,
     }
     print(json.dumps(out))

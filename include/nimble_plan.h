@@ -169,6 +169,37 @@ nimble_status_t nimble_plan_solve_warm(nimble_topo_t *topo, const double *d_traf
                                        double *d_lambda, void *hip_stream);
 
 /*
+ * The adaptive-step variant of the method (the multiplicative-weights scheme Sec. IV-B cites,
+ * in its variable-step form), which stops as soon as the plan is provably good enough:
+ *   step        sigma_t = 1 / max_e u_e^t: the most loaded link of an iteration grows by the
+ *               full factor 1 + eps;  len_e *= 1 + eps * sigma_t * u_e^t
+ *   plan        the sigma-weighted average of the iterations' routings: splits_p = (sum of
+ *               sigma_t over the iterations that chose p) / sum_t sigma_t, lambda likewise
+ *   early stop  every check_every iterations the weak-duality bound
+ *               LB = (sum_k d_k * cheapest cost of k) / (sum_e len_e)  <=  optimum  is taken
+ *               (both sums in index order, sequential inside chunks of 256 terms, the chunk
+ *               sums sequential); the solve stops once lambda <= (1 + eps)^2 * best LB.
+ *               Bottleneck-cost topologies (NIMBLE_COST_MAX) have no such bound and run
+ *               max_iters iterations.
+ *
+ *   max_iters    >= 1, max_iters * log1p(eps) <= 700
+ *   check_every  >= 1
+ *   d_splits, d_lambda   device outputs as for nimble_plan_solve
+ *   iters_done   host out: iterations made (0 for all-zero traffic: every pair then stays on
+ *                its first candidate)
+ *   lower_bound  host out: best LB seen (0 if no check was made)
+ * Unlike nimble_plan_solve this call synchronises hip_stream at every check and before it
+ * returns.  Always runs the streaming regime; needs the per-iteration choice log of
+ * max_iters rows (NIMBLE_ERR_ALLOC if it cannot be allocated).  Bit-identical to the plain CPU
+ * definition for integer-valued demands.
+ */
+nimble_status_t nimble_plan_solve_adaptive(nimble_topo_t *topo, const double *d_traffic,
+                                           double eps, int32_t max_iters, int32_t check_every,
+                                           double *d_splits, double *d_lambda,
+                                           int32_t *iters_done, double *lower_bound,
+                                           void *hip_stream);
+
+/*
  * Post-processing of a plan into what a dataplane consumes: bytes per candidate path in whole
  * chunks (the Paths / Flows lists of Algorithm 1), with the practical policies of Sec. I and
  * Sec. V-A: no fragmentation below the chunk granularity and no multi-hop forwarding of small

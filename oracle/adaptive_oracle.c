@@ -104,7 +104,9 @@ int nimble_oracle_solve_adaptive(int32_t n_links, const double *cap, int32_t n_c
     int32_t t = 0;
     const double gap = (1.0 + eps) * (1.0 + eps);
     while (t < max_iters) {
-        /* cheapest candidate of every commodity under the same prices (Jacobi) */
+        /* cheapest candidate of every commodity under the same prices (Jacobi); the
+           commodities are independent, so the threads change nothing */
+#pragma omp parallel for schedule(static)
         for (int k = 0; k < K; ++k) {
             double cbest = INFINITY;
             int jbest = 0;

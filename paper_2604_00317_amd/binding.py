@@ -28,6 +28,7 @@ EXPORTS = [
     "nimble_topo_set_regime", "nimble_topo_regime", "nimble_debug_run_phase",
     "nimble_host_build_reverse", "nimble_debug_set_spin_limit", "nimble_topo_phase_bytes",
     "nimble_alg1_solve_batch", "nimble_plan_quantize", "nimble_plan_solve_warm",
+    "nimble_plan_solve_adaptive",
     "nimble_host_records_roundtrip", "nimble_host_layout_stats",
     "nimble_host_build_reverse_streaming",
 ]
@@ -86,6 +87,9 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
                                             vp, vp, vp, vp]
     lib.nimble_plan_solve_warm.restype = ctypes.c_int
     lib.nimble_plan_solve_warm.argtypes = [vp, vp, ctypes.c_double, i32, vp, vp, vp, vp]
+    lib.nimble_plan_solve_adaptive.restype = ctypes.c_int
+    lib.nimble_plan_solve_adaptive.argtypes = [vp, vp, ctypes.c_double, i32, i32, vp, vp, vp, vp,
+                                               vp]
     lib.nimble_plan_quantize.restype = ctypes.c_int
     lib.nimble_plan_quantize.argtypes = [vp, vp, vp, i32, ctypes.c_int64, ctypes.c_double, vp, vp]
     lib.nimble_host_layout_stats.restype = ctypes.c_int
@@ -235,6 +239,20 @@ def nimble_plan_solve_warm(topo: Topo, d_traffic, eps: float, iters: int, d_len,
         int(iters), _dev_ptr(d_len, "float64", topo.n_links, "d_len"),
         _dev_ptr(d_splits, "float64", topo.n_paths, "d_splits"),
         _dev_ptr(d_lambda, "float64", 1, "d_lambda"), _stream_ptr(stream)))
+
+
+def nimble_plan_solve_adaptive(topo: Topo, d_traffic, eps: float, max_iters: int,
+                               check_every: int, d_splits, d_lambda, stream=None):
+    """Returns (iterations made, best lower bound); splits and lambda land in the tensors."""
+    iters = ctypes.c_int32(0)
+    lb = ctypes.c_double(0.0)
+    _check(load_library().nimble_plan_solve_adaptive(
+        topo.handle, _dev_ptr(d_traffic, "float64", topo.n_comm, "d_traffic"), float(eps),
+        int(max_iters), int(check_every),
+        _dev_ptr(d_splits, "float64", topo.n_paths, "d_splits"),
+        _dev_ptr(d_lambda, "float64", 1, "d_lambda"), ctypes.byref(iters), ctypes.byref(lb),
+        _stream_ptr(stream)))
+    return int(iters.value), float(lb.value)
 
 
 def nimble_plan_quantize(topo: Topo, d_traffic, d_splits, iters: int, chi: int,

@@ -48,6 +48,10 @@ struct nimble_topo {
     uint8_t *choice_log = nullptr;
     int64_t log_rows = 0;
     size_t log_stride = 0;
+    // workspace of the adaptive-step variant; the sigma log grows with max_iters
+    nimble::AdaptiveState ad{};
+    bool ad_ready = false;
+    int64_t ad_sigma_rows = 0;
     void *sync_words = nullptr; // barrier counter and reductions of the persistent kernel
     int n_cu = 0;
     unsigned int spin_limit = 1u << 22;   // barrier polls before a solve is abandoned
@@ -88,6 +92,9 @@ void release(nimble_topo *t)
     if (t->choice_log) (void)hipFree(t->choice_log);
     t->choice_log = nullptr;
     t->log_rows = 0;
+    if (t->ad.sigma_log) (void)hipFree(t->ad.sigma_log);
+    t->ad.sigma_log = nullptr;
+    t->ad_sigma_rows = 0;
 }
 
 // Makes sure the choice log holds `iters` rows; false when it cannot (too large or out of
@@ -291,6 +298,12 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     NIMBLE_TRY(upload(t, h.schunk_end.data(), h.schunk_end.size(), &d.schunk_end), "schunk");
     NIMBLE_TRY(upload(t, h.schunk_slot.data(), h.schunk_slot.size(), &d.schunk_slot), "schunk");
     NIMBLE_TRY(upload(t, h.pos_link.data(), h.pos_link.size(), &d.pos_link), "pos_link");
+    {
+        std::vector<int32_t> pos_of_link(h.pos_link.size());
+        for (size_t i = 0; i < h.pos_link.size(); ++i) pos_of_link[h.pos_link[i]] = static_cast<int32_t>(i);
+        NIMBLE_TRY(upload(t, pos_of_link.data(), pos_of_link.size(), &t->ad.pos_of_link),
+                   "pos_of_link");
+    }
     NIMBLE_TRY(upload(t, h.pos_slot_ptr.data(), h.pos_slot_ptr.size(), &d.pos_slot_ptr),
                "pos_slot_ptr");
     NIMBLE_TRY(upload(t, h.blk_desc.data(), h.blk_desc.size(), &d.blk_desc), "blk_desc");
@@ -518,6 +531,89 @@ nimble_status_t nimble_plan_solve_warm(nimble_topo_t *topo, const double *d_traf
     topo->last_regime = NIMBLE_REGIME_STREAM;
     return solve_stream(topo, d_traffic, eps, iters, d_splits, d_lambda,
                         static_cast<hipStream_t>(hip_stream), d_len);
+}
+
+nimble_status_t nimble_plan_solve_adaptive(nimble_topo_t *topo, const double *d_traffic,
+                                           double eps, int32_t max_iters, int32_t check_every,
+                                           double *d_splits, double *d_lambda,
+                                           int32_t *iters_done, double *lower_bound,
+                                           void *hip_stream)
+{
+    g_last_error.clear();
+    nimble_status_t st = check_solve_args(topo, d_traffic, eps, max_iters, d_splits, d_lambda);
+    if (st != NIMBLE_OK) return st;
+    if (check_every < 1) return fail(NIMBLE_ERR_INVALID, "check_every must be >= 1");
+    if (!iters_done || !lower_bound)
+        return fail(NIMBLE_ERR_INVALID, "iters_done and lower_bound must not be NULL");
+    st = check_device(topo);
+    if (st != NIMBLE_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    const nimble::DeviceTopo &d = topo->d;
+    nimble::AdaptiveState &a = topo->ad;
+    hipError_t e = hipSuccess;
+    if (!topo->ad_ready) {
+        const size_t n_chunks = (static_cast<size_t>(d.K) + 255) / 256 + (static_cast<size_t>(d.E) + 255) / 256;
+        e = allocate(topo, 2, &a.flags);
+        if (e == hipSuccess) e = allocate(topo, 4, &a.ascal);
+        if (e == hipSuccess) e = allocate(topo, static_cast<size_t>(d.K), &a.term);
+        if (e == hipSuccess) e = allocate(topo, n_chunks, &a.chunk);
+        if (e == hipSuccess) e = allocate(topo, static_cast<size_t>(d.E), &a.u_pos);
+        if (e == hipSuccess) e = allocate(topo, (static_cast<size_t>(d.E) + 15) / 16, &a.block_max_u);
+        if (e == hipSuccess) e = allocate(topo, (static_cast<size_t>(d.E) + 255) / 256, &a.block_max_s);
+        if (e != hipSuccess)
+            return e == hipErrorOutOfMemory ? fail(NIMBLE_ERR_ALLOC, "adaptive workspace")
+                                            : fail_hip(e, "adaptive workspace");
+        topo->ad_ready = true;
+    }
+    if (topo->ad_sigma_rows < max_iters) {
+        if (a.sigma_log) (void)hipFree(a.sigma_log);
+        a.sigma_log = nullptr;
+        topo->ad_sigma_rows = 0;
+        void *p = nullptr;
+        if (hipMalloc(&p, sizeof(double) * static_cast<size_t>(max_iters)) != hipSuccess) {
+            (void)hipGetLastError();
+            return fail(NIMBLE_ERR_ALLOC, "step log of the adaptive solve");
+        }
+        a.sigma_log = static_cast<double *>(p);
+        topo->ad_sigma_rows = max_iters;
+    }
+    // the weighted split fractions need the choice of every iteration
+    if (std::getenv("NIMBLE_TUNE_NO_CHOICE_LOG") || !ensure_choice_log(topo, max_iters))
+        return fail(NIMBLE_ERR_ALLOC, "the choice log of max_iters rows cannot be allocated");
+    topo->last_regime = NIMBLE_REGIME_STREAM;
+    const double gap = (1.0 + eps) * (1.0 + eps);
+    nimble::launch_ad_reset(a, s);
+    nimble::launch_init(d, d_traffic, nullptr, s);
+    int32_t flags_host[2] = {0, 0};
+    for (int32_t t = 0; t < max_iters; ++t) {
+        uint8_t *row = topo->choice_log + topo->log_stride * static_cast<size_t>(t);
+        nimble::launch_argmin(d, row, nullptr, s);
+        const bool check = ((t + 1) % check_every) == 0 && !d.cost_max;
+        if (check) nimble::launch_ad_bound(d, a, row, d_traffic, s);
+        nimble::launch_load_reduce(d, row, d_traffic, s);
+        nimble::launch_ad_update(d, a, eps, s);
+        if (check) {
+            // the stop decision is taken on the device; the host looks at it here
+            nimble::launch_ad_lambda(d, a, gap, true, s);
+            e = hipMemcpyAsync(flags_host, a.flags, sizeof(flags_host), hipMemcpyDeviceToHost, s);
+            if (e == hipSuccess) e = hipStreamSynchronize(s);
+            if (e != hipSuccess) return fail_hip(e, "adaptive solve (stop test)");
+            if (flags_host[0]) break;
+        }
+    }
+    nimble::launch_ad_lambda(d, a, gap, false, s);
+    e = nimble::launch_ad_histogram(d, a, topo->choice_log, topo->log_stride, d_splits, d_lambda, s);
+    if (e != hipSuccess) return fail_hip(e, "kernel launch (adaptive regime)");
+    double ascal_host[4] = {0, 0, 0, 0};
+    e = hipMemcpyAsync(flags_host, a.flags, sizeof(flags_host), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(ascal_host, a.ascal, sizeof(ascal_host), hipMemcpyDeviceToHost, s);
+    if (e == hipSuccess) e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return fail_hip(e, "adaptive solve (results)");
+    *iters_done = flags_host[1];
+    *lower_bound = ascal_host[2];
+    topo->state_ready = true;
+    return NIMBLE_OK;
 }
 
 nimble_status_t nimble_plan_quantize(nimble_topo_t *topo, const double *d_traffic,

@@ -120,6 +120,32 @@ hipError_t launch_persistent(const DeviceTopo &t, void *sync_words, int n_cu,
                              unsigned int spin_limit, const double *demand, double eps,
                              int32_t iters, double *splits, double *lambda, hipStream_t s);
 
+// ---- adaptive-step variant of the streaming regime --------------------------------------------
+// Device state of one adaptive solve (owned by the topology, sized for max_iters).
+struct AdaptiveState {
+    int32_t *flags;            // [0] stop flag, [1] iterations made
+    double *ascal;             // [0] W = sum of sigma, [1] bound of this check, [2] best bound,
+                               // [3] lambda
+    double *term;              // [K] d_k * cheapest cost_k
+    double *chunk;             // [ceil(K/256) + ceil(E/256)] chunk sums of alpha and D
+    double *u_pos;             // [E] normalised loads by position
+    double *block_max_u;       // [ceil(E/16)]
+    double *block_max_s;       // [ceil(E/256)]
+    double *sigma_log;         // [max_iters]
+    const int32_t *pos_of_link;  // [E] position of every link in the flat order
+};
+void launch_ad_reset(const AdaptiveState &a, hipStream_t s);
+// the weak-duality bound under the prices the choices in `choice` were made with
+void launch_ad_bound(const DeviceTopo &t, const AdaptiveState &a, const uint8_t *choice,
+                     const double *demand, hipStream_t s);
+// u, sigma, S, len, price, W from the slot partials of the reduce
+void launch_ad_update(const DeviceTopo &t, const AdaptiveState &a, double eps, hipStream_t s);
+// lambda = max S / W; with `check` also the best bound and the stop test
+void launch_ad_lambda(const DeviceTopo &t, const AdaptiveState &a, double gap, bool check,
+                      hipStream_t s);
+hipError_t launch_ad_histogram(const DeviceTopo &t, const AdaptiveState &a, const uint8_t *log,
+                               size_t stride, double *splits, double *lambda, hipStream_t s);
+
 // ---- Algorithm 1 (sequential sweep), one thread per problem of a batch -----------------------
 // LDS one workgroup (64 problems, down to 8 for larger topologies) needs, and whether it fits
 // the LDS of a compute unit.

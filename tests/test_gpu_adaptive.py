@@ -1,0 +1,91 @@
+"""GPU parity of nimble_plan_solve_adaptive against oracle/adaptive_oracle.c, through the C ABI."""
+import numpy as np
+import pytest
+
+from paper_2604_00317_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2604_00317_amd import binding
+    binding.load_library(build_if_missing=False)
+    return binding
+
+
+def gpu_adaptive(B, topo, demand, eps, max_iters, check_every, flags=0):
+    import torch
+    h = B.nimble_topo_create(topo.n_links, topo.cap, topo.n_comm, topo.comm_path_ptr,
+                             topo.n_paths, topo.path_link_ptr, topo.path_links, flags)
+    try:
+        d = torch.as_tensor(np.ascontiguousarray(demand, dtype=np.float64)).to("cuda:0")
+        splits = torch.full((topo.n_paths,), float("nan"), dtype=torch.float64, device="cuda:0")
+        lam = torch.full((1,), float("nan"), dtype=torch.float64, device="cuda:0")
+        iters, lb = B.nimble_plan_solve_adaptive(h, d, eps, max_iters, check_every, splits, lam)
+        return splits.cpu().numpy(), float(lam.item()), iters, lb
+    finally:
+        h.close()
+
+
+def check(oracle_mod, B, topo, demand, eps, max_iters, check_every, flags=0):
+    ref = oracle_mod.solve_adaptive(*topo.csr(), demand, eps, max_iters, check_every, flags=flags)
+    splits, lam, iters, lb = gpu_adaptive(B, topo, demand, eps, max_iters, check_every, flags)
+    assert iters == ref["iters"]
+    assert lb == ref["lb"]
+    assert lam == ref["lam"]
+    assert np.array_equal(splits, ref["splits"])
+    return ref
+
+
+@pytest.mark.parametrize("cfg,check_every", [(0, 10), (0, 1), (1, 7), (3, 25)])
+def test_stops_where_the_oracle_stops(oracle_mod, B, cfg, check_every):
+    w = W.make_config(cfg)
+    print(f"[adaptive] config {cfg} check_every={check_every}", flush=True)
+    ref = check(oracle_mod, B, w.topo, w.traffic, w.eps, 5000, check_every)
+    assert ref["iters"] < 5000 and ref["lam"] <= (1 + w.eps) ** 2 * ref["lb"]
+
+
+def test_iteration_limit_and_bottleneck_cost(oracle_mod, B):
+    w = W.make_config(1)
+    check(oracle_mod, B, w.topo, w.traffic, w.eps, 37, 10)             # limit before the gap
+    ref = check(oracle_mod, B, w.topo, w.traffic, w.eps, 60, 10, flags=1)
+    assert ref["iters"] == 60 and ref["lb"] == 0.0                     # no bound in this mode
+
+
+def test_tiled_layout_of_the_large_fabric(oracle_mod, B):
+    w = W.make_config(4)
+    print("[adaptive] config 4, 30 iterations", flush=True)
+    check(oracle_mod, B, w.topo, w.traffic, w.eps, 30, 10)
+
+
+@pytest.mark.parametrize("seed", [3, 4])
+def test_random_topologies(oracle_mod, B, seed):
+    rng = np.random.default_rng(seed)
+    t = W.random_topology(rng, 60, 300, 20, 4)
+    d = rng.integers(0, 1 << 24, size=t.n_comm).astype(np.float64)
+    check(oracle_mod, B, t, d, 0.1, 400, 5)
+
+
+def test_zero_traffic(oracle_mod, B):
+    w = W.make_config(0)
+    ref = check(oracle_mod, B, w.topo, np.zeros(w.topo.n_comm), 0.1, 40, 5)
+    assert ref["iters"] == 0 and ref["lam"] == 0.0
+
+
+def test_argument_errors(B):
+    import torch
+    w = W.make_config(0)
+    h = B.nimble_topo_create(*w.topo.csr())
+    d = torch.zeros(w.topo.n_comm, dtype=torch.float64, device="cuda:0")
+    sp = torch.zeros(w.topo.n_paths, dtype=torch.float64, device="cuda:0")
+    lam = torch.zeros(1, dtype=torch.float64, device="cuda:0")
+    try:
+        for eps, mi, ce in ((0.0, 10, 1), (0.1, 0, 1), (0.1, 10, 0)):
+            with pytest.raises(B.NimbleError) as ei:
+                B.nimble_plan_solve_adaptive(h, d, eps, mi, ce, sp, lam)
+            assert ei.value.status == B.NIMBLE_ERR_INVALID
+    finally:
+        h.close()
