@@ -80,6 +80,25 @@ def test_batched_single_node(oracle_mod, B, batch):
         assert lam[b] == ref["lam"], b
 
 
+@pytest.mark.parametrize("regime", [2, 3])
+def test_batch_outside_the_resident_regime(oracle_mod, B, regime):
+    """Topologies that do not fit LDS (or a forced regime) solve a batch one plan after another
+    on the stream, reusing the topology's workspace: every plan must still match the oracle."""
+    w = W.make_config(2, batch=3)
+    t = w.topo
+    h = B.nimble_topo_create(*t.csr())
+    try:
+        B.nimble_topo_set_regime(h, regime)
+        splits, lam = B.plan(h, w.traffic, w.eps, 60)
+        assert h.regime == regime
+    finally:
+        h.close()
+    for b in range(3):
+        ref = oracle_mod.solve(*t.csr(), w.traffic[b], w.eps, 60)
+        assert np.array_equal(splits[b], ref["splits"]), b
+        assert lam[b] == ref["lam"], b
+
+
 @pytest.mark.parametrize("regime", [1, 2, 3])
 @pytest.mark.parametrize("flags", [0, 1])
 @pytest.mark.parametrize("seed,E,K,pm,lm", [(1, 7, 3, 4, 3), (2, 40, 130, 9, 5),
