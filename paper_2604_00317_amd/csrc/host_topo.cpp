@@ -714,7 +714,8 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
         std::vector<uint16_t> cp16, cq16, loc16;
         auto align4 = [](int32_t x) { return (x + 3) & ~3; };
         auto bytes_needed = [&](int32_t nl, int32_t nk, int32_t npad) {
-            return kRecHeader + 4 * nl + 4 * nk + 2 * align4(2 * (nk + 1)) + npad * S;
+            (void)nl;    // the link table has a fixed size
+            return kRecTable + kRecHeader + 4 * nk + 2 * align4(2 * (nk + 1)) + npad * S;
         };
         // lanes per commodity in the record kernel: a lane scans two quads of the largest
         // commodity; a record holds as many commodities as one round of the wave covers
@@ -807,7 +808,7 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
             }
             t.records.resize(static_cast<size_t>(t.n_records + 1) * kRecBytes, 0);
             uint8_t *r = t.records.data() + static_cast<size_t>(t.n_records) * kRecBytes;
-            const int32_t off_sig = kRecHeader + 4 * nl;
+            const int32_t off_sig = kRecHeader;      // body offsets count from kRecTable
             const int32_t off_cp = off_sig + 4 * nk;
             const int32_t off_cq = off_cp + align4(2 * (nk + 1));
             const int32_t off_loc = off_cq + align4(2 * (nk + 1));
@@ -817,13 +818,22 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                                      static_cast<uint16_t>(off_sig),
                                      static_cast<uint16_t>(off_cq),
                                      static_cast<uint16_t>(npad)};
-            std::memcpy(r + 0, &k0, 4);
-            std::memcpy(r + 4, &p0, 4);
-            std::memcpy(r + 8, h16, 16);
-            std::memcpy(r + kRecHeader, links.data(), 4 * static_cast<size_t>(nl));
-            std::memcpy(r + off_sig, t.sigma.data() + k0, 4 * static_cast<size_t>(nk));
-            std::memcpy(r + off_cp, cp16.data(), 2 * cp16.size());
-            std::memcpy(r + off_cq, cq16.data(), 2 * cq16.size());
+            // gather c of lane l reads table entry 4*l + c, which is link 64*c + l
+            {
+                int32_t *tab = reinterpret_cast<int32_t *>(r);
+                for (int32_t l = 0; l < 64; ++l)
+                    for (int32_t c = 0; c < 4; ++c) {
+                        const int32_t i = 64 * c + l;
+                        tab[4 * l + c] = nl == 0 ? 0 : links[i < nl ? i : nl - 1];
+                    }
+            }
+            uint8_t *body = r + kRecTable;
+            std::memcpy(body + 0, &k0, 4);
+            std::memcpy(body + 4, &p0, 4);
+            std::memcpy(body + 8, h16, 16);
+            std::memcpy(body + off_sig, t.sigma.data() + k0, 4 * static_cast<size_t>(nk));
+            std::memcpy(body + off_cp, cp16.data(), 2 * cp16.size());
+            std::memcpy(body + off_cq, cq16.data(), 2 * cq16.size());
             // step-major over the padded candidates: index i of every candidate, then index
             // i+1, ...; four consecutive candidates (a quad) are one aligned 32-bit word
             {
@@ -832,7 +842,7 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                     for (int32_t i = 0; i < S; ++i)
                         soa[static_cast<size_t>(i) * npad + p] =
                             static_cast<uint8_t>(loc16[static_cast<size_t>(p) * S + i]);
-                std::memcpy(r + off_loc, soa.data(), soa.size());
+                std::memcpy(body + off_loc, soa.data(), soa.size());
             }
             t.n_records += 1;
             if (nl > t.rec_max_links) t.rec_max_links = nl;
@@ -908,7 +918,8 @@ extern "C" nimble_status_t nimble_host_records_roundtrip(int32_t n_links, int32_
     int64_t w = 0;
     int32_t next_comm = 0;
     for (int32_t ri = 0; ri < t.n_records; ++ri) {
-        const uint8_t *r = t.records.data() + static_cast<size_t>(ri) * nimble::kRecBytes;
+        const uint8_t *rec = t.records.data() + static_cast<size_t>(ri) * nimble::kRecBytes;
+        const uint8_t *r = rec + nimble::kRecTable;       // the body
         int32_t k0, p0;
         uint16_t h16[8];
         std::memcpy(&k0, r, 4);
@@ -918,7 +929,10 @@ extern "C" nimble_status_t nimble_host_records_roundtrip(int32_t n_links, int32_
         const int32_t off_cq = h16[6], npad = h16[7];
         if (k0 != next_comm || p0 != comm_path_ptr[k0]) return NIMBLE_ERR_INVALID;
         next_comm = k0 + nk;
-        const int32_t *links = reinterpret_cast<const int32_t *>(r + nimble::kRecHeader);
+        const int32_t *tab = reinterpret_cast<const int32_t *>(rec);
+        auto link_at = [&](int32_t i) { return tab[4 * (i % 64) + i / 64]; };
+        for (int32_t i = nl; i < 256; ++i)      // the fill repeats the last link
+            if (link_at(i) != (nl == 0 ? 0 : link_at(nl - 1))) return NIMBLE_ERR_INVALID;
         const uint16_t *cp16 = reinterpret_cast<const uint16_t *>(r + off_cp);
         const uint16_t *cq16 = reinterpret_cast<const uint16_t *>(r + off_cq);
         if (cq16[nk] != npad || npad % 4) return NIMBLE_ERR_INVALID;
@@ -934,7 +948,7 @@ extern "C" nimble_status_t nimble_host_records_roundtrip(int32_t n_links, int32_
                     const int32_t li = loc16[i * npad + pq];
                     if (li == nl) continue;
                     if (li > nl) return NIMBLE_ERR_INVALID;
-                    links_out[w++] = links[li];
+                    links_out[w++] = link_at(li);
                 }
             }
         }

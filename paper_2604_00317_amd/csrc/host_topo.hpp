@@ -104,11 +104,14 @@ constexpr int32_t kBlkMaxLinks = 512;
 // exactly `stride` 8-bit indices into the record's link table.  Paths shorter than the stride
 // are padded with the index n_links, whose price slot holds +0.0 (neutral for sum and for max
 // of positive prices); the candidates that pad a commodity to a multiple of 4 start with the
-// index n_links + 1, whose price slot holds +inf, so their cost is +inf.  Layout, offsets in bytes from the start of the record:
+// index n_links + 1, whose price slot holds +inf, so their cost is +inf.  The link table comes
+// first and always fills kRecTable bytes, stored the way the wave gathers it: 16-byte load l
+// holds the links 0*64+l, 1*64+l, 2*64+l, 3*64+l of the table (ascending link ids), entries
+// past n_links repeating the last link, so every entry is a valid link id and the gathers need
+// nothing but the table.  The body follows; its offsets count from kRecTable:
 //   0   int32 k0        first commodity
 //   4   int32 p0        first candidate path (global id)
 //   8   uint16 nk, np, n_links, off_cp, off_loc, off_sig, off_cq, npad
-//   24  int32 links[n_links]
 //   off_sig  int32 sigma[nk]      second numbering of the commodity (-1: none)
 //   off_cp   uint16 cp16[nk+1]    first candidate of commodity i, relative to p0
 //   off_cq   uint16 cq16[nk+1]    the same with every commodity padded to a multiple of 4
@@ -118,7 +121,9 @@ constexpr int32_t kBlkMaxLinks = 512;
 #define NIMBLE_REC_KB 4
 #endif
 constexpr int32_t kRecBytes = 1024 * NIMBLE_REC_KB;   // one 16-byte load per lane and KiB
+constexpr int32_t kRecTable = 1024;       // bytes of the link table: 4 gathers x 64 lanes
 constexpr int32_t kRecHeader = 24;
+constexpr int32_t kRecPriceSlots = 256;   // price slots a wave keeps per record
 constexpr int32_t kRecMaxLinks = 254;     // link table entries (8-bit indices); slots n_links and
                                           // n_links + 1 hold +0.0 and +inf
 constexpr int32_t kRecMaxStride = 8;      // longest path a record can hold

@@ -83,11 +83,11 @@ __global__ __launch_bounds__(kBlock) void k_argmin(int K, const int32_t *__restr
                                 n_waves, lane);
 }
 
-// Record path-cost gather + argmin: one wave (a 64-thread workgroup) per 4 KiB record of the
-// forward CSR.  The wave copies its record into LDS with four 16-byte loads per lane, gathers
-// the prices of the record's link table (the only access that leaves the record), and then L
-// lanes per commodity add S prices per candidate (8-bit table indices) from LDS in CSR order -- padding slots read
-// +0.0 -- and reduce (cost, index) across the group.  The sums are the same IEEE operations in
+// Record path-cost gather + argmin: one wave per 4 KiB record of the forward CSR.  The wave
+// gathers the prices of the record's link table (the only access that leaves the record)
+// into LDS, copies the body of the record into LDS with three 16-byte loads per lane, and
+// then L lanes per commodity add S prices per candidate (8-bit table indices) from LDS in CSR
+// order -- padding slots read +0.0 -- and reduce (cost, index) across the group.  The sums are the same IEEE operations in
 // the same order as in the untiled kernel.
 constexpr int kRecWaves = 4;     // independent waves per workgroup
 
@@ -101,73 +101,84 @@ __device__ __forceinline__ void wave_lds_sync()
 }
 
 template <int L, int S, bool MAXC>
-__global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records, int lds_per_wave,
+__global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records,
                                                       const uint8_t *__restrict__ records,
                                                       const double *__restrict__ price,
                                                       uint8_t *__restrict__ choice,
                                                       uint32_t *__restrict__ count,
                                                       uint8_t *__restrict__ choice2)
 {
-    // dynamic LDS, one private slice per wave: the record (kRecBytes) followed by the price
-    // table, sized by the launcher for the largest link table of the topology.  The waves of a
-    // workgroup never synchronise with each other.
-    extern __shared__ __align__(16) uint8_t s_all[];
-    uint8_t *s_rec = s_all + (threadIdx.x >> 6) * lds_per_wave;
-    double *s_price = reinterpret_cast<double *>(s_rec + kRecBytes);
+    // LDS, one private slice per wave: the body of the record (everything after the link
+    // table) followed by the price table.  The waves of a workgroup never synchronise with
+    // each other.
+    constexpr int kBody = kRecBytes - kRecTable;
+    __shared__ __align__(16) uint8_t s_all[kRecWaves * (kBody + 8 * kRecPriceSlots)];
+    uint8_t *s_rec = s_all + (threadIdx.x >> 6) * (kBody + 8 * kRecPriceSlots);
+    double *s_price = reinterpret_cast<double *>(s_rec + kBody);
     constexpr int kGroups = kWave / L;
-    constexpr int kLoads = kRecBytes / 1024;
+    constexpr int kLoads = kBody / 1024;
     const int lane = threadIdx.x & (kWave - 1);
     const int g = lane / L;
     const int j = lane % L;
     const int n_waves = gridDim.x * kRecWaves;
     int rec = blockIdx.x * kRecWaves + (threadIdx.x >> 6);
     if (rec >= n_records) return;                       // wave-uniform
-    // one 16-byte load per lane and KiB of record, all requested at once
-    u32x4 v[kLoads];
+    // Three requests are kept in flight per wave, each issued one record ahead of its use: the
+    // link table of the record after the next (one 16-byte load per lane), the prices of the
+    // next record's links (four gathers per lane, addressed straight from the table registers:
+    // the table is stored so that gather c of lane l is link 64c + l), and the body of the
+    // next record.  A record index past the end re-reads the wave's last record.
+    auto table_of = [&](int r) {
+        r = r < n_records ? r : rec;
+        return stream_load(reinterpret_cast<const u32x4 *>(records + size_t(r) * kRecBytes) +
+                           lane);
+    };
+    u32x4 tab = table_of(rec);
+    u32x4 body[kLoads];
+    double pr[4];
+    pr[0] = price[tab.x];
+    pr[1] = price[tab.y];
+    pr[2] = price[tab.z];
+    pr[3] = price[tab.w];
+    tab = table_of(rec + n_waves);
     {
-        const u32x4 *src = reinterpret_cast<const u32x4 *>(records + size_t(rec) * kRecBytes);
+        const u32x4 *src =
+            reinterpret_cast<const u32x4 *>(records + size_t(rec) * kRecBytes + kRecTable);
 #pragma unroll
-        for (int it = 0; it < kLoads; ++it) v[it] = stream_load(src + it * kWave + lane);
+        for (int it = 0; it < kLoads; ++it) body[it] = stream_load(src + it * kWave + lane);
     }
     for (; rec < n_records; rec += n_waves) {           // wave-uniform
         wave_lds_sync();                                // the previous record is done with LDS
 #pragma unroll
         for (int it = 0; it < kLoads; ++it)
-            reinterpret_cast<u32x4 *>(s_rec)[it * kWave + lane] = v[it];
+            reinterpret_cast<u32x4 *>(s_rec)[it * kWave + lane] = body[it];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) s_price[lane + q * kWave] = pr[q];
         wave_lds_sync();
         const int k0 = *reinterpret_cast<const int32_t *>(s_rec);
         const int p0 = *reinterpret_cast<const int32_t *>(s_rec + 4);
         const uint16_t *h16 = reinterpret_cast<const uint16_t *>(s_rec + 8);
         const int nk = h16[0], nl = h16[2], npad_rec = h16[7];
-        const int32_t *links = reinterpret_cast<const int32_t *>(s_rec + kRecHeader);
         const uint16_t *cp16 = reinterpret_cast<const uint16_t *>(s_rec + h16[3]);
         const uint8_t *loc8 = s_rec + h16[4];
         const int32_t *sig = reinterpret_cast<const int32_t *>(s_rec + h16[5]);
         const uint16_t *cq16 = reinterpret_cast<const uint16_t *>(s_rec + h16[6]);
-        // prices of the link table: always four gathers per lane (entries past the table
-        // re-read its last link), so that the record prefetch below, issued after them, can
-        // stay in flight while the gathers are consumed
-        double pr[4];
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int i = lane + q * kWave;
-            pr[q] = price[links[i < nl ? i : nl - 1]];
-        }
-        // the next record of this wave (the last one re-reads itself)
-        {
-            const int nxt = rec + n_waves < n_records ? rec + n_waves : rec;
-            const u32x4 *src = reinterpret_cast<const u32x4 *>(records + size_t(nxt) * kRecBytes);
-#pragma unroll
-            for (int it = 0; it < kLoads; ++it) v[it] = stream_load(src + it * kWave + lane);
-        }
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int i = lane + q * kWave;
-            if (i < nl) s_price[i] = pr[q];
-        }
-        if (lane == 0) {
+        if (lane == 0) {                             // after the table prices, in LDS order
             s_price[nl] = 0.0;                       // pads short paths
             s_price[nl + 1] = __builtin_inf();       // first step of padding candidates
+        }
+        // the next record: its prices, its body, and the table of the one after it
+        {
+            pr[0] = price[tab.x];
+            pr[1] = price[tab.y];
+            pr[2] = price[tab.z];
+            pr[3] = price[tab.w];
+            tab = table_of(rec + 2 * n_waves);
+            const int nxt = rec + n_waves < n_records ? rec + n_waves : rec;
+            const u32x4 *src =
+                reinterpret_cast<const u32x4 *>(records + size_t(nxt) * kRecBytes + kRecTable);
+#pragma unroll
+            for (int it = 0; it < kLoads; ++it) body[it] = stream_load(src + it * kWave + lane);
         }
         wave_lds_sync();
         const int rounds = (nk + kGroups - 1) / kGroups;
@@ -467,7 +478,6 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, uint8_t *choice, uint32_t
                         hipStream_t s)
 {
     if (t.n_records > 0) {
-        const int rec_lds = (kRecBytes + 8 * (t.rec_max_links + 2) + 15) & ~15;
         // records per wave: up to four (the next one is prefetched while one is scanned) once
         // there are more records than wave slots
         int rpw = (t.n_records + 4095) / 4096;
@@ -478,8 +488,8 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, uint8_t *choice, uint32_t
     case SS:                                                                                   \
         hipLaunchKernelGGL((k_argmin_rec<L, SS, MAXC>),                                        \
                            dim3(rec_grid),                                                     \
-                           dim3(kWave * kRecWaves), kRecWaves * rec_lds, s, t.n_records,       \
-                           rec_lds, t.records, t.price, choice, count, t.choice2);             \
+                           dim3(kWave * kRecWaves), 0, s, t.n_records, t.records, t.price,     \
+                           choice, count, t.choice2);                                          \
         return;
         switch (t.rec_stride) {
             NIMBLE_REC_LAUNCH(1)

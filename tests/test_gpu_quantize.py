@@ -72,6 +72,30 @@ def test_random_counts_many_candidates(oracle_mod, B, seed):
         assert np.array_equal(got, ref)
 
 
+@pytest.mark.parametrize("max_paths", [2, 3, 7, 12, 16, 25, 33, 64, 65])
+@pytest.mark.parametrize("iters", [12, 1 << 25])
+def test_every_group_width_with_ties(oracle_mod, B, max_paths, iters):
+    """One lane group per pair for up to 64 candidates (group widths 2..64), one thread per pair
+    beyond; few distinct counts, so equal remainders are broken by index; the large iteration
+    count takes the 64-bit rank keys."""
+    rng = np.random.default_rng(100 + max_paths)
+    t = W.random_topology(rng, 40, 150, max_paths, 2)
+    cp = t.comm_path_ptr
+    assert int(np.diff(cp).max()) == max_paths
+    splits = np.zeros(t.n_paths)
+    unit = iters // 12
+    for k in range(t.n_comm):
+        n = cp[k + 1] - cp[k]
+        c = rng.multinomial(12, np.ones(n) / n) * unit
+        c[0] += iters - c.sum()
+        splits[cp[k]:cp[k + 1]] = c / iters
+    d = rng.integers(0, 1 << 30, size=t.n_comm).astype(np.float64)
+    for chi in (1, 4096):
+        ref = oracle_mod.quantize(cp, d, splits, iters, chi, 0.0)
+        got = gpu_quantize(B, t, d, splits, iters, chi, 0.0)
+        assert np.array_equal(got, ref)
+
+
 def test_too_many_chunks_is_flagged_and_bad_arguments_are_refused(B):
     import torch
     w = W.make_config(0)
