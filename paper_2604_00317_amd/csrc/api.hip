@@ -259,7 +259,14 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     d.n_schunks = static_cast<int32_t>(h.schunk_begin.size());
     d.n_slots = h.n_slots;
     d.cost_max = (flags & NIMBLE_COST_MAX) != 0u;
-    d.n_update_blocks = (h.E + 15) / 16;   // 256-thread blocks, one 16-lane row per link
+    // 256-thread blocks; a link gets 16 lanes for its slot partials, or 4 when links have few
+    // slots (tiled layouts)
+    d.update_lanes = (static_cast<int64_t>(h.n_slots) <= 6LL * h.E) ? 4 : 16;
+    if (const char *v = std::getenv("NIMBLE_TUNE_UPDATE_LANES")) {
+        const int x = std::atoi(v);
+        if (x == 4 || x == 16) d.update_lanes = x;
+    }
+    d.n_update_blocks = (h.E + 256 / d.update_lanes - 1) / (256 / d.update_lanes);
     d.n_blocks = std::getenv("NIMBLE_TUNE_NO_LINK_BLOCKS") ? 0 : h.n_blocks;
 
 #define NIMBLE_TRY(call, what)                        \

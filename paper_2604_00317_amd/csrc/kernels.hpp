@@ -77,6 +77,7 @@ struct DeviceTopo {
     double *partial;           // [n_slots]
     double *scalars;           // [0] = 1/rho, [1..] = per-block maxima of S (update or link blocks)
     int32_t n_update_blocks;
+    int32_t update_lanes;      // lanes per link in the length update: 4 or 16
     int32_t reduce_blocks;     // 256-thread blocks of the link-load reduce (fills the chip once)
 };
 

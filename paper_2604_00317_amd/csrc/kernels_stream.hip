@@ -422,7 +422,7 @@ __global__ __launch_bounds__(kBlock) void k_width_fold(int n_blocks, double *__r
 }
 
 // length update fused with the per-block maximum of the congestion sums (lambda = max / iters)
-template <bool MAXC>
+template <bool MAXC, int RL>
 __global__ __launch_bounds__(kBlock) void k_update(int E, double eps,
                                                    const int32_t *__restrict__ pos_link,
                                                    const int32_t *__restrict__ pos_slot_ptr,
@@ -438,8 +438,9 @@ __global__ __launch_bounds__(kBlock) void k_update(int E, double eps,
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
-    const double s_new = update_phase<MAXC>(E, eps, scalars[0], pos_link, pos_slot_ptr, pos_xslot,
-                                            partial, invcap, len, price, S, wave, n_waves, lane);
+    const double s_new = update_phase<MAXC, RL>(E, eps, scalars[0], pos_link, pos_slot_ptr,
+                                                pos_xslot, partial, invcap, len, price, S, wave,
+                                                n_waves, lane);
     const double m = block_max(s_new, red);
     if (threadIdx.x == 0) scalars[1 + blockIdx.x] = m;
 }
@@ -652,14 +653,18 @@ void launch_histogram(const DeviceTopo &t, const uint8_t *log, size_t stride, in
 
 void launch_update(const DeviceTopo &t, double eps, hipStream_t s)
 {
-    if (t.cost_max)
-        hipLaunchKernelGGL(k_update<true>, dim3(t.n_update_blocks), dim3(kBlock), 0, s, t.E, eps,
-                           t.pos_link, t.pos_slot_ptr, t.pos_xslot, t.partial, t.invcap_pos, t.len, t.price,
-                           t.S, t.scalars);
-    else
-        hipLaunchKernelGGL(k_update<false>, dim3(t.n_update_blocks), dim3(kBlock), 0, s, t.E, eps,
-                           t.pos_link, t.pos_slot_ptr, t.pos_xslot, t.partial, t.invcap_pos, t.len, t.price,
-                           t.S, t.scalars);
+#define NIMBLE_UPDATE_LAUNCH(MC, RL)                                                           \
+    hipLaunchKernelGGL((k_update<MC, RL>), dim3(t.n_update_blocks), dim3(kBlock), 0, s, t.E,   \
+                       eps, t.pos_link, t.pos_slot_ptr, t.pos_xslot, t.partial, t.invcap_pos,  \
+                       t.len, t.price, t.S, t.scalars)
+    if (t.update_lanes == 4) {
+        if (t.cost_max) NIMBLE_UPDATE_LAUNCH(true, 4);
+        else NIMBLE_UPDATE_LAUNCH(false, 4);
+    } else {
+        if (t.cost_max) NIMBLE_UPDATE_LAUNCH(true, 16);
+        else NIMBLE_UPDATE_LAUNCH(false, 16);
+    }
+#undef NIMBLE_UPDATE_LAUNCH
 }
 
 void launch_reduce_update(const DeviceTopo &t, const uint8_t *choice, const double *demand,

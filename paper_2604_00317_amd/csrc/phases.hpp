@@ -510,19 +510,22 @@ __device__ __forceinline__ void reduce_strip_phase(
 // step), add their own in ascending slot order, and a fixed butterfly combines the 16 lane
 // sums; lane 0 of the row then applies  S_e += u_e,  len_e *= 1 + eps*u_e/rho,  price_e.
 // Returns, in lane 0 of every row, the new S_e (0 elsewhere) for the lambda max-reduce.
+// Links with few slots (tiled layouts: two or three per link) are better served by 4 lanes
+// each, which quarters the threads of the update; RL is the number of lanes per link.
+template <int RL = kRowLanes>
 __device__ __forceinline__ double row_partial_sum(int c0, int c1, int l,
                                                   const double *__restrict__ partial)
 {
     double acc = 0.0;
-    for (int c = c0 + l; c < c1; c += kRowLanes) acc = acc + partial[c];
+    for (int c = c0 + l; c < c1; c += RL) acc = acc + partial[c];
     acc = acc + partner_f64<1>(acc);
     acc = acc + partner_f64<2>(acc);
-    acc = acc + partner_f64<4>(acc);
-    acc = acc + partner_f64<8>(acc);
+    if constexpr (RL > 4) acc = acc + partner_f64<4>(acc);
+    if constexpr (RL > 8) acc = acc + partner_f64<8>(acc);
     return acc;
 }
 
-template <bool MAXC>
+template <bool MAXC, int RL = kRowLanes>
 __device__ __forceinline__ double update_phase(int E, double eps, double invrho,
                                                const int32_t *__restrict__ pos_link,
                                                const int32_t *__restrict__ pos_slot_ptr,
@@ -535,10 +538,12 @@ __device__ __forceinline__ double update_phase(int E, double eps, double invrho,
 {
     // invcap_pos, len and S are stored in the flat order of the rows (by position); only the
     // price array, which the candidate scan gathers from, is indexed by link id
-    const int row = lane / kRowLanes;
-    const int l = lane % kRowLanes;
+    static_assert(RL == 4 || RL == 16, "4 or 16 lanes per link");
+    constexpr int kRows = kWave / RL;
+    const int row = lane / RL;
+    const int l = lane % RL;
     double smax = 0.0;
-    for (int ibase = wave * kRowsPerWave; ibase < E; ibase += n_waves * kRowsPerWave) {
+    for (int ibase = wave * kRows; ibase < E; ibase += n_waves * kRows) {
         const int i = ibase + row;          // position in the flat order of the rows
         int e = 0, c0 = 0, c1 = 0, s0 = 0, s1 = 0;
         if (i < E) {
@@ -557,7 +562,7 @@ __device__ __forceinline__ double update_phase(int E, double eps, double invrho,
             l_old = len[i];
         }
         // octet slots, then (rarely any) single-pair slots
-        const double load = row_partial_sum(c0, c1, l, partial) + row_partial_sum(s0, s1, l, partial);
+        const double load = row_partial_sum<RL>(c0, c1, l, partial) + row_partial_sum<RL>(s0, s1, l, partial);
         if (i < E && l == 0) {
             const double u = load * ic;
             const double s_new = s_old + u;
