@@ -100,7 +100,7 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-template <int L, int S, bool MAXC>
+template <int L, int S, bool MAXC, bool TWO>
 __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records,
                                                       const uint8_t *__restrict__ records,
                                                       const double *__restrict__ price,
@@ -121,15 +121,17 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records,
     const int g = lane / L;
     const int j = lane % L;
     const int n_waves = gridDim.x * kRecWaves;
-    int rec = blockIdx.x * kRecWaves + (threadIdx.x >> 6);
-    if (rec >= n_records) return;                       // wave-uniform
+    // the record index is the same in all lanes; in a scalar register the tests on it below
+    // are scalar branches
+    int rec = __builtin_amdgcn_readfirstlane(blockIdx.x * kRecWaves + (threadIdx.x >> 6));
+    if (rec >= n_records) return;
     // Three requests are kept in flight per wave, each issued one record ahead of its use: the
     // link table of the record after the next (one 16-byte load per lane), the prices of the
     // next record's links (four gathers per lane, addressed straight from the table registers:
     // the table is stored so that gather c of lane l is link 64c + l), and the body of the
-    // next record.  A record index past the end re-reads the wave's last record.
+    // next record.  Past the wave's last record nothing is requested: the records are
+    // streamed past the L2, so a redundant request would cost HBM bandwidth like a real one.
     auto table_of = [&](int r) {
-        r = r < n_records ? r : rec;
         return stream_load(reinterpret_cast<const u32x4 *>(records + size_t(r) * kRecBytes) +
                            lane);
     };
@@ -140,7 +142,7 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records,
     pr[1] = price[tab.y];
     pr[2] = price[tab.z];
     pr[3] = price[tab.w];
-    tab = table_of(rec + n_waves);
+    if (rec + n_waves < n_records) tab = table_of(rec + n_waves);
     {
         const u32x4 *src =
             reinterpret_cast<const u32x4 *>(records + size_t(rec) * kRecBytes + kRecTable);
@@ -168,54 +170,90 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records,
             s_price[nl + 1] = __builtin_inf();       // first step of padding candidates
         }
         // the next record: its prices, its body, and the table of the one after it
-        {
+        if (rec + n_waves < n_records) {
             pr[0] = price[tab.x];
             pr[1] = price[tab.y];
             pr[2] = price[tab.z];
             pr[3] = price[tab.w];
-            tab = table_of(rec + 2 * n_waves);
-            const int nxt = rec + n_waves < n_records ? rec + n_waves : rec;
-            const u32x4 *src =
-                reinterpret_cast<const u32x4 *>(records + size_t(nxt) * kRecBytes + kRecTable);
+            if (rec + 2 * n_waves < n_records) tab = table_of(rec + 2 * n_waves);
+            const u32x4 *src = reinterpret_cast<const u32x4 *>(
+                records + size_t(rec + n_waves) * kRecBytes + kRecTable);
 #pragma unroll
             for (int it = 0; it < kLoads; ++it) body[it] = stream_load(src + it * kWave + lane);
         }
         wave_lds_sync();
+        // cost of the four candidates of one quad: the S table indices of four consecutive
+        // candidates come as S aligned 32-bit words; returns the minimum of the quad (padding
+        // candidates cost +inf) and the lowest candidate that holds it
+        auto scan_quad = [&](const uint32_t (&w)[S], double &m4, int &i4) {
+            double cst[4];
+#pragma unroll
+            for (int c4 = 0; c4 < 4; ++c4) {
+                // 0 + p0 is p0: the sum starts at the first price
+                cst[c4] = s_price[(w[0] >> (8 * c4)) & 0xFFu];
+#pragma unroll
+                for (int i = 1; i < S; ++i) {
+                    const double pe = s_price[(w[i] >> (8 * c4)) & 0xFFu];
+                    if constexpr (MAXC) cst[c4] = (pe > cst[c4]) ? pe : cst[c4];
+                    else cst[c4] = cst[c4] + pe;
+                }
+            }
+            m4 = fast_min_f64(fast_min_f64(cst[0], cst[1]), fast_min_f64(cst[2], cst[3]));
+            i4 = cst[0] == m4 ? 0 : (cst[1] == m4 ? 1 : (cst[2] == m4 ? 2 : 3));
+        };
+        const int wstride = npad_rec >> 2;
         const int rounds = (nk + kGroups - 1) / kGroups;
         for (int r = 0; r < rounds; ++r) {        // wave-uniform: all lanes reach the reduction
             const int c = r * kGroups + g;
             double best = __builtin_inf();
             int bj = 0x7FFFFFFF;
-            int p_lo = 0;
+            int p_lo = 0, np = 0, q_lo = 0;
             if (c < nk) {
                 p_lo = cp16[c];
-                const int np = cp16[c + 1] - p_lo;
-                const int q_lo = cq16[c];
+                np = cp16[c + 1] - p_lo;
+                q_lo = cq16[c];
+            }
+            if constexpr (TWO) {
+                // no commodity has more than 8 L candidates: lane j scans the quads j and
+                // j + L.  Both are fetched unconditionally (a quad that does not exist re-reads
+                // the commodity's first one and is dropped), so the index words and the prices
+                // of the two quads are in flight together.
+                const int ja = 4 * j, jb = 4 * j + 4 * L;
+                const bool va = ja < np, vb = jb < np;
+                const uint32_t *lpa =
+                    reinterpret_cast<const uint32_t *>(loc8 + q_lo + (va ? ja : 0));
+                const uint32_t *lpb =
+                    reinterpret_cast<const uint32_t *>(loc8 + q_lo + (vb ? jb : 0));
+                uint32_t wa[S], wb[S];
+#pragma unroll
+                for (int i = 0; i < S; ++i) {
+                    wa[i] = lpa[i * wstride];
+                    wb[i] = lpb[i * wstride];
+                }
+                double ma, mb;
+                int ia, ib;
+                scan_quad(wa, ma, ia);
+                scan_quad(wb, mb, ib);
+                if (va) bj = ja;
+                if (va && ma < best) {
+                    best = ma;
+                    bj = ja + ia;
+                }
+                if (vb && mb < best) {
+                    best = mb;
+                    bj = jb + ib;
+                }
+            } else {
                 if (4 * j < np) bj = 4 * j;
-                // lane j scans the quads j, j+L, ... of the commodity: the S table indices of
-                // four consecutive candidates come as S aligned 32-bit words
+                // lane j scans the quads j, j+L, ... of the commodity
                 for (int jq = 4 * j; jq < np; jq += 4 * L) {
                     const uint32_t *lp = reinterpret_cast<const uint32_t *>(loc8 + q_lo + jq);
                     uint32_t w[S];
 #pragma unroll
-                    for (int i = 0; i < S; ++i) w[i] = lp[i * (npad_rec >> 2)];
-                    double cst[4];
-#pragma unroll
-                    for (int c4 = 0; c4 < 4; ++c4) {
-                        // 0 + p0 is p0: the sum starts at the first price
-                        cst[c4] = s_price[(w[0] >> (8 * c4)) & 0xFFu];
-#pragma unroll
-                        for (int i = 1; i < S; ++i) {
-                            const double pe = s_price[(w[i] >> (8 * c4)) & 0xFFu];
-                            if constexpr (MAXC) cst[c4] = (pe > cst[c4]) ? pe : cst[c4];
-                            else cst[c4] = cst[c4] + pe;
-                        }
-                    }
-                    // minimum of the quad (padding candidates cost +inf), then the lowest
-                    // candidate that holds it
-                    const double m4 = fast_min_f64(fast_min_f64(cst[0], cst[1]),
-                                                   fast_min_f64(cst[2], cst[3]));
-                    const int i4 = cst[0] == m4 ? 0 : (cst[1] == m4 ? 1 : (cst[2] == m4 ? 2 : 3));
+                    for (int i = 0; i < S; ++i) w[i] = lp[i * wstride];
+                    double m4;
+                    int i4;
+                    scan_quad(w, m4, i4);
                     if (m4 < best) {
                         best = m4;
                         bj = jq + i4;
@@ -485,12 +523,18 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, uint8_t *choice, uint32_t
         if (rpw > 4) rpw = 4;
         if (t.rec_per_wave > 0) rpw = t.rec_per_wave;
         const int rec_grid = (t.n_records + kRecWaves * rpw - 1) / (kRecWaves * rpw);
+        // two quads per lane cover every commodity (the layout's own choice of L does)
+        const bool two = (t.pmax + 3) / 4 <= 2 * L;
 #define NIMBLE_REC_LAUNCH(SS)                                                                  \
     case SS:                                                                                   \
-        hipLaunchKernelGGL((k_argmin_rec<L, SS, MAXC>),                                        \
-                           dim3(rec_grid),                                                     \
-                           dim3(kWave * kRecWaves), 0, s, t.n_records, t.records, t.price,     \
-                           choice, count, t.choice2);                                          \
+        if (two)                                                                               \
+            hipLaunchKernelGGL((k_argmin_rec<L, SS, MAXC, true>), dim3(rec_grid),              \
+                               dim3(kWave * kRecWaves), 0, s, t.n_records, t.records, t.price, \
+                               choice, count, t.choice2);                                      \
+        else                                                                                   \
+            hipLaunchKernelGGL((k_argmin_rec<L, SS, MAXC, false>), dim3(rec_grid),             \
+                               dim3(kWave * kRecWaves), 0, s, t.n_records, t.records, t.price, \
+                               choice, count, t.choice2);                                      \
         return;
         switch (t.rec_stride) {
             NIMBLE_REC_LAUNCH(1)
