@@ -249,6 +249,12 @@ int64_t nimble_topo_phase_bytes(const nimble_topo_t *topo, int32_t phase);
 nimble_status_t nimble_topo_set_regime(nimble_topo_t *topo, int32_t regime);
 int32_t nimble_topo_regime(const nimble_topo_t *topo);
 
+/* 1 if the resident regime would run this topology with one commodity and one link per thread,
+ * their candidate lists and reverse rows held in registers (at most 8 candidates of at most 2
+ * links per commodity, at most 16 (commodity, mask) pairs per link); 0 if it keeps everything
+ * in LDS; -1 for a NULL handle.  Both kernels return the same bits. */
+int32_t nimble_topo_resident_in_registers(const nimble_topo_t *topo);
+
 /*
  * Benchmark helper: enqueue `reps` back-to-back launches of one phase of the streaming regime
  * on `hip_stream`, without changing the plan state another solve depends on

@@ -30,7 +30,7 @@ EXPORTS = [
     "nimble_alg1_solve_batch", "nimble_plan_quantize", "nimble_plan_solve_warm",
     "nimble_plan_solve_adaptive",
     "nimble_host_records_roundtrip", "nimble_host_layout_stats",
-    "nimble_host_build_reverse_streaming",
+    "nimble_host_build_reverse_streaming", "nimble_topo_resident_in_registers",
 ]
 
 _lib = None
@@ -66,7 +66,7 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.nimble_last_error.restype = ctypes.c_char_p
     lib.nimble_last_error.argtypes = []
     for name in ("nimble_topo_num_links", "nimble_topo_num_comm", "nimble_topo_num_paths",
-                 "nimble_topo_regime"):
+                 "nimble_topo_regime", "nimble_topo_resident_in_registers"):
         getattr(lib, name).restype = i32
         getattr(lib, name).argtypes = [vp]
     for name in ("nimble_topo_nnz", "nimble_topo_bytes_per_iter"):
@@ -166,6 +166,10 @@ class Topo:
     @property
     def regime(self) -> int:
         return load_library().nimble_topo_regime(self.handle)
+
+    @property
+    def resident_in_registers(self) -> bool:
+        return load_library().nimble_topo_resident_in_registers(self.handle) == 1
 
     def close(self) -> None:
         if self.handle is not None and self.handle.value:

@@ -241,6 +241,9 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     d.P = h.P;
     d.nnz = h.nnz;
     d.rev_pairs = static_cast<int64_t>(h.rev_pair.size() / 2);
+    d.rev_row_max = 0;
+    for (int32_t len : h.rev_rowlen) d.rev_row_max = std::max(d.rev_row_max, len);
+    d.resident_generic = std::getenv("NIMBLE_TUNE_RESIDENT_GENERIC") ? 1 : 0;
     d.n_records = h.n_records;
     d.rec_stride = h.rec_stride;
     d.rec_max_links = h.rec_max_links;
@@ -414,6 +417,10 @@ int32_t nimble_topo_num_paths(const nimble_topo_t *t) { return t ? t->d.P : -1; 
 int64_t nimble_topo_nnz(const nimble_topo_t *t) { return t ? t->d.nnz : -1; }
 int64_t nimble_topo_bytes_per_iter(const nimble_topo_t *t) { return t ? t->bytes_per_iter : -1; }
 int32_t nimble_topo_regime(const nimble_topo_t *t) { return t ? t->last_regime : -1; }
+int32_t nimble_topo_resident_in_registers(const nimble_topo_t *t)
+{
+    return t ? (nimble::resident_in_registers(t->d) ? 1 : 0) : -1;
+}
 
 int64_t nimble_topo_phase_bytes(const nimble_topo_t *t, int32_t phase)
 {

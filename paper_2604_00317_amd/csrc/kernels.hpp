@@ -25,6 +25,8 @@ struct DeviceTopo {
     const uint8_t *records;
     // reverse CSR of 8-byte (commodity, window | mask) pairs, rows padded to 2 pairs
     int64_t rev_pairs;         // padded number of pairs
+    int32_t rev_row_max;       // longest reverse row in pairs (without padding)
+    int32_t resident_generic;  // 1: the resident regime keeps to its LDS-only kernel
     const int32_t *rev_ptr;    // [E+1], in pairs
     const uint32_t *rev_pair;  // [2 * rev_pairs]
     // streaming layout of the reverse rows: one flat array of octets (base id | flags, 8
@@ -109,6 +111,7 @@ void launch_epilogue(const DeviceTopo &t, int32_t iters, const uint32_t *count, 
 size_t resident_state_bytes(const DeviceTopo &t);
 size_t resident_topo_bytes(const DeviceTopo &t);
 bool resident_fits(const DeviceTopo &t);
+bool resident_in_registers(const DeviceTopo &t);   // the resident regime keeps the topology in registers
 hipError_t launch_resident(const DeviceTopo &t, int32_t batch, const double *demand, double eps,
                            int32_t iters, double *splits, double *lambda, hipStream_t s);
 

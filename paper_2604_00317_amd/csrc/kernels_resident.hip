@@ -200,9 +200,227 @@ __global__ __launch_bounds__(1024) void k_resident(
     }
 }
 
+
+__host__ __device__ inline size_t reg_plan_bytes(int E, int K, int nt, int maxp)
+{
+    return sizeof(double) * (E + 2) + align8(K + 1) + sizeof(uint32_t) * maxp * nt;
+}
+
+// Register-resident variant for small dense fabrics (one modeled node): every thread owns one
+// commodity and one link for the whole solve, so what never changes between iterations lives in
+// registers -- the link ids of the commodity's MAXP x MAXL candidate steps, its choice counts,
+// the link's MAXROW reverse pairs with the demands they can add, and the link's length,
+// congestion sum and 1/capacity.  LDS holds only what threads exchange: the prices and the
+// choices.  Short paths are padded with the price slot E (+0.0, neutral for the sum and for the
+// maximum of positive prices), absent candidates start at slot E + 1 (+inf: never below the
+// best), absent pairs have an empty mask.  The additions are those of the generic kernel in the
+// same order (0 + p is p; adding +0.0 changes nothing), so the results are the same bits.
+template <bool MAXC, bool ONEWAVE, int MAXP, int MAXL, int MAXROW>
+__global__ __launch_bounds__(1024) void k_resident_reg(
+    int E, int K, int P, int batch, int nt, int plans_per_block, double eps, int iters,
+    const int32_t *__restrict__ g_cp, const int32_t *__restrict__ g_lp,
+    const int32_t *__restrict__ g_pl, const int32_t *__restrict__ g_rp,
+    const uint32_t *__restrict__ g_rev, const double *__restrict__ g_invcap,
+    const double *__restrict__ demand_all, double *__restrict__ splits_all,
+    double *__restrict__ lambda_all)
+{
+    static_assert(MAXP <= 8, "a choice is a bit of one mask byte; eight 8-bit counters per word");
+    static_assert(MAXROW % 4 == 0, "four mask bytes per register");
+    extern __shared__ __align__(16) unsigned char lds[];
+    __shared__ double red[16];
+    __shared__ double s_invrho[kMaxPlansPerBlock];
+
+    const int slot = threadIdx.x / nt;            // plan slot inside the workgroup
+    const int t = threadIdx.x - slot * nt;        // thread inside the plan group
+    const int plan = blockIdx.x * plans_per_block + slot;
+    const bool live = plan < batch;
+    const size_t plan_bytes = reg_plan_bytes(E, K, nt, MAXP);
+    double *price = reinterpret_cast<double *>(lds + plan_bytes * slot);
+    uint8_t *choice = reinterpret_cast<uint8_t *>(price + E + 2);
+    // choice counts of this thread's commodity, candidate j at [j * nt + t]
+    uint32_t *count = reinterpret_cast<uint32_t *>(choice + align8(K + 1)) + t;
+    const double *d_in = demand_all + static_cast<size_t>(live ? plan : 0) * K;
+    // a plan that is one wave needs no workgroup barrier: a wave's LDS operations execute in
+    // issue order
+    auto plan_sync = [] {
+        if constexpr (ONEWAVE) {
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        } else {
+            __syncthreads();
+        }
+    };
+
+    // the commodity of this thread: where the price of every candidate step lives
+    const bool has_k = t < K;
+    const double *pp[MAXP][MAXL];
+    int p0 = 0, np = 0;
+    if (has_k) {
+        p0 = g_cp[t];
+        np = g_cp[t + 1] - p0;
+    }
+#pragma unroll
+    for (int j = 0; j < MAXP; ++j) {
+        count[j * nt] = 0u;
+        int a = 0, b = 0;
+        if (j < np) {
+            a = g_lp[p0 + j];
+            b = g_lp[p0 + j + 1];
+        }
+#pragma unroll
+        for (int i = 0; i < MAXL; ++i) {
+            int e = (i == 0 && j >= np) ? E + 1 : E;
+            if (a + i < b) e = g_pl[a + i];
+            pp[j][i] = price + e;
+        }
+    }
+    // the link of this thread: for every reverse pair where the commodity's choice lives, the
+    // candidates that use the link, and the demand they add
+    const bool has_e = t < E;
+    const uint8_t *cptr[MAXROW];
+    uint32_t wb4[MAXROW / 4];      // the 8-bit candidate masks of four pairs per register
+    double dm[MAXROW];
+    double ic = 0.0, len = 1.0, S = 0.0, reach = 0.0;
+    {
+        int r0 = 0, rn = 0;
+        if (has_e) {
+            r0 = g_rp[t];
+            rn = g_rp[t + 1] - r0;
+            ic = g_invcap[t];
+        }
+#pragma unroll
+        for (int i = 0; i < MAXROW / 4; ++i) wb4[i] = 0u;
+#pragma unroll
+        for (int i = 0; i < MAXROW; ++i) {
+            cptr[i] = choice + K;                  // padding: the spare choice, empty mask
+            dm[i] = 0.0;
+            if (i < rn) {
+                const uint32_t wa = g_rev[2 * (r0 + i)];
+                const uint32_t k = wa & kCommMask;
+                if (k < static_cast<uint32_t>(K)) {
+                    cptr[i] = choice + k;
+                    wb4[i / 4] |= (g_rev[2 * (r0 + i) + 1] & 0xFFu) << (8 * (i % 4));
+                    dm[i] = d_in[k];
+                }
+                // width rho: every commodity that can reach the link counts once
+                if (wa & kFirstFlag) reach = reach + dm[i];
+            }
+        }
+    }
+    if (has_e) price[t] = MAXC ? 1.0 : ic;
+    if (t == 0) {
+        price[E] = 0.0;
+        price[E + 1] = __builtin_inf();
+        choice[K] = 0u;                            // read (never used) by padding pairs
+    }
+    // per-plan width: reduce inside the plan group through LDS (nt is a multiple of 64)
+    {
+        const double wm = wave_max(has_e ? reach * ic : 0.0);
+        if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x >> 6] = wm;
+        __syncthreads();
+        if (t == 0) {
+            double m = 0.0;
+            const int w0 = (slot * nt) >> 6, nw = nt >> 6;
+            for (int w = 0; w < nw; ++w) m = fmax(m, red[w0 + w]);
+            s_invrho[slot] = (m > 0.0) ? 1.0 / m : 0.0;
+        }
+        __syncthreads();
+    }
+    const double invrho = s_invrho[slot];
+
+    // eight 8-bit counters in one 64-bit word, emptied into the LDS counts before any can wrap
+    unsigned long long tally = 0ull;
+    auto flush = [&] {
+#pragma unroll
+        for (int j = 0; j < MAXP; ++j)
+            count[j * nt] += static_cast<uint32_t>(tally >> (8 * j)) & 0xFFu;
+        tally = 0ull;
+    };
+    for (int it = 0; it < iters; ++it) {
+        if (has_k) {
+            double best = __builtin_inf();
+            int bj = 0;
+            // the prices of four candidates are requested before the first is used
+            constexpr int kBatch = MAXP < 4 ? MAXP : 4;
+#pragma unroll
+            for (int j0 = 0; j0 < MAXP; j0 += kBatch) {
+                double pv[kBatch][MAXL];
+#pragma unroll
+                for (int j = 0; j < kBatch; ++j)
+#pragma unroll
+                    for (int i = 0; i < MAXL; ++i) pv[j][i] = *pp[j0 + j][i];
+#pragma unroll
+                for (int j = 0; j < kBatch; ++j) {
+                    double c = pv[j][0];                     // 0 + p is p
+#pragma unroll
+                    for (int i = 1; i < MAXL; ++i) {
+                        if constexpr (MAXC) c = (pv[j][i] > c) ? pv[j][i] : c;
+                        else c = c + pv[j][i];
+                    }
+                    if (c < best) {
+                        best = c;
+                        bj = j0 + j;
+                    }
+                }
+            }
+            choice[t] = static_cast<uint8_t>(bj);
+            tally += 1ull << (8 * bj);
+            if ((it & 127) == 127) flush();
+        }
+        plan_sync();
+        if (has_e) {
+            // the choices of all pairs are requested before the first is used
+            uint32_t ch[MAXROW];
+#pragma unroll
+            for (int i = 0; i < MAXROW; ++i) ch[i] = *cptr[i];
+            double load = 0.0;
+#pragma unroll
+            for (int i = 0; i < MAXROW; ++i) {
+                // all ones where the commodity's choice uses the link (adding +0.0 otherwise
+                // leaves the sum as it is); a choice is below 8, so it stays inside its byte
+                const int hit = __builtin_amdgcn_sbfe(static_cast<int>(wb4[i / 4] >> ch[i]),
+                                                      8 * (i % 4), 1);
+                load = load + __hiloint2double(__double2hiint(dm[i]) & hit,
+                                               __double2loint(dm[i]) & hit);
+            }
+            const double u = load * ic;
+            S = S + u;
+            const double g = u * invrho;
+            const double t1 = eps * g;
+            const double t2 = 1.0 + t1;
+            len = len * t2;
+            price[t] = MAXC ? len : len * ic;
+        }
+        plan_sync();
+    }
+
+    const double T = static_cast<double>(iters);
+    if (has_k) flush();
+    if (live && has_k) {
+        double *out = splits_all + static_cast<size_t>(plan) * P + p0;
+#pragma unroll
+        for (int j = 0; j < MAXP; ++j)
+            if (j < np) out[j] = static_cast<double>(count[j * nt]) / T;
+    }
+    const double sm = wave_max(has_e ? S : 0.0);
+    __syncthreads();
+    if ((threadIdx.x & (kWave - 1)) == 0) red[threadIdx.x >> 6] = sm;
+    __syncthreads();
+    if (t == 0 && live) {
+        double m = 0.0;
+        const int w0 = (slot * nt) >> 6, nw = nt >> 6;
+        for (int w = 0; w < nw; ++w) m = fmax(m, red[w0 + w]);
+        lambda_all[plan] = m / T;
+    }
+}
+
+constexpr int kRegMaxPaths = 8, kRegMaxLen = 2, kRegMaxRow = 16;
+
 struct ResidentPlan {
     int nt, plans_per_block;
     bool topo_lds;
+    bool in_registers;     // k_resident_reg: one commodity and one link per thread
     size_t lds_bytes;
 };
 
@@ -224,6 +442,9 @@ bool plan_resident(const DeviceTopo &t, int batch, ResidentPlan &rp)
     rp.plans_per_block = ppb;
     rp.topo_lds = lay.plan_bytes * ppb + lay.topo_bytes + 256 <= kLdsBudget;
     rp.lds_bytes = lay.plan_bytes * ppb + (rp.topo_lds ? lay.topo_bytes : 0);
+    rp.in_registers = !t.resident_generic && t.pmax <= kRegMaxPaths && t.lmax <= kRegMaxLen &&
+                      t.rev_row_max <= kRegMaxRow;
+    if (rp.in_registers) rp.lds_bytes = reg_plan_bytes(t.E, t.K, nt, kRegMaxPaths) * ppb;
     return true;
 }
 
@@ -245,6 +466,12 @@ bool resident_fits(const DeviceTopo &t)
     return plan_resident(t, 1, rp);
 }
 
+bool resident_in_registers(const DeviceTopo &t)
+{
+    ResidentPlan rp;
+    return plan_resident(t, 1, rp) && rp.in_registers;
+}
+
 hipError_t launch_resident(const DeviceTopo &t, int32_t batch, const double *demand, double eps,
                            int32_t iters, double *splits, double *lambda, hipStream_t s)
 {
@@ -257,6 +484,23 @@ hipError_t launch_resident(const DeviceTopo &t, int32_t batch, const double *dem
                        t.K, t.P, static_cast<int>(t.nnz), static_cast<int>(t.rev_pairs), batch,  \
                        rp.nt, rp.plans_per_block, eps, iters, t.comm_ptr, t.path_ptr,          \
                        t.path_links, t.rev_ptr, t.rev_pair, t.invcap, demand, splits, lambda)
+    if (rp.in_registers) {
+#define NIMBLE_REG_LAUNCH(MAXC, ONEW)                                                          \
+    hipLaunchKernelGGL((k_resident_reg<MAXC, ONEW, kRegMaxPaths, kRegMaxLen, kRegMaxRow>),     \
+                       dim3(grid), dim3(block), rp.lds_bytes, s, t.E, t.K, t.P, batch, rp.nt,  \
+                       rp.plans_per_block, eps, iters, t.comm_ptr, t.path_ptr, t.path_links,   \
+                       t.rev_ptr, t.rev_pair, t.invcap, demand, splits, lambda)
+        const bool one_wave = rp.nt == kWave;
+        if (t.cost_max) {
+            if (one_wave) NIMBLE_REG_LAUNCH(true, true);
+            else NIMBLE_REG_LAUNCH(true, false);
+        } else {
+            if (one_wave) NIMBLE_REG_LAUNCH(false, true);
+            else NIMBLE_REG_LAUNCH(false, false);
+        }
+#undef NIMBLE_REG_LAUNCH
+        return hipGetLastError();
+    }
     if (t.cost_max) {
         if (rp.topo_lds) NIMBLE_RES_LAUNCH(true, true);
         else NIMBLE_RES_LAUNCH(true, false);

@@ -376,7 +376,9 @@ __device__ __forceinline__ void reduce_tile_phase(
     // (tile_demand_index)
     const u32x4 *masks = reinterpret_cast<const u32x4 *>(tile_mask);
     const int my_row = tile_row_of_lane(lane);
-    for (int it = wave; it < n_items; it += n_waves) {               // wave-uniform
+    // the item index lives in a scalar register, so the descriptor words that all lanes share
+    // come by scalar loads
+    for (int it = __builtin_amdgcn_readfirstlane(wave); it < n_items; it += n_waves) {
         const int32_t *d = tile_desc + size_t(it) * kTileDescInts;
         const int base = __builtin_amdgcn_readfirstlane(d[0]);
         const int flags = __builtin_amdgcn_readfirstlane(d[1]);

@@ -70,6 +70,7 @@ def test_batched_single_node(oracle_mod, B, batch):
     print(f"[batch] batch={batch}", flush=True)
     h = B.nimble_topo_create(*t.csr())
     try:
+        assert h.resident_in_registers
         splits, lam = B.plan(h, w.traffic, w.eps, w.iters)
         assert h.regime == B.NIMBLE_REGIME_RESIDENT
     finally:
@@ -95,6 +96,57 @@ def test_batch_outside_the_resident_regime(oracle_mod, B, regime):
         h.close()
     for b in range(3):
         ref = oracle_mod.solve(*t.csr(), w.traffic[b], w.eps, 60)
+        assert np.array_equal(splits[b], ref["splits"]), b
+        assert lam[b] == ref["lam"], b
+
+
+@pytest.mark.parametrize("flags", [0, 1])
+@pytest.mark.parametrize("seed,E,K,pm,lm,in_regs", [(21, 30, 25, 8, 2, True),
+                                                    (22, 64, 64, 5, 2, True),
+                                                    (23, 100, 70, 8, 1, True),
+                                                    (24, 12, 9, 3, 2, True),
+                                                    (25, 130, 100, 8, 2, True),
+                                                    (26, 30, 25, 9, 2, False),
+                                                    (27, 30, 25, 8, 3, False),
+                                                    (28, 6, 60, 8, 2, False)])
+def test_resident_regime_register_and_lds_kernels(oracle_mod, B, monkeypatch, seed, E, K, pm, lm,
+                                                  in_regs, flags):
+    """Small fabrics (at most 8 candidates of 2 links, 16 pairs per link) keep the topology in
+    registers; one candidate, one link or one pair more and the LDS kernel runs.  Forcing the
+    LDS kernel on the small ones gives the same bits."""
+    rng = np.random.default_rng(seed)
+    t = W.random_topology(rng, E, K, pm, lm)
+    d = np.floor(rng.pareto(1.1, K) * 1e6)
+    d[rng.integers(0, K)] = 0.0
+    h = B.nimble_topo_create(*t.csr(), flags=flags)
+    try:
+        assert h.resident_in_registers == in_regs
+    finally:
+        h.close()
+    check(oracle_mod, B, t, d, 0.07, 60, 1, flags)
+    if in_regs:
+        monkeypatch.setenv("NIMBLE_TUNE_RESIDENT_GENERIC", "1")
+        h = B.nimble_topo_create(*t.csr(), flags=flags)
+        try:
+            assert not h.resident_in_registers
+        finally:
+            h.close()
+        check(oracle_mod, B, t, d, 0.07, 60, 1, flags)
+
+
+def test_batched_single_node_with_the_lds_kernel(oracle_mod, B, monkeypatch):
+    monkeypatch.setenv("NIMBLE_TUNE_RESIDENT_GENERIC", "1")
+    w = W.make_config(2, batch=5)
+    t = w.topo
+    h = B.nimble_topo_create(*t.csr())
+    try:
+        assert not h.resident_in_registers
+        splits, lam = B.plan(h, w.traffic, w.eps, w.iters)
+        assert h.regime == B.NIMBLE_REGIME_RESIDENT
+    finally:
+        h.close()
+    for b in range(5):
+        ref = oracle_mod.solve(*t.csr(), w.traffic[b], w.eps, w.iters)
         assert np.array_equal(splits[b], ref["splits"]), b
         assert lam[b] == ref["lam"], b
 
