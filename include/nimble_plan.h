@@ -128,7 +128,9 @@ nimble_status_t nimble_plan_solve_batch(nimble_topo_t *topo, int32_t batch,
  * lowest bottleneck cost max_e F(L_e) (strict `<` in candidate order), routes f = r if r < chi,
  * else the largest multiple of chi that is <= r * phi (one chunk when that is 0), and adds f to
  * the loads of that candidate's links at once (the next pair sees it).  F(L_e) = L_e / cap_e.
- * One GPU thread runs one problem.
+ * A group of lanes (one per candidate of the current pair) runs one problem; topologies with
+ * more than 64 candidates per pair, paths of more than 8 links, or tables beyond 64 KB of LDS
+ * run one thread per problem.
  *
  *   d_traffic   device [batch][n_comm], bytes >= 0
  *   phi         routed fraction of the remainder per visit, 0 < phi <= 1
@@ -141,8 +143,8 @@ nimble_status_t nimble_plan_solve_batch(nimble_topo_t *topo, int32_t batch,
  *               traffic left after max_sweeps sweeps
  *   d_sweeps    device int32 [batch] out: sweeps made
  *   hip_stream  as for nimble_plan_solve: the call only enqueues work.
- * Errors: NIMBLE_ERR_INVALID for bad arguments; NIMBLE_ERR_RANGE when 8 x (n_links + n_comm)
- * doubles exceed 150 KB (the per-problem state lives in LDS, 8 to 64 problems per workgroup).
+ * Errors: NIMBLE_ERR_INVALID for bad arguments; NIMBLE_ERR_RANGE when the topology fits neither
+ * kernel: 8 x (n_links + n_comm) doubles exceed 150 KB (the per-problem state lives in LDS).
  * Results are bit-identical to the plain CPU definition for any demands.
  */
 nimble_status_t nimble_alg1_solve_batch(nimble_topo_t *topo, int32_t batch,

@@ -244,6 +244,7 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     d.rev_row_max = 0;
     for (int32_t len : h.rev_rowlen) d.rev_row_max = std::max(d.rev_row_max, len);
     d.resident_generic = std::getenv("NIMBLE_TUNE_RESIDENT_GENERIC") ? 1 : 0;
+    d.alg1_thread_per_problem = std::getenv("NIMBLE_TUNE_ALG1_THREAD_PER_PROBLEM") ? 1 : 0;
     d.n_records = h.n_records;
     d.rec_stride = h.rec_stride;
     d.rec_max_links = h.rec_max_links;
@@ -523,7 +524,7 @@ nimble_status_t nimble_alg1_solve_batch(nimble_topo_t *topo, int32_t batch,
     if (max_sweeps < 1) return fail(NIMBLE_ERR_INVALID, "max_sweeps must be >= 1");
     if (!nimble::alg1_fits(topo->d))
         return fail(NIMBLE_ERR_RANGE,
-                    "8 x (links + commodities) doubles do not fit in the LDS of a compute unit");
+                    "the per-problem state does not fit in the LDS of a compute unit");
     nimble_status_t st = check_device(topo);
     if (st != NIMBLE_OK) return st;
     hipError_t e = nimble::launch_alg1(topo->d, batch, d_traffic, phi, chi, max_sweeps, d_flows,

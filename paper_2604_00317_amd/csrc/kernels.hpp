@@ -27,6 +27,7 @@ struct DeviceTopo {
     int64_t rev_pairs;         // padded number of pairs
     int32_t rev_row_max;       // longest reverse row in pairs (without padding)
     int32_t resident_generic;  // 1: the resident regime keeps to its LDS-only kernel
+    int32_t alg1_thread_per_problem;   // 1: Algorithm 1 keeps to its thread-per-problem kernel
     const int32_t *rev_ptr;    // [E+1], in pairs
     const uint32_t *rev_pair;  // [2 * rev_pairs]
     // streaming layout of the reverse rows: one flat array of octets (base id | flags, 8

@@ -17,6 +17,15 @@ def B():
     return binding
 
 
+@pytest.fixture(autouse=True, params=["lanes-per-problem", "thread-per-problem"])
+def alg1_kernel(request, monkeypatch):
+    """Every test runs with the library's own choice of kernel (a lane group per problem where
+    the fabric fits it) and with the thread-per-problem kernel forced."""
+    if request.param == "thread-per-problem":
+        monkeypatch.setenv("NIMBLE_TUNE_ALG1_THREAD_PER_PROBLEM", "1")
+    return request.param
+
+
 def make_topo(B, t, flags=0):
     return B.nimble_topo_create(t.n_links, t.cap, t.n_comm, t.comm_path_ptr, t.n_paths,
                                 t.path_link_ptr, t.path_links, flags)
@@ -61,6 +70,20 @@ def test_random_topologies_and_non_integer_demands(oracle_mod, B, seed):
     print(f"[alg1] random seed={seed}", flush=True)
     flows, lam, sweeps = check(oracle_mod, B, t, d, 0.3, 1000.0)
     assert sweeps[1] == 0 and lam[1] == 0.0
+
+
+@pytest.mark.parametrize("max_paths", [1, 2, 5, 16, 33, 64, 70])
+def test_every_group_width(oracle_mod, B, max_paths):
+    """Lane groups of 1 to 64 lanes per problem (several problems per wave, a ragged last
+    workgroup); 70 candidates are beyond a wave and take the thread-per-problem kernel."""
+    rng = np.random.default_rng(300 + max_paths)
+    t = W.random_topology(rng, 25, 12, max_paths, 3)
+    nb = 2 * (256 // min(64, max(1, 1 << (max_paths - 1).bit_length()))) + 3
+    nb = min(nb, 40)
+    d = np.floor(rng.pareto(1.2, (nb, t.n_comm)) * 1e5)
+    d[0] = 0.0
+    print(f"[alg1] max_paths={max_paths} problems={nb}", flush=True)
+    check(oracle_mod, B, t, d, 0.4, 5000.0)
 
 
 def test_chunk_larger_than_every_demand(oracle_mod, B):
