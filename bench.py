@@ -50,6 +50,24 @@ def time_phase(B, torch, h, phase, reps, d_traffic):
     return start.elapsed_time(stop) * 1e-3 / reps
 
 
+def time_stream_read(B, torch, nbytes, reps):
+    """Read bandwidth (GB/s) of a plain 16-byte-per-lane streaming read of `nbytes`, HIP events
+    on torch's current stream around `reps` back-to-back launches."""
+    buf = torch.zeros(nbytes // 8, dtype=torch.float64, device="cuda:0")
+    sink = torch.zeros(2, dtype=torch.float64, device="cuda:0")
+    start = torch.cuda.Event(enable_timing=True)
+    stop = torch.cuda.Event(enable_timing=True)
+    B.nimble_debug_stream_read(buf, nbytes, 3, sink)
+    torch.cuda.synchronize()
+    start.record()
+    B.nimble_debug_stream_read(buf, nbytes, reps, sink)
+    stop.record()
+    torch.cuda.synchronize()
+    sec = start.elapsed_time(stop) * 1e-3 / reps
+    del buf
+    return nbytes / sec / 1e9
+
+
 def read_traffic(kernel, workload):
     """HBM bytes per launch of `kernel` measured with rocprofv3 counters, from the committed
     summary profiles/hbm_traffic.txt (lines: workload kernel fetch_bytes write_bytes)."""
@@ -176,6 +194,16 @@ def main() -> int:
         # one reverse entry per incidence) would have to move: context for the compression
         plain = (8 * topo.nnz + 4 * topo.n_paths + 4 * topo.n_links + 24 * topo.n_comm +
                  48 * topo.n_links)
+        # what a plain streaming read reaches on this machine: a buffer far beyond the 256 MB
+        # Infinity Cache (HBM), and one of the dominant kernel's own size (re-read every launch,
+        # as the kernel's data is, so served by the Infinity Cache)
+        hbm_read = time_stream_read(B, torch, 2 << 30, 20)
+        own = max(int(kernels[dom]["bytes"]) // 16 * 16, 1 << 20)
+        own_read = time_stream_read(B, torch, own, 100)
+        roofline["empirical_read"] = dict(
+            unit="GB/s", buffer_2GiB=hbm_read, buffer_of_kernel_size=own_read,
+            kernel_bytes=own, frac_of_2GiB_read=kernels[dom]["gbs"] / hbm_read,
+            frac_of_same_size_read=kernels[dom]["gbs"] / own_read)
         roofline["plain_csr_bytes_per_iter"] = int(plain)
         roofline["plain_csr_equivalent_gbs"] = plain * w.iters * args.steps / elapsed / 1e9
     else:

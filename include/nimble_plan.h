@@ -270,6 +270,16 @@ nimble_status_t nimble_debug_run_phase(nimble_topo_t *topo, int32_t phase, int32
                                        const double *d_traffic, void *hip_stream);
 
 /*
+ * Benchmark helper: enqueue `reps` back-to-back launches of a plain streaming read of the first
+ * `bytes` (rounded down to 16) of d_buf on `hip_stream` -- 16-byte loads, nothing computed.  The
+ * benchmark times it to state the read bandwidth this machine reaches next to the published
+ * peak.  d_buf and d_sink are device pointers, 16-byte aligned; d_sink is 16 bytes that the
+ * kernel may write.  NIMBLE_ERR_INVALID for NULL or misaligned pointers, bytes < 16, reps < 1.
+ */
+nimble_status_t nimble_debug_stream_read(const void *d_buf, int64_t bytes, int32_t reps,
+                                         void *d_sink, void *hip_stream);
+
+/*
  * Test helper for the persistent regime: every grid-wide barrier of that kernel waits at most
  * `polls` polls of its arrival counter (default 2^22, about a second).  When a wait expires the
  * solve is abandoned -- every workgroup leaves the kernel at its next poll, d_splits is left

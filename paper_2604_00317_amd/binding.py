@@ -31,6 +31,7 @@ EXPORTS = [
     "nimble_plan_solve_adaptive",
     "nimble_host_records_roundtrip", "nimble_host_layout_stats",
     "nimble_host_build_reverse_streaming", "nimble_topo_resident_in_registers",
+    "nimble_debug_stream_read",
 ]
 
 _lib = None
@@ -78,6 +79,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.nimble_topo_set_regime.argtypes = [vp, i32]
     lib.nimble_debug_run_phase.restype = ctypes.c_int
     lib.nimble_debug_run_phase.argtypes = [vp, i32, i32, vp, vp]
+    lib.nimble_debug_stream_read.restype = ctypes.c_int
+    lib.nimble_debug_stream_read.argtypes = [vp, i64, i32, vp, vp]
     lib.nimble_debug_set_spin_limit.restype = ctypes.c_int
     lib.nimble_debug_set_spin_limit.argtypes = [vp, u32]
     lib.nimble_host_records_roundtrip.restype = ctypes.c_int
@@ -272,6 +275,17 @@ def nimble_debug_run_phase(topo: Topo, phase: int, reps: int, d_traffic, stream=
     _check(load_library().nimble_debug_run_phase(
         topo.handle, int(phase), int(reps),
         _dev_ptr(d_traffic, "float64", topo.n_comm, "d_traffic"), _stream_ptr(stream)))
+
+
+def nimble_debug_stream_read(d_buf, nbytes: int, reps: int, d_sink, stream=None) -> None:
+    """Enqueue `reps` plain streaming reads of the first `nbytes` of the device tensor d_buf."""
+    if not (d_buf.is_cuda and d_sink.is_cuda and d_buf.is_contiguous()):
+        raise ValueError("d_buf and d_sink must be contiguous device tensors")
+    if nbytes > d_buf.numel() * d_buf.element_size() or d_sink.numel() * d_sink.element_size() < 16:
+        raise ValueError("nbytes exceeds d_buf, or d_sink is smaller than 16 bytes")
+    _check(load_library().nimble_debug_stream_read(
+        ctypes.c_void_p(d_buf.data_ptr()), int(nbytes), int(reps),
+        ctypes.c_void_p(d_sink.data_ptr()), _stream_ptr(stream)))
 
 
 def nimble_debug_set_spin_limit(topo: Topo, polls: int) -> None:

@@ -687,4 +687,20 @@ nimble_status_t nimble_debug_run_phase(nimble_topo_t *topo, int32_t phase, int32
     return NIMBLE_OK;
 }
 
+nimble_status_t nimble_debug_stream_read(const void *d_buf, int64_t bytes, int32_t reps,
+                                         void *d_sink, void *hip_stream)
+{
+    g_last_error.clear();
+    if (!d_buf || !d_sink) return fail(NIMBLE_ERR_INVALID, "NULL argument");
+    if (bytes < 16 || reps < 1) return fail(NIMBLE_ERR_INVALID, "bytes must be >= 16, reps >= 1");
+    if ((reinterpret_cast<uintptr_t>(d_buf) | reinterpret_cast<uintptr_t>(d_sink)) & 15u)
+        return fail(NIMBLE_ERR_INVALID, "buffers must be 16-byte aligned");
+    hipStream_t s = static_cast<hipStream_t>(hip_stream);
+    for (int32_t r = 0; r < reps; ++r)
+        nimble::launch_stream_read(d_buf, static_cast<size_t>(bytes), d_sink, s);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return fail_hip(e, "kernel launch (streaming read)");
+    return NIMBLE_OK;
+}
+
 }  // extern "C"

@@ -84,6 +84,7 @@ struct DeviceTopo {
     int32_t reduce_blocks;     // 256-thread blocks of the link-load reduce (fills the chip once)
 };
 
+void launch_stream_read(const void *buf, size_t bytes, void *sink, hipStream_t s);
 int lanes_per_commodity(int pmax);   // power of two >= pmax, at most 64
 
 // ---- streaming regime: one launch per phase ------------------------------------------------

@@ -304,6 +304,23 @@ def test_argument_errors_on_device(B):
         h.close()
 
 
+def test_streaming_read_helper(B):
+    """The bandwidth probe of the benchmark: runs, leaves its buffer alone, refuses bad input."""
+    import torch
+    buf = torch.arange(1 << 16, dtype=torch.float64, device="cuda:0")
+    sink = torch.zeros(2, dtype=torch.float64, device="cuda:0")
+    B.nimble_debug_stream_read(buf, buf.numel() * 8, 3, sink)
+    B.nimble_debug_stream_read(buf, 16, 1, sink)
+    torch.cuda.synchronize()
+    assert torch.equal(buf, torch.arange(1 << 16, dtype=torch.float64, device="cuda:0"))
+    with pytest.raises(ValueError):
+        B.nimble_debug_stream_read(buf, buf.numel() * 8 + 16, 1, sink)
+    with pytest.raises(B.NimbleError):
+        B.nimble_debug_stream_read(buf, 8, 1, sink)
+    with pytest.raises(B.NimbleError):
+        B.nimble_debug_stream_read(buf[1:], 64, 1, sink)      # 8-byte aligned only
+
+
 def test_solve_on_side_stream_and_reuse(oracle_mod, B):
     import torch
     w = W.make_config(1)
