@@ -72,7 +72,8 @@ __global__ void k_ad_lb(int n_alpha, const double *__restrict__ chunk_alpha, int
     ascal[1] = alpha / D;
 }
 
-// normalised loads u = load / cap by position, and the maximum of every block
+// normalised loads u = load / cap by position, and the maximum of every block; RL lanes per link
+template <int RL>
 __global__ __launch_bounds__(kAdBlock) void k_ad_u(int E, const int32_t *__restrict__ pos_slot_ptr,
                                                    const int2 *__restrict__ pos_xslot,
                                                    const double *__restrict__ partial,
@@ -84,8 +85,8 @@ __global__ __launch_bounds__(kAdBlock) void k_ad_u(int E, const int32_t *__restr
     __shared__ double red[16];
     if (flags[0]) return;
     const int lane = threadIdx.x & (kWave - 1);
-    const int row = lane / kRowLanes, l = lane % kRowLanes;
-    const int i = ((blockIdx.x * kAdBlock + threadIdx.x) >> 6) * kRowsPerWave + row;
+    const int row = lane / RL, l = lane % RL;
+    const int i = ((blockIdx.x * kAdBlock + threadIdx.x) >> 6) * (kWave / RL) + row;
     int c0 = 0, c1 = 0, s0 = 0, s1 = 0;
     if (i < E) {
         c0 = pos_slot_ptr[i];
@@ -94,7 +95,8 @@ __global__ __launch_bounds__(kAdBlock) void k_ad_u(int E, const int32_t *__restr
         s0 = xs.x;
         s1 = xs.y;
     }
-    const double load = row_partial_sum(c0, c1, l, partial) + row_partial_sum(s0, s1, l, partial);
+    const double load =
+        row_partial_sum<RL>(c0, c1, l, partial) + row_partial_sum<RL>(s0, s1, l, partial);
     double u = 0.0;
     if (i < E) {
         u = load * invcap_pos[i];
@@ -242,10 +244,16 @@ void launch_ad_bound(const DeviceTopo &t, const AdaptiveState &a, const uint8_t 
 
 void launch_ad_update(const DeviceTopo &t, const AdaptiveState &a, double eps, hipStream_t s)
 {
-    // one 16-lane row per link in k_ad_u (16 links per block), one thread per link in k_ad_apply
-    const int gu = (t.E + 15) / 16;
-    hipLaunchKernelGGL(k_ad_u, dim3(gu), dim3(kAdBlock), 0, s, t.E, t.pos_slot_ptr, t.pos_xslot,
-                       t.partial, t.invcap_pos, a.flags, a.u_pos, a.block_max_u);
+    // 16 or 4 lanes per link in k_ad_u (as in the fixed-step update), one thread per link in
+    // k_ad_apply
+    const int per_block = kAdBlock / t.update_lanes;
+    const int gu = (t.E + per_block - 1) / per_block;
+    if (t.update_lanes == 4)
+        hipLaunchKernelGGL(k_ad_u<4>, dim3(gu), dim3(kAdBlock), 0, s, t.E, t.pos_slot_ptr,
+                           t.pos_xslot, t.partial, t.invcap_pos, a.flags, a.u_pos, a.block_max_u);
+    else
+        hipLaunchKernelGGL(k_ad_u<16>, dim3(gu), dim3(kAdBlock), 0, s, t.E, t.pos_slot_ptr,
+                           t.pos_xslot, t.partial, t.invcap_pos, a.flags, a.u_pos, a.block_max_u);
     const int ga = (t.E + kAdBlock - 1) / kAdBlock;
     if (t.cost_max)
         hipLaunchKernelGGL(k_ad_apply<true>, dim3(ga), dim3(kAdBlock), 0, s, t.E, eps, gu,
