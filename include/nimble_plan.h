@@ -105,6 +105,9 @@ void nimble_topo_destroy(nimble_topo_t *topo);
  *               nimble_debug_set_spin_limit)
  *   hip_stream  hipStream_t (NULL = default stream).  The call only enqueues work; outputs are
  *               valid after the stream is synchronised.  No host synchronisation inside.
+ * The first streaming-regime solve with a given iteration count may grow the topology's
+ * workspace (the choice log); later solves with the same or a smaller count enqueue kernels
+ * only, so a caller may capture them into a HIP graph on its own stream.
  */
 nimble_status_t nimble_plan_solve(nimble_topo_t *topo, const double *d_traffic, double eps,
                                   int32_t iters, double *d_splits, double *d_lambda,

@@ -304,6 +304,47 @@ def test_argument_errors_on_device(B):
         h.close()
 
 
+@pytest.mark.parametrize("cfg,iters", [(1, 40), (3, 60)])
+def test_a_solve_can_be_captured_in_a_graph(oracle_mod, B, cfg, iters):
+    """After one eager solve (which sizes the workspace) a solve only enqueues kernels, so a
+    caller may capture it; every replay, with eager solves of other traffic in between, gives
+    the oracle's bits again."""
+    import torch
+    w = W.make_config(cfg)
+    t = w.topo
+    ref = oracle_mod.solve(*t.csr(), w.traffic, w.eps, iters)
+    other = np.floor(w.traffic / 3.0)
+    ref_other = oracle_mod.solve(*t.csr(), other, w.eps, iters)
+    h = B.nimble_topo_create(*t.csr())
+    try:
+        d_tr = torch.as_tensor(w.traffic).to("cuda:0")
+        d_ot = torch.as_tensor(other).to("cuda:0")
+        d_sp = torch.empty(t.n_paths, dtype=torch.float64, device="cuda:0")
+        d_la = torch.empty(1, dtype=torch.float64, device="cuda:0")
+        d_sp2 = torch.empty_like(d_sp)
+        d_la2 = torch.empty_like(d_la)
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(side):
+            B.nimble_plan_solve(h, d_tr, w.eps, iters, d_sp, d_la)
+            torch.cuda.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                B.nimble_plan_solve(h, d_tr, w.eps, iters, d_sp, d_la)
+        torch.cuda.synchronize()
+        for replay in range(3):
+            d_sp.zero_()
+            d_la.zero_()
+            B.nimble_plan_solve(h, d_ot, w.eps, iters, d_sp2, d_la2)      # eager, in between
+            torch.cuda.synchronize()
+            assert np.array_equal(d_sp2.cpu().numpy(), ref_other["splits"]), replay
+            graph.replay()
+            torch.cuda.synchronize()
+            assert np.array_equal(d_sp.cpu().numpy(), ref["splits"]), replay
+            assert float(d_la.item()) == ref["lam"], replay
+    finally:
+        h.close()
+
+
 def test_streaming_read_helper(B):
     """The bandwidth probe of the benchmark: runs, leaves its buffer alone, refuses bad input."""
     import torch
