@@ -47,7 +47,10 @@ enum {
 
 /* kernel regimes, for nimble_topo_set_regime (testing and benchmarking) */
 enum {
-    NIMBLE_REGIME_AUTO = 0,     /* chosen from the problem size */
+    NIMBLE_REGIME_AUTO = 0,     /* chosen from the problem size and the number of plans: resident
+                                   when the per-plan state fits in LDS, unless so few plans of a
+                                   fabric with long reverse rows are asked for that streaming
+                                   them one after the other is faster */
     NIMBLE_REGIME_RESIDENT = 1, /* one workgroup per plan, whole iteration loop in one kernel,
                                    state in LDS */
     NIMBLE_REGIME_STREAM = 2,   /* one kernel per phase: two or three launches per iteration

@@ -144,10 +144,22 @@ nimble_status_t check_device(const nimble_topo *topo)
     return NIMBLE_OK;
 }
 
-int32_t pick_regime(const nimble_topo *topo)
+// The regime of a solve of `batch` plans.  The resident regime runs the plans side by side,
+// one thread group each, for the price of one; but the thread of its LDS kernel walks a
+// commodity's candidates and a link's reverse row alone (about 0.04 us per LDS access, measured
+// on the two-node fabric), while a streaming-regime iteration costs about two short kernels
+// (6.5 us) however wide the rows are.  A few plans of a fabric with long rows are therefore
+// streamed one after the other.
+int32_t pick_regime(const nimble_topo *topo, int32_t batch)
 {
     if (topo->forced_regime != NIMBLE_REGIME_AUTO) return topo->forced_regime;
-    return nimble::resident_fits(topo->d) ? NIMBLE_REGIME_RESIDENT : NIMBLE_REGIME_STREAM;
+    const nimble::DeviceTopo &d = topo->d;
+    if (!nimble::resident_fits(d)) return NIMBLE_REGIME_STREAM;
+    if (nimble::resident_in_registers(d)) return NIMBLE_REGIME_RESIDENT;
+    const double accesses = 2.0 * d.pmax * d.lmax + 3.0 * d.rev_row_max;
+    const double resident_us = 0.04 * accesses * ((batch + 255) / 256);
+    const double stream_us = 6.5 * batch;
+    return resident_us < stream_us ? NIMBLE_REGIME_RESIDENT : NIMBLE_REGIME_STREAM;
 }
 
 nimble_status_t solve_stream(nimble_topo *topo, const double *d_traffic, double eps,
@@ -464,7 +476,7 @@ nimble_status_t nimble_plan_solve(nimble_topo_t *topo, const double *d_traffic, 
     st = check_device(topo);
     if (st != NIMBLE_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const int32_t regime = pick_regime(topo);
+    const int32_t regime = pick_regime(topo, 1);
     topo->last_regime = regime;
     if (regime == NIMBLE_REGIME_RESIDENT) {
         hipError_t e = nimble::launch_resident(topo->d, 1, d_traffic, eps, iters, d_splits,
@@ -488,7 +500,7 @@ nimble_status_t nimble_plan_solve_batch(nimble_topo_t *topo, int32_t batch,
     st = check_device(topo);
     if (st != NIMBLE_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
-    const int32_t regime = pick_regime(topo);
+    const int32_t regime = pick_regime(topo, batch);
     topo->last_regime = regime;
     if (regime == NIMBLE_REGIME_RESIDENT) {
         hipError_t e = nimble::launch_resident(topo->d, batch, d_traffic, eps, iters, d_splits,

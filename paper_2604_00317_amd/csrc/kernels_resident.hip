@@ -17,6 +17,7 @@ namespace nimble {
 namespace {
 
 constexpr size_t kLdsBudget = 64 * 1024;   // static + dynamic LDS a kernel may use without opt-in
+constexpr size_t kLdsBudgetMax = 150 * 1024;   // with opt-in, for the LDS copy of the topology
 constexpr int kMaxPlansPerBlock = 4;
 
 struct ResidentLayout {
@@ -440,7 +441,8 @@ bool plan_resident(const DeviceTopo &t, int batch, ResidentPlan &rp)
         while (ppb > 1 && lay.plan_bytes * ppb + 256 > kLdsBudget) --ppb;
     }
     rp.plans_per_block = ppb;
-    rp.topo_lds = lay.plan_bytes * ppb + lay.topo_bytes + 256 <= kLdsBudget;
+    // the topology copy may take the LDS beyond 64 KB (the launch opts in)
+    rp.topo_lds = lay.plan_bytes * ppb + lay.topo_bytes + 256 <= kLdsBudgetMax;
     rp.lds_bytes = lay.plan_bytes * ppb + (rp.topo_lds ? lay.topo_bytes : 0);
     rp.in_registers = !t.resident_generic && t.pmax <= kRegMaxPaths && t.lmax <= kRegMaxLen &&
                       t.rev_row_max <= kRegMaxRow;
@@ -480,10 +482,19 @@ hipError_t launch_resident(const DeviceTopo &t, int32_t batch, const double *dem
     const int grid = (batch + rp.plans_per_block - 1) / rp.plans_per_block;
     const int block = rp.nt * rp.plans_per_block;
 #define NIMBLE_RES_LAUNCH(MAXC, TL)                                                            \
-    hipLaunchKernelGGL((k_resident<MAXC, TL>), dim3(grid), dim3(block), rp.lds_bytes, s, t.E,  \
-                       t.K, t.P, static_cast<int>(t.nnz), static_cast<int>(t.rev_pairs), batch,  \
-                       rp.nt, rp.plans_per_block, eps, iters, t.comm_ptr, t.path_ptr,          \
-                       t.path_links, t.rev_ptr, t.rev_pair, t.invcap, demand, splits, lambda)
+    do {                                                                                       \
+        if (rp.lds_bytes + 256 > kLdsBudget) {                                                 \
+            hipError_t ea = hipFuncSetAttribute(                                               \
+                reinterpret_cast<const void *>(&k_resident<MAXC, TL>),                         \
+                hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(rp.lds_bytes));   \
+            if (ea != hipSuccess) return ea;                                                   \
+        }                                                                                      \
+        hipLaunchKernelGGL((k_resident<MAXC, TL>), dim3(grid), dim3(block), rp.lds_bytes, s,   \
+                           t.E, t.K, t.P, static_cast<int>(t.nnz),                             \
+                           static_cast<int>(t.rev_pairs), batch, rp.nt, rp.plans_per_block,    \
+                           eps, iters, t.comm_ptr, t.path_ptr, t.path_links, t.rev_ptr,        \
+                           t.rev_pair, t.invcap, demand, splits, lambda);                      \
+    } while (0)
     if (rp.in_registers) {
 #define NIMBLE_REG_LAUNCH(MAXC, ONEW)                                                          \
     hipLaunchKernelGGL((k_resident_reg<MAXC, ONEW, kRegMaxPaths, kRegMaxLen, kRegMaxRow>),     \

@@ -134,6 +134,30 @@ def test_resident_regime_register_and_lds_kernels(oracle_mod, B, monkeypatch, se
         check(oracle_mod, B, t, d, 0.07, 60, 1, flags)
 
 
+def test_regime_chosen_from_batch_size_and_row_lengths(oracle_mod, B):
+    """The two-node fabric fits the resident regime, but its rail links carry 64 pairs each: one
+    plan is streamed (two short kernels per iteration beat one thread walking such a row), a
+    batch of plans runs side by side in the resident regime.  Same bits either way."""
+    w = W.make_config(1)
+    t = w.topo
+    iters = 50
+    tr = np.stack([w.traffic, np.floor(w.traffic / 2), np.floor(w.traffic / 5),
+                   np.zeros_like(w.traffic)])
+    refs = [oracle_mod.solve(*t.csr(), tr[b], w.eps, iters) for b in range(4)]
+    h = B.nimble_topo_create(*t.csr())
+    try:
+        splits, lam = B.plan(h, tr[0], w.eps, iters)
+        assert h.regime == B.NIMBLE_REGIME_STREAM
+        assert np.array_equal(splits, refs[0]["splits"]) and lam == refs[0]["lam"]
+        splits, lam = B.plan(h, tr, w.eps, iters)
+        assert h.regime == B.NIMBLE_REGIME_RESIDENT
+        for b in range(4):
+            assert np.array_equal(splits[b], refs[b]["splits"]), b
+            assert lam[b] == refs[b]["lam"], b
+    finally:
+        h.close()
+
+
 def test_batched_single_node_with_the_lds_kernel(oracle_mod, B, monkeypatch):
     monkeypatch.setenv("NIMBLE_TUNE_RESIDENT_GENERIC", "1")
     w = W.make_config(2, batch=5)
