@@ -386,6 +386,11 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
         if (const char *env = std::getenv("NIMBLE_TUNE_REDUCE_BLOCKS_PER_CU"))
             if (std::atoi(env) > 0) per_cu = std::atoi(env);
         d.reduce_blocks = t->n_cu * per_cu;
+        // the record kernel: 78 VGPRs, so six of its four-wave workgroups per compute unit
+        int rec_per_cu = 6;
+        if (const char *env = std::getenv("NIMBLE_TUNE_RECORD_BLOCKS_PER_CU"))
+            if (std::atoi(env) > 0) rec_per_cu = std::atoi(env);
+        d.rec_blocks = t->n_cu * rec_per_cu;
     }
 #undef NIMBLE_TRY
 

@@ -82,6 +82,7 @@ struct DeviceTopo {
     int32_t n_update_blocks;
     int32_t update_lanes;      // lanes per link in the length update: 4 or 16
     int32_t reduce_blocks;     // 256-thread blocks of the link-load reduce (fills the chip once)
+    int32_t rec_blocks;        // most workgroups of the record kernel (resident at once)
 };
 
 void launch_stream_read(const void *buf, size_t bytes, void *sink, hipStream_t s);

@@ -537,12 +537,14 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, uint8_t *choice, uint32_t
                         hipStream_t s)
 {
     if (t.n_records > 0) {
-        // records per wave: up to four (the next one is prefetched while one is scanned) once
-        // there are more records than wave slots
-        int rpw = (t.n_records + 4095) / 4096;
-        if (rpw > 4) rpw = 4;
-        if (t.rec_per_wave > 0) rpw = t.rec_per_wave;
-        const int rec_grid = (t.n_records + kRecWaves * rpw - 1) / (kRecWaves * rpw);
+        // one record per wave while the waves fit the chip at once; beyond that the grid is
+        // what is resident at once (the same number of workgroups on every compute unit) and a
+        // wave walks records rec, rec + n_waves, ..., the next one prefetched while one is
+        // scanned
+        int rec_grid = (t.n_records + kRecWaves - 1) / kRecWaves;
+        if (rec_grid > t.rec_blocks) rec_grid = t.rec_blocks;
+        if (t.rec_per_wave > 0)
+            rec_grid = (t.n_records + kRecWaves * t.rec_per_wave - 1) / (kRecWaves * t.rec_per_wave);
         // two quads per lane cover every commodity (the layout's own choice of L does)
         const bool two = (t.pmax + 3) / 4 <= 2 * L;
 #define NIMBLE_REC_LAUNCH(SS)                                                                  \
