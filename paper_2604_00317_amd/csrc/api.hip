@@ -407,7 +407,7 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     // per piece
     t->bytes_reduce += 2048LL * (h.n_pieces - h.n_pieces_uniform) + 8LL * h.n_pieces +
                        (128LL + 512 + 4096) * h.n_tile_items +
-                       512LL * static_cast<int64_t>(h.tile_pres.size() / 64 - 1) +
+                       64LL * static_cast<int64_t>(h.tile_pres.size() / 64 - 1) +
                        // strip items: base, presence, masks and slots per lane (20 B), one line
                        // of choices and one of demands per column, a partial per unit and row
                        64LL * (20 + 8 + 64 + 8) * h.n_strip_items;

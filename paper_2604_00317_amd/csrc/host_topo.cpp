@@ -474,24 +474,32 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
     }
     // A piece whose non-zero masks are all equal (the usual case when the candidates of a
     // fabric are enumerated by a product rule) is UNIFORM: it is stored as that one mask plus a
-    // presence bit per commodity.  Work items: pieces sorted by (numbering, window, kind, link),
-    // up to kTileRows pieces of one window and one kind per item.  Dense pieces keep their
+    // presence bit per commodity.  Work items: pieces sorted by (numbering, window, kind,
+    // covered commodities, link), up to kTileRows pieces of one window, one kind and (uniform
+    // pieces) one set of covered commodities per item: the rows of a uniform item have the same
+    // presence bits, so the kernel clears the demands of the commodities outside once per item.  Dense pieces keep their
     // 512 masks, lane-contiguous like the masks of a pass; a uniform item stores, per column,
     // one byte of presence bits for each of its rows.
     t.n_pieces = static_cast<int32_t>(pieces.size());
     t.n_pieces_uniform = 0;
     std::vector<uint32_t> piece_umask(pieces.size(), 0u);     // 0: dense
+    // which commodities of the window a uniform piece covers, hashed: pieces that cover the
+    // same commodities are packed into the same items (see the shared-presence flag below)
+    std::vector<uint64_t> piece_phash(pieces.size(), 0ull);
     for (size_t i = 0; i < pieces.size(); ++i) {
         uint32_t m = 0u;
+        uint64_t hsh = 1469598103934665603ull;
         bool uniform = !t.tiles_dense_only;
         for (size_t q = 0; q < 512 && uniform; ++q) {
             const uint32_t v = piece_mask[pieces[i].mask_at + q];
+            hsh = (hsh ^ (v != 0u ? 1u : 0u)) * 1099511628211ull;
             if (v == 0u) continue;
             if (m == 0u) m = v;
             else if (m != v) uniform = false;
         }
         if (uniform && m != 0u) {
             piece_umask[i] = m;
+            piece_phash[i] = hsh;
             t.n_pieces_uniform += 1;
         }
     }
@@ -505,12 +513,22 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
             if (px.sig != py.sig) return px.sig < py.sig;
             if (px.window != py.window) return px.window < py.window;
             if (kind(x) != kind(y)) return kind(x) < kind(y);
+            if (piece_phash[x] != piece_phash[y]) return piece_phash[x] < piece_phash[y];
             return px.link < py.link;
         });
         t.tile_mask.clear();
         t.tile_pres.clear();
         t.tile_desc.clear();
         int32_t n_dense = 0, n_uitems = 0;
+        // do two uniform pieces cover the same commodities of their window?
+        auto same_cover = [&](int32_t x, int32_t y) {
+            if (piece_phash[x] != piece_phash[y]) return false;
+            for (size_t q = 0; q < 512; ++q)
+                if ((piece_mask[pieces[x].mask_at + q] != 0u) !=
+                    (piece_mask[pieces[y].mask_at + q] != 0u))
+                    return false;
+            return true;
+        };
         for (size_t i = 0; i < ord.size(); ++i) {
             const int32_t pi = ord[i];
             const Piece &pc = pieces[pi];
@@ -518,6 +536,7 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
             const bool fresh = i == 0 || pieces[ord[i - 1]].sig != pc.sig ||
                                pieces[ord[i - 1]].window != pc.window ||
                                kind(ord[i - 1]) != kind(pi) ||
+                               (uni && !same_cover(ord[i - 1], pi)) ||
                                t.tile_desc[t.tile_desc.size() - kTileDescInts + 2] == kTileRows;
             if (fresh) {
                 t.tile_desc.resize(t.tile_desc.size() + kTileDescInts, 0);
@@ -529,7 +548,7 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                 d[3] = uni ? n_uitems : n_dense;
                 if (uni) {
                     n_uitems += 1;
-                    t.tile_pres.resize(t.tile_pres.size() + 64, 0ull);
+                    t.tile_pres.resize(t.tile_pres.size() + 64, 0u);
                 }
             }
             int32_t *d = &t.tile_desc[t.tile_desc.size() - kTileDescInts];
@@ -537,12 +556,14 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
             item_piece[item_piece.size() - kTileRows + r] = pi;
             if (uni) {
                 d[16 + r] = static_cast<int32_t>(piece_umask[pi]);
-                uint64_t *pres = &t.tile_pres[t.tile_pres.size() - 64];
+                // the same bits for every piece of the item (same_cover)
+                uint8_t *pres = &t.tile_pres[t.tile_pres.size() - 64];
                 for (size_t c = 0; c < 64; ++c) {
-                    uint64_t bits = 0;
+                    uint8_t bits = 0;
                     for (size_t w8 = 0; w8 < 8; ++w8)
-                        if (piece_mask[pc.mask_at + c * 8 + w8] != 0u) bits |= 1ull << w8;
-                    pres[c] |= bits << (8 * r);
+                        if (piece_mask[pc.mask_at + c * 8 + w8] != 0u)
+                            bits = static_cast<uint8_t>(bits | (1u << w8));
+                    pres[c] = bits;
                 }
             } else {
                 const size_t at = t.tile_mask.size();
@@ -557,7 +578,7 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
         t.n_tile_items = static_cast<int32_t>(t.tile_desc.size() / kTileDescInts);
         if (t.tile_desc.empty()) t.tile_desc.assign(kTileDescInts, 0);
         t.tile_mask.resize(t.tile_mask.size() + 512, 0u);      // one spare piece keeps it loadable
-        t.tile_pres.resize(t.tile_pres.size() + 64, 0ull);
+        t.tile_pres.resize(t.tile_pres.size() + 64, 0u);
         piece_mask.clear(); piece_mask.shrink_to_fit();
     }
 
@@ -1086,7 +1107,7 @@ extern "C" nimble_status_t nimble_host_build_reverse_streaming(int32_t n_links, 
                 for (int32_t s8 = 0; s8 < 8; ++s8) {
                     uint32_t m;
                     if (uni)
-                        m = ((t.tile_pres[64 * static_cast<size_t>(d[3]) + c] >> (8 * r + s8)) & 1ull)
+                        m = ((t.tile_pres[64 * static_cast<size_t>(d[3]) + c] >> s8) & 1u)
                                 ? static_cast<uint32_t>(d[16 + r]) : 0u;
                     else
                         m = t.tile_mask[at + (s8 / 4) * 256 + c * 4 + (s8 % 4)];

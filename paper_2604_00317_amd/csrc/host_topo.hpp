@@ -65,8 +65,8 @@ constexpr int32_t kSinglesPerLane = 8;        // a single-pair chunk holds 16 * 
 //                                        each, lane-contiguous like the masks of a pass);
 //                                        uniform: index of the item's block in tile_pres
 //   [8..15] slot of piece 0..7 (-1: none)      [16..23] uniform: mask of piece 0..7
-// tile_pres holds, per uniform item, 64 words of 64 bits: word c, byte r, bit s = commodity
-// window + 8c + s is present in piece r.
+// The pieces of a uniform item cover the same commodities; tile_pres holds, per uniform item,
+// 64 bytes: byte c, bit s = commodity window + 8c + s is present in the item's pieces.
 constexpr int32_t kTileIds = 512;
 constexpr int32_t kTileRows = 8;
 constexpr int32_t kTileDescInts = 32;
@@ -156,7 +156,7 @@ struct HostTopo {
     bool tiles_dense_only = false;       // option: never store a piece as uniform
     std::vector<int32_t> tile_desc;      // [kTileDescInts * n_tile_items]
     std::vector<uint32_t> tile_mask;     // [512 * (dense pieces + 1)]
-    std::vector<uint64_t> tile_pres;     // [64 * (uniform items + 1)]
+    std::vector<uint8_t> tile_pres;      // [64 * (uniform items + 1)]
     int32_t n_strip_items = 0, n_strip_rows = 0;
     std::vector<uint32_t> strip_base;    // [64 * (n_strip_items + 1)]
     std::vector<uint64_t> strip_pres;    // [64 * (n_strip_items + 1)]

@@ -52,7 +52,7 @@ struct DeviceTopo {
     int32_t n_tile_items;
     const int32_t *tile_desc;         // [32 * n_tile_items]
     const uint32_t *tile_mask;        // [512 * (dense pieces + 1)]
-    const uint64_t *tile_pres;        // [64 * (uniform items + 1)] presence bytes
+    const uint8_t *tile_pres;         // [64 * (uniform items + 1)] presence bytes
     int32_t tile_item_cost;           // weight of an item against an octet pass (wave split)
     // strip items: 8 units of 8 octets shared by up to 8 links each
     int32_t n_strip_items;

@@ -73,7 +73,7 @@ struct PersistentArgs {
     uint32_t pad_comm;
     const int32_t *tile_desc;
     const uint32_t *tile_mask;
-    const uint64_t *tile_pres;
+    const uint8_t *tile_pres;
     double *demand1n, *demand1t, *demand2t;
     int n_strip_items;
     const uint32_t *strip_base, *strip_mask;

@@ -310,7 +310,7 @@ struct ReduceArgs {
     const double *demand1n;
     const int32_t *tile_desc;
     const uint32_t *tile_mask;
-    const uint64_t *tile_pres;
+    const uint8_t *tile_pres;
     const double *demand1t, *demand2t;
     const int32_t *pass_first_slot;
     const uint32_t *oct_base, *oct_mask;

@@ -353,7 +353,8 @@ __device__ __forceinline__ void reduce_flat_phase(
 // their eight choices and eight demands once (coalesced over the wave) and uses them for every
 // piece of the item, whose masks arrive as two 16-byte loads per lane and piece.  No per-hit
 // gather is left.  Uniform pieces (one mask value plus presence bits) need no mask loads at
-// all: one 8-byte word per lane holds the presence bytes of all rows of the item.  The eight
+// all: the pieces of an item cover the same commodities, so one presence byte per lane serves
+// all rows of the item.  The eight
 // per-lane row sums are added over the wave by wave_sum8 and lanes 0..7 store one partial each.
 // MODE 1 (width rho): every commodity with a non-zero mask counts once.
 // Position of commodity number nb in the window-transposed demand copies: inside a window of
@@ -367,7 +368,7 @@ __device__ __forceinline__ int tile_demand_index(int nb)
 template <int MODE>
 __device__ __forceinline__ void reduce_tile_phase(
     int n_items, const int32_t *__restrict__ tile_desc, const uint32_t *__restrict__ tile_mask,
-    const uint64_t *__restrict__ tile_pres,
+    const uint8_t *__restrict__ tile_pres,
     const uint8_t *__restrict__ choice, const double *__restrict__ demand1t,
     const uint8_t *__restrict__ choice2, const double *__restrict__ demand2t,
     double *__restrict__ partial, int wave, int n_waves, int lane)
@@ -399,20 +400,28 @@ __device__ __forceinline__ void reduce_tile_phase(
         double acc[kTileRows];
         if ((flags & 2) != 0) {
             // uniform pieces: one mask per piece (wave-uniform) and one presence byte per
-            // lane and piece; rows past the last piece have presence 0
-            const uint64_t pres = tile_pres[size_t(first) * 64 + lane];
+            // lane (the same for every piece of the item).  A hit adds the demand
+            // as fma(d, 1.0, a) and a miss as fma(d, 0.0, a): the same sums as plain additions
+            // (demands are finite), one instruction per pair less than masking both halves.
+            // the rows of an item cover the same commodities (the layout packs them so): the
+            // demands of the others are cleared once, and a row only tests its mask
+            const uint32_t p0 = tile_pres[size_t(first) * 64 + lane];
+            double dz[8];
+#pragma unroll
+            for (int sl = 0; sl < 8; ++sl) dz[sl] = ((p0 >> sl) & 1u) != 0u ? dm[sl] : 0.0;
 #pragma unroll
             for (int r = 0; r < kTileRows; ++r) {
-                const uint32_t mr = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(d[16 + r]));
-                const uint32_t pb = static_cast<uint32_t>(pres >> (8 * r)) & 0xFFu;
+                // rows past the last piece carry an empty mask
+                const uint32_t mr = r < n_rows ? static_cast<uint32_t>(
+                                                     __builtin_amdgcn_readfirstlane(d[16 + r]))
+                                               : 0u;
                 double a = 0.0;
 #pragma unroll
                 for (int sl = 0; sl < 8; ++sl) {
-                    uint32_t h = pb >> sl;
-                    if constexpr (MODE == 0) h &= mr >> c8[sl];
-                    const int hit = __builtin_amdgcn_sbfe(static_cast<int>(h), 0u, 1u);
-                    a = a + __hiloint2double(__double2hiint(dm[sl]) & hit,
-                                             __double2loint(dm[sl]) & hit);
+                    uint32_t h = 1u;
+                    if constexpr (MODE == 0) h = (mr >> c8[sl]) & 1u;
+                    else h = mr != 0u ? 1u : 0u;
+                    a = __builtin_fma(dz[sl], static_cast<double>(h), a);
                 }
                 acc[r] = a;
             }
