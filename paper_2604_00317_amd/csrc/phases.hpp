@@ -490,10 +490,11 @@ __device__ __forceinline__ void reduce_strip_phase(
             ch = *reinterpret_cast<const uint2 *>((sig ? choice2 : choice) + base);
         const u32x4 *dq = reinterpret_cast<const u32x4 *>((sig ? demand2 : demand1n) + base);
         const u32x4 q0 = dq[0], q1 = dq[1], q2 = dq[2], q3 = dq[3];
-        const int dlo[8] = {int(q0.x), int(q0.z), int(q1.x), int(q1.z),
-                            int(q2.x), int(q2.z), int(q3.x), int(q3.z)};
-        const int dhi[8] = {int(q0.y), int(q0.w), int(q1.y), int(q1.w),
-                            int(q2.y), int(q2.w), int(q3.y), int(q3.w)};
+        const double dm[8] = {
+            __hiloint2double(int(q0.y), int(q0.x)), __hiloint2double(int(q0.w), int(q0.z)),
+            __hiloint2double(int(q1.y), int(q1.x)), __hiloint2double(int(q1.w), int(q1.z)),
+            __hiloint2double(int(q2.y), int(q2.x)), __hiloint2double(int(q2.w), int(q2.z)),
+            __hiloint2double(int(q3.y), int(q3.x)), __hiloint2double(int(q3.w), int(q3.z))};
         uint32_t c8[8];
 #pragma unroll
         for (int sl = 0; sl < 8; ++sl) c8[sl] = ((sl < 4 ? ch.x : ch.y) >> (8 * (sl & 3))) & 31u;
@@ -504,10 +505,11 @@ __device__ __forceinline__ void reduce_strip_phase(
             double a = 0.0;
 #pragma unroll
             for (int sl = 0; sl < 8; ++sl) {
-                uint32_t h = pb >> sl;
+                // a hit adds the demand as fma(d, 1.0, a), a miss as fma(d, 0.0, a): the same
+                // sums as plain additions (demands are finite)
+                uint32_t h = (pb >> sl) & 1u;
                 if constexpr (MODE == 0) h &= mr[r] >> c8[sl];
-                const int hit = __builtin_amdgcn_sbfe(static_cast<int>(h), 0u, 1u);
-                a = a + __hiloint2double(dhi[sl] & hit, dlo[sl] & hit);
+                a = __builtin_fma(dm[sl], static_cast<double>(h), a);
             }
             acc[r] = a;
         }
