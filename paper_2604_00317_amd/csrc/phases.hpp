@@ -441,14 +441,11 @@ __device__ __forceinline__ void reduce_tile_phase(
                 double a = 0.0;
 #pragma unroll
                 for (int sl = 0; sl < 8; ++sl) {
-                    // all ones where the commodity routes through the link, else zero
-                    int hit;
-                    if constexpr (MODE == 0)
-                        hit = __builtin_amdgcn_sbfe(static_cast<int>(mk[sl]), c8[sl], 1u);
-                    else
-                        hit = mk[sl] != 0u ? -1 : 0;
-                    a = a + __hiloint2double(__double2hiint(dm[sl]) & hit,
-                                             __double2loint(dm[sl]) & hit);
+                    // 1 where the commodity routes through the link, else 0
+                    uint32_t h;
+                    if constexpr (MODE == 0) h = (mk[sl] >> c8[sl]) & 1u;
+                    else h = mk[sl] != 0u ? 1u : 0u;
+                    a = __builtin_fma(dm[sl], static_cast<double>(h), a);
                 }
                 acc[r] = a;
             }
