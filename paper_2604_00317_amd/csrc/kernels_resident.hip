@@ -340,10 +340,9 @@ __global__ __launch_bounds__(1024) void k_resident_reg(
     };
     for (int it = 0; it < iters; ++it) {
         if (has_k) {
-            double best = __builtin_inf();
-            int bj = 0;
             // the prices of four candidates are requested before the first is used
             constexpr int kBatch = MAXP < 4 ? MAXP : 4;
+            double c[MAXP];
 #pragma unroll
             for (int j0 = 0; j0 < MAXP; j0 += kBatch) {
                 double pv[kBatch][MAXL];
@@ -353,18 +352,24 @@ __global__ __launch_bounds__(1024) void k_resident_reg(
                     for (int i = 0; i < MAXL; ++i) pv[j][i] = *pp[j0 + j][i];
 #pragma unroll
                 for (int j = 0; j < kBatch; ++j) {
-                    double c = pv[j][0];                     // 0 + p is p
+                    double cj = pv[j][0];                    // 0 + p is p
 #pragma unroll
                     for (int i = 1; i < MAXL; ++i) {
-                        if constexpr (MAXC) c = (pv[j][i] > c) ? pv[j][i] : c;
-                        else c = c + pv[j][i];
+                        if constexpr (MAXC) cj = (pv[j][i] > cj) ? pv[j][i] : cj;
+                        else cj = cj + pv[j][i];
                     }
-                    if (c < best) {
-                        best = c;
-                        bj = j0 + j;
-                    }
+                    c[j0 + j] = cj;
                 }
             }
+            // the minimum, then the lowest candidate that holds it: what the strict `<` scan
+            // in candidate order picks (all +inf, a commodity without traffic-bearing
+            // candidates, resolves to candidate 0 either way)
+            double best = c[0];
+#pragma unroll
+            for (int j = 1; j < MAXP; ++j) best = fast_min_f64(best, c[j]);
+            int bj = MAXP - 1;
+#pragma unroll
+            for (int j = MAXP - 2; j >= 0; --j) bj = (c[j] == best) ? j : bj;
             choice[t] = static_cast<uint8_t>(bj);
             tally += 1ull << (8 * bj);
             if ((it & 127) == 127) flush();
@@ -378,12 +383,11 @@ __global__ __launch_bounds__(1024) void k_resident_reg(
             double load = 0.0;
 #pragma unroll
             for (int i = 0; i < MAXROW; ++i) {
-                // all ones where the commodity's choice uses the link (adding +0.0 otherwise
-                // leaves the sum as it is); a choice is below 8, so it stays inside its byte
-                const int hit = __builtin_amdgcn_sbfe(static_cast<int>(wb4[i / 4] >> ch[i]),
-                                                      8 * (i % 4), 1);
-                load = load + __hiloint2double(__double2hiint(dm[i]) & hit,
-                                               __double2loint(dm[i]) & hit);
+                // 1 where the commodity's choice uses the link (a choice is below 8, so it
+                // stays inside its mask byte); fma(d, 1.0, load) rounds like load + d, and
+                // fma(d, 0.0, load) leaves the sum as it is (demands are finite)
+                const uint32_t h = ((wb4[i / 4] >> ch[i]) >> (8 * (i % 4))) & 1u;
+                load = __builtin_fma(dm[i], static_cast<double>(h), load);
             }
             const double u = load * ic;
             S = S + u;
