@@ -43,29 +43,56 @@ __global__ __launch_bounds__(kAdBlock) void k_ad_terms(int K, const int32_t *__r
     term[k] = demand[k] * c;
 }
 
-// chunk sums: thread c adds the terms 256c .. 256c + 255 in order; `index` (may be null)
-// redirects term i to x[index[i]]
+// chunk sums: chunk c is the sum of the terms 256c .. 256c + 255 added in order; `index` (may be
+// null) redirects term i to x[index[i]].  A workgroup owns kAdChunksPerBlock chunks: all its
+// threads fetch the terms side by side (coalesced) into LDS, a padded row per chunk so that
+// the rows start in different banks, and one thread per chunk then adds its row in order.
+constexpr int kAdChunksPerBlock = 16;
+constexpr int kAdRow = kAdChunk + 1;
+
 __global__ __launch_bounds__(kAdBlock) void k_ad_chunks(int n, const double *__restrict__ x,
                                                         const int32_t *__restrict__ index,
                                                         const int32_t *__restrict__ flags,
                                                         double *__restrict__ chunk)
 {
+    __shared__ double s_terms[kAdChunksPerBlock * kAdRow];
     if (flags[0]) return;
-    const int c = blockIdx.x * kAdBlock + threadIdx.x;
-    const int first = c * kAdChunk;
-    if (first >= n) return;
-    const int end = first + kAdChunk < n ? first + kAdChunk : n;
-    double s = 0.0;
-    for (int i = first; i < end; ++i) s = s + x[index ? index[i] : i];
-    chunk[c] = s;
+    const int c0 = blockIdx.x * kAdChunksPerBlock;
+    const int first = c0 * kAdChunk;
+    for (int q = threadIdx.x; q < kAdChunksPerBlock * kAdChunk; q += kAdBlock) {
+        const int i = first + q;
+        double v = 0.0;
+        if (i < n) v = x[index ? index[i] : i];
+        s_terms[(q / kAdChunk) * kAdRow + (q % kAdChunk)] = v;
+    }
+    __syncthreads();
+    const int c = c0 + threadIdx.x;
+    if (threadIdx.x < kAdChunksPerBlock && c * kAdChunk < n) {
+        const int len = n - c * kAdChunk < kAdChunk ? n - c * kAdChunk : kAdChunk;
+        const double *row = s_terms + threadIdx.x * kAdRow;
+        double s = 0.0;
+        for (int i = 0; i < len; ++i) s = s + row[i];
+        chunk[c] = s;
+    }
 }
 
-// ascal: [0] W, [1] bound of this check, [2] best bound, [3] lambda
-__global__ void k_ad_lb(int n_alpha, const double *__restrict__ chunk_alpha, int n_d,
-                        const double *__restrict__ chunk_d, const int32_t *__restrict__ flags,
-                        double *__restrict__ ascal)
+// ascal: [0] W, [1] bound of this check, [2] best bound, [3] lambda.  The chunk sums are added
+// in order by one thread, from LDS.
+__global__ __launch_bounds__(kAdBlock) void k_ad_lb(int n_alpha, const double *chunk_alpha,
+                                                    int n_d, const double *chunk_d,
+                                                    const int32_t *__restrict__ flags,
+                                                    double *__restrict__ ascal, bool staged)
 {
-    if (flags[0] || threadIdx.x != 0 || blockIdx.x != 0) return;
+    extern __shared__ double s_chunks[];
+    if (flags[0]) return;
+    if (staged) {
+        for (int i = threadIdx.x; i < n_alpha; i += kAdBlock) s_chunks[i] = chunk_alpha[i];
+        for (int i = threadIdx.x; i < n_d; i += kAdBlock) s_chunks[n_alpha + i] = chunk_d[i];
+        __syncthreads();
+        chunk_alpha = s_chunks;
+        chunk_d = s_chunks + n_alpha;
+    }
+    if (threadIdx.x != 0) return;
     double alpha = 0.0, D = 0.0;
     for (int i = 0; i < n_alpha; ++i) alpha = alpha + chunk_alpha[i];
     for (int i = 0; i < n_d; ++i) D = D + chunk_d[i];
@@ -234,12 +261,17 @@ void launch_ad_bound(const DeviceTopo &t, const AdaptiveState &a, const uint8_t 
         hipLaunchKernelGGL(k_ad_terms<false>, dim3(gk), dim3(kAdBlock), 0, s, t.K, t.comm_ptr,
                            t.path_ptr, t.path_links, t.price, choice, demand, a.flags, a.term);
     const int n_alpha = (t.K + kAdChunk - 1) / kAdChunk, n_d = (t.E + kAdChunk - 1) / kAdChunk;
-    hipLaunchKernelGGL(k_ad_chunks, dim3((n_alpha + kAdBlock - 1) / kAdBlock), dim3(kAdBlock), 0, s,
-                       t.K, a.term, static_cast<const int32_t *>(nullptr), a.flags, a.chunk);
-    hipLaunchKernelGGL(k_ad_chunks, dim3((n_d + kAdBlock - 1) / kAdBlock), dim3(kAdBlock), 0, s,
-                       t.E, t.len, a.pos_of_link, a.flags, a.chunk + n_alpha);
-    hipLaunchKernelGGL(k_ad_lb, dim3(1), dim3(64), 0, s, n_alpha, a.chunk, n_d, a.chunk + n_alpha,
-                       a.flags, a.ascal);
+    hipLaunchKernelGGL(k_ad_chunks,
+                       dim3((n_alpha + kAdChunksPerBlock - 1) / kAdChunksPerBlock), dim3(kAdBlock),
+                       0, s, t.K, a.term, static_cast<const int32_t *>(nullptr), a.flags, a.chunk);
+    hipLaunchKernelGGL(k_ad_chunks, dim3((n_d + kAdChunksPerBlock - 1) / kAdChunksPerBlock),
+                       dim3(kAdBlock), 0, s, t.E, t.len, a.pos_of_link, a.flags,
+                       a.chunk + n_alpha);
+    // the chunk sums go through LDS while they fit (32 KB: about a million commodities)
+    const size_t lb_lds = sizeof(double) * (static_cast<size_t>(n_alpha) + n_d);
+    const bool staged = lb_lds <= 32 * 1024;
+    hipLaunchKernelGGL(k_ad_lb, dim3(1), dim3(kAdBlock), staged ? lb_lds : 0, s, n_alpha, a.chunk,
+                       n_d, a.chunk + n_alpha, a.flags, a.ascal, staged);
 }
 
 void launch_ad_update(const DeviceTopo &t, const AdaptiveState &a, double eps, hipStream_t s)
