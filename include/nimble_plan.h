@@ -339,13 +339,14 @@ nimble_status_t nimble_host_records_roundtrip(int32_t n_links, int32_t n_comm,
 
 /*
  * Host-only helper (no device call): sizes of the device layout nimble_topo_create would build.
- * out is host int64 [15]: (commodity, window) pairs of the reverse CSR; octets (groups of 8
+ * out is host int64 [16]: (commodity, window) pairs of the reverse CSR; octets (groups of 8
  * consecutive commodity ids with one mask each); single pairs; octets numbered by the second
  * commodity numbering; single-pair chunks; partial-sum slots; forward records; indices per
  * candidate in a record; link blocks of the fused reduce + update kernel (0: not used); octets
  * including padding; dense (link, window of 512 commodities) pieces; work items of up to 8
  * pieces; pieces stored as one mask plus presence bits; strip items (8 units of 8 octets x up
- * to 8 links that share them); links whose row lives in a strip.
+ * to 8 links that share them); links whose row lives in a strip; 1 if the bodies of the forward
+ * records are laid out lane by lane (the record kernel then keeps them in registers), else 0.
  */
 nimble_status_t nimble_host_layout_stats(int32_t n_links, int32_t n_comm,
                                          const int32_t *comm_path_ptr, int32_t n_paths,

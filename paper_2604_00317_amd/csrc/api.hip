@@ -264,9 +264,13 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     d.rec_per_wave = 0;
     if (const char *env = std::getenv("NIMBLE_TUNE_RECORDS_PER_WAVE"))
         if (std::atoi(env) >= 1 && std::atoi(env) <= 64) d.rec_per_wave = std::atoi(env);
+    d.rec_lane_major = h.rec_lane_major;
+    // (a lane-major layout has its lanes per commodity built in)
     if (const char *env = std::getenv("NIMBLE_TUNE_RECORD_LANES")) {
         const int v = std::atoi(env);
-        if (v == 1 || v == 2 || v == 4 || v == 8 || v == 16 || v == 32 || v == 64) d.rec_lanes = v;
+        if (!d.rec_lane_major &&
+            (v == 1 || v == 2 || v == 4 || v == 8 || v == 16 || v == 32 || v == 64))
+            d.rec_lanes = v;
     }
     if (std::getenv("NIMBLE_TUNE_NO_RECORDS")) d.n_records = 0;
     d.pmax = h.pmax;

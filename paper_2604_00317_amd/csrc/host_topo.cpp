@@ -87,6 +87,7 @@ void read_layout_options(HostTopo &t)
         }
     };
     number("NIMBLE_TUNE_RECORD_COMM_CAP", 1, kRecMaxComm, t.rec_comm_cap);
+    number("NIMBLE_TUNE_RECORD_LANE_MAJOR", 0, 1, t.rec_lane_major);
     number("NIMBLE_TUNE_BLOCK_PASSES", 1, 1024, t.blk_passes);
     number("NIMBLE_TUNE_TILES", 0, 1, t.tiles);
     number("NIMBLE_TUNE_TILE_MIN_ITEMS", 1, kTileIds, t.tile_min_items);
@@ -736,6 +737,7 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
         auto align4 = [](int32_t x) { return (x + 3) & ~3; };
         auto bytes_needed = [&](int32_t nl, int32_t nk, int32_t npad) {
             (void)nl;    // the link table has a fixed size
+            if (t.rec_lane_major) return kRecBytes;      // a slot per commodity: always fits
             return kRecTable + kRecHeader + 4 * nk + 2 * align4(2 * (nk + 1)) + npad * S;
         };
         // lanes per commodity in the record kernel: a lane scans two quads of the largest
@@ -748,7 +750,14 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
             t.rec_lanes = lanes;
             if (t.rec_comm_cap <= 0) t.rec_comm_cap = 64 / lanes;
             if (t.rec_comm_cap > kRecMaxComm) t.rec_comm_cap = kRecMaxComm;
+            // the lane-major body needs two quads per lane to cover every commodity, paths
+            // that fit five words per quad, a second lane per slot for the record's own words,
+            // and 4 KiB records
+            t.rec_lane_major = (t.rec_lane_major != 0 && S <= kRecLaneSteps && lanes >= 2 &&
+                                quads <= 2 * lanes && kRecBytes == 4096) ? 1 : 0;
+            if (t.rec_lane_major && t.rec_comm_cap > 64 / lanes) t.rec_comm_cap = 64 / lanes;
         }
+        const bool lane_major = t.rec_lane_major != 0;
         bool ok = true;
         int32_t k = 0;
         while (k < n_comm && ok) {
@@ -824,8 +833,9 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                     if (v < 0xFFFEu) v = static_cast<uint16_t>(rank[v]);
             }
             for (auto &v : loc16) {
-                if (v == 0xFFFFu) v = static_cast<uint16_t>(nl);          // the +0.0 price slot
-                else if (v == 0xFFFEu) v = static_cast<uint16_t>(nl + 1); // the +inf price slot
+                // the +0.0 and the +inf price slot
+                if (v == 0xFFFFu) v = static_cast<uint16_t>(lane_major ? kRecZeroSlot : nl);
+                else if (v == 0xFFFEu) v = static_cast<uint16_t>(lane_major ? kRecInfSlot : nl + 1);
             }
             t.records.resize(static_cast<size_t>(t.n_records + 1) * kRecBytes, 0);
             uint8_t *r = t.records.data() + static_cast<size_t>(t.n_records) * kRecBytes;
@@ -849,6 +859,41 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                     }
             }
             uint8_t *body = r + kRecTable;
+            if (lane_major) {
+                const int32_t L = t.rec_lanes;
+                std::vector<uint32_t> words(64 * kRecLaneWords, 0u);
+                for (int32_t lane = 0; lane < 64; ++lane) {
+                    const int32_t g = lane / L, j = lane % L;
+                    uint32_t *w = &words[static_cast<size_t>(lane) * kRecLaneWords];
+                    const int32_t np_g = g < nk ? cp16[g + 1] - cp16[g] : 0;
+                    for (int32_t q = 0; q < 2; ++q)
+                        for (int32_t i = 0; i < kRecLaneSteps; ++i) {
+                            uint32_t word = 0u;
+                            for (int32_t c4 = 0; c4 < 4; ++c4) {
+                                const int32_t cand = 4 * (j + L * q) + c4;
+                                uint32_t byte = i == 0 ? kRecInfSlot : kRecZeroSlot;
+                                if (cand < np_g && i < S)
+                                    byte = loc16[static_cast<size_t>(cq16[g] + cand) * S + i];
+                                word |= byte << (8 * c4);
+                            }
+                            w[q * kRecLaneSteps + i] = word;
+                        }
+                    if (g < nk) {
+                        w[10] = static_cast<uint32_t>(np_g) | (static_cast<uint32_t>(cp16[g]) << 8);
+                        if (j == 0) w[11] = static_cast<uint32_t>(t.sigma[k0 + g]);
+                    }
+                }
+                words[1 * kRecLaneWords + 11] =
+                    static_cast<uint32_t>(k0) | (static_cast<uint32_t>(nk) << 24);
+                words[static_cast<size_t>(L + 1) * kRecLaneWords + 11] = static_cast<uint32_t>(p0);
+                for (int32_t lane = 0; lane < 64; ++lane)
+                    for (int32_t it = 0; it < 3; ++it)
+                        std::memcpy(body + 1024 * it + 16 * lane,
+                                    &words[static_cast<size_t>(lane) * kRecLaneWords + 4 * it], 16);
+                t.n_records += 1;
+                if (nl > t.rec_max_links) t.rec_max_links = nl;
+                continue;
+            }
             std::memcpy(body + 0, &k0, 4);
             std::memcpy(body + 4, &p0, 4);
             std::memcpy(body + 8, h16, 16);
@@ -873,6 +918,7 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
             t.records.clear();
         }
     }
+    if (t.n_records == 0) t.rec_lane_major = 0;
 }
 
 }  // namespace nimble
@@ -940,6 +986,58 @@ extern "C" nimble_status_t nimble_host_records_roundtrip(int32_t n_links, int32_
     int32_t next_comm = 0;
     for (int32_t ri = 0; ri < t.n_records; ++ri) {
         const uint8_t *rec = t.records.data() + static_cast<size_t>(ri) * nimble::kRecBytes;
+        if (t.rec_lane_major) {
+            // lane-major body: word idx of lane l is in load idx / 4 of that lane
+            const int32_t L = t.rec_lanes;
+            auto word = [&](int32_t lane, int32_t idx) {
+                uint32_t v;
+                std::memcpy(&v, rec + nimble::kRecTable + 1024 * (idx / 4) + 16 * lane +
+                                    4 * (idx % 4), 4);
+                return v;
+            };
+            const int32_t *tab = reinterpret_cast<const int32_t *>(rec);
+            auto link_at = [&](int32_t i) { return tab[4 * (i % 64) + i / 64]; };
+            const int32_t k0 = static_cast<int32_t>(word(1, 11) & 0xFFFFFFu);
+            const int32_t nk = static_cast<int32_t>(word(1, 11) >> 24);
+            const int32_t p0 = static_cast<int32_t>(word(L + 1, 11));
+            if (k0 != next_comm || nk < 1 || nk > 64 / L || p0 != comm_path_ptr[k0])
+                return NIMBLE_ERR_INVALID;
+            next_comm = k0 + nk;
+            for (int32_t g = 0; g < 64 / L; ++g) {
+                const uint32_t meta = word(g * L, 10);
+                for (int32_t j = 1; j < L; ++j)
+                    if (word(g * L + j, 10) != meta) return NIMBLE_ERR_INVALID;
+                if (g >= nk) {
+                    if (meta != 0u) return NIMBLE_ERR_INVALID;
+                    continue;
+                }
+                const int32_t np = static_cast<int32_t>(meta & 0xFFu);
+                const int32_t p_lo = static_cast<int32_t>(meta >> 8);
+                if (p0 + p_lo != comm_path_ptr[k0 + g] ||
+                    np != comm_path_ptr[k0 + g + 1] - comm_path_ptr[k0 + g])
+                    return NIMBLE_ERR_INVALID;
+                if (static_cast<int32_t>(word(g * L, 11)) != t.sigma[k0 + g])
+                    return NIMBLE_ERR_INVALID;
+                for (int32_t cand = 0; cand < 8 * L; ++cand) {
+                    const int32_t j = (cand / 4) % L, q = (cand / 4) / L, c4 = cand % 4;
+                    for (int32_t i = 0; i < nimble::kRecLaneSteps; ++i) {
+                        const int32_t li = static_cast<int32_t>(
+                            (word(g * L + j, q * nimble::kRecLaneSteps + i) >> (8 * c4)) & 0xFFu);
+                        if (cand >= np) {      // an absent candidate costs +inf
+                            if (li != (i == 0 ? nimble::kRecInfSlot : nimble::kRecZeroSlot))
+                                return NIMBLE_ERR_INVALID;
+                            continue;
+                        }
+                        if (li == nimble::kRecZeroSlot) continue;
+                        if (li > nimble::kRecZeroSlot || i >= t.rec_stride)
+                            return NIMBLE_ERR_INVALID;
+                        links_out[w++] = link_at(li);
+                    }
+                    if (cand < np) path_record[p0 + p_lo + cand] = ri;
+                }
+            }
+            continue;
+        }
         const uint8_t *r = rec + nimble::kRecTable;       // the body
         int32_t k0, p0;
         uint16_t h16[8];
@@ -1008,6 +1106,7 @@ extern "C" nimble_status_t nimble_host_layout_stats(int32_t n_links, int32_t n_c
     out[12] = t.n_pieces_uniform;
     out[13] = t.n_strip_items;
     out[14] = t.n_strip_rows;
+    out[15] = t.rec_lane_major;
     return NIMBLE_OK;
 }
 

@@ -117,6 +117,25 @@ constexpr int32_t kBlkMaxLinks = 512;
 //   off_cq   uint16 cq16[nk+1]    the same with every commodity padded to a multiple of 4
 //   off_loc  uint8  loc8[stride][npad]  (index i of every padded candidate, then index i+1,
 //                                        ...): four consecutive candidates are one 32-bit word
+// Lane-major body (paths of at most kRecLaneSteps links, at least two lanes per commodity): the
+// record kernel gives commodity slot g the lanes g*L .. g*L + L - 1 and lane j of a slot the
+// candidates 4j .. 4j+3 (quad A) and 4(j+L) .. 4(j+L)+3 (quad B).  The body is then stored so
+// that the three 16-byte loads of a lane return exactly that lane's 12 words -- the lane keeps
+// them in registers and nothing but the prices goes through LDS:
+//   word i     (i < 5)   step i of quad A: the table indices of its four candidates, one byte each
+//   word 5 + i (i < 5)   step i of quad B
+//   word 10              candidates of the commodity (low byte) | its first candidate relative
+//                        to p0, shifted left by 8; 0 for an empty slot
+//   word 11              lane 0 of a slot: sigma of the commodity; lane 1 of slot 0:
+//                        k0 | nk << 24; lane 1 of slot 1: p0
+// Load `it` of lane l sits at byte kRecTable + 1024*it + 16*l.  Short paths are padded with
+// the index kRecZeroSlot and absent candidates start with kRecInfSlot (their price slots hold
+// +0.0 and +inf), so a record has at most kRecMaxLinks table entries in use.
+constexpr int32_t kRecLaneWords = 12;
+constexpr int32_t kRecLaneSteps = 5;
+constexpr int32_t kRecZeroSlot = 254;
+constexpr int32_t kRecInfSlot = 255;
+
 #ifndef NIMBLE_REC_KB
 #define NIMBLE_REC_KB 4
 #endif
@@ -188,6 +207,8 @@ struct HostTopo {
                                          // the record kernel, 64 / rec_lanes)
     int32_t rec_lanes = 0;               // lanes per commodity the record kernel should use
     int32_t rec_stride = 0;              // indices per candidate = lmax
+    int32_t rec_lane_major = 1;          // option in, layout out: the body of a record is laid
+                                         // out lane by lane (see kRecLaneWords)
     int32_t n_records = 0;
     int32_t rec_max_links = 0;           // largest link table of any record
     std::vector<uint8_t> records;        // [n_records * kRecBytes]

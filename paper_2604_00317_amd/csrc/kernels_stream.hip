@@ -272,6 +272,122 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records,
     }
 }
 
+// The same for records with a lane-major body: the three 16-byte loads of a lane return its own
+// twelve words (the table indices of its two quads, five steps each, and two words about its
+// commodity and the record), so the body never goes through LDS -- only the prices do.  The
+// price slots kRecZeroSlot / kRecInfSlot hold +0.0 / +inf for short paths and absent
+// candidates.  One scan round per record: a record has at most 64 / L commodities.
+template <int L, int S, bool MAXC>
+__global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records,
+                                                       const uint8_t *__restrict__ records,
+                                                       const double *__restrict__ price,
+                                                       uint8_t *__restrict__ choice,
+                                                       uint32_t *__restrict__ count,
+                                                       uint8_t *__restrict__ choice2)
+{
+    static_assert(L >= 2 && S <= kRecLaneSteps, "lane-major records: two lanes, five steps");
+    __shared__ double s_all[kRecWaves * kRecPriceSlots];
+    double *s_price = s_all + (threadIdx.x >> 6) * kRecPriceSlots;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int g = lane / L;
+    const int j = lane % L;
+    const int n_waves = gridDim.x * kRecWaves;
+    int rec = __builtin_amdgcn_readfirstlane(blockIdx.x * kRecWaves + (threadIdx.x >> 6));
+    if (rec >= n_records) return;
+    // in flight while a record is scanned: the table of the record after the next, the prices
+    // and the body of the next one; nothing is requested past the wave's last record
+    auto table_of = [&](int r) {
+        return stream_load(reinterpret_cast<const u32x4 *>(records + size_t(r) * kRecBytes) +
+                           lane);
+    };
+    u32x4 tab = table_of(rec);
+    u32x4 body[3];
+    double pr[4];
+    pr[0] = price[tab.x];
+    pr[1] = price[tab.y];
+    pr[2] = price[tab.z];
+    pr[3] = price[tab.w];
+    if (rec + n_waves < n_records) tab = table_of(rec + n_waves);
+    {
+        const u32x4 *src =
+            reinterpret_cast<const u32x4 *>(records + size_t(rec) * kRecBytes + kRecTable);
+#pragma unroll
+        for (int it = 0; it < 3; ++it) body[it] = stream_load(src + it * kWave + lane);
+    }
+    for (; rec < n_records; rec += n_waves) {           // wave-uniform
+        wave_lds_sync();                                // the previous record is done with LDS
+#pragma unroll
+        for (int q = 0; q < 4; ++q) s_price[lane + q * kWave] = pr[q];
+        if (lane == 0) {                             // after the table prices, in LDS order
+            s_price[kRecZeroSlot] = 0.0;             // pads short paths
+            s_price[kRecInfSlot] = __builtin_inf();  // first step of absent candidates
+        }
+        // this lane's words leave the load registers, which take the next record
+        const uint32_t w[10] = {body[0].x, body[0].y, body[0].z, body[0].w, body[1].x,
+                                body[1].y, body[1].z, body[1].w, body[2].x, body[2].y};
+        const uint32_t meta = body[2].z;
+        const int32_t own = static_cast<int32_t>(body[2].w);
+        if (rec + n_waves < n_records) {
+            pr[0] = price[tab.x];
+            pr[1] = price[tab.y];
+            pr[2] = price[tab.z];
+            pr[3] = price[tab.w];
+            if (rec + 2 * n_waves < n_records) tab = table_of(rec + 2 * n_waves);
+            const u32x4 *src = reinterpret_cast<const u32x4 *>(
+                records + size_t(rec + n_waves) * kRecBytes + kRecTable);
+#pragma unroll
+            for (int it = 0; it < 3; ++it) body[it] = stream_load(src + it * kWave + lane);
+        }
+        wave_lds_sync();
+        auto scan_quad = [&](const uint32_t *wq, double &m4, int &i4) {
+            double cst[4];
+#pragma unroll
+            for (int c4 = 0; c4 < 4; ++c4) {
+                // 0 + p0 is p0: the sum starts at the first price
+                cst[c4] = s_price[(wq[0] >> (8 * c4)) & 0xFFu];
+#pragma unroll
+                for (int i = 1; i < S; ++i) {
+                    const double pe = s_price[(wq[i] >> (8 * c4)) & 0xFFu];
+                    if constexpr (MAXC) cst[c4] = (pe > cst[c4]) ? pe : cst[c4];
+                    else cst[c4] = cst[c4] + pe;
+                }
+            }
+            m4 = fast_min_f64(fast_min_f64(cst[0], cst[1]), fast_min_f64(cst[2], cst[3]));
+            i4 = cst[0] == m4 ? 0 : (cst[1] == m4 ? 1 : (cst[2] == m4 ? 2 : 3));
+        };
+        const int np = static_cast<int>(meta & 0xFFu);
+        const int p_lo = static_cast<int>(meta >> 8);
+        const int ja = 4 * j, jb = 4 * j + 4 * L;
+        double ma, mb;
+        int ia, ib;
+        scan_quad(w, ma, ia);
+        scan_quad(w + kRecLaneSteps, mb, ib);
+        // the strict `<` scan in candidate order: quad A first; absent candidates cost +inf
+        double best = __builtin_inf();
+        int bj = ja < np ? ja : 0x7FFFFFFF;
+        if (ja < np && ma < best) {
+            best = ma;
+            bj = ja + ia;
+        }
+        if (jb < np && mb < best) {
+            best = mb;
+            bj = jb + ib;
+        }
+        bj = group_argmin_two_pass<L>(best, bj);
+        // the record's own words: k0 | nk << 24 in lane 1, p0 in lane L + 1
+        const int k0 = __builtin_amdgcn_readlane(own, 1) & 0xFFFFFF;
+        if (np > 0 && j == 0) {
+            choice[k0 + g] = static_cast<uint8_t>(bj);
+            if (own >= 0) choice2[own] = static_cast<uint8_t>(bj);   // copy in sigma order
+        }
+        // counts are kept only when the choices are not logged per iteration
+        if (count != nullptr) {
+            const int p0 = __builtin_amdgcn_readlane(own, L + 1);
+            if (np > 0 && j == 0) count[p0 + p_lo + bj] += 1u;
+        }
+    }
+}
+
 // Split fractions from the per-iteration choice log: one lane per commodity walks its column
 // of the log and counts in LDS (a padded row per lane, so lanes hit different banks).
 __global__ __launch_bounds__(kWave) void k_histogram(int K, int iters, int pmax, size_t stride,
@@ -545,6 +661,24 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, uint8_t *choice, uint32_t
         if (rec_grid > t.rec_blocks) rec_grid = t.rec_blocks;
         if (t.rec_per_wave > 0)
             rec_grid = (t.n_records + kRecWaves * t.rec_per_wave - 1) / (kRecWaves * t.rec_per_wave);
+        if constexpr (L >= 2) {
+            if (t.rec_lane_major) {
+#define NIMBLE_RECL_LAUNCH(SS)                                                                 \
+    case SS:                                                                                   \
+        hipLaunchKernelGGL((k_argmin_recl<L, SS, MAXC>), dim3(rec_grid),                       \
+                           dim3(kWave * kRecWaves), 0, s, t.n_records, t.records, t.price,     \
+                           choice, count, t.choice2);                                          \
+        return;
+                switch (t.rec_stride) {
+                    NIMBLE_RECL_LAUNCH(1)
+                    NIMBLE_RECL_LAUNCH(2)
+                    NIMBLE_RECL_LAUNCH(3)
+                    NIMBLE_RECL_LAUNCH(4)
+                    NIMBLE_RECL_LAUNCH(5)
+                }
+#undef NIMBLE_RECL_LAUNCH
+            }
+        }
         // two quads per lane cover every commodity (the layout's own choice of L does)
         const bool two = (t.pmax + 3) / 4 <= 2 * L;
 #define NIMBLE_REC_LAUNCH(SS)                                                                  \
