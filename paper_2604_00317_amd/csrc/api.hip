@@ -265,6 +265,7 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     if (const char *env = std::getenv("NIMBLE_TUNE_RECORDS_PER_WAVE"))
         if (std::atoi(env) >= 1 && std::atoi(env) <= 64) d.rec_per_wave = std::atoi(env);
     d.rec_lane_major = h.rec_lane_major;
+    d.rec_table16 = h.rec_table16;
     // (a lane-major layout has its lanes per commodity built in)
     if (const char *env = std::getenv("NIMBLE_TUNE_RECORD_LANES")) {
         const int v = std::atoi(env);
@@ -400,7 +401,7 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
 
     // stored bytes one iteration streams, phase by phase
     if (d.n_records > 0)
-        t->bytes_argmin = static_cast<int64_t>(nimble::kRecBytes) * d.n_records + 2LL * h.K;
+        t->bytes_argmin = static_cast<int64_t>(h.rec_bytes) * d.n_records + 2LL * h.K;
     else
         t->bytes_argmin = 4LL * (h.K + 1) + 4LL * (h.P + 1) + 4LL * h.nnz + 14LL * h.K;
     t->bytes_reduce = 36LL * static_cast<int64_t>(h.oct_base.size()) + 4LL * d.n_passes +

@@ -88,6 +88,7 @@ void read_layout_options(HostTopo &t)
     };
     number("NIMBLE_TUNE_RECORD_COMM_CAP", 1, kRecMaxComm, t.rec_comm_cap);
     number("NIMBLE_TUNE_RECORD_LANE_MAJOR", 0, 1, t.rec_lane_major);
+    number("NIMBLE_TUNE_RECORD_TABLE16", 0, 1, t.rec_table16);
     number("NIMBLE_TUNE_BLOCK_PASSES", 1, 1024, t.blk_passes);
     number("NIMBLE_TUNE_TILES", 0, 1, t.tiles);
     number("NIMBLE_TUNE_TILE_MIN_ITEMS", 1, kTileIds, t.tile_min_items);
@@ -758,6 +759,10 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
             if (t.rec_lane_major && t.rec_comm_cap > 64 / lanes) t.rec_comm_cap = 64 / lanes;
         }
         const bool lane_major = t.rec_lane_major != 0;
+        t.rec_table16 = (lane_major && t.rec_table16 != 0 && n_links <= 65535) ? 1 : 0;
+        const bool table16 = t.rec_table16 != 0;
+        t.rec_bytes = table16 ? kRecBytes16 : kRecBytes;
+        const int32_t table_bytes = table16 ? kRecTable16 : kRecTable;
         bool ok = true;
         int32_t k = 0;
         while (k < n_comm && ok) {
@@ -837,8 +842,8 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                 if (v == 0xFFFFu) v = static_cast<uint16_t>(lane_major ? kRecZeroSlot : nl);
                 else if (v == 0xFFFEu) v = static_cast<uint16_t>(lane_major ? kRecInfSlot : nl + 1);
             }
-            t.records.resize(static_cast<size_t>(t.n_records + 1) * kRecBytes, 0);
-            uint8_t *r = t.records.data() + static_cast<size_t>(t.n_records) * kRecBytes;
+            t.records.resize(static_cast<size_t>(t.n_records + 1) * t.rec_bytes, 0);
+            uint8_t *r = t.records.data() + static_cast<size_t>(t.n_records) * t.rec_bytes;
             const int32_t off_sig = kRecHeader;      // body offsets count from kRecTable
             const int32_t off_cp = off_sig + 4 * nk;
             const int32_t off_cq = off_cp + align4(2 * (nk + 1));
@@ -852,13 +857,16 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
             // gather c of lane l reads table entry 4*l + c, which is link 64*c + l
             {
                 int32_t *tab = reinterpret_cast<int32_t *>(r);
+                uint16_t *tab16 = reinterpret_cast<uint16_t *>(r);
                 for (int32_t l = 0; l < 64; ++l)
                     for (int32_t c = 0; c < 4; ++c) {
                         const int32_t i = 64 * c + l;
-                        tab[4 * l + c] = nl == 0 ? 0 : links[i < nl ? i : nl - 1];
+                        const int32_t e = nl == 0 ? 0 : links[i < nl ? i : nl - 1];
+                        if (table16) tab16[4 * l + c] = static_cast<uint16_t>(e);
+                        else tab[4 * l + c] = e;
                     }
             }
-            uint8_t *body = r + kRecTable;
+            uint8_t *body = r + table_bytes;
             if (lane_major) {
                 const int32_t L = t.rec_lanes;
                 std::vector<uint32_t> words(64 * kRecLaneWords, 0u);
@@ -918,7 +926,11 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
             t.records.clear();
         }
     }
-    if (t.n_records == 0) t.rec_lane_major = 0;
+    if (t.n_records == 0) {
+        t.rec_lane_major = 0;
+        t.rec_table16 = 0;
+    }
+    if (t.rec_bytes == 0) t.rec_bytes = kRecBytes;
 }
 
 }  // namespace nimble
@@ -975,6 +987,7 @@ extern "C" nimble_status_t nimble_host_records_roundtrip(int32_t n_links, int32_
     if (!links_out || !path_record || !n_records_out) return NIMBLE_ERR_INVALID;
     std::vector<double> cap(n_links, 1.0);
     nimble::HostTopo t;
+    nimble::read_layout_options(t);
     nimble::build_host_topo(n_links, cap.data(), n_comm, comm_path_ptr, n_paths, path_link_ptr,
                             path_links, t);
     *n_records_out = t.n_records;
@@ -985,18 +998,23 @@ extern "C" nimble_status_t nimble_host_records_roundtrip(int32_t n_links, int32_
     int64_t w = 0;
     int32_t next_comm = 0;
     for (int32_t ri = 0; ri < t.n_records; ++ri) {
-        const uint8_t *rec = t.records.data() + static_cast<size_t>(ri) * nimble::kRecBytes;
+        const uint8_t *rec = t.records.data() + static_cast<size_t>(ri) * t.rec_bytes;
         if (t.rec_lane_major) {
+            const int32_t table_bytes = t.rec_table16 ? nimble::kRecTable16 : nimble::kRecTable;
             // lane-major body: word idx of lane l is in load idx / 4 of that lane
             const int32_t L = t.rec_lanes;
             auto word = [&](int32_t lane, int32_t idx) {
                 uint32_t v;
-                std::memcpy(&v, rec + nimble::kRecTable + 1024 * (idx / 4) + 16 * lane +
-                                    4 * (idx % 4), 4);
+                std::memcpy(&v, rec + table_bytes + 1024 * (idx / 4) + 16 * lane + 4 * (idx % 4),
+                            4);
                 return v;
             };
             const int32_t *tab = reinterpret_cast<const int32_t *>(rec);
-            auto link_at = [&](int32_t i) { return tab[4 * (i % 64) + i / 64]; };
+            const uint16_t *tab16 = reinterpret_cast<const uint16_t *>(rec);
+            auto link_at = [&](int32_t i) {
+                const int32_t at = 4 * (i % 64) + i / 64;
+                return t.rec_table16 ? static_cast<int32_t>(tab16[at]) : tab[at];
+            };
             const int32_t k0 = static_cast<int32_t>(word(1, 11) & 0xFFFFFFu);
             const int32_t nk = static_cast<int32_t>(word(1, 11) >> 24);
             const int32_t p0 = static_cast<int32_t>(word(L + 1, 11));

@@ -131,6 +131,10 @@ constexpr int32_t kBlkMaxLinks = 512;
 // Load `it` of lane l sits at byte kRecTable + 1024*it + 16*l.  Short paths are padded with
 // the index kRecZeroSlot and absent candidates start with kRecInfSlot (their price slots hold
 // +0.0 and +inf), so a record has at most kRecMaxLinks table entries in use.
+// While link ids fit 16 bits a lane-major record stores its table as 256 uint16 (512 bytes, the
+// same gather order: 8-byte load l holds the links l, 64+l, 128+l, 192+l) and is 3.5 KiB long.
+constexpr int32_t kRecTable16 = 512;
+constexpr int32_t kRecBytes16 = kRecTable16 + 3 * 1024;
 constexpr int32_t kRecLaneWords = 12;
 constexpr int32_t kRecLaneSteps = 5;
 constexpr int32_t kRecZeroSlot = 254;
@@ -209,6 +213,8 @@ struct HostTopo {
     int32_t rec_stride = 0;              // indices per candidate = lmax
     int32_t rec_lane_major = 1;          // option in, layout out: the body of a record is laid
                                          // out lane by lane (see kRecLaneWords)
+    int32_t rec_table16 = 1;             // option in, layout out: 16-bit link tables
+    int32_t rec_bytes = 0;               // bytes of a record: kRecBytes, or kRecBytes16
     int32_t n_records = 0;
     int32_t rec_max_links = 0;           // largest link table of any record
     std::vector<uint8_t> records;        // [n_records * kRecBytes]

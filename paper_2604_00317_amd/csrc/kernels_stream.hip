@@ -277,7 +277,7 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records,
 // commodity and the record), so the body never goes through LDS -- only the prices do.  The
 // price slots kRecZeroSlot / kRecInfSlot hold +0.0 / +inf for short paths and absent
 // candidates.  One scan round per record: a record has at most 64 / L commodities.
-template <int L, int S, bool MAXC>
+template <int L, int S, bool MAXC, bool T16>
 __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records,
                                                        const uint8_t *__restrict__ records,
                                                        const double *__restrict__ price,
@@ -286,6 +286,9 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records,
                                                        uint8_t *__restrict__ choice2)
 {
     static_assert(L >= 2 && S <= kRecLaneSteps, "lane-major records: two lanes, five steps");
+    // T16: the link table is 256 uint16 (8 bytes per lane) and the record 3.5 KiB
+    constexpr int kTab = T16 ? kRecTable16 : kRecTable;
+    constexpr int kRec = T16 ? kRecBytes16 : kRecBytes;
     __shared__ double s_all[kRecWaves * kRecPriceSlots];
     double *s_price = s_all + (threadIdx.x >> 6) * kRecPriceSlots;
     const int lane = threadIdx.x & (kWave - 1);
@@ -296,24 +299,42 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records,
     if (rec >= n_records) return;
     // in flight while a record is scanned: the table of the record after the next, the prices
     // and the body of the next one; nothing is requested past the wave's last record
-    auto table_of = [&](int r) {
-        return stream_load(reinterpret_cast<const u32x4 *>(records + size_t(r) * kRecBytes) +
-                           lane);
+    struct Ids {
+        uint32_t a, b, c, d;        // links lane, 64 + lane, 128 + lane, 192 + lane of the table
     };
-    u32x4 tab = table_of(rec);
+    auto table_of = [&](int r) {
+        Ids ids;
+        const uint8_t *base = records + size_t(r) * kRec;
+        if constexpr (T16) {
+            typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+            const u32x2 v = stream_load(reinterpret_cast<const u32x2 *>(base) + lane);
+            ids.a = v.x & 0xFFFFu;
+            ids.b = v.x >> 16;
+            ids.c = v.y & 0xFFFFu;
+            ids.d = v.y >> 16;
+        } else {
+            const u32x4 v = stream_load(reinterpret_cast<const u32x4 *>(base) + lane);
+            ids.a = v.x;
+            ids.b = v.y;
+            ids.c = v.z;
+            ids.d = v.w;
+        }
+        return ids;
+    };
+    auto body_of = [&](int r, u32x4 (&buf)[3]) {
+        const u32x4 *src = reinterpret_cast<const u32x4 *>(records + size_t(r) * kRec + kTab);
+#pragma unroll
+        for (int it = 0; it < 3; ++it) buf[it] = stream_load(src + it * kWave + lane);
+    };
+    Ids tab = table_of(rec);
     u32x4 body[3];
     double pr[4];
-    pr[0] = price[tab.x];
-    pr[1] = price[tab.y];
-    pr[2] = price[tab.z];
-    pr[3] = price[tab.w];
+    pr[0] = price[tab.a];
+    pr[1] = price[tab.b];
+    pr[2] = price[tab.c];
+    pr[3] = price[tab.d];
     if (rec + n_waves < n_records) tab = table_of(rec + n_waves);
-    {
-        const u32x4 *src =
-            reinterpret_cast<const u32x4 *>(records + size_t(rec) * kRecBytes + kRecTable);
-#pragma unroll
-        for (int it = 0; it < 3; ++it) body[it] = stream_load(src + it * kWave + lane);
-    }
+    body_of(rec, body);
     for (; rec < n_records; rec += n_waves) {           // wave-uniform
         wave_lds_sync();                                // the previous record is done with LDS
 #pragma unroll
@@ -328,15 +349,12 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records,
         const uint32_t meta = body[2].z;
         const int32_t own = static_cast<int32_t>(body[2].w);
         if (rec + n_waves < n_records) {
-            pr[0] = price[tab.x];
-            pr[1] = price[tab.y];
-            pr[2] = price[tab.z];
-            pr[3] = price[tab.w];
+            pr[0] = price[tab.a];
+            pr[1] = price[tab.b];
+            pr[2] = price[tab.c];
+            pr[3] = price[tab.d];
             if (rec + 2 * n_waves < n_records) tab = table_of(rec + 2 * n_waves);
-            const u32x4 *src = reinterpret_cast<const u32x4 *>(
-                records + size_t(rec + n_waves) * kRecBytes + kRecTable);
-#pragma unroll
-            for (int it = 0; it < 3; ++it) body[it] = stream_load(src + it * kWave + lane);
+            body_of(rec + n_waves, body);
         }
         wave_lds_sync();
         auto scan_quad = [&](const uint32_t *wq, double &m4, int &i4) {
@@ -665,9 +683,14 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, uint8_t *choice, uint32_t
             if (t.rec_lane_major) {
 #define NIMBLE_RECL_LAUNCH(SS)                                                                 \
     case SS:                                                                                   \
-        hipLaunchKernelGGL((k_argmin_recl<L, SS, MAXC>), dim3(rec_grid),                       \
-                           dim3(kWave * kRecWaves), 0, s, t.n_records, t.records, t.price,     \
-                           choice, count, t.choice2);                                          \
+        if (t.rec_table16)                                                                     \
+            hipLaunchKernelGGL((k_argmin_recl<L, SS, MAXC, true>), dim3(rec_grid),             \
+                               dim3(kWave * kRecWaves), 0, s, t.n_records, t.records, t.price, \
+                               choice, count, t.choice2);                                      \
+        else                                                                                   \
+            hipLaunchKernelGGL((k_argmin_recl<L, SS, MAXC, false>), dim3(rec_grid),            \
+                               dim3(kWave * kRecWaves), 0, s, t.n_records, t.records, t.price, \
+                               choice, count, t.choice2);                                      \
         return;
                 switch (t.rec_stride) {
                     NIMBLE_RECL_LAUNCH(1)

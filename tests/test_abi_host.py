@@ -113,11 +113,26 @@ def test_reverse_csr_random_ragged():
     assert rev_ptr[-1] == t.nnz
 
 
+RECORD_FORMATS = {
+    # lane-major bodies with 16-bit link tables (the default where the fabric allows it), with
+    # 32-bit tables, and record-major bodies
+    "lane-major, 16-bit table": {},
+    "lane-major, 32-bit table": {"NIMBLE_TUNE_RECORD_TABLE16": "0"},
+    "record-major": {"NIMBLE_TUNE_RECORD_LANE_MAJOR": "0"},
+}
+
+
+@pytest.mark.parametrize("fmt", list(RECORD_FORMATS))
 @pytest.mark.parametrize("cfg", [0, 1, 3])
-def test_forward_records_round_trip(cfg):
+def test_forward_records_round_trip(cfg, fmt, monkeypatch):
+    for name, value in RECORD_FORMATS[fmt].items():
+        monkeypatch.setenv(name, value)
     t = W.config_topology(cfg)
-    links, path_rec, n_rec = B.nimble_host_records_roundtrip(
-        t.n_links, t.n_comm, t.comm_path_ptr, t.n_paths, t.path_link_ptr, t.path_links)
+    args = (t.n_links, t.n_comm, t.comm_path_ptr, t.n_paths, t.path_link_ptr, t.path_links)
+    links, path_rec, n_rec = B.nimble_host_records_roundtrip(*args)
+    # the single node has at most 7 candidates per pair: one lane per commodity, record-major
+    lane_major = cfg != 0 and fmt != "record-major"
+    assert B.nimble_host_layout_stats(*args)["records_lane_major"] == int(lane_major)
     assert n_rec >= 1
     assert np.array_equal(links, t.path_links)
     # records are runs of whole commodities, in order
@@ -128,10 +143,20 @@ def test_forward_records_round_trip(cfg):
     assert np.bincount(path_rec).max() * stride <= 4096
 
 
-def test_forward_records_ragged_and_unfit():
+@pytest.mark.parametrize("fmt", list(RECORD_FORMATS))
+def test_forward_records_ragged_and_unfit(fmt, monkeypatch):
+    for name, value in RECORD_FORMATS[fmt].items():
+        monkeypatch.setenv(name, value)
     rng = np.random.default_rng(21)
-    t = W.random_topology(rng, n_links=300, n_comm=700, max_paths=20, max_len=2)
-    links, path_rec, n_rec = B.nimble_host_records_roundtrip(
+    # (random path lengths beyond 2 pad the fixed-stride records by more than half: no records)
+    for max_paths, max_len in ((20, 2), (33, 2), (64, 2), (127, 1), (9, 2)):
+        t = W.random_topology(rng, n_links=300, n_comm=700, max_paths=max_paths, max_len=max_len)
+        links, path_rec, n_rec = B.nimble_host_records_roundtrip(
+            t.n_links, t.n_comm, t.comm_path_ptr, t.n_paths, t.path_link_ptr, t.path_links)
+        assert n_rec > 1 and np.array_equal(links, t.path_links)
+    # link ids beyond 16 bits keep the 32-bit table
+    t = W.random_topology(rng, n_links=70000, n_comm=300, max_paths=12, max_len=2)
+    links, _, n_rec = B.nimble_host_records_roundtrip(
         t.n_links, t.n_comm, t.comm_path_ptr, t.n_paths, t.path_link_ptr, t.path_links)
     assert n_rec > 1 and np.array_equal(links, t.path_links)
     # paths of 70 links exceed the record stride: no records, the untiled kernel is used

@@ -225,6 +225,32 @@ def test_edge_cases(oracle_mod, B, regime):
     check(oracle_mod, B, w.topo, w.traffic, w.eps, 120, regime, flags=1)
 
 
+@pytest.mark.parametrize("flags", [0, 1])
+@pytest.mark.parametrize("env", [{"NIMBLE_TUNE_RECORD_TABLE16": "0"},
+                                 {"NIMBLE_TUNE_RECORD_LANE_MAJOR": "0"},
+                                 {"NIMBLE_TUNE_RECORD_LANE_MAJOR": "0",
+                                  "NIMBLE_TUNE_NO_CHOICE_LOG": "1"},
+                                 {"NIMBLE_TUNE_NO_CHOICE_LOG": "1"}],
+                         ids=["lane-major-32", "record-major", "record-major-counters",
+                              "lane-major-16-counters"])
+def test_every_forward_record_format(oracle_mod, B, monkeypatch, env, flags):
+    """The default on these fabrics is lane-major record bodies with 16-bit link tables; the
+    32-bit table (fabrics of more than 65535 links) and the record-major body (more than five
+    links per path, or fewer than nine candidates per commodity) must give the same plans, with
+    the choice log and with per-path counters."""
+    for name, value in env.items():
+        monkeypatch.setenv(name, value)
+    for cfg, iters in ((1, 120), (3, 60)):
+        w = W.make_config(cfg)
+        check(oracle_mod, B, w.topo, w.traffic, w.eps, iters, regime=2, flags=flags)
+    # ragged: 1 to 40 candidates of one or two links, commodities without traffic
+    rng = np.random.default_rng(77)
+    t = W.random_topology(rng, 120, 900, 40, 2)
+    d = np.floor(rng.pareto(1.1, t.n_comm) * 1e6)
+    d[::9] = 0.0
+    check(oracle_mod, B, t, d, 0.07, 50, 2, flags)
+
+
 def test_streaming_regime_without_choice_log(oracle_mod, B, monkeypatch):
     """When the per-iteration choice log is unavailable the streaming regime counts per path
     every iteration instead; both ways must give the same plan."""
