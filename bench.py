@@ -30,7 +30,8 @@ PHASES = ["argmin", "load_reduce", "update"]
 
 def phase_bytes(lib_topo):
     """Stored bytes each streaming-regime kernel has to move per launch, as the library lays
-    the topology out (4 KiB forward records with 8-bit link indices, 36-byte reverse octets)."""
+    the topology out (3.5 or 4 KiB forward records with 8-bit link indices, tile and strip items,
+    36-byte reverse octets)."""
     d = {name: lib_topo.phase_bytes(i) for i, name in enumerate(PHASES)}
     d["total"] = lib_topo.bytes_per_iter
     return d

@@ -321,10 +321,11 @@ nimble_status_t nimble_host_build_reverse_streaming(int32_t n_links, int32_t n_c
                                                     int32_t *rev_comm, int32_t *rev_path);
 
 /*
- * Host-only helper (no device call): repacks the forward CSR into the self-contained 4 KiB
- * records the path-cost kernel streams (a run of consecutive commodities, the record's own
- * link table, and a fixed number of 8-bit link-table indices per candidate) exactly as
- * nimble_topo_create does, and reads every incidence back through them.  links_out is host
+ * Host-only helper (no device call): repacks the forward CSR into the self-contained records
+ * of 3.5 or 4 KiB the path-cost kernel streams (a run of consecutive commodities, the record's
+ * own link table, and a fixed number of 8-bit link-table indices per candidate, laid out lane by
+ * lane or record-major) exactly as nimble_topo_create does, and reads every incidence back
+ * through them.  links_out is host
  * [nnz] out and must equal path_links; path_record is host [n_paths] out, the record of every
  * path; n_records_out receives the number of records, or 0 when the topology does not fit
  * records (a path longer than 8 links, padding above 1.5x, more than 254 distinct links or
