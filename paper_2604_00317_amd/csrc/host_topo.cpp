@@ -755,7 +755,7 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
             // that fit five words per quad, a second lane per slot for the record's own words,
             // and 4 KiB records
             t.rec_lane_major = (t.rec_lane_major != 0 && S <= kRecLaneSteps && lanes >= 2 &&
-                                quads <= 2 * lanes && kRecBytes == 4096) ? 1 : 0;
+                                lanes <= 16 && quads <= 2 * lanes && kRecBytes == 4096) ? 1 : 0;
             if (t.rec_lane_major && t.rec_comm_cap > 64 / lanes) t.rec_comm_cap = 64 / lanes;
         }
         const bool lane_major = t.rec_lane_major != 0;

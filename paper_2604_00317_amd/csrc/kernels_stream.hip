@@ -285,7 +285,8 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records,
                                                        uint32_t *__restrict__ count,
                                                        uint8_t *__restrict__ choice2)
 {
-    static_assert(L >= 2 && S <= kRecLaneSteps, "lane-major records: two lanes, five steps");
+    static_assert(L >= 2 && L <= 16 && S <= kRecLaneSteps,
+                  "lane-major records: 2 to 16 lanes per commodity, five steps");
     // T16: the link table is 256 uint16 (8 bytes per lane) and the record 3.5 KiB
     constexpr int kTab = T16 ? kRecTable16 : kRecTable;
     constexpr int kRec = T16 ? kRecBytes16 : kRecBytes;
@@ -679,7 +680,7 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, uint8_t *choice, uint32_t
         if (rec_grid > t.rec_blocks) rec_grid = t.rec_blocks;
         if (t.rec_per_wave > 0)
             rec_grid = (t.n_records + kRecWaves * t.rec_per_wave - 1) / (kRecWaves * t.rec_per_wave);
-        if constexpr (L >= 2) {
+        if constexpr (L >= 2 && L <= 16) {      // (a slot's lanes 1 and L + 1 hold record words)
             if (t.rec_lane_major) {
 #define NIMBLE_RECL_LAUNCH(SS)                                                                 \
     case SS:                                                                                   \
