@@ -100,6 +100,30 @@ __device__ __forceinline__ void wave_lds_sync()
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+// Cost of the four candidates of one quad: w[i] holds the table indices of step i of four
+// consecutive candidates, one byte each; the prices come from the wave's price slots in LDS
+// (short paths read +0.0, absent candidates start at +inf).  Returns the minimum of the quad and
+// the lowest candidate that holds it.  The sums are the same IEEE operations in the same order
+// as in the untiled kernel (0 + p is p: the sum starts at the first price).
+template <int S, bool MAXC>
+__device__ __forceinline__ void scan_quad(const double *s_price, const uint32_t *w, double &m4,
+                                          int &i4)
+{
+    double cst[4];
+#pragma unroll
+    for (int c4 = 0; c4 < 4; ++c4) {
+        cst[c4] = s_price[(w[0] >> (8 * c4)) & 0xFFu];
+#pragma unroll
+        for (int i = 1; i < S; ++i) {
+            const double pe = s_price[(w[i] >> (8 * c4)) & 0xFFu];
+            if constexpr (MAXC) cst[c4] = (pe > cst[c4]) ? pe : cst[c4];
+            else cst[c4] = cst[c4] + pe;
+        }
+    }
+    m4 = fast_min_f64(fast_min_f64(cst[0], cst[1]), fast_min_f64(cst[2], cst[3]));
+    i4 = cst[0] == m4 ? 0 : (cst[1] == m4 ? 1 : (cst[2] == m4 ? 2 : 3));
+}
+
 template <int L, int S, bool MAXC, bool TWO>
 __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records,
                                                       const uint8_t *__restrict__ records,
@@ -182,25 +206,6 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records,
             for (int it = 0; it < kLoads; ++it) body[it] = stream_load(src + it * kWave + lane);
         }
         wave_lds_sync();
-        // cost of the four candidates of one quad: the S table indices of four consecutive
-        // candidates come as S aligned 32-bit words; returns the minimum of the quad (padding
-        // candidates cost +inf) and the lowest candidate that holds it
-        auto scan_quad = [&](const uint32_t (&w)[S], double &m4, int &i4) {
-            double cst[4];
-#pragma unroll
-            for (int c4 = 0; c4 < 4; ++c4) {
-                // 0 + p0 is p0: the sum starts at the first price
-                cst[c4] = s_price[(w[0] >> (8 * c4)) & 0xFFu];
-#pragma unroll
-                for (int i = 1; i < S; ++i) {
-                    const double pe = s_price[(w[i] >> (8 * c4)) & 0xFFu];
-                    if constexpr (MAXC) cst[c4] = (pe > cst[c4]) ? pe : cst[c4];
-                    else cst[c4] = cst[c4] + pe;
-                }
-            }
-            m4 = fast_min_f64(fast_min_f64(cst[0], cst[1]), fast_min_f64(cst[2], cst[3]));
-            i4 = cst[0] == m4 ? 0 : (cst[1] == m4 ? 1 : (cst[2] == m4 ? 2 : 3));
-        };
         const int wstride = npad_rec >> 2;
         const int rounds = (nk + kGroups - 1) / kGroups;
         for (int r = 0; r < rounds; ++r) {        // wave-uniform: all lanes reach the reduction
@@ -232,8 +237,8 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records,
                 }
                 double ma, mb;
                 int ia, ib;
-                scan_quad(wa, ma, ia);
-                scan_quad(wb, mb, ib);
+                scan_quad<S, MAXC>(s_price, wa, ma, ia);
+                scan_quad<S, MAXC>(s_price, wb, mb, ib);
                 if (va) bj = ja;
                 if (va && ma < best) {
                     best = ma;
@@ -253,7 +258,7 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records,
                     for (int i = 0; i < S; ++i) w[i] = lp[i * wstride];
                     double m4;
                     int i4;
-                    scan_quad(w, m4, i4);
+                    scan_quad<S, MAXC>(s_price, w, m4, i4);
                     if (m4 < best) {
                         best = m4;
                         bj = jq + i4;
@@ -358,29 +363,13 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records,
             body_of(rec + n_waves, body);
         }
         wave_lds_sync();
-        auto scan_quad = [&](const uint32_t *wq, double &m4, int &i4) {
-            double cst[4];
-#pragma unroll
-            for (int c4 = 0; c4 < 4; ++c4) {
-                // 0 + p0 is p0: the sum starts at the first price
-                cst[c4] = s_price[(wq[0] >> (8 * c4)) & 0xFFu];
-#pragma unroll
-                for (int i = 1; i < S; ++i) {
-                    const double pe = s_price[(wq[i] >> (8 * c4)) & 0xFFu];
-                    if constexpr (MAXC) cst[c4] = (pe > cst[c4]) ? pe : cst[c4];
-                    else cst[c4] = cst[c4] + pe;
-                }
-            }
-            m4 = fast_min_f64(fast_min_f64(cst[0], cst[1]), fast_min_f64(cst[2], cst[3]));
-            i4 = cst[0] == m4 ? 0 : (cst[1] == m4 ? 1 : (cst[2] == m4 ? 2 : 3));
-        };
         const int np = static_cast<int>(meta & 0xFFu);
         const int p_lo = static_cast<int>(meta >> 8);
         const int ja = 4 * j, jb = 4 * j + 4 * L;
         double ma, mb;
         int ia, ib;
-        scan_quad(w, ma, ia);
-        scan_quad(w + kRecLaneSteps, mb, ib);
+        scan_quad<S, MAXC>(s_price, w, ma, ia);
+        scan_quad<S, MAXC>(s_price, w + kRecLaneSteps, mb, ib);
         // the strict `<` scan in candidate order: quad A first; absent candidates cost +inf
         double best = __builtin_inf();
         int bj = ja < np ? ja : 0x7FFFFFFF;
