@@ -113,7 +113,7 @@ __device__ __forceinline__ void reduce_both(const PersistentArgs &a, int wave, i
                              a.strip_slot, a.choice, a.demand1n, a.choice2, a.demand2, a.partial,
                              wave, n_waves, lane);
     reduce_flat_phase<MODE>(0, a.n_passes, a.pass_first_slot, a.oct_base, a.oct_mask, a.choice,
-                            a.demand, a.choice2, a.demand2, a.partial, 0, wave, n_waves, lane);
+                            a.demand1n, a.choice2, a.demand2, a.partial, 0, wave, n_waves, lane);
     reduce_phase<MODE, kSinglesPerLane>(a.n_schunks, a.schunk_begin, a.schunk_end, a.schunk_slot,
                                         a.single_pair, a.pad_comm, a.choice, a.demand, a.partial,
                                         n_waves - 1 - wave, n_waves, lane);

@@ -464,7 +464,7 @@ __global__ __launch_bounds__(kBlock) void k_load_reduce(ReduceArgs a)
                                  a.partial, wave - a.n_tile_waves, a.n_strip_waves, lane);
     else
         reduce_flat_phase<MODE>(0, a.n_passes, a.pass_first_slot, a.oct_base, a.oct_mask,
-                                a.choice, a.demand, a.choice2, a.demand2, a.partial, 0,
+                                a.choice, a.demand1n, a.choice2, a.demand2, a.partial, 0,
                                 wave - a.n_tile_waves - a.n_strip_waves,
                                 n_waves - a.n_tile_waves - a.n_strip_waves, lane);
     // single pairs (commodities with more than 32 candidates) are walked from the other end of
@@ -486,7 +486,7 @@ struct FusedArgs {
     const uint32_t *oct_base, *oct_mask;
     const int32_t *pos_link, *pos_slot_ptr;
     const uint8_t *choice, *choice2;
-    const double *demand, *demand2;
+    const double *demand1n, *demand2;      // the library's padded copies, by id and by sigma
     const double *invcap_pos;
     double *len, *price, *S, *scalars;
     double eps;
@@ -544,7 +544,7 @@ __global__ __launch_bounds__(kBlock) void k_reduce_update(FusedArgs a)
     };
     const LinkState st0 = fetch(i0 + row);
     const LinkState st1 = fetch(i0 + row + kRows);
-    reduce_flat_phase<0>(p0, p1, a.pass_first_slot, a.oct_base, a.oct_mask, a.choice, a.demand,
+    reduce_flat_phase<0>(p0, p1, a.pass_first_slot, a.oct_base, a.oct_mask, a.choice, a.demand1n,
                          a.choice2, a.demand2, s_part, slot0, wave, kBlock / kWave, lane);
     __syncthreads();
     apply(i0 + row, st0);
@@ -898,7 +898,7 @@ void launch_reduce_update(const DeviceTopo &t, const uint8_t *choice, const doub
     a.pos_slot_ptr = t.pos_slot_ptr;
     a.choice = choice;
     a.choice2 = t.choice2;
-    a.demand = demand;
+    a.demand1n = t.demand1n;
     a.demand2 = t.demand2;
     a.invcap_pos = t.invcap_pos;
     a.len = t.len;

@@ -232,75 +232,58 @@ __device__ __forceinline__ void reduce_phase(int n_chunks, const int32_t *__rest
 // (one octet per lane).  Flag bits in the base word: kOctNewSlot = this octet starts a new
 // partial-sum slot (first octet of a link's row, or of a pass), kOctSigma = base is in the
 // second commodity numbering (choices and demands are read from the sigma-ordered copies).
-// Per lane the demands of the hits are added in slot order; the lanes of one slot are then
-// combined by a segmented inclusive scan (fixed distances 1,2,..,32: the same tree on every
-// run) and the last lane of the segment stores the sum.  No floating-point atomics.
+// A lane fetches the eight choices (one 8-byte load) and the eight demands (four 16-byte loads
+// from the library's own padded copies) of its octet together -- both depend on the base word
+// only, which was prefetched -- and adds the demands of the hits in slot order (fma(d, 1.0, a)
+// for a hit, fma(d, 0.0, a) otherwise: the same sums as plain additions, demands are finite);
+// the lanes of one slot are then combined by a segmented inclusive scan (fixed distances
+// 1,2,..,32: the same tree on every run) and the last lane of the segment stores the sum.  No
+// floating-point atomics.
 // MODE 1 (width rho): every commodity with a non-zero mask counts once.
 template <int MODE>
 __device__ __forceinline__ void reduce_flat_phase(
     int pass_begin, int pass_end, const int32_t *__restrict__ pass_first_slot,
     const uint32_t *__restrict__ oct_base, const uint32_t *__restrict__ oct_mask,
-    const uint8_t *__restrict__ choice, const double *__restrict__ demand,
+    const uint8_t *__restrict__ choice, const double *__restrict__ demand1n,
     const uint8_t *__restrict__ choice2, const double *__restrict__ demand2,
     double *__restrict__ partial, int slot_base, int wave, int n_waves, int lane)
 {
     // passes pass_begin + wave, + n_waves, ... below pass_end; slot s goes to
-    // partial[s - slot_base] (global memory, or the LDS of a link block)
+    // partial[s - slot_base] (global memory, or the LDS of a link block).
+    // demand1n / demand2: the demands by id / by sigma number, with 8 spare entries.
     const int first = pass_begin + wave;
     if (first >= pass_end) return;
     const int last = pass_end - 1;
     const u32x4 *masks = reinterpret_cast<const u32x4 *>(oct_mask);
-    // Software pipeline over the passes of this wave, two passes in flight:
-    //   A  gather the choices of pass i            (its octets arrived during pass i-1)
-    //   B  request the octets of pass i+1
-    //   C  finish pass i-1: its demand loads were issued before A and B, so waiting for them
-    //      leaves A and B in flight; segmented scan, store of the partial sums
-    //   D  hit bits of pass i, request the demands of (up to two) hits per lane
-    // Every load on this path is unconditional (absent hits read element 0 and are masked to
-    // +0.0; passes beyond the end re-read the last pass), which keeps the number of
-    // outstanding requests known to the compiler so that it waits for the oldest only.
+    // While a pass is worked on, the octets of the wave's next pass are in flight.  Every load
+    // is unconditional (passes beyond the end re-read the range's last pass), which keeps the
+    // number of outstanding requests known to the compiler so that it waits for the oldest only.
     uint32_t bw = stream_load(oct_base + size_t(first) * kWave + lane);
     // masks of a pass: words 0..3 of the 64 octets lane after lane, then words 4..7
     u32x4 m0 = stream_load(masks + size_t(first) * 128 + lane);
     u32x4 m1 = stream_load(masks + size_t(first) * 128 + 64 + lane);
-    // carried state of the pass that is waiting for its demands
-    bool have_prev = false;
-    double pd0 = 0.0, pd1 = 0.0, pextra = 0.0;
-    int pmask0 = 0, pmask1 = 0, pslot = 0;
-    uint32_t pflag = 0u;
-    auto finish = [&](double d0, double d1, int k0, int k1, double extra, uint32_t flagword,
-                      int first_slot) {
-        // masked, not selected: a select would let the compiler move the load under the
-        // condition and wait for it on its own
-        double acc = __hiloint2double(__double2hiint(d0) & k0, __double2loint(d0) & k0);
-        acc = acc + __hiloint2double(__double2hiint(d1) & k1, __double2loint(d1) & k1);
-        acc = acc + extra;
-        const unsigned long long heads = __ballot((flagword & kOctNewSlot) != 0u);   // bit 0 set
-        const unsigned long long upto = heads & (~0ull >> (63 - lane));   // heads at lanes <= lane
-        const int start = 63 - __clzll(static_cast<long long>(upto));
-        acc = segmented_scan_f64(acc, start, lane);
-        const bool tail = lane == kWave - 1 || ((heads >> (lane + 1)) & 1ull) != 0ull;
-        if (tail) partial[first_slot - slot_base + __popcll(upto) - 1] = acc;
-    };
     for (int pass = first; pass < pass_end; pass += n_waves) {     // wave-uniform
-        // A
         const bool sig = (bw & kOctSigma) != 0u;
         const int base = static_cast<int>(bw & ~3u);
-        const uint8_t *ch_src = sig ? choice2 : choice;
-        const double *dm_src = sig ? demand2 : demand;
         uint2 ch = make_uint2(0u, 0u);
-        if constexpr (MODE == 0) ch = *reinterpret_cast<const uint2 *>(ch_src + base);
+        if constexpr (MODE == 0)
+            ch = *reinterpret_cast<const uint2 *>((sig ? choice2 : choice) + base);
+        const u32x4 *dq = reinterpret_cast<const u32x4 *>((sig ? demand2 : demand1n) + base);
+        const u32x4 q0 = dq[0], q1 = dq[1], q2 = dq[2], q3 = dq[3];
         const int first_slot = pass_first_slot[pass];
-        // B
-        const int np = pass + n_waves < last ? pass + n_waves : last;
-        const uint32_t nbw = stream_load(oct_base + size_t(np) * kWave + lane);
-        const u32x4 nm0 = stream_load(masks + size_t(np) * 128 + lane);
-        const u32x4 nm1 = stream_load(masks + size_t(np) * 128 + 64 + lane);
-        // C
-        if (have_prev) finish(pd0, pd1, pmask0, pmask1, pextra, pflag, pslot);
-        // D
+        const uint32_t flagword = bw;
         const uint32_t mk[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
-        uint32_t hits = 0u;
+        // the next pass of this wave
+        const int np = pass + n_waves < last ? pass + n_waves : last;
+        bw = stream_load(oct_base + size_t(np) * kWave + lane);
+        m0 = stream_load(masks + size_t(np) * 128 + lane);
+        m1 = stream_load(masks + size_t(np) * 128 + 64 + lane);
+        const double dm[8] = {
+            __hiloint2double(int(q0.y), int(q0.x)), __hiloint2double(int(q0.w), int(q0.z)),
+            __hiloint2double(int(q1.y), int(q1.x)), __hiloint2double(int(q1.w), int(q1.z)),
+            __hiloint2double(int(q2.y), int(q2.x)), __hiloint2double(int(q2.w), int(q2.z)),
+            __hiloint2double(int(q3.y), int(q3.x)), __hiloint2double(int(q3.w), int(q3.z))};
+        double acc = 0.0;
 #pragma unroll
         for (int sl = 0; sl < 8; ++sl) {
             uint32_t h;
@@ -311,40 +294,15 @@ __device__ __forceinline__ void reduce_flat_phase(
             } else {
                 h = mk[sl] != 0u ? 1u : 0u;
             }
-            hits |= h << sl;
+            acc = __builtin_fma(dm[sl], static_cast<double>(h), acc);
         }
-        // the first two hits of the lane, in slot order; a lane without a hit reads element 0
-        // of the demand array instead (all such lanes share one cache line) and is masked
-        const bool ok0 = hits != 0u;
-        const int i0 = ok0 ? base + __ffs(hits) - 1 : 0;
-        hits &= hits - 1u;
-        const bool ok1 = hits != 0u;
-        const int i1 = ok1 ? base + __ffs(hits) - 1 : 0;
-        hits &= hits - 1u;
-        const double d0 = dm_src[i0];
-        const double d1 = dm_src[i1];
-        // further hits of a lane are rare: fetch them at once (this wait is for everything)
-        double extra = 0.0;
-        if (__any(hits != 0u)) {
-            while (hits != 0u) {
-                const int t = __ffs(hits) - 1;
-                hits &= hits - 1u;
-                extra = extra + dm_src[base + t];
-            }
-        }
-        pd0 = d0;
-        pd1 = d1;
-        pmask0 = -static_cast<int>(ok0);
-        pmask1 = -static_cast<int>(ok1);
-        pextra = extra;
-        pflag = bw;
-        pslot = first_slot;
-        have_prev = true;
-        bw = nbw;
-        m0 = nm0;
-        m1 = nm1;
+        const unsigned long long heads = __ballot((flagword & kOctNewSlot) != 0u);   // bit 0 set
+        const unsigned long long upto = heads & (~0ull >> (63 - lane));   // heads at lanes <= lane
+        const int start = 63 - __clzll(static_cast<long long>(upto));
+        acc = segmented_scan_f64(acc, start, lane);
+        const bool tail = lane == kWave - 1 || ((heads >> (lane + 1)) & 1ull) != 0ull;
+        if (tail) partial[first_slot - slot_base + __popcll(upto) - 1] = acc;
     }
-    if (have_prev) finish(pd0, pd1, pmask0, pmask1, pextra, pflag, pslot);
 }
 
 // ---- phase B, tile part ---------------------------------------------------------------------
