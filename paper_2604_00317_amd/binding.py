@@ -53,6 +53,11 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
             raise FileNotFoundError(LIB_PATH)
         from . import build as _build
         _build.build()
+    # Device pointers and streams cross the boundary, so the library and torch must share one
+    # HIP runtime.  torch brings its own copy: it is imported first, and the library's dependency
+    # on the runtime then resolves to the copy already in the process (loaded the other way
+    # round, torch finds a runtime it was not built for and reports no GPU).
+    import torch  # noqa: F401
     lib = ctypes.CDLL(LIB_PATH)
     vp, i32, i64, u32, dbl = (ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32,
                               ctypes.c_double)
