@@ -308,18 +308,28 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records,
     struct Ids {
         uint32_t a, b, c, d;        // links lane, 64 + lane, 128 + lane, 192 + lane of the table
     };
+    // The records are read around the L2 (buffer loads with the sc0 and sc1 bits): 59 MB per
+    // launch would otherwise push out what the reduce and update kernels find there again in
+    // the next iteration (their 30 MB fit the L2, the records never will).  A record is one
+    // buffer: the hardware drops loads beyond its end.
+    constexpr int kAroundL2 = 1 | 16;            // cache policy bits of the buffer loads: sc0, sc1
+    auto record = [&](int r) {
+        return __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint8_t *>(records + size_t(r) * kRec), 0, kRec, 0x00020000);
+    };
     auto table_of = [&](int r) {
         Ids ids;
-        const uint8_t *base = records + size_t(r) * kRec;
         if constexpr (T16) {
             typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-            const u32x2 v = stream_load(reinterpret_cast<const u32x2 *>(base) + lane);
+            const u32x2 v =
+                __builtin_amdgcn_raw_buffer_load_b64(record(r), lane * 8, 0, kAroundL2);
             ids.a = v.x & 0xFFFFu;
             ids.b = v.x >> 16;
             ids.c = v.y & 0xFFFFu;
             ids.d = v.y >> 16;
         } else {
-            const u32x4 v = stream_load(reinterpret_cast<const u32x4 *>(base) + lane);
+            const u32x4 v =
+                __builtin_amdgcn_raw_buffer_load_b128(record(r), lane * 16, 0, kAroundL2);
             ids.a = v.x;
             ids.b = v.y;
             ids.c = v.z;
@@ -328,9 +338,11 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records,
         return ids;
     };
     auto body_of = [&](int r, u32x4 (&buf)[3]) {
-        const u32x4 *src = reinterpret_cast<const u32x4 *>(records + size_t(r) * kRec + kTab);
+        const __amdgpu_buffer_rsrc_t rs = record(r);
 #pragma unroll
-        for (int it = 0; it < 3; ++it) buf[it] = stream_load(src + it * kWave + lane);
+        for (int it = 0; it < 3; ++it)
+            buf[it] = __builtin_amdgcn_raw_buffer_load_b128(rs, kTab + it * 1024 + lane * 16, 0,
+                                                            kAroundL2);
     };
     Ids tab = table_of(rec);
     u32x4 body[3];
