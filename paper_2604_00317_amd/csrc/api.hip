@@ -266,6 +266,9 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
         if (std::atoi(env) >= 1 && std::atoi(env) <= 64) d.rec_per_wave = std::atoi(env);
     d.rec_lane_major = h.rec_lane_major;
     d.rec_table16 = h.rec_table16;
+    d.rec_around_l2 = -1;
+    if (const char *env = std::getenv("NIMBLE_TUNE_RECORD_AROUND_L2"))
+        d.rec_around_l2 = std::atoi(env) != 0 ? 1 : 0;
     // (a lane-major layout has its lanes per commodity built in)
     if (const char *env = std::getenv("NIMBLE_TUNE_RECORD_LANES")) {
         const int v = std::atoi(env);

@@ -23,6 +23,7 @@ struct DeviceTopo {
     int32_t rec_lanes;         // lanes per commodity in the record kernel (0: automatic)
     int32_t rec_lane_major;    // 1: record bodies are laid out lane by lane (k_argmin_recl)
     int32_t rec_table16;       // 1: 16-bit link tables, 3.5 KiB records
+    int32_t rec_around_l2;     // records read around the L2: 1, 0, or -1 (by their total size)
     int32_t rec_per_wave;      // records a wave walks in the record kernel (0: default)
     const uint8_t *records;
     // reverse CSR of 8-byte (commodity, window | mask) pairs, rows padded to 2 pairs

@@ -283,7 +283,7 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records,
 // price slots kRecZeroSlot / kRecInfSlot hold +0.0 / +inf for short paths and absent
 // candidates.  One scan round per record: a record has at most 64 / L commodities.
 template <int L, int S, bool MAXC, bool T16>
-__global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records,
+__global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records, int around_l2,
                                                        const uint8_t *__restrict__ records,
                                                        const double *__restrict__ price,
                                                        uint8_t *__restrict__ choice,
@@ -308,10 +308,11 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records,
     struct Ids {
         uint32_t a, b, c, d;        // links lane, 64 + lane, 128 + lane, 192 + lane of the table
     };
-    // The records are read around the L2 (buffer loads with the sc0 and sc1 bits): 59 MB per
-    // launch would otherwise push out what the reduce and update kernels find there again in
-    // the next iteration (their 30 MB fit the L2, the records never will).  A record is one
-    // buffer: the hardware drops loads beyond its end.
+    // Records that together exceed the L2 are read around it (buffer loads with the sc0 and sc1
+    // bits; around_l2 is the same for the whole launch): 59 MB per launch on the 64-node fabric
+    // would otherwise push out what the reduce and update kernels find there again in the next
+    // iteration (their 30 MB fit the L2, the records never will).  A record is one buffer: the
+    // hardware drops loads beyond its end.
     constexpr int kAroundL2 = 1 | 16;            // cache policy bits of the buffer loads: sc0, sc1
     auto record = [&](int r) {
         return __builtin_amdgcn_make_buffer_rsrc(
@@ -322,14 +323,17 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records,
         if constexpr (T16) {
             typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
             const u32x2 v =
-                __builtin_amdgcn_raw_buffer_load_b64(record(r), lane * 8, 0, kAroundL2);
+                around_l2 ? __builtin_amdgcn_raw_buffer_load_b64(record(r), lane * 8, 0, kAroundL2)
+                          : __builtin_amdgcn_raw_buffer_load_b64(record(r), lane * 8, 0, 0);
             ids.a = v.x & 0xFFFFu;
             ids.b = v.x >> 16;
             ids.c = v.y & 0xFFFFu;
             ids.d = v.y >> 16;
         } else {
             const u32x4 v =
-                __builtin_amdgcn_raw_buffer_load_b128(record(r), lane * 16, 0, kAroundL2);
+                around_l2
+                    ? __builtin_amdgcn_raw_buffer_load_b128(record(r), lane * 16, 0, kAroundL2)
+                    : __builtin_amdgcn_raw_buffer_load_b128(record(r), lane * 16, 0, 0);
             ids.a = v.x;
             ids.b = v.y;
             ids.c = v.z;
@@ -339,10 +343,17 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records,
     };
     auto body_of = [&](int r, u32x4 (&buf)[3]) {
         const __amdgpu_buffer_rsrc_t rs = record(r);
+        if (around_l2) {
 #pragma unroll
-        for (int it = 0; it < 3; ++it)
-            buf[it] = __builtin_amdgcn_raw_buffer_load_b128(rs, kTab + it * 1024 + lane * 16, 0,
-                                                            kAroundL2);
+            for (int it = 0; it < 3; ++it)
+                buf[it] = __builtin_amdgcn_raw_buffer_load_b128(
+                    rs, kTab + it * 1024 + lane * 16, 0, kAroundL2);
+        } else {
+#pragma unroll
+            for (int it = 0; it < 3; ++it)
+                buf[it] = __builtin_amdgcn_raw_buffer_load_b128(
+                    rs, kTab + it * 1024 + lane * 16, 0, 0);
+        }
     };
     Ids tab = table_of(rec);
     u32x4 body[3];
@@ -683,16 +694,21 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, uint8_t *choice, uint32_t
             rec_grid = (t.n_records + kRecWaves * t.rec_per_wave - 1) / (kRecWaves * t.rec_per_wave);
         if constexpr (L >= 2 && L <= 16) {      // (a slot's lanes 1 and L + 1 hold record words)
             if (t.rec_lane_major) {
+                // records beyond half of the 32 MB of L2 are read around it
+                const int64_t rec_bytes = static_cast<int64_t>(t.n_records) *
+                                          (t.rec_table16 ? kRecBytes16 : kRecBytes);
+                int around_l2 = rec_bytes > (16LL << 20) ? 1 : 0;
+                if (t.rec_around_l2 >= 0) around_l2 = t.rec_around_l2;
 #define NIMBLE_RECL_LAUNCH(SS)                                                                 \
     case SS:                                                                                   \
         if (t.rec_table16)                                                                     \
             hipLaunchKernelGGL((k_argmin_recl<L, SS, MAXC, true>), dim3(rec_grid),             \
-                               dim3(kWave * kRecWaves), 0, s, t.n_records, t.records, t.price, \
-                               choice, count, t.choice2);                                      \
+                               dim3(kWave * kRecWaves), 0, s, t.n_records, around_l2,          \
+                               t.records, t.price, choice, count, t.choice2);                  \
         else                                                                                   \
             hipLaunchKernelGGL((k_argmin_recl<L, SS, MAXC, false>), dim3(rec_grid),            \
-                               dim3(kWave * kRecWaves), 0, s, t.n_records, t.records, t.price, \
-                               choice, count, t.choice2);                                      \
+                               dim3(kWave * kRecWaves), 0, s, t.n_records, around_l2,          \
+                               t.records, t.price, choice, count, t.choice2);                  \
         return;
                 switch (t.rec_stride) {
                     NIMBLE_RECL_LAUNCH(1)
