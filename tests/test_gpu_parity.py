@@ -230,14 +230,19 @@ def test_edge_cases(oracle_mod, B, regime):
                                  {"NIMBLE_TUNE_RECORD_LANE_MAJOR": "0"},
                                  {"NIMBLE_TUNE_RECORD_LANE_MAJOR": "0",
                                   "NIMBLE_TUNE_NO_CHOICE_LOG": "1"},
-                                 {"NIMBLE_TUNE_NO_CHOICE_LOG": "1"}],
+                                 {"NIMBLE_TUNE_NO_CHOICE_LOG": "1"},
+                                 {"NIMBLE_TUNE_RECORD_AROUND_L2": "1"},
+                                 {"NIMBLE_TUNE_RECORD_AROUND_L2": "1",
+                                  "NIMBLE_TUNE_RECORD_TABLE16": "0"}],
                          ids=["lane-major-32", "record-major", "record-major-counters",
-                              "lane-major-16-counters"])
+                              "lane-major-16-counters", "lane-major-16-around-l2",
+                              "lane-major-32-around-l2"])
 def test_every_forward_record_format(oracle_mod, B, monkeypatch, env, flags):
     """The default on these fabrics is lane-major record bodies with 16-bit link tables; the
     32-bit table (fabrics of more than 65535 links) and the record-major body (more than five
     links per path, or fewer than nine candidates per commodity) must give the same plans, with
-    the choice log and with per-path counters."""
+    the choice log and with per-path counters.  Records that exceed the L2 are fetched with
+    loads that bypass it; the switch forces those loads on fabrics of any size."""
     for name, value in env.items():
         monkeypatch.setenv(name, value)
     for cfg, iters in ((1, 120), (3, 60)):
