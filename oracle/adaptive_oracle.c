@@ -37,7 +37,9 @@
  * Pins (tests/test_adaptive_pins.py): the switch iteration on two parallel links worked by
  * hand, LB <= LP optimum <= lambda on tiny instances (exact simplex), the stopping guarantee,
  * splits summing to 1, fewer iterations than the fixed-step method for the same gap, zero
- * traffic, and the chunked sum against math.fsum.
+ * traffic, the chunked sum against math.fsum, the bottleneck-mode price (hand-worked, unequal
+ * capacities), and the stop iteration under a plain sequential sum
+ * (tests/test_oracle_mutations.py).
  */
 #include <math.h>
 #include <stdint.h>

@@ -31,7 +31,10 @@
  * Pins (tests/test_oracle_pins.py): equal and unequal parallel links (closed forms), uniform
  * traffic on a full mesh, single-path topologies (static congestion), single hot pair on a
  * mesh / on rails, invariants, power-of-two scaling and link relabelling, an exact LP optimum
- * from a dense simplex on tiny inputs, and the weak-duality lower bound.
+ * from a dense simplex on tiny inputs, the weak-duality lower bound, and a hand-worked
+ * bottleneck-mode trajectory on two links of unequal capacity (price = len, initially too).
+ * tests/test_oracle_mutations.py alters one statement at a time in a copy of this file and
+ * checks that the pins notice.
  */
 #include <math.h>
 #include <stdint.h>

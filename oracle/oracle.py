@@ -33,8 +33,12 @@ def build(force: bool = True) -> str:
 def _load():
     global _lib
     if _lib is None:
-        build(force=False)
-        lib = ctypes.CDLL(_LIB)
+        # NIMBLE_ORACLE_LIB: a library built elsewhere from a deliberately altered copy of the
+        # sources (the mutation test checks that the pins notice the alteration)
+        variant = os.environ.get("NIMBLE_ORACLE_LIB")
+        if not variant:
+            build(force=False)
+        lib = ctypes.CDLL(variant or _LIB)
         lib.nimble_oracle_solve.restype = ctypes.c_int
         lib.nimble_oracle_solve.argtypes = [
             ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32, ctypes.c_void_p, ctypes.c_int32,

@@ -30,6 +30,28 @@ def test_switch_iteration_worked_by_hand(oracle_mod):
     assert r9["splits"].tolist() == [80.0 / 85.0, 5.0 / 85.0]
 
 
+def test_bottleneck_price_is_the_length_alone_hand_derived(oracle_mod):
+    """Bottleneck mode, unequal capacities: price = len (Sec. IV-B's bottleneck path cost), so
+    the two links alternate from the first iteration (tests/golden/bottleneck_two_links.txt,
+    worked by hand); with price = len / cap link 0 would be kept for eight iterations."""
+    line = [l.split() for l in open(os.path.join(GOLDEN, "bottleneck_two_links.txt"))
+            if l.split() and l.split()[0] == "adaptive"][0]
+    sig = [float(x) for x in line[1:]]
+    r = oracle_mod.solve_adaptive(*parallel_links([100.0, 50.0]), [10.0], 0.1, len(sig), 1000,
+                                  flags=1)
+    assert r["iters"] == len(sig)
+    assert r["sigma"].tolist() == sig
+    assert r["weight"].tolist() == [30.0, 15.0]
+    assert r["splits"].tolist() == [30.0 / 45.0, 15.0 / 45.0]
+    assert r["lam"] == pytest.approx(10.0 / 150.0, rel=1e-14)
+    line = [l.split() for l in open(os.path.join(GOLDEN, "bottleneck_two_links.txt"))
+            if l.split() and l.split()[0] == "adaptive_swapped"][0]
+    sig = [float(x) for x in line[1:]]
+    r = oracle_mod.solve_adaptive(*parallel_links([50.0, 100.0]), [10.0], 0.1, len(sig), 1000,
+                                  flags=1)
+    assert r["sigma"].tolist() == sig
+
+
 def test_parallel_links_reach_the_closed_form(oracle_mod):
     caps = [100.0, 50.0, 25.0]
     r = oracle_mod.solve_adaptive(*parallel_links(caps), [70.0], 0.05, 100000, 5)

@@ -305,6 +305,43 @@ def test_bottleneck_cost_mode(oracle_mod):
     assert np.all(r["count"][t.comm_path_ptr[:-1]] == 50)
 
 
+def _golden_line(name, key):
+    with open(os.path.join(GOLDEN, name)) as f:
+        for line in f:
+            if line.split() and line.split()[0] == key:
+                return line.split()[1:]
+    raise KeyError(key)
+
+
+def test_bottleneck_price_is_the_length_alone_hand_derived(oracle_mod):
+    """Bottleneck mode on two parallel links of unequal capacity (100 and 50 GB/s): the price
+    of a link is its length, not length / capacity, so both candidates start level and the
+    choices follow tests/golden/bottleneck_two_links.txt (worked by hand from Sec. IV-B's
+    bottleneck path cost).  With price = len / cap the faster link would be kept for the first
+    15 iterations; equal-capacity pins cannot tell the two apart."""
+    want = [int(x) for x in _golden_line("bottleneck_two_links.txt", "fixed")]
+    t = parallel_links([100e9, 50e9])
+    for T in range(1, len(want) + 1):
+        ones = sum(want[:T])
+        assert run(oracle_mod, t, [1e6], 0.1, T, flags=1)["count"].tolist() == [T - ones, ones]
+    # capacities swapped: the initial prices are lengths too, so the first tie still goes to
+    # candidate 0 (initial prices 1/cap would start on the faster link)
+    swapped = [int(x) for x in _golden_line("bottleneck_two_links.txt", "fixed_swapped")]
+    t2 = parallel_links([50e9, 100e9])
+    for T in range(1, len(swapped) + 1):
+        ones = sum(swapped[:T])
+        assert run(oracle_mod, t2, [1e6], 0.1, T, flags=1)["count"].tolist() == [T - ones, ones]
+    # the lengths themselves after the 13 iterations: 1.05^8 and 1.1^5
+    r = oracle_mod.solve(2, [100e9, 50e9], 1, [0, 2], 2, [0, 1, 2], [0, 1], [1e6], 0.1, len(want),
+                         flags=1, len0=np.ones(2))
+    assert r["len"] == pytest.approx([1.05 ** 8, 1.1 ** 5], rel=1e-13)
+    # warm start in bottleneck mode prices the given lengths as they are: from (2, 1) link 1
+    # is taken until 1.1^n exceeds 2 (n = 8), whatever the capacities
+    r = oracle_mod.solve(2, [100e9, 50e9], 1, [0, 2], 2, [0, 1, 2], [0, 1], [1e6], 0.1, 9,
+                         flags=1, len0=np.array([2.0, 1.0]))
+    assert r["count"].tolist() == [1, 8]
+
+
 def test_thread_count_does_not_change_results(oracle_mod):
     w = W.make_config(1)
     oracle_mod.set_threads(1)
