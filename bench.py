@@ -96,6 +96,7 @@ def run_config(B, W, torch, cfg, regime, steps, warmup, iters_override=0, batch_
     h = B.nimble_topo_create(*topo.csr())
     t_create = time.perf_counter() - t_create
     B.nimble_topo_set_regime(h, regime)
+    B.nimble_topo_reserve(h, w.iters)       # the choice log, sized outside the timed solves
     batch = max(w.batch, 1)
     d_traffic = torch.as_tensor(np.ascontiguousarray(w.traffic).reshape(-1)).to(dev)
     d_splits = torch.empty(batch * topo.n_paths, dtype=torch.float64, device=dev)

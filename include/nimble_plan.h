@@ -108,13 +108,26 @@ void nimble_topo_destroy(nimble_topo_t *topo);
  *               nimble_debug_set_spin_limit)
  *   hip_stream  hipStream_t (NULL = default stream).  The call only enqueues work; outputs are
  *               valid after the stream is synchronised.  No host synchronisation inside.
- * The first streaming-regime solve with a given iteration count may grow the topology's
- * workspace (the choice log); later solves with the same or a smaller count enqueue kernels
- * only, so a caller may capture them into a HIP graph on its own stream.
+ * Nothing is allocated or freed here, so a caller may capture the call into a HIP graph on its
+ * own stream.  The streaming regime records the choices of every iteration in the topology's
+ * choice log when that holds `iters` rows (see nimble_topo_reserve) and counts the split
+ * fractions from it once at the end; with a shorter log every iteration bumps a per-path
+ * counter instead (same results, slower on large fabrics).
  */
 nimble_status_t nimble_plan_solve(nimble_topo_t *topo, const double *d_traffic, double eps,
                                   int32_t iters, double *d_splits, double *d_lambda,
                                   void *hip_stream);
+
+/*
+ * Sizes the topology's choice log for streaming-regime solves of up to `iters` iterations
+ * (one byte per commodity, rounded up to 512, and iteration).  nimble_topo_create reserves 1024
+ * iterations by itself when that takes at most 64 MiB; larger fabrics or longer solves call
+ * this once, outside the solve loop: it may free and allocate device memory, which
+ * synchronises the device.  A log never shrinks.  NIMBLE_ERR_RANGE beyond 1 GiB,
+ * NIMBLE_ERR_ALLOC when the memory cannot be had (the topology keeps working, with per-path
+ * counters).
+ */
+nimble_status_t nimble_topo_reserve(nimble_topo_t *topo, int32_t iters);
 
 /*
  * `batch` independent plans on the same topology (one per MoE layer x micro-batch), solved
@@ -170,7 +183,8 @@ nimble_status_t nimble_alg1_solve_batch(nimble_topo_t *topo, int32_t batch,
  *           everywhere is the cold start).  Lengths grow by at most (1 + eps) per iteration:
  *           the caller rescales them (e.g. by a power of two, which changes nothing else)
  *           before they can overflow.
- * The other arguments as for nimble_plan_solve.  Always runs the streaming regime.
+ * The other arguments as for nimble_plan_solve.  Always runs the streaming regime; like
+ * nimble_plan_solve it only enqueues work.
  */
 nimble_status_t nimble_plan_solve_warm(nimble_topo_t *topo, const double *d_traffic, double eps,
                                        int32_t iters, double *d_len, double *d_splits,
@@ -198,8 +212,9 @@ nimble_status_t nimble_plan_solve_warm(nimble_topo_t *topo, const double *d_traf
  *   lower_bound  host out: best LB seen (0 if no check was made)
  * Unlike nimble_plan_solve this call synchronises hip_stream at every check and before it
  * returns.  Always runs the streaming regime; needs the per-iteration choice log of
- * max_iters rows (NIMBLE_ERR_ALLOC if it cannot be allocated).  Bit-identical to the plain CPU
- * definition for integer-valued demands.
+ * max_iters rows and grows it when it is shorter (NIMBLE_ERR_ALLOC if it cannot be allocated,
+ * NIMBLE_ERR_RANGE beyond 1 GiB), as well as a workspace of its own on the first call.
+ * Bit-identical to the plain CPU definition for integer-valued demands.
  */
 nimble_status_t nimble_plan_solve_adaptive(nimble_topo_t *topo, const double *d_traffic,
                                            double eps, int32_t max_iters, int32_t check_every,
@@ -256,103 +271,6 @@ int64_t nimble_topo_phase_bytes(const nimble_topo_t *topo, int32_t phase);
  * does not fit that regime.  The regime actually used is returned by nimble_topo_regime. */
 nimble_status_t nimble_topo_set_regime(nimble_topo_t *topo, int32_t regime);
 int32_t nimble_topo_regime(const nimble_topo_t *topo);
-
-/* 1 if the resident regime would run this topology with one commodity and one link per thread,
- * their candidate lists and reverse rows held in registers (at most 8 candidates of at most 2
- * links per commodity, at most 16 (commodity, mask) pairs per link); 0 if it keeps everything
- * in LDS; -1 for a NULL handle.  Both kernels return the same bits. */
-int32_t nimble_topo_resident_in_registers(const nimble_topo_t *topo);
-
-/*
- * Benchmark helper: enqueue `reps` back-to-back launches of one phase of the streaming regime
- * on `hip_stream`, without changing the plan state another solve depends on
- * (phase 0: path-cost gather + argmin, 1: link-load reduce, 2: length update with step 0; on
- * topologies whose reduce and update run as one kernel phase 1 is that kernel and phase 2 is
- * refused with NIMBLE_ERR_INVALID).  The state must have been initialised by a previous
- * streaming-regime nimble_plan_solve on this topology with the same d_traffic.  Used to time a
- * kernel's average launch with HIP events.
- */
-nimble_status_t nimble_debug_run_phase(nimble_topo_t *topo, int32_t phase, int32_t reps,
-                                       const double *d_traffic, void *hip_stream);
-
-/*
- * Benchmark helper: enqueue `reps` back-to-back launches of a plain streaming read of the first
- * `bytes` (rounded down to 16) of d_buf on `hip_stream` -- 16-byte loads, nothing computed.  The
- * benchmark times it to state the read bandwidth this machine reaches next to the published
- * peak.  d_buf and d_sink are device pointers, 16-byte aligned; d_sink is 16 bytes that the
- * kernel may write.  NIMBLE_ERR_INVALID for NULL or misaligned pointers, bytes < 16, reps < 1.
- */
-nimble_status_t nimble_debug_stream_read(const void *d_buf, int64_t bytes, int32_t reps,
-                                         void *d_sink, void *hip_stream);
-
-/*
- * Test helper for the persistent regime: every grid-wide barrier of that kernel waits at most
- * `polls` polls of its arrival counter (default 2^22, about a second).  When a wait expires the
- * solve is abandoned -- every workgroup leaves the kernel at its next poll, d_splits is left
- * undefined and d_lambda[0] is written as NaN.  With polls = 0 the first barrier that is not
- * already complete gives up, which lets a test exercise the abandon path without hanging
- * anything.
- */
-nimble_status_t nimble_debug_set_spin_limit(nimble_topo_t *topo, uint32_t polls);
-
-/*
- * Host-only helper (no device call): the reverse CSR exactly as nimble_topo_create builds it,
- * unpadded.  rev_ptr is host [n_links+1] out; rev_comm / rev_path are host [nnz] out (the
- * commodity and the candidate index inside that commodity of every incidence).  Returns the
- * same validation codes as nimble_topo_create.
- */
-nimble_status_t nimble_host_build_reverse(int32_t n_links, int32_t n_comm,
-                                          const int32_t *comm_path_ptr, int32_t n_paths,
-                                          const int32_t *path_link_ptr,
-                                          const int32_t *path_links, int32_t *rev_ptr,
-                                          int32_t *rev_comm, int32_t *rev_path);
-
-/*
- * Host-only helper (no device call): the same reverse CSR, but decoded from the streaming
- * layout the link-load kernel walks (flat octets under the two commodity numberings, slot
- * flags, chunked single pairs), with every row sorted by (commodity, path).  Must equal the
- * output of nimble_host_build_reverse.
- */
-nimble_status_t nimble_host_build_reverse_streaming(int32_t n_links, int32_t n_comm,
-                                                    const int32_t *comm_path_ptr,
-                                                    int32_t n_paths,
-                                                    const int32_t *path_link_ptr,
-                                                    const int32_t *path_links, int32_t *rev_ptr,
-                                                    int32_t *rev_comm, int32_t *rev_path);
-
-/*
- * Host-only helper (no device call): repacks the forward CSR into the self-contained records
- * of 3.5 or 4 KiB the path-cost kernel streams (a run of consecutive commodities, the record's
- * own link table, and a fixed number of 8-bit link-table indices per candidate, laid out lane by
- * lane or record-major) exactly as nimble_topo_create does, and reads every incidence back
- * through them.  links_out is host
- * [nnz] out and must equal path_links; path_record is host [n_paths] out, the record of every
- * path; n_records_out receives the number of records, or 0 when the topology does not fit
- * records (a path longer than 8 links, padding above 1.5x, more than 254 distinct links or
- * 4 KiB for a single commodity) -- then the untiled kernel is used and the other outputs are
- * not written.
- */
-nimble_status_t nimble_host_records_roundtrip(int32_t n_links, int32_t n_comm,
-                                            const int32_t *comm_path_ptr, int32_t n_paths,
-                                            const int32_t *path_link_ptr,
-                                            const int32_t *path_links, int32_t *links_out,
-                                              int32_t *path_record, int32_t *n_records_out);
-
-/*
- * Host-only helper (no device call): sizes of the device layout nimble_topo_create would build.
- * out is host int64 [16]: (commodity, window) pairs of the reverse CSR; octets (groups of 8
- * consecutive commodity ids with one mask each); single pairs; octets numbered by the second
- * commodity numbering; single-pair chunks; partial-sum slots; forward records; indices per
- * candidate in a record; link blocks of the fused reduce + update kernel (0: not used); octets
- * including padding; dense (link, window of 512 commodities) pieces; work items of up to 8
- * pieces; pieces stored as one mask plus presence bits; strip items (8 units of 8 octets x up
- * to 8 links that share them); links whose row lives in a strip; 1 if the bodies of the forward
- * records are laid out lane by lane (the record kernel then keeps them in registers), else 0.
- */
-nimble_status_t nimble_host_layout_stats(int32_t n_links, int32_t n_comm,
-                                         const int32_t *comm_path_ptr, int32_t n_paths,
-                                         const int32_t *path_link_ptr,
-                                         const int32_t *path_links, int64_t *out);
 
 #ifdef __cplusplus
 }

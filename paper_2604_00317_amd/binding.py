@@ -1,6 +1,7 @@
 """ctypes binding of libnimble_plan.so: argument marshalling only.
 
-The functions carry the names of the C ABI (include/nimble_plan.h).  Device buffers are torch
+The functions carry the names of the C ABI (include/nimble_plan.h, and
+include/nimble_plan_debug.h for the test and benchmark helpers).  Device buffers are torch
 tensors (torch is used for device memory and streams, nothing else); every step of a plan runs
 in the library's HIP kernels.  If the library is missing this module raises -- there is no
 fallback path.
@@ -31,7 +32,7 @@ EXPORTS = [
     "nimble_plan_solve_adaptive",
     "nimble_host_records_roundtrip", "nimble_host_layout_stats",
     "nimble_host_build_reverse_streaming", "nimble_topo_resident_in_registers",
-    "nimble_debug_stream_read",
+    "nimble_debug_stream_read", "nimble_topo_reserve", "nimble_host_resident_kernel",
 ]
 
 _lib = None
@@ -67,6 +68,10 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.nimble_topo_destroy.argtypes = [vp]
     lib.nimble_plan_solve.restype = ctypes.c_int
     lib.nimble_plan_solve.argtypes = [vp, vp, dbl, i32, vp, vp, vp]
+    lib.nimble_topo_reserve.restype = ctypes.c_int
+    lib.nimble_topo_reserve.argtypes = [vp, i32]
+    lib.nimble_host_resident_kernel.restype = ctypes.c_int
+    lib.nimble_host_resident_kernel.argtypes = [i32, i32, vp, i32, vp, vp, vp]
     lib.nimble_plan_solve_batch.restype = ctypes.c_int
     lib.nimble_plan_solve_batch.argtypes = [vp, i32, vp, dbl, i32, vp, vp, vp]
     lib.nimble_last_error.restype = ctypes.c_char_p
@@ -216,6 +221,10 @@ def nimble_topo_set_regime(topo: Topo, regime: int) -> None:
     _check(load_library().nimble_topo_set_regime(topo.handle, regime))
 
 
+def nimble_topo_reserve(topo: Topo, iters: int) -> None:
+    _check(load_library().nimble_topo_reserve(topo.handle, int(iters)))
+
+
 def nimble_plan_solve(topo: Topo, d_traffic, eps: float, iters: int, d_splits, d_lambda,
                       stream=None) -> None:
     """Enqueues one plan on `stream` (torch stream; None = current)."""
@@ -334,8 +343,23 @@ def nimble_host_records_roundtrip(n_links, n_comm, comm_path_ptr, n_paths, path_
     return links_out[:int(lp[-1])], path_rec[:n_paths], int(n_recs.value)
 
 
+def nimble_host_resident_kernel(n_links, n_comm, comm_path_ptr, n_paths, path_link_ptr,
+                                path_links) -> int:
+    """Host-only: 0 = the resident regime does not fit, 1 = its LDS kernel, 2 = its register
+    kernel (see include/nimble_plan_debug.h)."""
+    cp = _host(comm_path_ptr, np.int32)
+    lp = _host(path_link_ptr, np.int32)
+    pl = _host(path_links, np.int32)
+    out = ctypes.c_int32(-1)
+    st = load_library().nimble_host_resident_kernel(n_links, n_comm, _hp(cp), n_paths, _hp(lp),
+                                                    _hp(pl), ctypes.byref(out))
+    if st != NIMBLE_OK:
+        raise NimbleError(st, "invalid CSR")
+    return int(out.value)
+
+
 def nimble_host_layout_stats(n_links, n_comm, comm_path_ptr, n_paths, path_link_ptr, path_links):
-    """Host-only: dict of the sizes of the device layout (see include/nimble_plan.h)."""
+    """Host-only: dict of the sizes of the device layout (see include/nimble_plan_debug.h)."""
     cp = _host(comm_path_ptr, np.int32)
     lp = _host(path_link_ptr, np.int32)
     pl = _host(path_links, np.int32)
@@ -355,6 +379,11 @@ def plan(topo: Topo, traffic, eps: float, iters: int, device: str = "cuda:0"):
     import torch
     d = torch.as_tensor(np.ascontiguousarray(traffic, dtype=np.float64)).to(device)
     nan = float("nan")     # outputs start poisoned so that stale memory can never pass a check
+    try:
+        nimble_topo_reserve(topo, iters)  # the choice log, sized outside the solve
+    except NimbleError as err:            # too long a log: the solve keeps per-path counters
+        if err.status not in (NIMBLE_ERR_RANGE, NIMBLE_ERR_ALLOC):
+            raise
     if d.dim() == 1:
         splits = torch.full((topo.n_paths,), nan, dtype=torch.float64, device=device)
         lam = torch.full((1,), nan, dtype=torch.float64, device=device)

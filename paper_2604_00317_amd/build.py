@@ -17,16 +17,27 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=o
          "-Wno-unused-command-line-argument"]
 
 
-def build(verbose: bool = False) -> str:
+def build(verbose: bool = False, jobs: int = 8) -> str:
+    """Compiles every source to an object file (side by side, `jobs` at a time) and links them."""
+    from concurrent.futures import ThreadPoolExecutor
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     extra = os.environ.get("NIMBLE_EXTRA_HIPCC_FLAGS", "").split()
-    cmd = [hipcc, *FLAGS, *extra, "-shared", "-o", LIB]
-    for s in SOURCES:
+    objdir = os.path.join(_HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+
+    def compile_one(s: str) -> str:
         src = os.path.join(CSRC, s)
-        if s.endswith(".cpp"):
-            cmd += ["-x", "hip", src]
-        else:
-            cmd.append(src)
+        obj = os.path.join(objdir, os.path.splitext(s)[0] + ".o")
+        cmd = [hipcc, *FLAGS, *extra, "-c", "-o", obj]
+        cmd += ["-x", "hip", src] if s.endswith(".cpp") else [src]
+        if verbose:
+            print(" ".join(cmd))
+        subprocess.run(cmd, check=True)
+        return obj
+
+    with ThreadPoolExecutor(max_workers=max(1, jobs)) as pool:
+        objs = list(pool.map(compile_one, SOURCES))
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     if verbose:
         print(" ".join(cmd))
     subprocess.run(cmd, check=True)

@@ -13,6 +13,7 @@
 #include <vector>
 
 #include "../../include/nimble_plan.h"
+#include "../../include/nimble_plan_debug.h"
 #include "host_topo.hpp"
 #include "kernels.hpp"
 
@@ -43,11 +44,13 @@ struct nimble_topo {
     int32_t last_regime = NIMBLE_REGIME_AUTO;
     int64_t bytes_per_iter = 0, bytes_argmin = 0, bytes_reduce = 0, bytes_update = 0;
     bool state_ready = false;   // a stream-regime solve has initialised the workspace
+    uint8_t *state_log = nullptr;   // the log that solve wrote its choices to (null: counters)
     // per-iteration choice log of the streaming regime (rows of log_stride bytes); grows on
     // demand, so the first solve with more iterations than any before allocates
     uint8_t *choice_log = nullptr;
     int64_t log_rows = 0;
     size_t log_stride = 0;
+    bool no_choice_log = false;  // tuning switch read at create: keep per-path counters instead
     // workspace of the adaptive-step variant; the sigma log grows with max_iters
     nimble::AdaptiveState ad{};
     bool ad_ready = false;
@@ -97,28 +100,39 @@ void release(nimble_topo *t)
     t->ad_sigma_rows = 0;
 }
 
-// Makes sure the choice log holds `iters` rows; false when it cannot (too large or out of
-// memory), in which case the solve keeps per-path counts instead.
-bool ensure_choice_log(nimble_topo *t, int32_t iters)
+// Bytes of one row of a choice log: whole windows of choices (the tile phase reads them 512 at
+// a time), with room for the 8 spare entries an octet may touch.
+size_t choice_log_stride(const nimble_topo *t)
 {
-    if (std::getenv("NIMBLE_TUNE_NO_CHOICE_LOG")) return false;
-    if (t->log_rows >= iters) return true;
-    // a row holds whole windows of choices (the tile phase reads them 512 at a time)
-    const size_t stride = (static_cast<size_t>(t->d.K) + 8 + 511) & ~static_cast<size_t>(511);
+    return (static_cast<size_t>(t->d.K) + 8 + 511) & ~static_cast<size_t>(511);
+}
+
+constexpr size_t kChoiceLogCap = static_cast<size_t>(1) << 30;       // most a topology reserves
+constexpr size_t kChoiceLogAtCreate = static_cast<size_t>(64) << 20; // reserved without being asked
+constexpr int32_t kDefaultLogRows = 1024;
+
+// Makes the choice log hold `iters` rows; may free and allocate (both synchronise the device).
+// Only nimble_topo_create, nimble_topo_reserve and the adaptive solve call this -- never
+// nimble_plan_solve, which uses the log it finds or keeps per-path counters.
+nimble_status_t grow_choice_log(nimble_topo *t, int32_t iters)
+{
+    if (t->log_rows >= iters) return NIMBLE_OK;
+    const size_t stride = choice_log_stride(t);
     const size_t bytes = stride * static_cast<size_t>(iters);
-    if (bytes > (static_cast<size_t>(4) << 30)) return false;
+    if (bytes > kChoiceLogCap)
+        return fail(NIMBLE_ERR_RANGE, "the choice log of that many iterations exceeds 1 GiB");
     if (t->choice_log) (void)hipFree(t->choice_log);      // waits for work that still uses it
     t->choice_log = nullptr;
     t->log_rows = 0;
     void *p = nullptr;
     if (hipMalloc(&p, bytes) != hipSuccess) {
         (void)hipGetLastError();
-        return false;
+        return fail(NIMBLE_ERR_ALLOC, "the choice log cannot be allocated");
     }
     t->choice_log = static_cast<uint8_t *>(p);
     t->log_rows = iters;
     t->log_stride = stride;
-    return true;
+    return NIMBLE_OK;
 }
 
 nimble_status_t check_solve_args(const nimble_topo *topo, const double *d_traffic, double eps,
@@ -162,19 +176,20 @@ int32_t pick_regime(const nimble_topo *topo, int32_t batch)
     return resident_us < stream_us ? NIMBLE_REGIME_RESIDENT : NIMBLE_REGIME_STREAM;
 }
 
+// One streaming-regime solve.  Only enqueues kernels: nothing is allocated, freed or
+// synchronised here.  `log` (rows of `log_stride` bytes, at least `iters` of them) receives the
+// choices of every iteration and the split fractions are counted from it once at the end; with
+// log == nullptr every iteration bumps a per-path counter instead.
 nimble_status_t solve_stream(nimble_topo *topo, const double *d_traffic, double eps,
                              int32_t iters, double *d_splits, double *d_lambda, hipStream_t s,
-                             double *d_len = nullptr)
+                             uint8_t *log, size_t log_stride, double *d_len = nullptr)
 {
     const nimble::DeviceTopo &d = topo->d;
-    // choices are logged per iteration when the log fits (the split fractions are then
-    // counted once at the end); otherwise every iteration bumps a per-path counter
-    const bool logged = ensure_choice_log(topo, iters);
+    const bool logged = log != nullptr;
     nimble::launch_init(d, d_traffic, d_len, s);
     nimble::launch_width(d, d_traffic, s);
     for (int32_t it = 0; it < iters; ++it) {
-        uint8_t *row = logged ? topo->choice_log + topo->log_stride * static_cast<size_t>(it)
-                              : d.choice;
+        uint8_t *row = logged ? log + log_stride * static_cast<size_t>(it) : d.choice;
         nimble::launch_argmin(d, row, logged ? nullptr : d.count, s);
         if (d.n_blocks > 0) {
             nimble::launch_reduce_update(d, row, d_traffic, eps, s);
@@ -184,13 +199,19 @@ nimble_status_t solve_stream(nimble_topo *topo, const double *d_traffic, double 
         }
     }
     nimble::launch_epilogue(d, iters, logged ? nullptr : d.count, d_splits, d_lambda, s);
-    if (logged)
-        nimble::launch_histogram(d, topo->choice_log, topo->log_stride, iters, d_splits, s);
+    if (logged) nimble::launch_histogram(d, log, log_stride, iters, d_splits, s);
     if (d_len) nimble::launch_export_len(d, d_len, s);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail_hip(e, "kernel launch (streaming regime)");
     topo->state_ready = true;
+    topo->state_log = logged ? log : nullptr;
     return NIMBLE_OK;
+}
+
+// The topology's own choice log when it holds `iters` rows, else none (per-path counters).
+uint8_t *own_log(const nimble_topo *topo, int32_t iters)
+{
+    return (!topo->no_choice_log && topo->log_rows >= iters) ? topo->choice_log : nullptr;
 }
 
 nimble_status_t solve_persistent(nimble_topo *topo, const double *d_traffic, double eps,
@@ -255,6 +276,7 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     d.rev_pairs = static_cast<int64_t>(h.rev_pair.size() / 2);
     d.rev_row_max = 0;
     for (int32_t len : h.rev_rowlen) d.rev_row_max = std::max(d.rev_row_max, len);
+    t->no_choice_log = std::getenv("NIMBLE_TUNE_NO_CHOICE_LOG") != nullptr;
     d.resident_generic = std::getenv("NIMBLE_TUNE_RESIDENT_GENERIC") ? 1 : 0;
     d.alg1_thread_per_problem = std::getenv("NIMBLE_TUNE_ALG1_THREAD_PER_PROBLEM") ? 1 : 0;
     d.n_records = h.n_records;
@@ -400,7 +422,19 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
             if (std::atoi(env) > 0) rec_per_cu = std::atoi(env);
         d.rec_blocks = t->n_cu * rec_per_cu;
     }
+
 #undef NIMBLE_TRY
+    // a choice log for solves of up to kDefaultLogRows iterations, when that is small; larger
+    // ones are the caller's decision (nimble_topo_reserve)
+    if (!t->no_choice_log &&
+        choice_log_stride(t) * static_cast<size_t>(kDefaultLogRows) <= kChoiceLogAtCreate) {
+        nimble_status_t st_log = grow_choice_log(t, kDefaultLogRows);
+        if (st_log != NIMBLE_OK) {
+            release(t);
+            delete t;
+            return st_log;
+        }
+    }
 
     // stored bytes one iteration streams, phase by phase
     if (d.n_records > 0)
@@ -499,7 +533,8 @@ nimble_status_t nimble_plan_solve(nimble_topo_t *topo, const double *d_traffic, 
     }
     if (regime == NIMBLE_REGIME_PERSISTENT)
         return solve_persistent(topo, d_traffic, eps, iters, d_splits, d_lambda, s);
-    return solve_stream(topo, d_traffic, eps, iters, d_splits, d_lambda, s);
+    return solve_stream(topo, d_traffic, eps, iters, d_splits, d_lambda, s, own_log(topo, iters),
+                        topo->log_stride);
 }
 
 nimble_status_t nimble_plan_solve_batch(nimble_topo_t *topo, int32_t batch,
@@ -526,9 +561,55 @@ nimble_status_t nimble_plan_solve_batch(nimble_topo_t *topo, int32_t batch,
         double *sp = d_splits + static_cast<size_t>(b) * topo->d.P;
         st = regime == NIMBLE_REGIME_PERSISTENT
                  ? solve_persistent(topo, tr, eps, iters, sp, d_lambda + b, s)
-                 : solve_stream(topo, tr, eps, iters, sp, d_lambda + b, s);
+                 : solve_stream(topo, tr, eps, iters, sp, d_lambda + b, s, own_log(topo, iters),
+                                topo->log_stride);
         if (st != NIMBLE_OK) return st;
     }
+    return NIMBLE_OK;
+}
+
+nimble_status_t nimble_topo_reserve(nimble_topo_t *topo, int32_t iters)
+{
+    g_last_error.clear();
+    if (!topo) return fail(NIMBLE_ERR_INVALID, "topology handle is NULL");
+    if (iters < 1) return fail(NIMBLE_ERR_INVALID, "iters must be >= 1");
+    nimble_status_t st = check_device(topo);
+    if (st != NIMBLE_OK) return st;
+    if (topo->no_choice_log) return NIMBLE_OK;
+    return grow_choice_log(topo, iters);
+}
+
+nimble_status_t nimble_host_resident_kernel(int32_t n_links, int32_t n_comm,
+                                            const int32_t *comm_path_ptr, int32_t n_paths,
+                                            const int32_t *path_link_ptr,
+                                            const int32_t *path_links, int32_t *kernel_out)
+{
+    g_last_error.clear();
+    if (!kernel_out) return fail(NIMBLE_ERR_INVALID, "kernel_out is NULL");
+    std::vector<double> cap(n_links > 0 ? static_cast<size_t>(n_links) : 0, 1.0);
+    std::string why;
+    nimble_status_t st = nimble::validate_csr(n_links, cap.data(), n_comm, comm_path_ptr, n_paths,
+                                              path_link_ptr, path_links, why);
+    if (st != NIMBLE_OK) return fail(st, why);
+    nimble::HostTopo h;
+    try {
+        nimble::read_layout_options(h);
+        nimble::build_host_topo(n_links, cap.data(), n_comm, comm_path_ptr, n_paths,
+                                path_link_ptr, path_links, h);
+    } catch (const std::bad_alloc &) {
+        return fail(NIMBLE_ERR_ALLOC, "host allocation failed");
+    }
+    nimble::DeviceTopo d{};
+    d.E = h.E;
+    d.K = h.K;
+    d.P = h.P;
+    d.nnz = h.nnz;
+    d.pmax = h.pmax;
+    d.lmax = h.lmax;
+    d.rev_pairs = static_cast<int64_t>(h.rev_pair.size() / 2);
+    for (int32_t len : h.rev_rowlen) d.rev_row_max = std::max(d.rev_row_max, len);
+    d.resident_generic = std::getenv("NIMBLE_TUNE_RESIDENT_GENERIC") ? 1 : 0;
+    *kernel_out = !nimble::resident_fits(d) ? 0 : (nimble::resident_in_registers(d) ? 2 : 1);
     return NIMBLE_OK;
 }
 
@@ -570,7 +651,8 @@ nimble_status_t nimble_plan_solve_warm(nimble_topo_t *topo, const double *d_traf
     if (st != NIMBLE_OK) return st;
     topo->last_regime = NIMBLE_REGIME_STREAM;
     return solve_stream(topo, d_traffic, eps, iters, d_splits, d_lambda,
-                        static_cast<hipStream_t>(hip_stream), d_len);
+                        static_cast<hipStream_t>(hip_stream), own_log(topo, iters),
+                        topo->log_stride, d_len);
 }
 
 nimble_status_t nimble_plan_solve_adaptive(nimble_topo_t *topo, const double *d_traffic,
@@ -592,7 +674,10 @@ nimble_status_t nimble_plan_solve_adaptive(nimble_topo_t *topo, const double *d_
     nimble::AdaptiveState &a = topo->ad;
     hipError_t e = hipSuccess;
     if (!topo->ad_ready) {
+        // all or nothing: what a failed attempt did allocate is given back, so that a retry
+        // does not pile up buffers
         const size_t n_chunks = (static_cast<size_t>(d.K) + 255) / 256 + (static_cast<size_t>(d.E) + 255) / 256;
+        const size_t mark = topo->allocs.size();
         e = allocate(topo, 2, &a.flags);
         if (e == hipSuccess) e = allocate(topo, 4, &a.ascal);
         if (e == hipSuccess) e = allocate(topo, static_cast<size_t>(d.K), &a.term);
@@ -600,9 +685,15 @@ nimble_status_t nimble_plan_solve_adaptive(nimble_topo_t *topo, const double *d_
         if (e == hipSuccess) e = allocate(topo, static_cast<size_t>(d.E), &a.u_pos);
         if (e == hipSuccess) e = allocate(topo, (static_cast<size_t>(d.E) + 15) / 16, &a.block_max_u);
         if (e == hipSuccess) e = allocate(topo, (static_cast<size_t>(d.E) + 255) / 256, &a.block_max_s);
-        if (e != hipSuccess)
+        if (e != hipSuccess) {
+            while (topo->allocs.size() > mark) {
+                (void)hipFree(topo->allocs.back());
+                topo->allocs.pop_back();
+            }
+            (void)hipGetLastError();
             return e == hipErrorOutOfMemory ? fail(NIMBLE_ERR_ALLOC, "adaptive workspace")
                                             : fail_hip(e, "adaptive workspace");
+        }
         topo->ad_ready = true;
     }
     if (topo->ad_sigma_rows < max_iters) {
@@ -618,8 +709,10 @@ nimble_status_t nimble_plan_solve_adaptive(nimble_topo_t *topo, const double *d_
         topo->ad_sigma_rows = max_iters;
     }
     // the weighted split fractions need the choice of every iteration
-    if (std::getenv("NIMBLE_TUNE_NO_CHOICE_LOG") || !ensure_choice_log(topo, max_iters))
-        return fail(NIMBLE_ERR_ALLOC, "the choice log of max_iters rows cannot be allocated");
+    if (topo->no_choice_log)
+        return fail(NIMBLE_ERR_ALLOC, "the adaptive solve needs the choice log, which is switched off");
+    st = grow_choice_log(topo, max_iters);
+    if (st != NIMBLE_OK) return st;
     topo->last_regime = NIMBLE_REGIME_STREAM;
     const double gap = (1.0 + eps) * (1.0 + eps);
     nimble::launch_ad_reset(a, s);
@@ -653,6 +746,7 @@ nimble_status_t nimble_plan_solve_adaptive(nimble_topo_t *topo, const double *d_
     *iters_done = flags_host[1];
     *lower_bound = ascal_host[2];
     topo->state_ready = true;
+    topo->state_log = topo->choice_log;
     return NIMBLE_OK;
 }
 
@@ -700,8 +794,8 @@ nimble_status_t nimble_debug_run_phase(nimble_topo_t *topo, int32_t phase, int32
     if (st != NIMBLE_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(hip_stream);
     for (int32_t r = 0; r < reps; ++r) {
-        uint8_t *row = topo->log_rows > 0 ? topo->choice_log : topo->d.choice;
-        if (phase == 0) nimble::launch_argmin(topo->d, row, topo->log_rows > 0 ? nullptr : topo->d.count, s);
+        uint8_t *row = topo->state_log ? topo->state_log : topo->d.choice;
+        if (phase == 0) nimble::launch_argmin(topo->d, row, topo->state_log ? nullptr : topo->d.count, s);
         else if (phase == 1 && topo->d.n_blocks > 0)
             nimble::launch_reduce_update(topo->d, row, d_traffic, 0.0, s);
         else if (phase == 1) nimble::launch_load_reduce(topo->d, row, d_traffic, s);

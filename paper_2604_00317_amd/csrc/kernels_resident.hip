@@ -448,8 +448,10 @@ bool plan_resident(const DeviceTopo &t, int batch, ResidentPlan &rp)
     // the topology copy may take the LDS beyond 64 KB (the launch opts in)
     rp.topo_lds = lay.plan_bytes * ppb + lay.topo_bytes + 256 <= kLdsBudgetMax;
     rp.lds_bytes = lay.plan_bytes * ppb + (rp.topo_lds ? lay.topo_bytes : 0);
+    // the register kernel gives every thread exactly one commodity and one link (no striding):
+    // a plan with more of either than its threads keeps to the LDS kernel, which strides
     rp.in_registers = !t.resident_generic && t.pmax <= kRegMaxPaths && t.lmax <= kRegMaxLen &&
-                      t.rev_row_max <= kRegMaxRow;
+                      t.rev_row_max <= kRegMaxRow && need <= nt;
     if (rp.in_registers) rp.lds_bytes = reg_plan_bytes(t.E, t.K, nt, kRegMaxPaths) * ppb;
     return true;
 }

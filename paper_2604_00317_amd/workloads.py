@@ -349,3 +349,35 @@ def random_topology(rng: np.random.Generator, n_links: int, n_comm: int, max_pat
                     path_links=np.asarray(pl, dtype=np.int32),
                     src=np.zeros(K, dtype=np.int32), dst=np.zeros(K, dtype=np.int32),
                     meta=dict(kind="random"))
+
+
+def two_candidate_mesh(G: int) -> Topology:
+    """Full mesh of G GPUs (G odd), every ordered pair (s, d) with two candidates: the direct
+    link and the relay r = 2d - s mod G, which is neither s nor d and puts exactly one relay
+    path on each hop of every link.  K = E = G (G - 1), three pairs per link: small enough for
+    the register kernel of the resident regime in every respect but the number of commodities
+    and links."""
+    assert G % 2 == 1
+    link = {}
+    for a in range(G):
+        for b in range(G):
+            if a != b:
+                link[(a, b)] = len(link)
+    cp, lp, pl = [0], [0], []
+    for s in range(G):
+        for d in range(G):
+            if s == d:
+                continue
+            r = (2 * d - s) % G
+            pl += [link[(s, d)]]
+            lp.append(len(pl))
+            pl += [link[(s, r)], link[(r, d)]]
+            lp.append(len(pl))
+            cp.append(len(lp) - 1)
+    n = len(link)
+    return Topology(n_links=n, cap=np.full(n, 100e9), n_comm=n,
+                      comm_path_ptr=np.asarray(cp, dtype=np.int32), n_paths=len(lp) - 1,
+                      path_link_ptr=np.asarray(lp, dtype=np.int32),
+                      path_links=np.asarray(pl, dtype=np.int32),
+                      src=np.zeros(n, dtype=np.int32), dst=np.zeros(n, dtype=np.int32),
+                      meta=dict(kind="mesh2"))

@@ -16,7 +16,10 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 def test_library_exports_every_declared_symbol():
     lib = B.load_library()
-    header = open(os.path.join(ROOT, "include", "nimble_plan.h")).read()
+    header = ""
+    for name in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        if name.endswith(".h"):
+            header += open(os.path.join(ROOT, "include", name)).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
     declared = set(re.findall(r"\b(nimble_[a-z0-9_]+)\s*\(", header))
     assert declared, "no declarations found"
@@ -249,3 +252,23 @@ def test_streaming_reverse_layout_random(seed, E, K, pm, lm):
         assert st["link_blocks"] == 0
     else:
         assert st["link_blocks"] > 0
+
+
+def test_register_kernel_only_when_a_thread_per_commodity_and_link_exists():
+    """The register kernel of the resident regime has no striding: one commodity and one link
+    per thread of a workgroup of at most 1024.  A fabric with short lists but more commodities
+    or links than that must take the LDS kernel (kernel 1), not the register kernel (2)."""
+    for G, want in ((9, 2), (31, 2), (33, 1), (35, 1)):
+        t = W.two_candidate_mesh(G)
+        assert t.n_comm == G * (G - 1)
+        got = B.nimble_host_resident_kernel(t.n_links, t.n_comm, t.comm_path_ptr, t.n_paths,
+                                            t.path_link_ptr, t.path_links)
+        assert got == want, (G, got)
+    w = W.make_config(0)
+    t = w.topo
+    assert B.nimble_host_resident_kernel(t.n_links, t.n_comm, t.comm_path_ptr, t.n_paths,
+                                         t.path_link_ptr, t.path_links) == 2
+    w = W.make_config(3)
+    t = w.topo
+    assert B.nimble_host_resident_kernel(t.n_links, t.n_comm, t.comm_path_ptr, t.n_paths,
+                                         t.path_link_ptr, t.path_links) == 0

@@ -134,6 +134,23 @@ def test_resident_regime_register_and_lds_kernels(oracle_mod, B, monkeypatch, se
         check(oracle_mod, B, t, d, 0.07, 60, 1, flags)
 
 
+def test_resident_regime_with_more_commodities_and_links_than_threads(oracle_mod, B):
+    """A 35-GPU mesh with two candidates per pair: K = E = 1190, lists short enough for the
+    register kernel but more commodities and links than a workgroup has threads.  The resident
+    regime must stride (LDS kernel): every commodity routed, every link priced."""
+    t = W.two_candidate_mesh(35)
+    rng = np.random.default_rng(34)
+    d = np.floor(rng.pareto(1.1, t.n_comm) * 1e6)
+    h = B.nimble_topo_create(*t.csr())
+    try:
+        assert not h.resident_in_registers
+    finally:
+        h.close()
+    for flags in (0, 1):
+        check(oracle_mod, B, t, d, 0.07, 40, 1, flags)
+        check(oracle_mod, B, t, d, 0.07, 40, 0, flags)     # whatever the library picks itself
+
+
 def test_regime_chosen_from_batch_size_and_row_lengths(oracle_mod, B):
     """The two-node fabric fits the resident regime, but its rail links carry 64 pairs each: one
     plan is streamed (two short kernels per iteration beat one thread walking such a row), a
