@@ -130,6 +130,24 @@ nimble_status_t nimble_plan_solve(nimble_topo_t *topo, const double *d_traffic, 
 nimble_status_t nimble_topo_reserve(nimble_topo_t *topo, int32_t iters);
 
 /*
+ * nimble_plan_solve for callers that cannot allocate device memory and cannot let the library
+ * do it either: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same results, always the streaming regime; the per-iteration
+ * choice log lives in a buffer of nimble_static_scratch_bytes() bytes (32 MiB) that is part
+ * of the library's device image -- every GPU the library runs on holds one until the process
+ * ends -- instead of the topology's own log.  The call allocates and frees nothing and does
+ * not synchronise.
+ *   limit   (n_comm + 8 rounded up to 512) * iters <= nimble_static_scratch_bytes(), else
+ *           NIMBLE_ERR_RANGE (1000 iterations of 16 256 commodities fit, of 261 632 do not)
+ *   sharing all topologies on one GPU share the buffer: calls that overlap on one GPU (two
+ *           streams, two threads) race on it; calls on one stream, one after the other, do not
+ */
+nimble_status_t nimble_plan_solve_static(nimble_topo_t *topo, const double *d_traffic, double eps,
+                                         int32_t iters, double *d_splits, double *d_lambda,
+                                         void *hip_stream);
+int64_t nimble_static_scratch_bytes(void);
+
+/*
  * `batch` independent plans on the same topology (one per MoE layer x micro-batch), solved
  * concurrently.  d_traffic is device [batch][n_comm], d_splits device [batch][n_paths],
  * d_lambda device [batch]; the rest as nimble_plan_solve.  batch >= 1.  Topologies whose

@@ -33,6 +33,7 @@ EXPORTS = [
     "nimble_host_records_roundtrip", "nimble_host_layout_stats",
     "nimble_host_build_reverse_streaming", "nimble_topo_resident_in_registers",
     "nimble_debug_stream_read", "nimble_topo_reserve", "nimble_host_resident_kernel",
+    "nimble_plan_solve_static", "nimble_static_scratch_bytes",
 ]
 
 _lib = None
@@ -68,6 +69,10 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.nimble_topo_destroy.argtypes = [vp]
     lib.nimble_plan_solve.restype = ctypes.c_int
     lib.nimble_plan_solve.argtypes = [vp, vp, dbl, i32, vp, vp, vp]
+    lib.nimble_plan_solve_static.restype = ctypes.c_int
+    lib.nimble_plan_solve_static.argtypes = [vp, vp, dbl, i32, vp, vp, vp]
+    lib.nimble_static_scratch_bytes.restype = i64
+    lib.nimble_static_scratch_bytes.argtypes = []
     lib.nimble_topo_reserve.restype = ctypes.c_int
     lib.nimble_topo_reserve.argtypes = [vp, i32]
     lib.nimble_host_resident_kernel.restype = ctypes.c_int
@@ -232,6 +237,19 @@ def nimble_plan_solve(topo: Topo, d_traffic, eps: float, iters: int, d_splits, d
         topo.handle, _dev_ptr(d_traffic, "float64", topo.n_comm, "d_traffic"), float(eps),
         int(iters), _dev_ptr(d_splits, "float64", topo.n_paths, "d_splits"),
         _dev_ptr(d_lambda, "float64", 1, "d_lambda"), _stream_ptr(stream)))
+
+
+def nimble_plan_solve_static(topo: Topo, d_traffic, eps: float, iters: int, d_splits, d_lambda,
+                             stream=None) -> None:
+    """nimble_plan_solve with its choice log in the library's static device scratch."""
+    _check(load_library().nimble_plan_solve_static(
+        topo.handle, _dev_ptr(d_traffic, "float64", topo.n_comm, "d_traffic"), float(eps),
+        int(iters), _dev_ptr(d_splits, "float64", topo.n_paths, "d_splits"),
+        _dev_ptr(d_lambda, "float64", 1, "d_lambda"), _stream_ptr(stream)))
+
+
+def nimble_static_scratch_bytes() -> int:
+    return int(load_library().nimble_static_scratch_bytes())
 
 
 def nimble_plan_solve_batch(topo: Topo, batch: int, d_traffic, eps: float, iters: int, d_splits,

@@ -8,6 +8,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -17,6 +18,17 @@
 #include "host_topo.hpp"
 #include "kernels.hpp"
 
+#ifndef NIMBLE_STATIC_SCRATCH_BYTES
+#define NIMBLE_STATIC_SCRATCH_BYTES (32u << 20)
+#endif
+
+
+// Scratch of nimble_plan_solve_static: the per-iteration choice log of one streaming-regime
+// solve.  Every GPU the library runs on holds its own copy of this array until the process
+// ends.  Host code never uses the array's name as an address: the address on a device comes
+// from hipGetSymbolAddress (static_scratch_of) and is what kernels are given.
+constexpr size_t kStaticScratchBytes = static_cast<size_t>(NIMBLE_STATIC_SCRATCH_BYTES);
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
 
 namespace {
 
@@ -32,6 +44,31 @@ nimble_status_t fail_hip(hipError_t e, const char *what)
 {
     g_last_error = std::string(what) + ": " + hipGetErrorString(e);
     return NIMBLE_ERR_HIP;
+}
+
+// Device address of `scratch` on every device, resolved once per device with that device
+// current (every GPU holds its own copy of the array at its own address).
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+hipError_t static_scratch_of(int device, unsigned char **out)
+{
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[device]) {
+        int cur = -1;
+        hipError_t e = hipGetDevice(&cur);
+        if (e != hipSuccess) return e;
+        if (cur != device) return hipErrorInvalidDevice;
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        g_scratch_ptr[device] = p;
+    }
+    *out = static_cast<unsigned char *>(g_scratch_ptr[device]);
+    return hipSuccess;
 }
 
 }  // namespace
@@ -423,6 +460,11 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
         d.rec_blocks = t->n_cu * rec_per_cu;
     }
 
+    {
+        // the address of the static scratch on this device (nimble_plan_solve_static)
+        unsigned char *sp = nullptr;
+        NIMBLE_TRY(static_scratch_of(t->device, &sp), "hipGetSymbolAddress (static scratch)");
+    }
 #undef NIMBLE_TRY
     // a choice log for solves of up to kDefaultLogRows iterations, when that is small; larger
     // ones are the caller's decision (nimble_topo_reserve)
@@ -577,6 +619,33 @@ nimble_status_t nimble_topo_reserve(nimble_topo_t *topo, int32_t iters)
     if (st != NIMBLE_OK) return st;
     if (topo->no_choice_log) return NIMBLE_OK;
     return grow_choice_log(topo, iters);
+}
+
+int64_t nimble_static_scratch_bytes(void) { return static_cast<int64_t>(kStaticScratchBytes); }
+
+nimble_status_t nimble_plan_solve_static(nimble_topo_t *topo, const double *d_traffic, double eps,
+                                         int32_t iters, double *d_splits, double *d_lambda,
+                                         void *hip_stream)
+{
+    g_last_error.clear();
+    nimble_status_t st = check_solve_args(topo, d_traffic, eps, iters, d_splits, d_lambda);
+    if (st != NIMBLE_OK) return st;
+    st = check_device(topo);
+    if (st != NIMBLE_OK) return st;
+    const size_t stride = choice_log_stride(topo);
+    if (stride * static_cast<size_t>(iters) > kStaticScratchBytes)
+        return fail(NIMBLE_ERR_RANGE,
+                    "choice log (commodities rounded up to 512, times iters) exceeds the static "
+                    "scratch of " + std::to_string(kStaticScratchBytes) + " bytes");
+    // resolved at nimble_topo_create on this device; this lookup only reads the table
+    unsigned char *log = nullptr;
+    hipError_t e = static_scratch_of(topo->device, &log);
+    if (e != hipSuccess) return fail_hip(e, "hipGetSymbolAddress (static scratch)");
+    topo->last_regime = NIMBLE_REGIME_STREAM;
+    // every row of the log is written (entries 0..K-1) before it is read and nothing has to
+    // start at zero, so what the previous call left behind does no harm
+    return solve_stream(topo, d_traffic, eps, iters, d_splits, d_lambda,
+                        static_cast<hipStream_t>(hip_stream), log, stride);
 }
 
 nimble_status_t nimble_host_resident_kernel(int32_t n_links, int32_t n_comm,
