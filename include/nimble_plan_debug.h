@@ -79,12 +79,13 @@ nimble_status_t nimble_host_build_reverse_streaming(int32_t n_links, int32_t n_c
 
 /*
  * Host-only helper (no device call): repacks the forward CSR into the self-contained records
- * of 3.5 or 4 KiB the path-cost kernel streams (a run of consecutive commodities, the record's
+ * of 3.5 or 4 KiB (1 KiB plus a dictionary of bodies where many records share their bodies)
+ * the path-cost kernel streams (a run of consecutive commodities, the record's
  * own link table, and a fixed number of 8-bit link-table indices per candidate, laid out lane by
  * lane or record-major) exactly as nimble_topo_create does, and reads every incidence back
  * through them.  links_out is host
  * [nnz] out and must equal path_links; path_record is host [n_paths] out, the record of every
- * path; n_records_out receives the number of records, or 0 when the topology does not fit
+ * path (records numbered by their first commodity); n_records_out receives the number of records, or 0 when the topology does not fit
  * records (a path longer than 8 links, padding above 1.5x, more than 254 distinct links or
  * 4 KiB for a single commodity) -- then the untiled kernel is used and the other outputs are
  * not written.
@@ -97,14 +98,16 @@ nimble_status_t nimble_host_records_roundtrip(int32_t n_links, int32_t n_comm,
 
 /*
  * Host-only helper (no device call): sizes of the device layout nimble_topo_create would build.
- * out is host int64 [16]: (commodity, window) pairs of the reverse CSR; octets (groups of 8
+ * out is host int64 [18]: (commodity, window) pairs of the reverse CSR; octets (groups of 8
  * consecutive commodity ids with one mask each); single pairs; octets numbered by the second
  * commodity numbering; single-pair chunks; partial-sum slots; forward records; indices per
  * candidate in a record; link blocks of the fused reduce + update kernel (0: not used); octets
  * including padding; dense (link, window of 512 commodities) pieces; work items of up to 8
  * pieces; pieces stored as one mask plus presence bits; strip items (8 units of 8 octets x up
  * to 8 links that share them); links whose row lives in a strip; 1 if the bodies of the forward
- * records are laid out lane by lane (the record kernel then keeps them in registers), else 0.
+ * records are laid out lane by lane (the record kernel then keeps them in registers), else 0;
+ * 1 if those bodies are kept once each in a dictionary (records of 1 KiB that name their body),
+ * else 0; the number of distinct bodies in that dictionary.
  */
 nimble_status_t nimble_host_layout_stats(int32_t n_links, int32_t n_comm,
                                          const int32_t *comm_path_ptr, int32_t n_paths,

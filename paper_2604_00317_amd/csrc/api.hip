@@ -325,6 +325,8 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
         if (std::atoi(env) >= 1 && std::atoi(env) <= 64) d.rec_per_wave = std::atoi(env);
     d.rec_lane_major = h.rec_lane_major;
     d.rec_table16 = h.rec_table16;
+    d.rec_dict = h.rec_dict;
+    d.n_bodies = h.n_bodies;
     d.rec_around_l2 = -1;
     if (const char *env = std::getenv("NIMBLE_TUNE_RECORD_AROUND_L2"))
         d.rec_around_l2 = std::atoi(env) != 0 ? 1 : 0;
@@ -459,6 +461,47 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
             if (std::atoi(env) > 0) rec_per_cu = std::atoi(env);
         d.rec_blocks = t->n_cu * rec_per_cu;
     }
+    if (d.rec_dict && d.n_records > 0) {
+        // Runs of records for the waves of the record kernel: a run holds records of one body
+        // (the wave fetches that body once), and the runs are as short as the number of waves
+        // that are resident at once allows, so that the grid still fills the chip once.
+        const int64_t max_waves = 4LL * d.rec_blocks;
+        std::vector<int32_t> run_begin;      // first record of every body's range
+        for (int32_t i = 0; i < d.n_records; ++i)
+            if (i == 0 || h.rec_body[i] != h.rec_body[i - 1]) run_begin.push_back(i);
+        run_begin.push_back(d.n_records);
+        int32_t per = 1;
+        if (const char *env = std::getenv("NIMBLE_TUNE_RECORDS_PER_WAVE"))
+            if (std::atoi(env) >= 1 && std::atoi(env) <= 64) per = std::atoi(env);
+        for (;; ++per) {
+            int64_t n = 0;
+            for (size_t b = 0; b + 1 < run_begin.size(); ++b)
+                n += (run_begin[b + 1] - run_begin[b] + per - 1) / per;
+            if (n <= max_waves || d.rec_per_wave > 0) break;
+        }
+        std::vector<int32_t> chunks;
+        for (size_t b = 0; b + 1 < run_begin.size(); ++b) {
+            // the records of a body are dealt as evenly as its number of runs allows
+            const int32_t n_rec = run_begin[b + 1] - run_begin[b];
+            const int32_t n_runs = (n_rec + per - 1) / per;
+            int32_t at = run_begin[b];
+            for (int32_t r = 0; r < n_runs; ++r) {
+                const int32_t cnt = n_rec / n_runs + (r < n_rec % n_runs ? 1 : 0);
+                chunks.push_back(at);
+                chunks.push_back(cnt);
+                chunks.push_back(h.rec_body[at]);
+                chunks.push_back(0);
+                at += cnt;
+            }
+        }
+        d.n_rec_chunks = static_cast<int32_t>(chunks.size() / 4);
+        const int4 *pc = nullptr;
+        NIMBLE_TRY(upload(t, reinterpret_cast<const int4 *>(chunks.data()), chunks.size() / 4, &pc),
+                   "record runs");
+        d.rec_chunks = pc;
+        NIMBLE_TRY(upload(t, h.rec_dict_words.data(), h.rec_dict_words.size(), &d.rec_dict_words),
+                   "record bodies");
+    }
 
     {
         // the address of the static scratch on this device (nimble_plan_solve_static)
@@ -480,7 +523,11 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
 
     // stored bytes one iteration streams, phase by phase
     if (d.n_records > 0)
-        t->bytes_argmin = static_cast<int64_t>(h.rec_bytes) * d.n_records + 2LL * h.K;
+        // (a dictionary of bodies is counted once: it stays in the L2)
+        t->bytes_argmin = static_cast<int64_t>(h.rec_bytes) * d.n_records + 2LL * h.K +
+                          (d.rec_dict ? 4LL * static_cast<int64_t>(h.rec_dict_words.size()) +
+                                            16LL * d.n_rec_chunks
+                                      : 0LL);
     else
         t->bytes_argmin = 4LL * (h.K + 1) + 4LL * (h.P + 1) + 4LL * h.nnz + 14LL * h.K;
     t->bytes_reduce = 36LL * static_cast<int64_t>(h.oct_base.size()) + 4LL * d.n_passes +

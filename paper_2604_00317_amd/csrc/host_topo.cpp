@@ -7,6 +7,7 @@
 #include <cstring>
 #include <functional>
 #include <queue>
+#include <string>
 #include <unordered_map>
 
 namespace nimble {
@@ -89,12 +90,318 @@ void read_layout_options(HostTopo &t)
     number("NIMBLE_TUNE_RECORD_COMM_CAP", 1, kRecMaxComm, t.rec_comm_cap);
     number("NIMBLE_TUNE_RECORD_LANE_MAJOR", 0, 1, t.rec_lane_major);
     number("NIMBLE_TUNE_RECORD_TABLE16", 0, 1, t.rec_table16);
+    number("NIMBLE_TUNE_RECORD_DICT", 0, 1, t.rec_dict);
     number("NIMBLE_TUNE_BLOCK_PASSES", 1, 1024, t.blk_passes);
     number("NIMBLE_TUNE_TILES", 0, 1, t.tiles);
     number("NIMBLE_TUNE_TILE_MIN_ITEMS", 1, kTileIds, t.tile_min_items);
     int32_t dense_only = 0;
     number("NIMBLE_TUNE_TILES_DENSE_ONLY", 0, 1, dense_only);
     t.tiles_dense_only = dense_only != 0;
+}
+
+// ---- forward records ----------------------------------------------------------------------
+// Repacks the forward CSR into the records the path-cost kernel streams (see host_topo.hpp).
+// Needs t.pmax, t.lmax, t.nnz and t.sigma; t.rec_comm_cap, t.rec_lane_major, t.rec_table16 and
+// t.rec_dict are read as options and come back as what was built.
+static void build_forward_records_once(int32_t n_links, int32_t n_comm,
+                                       const int32_t *comm_path_ptr, int32_t n_paths,
+                                       const int32_t *path_link_ptr, const int32_t *path_links,
+                                       bool want_dict, HostTopo &t)
+{
+    t.n_records = 0;
+    t.rec_max_links = 0;
+    t.records.clear();
+    t.rec_stride = t.lmax;
+    t.n_bodies = 0;
+    t.rec_dict_words.clear();
+    t.rec_body.clear();
+    bool dict = false;
+    std::unordered_map<std::string, int32_t> body_ids;
+    const bool shape_ok = t.lmax <= kRecMaxStride &&
+                          static_cast<double>(t.lmax) * n_paths <= 1.5 * static_cast<double>(t.nnz);
+    if (shape_ok) {
+        const int32_t S = t.rec_stride;
+        std::vector<int32_t> stamp(n_links, -1), local(n_links, 0);
+        std::vector<int32_t> links;
+        std::vector<uint16_t> cp16, cq16, loc16;
+        auto align4 = [](int32_t x) { return (x + 3) & ~3; };
+        auto bytes_needed = [&](int32_t nl, int32_t nk, int32_t npad) {
+            (void)nl;    // the link table has a fixed size
+            if (t.rec_lane_major) return kRecBytes;      // a slot per commodity: always fits
+            return kRecTable + kRecHeader + 4 * nk + 2 * align4(2 * (nk + 1)) + npad * S;
+        };
+        // lanes per commodity in the record kernel: a lane scans two quads of the largest
+        // commodity; a record holds as many commodities as one round of the wave covers
+        // (64 / lanes), unless the caller set the capacity
+        {
+            const int32_t quads = (t.pmax + 3) / 4;
+            int32_t lanes = 1;
+            while (2 * lanes < quads && lanes < 64) lanes <<= 1;
+            t.rec_lanes = lanes;
+            if (t.rec_comm_cap <= 0) t.rec_comm_cap = 64 / lanes;
+            if (t.rec_comm_cap > kRecMaxComm) t.rec_comm_cap = kRecMaxComm;
+            // the lane-major body needs two quads per lane to cover every commodity, paths
+            // that fit five words per quad, a second lane per slot for the record's own words,
+            // and 4 KiB records
+            t.rec_lane_major = (t.rec_lane_major != 0 && S <= kRecLaneSteps && lanes >= 2 &&
+                                lanes <= 16 && quads <= 2 * lanes && kRecBytes == 4096) ? 1 : 0;
+            if (t.rec_lane_major && t.rec_comm_cap > 64 / lanes) t.rec_comm_cap = 64 / lanes;
+        }
+        const bool lane_major = t.rec_lane_major != 0;
+        t.rec_table16 = (lane_major && t.rec_table16 != 0 && n_links <= 65535) ? 1 : 0;
+        const bool table16 = t.rec_table16 != 0;
+        // the dictionary format needs the lane-major body and the 16-bit table
+        dict = want_dict && lane_major && table16;
+        t.rec_bytes = dict ? kRecBytesDict : (table16 ? kRecBytes16 : kRecBytes);
+        const int32_t table_bytes = table16 ? kRecTable16 : kRecTable;
+        bool ok = true;
+        int32_t k = 0;
+        while (k < n_comm && ok) {
+            const int32_t rec_id = t.n_records;
+            const int32_t k0 = k, p0 = comm_path_ptr[k];
+            links.clear();
+            cp16.assign(1, 0);
+            cq16.assign(1, 0);
+            loc16.clear();
+            int32_t np = 0, npad = 0;
+            while (k < n_comm && k - k0 < t.rec_comm_cap) {
+                const int32_t pa = comm_path_ptr[k], pb = comm_path_ptr[k + 1];
+                // distinct links this commodity would add
+                int32_t add = 0;
+                for (int32_t i = path_link_ptr[pa]; i < path_link_ptr[pb]; ++i) {
+                    const int32_t e = path_links[i];
+                    if (stamp[e] != rec_id && stamp[e] != -2 - rec_id) {
+                        stamp[e] = -2 - rec_id;
+                        ++add;
+                    }
+                }
+                const int32_t nl_new = static_cast<int32_t>(links.size()) + add;
+                const bool fits = nl_new <= kRecMaxLinks &&
+                                  bytes_needed(nl_new, k - k0 + 1, npad + align4(pb - pa)) <=
+                                      kRecBytes;
+                if (!fits) {
+                    for (int32_t i = path_link_ptr[pa]; i < path_link_ptr[pb]; ++i)
+                        if (stamp[path_links[i]] == -2 - rec_id) stamp[path_links[i]] = -1;
+                    break;
+                }
+                for (int32_t p = pa; p < pb; ++p) {
+                    const int32_t la = path_link_ptr[p], lb = path_link_ptr[p + 1];
+                    for (int32_t i = la; i < lb; ++i) {
+                        const int32_t e = path_links[i];
+                        if (stamp[e] != rec_id) {
+                            stamp[e] = rec_id;
+                            local[e] = static_cast<int32_t>(links.size());
+                            links.push_back(e);
+                        }
+                        loc16.push_back(static_cast<uint16_t>(local[e]));
+                    }
+                    for (int32_t i = lb - la; i < S; ++i) loc16.push_back(0xFFFFu);  // patched below
+                }
+                // candidates are padded to whole quads; a padding candidate starts at the
+                // +inf price slot, so it never wins the argmin
+                for (int32_t q = pb - pa; q < align4(pb - pa); ++q)
+                    for (int32_t i = 0; i < S; ++i) loc16.push_back(i == 0 ? 0xFFFEu : 0xFFFFu);
+                np += pb - pa;
+                npad += align4(pb - pa);
+                cp16.push_back(static_cast<uint16_t>(np));
+                cq16.push_back(static_cast<uint16_t>(npad));
+                ++k;
+            }
+            if (k == k0) {      // one commodity alone does not fit a record
+                ok = false;
+                break;
+            }
+            const int32_t nk = k - k0, nl = static_cast<int32_t>(links.size());
+            // the link table in ascending id order: neighbouring lanes then gather neighbouring
+            // prices (fewer cache lines per gather)
+            {
+                std::vector<int32_t> order(nl), rank(nl);
+                for (int32_t i = 0; i < nl; ++i) order[i] = i;
+                std::sort(order.begin(), order.end(),
+                          [&](int32_t x, int32_t y) { return links[x] < links[y]; });
+                std::vector<int32_t> sorted(nl);
+                for (int32_t i = 0; i < nl; ++i) {
+                    sorted[i] = links[order[i]];
+                    rank[order[i]] = i;
+                }
+                links.swap(sorted);
+                for (auto &v : loc16)
+                    if (v < 0xFFFEu) v = static_cast<uint16_t>(rank[v]);
+            }
+            for (auto &v : loc16) {
+                // the +0.0 and the +inf price slot
+                if (v == 0xFFFFu) v = static_cast<uint16_t>(lane_major ? kRecZeroSlot : nl);
+                else if (v == 0xFFFEu) v = static_cast<uint16_t>(lane_major ? kRecInfSlot : nl + 1);
+            }
+            t.records.resize(static_cast<size_t>(t.n_records + 1) * t.rec_bytes, 0);
+            uint8_t *r = t.records.data() + static_cast<size_t>(t.n_records) * t.rec_bytes;
+            const int32_t off_sig = kRecHeader;      // body offsets count from kRecTable
+            const int32_t off_cp = off_sig + 4 * nk;
+            const int32_t off_cq = off_cp + align4(2 * (nk + 1));
+            const int32_t off_loc = off_cq + align4(2 * (nk + 1));
+            const uint16_t h16[8] = {static_cast<uint16_t>(nk), static_cast<uint16_t>(np),
+                                     static_cast<uint16_t>(nl), static_cast<uint16_t>(off_cp),
+                                     static_cast<uint16_t>(off_loc),
+                                     static_cast<uint16_t>(off_sig),
+                                     static_cast<uint16_t>(off_cq),
+                                     static_cast<uint16_t>(npad)};
+            // gather c of lane l reads table entry 4*l + c, which is link 64*c + l; in the
+            // dictionary format a lane's four 16-bit entries open its 16 bytes of the record
+            {
+                int32_t *tab = reinterpret_cast<int32_t *>(r);
+                uint16_t *tab16 = reinterpret_cast<uint16_t *>(r);
+                for (int32_t l = 0; l < 64; ++l)
+                    for (int32_t c = 0; c < 4; ++c) {
+                        const int32_t i = 64 * c + l;
+                        const int32_t e = nl == 0 ? 0 : links[i < nl ? i : nl - 1];
+                        if (dict) tab16[8 * l + c] = static_cast<uint16_t>(e);
+                        else if (table16) tab16[4 * l + c] = static_cast<uint16_t>(e);
+                        else tab[4 * l + c] = e;
+                    }
+            }
+            uint8_t *body = r + table_bytes;
+            if (lane_major) {
+                const int32_t L = t.rec_lanes;
+                std::vector<uint32_t> words(64 * kRecLaneWords, 0u);
+                for (int32_t lane = 0; lane < 64; ++lane) {
+                    const int32_t g = lane / L, j = lane % L;
+                    uint32_t *w = &words[static_cast<size_t>(lane) * kRecLaneWords];
+                    const int32_t np_g = g < nk ? cp16[g + 1] - cp16[g] : 0;
+                    for (int32_t q = 0; q < 2; ++q)
+                        for (int32_t i = 0; i < kRecLaneSteps; ++i) {
+                            uint32_t word = 0u;
+                            for (int32_t c4 = 0; c4 < 4; ++c4) {
+                                const int32_t cand = 4 * (j + L * q) + c4;
+                                uint32_t byte = i == 0 ? kRecInfSlot : kRecZeroSlot;
+                                if (cand < np_g && i < S)
+                                    byte = loc16[static_cast<size_t>(cq16[g] + cand) * S + i];
+                                word |= byte << (8 * c4);
+                            }
+                            w[q * kRecLaneSteps + i] = word;
+                        }
+                    if (g < nk) {
+                        w[10] = static_cast<uint32_t>(np_g) | (static_cast<uint32_t>(cp16[g]) << 8);
+                        if (j == 0) w[11] = static_cast<uint32_t>(t.sigma[k0 + g]);
+                    }
+                }
+                words[1 * kRecLaneWords + 11] =
+                    static_cast<uint32_t>(k0) | (static_cast<uint32_t>(nk) << 24);
+                words[static_cast<size_t>(L + 1) * kRecLaneWords + 11] = static_cast<uint32_t>(p0);
+                if (dict) {
+                    // words 0..10 of every lane say how the candidates index the link table and
+                    // nothing about which commodities or links these are: records of the same
+                    // shape share them.  The record keeps its table, word 11 and the number of
+                    // its body.
+                    std::string key(64 * 11 * 4, '\0');
+                    for (int32_t lane = 0; lane < 64; ++lane)
+                        std::memcpy(&key[static_cast<size_t>(lane) * 44],
+                                    &words[static_cast<size_t>(lane) * kRecLaneWords], 44);
+                    auto found = body_ids.find(key);
+                    int32_t id;
+                    if (found == body_ids.end()) {
+                        id = t.n_bodies++;
+                        body_ids.emplace(std::move(key), id);
+                        const size_t at = t.rec_dict_words.size();
+                        t.rec_dict_words.resize(at + 3 * 64 * 4, 0u);
+                        for (int32_t lane = 0; lane < 64; ++lane)
+                            for (int32_t it = 0; it < 3; ++it)
+                                for (int32_t q = 0; q < 4; ++q)
+                                    if (4 * it + q < 11)
+                                        t.rec_dict_words[at + (static_cast<size_t>(it) * 64 + lane) * 4 + q] =
+                                            words[static_cast<size_t>(lane) * kRecLaneWords + 4 * it + q];
+                    } else {
+                        id = found->second;
+                    }
+                    uint32_t *r32 = reinterpret_cast<uint32_t *>(r);
+                    for (int32_t lane = 0; lane < 64; ++lane) {
+                        r32[4 * lane + 2] = words[static_cast<size_t>(lane) * kRecLaneWords + 11];
+                        r32[4 * lane + 3] = static_cast<uint32_t>(id);
+                    }
+                    t.rec_body.push_back(id);
+                    t.n_records += 1;
+                    if (nl > t.rec_max_links) t.rec_max_links = nl;
+                    continue;
+                }
+                for (int32_t lane = 0; lane < 64; ++lane)
+                    for (int32_t it = 0; it < 3; ++it)
+                        std::memcpy(body + 1024 * it + 16 * lane,
+                                    &words[static_cast<size_t>(lane) * kRecLaneWords + 4 * it], 16);
+                t.n_records += 1;
+                if (nl > t.rec_max_links) t.rec_max_links = nl;
+                continue;
+            }
+            std::memcpy(body + 0, &k0, 4);
+            std::memcpy(body + 4, &p0, 4);
+            std::memcpy(body + 8, h16, 16);
+            std::memcpy(body + off_sig, t.sigma.data() + k0, 4 * static_cast<size_t>(nk));
+            std::memcpy(body + off_cp, cp16.data(), 2 * cp16.size());
+            std::memcpy(body + off_cq, cq16.data(), 2 * cq16.size());
+            // step-major over the padded candidates: index i of every candidate, then index
+            // i+1, ...; four consecutive candidates (a quad) are one aligned 32-bit word
+            {
+                std::vector<uint8_t> soa(loc16.size());
+                for (int32_t p = 0; p < npad; ++p)
+                    for (int32_t i = 0; i < S; ++i)
+                        soa[static_cast<size_t>(i) * npad + p] =
+                            static_cast<uint8_t>(loc16[static_cast<size_t>(p) * S + i]);
+                std::memcpy(body + off_loc, soa.data(), soa.size());
+            }
+            t.n_records += 1;
+            if (nl > t.rec_max_links) t.rec_max_links = nl;
+        }
+        if (!ok) {
+            t.n_records = 0;
+            t.records.clear();
+        }
+        if (ok && dict) {
+            // records of one body next to each other (stable: ascending commodities inside a
+            // body), so that a wave that walks a run of records fetches its body once
+            std::vector<int32_t> order(t.n_records);
+            for (int32_t i = 0; i < t.n_records; ++i) order[i] = i;
+            std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
+                return t.rec_body[x] < t.rec_body[y];
+            });
+            std::vector<uint8_t> sorted(t.records.size());
+            std::vector<int32_t> body_sorted(t.n_records);
+            for (int32_t i = 0; i < t.n_records; ++i) {
+                std::memcpy(&sorted[static_cast<size_t>(i) * kRecBytesDict],
+                            &t.records[static_cast<size_t>(order[i]) * kRecBytesDict], kRecBytesDict);
+                body_sorted[i] = t.rec_body[order[i]];
+            }
+            t.records.swap(sorted);
+            t.rec_body.swap(body_sorted);
+        }
+    }
+    t.rec_dict = (t.n_records > 0 && dict) ? 1 : 0;
+    if (t.n_records == 0) {
+        t.rec_lane_major = 0;
+        t.rec_table16 = 0;
+    }
+    if (t.rec_bytes == 0) t.rec_bytes = kRecBytes;
+}
+
+void build_forward_records(int32_t n_links, int32_t n_comm, const int32_t *comm_path_ptr,
+                           int32_t n_paths, const int32_t *path_link_ptr,
+                           const int32_t *path_links, HostTopo &t)
+{
+    // Lane-major records with 16-bit tables are first built with a dictionary of bodies (a
+    // record then is 1 KiB: table, the record's own words and the number of its body).  The
+    // dictionary stays when it pays -- bodies shared by four records each on average, as on
+    // large fabrics built by a product rule -- or when the option asks for it; otherwise the
+    // records are built again with their bodies inline (on the 16-node fabric, three records
+    // per body, the dictionary changed nothing: the kernel is a latency chain there).
+    const int32_t opt_cap = t.rec_comm_cap, opt_lm = t.rec_lane_major, opt_t16 = t.rec_table16;
+    const int32_t opt_dict = t.rec_dict;
+    if (opt_dict != 0) {
+        build_forward_records_once(n_links, n_comm, comm_path_ptr, n_paths, path_link_ptr,
+                                   path_links, true, t);
+        if (t.rec_dict == 1 && (opt_dict == 1 || 4LL * t.n_bodies <= t.n_records)) return;
+        t.rec_comm_cap = opt_cap;
+        t.rec_lane_major = opt_lm;
+        t.rec_table16 = opt_t16;
+    }
+    build_forward_records_once(n_links, n_comm, comm_path_ptr, n_paths, path_link_ptr,
+                               path_links, false, t);
 }
 
 void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
@@ -723,214 +1030,7 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
         }
     }
 
-    // ---- forward records ------------------------------------------------------------------
-    t.n_records = 0;
-    t.rec_max_links = 0;
-    t.records.clear();
-    t.rec_stride = t.lmax;
-    const bool shape_ok = t.lmax <= kRecMaxStride &&
-                          static_cast<double>(t.lmax) * n_paths <= 1.5 * static_cast<double>(t.nnz);
-    if (shape_ok) {
-        const int32_t S = t.rec_stride;
-        std::vector<int32_t> stamp(n_links, -1), local(n_links, 0);
-        std::vector<int32_t> links;
-        std::vector<uint16_t> cp16, cq16, loc16;
-        auto align4 = [](int32_t x) { return (x + 3) & ~3; };
-        auto bytes_needed = [&](int32_t nl, int32_t nk, int32_t npad) {
-            (void)nl;    // the link table has a fixed size
-            if (t.rec_lane_major) return kRecBytes;      // a slot per commodity: always fits
-            return kRecTable + kRecHeader + 4 * nk + 2 * align4(2 * (nk + 1)) + npad * S;
-        };
-        // lanes per commodity in the record kernel: a lane scans two quads of the largest
-        // commodity; a record holds as many commodities as one round of the wave covers
-        // (64 / lanes), unless the caller set the capacity
-        {
-            const int32_t quads = (t.pmax + 3) / 4;
-            int32_t lanes = 1;
-            while (2 * lanes < quads && lanes < 64) lanes <<= 1;
-            t.rec_lanes = lanes;
-            if (t.rec_comm_cap <= 0) t.rec_comm_cap = 64 / lanes;
-            if (t.rec_comm_cap > kRecMaxComm) t.rec_comm_cap = kRecMaxComm;
-            // the lane-major body needs two quads per lane to cover every commodity, paths
-            // that fit five words per quad, a second lane per slot for the record's own words,
-            // and 4 KiB records
-            t.rec_lane_major = (t.rec_lane_major != 0 && S <= kRecLaneSteps && lanes >= 2 &&
-                                lanes <= 16 && quads <= 2 * lanes && kRecBytes == 4096) ? 1 : 0;
-            if (t.rec_lane_major && t.rec_comm_cap > 64 / lanes) t.rec_comm_cap = 64 / lanes;
-        }
-        const bool lane_major = t.rec_lane_major != 0;
-        t.rec_table16 = (lane_major && t.rec_table16 != 0 && n_links <= 65535) ? 1 : 0;
-        const bool table16 = t.rec_table16 != 0;
-        t.rec_bytes = table16 ? kRecBytes16 : kRecBytes;
-        const int32_t table_bytes = table16 ? kRecTable16 : kRecTable;
-        bool ok = true;
-        int32_t k = 0;
-        while (k < n_comm && ok) {
-            const int32_t rec_id = t.n_records;
-            const int32_t k0 = k, p0 = comm_path_ptr[k];
-            links.clear();
-            cp16.assign(1, 0);
-            cq16.assign(1, 0);
-            loc16.clear();
-            int32_t np = 0, npad = 0;
-            while (k < n_comm && k - k0 < t.rec_comm_cap) {
-                const int32_t pa = comm_path_ptr[k], pb = comm_path_ptr[k + 1];
-                // distinct links this commodity would add
-                int32_t add = 0;
-                for (int32_t i = path_link_ptr[pa]; i < path_link_ptr[pb]; ++i) {
-                    const int32_t e = path_links[i];
-                    if (stamp[e] != rec_id && stamp[e] != -2 - rec_id) {
-                        stamp[e] = -2 - rec_id;
-                        ++add;
-                    }
-                }
-                const int32_t nl_new = static_cast<int32_t>(links.size()) + add;
-                const bool fits = nl_new <= kRecMaxLinks &&
-                                  bytes_needed(nl_new, k - k0 + 1, npad + align4(pb - pa)) <=
-                                      kRecBytes;
-                if (!fits) {
-                    for (int32_t i = path_link_ptr[pa]; i < path_link_ptr[pb]; ++i)
-                        if (stamp[path_links[i]] == -2 - rec_id) stamp[path_links[i]] = -1;
-                    break;
-                }
-                for (int32_t p = pa; p < pb; ++p) {
-                    const int32_t la = path_link_ptr[p], lb = path_link_ptr[p + 1];
-                    for (int32_t i = la; i < lb; ++i) {
-                        const int32_t e = path_links[i];
-                        if (stamp[e] != rec_id) {
-                            stamp[e] = rec_id;
-                            local[e] = static_cast<int32_t>(links.size());
-                            links.push_back(e);
-                        }
-                        loc16.push_back(static_cast<uint16_t>(local[e]));
-                    }
-                    for (int32_t i = lb - la; i < S; ++i) loc16.push_back(0xFFFFu);  // patched below
-                }
-                // candidates are padded to whole quads; a padding candidate starts at the
-                // +inf price slot, so it never wins the argmin
-                for (int32_t q = pb - pa; q < align4(pb - pa); ++q)
-                    for (int32_t i = 0; i < S; ++i) loc16.push_back(i == 0 ? 0xFFFEu : 0xFFFFu);
-                np += pb - pa;
-                npad += align4(pb - pa);
-                cp16.push_back(static_cast<uint16_t>(np));
-                cq16.push_back(static_cast<uint16_t>(npad));
-                ++k;
-            }
-            if (k == k0) {      // one commodity alone does not fit a record
-                ok = false;
-                break;
-            }
-            const int32_t nk = k - k0, nl = static_cast<int32_t>(links.size());
-            // the link table in ascending id order: neighbouring lanes then gather neighbouring
-            // prices (fewer cache lines per gather)
-            {
-                std::vector<int32_t> order(nl), rank(nl);
-                for (int32_t i = 0; i < nl; ++i) order[i] = i;
-                std::sort(order.begin(), order.end(),
-                          [&](int32_t x, int32_t y) { return links[x] < links[y]; });
-                std::vector<int32_t> sorted(nl);
-                for (int32_t i = 0; i < nl; ++i) {
-                    sorted[i] = links[order[i]];
-                    rank[order[i]] = i;
-                }
-                links.swap(sorted);
-                for (auto &v : loc16)
-                    if (v < 0xFFFEu) v = static_cast<uint16_t>(rank[v]);
-            }
-            for (auto &v : loc16) {
-                // the +0.0 and the +inf price slot
-                if (v == 0xFFFFu) v = static_cast<uint16_t>(lane_major ? kRecZeroSlot : nl);
-                else if (v == 0xFFFEu) v = static_cast<uint16_t>(lane_major ? kRecInfSlot : nl + 1);
-            }
-            t.records.resize(static_cast<size_t>(t.n_records + 1) * t.rec_bytes, 0);
-            uint8_t *r = t.records.data() + static_cast<size_t>(t.n_records) * t.rec_bytes;
-            const int32_t off_sig = kRecHeader;      // body offsets count from kRecTable
-            const int32_t off_cp = off_sig + 4 * nk;
-            const int32_t off_cq = off_cp + align4(2 * (nk + 1));
-            const int32_t off_loc = off_cq + align4(2 * (nk + 1));
-            const uint16_t h16[8] = {static_cast<uint16_t>(nk), static_cast<uint16_t>(np),
-                                     static_cast<uint16_t>(nl), static_cast<uint16_t>(off_cp),
-                                     static_cast<uint16_t>(off_loc),
-                                     static_cast<uint16_t>(off_sig),
-                                     static_cast<uint16_t>(off_cq),
-                                     static_cast<uint16_t>(npad)};
-            // gather c of lane l reads table entry 4*l + c, which is link 64*c + l
-            {
-                int32_t *tab = reinterpret_cast<int32_t *>(r);
-                uint16_t *tab16 = reinterpret_cast<uint16_t *>(r);
-                for (int32_t l = 0; l < 64; ++l)
-                    for (int32_t c = 0; c < 4; ++c) {
-                        const int32_t i = 64 * c + l;
-                        const int32_t e = nl == 0 ? 0 : links[i < nl ? i : nl - 1];
-                        if (table16) tab16[4 * l + c] = static_cast<uint16_t>(e);
-                        else tab[4 * l + c] = e;
-                    }
-            }
-            uint8_t *body = r + table_bytes;
-            if (lane_major) {
-                const int32_t L = t.rec_lanes;
-                std::vector<uint32_t> words(64 * kRecLaneWords, 0u);
-                for (int32_t lane = 0; lane < 64; ++lane) {
-                    const int32_t g = lane / L, j = lane % L;
-                    uint32_t *w = &words[static_cast<size_t>(lane) * kRecLaneWords];
-                    const int32_t np_g = g < nk ? cp16[g + 1] - cp16[g] : 0;
-                    for (int32_t q = 0; q < 2; ++q)
-                        for (int32_t i = 0; i < kRecLaneSteps; ++i) {
-                            uint32_t word = 0u;
-                            for (int32_t c4 = 0; c4 < 4; ++c4) {
-                                const int32_t cand = 4 * (j + L * q) + c4;
-                                uint32_t byte = i == 0 ? kRecInfSlot : kRecZeroSlot;
-                                if (cand < np_g && i < S)
-                                    byte = loc16[static_cast<size_t>(cq16[g] + cand) * S + i];
-                                word |= byte << (8 * c4);
-                            }
-                            w[q * kRecLaneSteps + i] = word;
-                        }
-                    if (g < nk) {
-                        w[10] = static_cast<uint32_t>(np_g) | (static_cast<uint32_t>(cp16[g]) << 8);
-                        if (j == 0) w[11] = static_cast<uint32_t>(t.sigma[k0 + g]);
-                    }
-                }
-                words[1 * kRecLaneWords + 11] =
-                    static_cast<uint32_t>(k0) | (static_cast<uint32_t>(nk) << 24);
-                words[static_cast<size_t>(L + 1) * kRecLaneWords + 11] = static_cast<uint32_t>(p0);
-                for (int32_t lane = 0; lane < 64; ++lane)
-                    for (int32_t it = 0; it < 3; ++it)
-                        std::memcpy(body + 1024 * it + 16 * lane,
-                                    &words[static_cast<size_t>(lane) * kRecLaneWords + 4 * it], 16);
-                t.n_records += 1;
-                if (nl > t.rec_max_links) t.rec_max_links = nl;
-                continue;
-            }
-            std::memcpy(body + 0, &k0, 4);
-            std::memcpy(body + 4, &p0, 4);
-            std::memcpy(body + 8, h16, 16);
-            std::memcpy(body + off_sig, t.sigma.data() + k0, 4 * static_cast<size_t>(nk));
-            std::memcpy(body + off_cp, cp16.data(), 2 * cp16.size());
-            std::memcpy(body + off_cq, cq16.data(), 2 * cq16.size());
-            // step-major over the padded candidates: index i of every candidate, then index
-            // i+1, ...; four consecutive candidates (a quad) are one aligned 32-bit word
-            {
-                std::vector<uint8_t> soa(loc16.size());
-                for (int32_t p = 0; p < npad; ++p)
-                    for (int32_t i = 0; i < S; ++i)
-                        soa[static_cast<size_t>(i) * npad + p] =
-                            static_cast<uint8_t>(loc16[static_cast<size_t>(p) * S + i]);
-                std::memcpy(body + off_loc, soa.data(), soa.size());
-            }
-            t.n_records += 1;
-            if (nl > t.rec_max_links) t.rec_max_links = nl;
-        }
-        if (!ok) {
-            t.n_records = 0;
-            t.records.clear();
-        }
-    }
-    if (t.n_records == 0) {
-        t.rec_lane_major = 0;
-        t.rec_table16 = 0;
-    }
-    if (t.rec_bytes == 0) t.rec_bytes = kRecBytes;
+    build_forward_records(n_links, n_comm, comm_path_ptr, n_paths, path_link_ptr, path_links, t);
 }
 
 }  // namespace nimble
@@ -997,14 +1097,45 @@ extern "C" nimble_status_t nimble_host_records_roundtrip(int32_t n_links, int32_
     // index n_links is skipped
     int64_t w = 0;
     int32_t next_comm = 0;
-    for (int32_t ri = 0; ri < t.n_records; ++ri) {
+    // records in a dictionary layout are stored by body: visit them by first commodity
+    std::vector<int32_t> visit(t.n_records);
+    for (int32_t i = 0; i < t.n_records; ++i) visit[i] = i;
+    if (t.rec_dict) {
+        if (static_cast<int32_t>(t.rec_body.size()) != t.n_records) return NIMBLE_ERR_INVALID;
+        auto k0_of = [&](int32_t ri) {
+            uint32_t v;      // word 11 of lane 1
+            std::memcpy(&v, t.records.data() + static_cast<size_t>(ri) * t.rec_bytes + 16 + 8, 4);
+            return static_cast<int32_t>(v & 0xFFFFFFu);
+        };
+        std::sort(visit.begin(), visit.end(),
+                  [&](int32_t x, int32_t y) { return k0_of(x) < k0_of(y); });
+        for (int32_t i = 1; i < t.n_records; ++i)
+            if (t.rec_body[i - 1] > t.rec_body[i]) return NIMBLE_ERR_INVALID;
+    }
+    for (int32_t vi = 0; vi < t.n_records; ++vi) {
+        const int32_t ri = visit[vi];
         const uint8_t *rec = t.records.data() + static_cast<size_t>(ri) * t.rec_bytes;
         if (t.rec_lane_major) {
             const int32_t table_bytes = t.rec_table16 ? nimble::kRecTable16 : nimble::kRecTable;
-            // lane-major body: word idx of lane l is in load idx / 4 of that lane
+            // lane-major body: word idx of lane l is in load idx / 4 of that lane; with a
+            // dictionary words 0..10 come from the record's body there, word 11 and the body
+            // number from the lane's 16 bytes of the record
             const int32_t L = t.rec_lanes;
             auto word = [&](int32_t lane, int32_t idx) {
                 uint32_t v;
+                if (t.rec_dict) {
+                    if (idx == 11) {
+                        std::memcpy(&v, rec + 16 * lane + 8, 4);
+                        return v;
+                    }
+                    uint32_t body;
+                    std::memcpy(&body, rec + 16 * lane + 12, 4);
+                    if (static_cast<int32_t>(body) != t.rec_body[ri] ||
+                        static_cast<int32_t>(body) >= t.n_bodies)
+                        return 0xFFFFFFFFu;      // fails every check below
+                    return t.rec_dict_words[(static_cast<size_t>(body) * 3 + idx / 4) * 256 +
+                                            4 * lane + idx % 4];
+                }
                 std::memcpy(&v, rec + table_bytes + 1024 * (idx / 4) + 16 * lane + 4 * (idx % 4),
                             4);
                 return v;
@@ -1012,6 +1143,7 @@ extern "C" nimble_status_t nimble_host_records_roundtrip(int32_t n_links, int32_
             const int32_t *tab = reinterpret_cast<const int32_t *>(rec);
             const uint16_t *tab16 = reinterpret_cast<const uint16_t *>(rec);
             auto link_at = [&](int32_t i) {
+                if (t.rec_dict) return static_cast<int32_t>(tab16[8 * (i % 64) + i / 64]);
                 const int32_t at = 4 * (i % 64) + i / 64;
                 return t.rec_table16 ? static_cast<int32_t>(tab16[at]) : tab[at];
             };
@@ -1051,7 +1183,7 @@ extern "C" nimble_status_t nimble_host_records_roundtrip(int32_t n_links, int32_
                             return NIMBLE_ERR_INVALID;
                         links_out[w++] = link_at(li);
                     }
-                    if (cand < np) path_record[p0 + p_lo + cand] = ri;
+                    if (cand < np) path_record[p0 + p_lo + cand] = vi;
                 }
             }
             continue;
@@ -1125,6 +1257,8 @@ extern "C" nimble_status_t nimble_host_layout_stats(int32_t n_links, int32_t n_c
     out[13] = t.n_strip_items;
     out[14] = t.n_strip_rows;
     out[15] = t.rec_lane_major;
+    out[16] = t.rec_dict;
+    out[17] = t.n_bodies;
     return NIMBLE_OK;
 }
 

@@ -133,6 +133,16 @@ constexpr int32_t kBlkMaxLinks = 512;
 // +0.0 and +inf), so a record has at most kRecMaxLinks table entries in use.
 // While link ids fit 16 bits a lane-major record stores its table as 256 uint16 (512 bytes, the
 // same gather order: 8-byte load l holds the links l, 64+l, 128+l, 192+l) and is 3.5 KiB long.
+// Dictionary format (lane-major bodies, 16-bit tables): words 0..10 of a lane describe how the
+// candidates of the record index its link table, not which commodities or links they are, so
+// on fabrics built by a product rule (rail x egress x ingress) thousands of records share a few
+// dozen bodies.  The bodies then live once in a dictionary (kRecBodyBytes each: load `it` of
+// lane l at 1024*it + 16*l as above, word 11 zero) that stays in the L2, and a record shrinks
+// to kRecBytesDict: 16 bytes per lane -- its four 16-bit table entries, its word 11, and the
+// number of the record's body (the same in all lanes).  Records are stored sorted by body, so
+// a wave that walks a run of records of one body fetches the body once.
+constexpr int32_t kRecBytesDict = 1024;
+constexpr int32_t kRecBodyBytes = 3 * 1024;
 constexpr int32_t kRecTable16 = 512;
 constexpr int32_t kRecBytes16 = kRecTable16 + 3 * 1024;
 constexpr int32_t kRecLaneWords = 12;
@@ -214,7 +224,14 @@ struct HostTopo {
     int32_t rec_lane_major = 1;          // option in, layout out: the body of a record is laid
                                          // out lane by lane (see kRecLaneWords)
     int32_t rec_table16 = 1;             // option in, layout out: 16-bit link tables
-    int32_t rec_bytes = 0;               // bytes of a record: kRecBytes, or kRecBytes16
+    int32_t rec_dict = -1;               // option in (-1: when it pays, 0: never, 1: whenever
+                                         // the format allows), layout out (0 / 1): bodies in a
+                                         // dictionary, records of kRecBytesDict
+    int32_t n_bodies = 0;                // distinct bodies
+    std::vector<uint32_t> rec_dict_words; // [n_bodies * kRecBodyBytes / 4]
+    std::vector<int32_t> rec_body;       // [n_records] body of every record (ascending)
+    int32_t rec_bytes = 0;               // bytes of a record: kRecBytes, kRecBytes16 or
+                                         // kRecBytesDict
     int32_t n_records = 0;
     int32_t rec_max_links = 0;           // largest link table of any record
     std::vector<uint8_t> records;        // [n_records * kRecBytes]
@@ -236,5 +253,11 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
                      const int32_t *comm_path_ptr, int32_t n_paths,
                      const int32_t *path_link_ptr, const int32_t *path_links,
                      HostTopo &out);
+
+// The forward records alone (build_host_topo calls it last): needs out.pmax, out.lmax, out.nnz
+// and out.sigma.
+void build_forward_records(int32_t n_links, int32_t n_comm, const int32_t *comm_path_ptr,
+                           int32_t n_paths, const int32_t *path_link_ptr,
+                           const int32_t *path_links, HostTopo &out);
 
 }  // namespace nimble

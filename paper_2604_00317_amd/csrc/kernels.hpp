@@ -26,6 +26,13 @@ struct DeviceTopo {
     int32_t rec_around_l2;     // records read around the L2: 1, 0, or -1 (by their total size)
     int32_t rec_per_wave;      // records a wave walks in the record kernel (0: default)
     const uint8_t *records;
+    // dictionary layout of the records (rec_dict = 1): 1 KiB records sorted by body, the bodies
+    // once each in rec_dict_words, and the runs of records the waves of the record kernel walk
+    int32_t rec_dict;          // 1: records name their body in a dictionary
+    int32_t n_bodies;
+    const uint32_t *rec_dict_words;   // [n_bodies * 768]
+    int32_t n_rec_chunks;      // waves of the record kernel
+    const int4 *rec_chunks;    // [n_rec_chunks] first record, records, body, 0: one body per run
     // reverse CSR of 8-byte (commodity, window | mask) pairs, rows padded to 2 pairs
     int64_t rev_pairs;         // padded number of pairs
     int32_t rev_row_max;       // longest reverse row in pairs (without padding)

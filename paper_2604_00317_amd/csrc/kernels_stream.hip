@@ -432,6 +432,110 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records,
     }
 }
 
+// The same for records whose bodies live in a dictionary: a wave walks a run of records that
+// share one body.  It fetches the body once (three cached 16-byte loads per lane: the few
+// bodies of a fabric stay in the L2) and per record only its 16 bytes per lane: four 16-bit
+// link table entries, the lane's own word (sigma, or the record's first commodity / first
+// candidate) and the body number.  In flight while a record is scanned: the 16 bytes of the
+// record after the next and the prices of the next one.
+template <int L, int S, bool MAXC>
+__global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recd(int n_chunks, int around_l2,
+                                                       const int4 *__restrict__ chunks,
+                                                       const uint8_t *__restrict__ records,
+                                                       const u32x4 *__restrict__ bodies,
+                                                       const double *__restrict__ price,
+                                                       uint8_t *__restrict__ choice,
+                                                       uint32_t *__restrict__ count,
+                                                       uint8_t *__restrict__ choice2)
+{
+    static_assert(L >= 2 && L <= 16 && S <= kRecLaneSteps,
+                  "lane-major records: 2 to 16 lanes per commodity, five steps");
+    __shared__ double s_all[kRecWaves * kRecPriceSlots];
+    double *s_price = s_all + (threadIdx.x >> 6) * kRecPriceSlots;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int g = lane / L;
+    const int j = lane % L;
+    const int chunk = __builtin_amdgcn_readfirstlane(blockIdx.x * kRecWaves + (threadIdx.x >> 6));
+    if (chunk >= n_chunks) return;
+    const int4 ck = chunks[chunk];
+    int rec = __builtin_amdgcn_readfirstlane(ck.x);
+    const int end = rec + __builtin_amdgcn_readfirstlane(ck.y);
+    const int body_id = __builtin_amdgcn_readfirstlane(ck.z);
+    constexpr int kAroundL2 = 1 | 16;            // cache policy bits of the buffer loads: sc0, sc1
+    auto head_of = [&](int r) {
+        const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+            const_cast<uint8_t *>(records + size_t(r) * kRecBytesDict), 0, kRecBytesDict,
+            0x00020000);
+        return around_l2 ? __builtin_amdgcn_raw_buffer_load_b128(rs, lane * 16, 0, kAroundL2)
+                         : __builtin_amdgcn_raw_buffer_load_b128(rs, lane * 16, 0, 0);
+    };
+    u32x4 head = head_of(rec);
+    // the body of the run: this lane's words 0..10
+    const u32x4 *bsrc = bodies + size_t(body_id) * (kRecBodyBytes / 16) + lane;
+    const u32x4 b0 = bsrc[0], b1 = bsrc[kWave], b2 = bsrc[2 * kWave];
+    const uint32_t w[10] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w, b2.x, b2.y};
+    const uint32_t meta = b2.z;
+    const int np = static_cast<int>(meta & 0xFFu);
+    const int p_lo = static_cast<int>(meta >> 8);
+    const int ja = 4 * j, jb = 4 * j + 4 * L;
+    double pr[4];
+    pr[0] = price[head.x & 0xFFFFu];
+    pr[1] = price[head.x >> 16];
+    pr[2] = price[head.y & 0xFFFFu];
+    pr[3] = price[head.y >> 16];
+    int32_t own_next = static_cast<int32_t>(head.z);
+    if (rec + 1 < end) head = head_of(rec + 1);
+    for (; rec < end; ++rec) {                          // wave-uniform
+        wave_lds_sync();                                // the previous record is done with LDS
+#pragma unroll
+        for (int q = 0; q < 4; ++q) s_price[lane + q * kWave] = pr[q];
+        if (lane == 0) {                             // after the table prices, in LDS order
+            s_price[kRecZeroSlot] = 0.0;             // pads short paths
+            s_price[kRecInfSlot] = __builtin_inf();  // first step of absent candidates
+        }
+        const int32_t own = own_next;
+        if (rec + 1 < end) {
+            pr[0] = price[head.x & 0xFFFFu];
+            pr[1] = price[head.x >> 16];
+            pr[2] = price[head.y & 0xFFFFu];
+            pr[3] = price[head.y >> 16];
+            own_next = static_cast<int32_t>(head.z);
+            if (rec + 2 < end) head = head_of(rec + 2);
+        }
+        wave_lds_sync();
+        double ma, mb;
+        int ia, ib;
+        scan_quad<S, MAXC>(s_price, w, ma, ia);
+        scan_quad<S, MAXC>(s_price, w + kRecLaneSteps, mb, ib);
+        // the strict `<` scan in candidate order: quad A first; absent candidates cost +inf
+        double best = __builtin_inf();
+        int bj = ja < np ? ja : 0x7FFFFFFF;
+        if (ja < np && ma < best) {
+            best = ma;
+            bj = ja + ia;
+        }
+        if (jb < np && mb < best) {
+            best = mb;
+            bj = jb + ib;
+        }
+        bj = group_argmin_two_pass<L>(best, bj);
+        // the record's own words: k0 | nk << 24 in lane 1, p0 in lane L + 1; a slot beyond the
+        // record's commodities (the body may hold more than this record does) writes nothing
+        const int k0nk = __builtin_amdgcn_readlane(own, 1);
+        const int k0 = k0nk & 0xFFFFFF;
+        const bool live = np > 0 && g < static_cast<int>(static_cast<uint32_t>(k0nk) >> 24);
+        if (live && j == 0) {
+            choice[k0 + g] = static_cast<uint8_t>(bj);
+            if (own >= 0) choice2[own] = static_cast<uint8_t>(bj);   // copy in sigma order
+        }
+        // counts are kept only when the choices are not logged per iteration
+        if (count != nullptr) {
+            const int p0 = __builtin_amdgcn_readlane(own, L + 1);
+            if (live && j == 0) count[p0 + p_lo + bj] += 1u;
+        }
+    }
+}
+
 // Split fractions from the per-iteration choice log: one lane per commodity walks its column
 // of the log and counts in LDS (a padded row per lane, so lanes hit different banks).
 __global__ __launch_bounds__(kWave) void k_histogram(int K, int iters, int pmax, size_t stride,
@@ -708,10 +812,29 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, uint8_t *choice, uint32_t
         if constexpr (L >= 2 && L <= 16) {      // (a slot's lanes 1 and L + 1 hold record words)
             if (t.rec_lane_major) {
                 // records beyond half of the 32 MB of L2 are read around it
-                const int64_t rec_bytes = static_cast<int64_t>(t.n_records) *
-                                          (t.rec_table16 ? kRecBytes16 : kRecBytes);
+                const int64_t rec_bytes =
+                    static_cast<int64_t>(t.n_records) *
+                    (t.rec_dict ? kRecBytesDict : (t.rec_table16 ? kRecBytes16 : kRecBytes));
                 int around_l2 = rec_bytes > (16LL << 20) ? 1 : 0;
                 if (t.rec_around_l2 >= 0) around_l2 = t.rec_around_l2;
+                if (t.rec_dict) {
+                    const int dgrid = (t.n_rec_chunks + kRecWaves - 1) / kRecWaves;
+#define NIMBLE_RECD_LAUNCH(SS)                                                                 \
+    case SS:                                                                                   \
+        hipLaunchKernelGGL((k_argmin_recd<L, SS, MAXC>), dim3(dgrid), dim3(kWave * kRecWaves), \
+                           0, s, t.n_rec_chunks, around_l2, t.rec_chunks, t.records,           \
+                           reinterpret_cast<const u32x4 *>(t.rec_dict_words), t.price, choice, \
+                           count, t.choice2);                                                  \
+        return;
+                    switch (t.rec_stride) {
+                        NIMBLE_RECD_LAUNCH(1)
+                        NIMBLE_RECD_LAUNCH(2)
+                        NIMBLE_RECD_LAUNCH(3)
+                        NIMBLE_RECD_LAUNCH(4)
+                        NIMBLE_RECD_LAUNCH(5)
+                    }
+#undef NIMBLE_RECD_LAUNCH
+                }
 #define NIMBLE_RECL_LAUNCH(SS)                                                                 \
     case SS:                                                                                   \
         if (t.rec_table16)                                                                     \

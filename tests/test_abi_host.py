@@ -119,7 +119,9 @@ def test_reverse_csr_random_ragged():
 RECORD_FORMATS = {
     # lane-major bodies with 16-bit link tables (the default where the fabric allows it), with
     # 32-bit tables, and record-major bodies
-    "lane-major, 16-bit table": {},
+    "lane-major, 16-bit table": {"NIMBLE_TUNE_RECORD_DICT": "0"},
+    "lane-major, 16-bit table, bodies in a dictionary": {"NIMBLE_TUNE_RECORD_DICT": "1"},
+    "default": {},
     "lane-major, 32-bit table": {"NIMBLE_TUNE_RECORD_TABLE16": "0"},
     "record-major": {"NIMBLE_TUNE_RECORD_LANE_MAJOR": "0"},
 }
@@ -135,7 +137,15 @@ def test_forward_records_round_trip(cfg, fmt, monkeypatch):
     links, path_rec, n_rec = B.nimble_host_records_roundtrip(*args)
     # the single node has at most 7 candidates per pair: one lane per commodity, record-major
     lane_major = cfg != 0 and fmt != "record-major"
-    assert B.nimble_host_layout_stats(*args)["records_lane_major"] == int(lane_major)
+    st = B.nimble_host_layout_stats(*args)
+    assert st["records_lane_major"] == int(lane_major)
+    if "dictionary" in fmt and lane_major:
+        assert st["records_dict"] == 1 and 1 <= st["record_bodies"] <= n_rec
+    if fmt == "default":
+        # three records per body on the 16-node fabric: not enough for the dictionary to pay
+        assert st["records_dict"] == 0
+    if "dictionary" not in fmt and fmt != "default":
+        assert st["records_dict"] == 0
     assert n_rec >= 1
     assert np.array_equal(links, t.path_links)
     # records are runs of whole commodities, in order
@@ -272,3 +282,16 @@ def test_register_kernel_only_when_a_thread_per_commodity_and_link_exists():
     t = w.topo
     assert B.nimble_host_resident_kernel(t.n_links, t.n_comm, t.comm_path_ptr, t.n_paths,
                                          t.path_link_ptr, t.path_links) == 0
+
+
+def test_dictionary_of_record_bodies_on_a_large_product_fabric():
+    """A 24-node fabric with 8 rails (the construction of the 64-node benchmark fabric): its
+    records share a few dozen bodies, so the default layout keeps them in a dictionary, and
+    every incidence still reads back through table, own words and body."""
+    t = W.build_fabric(24, 8, 8, [[r, r ^ 1] for r in range(8)])
+    args = (t.n_links, t.n_comm, t.comm_path_ptr, t.n_paths, t.path_link_ptr, t.path_links)
+    st = B.nimble_host_layout_stats(*args)
+    assert st["records_dict"] == 1 and 4 * st["record_bodies"] <= st["records"]
+    links, path_rec, n_rec = B.nimble_host_records_roundtrip(*args)
+    assert n_rec == st["records"] and np.array_equal(links, t.path_links)
+    assert np.all(np.diff(path_rec) >= 0) and path_rec[-1] == n_rec - 1

@@ -250,13 +250,28 @@ def test_edge_cases(oracle_mod, B, regime):
                                  {"NIMBLE_TUNE_NO_CHOICE_LOG": "1"},
                                  {"NIMBLE_TUNE_RECORD_AROUND_L2": "1"},
                                  {"NIMBLE_TUNE_RECORD_AROUND_L2": "1",
-                                  "NIMBLE_TUNE_RECORD_TABLE16": "0"}],
+                                  "NIMBLE_TUNE_RECORD_TABLE16": "0"},
+                                 {"NIMBLE_TUNE_RECORD_DICT": "0"},
+                                 {"NIMBLE_TUNE_RECORD_DICT": "0",
+                                  "NIMBLE_TUNE_RECORD_AROUND_L2": "1"},
+                                 {"NIMBLE_TUNE_RECORD_DICT": "1"},
+                                 {"NIMBLE_TUNE_RECORD_DICT": "1",
+                                  "NIMBLE_TUNE_RECORD_AROUND_L2": "1"},
+                                 {"NIMBLE_TUNE_RECORD_DICT": "1",
+                                  "NIMBLE_TUNE_NO_CHOICE_LOG": "1"},
+                                 {"NIMBLE_TUNE_RECORD_DICT": "1",
+                                  "NIMBLE_TUNE_RECORDS_PER_WAVE": "3"}],
                          ids=["lane-major-32", "record-major", "record-major-counters",
                               "lane-major-16-counters", "lane-major-16-around-l2",
-                              "lane-major-32-around-l2"])
+                              "lane-major-32-around-l2", "lane-major-16-inline",
+                              "lane-major-16-inline-around-l2", "dictionary",
+                              "dictionary-around-l2", "dictionary-counters",
+                              "dictionary-runs-of-3"])
 def test_every_forward_record_format(oracle_mod, B, monkeypatch, env, flags):
-    """The default on these fabrics is lane-major record bodies with 16-bit link tables; the
-    32-bit table (fabrics of more than 65535 links) and the record-major body (more than five
+    """The default on these fabrics is lane-major record bodies with 16-bit link tables, kept
+    once each in a dictionary where records share them (the 16-node fabric) and inline otherwise;
+    both are forced here on every fabric, the ragged one included, where no two records share a
+    body.  The 32-bit table (fabrics of more than 65535 links) and the record-major body (more than five
     links per path, or fewer than nine candidates per commodity) must give the same plans, with
     the choice log and with per-path counters.  Records that exceed the L2 are fetched with
     loads that bypass it; the switch forces those loads on fabrics of any size."""
