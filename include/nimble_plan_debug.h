@@ -43,6 +43,26 @@ nimble_status_t nimble_debug_stream_read(const void *d_buf, int64_t bytes, int32
                                          void *d_sink, void *hip_stream);
 
 /*
+ * Benchmark helper: enqueue one cooperative kernel of (compute units x blocks_per_cu, rounded
+ * down to a multiple of 8) workgroups of `threads` threads that makes 2 x rounds grid-wide
+ * barriers and checks after every other one that a word another workgroup wrote before the
+ * barrier has arrived.  kind: 0 one arrival counter, relaxed agent-scope atomics, data
+ * exchanged with agent-scope stores and loads; 1 the same counter between agent-scope fences,
+ * data exchanged with ordinary stores and loads; 2 one counter per XCD (by the hardware's XCC id)
+ * and a global one, all workgroups poll one generation word; 3 as 2, but only the last arriver
+ * of an XCD polls the global word and releases the others through a word of their own XCD; 4 no
+ * read-modify-write: every workgroup stores its round into its own word of a flag array and
+ * its first wave reads the whole array until all words have arrived (at most 2048 workgroups).
+ * Every wait gives up after spin_limit polls.  d_work: device memory of work_bytes >= 16384 +
+ * 128 per workgroup.  d_out: device int32 [32] out: [0] words that had not arrived, [1] 1 if a
+ * wait expired, [2..17] workgroups that ran on XCC id 0..15, [18] rounds completed.  Timed with
+ * HIP events by the caller: duration / (2 x rounds) is the cost of one barrier.
+ */
+nimble_status_t nimble_debug_barrier_probe(int32_t kind, int32_t blocks_per_cu, int32_t threads,
+                                           int32_t rounds, uint32_t spin_limit, void *d_work,
+                                           int64_t work_bytes, int32_t *d_out, void *hip_stream);
+
+/*
  * Test helper for the persistent regime: every grid-wide barrier of that kernel waits at most
  * `polls` polls of its arrival counter (default 2^22, about a second).  When a wait expires the
  * solve is abandoned -- every workgroup leaves the kernel at its next poll, d_splits is left

@@ -33,7 +33,7 @@ EXPORTS = [
     "nimble_host_records_roundtrip", "nimble_host_layout_stats",
     "nimble_host_build_reverse_streaming", "nimble_topo_resident_in_registers",
     "nimble_debug_stream_read", "nimble_topo_reserve", "nimble_host_resident_kernel",
-    "nimble_plan_solve_static", "nimble_static_scratch_bytes",
+    "nimble_plan_solve_static", "nimble_static_scratch_bytes", "nimble_debug_barrier_probe",
 ]
 
 _lib = None
@@ -94,6 +94,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.nimble_topo_set_regime.argtypes = [vp, i32]
     lib.nimble_debug_run_phase.restype = ctypes.c_int
     lib.nimble_debug_run_phase.argtypes = [vp, i32, i32, vp, vp]
+    lib.nimble_debug_barrier_probe.restype = ctypes.c_int
+    lib.nimble_debug_barrier_probe.argtypes = [i32, i32, i32, i32, u32, vp, i64, vp, vp]
     lib.nimble_debug_stream_read.restype = ctypes.c_int
     lib.nimble_debug_stream_read.argtypes = [vp, i64, i32, vp, vp]
     lib.nimble_debug_set_spin_limit.restype = ctypes.c_int
@@ -318,6 +320,16 @@ def nimble_debug_stream_read(d_buf, nbytes: int, reps: int, d_sink, stream=None)
     _check(load_library().nimble_debug_stream_read(
         ctypes.c_void_p(d_buf.data_ptr()), int(nbytes), int(reps),
         ctypes.c_void_p(d_sink.data_ptr()), _stream_ptr(stream)))
+
+
+def nimble_debug_barrier_probe(kind: int, blocks_per_cu: int, threads: int, rounds: int,
+                               spin_limit: int, d_work, d_out, stream=None) -> None:
+    """Enqueue the grid-barrier probe (see include/nimble_plan_debug.h); d_work is a uint8 device
+    tensor, d_out an int32 device tensor of 32 elements."""
+    _check(load_library().nimble_debug_barrier_probe(
+        int(kind), int(blocks_per_cu), int(threads), int(rounds), int(spin_limit),
+        ctypes.c_void_p(d_work.data_ptr()), int(d_work.numel() * d_work.element_size()),
+        _dev_ptr(d_out, "int32", 32, "d_out"), _stream_ptr(stream)))
 
 
 def nimble_debug_set_spin_limit(topo: Topo, polls: int) -> None:

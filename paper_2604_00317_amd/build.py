@@ -8,7 +8,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB = os.path.join(_HERE, "libnimble_plan.so")
 SOURCES = ["api.hip", "kernels_stream.hip", "kernels_resident.hip",
-           "kernels_persistent.hip", "kernels_alg1.hip", "kernels_post.hip", "kernels_adaptive.hip",
+           "kernels_persistent.hip", "kernels_alg1.hip", "kernels_post.hip", "kernels_adaptive.hip", "kernels_probe.hip",
            "host_topo.cpp"]
 # -ffp-contract=off: one IEEE operation per statement on host and device (no FMA contraction).
 # packed-fp32-ops is switched off for every device compile of this build.

@@ -451,12 +451,19 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
         NIMBLE_TRY(hipDeviceGetAttribute(&t->n_cu, hipDeviceAttributeMultiprocessorCount,
                                          t->device),
                    "hipDeviceGetAttribute");
-        int per_cu = 6;
+        // the reduce kernel takes 114 VGPRs: four of its four-wave workgroups per compute unit
+        // are resident at once, and a grid of exactly those measured best (22.2 ms per plan on
+        // the 64-node fabric against 22.4 to 23.0 with three, five, six or eight)
+        int per_cu = 4;
         if (const char *env = std::getenv("NIMBLE_TUNE_REDUCE_BLOCKS_PER_CU"))
             if (std::atoi(env) > 0) per_cu = std::atoi(env);
         d.reduce_blocks = t->n_cu * per_cu;
-        // the record kernel: 78 VGPRs, so six of its four-wave workgroups per compute unit
+        // the record kernel with inline bodies: 78 VGPRs, so six of its four-wave workgroups
+        // per compute unit; the dictionary kernel says itself how many fit (its grid must be
+        // resident at once: a workgroup that starts late finishes late)
         int rec_per_cu = 6;
+        d.cost_max = (flags & NIMBLE_COST_MAX) != 0u;
+        if (const int occ = nimble::record_kernel_blocks_per_cu(d)) rec_per_cu = occ;
         if (const char *env = std::getenv("NIMBLE_TUNE_RECORD_BLOCKS_PER_CU"))
             if (std::atoi(env) > 0) rec_per_cu = std::atoi(env);
         d.rec_blocks = t->n_cu * rec_per_cu;
@@ -919,6 +926,32 @@ nimble_status_t nimble_debug_run_phase(nimble_topo_t *topo, int32_t phase, int32
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return fail_hip(e, "kernel launch (phase timing)");
+    return NIMBLE_OK;
+}
+
+nimble_status_t nimble_debug_barrier_probe(int32_t kind, int32_t blocks_per_cu, int32_t threads,
+                                           int32_t rounds, uint32_t spin_limit, void *d_work,
+                                           int64_t work_bytes, int32_t *d_out, void *hip_stream)
+{
+    g_last_error.clear();
+    if (!d_work || !d_out) return fail(NIMBLE_ERR_INVALID, "NULL argument");
+    if (kind < 0 || kind > 4 || blocks_per_cu < 1 || blocks_per_cu > 8 || rounds < 1 ||
+        threads < 64 || threads > 1024 || threads % 64)
+        return fail(NIMBLE_ERR_INVALID, "kind 0..4, 1..8 blocks per CU, 64..1024 threads");
+    int dev = -1, n_cu = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e == hipSuccess)
+        e = hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return fail_hip(e, "device query");
+    // 8 XCDs on this part; the grid is a multiple of their number
+    const int n_xcd = 8;
+    const int blocks = n_cu * blocks_per_cu / n_xcd * n_xcd;
+    if (blocks < n_xcd) return fail(NIMBLE_ERR_RANGE, "fewer compute units than XCDs");
+    if (static_cast<int64_t>(nimble::barrier_probe_bytes(blocks)) > work_bytes)
+        return fail(NIMBLE_ERR_INVALID, "d_work is too small for this grid");
+    e = nimble::launch_barrier_probe(kind, blocks, threads, rounds, spin_limit, n_xcd, d_work,
+                                     d_out, static_cast<hipStream_t>(hip_stream));
+    if (e != hipSuccess) return fail_hip(e, "cooperative launch (barrier probe)");
     return NIMBLE_OK;
 }
 

@@ -96,6 +96,8 @@ struct DeviceTopo {
 };
 
 void launch_stream_read(const void *buf, size_t bytes, void *sink, hipStream_t s);
+// workgroups of the dictionary record kernel a compute unit holds at once (0: not that kernel)
+int record_kernel_blocks_per_cu(const DeviceTopo &t);
 int lanes_per_commodity(int pmax);   // power of two >= pmax, at most 64
 
 // ---- streaming regime: one launch per phase ------------------------------------------------
@@ -136,6 +138,13 @@ size_t persistent_sync_bytes();
 hipError_t launch_persistent(const DeviceTopo &t, void *sync_words, int n_cu,
                              unsigned int spin_limit, const double *demand, double eps,
                              int32_t iters, double *splits, double *lambda, hipStream_t s);
+
+// ---- probe of grid-wide barriers (benchmark only) -------------------------------------------
+// `work` is device memory of barrier_probe_bytes(blocks) bytes; `out` is device int32 [32].
+size_t barrier_probe_bytes(int max_blocks);
+hipError_t launch_barrier_probe(int kind, int blocks, int threads, int rounds,
+                                unsigned int spin_limit, int n_xcd, void *work, int *out,
+                                hipStream_t s);
 
 // ---- adaptive-step variant of the streaming regime --------------------------------------------
 // Device state of one adaptive solve (owned by the topology, sized for max_iters).

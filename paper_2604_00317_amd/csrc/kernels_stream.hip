@@ -979,6 +979,62 @@ void launch_reduce_mode(const DeviceTopo &t, const uint8_t *choice, const double
 
 }  // namespace
 
+namespace {
+
+template <int L, bool MAXC>
+int recd_blocks_per_cu(int stride)
+{
+    int n = 0;
+    hipError_t e = hipErrorInvalidValue;
+#define NIMBLE_RECD_OCC(SS)                                                                    \
+    case SS:                                                                                   \
+        e = hipOccupancyMaxActiveBlocksPerMultiprocessor(                                      \
+            &n, reinterpret_cast<const void *>(&k_argmin_recd<L, SS, MAXC>), kWave * kRecWaves, \
+            0);                                                                                \
+        break;
+    switch (stride) {
+        NIMBLE_RECD_OCC(1)
+        NIMBLE_RECD_OCC(2)
+        NIMBLE_RECD_OCC(3)
+        NIMBLE_RECD_OCC(4)
+        NIMBLE_RECD_OCC(5)
+    }
+#undef NIMBLE_RECD_OCC
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return 0;
+    }
+    return n;
+}
+
+}  // namespace
+
+// Workgroups of the record kernel a compute unit holds at once (from the registers and LDS the
+// kernel that would run takes); 0 when unknown.
+int record_kernel_blocks_per_cu(const DeviceTopo &t)
+{
+    if (!(t.n_records > 0 && t.rec_lane_major && t.rec_dict)) return 0;
+    const int quads = (t.pmax + 3) / 4;
+    int L = 1;
+    while (2 * L < quads && L < kWave) L <<= 1;
+    if (t.rec_lanes > 0) L = t.rec_lanes;
+    switch (L) {
+    case 2:
+        return t.cost_max ? recd_blocks_per_cu<2, true>(t.rec_stride)
+                          : recd_blocks_per_cu<2, false>(t.rec_stride);
+    case 4:
+        return t.cost_max ? recd_blocks_per_cu<4, true>(t.rec_stride)
+                          : recd_blocks_per_cu<4, false>(t.rec_stride);
+    case 8:
+        return t.cost_max ? recd_blocks_per_cu<8, true>(t.rec_stride)
+                          : recd_blocks_per_cu<8, false>(t.rec_stride);
+    case 16:
+        return t.cost_max ? recd_blocks_per_cu<16, true>(t.rec_stride)
+                          : recd_blocks_per_cu<16, false>(t.rec_stride);
+    default: return 0;
+    }
+}
+
 void launch_stream_read(const void *buf, size_t bytes, void *sink, hipStream_t s)
 {
     hipLaunchKernelGGL(k_stream_read, dim3(256 * 8), dim3(kBlock), 0, s,

@@ -471,6 +471,36 @@ def test_solve_on_side_stream_and_reuse(oracle_mod, B):
         h.close()
 
 
+@pytest.mark.parametrize("kind", [0, 1, 2, 3, 4])
+def test_grid_barrier_probe(B, kind):
+    """The barrier probe behind the benchmark's barrier figures: every design either lets the
+    word written before a barrier arrive after it, on every round, or gives up within its
+    bounded wait and says so (design 3 releases through a word read at workgroup scope, which
+    this part serves from a cache that never sees the release).  A spin limit of zero makes any
+    design give up at its first incomplete wait; the kernel still ends normally."""
+    import torch
+    work = torch.zeros(1 << 19, dtype=torch.uint8, device="cuda:0")
+    out = torch.zeros(32, dtype=torch.int32, device="cuda:0")
+    print(f"[barrier probe] kind={kind}", flush=True)
+    B.nimble_debug_barrier_probe(kind, 1, 256, 25, 1 << 16, work, out)
+    torch.cuda.synchronize()
+    o = out.cpu().numpy()
+    assert o[2:18].sum() > 0 and np.all(o[2:10] == o[2])      # 8 XCDs, evenly filled
+    assert np.all(o[10:18] == 0)
+    if kind == 3:
+        assert o[1] == 1 or (o[0] == 0 and o[18] == 25)
+    else:
+        assert o[0] == 0 and o[1] == 0 and o[18] == 25
+    B.nimble_debug_barrier_probe(kind, 2, 128, 25, 0, work, out)
+    torch.cuda.synchronize()
+    o = out.cpu().numpy()
+    assert o[0] == 0 and (o[1] == 1 or o[18] == 25)
+    with pytest.raises(B.NimbleError):
+        B.nimble_debug_barrier_probe(7, 1, 256, 5, 10, work, out)
+    with pytest.raises(B.NimbleError):
+        B.nimble_debug_barrier_probe(0, 1, 256, 5, 10, work[:64], out)
+
+
 def test_persistent_regime_abandons_cleanly_when_a_barrier_wait_expires(B):
     """With a poll limit of 0 the first incomplete barrier gives up: every workgroup leaves the
     kernel, lambda comes back as NaN, and the topology is usable again afterwards."""
