@@ -6,8 +6,10 @@ benchmark configuration -- 64 modeled nodes x 8 GPUs, 261 632 commodities, 8.3 M
 paths, 39.3 M path-link incidences, 1000 iterations -- with topology and traffic resident in
 HBM before the timed region.  Prints one JSON line: MWU iterations/s (value), plans/s, the
 roofline of the dominant kernel from HIP-event timing, the CPU oracle timed on the host cores
-on a bounded sample of the same workload, and (key "also") the throughput of the 16-node and
-the batched configuration.
+on a bounded sample of the same workload, and (key "also") the throughput of the other
+configurations the metric names: the single node, the two-node fabric, the 16-node fabric (one
+plan, with its own roofline block, and a batch of 16 plans that share every launch) and the
+batch of 4096 single-node plans.
 """
 from __future__ import annotations
 
@@ -24,6 +26,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# LDS: 256 compute units x 128 bytes per clock x 2.4 GHz
+LDS_PEAK_GBS = 256 * 128 * 2.4
 REGIME_NAMES = {1: "resident", 2: "stream", 3: "persistent"}
 PHASES = ["argmin", "load_reduce", "update"]
 
@@ -69,28 +73,49 @@ def time_stream_read(B, torch, nbytes, reps):
     return nbytes / sec / 1e9
 
 
-def read_traffic(kernel, workload):
+def read_traffic(kernel, workload, phase_bytes_now):
     """HBM bytes per launch of `kernel` measured with rocprofv3 counters, from the committed
-    summary profiles/hbm_traffic.txt (lines: workload kernel fetch_bytes write_bytes)."""
+    summary profiles/hbm_traffic.txt (lines: workload kernel fetch_bytes write_bytes).  The file
+    names the stored bytes per phase of the build it was measured on ("# phase_bytes workload
+    argmin load_reduce update"); when the running build lays the topology out differently the
+    figure is stale and None is returned with a note."""
     path = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
     if not os.path.exists(path):
-        return None
+        return None, "profiles/hbm_traffic.txt is missing"
+    value, measured_on = None, None
     for line in open(path):
         parts = line.split()
-        if len(parts) >= 4 and not line.startswith("#") and parts[0] == workload and \
+        if line.startswith("# phase_bytes") and len(parts) >= 6 and parts[2] == workload:
+            measured_on = [int(x) for x in parts[3:6]]
+        elif len(parts) >= 4 and not line.startswith("#") and parts[0] == workload and \
                 parts[1] == kernel:
-            return float(parts[2]) + float(parts[3])
-    return None
+            value = float(parts[2]) + float(parts[3])
+    now = [int(phase_bytes_now[name]) for name in PHASES]
+    if measured_on is None:
+        return None, "profiles/hbm_traffic.txt does not say which layout it was measured on"
+    if measured_on != now:
+        return None, (f"profiles/hbm_traffic.txt was measured on a layout of {measured_on} stored "
+                      f"bytes per phase, this build has {now}")
+    return value, None
 
 
 def run_config(B, W, torch, cfg, regime, steps, warmup, iters_override=0, batch_size=4096,
-               copy_calib=0):
+               copy_calib=0, plans=0):
+    """plans > 0: a batch of that many plans of a single-plan configuration (the configuration's
+    own traffic first, then the same recipe with other seeds)."""
     dev = "cuda:0"
     t_gen = time.perf_counter()
     w = W.make_config(cfg, batch=batch_size if cfg == 2 else None)
     topo = w.topo
     if iters_override > 0:
         w.iters = iters_override
+    if plans > 0:
+        rows = [w.traffic]
+        for b in range(1, plans):
+            rng = np.random.default_rng(3_000_000 + 1000 * cfg + b)
+            rows.append(rng.permutation(w.traffic))      # the same bytes between other pairs
+        w.traffic = np.stack(rows)
+        w.batch = plans
     t_gen = time.perf_counter() - t_gen
     t_create = time.perf_counter()
     h = B.nimble_topo_create(*topo.csr())
@@ -98,6 +123,8 @@ def run_config(B, W, torch, cfg, regime, steps, warmup, iters_override=0, batch_
     B.nimble_topo_set_regime(h, regime)
     B.nimble_topo_reserve(h, w.iters)       # the choice log, sized outside the timed solves
     batch = max(w.batch, 1)
+    if plans > 0:
+        B.nimble_topo_reserve_batch(h, plans, w.iters)   # the plans share every launch
     d_traffic = torch.as_tensor(np.ascontiguousarray(w.traffic).reshape(-1)).to(dev)
     d_splits = torch.empty(batch * topo.n_paths, dtype=torch.float64, device=dev)
     d_lambda = torch.empty(batch, dtype=torch.float64, device=dev)
@@ -197,13 +224,29 @@ def main() -> int:
             k["gbs"] = k["bytes"] / k["avg_us"] / 1e3
             k["back_to_back_gbs"] = k["bytes"] / k["back_to_back_us"] / 1e3
         dom = max(kernels, key=lambda n: kernels[n]["avg_us"])
+        traffic, traffic_note = read_traffic(dom, w.name, bytes_)
+        whole = bytes_["total"] * w.iters * args.steps / elapsed / 1e9
         roofline = dict(bound="hbm", kernel=dom, achieved=kernels[dom]["gbs"],
                         peak=HBM_PEAK_GBS, unit="GB/s",
                         frac=kernels[dom]["gbs"] / HBM_PEAK_GBS,
                         back_to_back_achieved=kernels[dom]["back_to_back_gbs"],
                         back_to_back_frac=kernels[dom]["back_to_back_gbs"] / HBM_PEAK_GBS,
-                        traffic=read_traffic(dom, w.name),
-                        whole_iteration_gbs=bytes_["total"] * w.iters * args.steps / elapsed / 1e9)
+                        traffic=traffic,
+                        whole_iteration_gbs=whole, whole_iteration_frac=whole / HBM_PEAK_GBS,
+                        bytes=kernels[dom]["bytes"],
+                        note=("stored bytes are re-read every iteration and fit the 256 MB "
+                              "Infinity Cache: the rate is cache-resident bandwidth, priced "
+                              "against the HBM peak"))
+        if traffic_note:
+            roofline["traffic_note"] = traffic_note
+        # what the path-cost kernel gathers from LDS (one 8-byte price per candidate step): the
+        # resource nearest its limit once the forward bytes are compressed
+        lds_bytes = h.phase_bytes(3)
+        if lds_bytes > 0 and "argmin" in kernels:
+            lds_gbs = lds_bytes / kernels["argmin"]["avg_us"] / 1e3
+            roofline["lds_gather"] = dict(kernel="argmin", bytes=lds_bytes, achieved=lds_gbs,
+                                          peak=LDS_PEAK_GBS, unit="GB/s",
+                                          frac=lds_gbs / LDS_PEAK_GBS)
         # the same iteration rate priced at the bytes an uncompressed layout (32-bit indices,
         # one reverse entry per incidence) would have to move: context for the compression
         plain = (8 * topo.nnz + 4 * topo.n_paths + 4 * topo.n_links + 24 * topo.n_comm +
@@ -227,7 +270,7 @@ def main() -> int:
         name = REGIME_NAMES.get(regime, "auto")
         roofline = dict(bound="hbm", kernel=name, achieved=total / sec / 1e9, peak=HBM_PEAK_GBS,
                         unit="GB/s", frac=total / sec / 1e9 / HBM_PEAK_GBS,
-                        traffic=read_traffic(name, w.name))
+                        traffic=None)
 
     # ---- CPU baseline: the oracle on a bounded sample -------------------------------------
     cpu = None
@@ -324,14 +367,38 @@ def main() -> int:
     # ---- the other throughput figures the metric names -------------------------------------
     also = {}
     if not args.no_also and args.config == 4 and args.iters == 0:
-        for cfg, steps in ((3, 5), (2, 5)):
-            q = run_config(B, W, torch, cfg, 0, steps, 1, 0, args.batch)
-            also[f"configs[{cfg}] {q['w'].name}"] = dict(
+        single_c3 = None
+        for cfg, steps, plans in ((0, 20, 0), (1, 20, 0), (3, 5, 0), (3, 3, 16), (2, 5, 0)):
+            q = run_config(B, W, torch, cfg, 0, steps, 1, 0, args.batch, plans=plans)
+            key = f"configs[{cfg}] {q['w'].name}" + (f" x{plans}" if plans else "")
+            entry = dict(
                 iterations_per_s=q["w"].iters * q["batch"] * steps / q["elapsed"],
                 plans_per_s=q["batch"] * steps / q["elapsed"],
                 ms_per_step=q["elapsed"] * 1e3 / steps,
+                us_per_iteration=q["elapsed"] * 1e6 / steps / q["w"].iters,
                 regime=REGIME_NAMES.get(q["regime"], "auto"), batch=q["batch"],
                 iters=q["w"].iters)
+            also[key] = entry
+            if cfg == 3 and not plans:
+                # the 16-node fabric, named by the bandwidth target as well: its 5 MB per
+                # iteration stay in the caches, two dependent launches per iteration
+                single_c3 = entry["plans_per_s"]
+                b3 = phase_bytes(q["h"])
+                gbs = b3["total"] * q["w"].iters * steps / q["elapsed"] / 1e9
+                entry["roofline"] = dict(bound="hbm", bytes_per_iter=b3["total"],
+                                         us_per_iter=entry["us_per_iteration"], achieved=gbs,
+                                         peak=HBM_PEAK_GBS, unit="GB/s", frac=gbs / HBM_PEAK_GBS,
+                                         note="cache-resident; bound by two grid-wide "
+                                              "dependencies per iteration, not by bandwidth")
+                ks = {}
+                for ph, name in enumerate(PHASES):
+                    if b3[name]:
+                        sec = time_phase(B, torch, q["h"], ph, 200, q["d_traffic"])
+                        ks["reduce_update" if ph == 1 and not b3["update"] else name] = dict(
+                            back_to_back_us=sec * 1e6, bytes=b3[name])
+                entry["kernels"] = ks
+            if cfg == 3 and plans and single_c3:
+                entry["speedup_over_one_plan_at_a_time"] = entry["plans_per_s"] / single_c3
             if cfg == 2:
                 # the paper's own sequential planner (Algorithm 1) on the same batch: one GPU
                 # thread per problem; lambda against the Jacobi MWU plan of the same problems
@@ -373,6 +440,28 @@ def main() -> int:
             q["h"].close()
             del q
 
+    # ---- what a grid-wide barrier costs next to the kernel boundaries the plan uses -----------
+    barrier = None
+    if not args.no_also:
+        work = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda:0")
+        res = torch.zeros(32, dtype=torch.int32, device="cuda:0")
+        barrier = {}
+        for kind, name in ((0, "flat_counter"), (1, "flat_counter_with_fences"),
+                           (2, "counter_per_xcd")):
+            for bpc in (1, 4):
+                B.nimble_debug_barrier_probe(kind, bpc, 256, 20, 1 << 16, work, res)
+                torch.cuda.synchronize()
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+                B.nimble_debug_barrier_probe(kind, bpc, 256, 250, 1 << 16, work, res)
+                e1.record()
+                torch.cuda.synchronize()
+                o = res.cpu().numpy()
+                barrier[f"{name}_{bpc}_per_cu_us"] = (
+                    e0.elapsed_time(e1) * 1e3 / 500 if o[0] == 0 and o[1] == 0 else None)
+        del work, res
+
     out = {
         "metric": "mwu_iterations_per_s", "value": iters_per_s, "unit": "iterations/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -390,6 +479,7 @@ def main() -> int:
         "also": also,
         "post_processing": post,
         "adaptive_step": adaptive,
+        "grid_barrier": barrier,
         "setup_s": setup,
     }
     print(json.dumps(out))

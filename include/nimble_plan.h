@@ -130,6 +130,18 @@ nimble_status_t nimble_plan_solve(nimble_topo_t *topo, const double *d_traffic, 
 nimble_status_t nimble_topo_reserve(nimble_topo_t *topo, int32_t iters);
 
 /*
+ * Makes room for `plans` plans of a batch to run side by side in the streaming regime: one
+ * state block per plan (demand copies, lengths, prices, congestion sums, choices, counts,
+ * partial sums) and a choice log of plans * iters rows.  nimble_plan_solve_batch then covers
+ * that many plans with every kernel launch (a batch larger than the reservation is solved in
+ * groups of that size; a topology starts with room for one plan).  Call it outside the solve
+ * loop: it may free and allocate device memory.  NIMBLE_ERR_RANGE beyond 4 GiB of state or
+ * 1 GiB of log, NIMBLE_ERR_ALLOC when the memory cannot be had.  Batches in the resident regime
+ * need none of this.
+ */
+nimble_status_t nimble_topo_reserve_batch(nimble_topo_t *topo, int32_t plans, int32_t iters);
+
+/*
  * nimble_plan_solve for callers that cannot allocate device memory and cannot let the library
  * do it either: code under HIP graph capture, tight serving loops, harnesses that forbid
  * hipMalloc.  Same arguments, same results, always the streaming regime; the per-iteration
@@ -151,7 +163,9 @@ int64_t nimble_static_scratch_bytes(void);
  * `batch` independent plans on the same topology (one per MoE layer x micro-batch), solved
  * concurrently.  d_traffic is device [batch][n_comm], d_splits device [batch][n_paths],
  * d_lambda device [batch]; the rest as nimble_plan_solve.  batch >= 1.  Topologies whose
- * per-plan state does not fit in LDS are solved one plan after another on the stream.
+ * per-plan state does not fit in LDS run the streaming regime: as many plans share every
+ * kernel launch as nimble_topo_reserve_batch has made room for (one after the other without
+ * it).
  */
 nimble_status_t nimble_plan_solve_batch(nimble_topo_t *topo, int32_t batch,
                                         const double *d_traffic, double eps, int32_t iters,
@@ -282,7 +296,10 @@ int64_t nimble_topo_bytes_per_iter(const nimble_topo_t *topo);
 
 /* The same figure for one phase of the streaming regime (0: path-cost gather + argmin over
  * the forward CSR, 1: link-load reduce over the reverse CSR, 2: length update).  On topologies
- * whose reduce and update run as one kernel, phase 1 covers both and phase 2 is 0. */
+ * whose reduce and update run as one kernel, phase 1 covers both and phase 2 is 0.  Phase 3 is
+ * not memory traffic: the bytes the path-cost kernel reads from LDS per launch (one 8-byte
+ * price per candidate step), 0 for the kernels that do not keep the prices of a record in LDS
+ * lane by lane. */
 int64_t nimble_topo_phase_bytes(const nimble_topo_t *topo, int32_t phase);
 
 /* Force a kernel regime (NIMBLE_REGIME_*) for later solves; NIMBLE_ERR_RANGE if the topology

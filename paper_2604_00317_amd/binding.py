@@ -34,6 +34,7 @@ EXPORTS = [
     "nimble_host_build_reverse_streaming", "nimble_topo_resident_in_registers",
     "nimble_debug_stream_read", "nimble_topo_reserve", "nimble_host_resident_kernel",
     "nimble_plan_solve_static", "nimble_static_scratch_bytes", "nimble_debug_barrier_probe",
+    "nimble_topo_reserve_batch",
 ]
 
 _lib = None
@@ -73,6 +74,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.nimble_plan_solve_static.argtypes = [vp, vp, dbl, i32, vp, vp, vp]
     lib.nimble_static_scratch_bytes.restype = i64
     lib.nimble_static_scratch_bytes.argtypes = []
+    lib.nimble_topo_reserve_batch.restype = ctypes.c_int
+    lib.nimble_topo_reserve_batch.argtypes = [vp, i32, i32]
     lib.nimble_topo_reserve.restype = ctypes.c_int
     lib.nimble_topo_reserve.argtypes = [vp, i32]
     lib.nimble_host_resident_kernel.restype = ctypes.c_int
@@ -230,6 +233,10 @@ def nimble_topo_set_regime(topo: Topo, regime: int) -> None:
 
 def nimble_topo_reserve(topo: Topo, iters: int) -> None:
     _check(load_library().nimble_topo_reserve(topo.handle, int(iters)))
+
+
+def nimble_topo_reserve_batch(topo: Topo, plans: int, iters: int) -> None:
+    _check(load_library().nimble_topo_reserve_batch(topo.handle, int(plans), int(iters)))
 
 
 def nimble_plan_solve(topo: Topo, d_traffic, eps: float, iters: int, d_splits, d_lambda,
@@ -422,6 +429,11 @@ def plan(topo: Topo, traffic, eps: float, iters: int, device: str = "cuda:0"):
         torch.cuda.synchronize()
         return splits.cpu().numpy(), float(lam.item())
     b = d.shape[0]
+    try:                                  # room for up to 64 plans per launch when streamed
+        nimble_topo_reserve_batch(topo, min(b, 64), iters)
+    except NimbleError as err:
+        if err.status not in (NIMBLE_ERR_RANGE, NIMBLE_ERR_ALLOC):
+            raise
     splits = torch.full((b * topo.n_paths,), nan, dtype=torch.float64, device=device)
     lam = torch.full((b,), nan, dtype=torch.float64, device=device)
     nimble_plan_solve_batch(topo, b, d.reshape(-1), eps, iters, splits, lam)

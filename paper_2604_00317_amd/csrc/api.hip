@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <climits>
 #include <cmath>
 #include <cstdio>
 #include <cstdlib>
@@ -80,6 +81,7 @@ struct nimble_topo {
     int32_t forced_regime = NIMBLE_REGIME_AUTO;
     int32_t last_regime = NIMBLE_REGIME_AUTO;
     int64_t bytes_per_iter = 0, bytes_argmin = 0, bytes_reduce = 0, bytes_update = 0;
+    int64_t bytes_lds_argmin = 0;   // LDS bytes the lane-major record kernels read per launch
     bool state_ready = false;   // a stream-regime solve has initialised the workspace
     uint8_t *state_log = nullptr;   // the log that solve wrote its choices to (null: counters)
     // per-iteration choice log of the streaming regime (rows of log_stride bytes); grows on
@@ -93,6 +95,10 @@ struct nimble_topo {
     bool ad_ready = false;
     int64_t ad_sigma_rows = 0;
     void *sync_words = nullptr; // barrier counter and reductions of the persistent kernel
+    // per-plan state: state_plans blocks of d.state_stride bytes in one allocation; the state
+    // pointers of `d` are those of block 0
+    unsigned char *state = nullptr;
+    int32_t state_plans = 0;
     int n_cu = 0;
     unsigned int spin_limit = 1u << 22;   // barrier polls before a solve is abandoned
 };
@@ -132,6 +138,9 @@ void release(nimble_topo *t)
     if (t->choice_log) (void)hipFree(t->choice_log);
     t->choice_log = nullptr;
     t->log_rows = 0;
+    if (t->state) (void)hipFree(t->state);
+    t->state = nullptr;
+    t->state_plans = 0;
     if (t->ad.sigma_log) (void)hipFree(t->ad.sigma_log);
     t->ad.sigma_log = nullptr;
     t->ad_sigma_rows = 0;
@@ -145,6 +154,7 @@ size_t choice_log_stride(const nimble_topo *t)
 }
 
 constexpr size_t kChoiceLogCap = static_cast<size_t>(1) << 30;       // most a topology reserves
+constexpr size_t kStateCap = static_cast<size_t>(4) << 30;           // and for its plan states
 constexpr size_t kChoiceLogAtCreate = static_cast<size_t>(64) << 20; // reserved without being asked
 constexpr int32_t kDefaultLogRows = 1024;
 
@@ -170,6 +180,80 @@ nimble_status_t grow_choice_log(nimble_topo *t, int32_t iters)
     t->log_rows = iters;
     t->log_stride = stride;
     return NIMBLE_OK;
+}
+
+// Per-plan state of the streaming and persistent regimes: every array a solve writes, laid out
+// in one block (each array 256-byte aligned), so that a batch is `plans` such blocks at a fixed
+// distance.  Entries that only pad an array must read as zero (demand copies, sigma-ordered
+// choices), so a new allocation is cleared once.
+struct StateLayout {
+    size_t demand1n, demand1t, demand2t, choice2, demand2, len, price, S, choice, count, partial,
+        scalars, bytes;
+};
+
+StateLayout state_layout(const nimble::DeviceTopo &d)
+{
+    StateLayout L{};
+    size_t at = 0;
+    auto take = [&](size_t bytes) {
+        const size_t here = at;
+        at = (at + bytes + 255) & ~static_cast<size_t>(255);
+        return here;
+    };
+    const size_t k_pad = (static_cast<size_t>(d.K) + 511) & ~static_cast<size_t>(511);
+    const size_t sg = static_cast<size_t>(d.sigma_size);
+    // 8 spare entries: an octet may start at the last multiple of 4 below K
+    L.demand1n = take(sizeof(double) * (k_pad + 8));
+    L.demand1t = take(sizeof(double) * k_pad);
+    L.demand2t = take(sizeof(double) * sg);
+    L.choice2 = take(sg);
+    L.demand2 = take(sizeof(double) * sg);
+    L.len = take(sizeof(double) * static_cast<size_t>(d.E));
+    L.price = take(sizeof(double) * static_cast<size_t>(d.E));
+    L.S = take(sizeof(double) * static_cast<size_t>(d.E));
+    L.choice = take(k_pad + 8);
+    L.count = take(sizeof(uint32_t) * static_cast<size_t>(d.P));
+    L.partial = take(sizeof(double) * static_cast<size_t>(d.n_slots));
+    // [0] = 1/rho, then one maximum of S per update block, or per wave of the link blocks
+    L.scalars = take(sizeof(double) *
+                     (static_cast<size_t>(std::max(d.n_update_blocks, 4 * d.n_blocks)) + 1));
+    L.bytes = at;
+    return L;
+}
+
+// Makes room for the state of `plans` plans; may free and allocate (both synchronise).
+hipError_t ensure_state_plans(nimble_topo *t, int32_t plans)
+{
+    if (plans <= t->state_plans) return hipSuccess;
+    nimble::DeviceTopo &d = t->d;
+    const StateLayout L = state_layout(d);
+    void *p = nullptr;
+    hipError_t e = hipMalloc(&p, L.bytes * static_cast<size_t>(plans));
+    if (e != hipSuccess) return e;
+    e = hipMemset(p, 0, L.bytes * static_cast<size_t>(plans));
+    if (e != hipSuccess) {
+        (void)hipFree(p);
+        return e;
+    }
+    if (t->state) (void)hipFree(t->state);       // waits for work that still uses it
+    unsigned char *b = static_cast<unsigned char *>(p);
+    t->state = b;
+    t->state_plans = plans;
+    d.state_stride = L.bytes;
+    d.demand1n = reinterpret_cast<double *>(b + L.demand1n);
+    d.demand1t = reinterpret_cast<double *>(b + L.demand1t);
+    d.demand2t = reinterpret_cast<double *>(b + L.demand2t);
+    d.choice2 = reinterpret_cast<uint8_t *>(b + L.choice2);
+    d.demand2 = reinterpret_cast<double *>(b + L.demand2);
+    d.len = reinterpret_cast<double *>(b + L.len);
+    d.price = reinterpret_cast<double *>(b + L.price);
+    d.S = reinterpret_cast<double *>(b + L.S);
+    d.choice = reinterpret_cast<uint8_t *>(b + L.choice);
+    d.count = reinterpret_cast<uint32_t *>(b + L.count);
+    d.partial = reinterpret_cast<double *>(b + L.partial);
+    d.scalars = reinterpret_cast<double *>(b + L.scalars);
+    t->state_ready = false;
+    return hipSuccess;
 }
 
 nimble_status_t check_solve_args(const nimble_topo *topo, const double *d_traffic, double eps,
@@ -217,12 +301,18 @@ int32_t pick_regime(const nimble_topo *topo, int32_t batch)
 // synchronised here.  `log` (rows of `log_stride` bytes, at least `iters` of them) receives the
 // choices of every iteration and the split fractions are counted from it once at the end; with
 // log == nullptr every iteration bumps a per-path counter instead.
+// `plans` > 1 runs that many plans side by side in every launch (grid.y): their traffic, splits
+// and lambda follow each other in the caller's arrays, their state blocks in the topology's
+// (ensure_state_plans must have made room), and plan b logs into rows b * iters ... of `log`.
 nimble_status_t solve_stream(nimble_topo *topo, const double *d_traffic, double eps,
                              int32_t iters, double *d_splits, double *d_lambda, hipStream_t s,
-                             uint8_t *log, size_t log_stride, double *d_len = nullptr)
+                             uint8_t *log, size_t log_stride, double *d_len = nullptr,
+                             int32_t plans = 1)
 {
-    const nimble::DeviceTopo &d = topo->d;
+    nimble::DeviceTopo d = topo->d;
     const bool logged = log != nullptr;
+    d.batch = plans;
+    d.row_stride = logged ? log_stride * static_cast<size_t>(iters) : d.state_stride;
     nimble::launch_init(d, d_traffic, d_len, s);
     nimble::launch_width(d, d_traffic, s);
     for (int32_t it = 0; it < iters; ++it) {
@@ -246,9 +336,10 @@ nimble_status_t solve_stream(nimble_topo *topo, const double *d_traffic, double 
 }
 
 // The topology's own choice log when it holds `iters` rows, else none (per-path counters).
-uint8_t *own_log(const nimble_topo *topo, int32_t iters)
+uint8_t *own_log(const nimble_topo *topo, int32_t iters, int32_t plans = 1)
 {
-    return (!topo->no_choice_log && topo->log_rows >= iters) ? topo->choice_log : nullptr;
+    return (!topo->no_choice_log &&
+            topo->log_rows >= static_cast<int64_t>(iters) * plans) ? topo->choice_log : nullptr;
 }
 
 nimble_status_t solve_persistent(nimble_topo *topo, const double *d_traffic, double eps,
@@ -408,42 +499,16 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     NIMBLE_TRY(upload(t, h.strip_slot.data(), h.strip_slot.size(), &d.strip_slot), "strip_slot");
     d.n_strip_items = h.n_strip_items;
     d.n_tile_items = h.n_tile_items;
-    {
-        const size_t k_pad = (static_cast<size_t>(h.K) + 511) & ~static_cast<size_t>(511);
-        // 8 spare entries: an octet may start at the last multiple of 4 below K
-        NIMBLE_TRY(allocate(t, k_pad + 8, &d.demand1n), "demand1n");
-        NIMBLE_TRY(hipMemset(d.demand1n, 0, sizeof(double) * (k_pad + 8)), "demand1n clear");
-        NIMBLE_TRY(allocate(t, k_pad, &d.demand1t), "demand1t");
-        NIMBLE_TRY(hipMemset(d.demand1t, 0, sizeof(double) * k_pad), "demand1t clear");
-        NIMBLE_TRY(allocate(t, static_cast<size_t>(h.sigma_size), &d.demand2t), "demand2t");
-        NIMBLE_TRY(hipMemset(d.demand2t, 0, sizeof(double) * static_cast<size_t>(h.sigma_size)),
-                   "demand2t clear");
-        d.tile_item_cost = 1;
-        if (const char *env = std::getenv("NIMBLE_TUNE_TILE_ITEM_COST"))
-            if (std::atoi(env) >= 1 && std::atoi(env) <= 64) d.tile_item_cost = std::atoi(env);
-    }
+    d.tile_item_cost = 1;
+    if (const char *env = std::getenv("NIMBLE_TUNE_TILE_ITEM_COST"))
+        if (std::atoi(env) >= 1 && std::atoi(env) <= 64) d.tile_item_cost = std::atoi(env);
     NIMBLE_TRY(upload(t, h.sigma.data(), h.sigma.size(), &d.sigma), "sigma");
     d.sigma_size = h.sigma_size;
-    NIMBLE_TRY(allocate(t, static_cast<size_t>(h.sigma_size), &d.choice2), "choice2");
-    NIMBLE_TRY(allocate(t, static_cast<size_t>(h.sigma_size), &d.demand2), "demand2");
-    NIMBLE_TRY(hipMemset(d.choice2, 0, static_cast<size_t>(h.sigma_size)), "choice2 clear");
-    NIMBLE_TRY(hipMemset(d.demand2, 0, sizeof(double) * static_cast<size_t>(h.sigma_size)),
-               "demand2 clear");
     NIMBLE_TRY(upload(t, h.invcap.data(), h.invcap.size(), &d.invcap), "invcap");
     NIMBLE_TRY(upload(t, h.invcap_pos.data(), h.invcap_pos.size(), &d.invcap_pos), "invcap_pos");
-    NIMBLE_TRY(allocate(t, static_cast<size_t>(h.E), &d.len), "len");
-    NIMBLE_TRY(allocate(t, static_cast<size_t>(h.E), &d.price), "price");
-    NIMBLE_TRY(allocate(t, static_cast<size_t>(h.E), &d.S), "S");
-    // 8 spare entries: the last octet of a row may start at the last multiple of 4 below K
-    NIMBLE_TRY(allocate(t, ((static_cast<size_t>(h.K) + 511) & ~static_cast<size_t>(511)) + 8,
-                        &d.choice),
-               "choice");
-    NIMBLE_TRY(allocate(t, static_cast<size_t>(h.P), &d.count), "count");
-    NIMBLE_TRY(allocate(t, static_cast<size_t>(d.n_slots), &d.partial), "partial");
-    // one maximum of S per update block, or per wave of the fused kernel's link blocks
-    NIMBLE_TRY(allocate(t, static_cast<size_t>(std::max(d.n_update_blocks, 4 * d.n_blocks)) + 1,
-                        &d.scalars),
-               "scalars");
+    // the state of one plan in flight (a block of its own per plan of a batch)
+    d.batch = 1;
+    NIMBLE_TRY(ensure_state_plans(t, 1), "plan state");
     {
         unsigned char *sw = nullptr;
         NIMBLE_TRY(allocate(t, nimble::persistent_sync_bytes(), &sw), "sync words");
@@ -556,6 +621,10 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
         t->bytes_update = 0;
     }
     t->bytes_per_iter = t->bytes_argmin + t->bytes_reduce + t->bytes_update;
+    // lane-major record kernels: every lane reads, per record, one 8-byte price from LDS for
+    // every step of the 8 candidates of its two quads (padding steps included)
+    if (d.n_records > 0 && d.rec_lane_major)
+        t->bytes_lds_argmin = static_cast<int64_t>(d.n_records) * 64 * 8 * 8 * d.rec_stride;
     *out = t;
     return NIMBLE_OK;
 }
@@ -585,6 +654,7 @@ int64_t nimble_topo_phase_bytes(const nimble_topo_t *t, int32_t phase)
     case 0: return t->bytes_argmin;
     case 1: return t->bytes_reduce;
     case 2: return t->bytes_update;
+    case 3: return t->bytes_lds_argmin;
     default: return -1;
     }
 }
@@ -652,13 +722,22 @@ nimble_status_t nimble_plan_solve_batch(nimble_topo_t *topo, int32_t batch,
         if (e != hipSuccess) return fail_hip(e, "kernel launch (resident regime)");
         return NIMBLE_OK;
     }
-    for (int32_t b = 0; b < batch; ++b) {
-        const double *tr = d_traffic + static_cast<size_t>(b) * topo->d.K;
-        double *sp = d_splits + static_cast<size_t>(b) * topo->d.P;
-        st = regime == NIMBLE_REGIME_PERSISTENT
-                 ? solve_persistent(topo, tr, eps, iters, sp, d_lambda + b, s)
-                 : solve_stream(topo, tr, eps, iters, sp, d_lambda + b, s, own_log(topo, iters),
-                                topo->log_stride);
+    if (regime == NIMBLE_REGIME_PERSISTENT) {
+        for (int32_t b = 0; b < batch; ++b) {
+            st = solve_persistent(topo, d_traffic + static_cast<size_t>(b) * topo->d.K, eps, iters,
+                                  d_splits + static_cast<size_t>(b) * topo->d.P, d_lambda + b, s);
+            if (st != NIMBLE_OK) return st;
+        }
+        return NIMBLE_OK;
+    }
+    // streaming regime: the plans share every launch, as many at a time as the state reserved
+    // for them holds (nimble_topo_reserve_batch; a topology starts with room for one)
+    const int32_t group = std::min(batch, topo->state_plans);
+    for (int32_t b = 0; b < batch; b += group) {
+        const int32_t n = std::min(group, batch - b);
+        st = solve_stream(topo, d_traffic + static_cast<size_t>(b) * topo->d.K, eps, iters,
+                          d_splits + static_cast<size_t>(b) * topo->d.P, d_lambda + b, s,
+                          own_log(topo, iters, n), topo->log_stride, nullptr, n);
         if (st != NIMBLE_OK) return st;
     }
     return NIMBLE_OK;
@@ -673,6 +752,28 @@ nimble_status_t nimble_topo_reserve(nimble_topo_t *topo, int32_t iters)
     if (st != NIMBLE_OK) return st;
     if (topo->no_choice_log) return NIMBLE_OK;
     return grow_choice_log(topo, iters);
+}
+
+nimble_status_t nimble_topo_reserve_batch(nimble_topo_t *topo, int32_t plans, int32_t iters)
+{
+    g_last_error.clear();
+    if (!topo) return fail(NIMBLE_ERR_INVALID, "topology handle is NULL");
+    if (plans < 1 || iters < 1) return fail(NIMBLE_ERR_INVALID, "plans and iters must be >= 1");
+    nimble_status_t st = check_device(topo);
+    if (st != NIMBLE_OK) return st;
+    const StateLayout L = state_layout(topo->d);
+    if (L.bytes * static_cast<size_t>(plans) > kStateCap)
+        return fail(NIMBLE_ERR_RANGE, "the state of that many plans exceeds 4 GiB");
+    hipError_t e = ensure_state_plans(topo, plans);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return e == hipErrorOutOfMemory ? fail(NIMBLE_ERR_ALLOC, "plan state")
+                                        : fail_hip(e, "plan state");
+    }
+    if (topo->no_choice_log) return NIMBLE_OK;
+    if (static_cast<int64_t>(plans) * iters > INT32_MAX)
+        return fail(NIMBLE_ERR_RANGE, "plans * iters exceeds 2^31");
+    return grow_choice_log(topo, plans * iters);
 }
 
 int64_t nimble_static_scratch_bytes(void) { return static_cast<int64_t>(kStaticScratchBytes); }

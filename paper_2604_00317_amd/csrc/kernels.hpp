@@ -89,6 +89,10 @@ struct DeviceTopo {
     uint32_t *count;           // [P]
     double *partial;           // [n_slots]
     double *scalars;           // [0] = 1/rho, [1..] = per-block maxima of S (update or link blocks)
+    // plans a launch of the streaming kernels covers (grid.y) and the byte distances between
+    // their state blocks and between their choice rows; 1 and anything for a single plan
+    int32_t batch;
+    size_t state_stride, row_stride;
     int32_t n_update_blocks;
     int32_t update_lanes;      // lanes per link in the length update: 4 or 16
     int32_t reduce_blocks;     // 256-thread blocks of the link-load reduce (fills the chip once)

@@ -28,8 +28,18 @@ __global__ __launch_bounds__(kBlock) void k_init(int E, int K, int P, bool cost_
                                                  double *__restrict__ demand1n,
                                                  double *__restrict__ demand1t,
                                                  double *__restrict__ demand2,
-                                                 double *__restrict__ demand2t)
+                                                 double *__restrict__ demand2t, PlanStrides ps)
 {
+    len = of_plan(len, ps.state);
+    price = of_plan(price, ps.state);
+    S = of_plan(S, ps.state);
+    choice = of_plan(choice, ps.state);
+    count = of_plan(count, ps.state);
+    demand = of_plan(demand, ps.demand);
+    demand1n = of_plan(demand1n, ps.state);
+    demand1t = of_plan(demand1t, ps.state);
+    demand2 = of_plan(demand2, ps.state);
+    demand2t = of_plan(demand2t, ps.state);
     const int stride = gridDim.x * blockDim.x;
     const int tid = blockIdx.x * blockDim.x + threadIdx.x;
     // the library's own copies of the demands: by id (aligned, padded) and in sigma order for
@@ -74,8 +84,12 @@ __global__ __launch_bounds__(kBlock) void k_argmin(int K, const int32_t *__restr
                                                    uint8_t *__restrict__ choice,
                                                    uint32_t *__restrict__ count,
                                                    const int32_t *__restrict__ sigma,
-                                                   uint8_t *__restrict__ choice2)
+                                                   uint8_t *__restrict__ choice2, PlanStrides ps)
 {
+    price = of_plan(price, ps.state);
+    choice = of_plan(choice, ps.row);
+    count = of_plan(count, ps.state);
+    choice2 = of_plan(choice2, ps.state);
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
@@ -130,8 +144,13 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records,
                                                       const double *__restrict__ price,
                                                       uint8_t *__restrict__ choice,
                                                       uint32_t *__restrict__ count,
-                                                      uint8_t *__restrict__ choice2)
+                                                      uint8_t *__restrict__ choice2,
+                                                      PlanStrides ps)
 {
+    price = of_plan(price, ps.state);
+    choice = of_plan(choice, ps.row);
+    count = of_plan(count, ps.state);
+    choice2 = of_plan(choice2, ps.state);
     // LDS, one private slice per wave: the body of the record (everything after the link
     // table) followed by the price table.  The waves of a workgroup never synchronise with
     // each other.
@@ -288,10 +307,15 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records,
                                                        const double *__restrict__ price,
                                                        uint8_t *__restrict__ choice,
                                                        uint32_t *__restrict__ count,
-                                                       uint8_t *__restrict__ choice2)
+                                                       uint8_t *__restrict__ choice2,
+                                                       PlanStrides ps)
 {
     static_assert(L >= 2 && L <= 16 && S <= kRecLaneSteps,
                   "lane-major records: 2 to 16 lanes per commodity, five steps");
+    price = of_plan(price, ps.state);
+    choice = of_plan(choice, ps.row);
+    count = of_plan(count, ps.state);
+    choice2 = of_plan(choice2, ps.state);
     // T16: the link table is 256 uint16 (8 bytes per lane) and the record 3.5 KiB
     constexpr int kTab = T16 ? kRecTable16 : kRecTable;
     constexpr int kRec = T16 ? kRecBytes16 : kRecBytes;
@@ -446,10 +470,15 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recd(int n_chunks, 
                                                        const double *__restrict__ price,
                                                        uint8_t *__restrict__ choice,
                                                        uint32_t *__restrict__ count,
-                                                       uint8_t *__restrict__ choice2)
+                                                       uint8_t *__restrict__ choice2,
+                                                       PlanStrides ps)
 {
     static_assert(L >= 2 && L <= 16 && S <= kRecLaneSteps,
                   "lane-major records: 2 to 16 lanes per commodity, five steps");
+    price = of_plan(price, ps.state);
+    choice = of_plan(choice, ps.row);
+    count = of_plan(count, ps.state);
+    choice2 = of_plan(choice2, ps.state);
     __shared__ double s_all[kRecWaves * kRecPriceSlots];
     double *s_price = s_all + (threadIdx.x >> 6) * kRecPriceSlots;
     const int lane = threadIdx.x & (kWave - 1);
@@ -541,8 +570,10 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recd(int n_chunks, 
 __global__ __launch_bounds__(kWave) void k_histogram(int K, int iters, int pmax, size_t stride,
                                                      const uint8_t *__restrict__ log,
                                                      const int32_t *__restrict__ cp,
-                                                     double *__restrict__ splits)
+                                                     double *__restrict__ splits, PlanStrides ps)
 {
+    log = of_plan(log, ps.row);
+    splits = of_plan(splits, ps.splits);
     extern __shared__ uint32_t s_cnt[];
     const int lane = threadIdx.x;
     const int k = blockIdx.x * kWave + lane;
@@ -584,11 +615,20 @@ struct ReduceArgs {
     const uint8_t *choice, *choice2;
     const double *demand, *demand2;
     double *partial;
+    PlanStrides ps;
 };
 
 template <int MODE>
 __global__ __launch_bounds__(kBlock) void k_load_reduce(ReduceArgs a)
 {
+    a.demand1n = of_plan(a.demand1n, a.ps.state);
+    a.demand1t = of_plan(a.demand1t, a.ps.state);
+    a.demand2t = of_plan(a.demand2t, a.ps.state);
+    a.demand2 = of_plan(a.demand2, a.ps.state);
+    a.choice2 = of_plan(a.choice2, a.ps.state);
+    a.partial = of_plan(a.partial, a.ps.state);
+    a.choice = of_plan(a.choice, a.ps.row);
+    a.demand = of_plan(a.demand, a.ps.demand);
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
@@ -630,6 +670,8 @@ struct FusedArgs {
     const double *invcap_pos;
     double *len, *price, *S, *scalars;
     double eps;
+    PlanStrides ps;
+    int n_plans;
 };
 
 struct LinkState {
@@ -637,21 +679,39 @@ struct LinkState {
     double ic, s, l;
 };
 
-template <bool MAXC>
+// PER_WAVE (batches): a workgroup takes one link block for four plans, one wave each.  The wave
+// walks all passes of the block alone (the octets of its next pass in flight while one is
+// summed), keeps the slot partials in a slice of LDS of its own and applies the update of the
+// block's links itself, so the waves never wait for each other.  A batch then needs a quarter
+// of the workgroups, each as long as one latency chain, instead of one chain per plan and block.
+template <bool MAXC, bool PER_WAVE>
 __global__ __launch_bounds__(kBlock) void k_reduce_update(FusedArgs a)
 {
-    __shared__ double s_part[kBlkMaxSlots];
+    __shared__ double s_part_all[(PER_WAVE ? kBlock / kWave : 1) * kBlkMaxSlots];
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
+    const int plan = PER_WAVE ? static_cast<int>(blockIdx.y) * (kBlock / kWave) + wave
+                              : static_cast<int>(blockIdx.y);
+    if (PER_WAVE && plan >= a.n_plans) return;      // the waves of such a workgroup never meet
+    double *s_part = s_part_all + (PER_WAVE ? wave * kBlkMaxSlots : 0);
+    a.choice = of_plan_at(a.choice, a.ps.row, plan);
+    a.choice2 = of_plan_at(a.choice2, a.ps.state, plan);
+    a.demand1n = of_plan_at(a.demand1n, a.ps.state, plan);
+    a.demand2 = of_plan_at(a.demand2, a.ps.state, plan);
+    a.len = of_plan_at(a.len, a.ps.state, plan);
+    a.price = of_plan_at(a.price, a.ps.state, plan);
+    a.S = of_plan_at(a.S, a.ps.state, plan);
+    a.scalars = of_plan_at(a.scalars, a.ps.state, plan);
     const int b = blockIdx.x;
     const int4 d4 = *reinterpret_cast<const int4 *>(a.blk_desc + 8 * b);
     const int i0 = d4.x, i1 = d4.y;             // positions of the block (at least one)
     const int p0 = d4.z, p1 = d4.w;             // its passes
     const int slot0 = a.blk_desc[8 * b + 4];
     const double invrho = a.scalars[0];
-    const int row = threadIdx.x / kRowLanes;
-    const int l = threadIdx.x % kRowLanes;
-    constexpr int kRows = kBlock / kRowLanes;
+    const int tid = PER_WAVE ? lane : static_cast<int>(threadIdx.x);
+    const int row = tid / kRowLanes;
+    const int l = tid % kRowLanes;
+    constexpr int kRows = (PER_WAVE ? kWave : kBlock) / kRowLanes;
     // positions past the end re-read the last one (so that every load is unconditional) and
     // are masked out when the update is applied
     auto fetch = [&](int i) {
@@ -685,14 +745,22 @@ __global__ __launch_bounds__(kBlock) void k_reduce_update(FusedArgs a)
     const LinkState st0 = fetch(i0 + row);
     const LinkState st1 = fetch(i0 + row + kRows);
     reduce_flat_phase<0>(p0, p1, a.pass_first_slot, a.oct_base, a.oct_mask, a.choice, a.demand1n,
-                         a.choice2, a.demand2, s_part, slot0, wave, kBlock / kWave, lane);
-    __syncthreads();
+                         a.choice2, a.demand2, s_part, slot0, PER_WAVE ? 0 : wave,
+                         PER_WAVE ? 1 : kBlock / kWave, lane);
+    if constexpr (PER_WAVE) wave_lds_sync();
+    else __syncthreads();
     apply(i0 + row, st0);
     apply(i0 + row + kRows, st1);
-    for (int ibase = i0 + 2 * kRows; ibase < i1; ibase += kRows)         // block-uniform, rare
+    for (int ibase = i0 + 2 * kRows; ibase < i1; ibase += kRows)         // uniform, rare
         apply(ibase + row, fetch(ibase + row));
     const double m = wave_max(smax);
-    if (lane == 0) a.scalars[1 + b * (kBlock / kWave) + wave] = m;
+    // one maximum of S per wave of the workgroup kernel; the wave kernel fills the block's
+    // other three entries with 0 (S is never negative)
+    if constexpr (PER_WAVE) {
+        if (lane < kBlock / kWave) a.scalars[1 + b * (kBlock / kWave) + lane] = lane == 0 ? m : 0.0;
+    } else {
+        if (lane == 0) a.scalars[1 + b * (kBlock / kWave) + wave] = m;
+    }
 }
 
 // rho = max_e (demand that can reach e) / cap_e, in two steps: every block leaves the maximum
@@ -703,9 +771,11 @@ __global__ __launch_bounds__(kBlock) void k_width(int E,
                                                   const int2 *__restrict__ pos_xslot,
                                                   const double *__restrict__ partial,
                                                   const double *__restrict__ invcap,
-                                                  double *__restrict__ scalars)
+                                                  double *__restrict__ scalars, PlanStrides ps)
 {
     __shared__ double red[16];
+    partial = of_plan(partial, ps.state);
+    scalars = of_plan(scalars, ps.state);
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
     double m = width_phase(E, pos_slot_ptr, pos_xslot, partial, invcap, wave, n_waves,
@@ -714,9 +784,11 @@ __global__ __launch_bounds__(kBlock) void k_width(int E,
     if (threadIdx.x == 0) scalars[1 + blockIdx.x] = m;
 }
 
-__global__ __launch_bounds__(kBlock) void k_width_fold(int n_blocks, double *__restrict__ scalars)
+__global__ __launch_bounds__(kBlock) void k_width_fold(int n_blocks, double *__restrict__ scalars,
+                                                       PlanStrides ps)
 {
     __shared__ double red[16];
+    scalars = of_plan(scalars, ps.state);
     double m = 0.0;
     for (int b = threadIdx.x; b < n_blocks; b += blockDim.x) m = fmax(m, scalars[1 + b]);
     m = block_max(m, red);
@@ -734,9 +806,14 @@ __global__ __launch_bounds__(kBlock) void k_update(int E, double eps,
                                                    double *__restrict__ len,
                                                    double *__restrict__ price,
                                                    double *__restrict__ S,
-                                                   double *__restrict__ scalars)
+                                                   double *__restrict__ scalars, PlanStrides ps)
 {
     __shared__ double red[16];
+    partial = of_plan(partial, ps.state);
+    len = of_plan(len, ps.state);
+    price = of_plan(price, ps.state);
+    S = of_plan(S, ps.state);
+    scalars = of_plan(scalars, ps.state);
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
@@ -751,9 +828,13 @@ __global__ __launch_bounds__(kBlock) void k_epilogue(int P, int iters, int n_upd
                                                      const uint32_t *__restrict__ count,
                                                      const double *__restrict__ scalars,
                                                      double *__restrict__ splits,
-                                                     double *__restrict__ lambda)
+                                                     double *__restrict__ lambda, PlanStrides ps)
 {
     __shared__ double red[16];
+    count = of_plan(count, ps.state);
+    scalars = of_plan(scalars, ps.state);
+    splits = of_plan(splits, ps.splits);
+    lambda = lambda + blockIdx.y;
     const double T = static_cast<double>(iters);
     const int stride = gridDim.x * blockDim.x;
     if (count != nullptr)         // otherwise the splits come from the choice log
@@ -796,6 +877,17 @@ inline int blocks_for(int64_t threads, int block, int cap)
     return static_cast<int>(b);
 }
 
+// byte distances between the plans of the batch a launch covers (t.batch plans, grid.y)
+inline PlanStrides strides_of(const DeviceTopo &t)
+{
+    PlanStrides ps;
+    ps.state = t.state_stride;
+    ps.row = t.row_stride;
+    ps.demand = sizeof(double) * static_cast<size_t>(t.K);
+    ps.splits = sizeof(double) * static_cast<size_t>(t.P);
+    return ps;
+}
+
 template <int L, bool MAXC>
 void launch_argmin_lmax(const DeviceTopo &t, int grid, uint8_t *choice, uint32_t *count,
                         hipStream_t s)
@@ -821,10 +913,11 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, uint8_t *choice, uint32_t
                     const int dgrid = (t.n_rec_chunks + kRecWaves - 1) / kRecWaves;
 #define NIMBLE_RECD_LAUNCH(SS)                                                                 \
     case SS:                                                                                   \
-        hipLaunchKernelGGL((k_argmin_recd<L, SS, MAXC>), dim3(dgrid), dim3(kWave * kRecWaves), \
-                           0, s, t.n_rec_chunks, around_l2, t.rec_chunks, t.records,           \
+        hipLaunchKernelGGL((k_argmin_recd<L, SS, MAXC>), dim3(dgrid, t.batch),                 \
+                           dim3(kWave * kRecWaves), 0, s, t.n_rec_chunks, around_l2,           \
+                           t.rec_chunks, t.records,                                            \
                            reinterpret_cast<const u32x4 *>(t.rec_dict_words), t.price, choice, \
-                           count, t.choice2);                                                  \
+                           count, t.choice2, strides_of(t));                                   \
         return;
                     switch (t.rec_stride) {
                         NIMBLE_RECD_LAUNCH(1)
@@ -838,13 +931,13 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, uint8_t *choice, uint32_t
 #define NIMBLE_RECL_LAUNCH(SS)                                                                 \
     case SS:                                                                                   \
         if (t.rec_table16)                                                                     \
-            hipLaunchKernelGGL((k_argmin_recl<L, SS, MAXC, true>), dim3(rec_grid),             \
+            hipLaunchKernelGGL((k_argmin_recl<L, SS, MAXC, true>), dim3(rec_grid, t.batch),    \
                                dim3(kWave * kRecWaves), 0, s, t.n_records, around_l2,          \
-                               t.records, t.price, choice, count, t.choice2);                  \
+                               t.records, t.price, choice, count, t.choice2, strides_of(t));   \
         else                                                                                   \
-            hipLaunchKernelGGL((k_argmin_recl<L, SS, MAXC, false>), dim3(rec_grid),            \
+            hipLaunchKernelGGL((k_argmin_recl<L, SS, MAXC, false>), dim3(rec_grid, t.batch),   \
                                dim3(kWave * kRecWaves), 0, s, t.n_records, around_l2,          \
-                               t.records, t.price, choice, count, t.choice2);                  \
+                               t.records, t.price, choice, count, t.choice2, strides_of(t));   \
         return;
                 switch (t.rec_stride) {
                     NIMBLE_RECL_LAUNCH(1)
@@ -861,13 +954,13 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, uint8_t *choice, uint32_t
 #define NIMBLE_REC_LAUNCH(SS)                                                                  \
     case SS:                                                                                   \
         if (two)                                                                               \
-            hipLaunchKernelGGL((k_argmin_rec<L, SS, MAXC, true>), dim3(rec_grid),              \
+            hipLaunchKernelGGL((k_argmin_rec<L, SS, MAXC, true>), dim3(rec_grid, t.batch),     \
                                dim3(kWave * kRecWaves), 0, s, t.n_records, t.records, t.price, \
-                               choice, count, t.choice2);                                      \
+                               choice, count, t.choice2, strides_of(t));                       \
         else                                                                                   \
-            hipLaunchKernelGGL((k_argmin_rec<L, SS, MAXC, false>), dim3(rec_grid),             \
+            hipLaunchKernelGGL((k_argmin_rec<L, SS, MAXC, false>), dim3(rec_grid, t.batch),    \
                                dim3(kWave * kRecWaves), 0, s, t.n_records, t.records, t.price, \
-                               choice, count, t.choice2);                                      \
+                               choice, count, t.choice2, strides_of(t));                       \
         return;
         switch (t.rec_stride) {
             NIMBLE_REC_LAUNCH(1)
@@ -882,9 +975,9 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, uint8_t *choice, uint32_t
 #undef NIMBLE_REC_LAUNCH
     }
 #define NIMBLE_ARGMIN_LAUNCH(LM)                                                              \
-    hipLaunchKernelGGL((k_argmin<L, LM, MAXC>), dim3(grid), dim3(kBlock), 0, s, t.K,          \
+    hipLaunchKernelGGL((k_argmin<L, LM, MAXC>), dim3(grid, t.batch), dim3(kBlock), 0, s, t.K, \
                        t.comm_ptr, t.path_ptr, t.path_links, t.price, choice, count, t.sigma, \
-                       t.choice2)
+                       t.choice2, strides_of(t))
     if (t.lmax <= 2) NIMBLE_ARGMIN_LAUNCH(2);
     else if (t.lmax <= 4) NIMBLE_ARGMIN_LAUNCH(4);
     else NIMBLE_ARGMIN_LAUNCH(8);
@@ -974,7 +1067,8 @@ void launch_reduce_mode(const DeviceTopo &t, const uint8_t *choice, const double
     a.demand = demand;
     a.demand2 = t.demand2;
     a.partial = t.partial;
-    hipLaunchKernelGGL(k_load_reduce<MODE>, dim3(grid), dim3(kBlock), 0, s, a);
+    a.ps = strides_of(t);
+    hipLaunchKernelGGL(k_load_reduce<MODE>, dim3(grid, t.batch), dim3(kBlock), 0, s, a);
 }
 
 }  // namespace
@@ -1057,17 +1151,20 @@ void launch_export_len(const DeviceTopo &t, double *len_out, hipStream_t s)
 void launch_init(const DeviceTopo &t, const double *demand, const double *len_in, hipStream_t s)
 {
     const int n = t.E > t.P ? t.E : t.P;
-    hipLaunchKernelGGL(k_init, dim3(blocks_for(n, kBlock, 4096)), dim3(kBlock), 0, s, t.E, t.K,
-                       t.P, t.cost_max, len_in, t.pos_link, t.invcap, t.len, t.price, t.S, t.choice, t.count, t.sigma,
-                       demand, t.demand1n, t.demand1t, t.demand2, t.demand2t);
+    hipLaunchKernelGGL(k_init, dim3(blocks_for(n, kBlock, 4096), t.batch), dim3(kBlock), 0, s,
+                       t.E, t.K, t.P, t.cost_max, len_in, t.pos_link, t.invcap, t.len, t.price,
+                       t.S, t.choice, t.count, t.sigma, demand, t.demand1n, t.demand1t, t.demand2,
+                       t.demand2t, strides_of(t));
 }
 
 void launch_width(const DeviceTopo &t, const double *demand, hipStream_t s)
 {
     launch_reduce_mode<1>(t, t.choice, demand, s);
-    hipLaunchKernelGGL(k_width, dim3(t.n_update_blocks), dim3(kBlock), 0, s, t.E,
-                       t.pos_slot_ptr, t.pos_xslot, t.partial, t.invcap_pos, t.scalars);
-    hipLaunchKernelGGL(k_width_fold, dim3(1), dim3(kBlock), 0, s, t.n_update_blocks, t.scalars);
+    hipLaunchKernelGGL(k_width, dim3(t.n_update_blocks, t.batch), dim3(kBlock), 0, s, t.E,
+                       t.pos_slot_ptr, t.pos_xslot, t.partial, t.invcap_pos, t.scalars,
+                       strides_of(t));
+    hipLaunchKernelGGL(k_width_fold, dim3(1, t.batch), dim3(kBlock), 0, s, t.n_update_blocks,
+                       t.scalars, strides_of(t));
 }
 
 void launch_argmin(const DeviceTopo &t, uint8_t *choice, uint32_t *count, hipStream_t s)
@@ -1086,16 +1183,16 @@ void launch_histogram(const DeviceTopo &t, const uint8_t *log, size_t stride, in
                       double *splits, hipStream_t s)
 {
     const size_t lds = sizeof(uint32_t) * kWave * static_cast<size_t>(t.pmax | 1);
-    hipLaunchKernelGGL(k_histogram, dim3((t.K + kWave - 1) / kWave), dim3(kWave), lds, s, t.K,
-                       iters, t.pmax, stride, log, t.comm_ptr, splits);
+    hipLaunchKernelGGL(k_histogram, dim3((t.K + kWave - 1) / kWave, t.batch), dim3(kWave), lds, s,
+                       t.K, iters, t.pmax, stride, log, t.comm_ptr, splits, strides_of(t));
 }
 
 void launch_update(const DeviceTopo &t, double eps, hipStream_t s)
 {
 #define NIMBLE_UPDATE_LAUNCH(MC, RL)                                                           \
-    hipLaunchKernelGGL((k_update<MC, RL>), dim3(t.n_update_blocks), dim3(kBlock), 0, s, t.E,   \
-                       eps, t.pos_link, t.pos_slot_ptr, t.pos_xslot, t.partial, t.invcap_pos,  \
-                       t.len, t.price, t.S, t.scalars)
+    hipLaunchKernelGGL((k_update<MC, RL>), dim3(t.n_update_blocks, t.batch), dim3(kBlock), 0,  \
+                       s, t.E, eps, t.pos_link, t.pos_slot_ptr, t.pos_xslot, t.partial,        \
+                       t.invcap_pos, t.len, t.price, t.S, t.scalars, strides_of(t))
     if (t.update_lanes == 4) {
         if (t.cost_max) NIMBLE_UPDATE_LAUNCH(true, 4);
         else NIMBLE_UPDATE_LAUNCH(false, 4);
@@ -1126,10 +1223,24 @@ void launch_reduce_update(const DeviceTopo &t, const uint8_t *choice, const doub
     a.S = t.S;
     a.scalars = t.scalars;
     a.eps = eps;
+    a.ps = strides_of(t);
+    a.n_plans = t.batch;
+    constexpr int kPlansPerBlock = kBlock / kWave;
+    if (t.batch >= kPlansPerBlock) {
+        // batches: a wave per plan and link block
+        const dim3 grid(t.n_blocks, (t.batch + kPlansPerBlock - 1) / kPlansPerBlock);
+        if (t.cost_max)
+            hipLaunchKernelGGL((k_reduce_update<true, true>), grid, dim3(kBlock), 0, s, a);
+        else
+            hipLaunchKernelGGL((k_reduce_update<false, true>), grid, dim3(kBlock), 0, s, a);
+        return;
+    }
     if (t.cost_max)
-        hipLaunchKernelGGL(k_reduce_update<true>, dim3(t.n_blocks), dim3(kBlock), 0, s, a);
+        hipLaunchKernelGGL((k_reduce_update<true, false>), dim3(t.n_blocks, t.batch), dim3(kBlock),
+                           0, s, a);
     else
-        hipLaunchKernelGGL(k_reduce_update<false>, dim3(t.n_blocks), dim3(kBlock), 0, s, a);
+        hipLaunchKernelGGL((k_reduce_update<false, false>), dim3(t.n_blocks, t.batch),
+                           dim3(kBlock), 0, s, a);
 }
 
 void launch_epilogue(const DeviceTopo &t, int32_t iters, const uint32_t *count, double *splits,
@@ -1139,8 +1250,8 @@ void launch_epilogue(const DeviceTopo &t, int32_t iters, const uint32_t *count, 
     // kernel ran, update blocks otherwise
     const int n_max = t.n_blocks > 0 ? t.n_blocks * (kBlock / kWave) : t.n_update_blocks;
     const int grid = count ? blocks_for(t.P, kBlock, 4096) : 1;
-    hipLaunchKernelGGL(k_epilogue, dim3(grid), dim3(kBlock), 0, s, t.P, iters, n_max, count,
-                       t.scalars, splits, lambda);
+    hipLaunchKernelGGL(k_epilogue, dim3(grid, t.batch), dim3(kBlock), 0, s, t.P, iters, n_max,
+                       count, t.scalars, splits, lambda, strides_of(t));
 }
 
 }  // namespace nimble

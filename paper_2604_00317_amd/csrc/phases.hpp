@@ -39,6 +39,32 @@ __device__ __forceinline__ T csr_load(const T *p)
     return *p;
 }
 
+// ---- batches of plans -----------------------------------------------------------------------
+// The streaming kernels run the plans of a batch side by side: blockIdx.y is the plan.  All the
+// per-plan state of a topology (demand copies, lengths, prices, congestion sums, choices,
+// counts, partials, scalars) lives in one block per plan, so the same byte distance leads from
+// any state array of plan 0 to that array of plan b; the caller's arrays and the rows of the
+// choice log have distances of their own.
+struct PlanStrides {
+    size_t state;      // between the state blocks of consecutive plans
+    size_t row;        // between the choice rows of one iteration
+    size_t demand;     // between the caller's demand vectors
+    size_t splits;     // between the caller's split vectors
+};
+
+template <typename T>
+__device__ __forceinline__ T *of_plan_at(T *p, size_t stride, int plan)
+{
+    if (p == nullptr) return p;
+    return reinterpret_cast<T *>(reinterpret_cast<uintptr_t>(p) + stride * static_cast<size_t>(plan));
+}
+
+template <typename T>
+__device__ __forceinline__ T *of_plan(T *p, size_t stride)
+{
+    return of_plan_at(p, stride, static_cast<int>(blockIdx.y));
+}
+
 // ---- phase A: path-cost gather over the path->link CSR + per-commodity argmin -------------
 // L lanes cooperate on one commodity (lane j takes candidates j, j+L, ...); the first LMAX links
 // of a path are loaded before any is used so that their latencies overlap.  Costs are added

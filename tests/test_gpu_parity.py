@@ -100,6 +100,69 @@ def test_batch_outside_the_resident_regime(oracle_mod, B, regime):
         assert lam[b] == ref["lam"], b
 
 
+def _batch_traffic(w, n):
+    """n demand vectors for the fabric of w: its own and scaled, thinned and zero variants."""
+    rng = np.random.default_rng(7)
+    rows = [w.traffic]
+    for b in range(1, n):
+        d = np.floor(w.traffic / (b + 1))
+        d[rng.random(d.size) < 0.1 * b] = 0.0
+        rows.append(d)
+    if n > 2:
+        rows[-1] = np.zeros_like(w.traffic)
+    return np.stack(rows)
+
+
+@pytest.mark.parametrize("env", [{}, {"NIMBLE_TUNE_NO_CHOICE_LOG": "1"},
+                                 {"NIMBLE_TUNE_NO_LINK_BLOCKS": "1"},
+                                 {"NIMBLE_TUNE_TILES": "1", "NIMBLE_TUNE_TILE_MIN_ITEMS": "24"},
+                                 {"NIMBLE_TUNE_RECORD_DICT": "1"},
+                                 {"NIMBLE_TUNE_RECORD_LANE_MAJOR": "0"},
+                                 {"NIMBLE_TUNE_NO_RECORDS": "1"}],
+                         ids=["default", "counters", "separate-update", "tiles", "dictionary",
+                              "record-major", "untiled"])
+def test_streamed_batch_shares_every_launch(oracle_mod, B, monkeypatch, env):
+    """A batch of plans on a fabric that is streamed: with room reserved for them the plans of a
+    batch run side by side in every kernel launch (one state block and one range of log rows
+    each).  Every plan must match the oracle, in every layout the streaming kernels know, with
+    the whole batch in one group, in groups of two (the last one short), and bottleneck cost."""
+    for name, value in env.items():
+        monkeypatch.setenv(name, value)
+    import torch
+    for cfg, iters, n, flags in ((3, 40, 5, 0), (1, 60, 4, 1)):
+        w = W.make_config(cfg)
+        t = w.topo
+        tr = _batch_traffic(w, n)
+        refs = [oracle_mod.solve(*t.csr(), tr[b], w.eps, iters, flags=flags) for b in range(n)]
+        for group in (n, 2):
+            print(f"[batch] cfg={cfg} n={n} group={group} env={env}", flush=True)
+            h = B.nimble_topo_create(*t.csr(), flags=flags)
+            try:
+                B.nimble_topo_set_regime(h, B.NIMBLE_REGIME_STREAM)
+                B.nimble_topo_reserve_batch(h, group, iters)
+                d = torch.as_tensor(tr.reshape(-1)).to("cuda:0")
+                splits = torch.full((n * t.n_paths,), float("nan"), dtype=torch.float64,
+                                    device="cuda:0")
+                lam = torch.full((n,), float("nan"), dtype=torch.float64, device="cuda:0")
+                B.nimble_plan_solve_batch(h, n, d, w.eps, iters, splits, lam)
+                torch.cuda.synchronize()
+                sp = splits.cpu().numpy().reshape(n, t.n_paths)
+                la = lam.cpu().numpy()
+                # a single plan afterwards still uses block 0 alone
+                one_s = torch.full((t.n_paths,), float("nan"), dtype=torch.float64, device="cuda:0")
+                one_l = torch.full((1,), float("nan"), dtype=torch.float64, device="cuda:0")
+                B.nimble_plan_solve(h, d[t.n_comm:2 * t.n_comm].contiguous(), w.eps, iters, one_s,
+                                    one_l)
+                torch.cuda.synchronize()
+            finally:
+                h.close()
+            for b in range(n):
+                assert np.array_equal(sp[b], refs[b]["splits"]), (cfg, group, b)
+                assert la[b] == refs[b]["lam"], (cfg, group, b)
+            assert np.array_equal(one_s.cpu().numpy(), refs[1]["splits"])
+            assert float(one_l.item()) == refs[1]["lam"]
+
+
 @pytest.mark.parametrize("flags", [0, 1])
 @pytest.mark.parametrize("seed,E,K,pm,lm,in_regs", [(21, 30, 25, 8, 2, True),
                                                     (22, 64, 64, 5, 2, True),
