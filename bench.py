@@ -118,7 +118,7 @@ def run_config(B, W, torch, cfg, regime, steps, warmup, iters_override=0, batch_
         w.batch = plans
     t_gen = time.perf_counter() - t_gen
     t_create = time.perf_counter()
-    h = B.nimble_topo_create(*topo.csr())
+    h = B.nimble_topo_create(*topo.csr(), flags=B.NIMBLE_LAYOUT_BATCH if plans > 0 else 0)
     t_create = time.perf_counter() - t_create
     B.nimble_topo_set_regime(h, regime)
     B.nimble_topo_reserve(h, w.iters)       # the choice log, sized outside the timed solves

@@ -41,8 +41,12 @@ typedef enum {
 /* flags of nimble_topo_create */
 enum {
     NIMBLE_COST_SUM = 0u, /* path cost = sum of link prices, price = len/cap (default) */
-    NIMBLE_COST_MAX = 1u  /* path cost = max of link prices, price = len: the bottleneck
+    NIMBLE_COST_MAX = 1u, /* path cost = max of link prices, price = len: the bottleneck
                              rule of Sec. IV-B (intra-node 2-hop and inter-node path costs) */
+    NIMBLE_LAYOUT_BATCH = 2u /* the topology will mostly solve batches of plans in the streaming
+                             regime (nimble_topo_reserve_batch): lay the reverse CSR out for
+                             launches that cover many plans, at the price of slower single
+                             plans on mid-size fabrics.  Results do not depend on it. */
 };
 
 /* kernel regimes, for nimble_topo_set_regime (testing and benchmarking) */
@@ -73,7 +77,7 @@ enum {
  *   path_link_ptr  host [n_paths+1], path_link_ptr[0] = 0, strictly increasing
  *   path_links     host [path_link_ptr[n_paths]], link ids in [0, n_links), no link twice in
  *                  one path; the order inside a path is the order costs are added in
- *   flags          NIMBLE_COST_SUM or NIMBLE_COST_MAX
+ *   flags          NIMBLE_COST_SUM or NIMBLE_COST_MAX, optionally | NIMBLE_LAYOUT_BATCH
  *   out            receives the handle; release it with nimble_topo_destroy
  *
  * Validation happens here, on the host, before any device call: malformed input returns

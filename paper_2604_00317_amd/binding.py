@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libnimble_plan.so")
 
 NIMBLE_OK, NIMBLE_ERR_INVALID, NIMBLE_ERR_ALLOC, NIMBLE_ERR_HIP, NIMBLE_ERR_RANGE = range(5)
-NIMBLE_COST_SUM, NIMBLE_COST_MAX = 0, 1
+NIMBLE_COST_SUM, NIMBLE_COST_MAX, NIMBLE_LAYOUT_BATCH = 0, 1, 2
 NIMBLE_REGIME_AUTO, NIMBLE_REGIME_RESIDENT, NIMBLE_REGIME_STREAM, NIMBLE_REGIME_PERSISTENT = \
     range(4)
 

@@ -368,7 +368,7 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     if (!out) return fail(NIMBLE_ERR_INVALID, "out is NULL");
     *out = nullptr;
     if (!cap) return fail(NIMBLE_ERR_INVALID, "cap is NULL");
-    if (flags & ~static_cast<uint32_t>(NIMBLE_COST_MAX))
+    if (flags & ~static_cast<uint32_t>(NIMBLE_COST_MAX | NIMBLE_LAYOUT_BATCH))
         return fail(NIMBLE_ERR_INVALID, "unknown flag bits");
     std::string why;
     nimble_status_t st = nimble::validate_csr(n_links, cap, n_comm, comm_path_ptr, n_paths,
@@ -382,6 +382,10 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     nimble::HostTopo h;
     try {
         t = new nimble_topo();
+        // a topology meant for batches takes the tiled reverse layout whatever its size: its
+        // choices and demands are fetched window by window, which is what bounds a launch that
+        // covers many plans (a single plan of a mid-size fabric is faster with link blocks)
+        if (flags & NIMBLE_LAYOUT_BATCH) h.tiles = 1;
         nimble::read_layout_options(h);
         nimble::build_host_topo(n_links, cap, n_comm, comm_path_ptr, n_paths, path_link_ptr,
                                 path_links, h);
@@ -508,6 +512,9 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     NIMBLE_TRY(upload(t, h.invcap_pos.data(), h.invcap_pos.size(), &d.invcap_pos), "invcap_pos");
     // the state of one plan in flight (a block of its own per plan of a batch)
     d.batch = 1;
+    d.batch_kernel = 0;
+    if (const char *env = std::getenv("NIMBLE_TUNE_BATCH_KERNEL"))
+        if (std::atoi(env) >= 0 && std::atoi(env) <= 1) d.batch_kernel = std::atoi(env);
     NIMBLE_TRY(ensure_state_plans(t, 1), "plan state");
     {
         unsigned char *sw = nullptr;

@@ -93,6 +93,8 @@ struct DeviceTopo {
     // their state blocks and between their choice rows; 1 and anything for a single plan
     int32_t batch;
     size_t state_stride, row_stride;
+    int32_t batch_kernel;      // tuning: 0 four plans per workgroup in the fused reduce + update
+                               // of a batch, 1 the single-plan kernel for every plan
     int32_t n_update_blocks;
     int32_t update_lanes;      // lanes per link in the length update: 4 or 16
     int32_t reduce_blocks;     // 256-thread blocks of the link-load reduce (fills the chip once)

@@ -679,39 +679,29 @@ struct LinkState {
     double ic, s, l;
 };
 
-// PER_WAVE (batches): a workgroup takes one link block for four plans, one wave each.  The wave
-// walks all passes of the block alone (the octets of its next pass in flight while one is
-// summed), keeps the slot partials in a slice of LDS of its own and applies the update of the
-// block's links itself, so the waves never wait for each other.  A batch then needs a quarter
-// of the workgroups, each as long as one latency chain, instead of one chain per plan and block.
-template <bool MAXC, bool PER_WAVE>
+template <bool MAXC>
 __global__ __launch_bounds__(kBlock) void k_reduce_update(FusedArgs a)
 {
-    __shared__ double s_part_all[(PER_WAVE ? kBlock / kWave : 1) * kBlkMaxSlots];
+    __shared__ double s_part[kBlkMaxSlots];
+    a.choice = of_plan(a.choice, a.ps.row);
+    a.choice2 = of_plan(a.choice2, a.ps.state);
+    a.demand1n = of_plan(a.demand1n, a.ps.state);
+    a.demand2 = of_plan(a.demand2, a.ps.state);
+    a.len = of_plan(a.len, a.ps.state);
+    a.price = of_plan(a.price, a.ps.state);
+    a.S = of_plan(a.S, a.ps.state);
+    a.scalars = of_plan(a.scalars, a.ps.state);
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
-    const int plan = PER_WAVE ? static_cast<int>(blockIdx.y) * (kBlock / kWave) + wave
-                              : static_cast<int>(blockIdx.y);
-    if (PER_WAVE && plan >= a.n_plans) return;      // the waves of such a workgroup never meet
-    double *s_part = s_part_all + (PER_WAVE ? wave * kBlkMaxSlots : 0);
-    a.choice = of_plan_at(a.choice, a.ps.row, plan);
-    a.choice2 = of_plan_at(a.choice2, a.ps.state, plan);
-    a.demand1n = of_plan_at(a.demand1n, a.ps.state, plan);
-    a.demand2 = of_plan_at(a.demand2, a.ps.state, plan);
-    a.len = of_plan_at(a.len, a.ps.state, plan);
-    a.price = of_plan_at(a.price, a.ps.state, plan);
-    a.S = of_plan_at(a.S, a.ps.state, plan);
-    a.scalars = of_plan_at(a.scalars, a.ps.state, plan);
     const int b = blockIdx.x;
     const int4 d4 = *reinterpret_cast<const int4 *>(a.blk_desc + 8 * b);
     const int i0 = d4.x, i1 = d4.y;             // positions of the block (at least one)
     const int p0 = d4.z, p1 = d4.w;             // its passes
     const int slot0 = a.blk_desc[8 * b + 4];
     const double invrho = a.scalars[0];
-    const int tid = PER_WAVE ? lane : static_cast<int>(threadIdx.x);
-    const int row = tid / kRowLanes;
-    const int l = tid % kRowLanes;
-    constexpr int kRows = (PER_WAVE ? kWave : kBlock) / kRowLanes;
+    const int row = threadIdx.x / kRowLanes;
+    const int l = threadIdx.x % kRowLanes;
+    constexpr int kRows = kBlock / kRowLanes;
     // positions past the end re-read the last one (so that every load is unconditional) and
     // are masked out when the update is applied
     auto fetch = [&](int i) {
@@ -745,21 +735,97 @@ __global__ __launch_bounds__(kBlock) void k_reduce_update(FusedArgs a)
     const LinkState st0 = fetch(i0 + row);
     const LinkState st1 = fetch(i0 + row + kRows);
     reduce_flat_phase<0>(p0, p1, a.pass_first_slot, a.oct_base, a.oct_mask, a.choice, a.demand1n,
-                         a.choice2, a.demand2, s_part, slot0, PER_WAVE ? 0 : wave,
-                         PER_WAVE ? 1 : kBlock / kWave, lane);
-    if constexpr (PER_WAVE) wave_lds_sync();
-    else __syncthreads();
+                         a.choice2, a.demand2, s_part, slot0, wave, kBlock / kWave, lane);
+    __syncthreads();
     apply(i0 + row, st0);
     apply(i0 + row + kRows, st1);
-    for (int ibase = i0 + 2 * kRows; ibase < i1; ibase += kRows)         // uniform, rare
+    for (int ibase = i0 + 2 * kRows; ibase < i1; ibase += kRows)         // block-uniform, rare
         apply(ibase + row, fetch(ibase + row));
     const double m = wave_max(smax);
-    // one maximum of S per wave of the workgroup kernel; the wave kernel fills the block's
-    // other three entries with 0 (S is never negative)
-    if constexpr (PER_WAVE) {
-        if (lane < kBlock / kWave) a.scalars[1 + b * (kBlock / kWave) + lane] = lane == 0 ? m : 0.0;
-    } else {
-        if (lane == 0) a.scalars[1 + b * (kBlock / kWave) + wave] = m;
+    if (lane == 0) a.scalars[1 + b * (kBlock / kWave) + wave] = m;
+}
+
+// The same for batches, U plans per workgroup: the four waves split the passes of the block as
+// in the single-plan kernel, and every wave sums its pass for all U plans at once
+// (reduce_flat_phase_multi), so that one trip to memory serves U plans.  A 16-lane row then
+// applies the update of a link for the U plans in turn.
+template <bool MAXC, int U>
+__global__ __launch_bounds__(kBlock) void k_reduce_update_multi(FusedArgs a)
+{
+    __shared__ double s_part_all[U * kBlkMaxSlots];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x >> 6;
+    const uint8_t *choice[U], *choice2[U];
+    const double *demand1n[U], *demand2[U];
+    double *s_part[U], *len[U], *price[U], *S[U], *scalars[U];
+    bool live[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int want = static_cast<int>(blockIdx.y) * U + u;
+        live[u] = want < a.n_plans;
+        const int plan = live[u] ? want : a.n_plans - 1;       // (repeats an existing plan)
+        choice[u] = of_plan_at(a.choice, a.ps.row, plan);
+        choice2[u] = of_plan_at(a.choice2, a.ps.state, plan);
+        demand1n[u] = of_plan_at(a.demand1n, a.ps.state, plan);
+        demand2[u] = of_plan_at(a.demand2, a.ps.state, plan);
+        len[u] = of_plan_at(a.len, a.ps.state, plan);
+        price[u] = of_plan_at(a.price, a.ps.state, plan);
+        S[u] = of_plan_at(a.S, a.ps.state, plan);
+        scalars[u] = of_plan_at(a.scalars, a.ps.state, plan);
+        s_part[u] = s_part_all + u * kBlkMaxSlots;
+    }
+    const int b = blockIdx.x;
+    const int4 d4 = *reinterpret_cast<const int4 *>(a.blk_desc + 8 * b);
+    const int i0 = d4.x, i1 = d4.y;             // positions of the block (at least one)
+    const int p0 = d4.z, p1 = d4.w;             // its passes
+    const int slot0 = a.blk_desc[8 * b + 4];
+    const int row = threadIdx.x / kRowLanes;
+    const int l = threadIdx.x % kRowLanes;
+    constexpr int kRows = kBlock / kRowLanes;
+    double invrho[U], smax[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        invrho[u] = scalars[u][0];
+        smax[u] = 0.0;
+    }
+    reduce_flat_phase_multi<U>(p0, p1, a.pass_first_slot, a.oct_base, a.oct_mask, choice, demand1n,
+                               choice2, demand2, s_part, slot0, wave, kBlock / kWave, lane);
+    __syncthreads();
+    for (int ibase = i0; ibase < i1; ibase += kRows) {                  // block-uniform
+        const int i = ibase + row;
+        const bool valid = i < i1;
+        const int ic_i = valid ? i : i1 - 1;
+        const int e = a.pos_link[ic_i];
+        const int c0 = a.pos_slot_ptr[ic_i] - slot0;
+        const int c1 = valid ? a.pos_slot_ptr[ic_i + 1] - slot0 : c0;
+        const double ic = a.invcap_pos[ic_i];
+        double s_old[U], l_old[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            s_old[u] = S[u][ic_i];
+            l_old[u] = len[u][ic_i];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const double load = row_partial_sum(c0, c1, l, s_part[u]);
+            if (valid && l == 0 && live[u]) {
+                const double uu = load * ic;
+                const double s_new = s_old[u] + uu;
+                S[u][i] = s_new;
+                const double g = uu * invrho[u];
+                const double t1 = a.eps * g;
+                const double t2 = 1.0 + t1;
+                const double ln = l_old[u] * t2;
+                len[u][i] = ln;
+                price[u][e] = MAXC ? ln : ln * ic;
+                smax[u] = fmax(smax[u], s_new);
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const double m = wave_max(smax[u]);
+        if (lane == 0 && live[u]) scalars[u][1 + b * (kBlock / kWave) + wave] = m;
     }
 }
 
@@ -1225,22 +1291,23 @@ void launch_reduce_update(const DeviceTopo &t, const uint8_t *choice, const doub
     a.eps = eps;
     a.ps = strides_of(t);
     a.n_plans = t.batch;
-    constexpr int kPlansPerBlock = kBlock / kWave;
-    if (t.batch >= kPlansPerBlock) {
-        // batches: a wave per plan and link block
+    constexpr int kPlansPerBlock = 4;
+    if (t.batch >= kPlansPerBlock && t.batch_kernel == 0) {
+        // batches: four plans per workgroup, their loads in flight together
         const dim3 grid(t.n_blocks, (t.batch + kPlansPerBlock - 1) / kPlansPerBlock);
         if (t.cost_max)
-            hipLaunchKernelGGL((k_reduce_update<true, true>), grid, dim3(kBlock), 0, s, a);
+            hipLaunchKernelGGL((k_reduce_update_multi<true, kPlansPerBlock>), grid, dim3(kBlock), 0,
+                               s, a);
         else
-            hipLaunchKernelGGL((k_reduce_update<false, true>), grid, dim3(kBlock), 0, s, a);
+            hipLaunchKernelGGL((k_reduce_update_multi<false, kPlansPerBlock>), grid, dim3(kBlock),
+                               0, s, a);
         return;
     }
     if (t.cost_max)
-        hipLaunchKernelGGL((k_reduce_update<true, false>), dim3(t.n_blocks, t.batch), dim3(kBlock),
-                           0, s, a);
+        hipLaunchKernelGGL(k_reduce_update<true>, dim3(t.n_blocks, t.batch), dim3(kBlock), 0, s, a);
     else
-        hipLaunchKernelGGL((k_reduce_update<false, false>), dim3(t.n_blocks, t.batch),
-                           dim3(kBlock), 0, s, a);
+        hipLaunchKernelGGL(k_reduce_update<false>, dim3(t.n_blocks, t.batch), dim3(kBlock), 0, s,
+                           a);
 }
 
 void launch_epilogue(const DeviceTopo &t, int32_t iters, const uint32_t *count, double *splits,

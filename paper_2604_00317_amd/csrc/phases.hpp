@@ -341,6 +341,80 @@ __device__ __forceinline__ void reduce_flat_phase(
     }
 }
 
+// The octet part for U plans of a batch at once: the octets of a pass (base words, masks, slot
+// numbers) are the same for every plan, only the choices and the demands differ.  A lane
+// fetches them for all U plans together -- U times the loads in flight for one trip to memory --
+// and then sums plan after plan with the arithmetic of reduce_flat_phase (the same additions in
+// the same order, so every plan gets the bits it would get alone).  choice, demand1n, choice2,
+// demand2 and partial are arrays of U pointers; a plan that does not exist repeats the
+// pointers of one that does (its sums are computed and stored twice, which is harmless).
+template <int U>
+__device__ __forceinline__ void reduce_flat_phase_multi(
+    int pass_begin, int pass_end, const int32_t *__restrict__ pass_first_slot,
+    const uint32_t *__restrict__ oct_base, const uint32_t *__restrict__ oct_mask,
+    const uint8_t *const (&choice)[U], const double *const (&demand1n)[U],
+    const uint8_t *const (&choice2)[U], const double *const (&demand2)[U],
+    double *const (&partial)[U], int slot_base, int wave, int n_waves, int lane)
+{
+    const int first = pass_begin + wave;
+    if (first >= pass_end) return;
+    const int last = pass_end - 1;
+    const u32x4 *masks = reinterpret_cast<const u32x4 *>(oct_mask);
+    uint32_t bw = layout_load(oct_base + size_t(first) * kWave + lane);
+    u32x4 m0 = layout_load(masks + size_t(first) * 128 + lane);
+    u32x4 m1 = layout_load(masks + size_t(first) * 128 + 64 + lane);
+    for (int pass = first; pass < pass_end; pass += n_waves) {     // wave-uniform
+        const bool sig = (bw & kOctSigma) != 0u;
+        const int base = static_cast<int>(bw & ~3u);
+        uint2 ch[U];
+        u32x4 q[U][4];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            ch[u] = *reinterpret_cast<const uint2 *>((sig ? choice2[u] : choice[u]) + base);
+            const u32x4 *dq =
+                reinterpret_cast<const u32x4 *>((sig ? demand2[u] : demand1n[u]) + base);
+            q[u][0] = dq[0];
+            q[u][1] = dq[1];
+            q[u][2] = dq[2];
+            q[u][3] = dq[3];
+        }
+        const int first_slot = pass_first_slot[pass];
+        const uint32_t flagword = bw;
+        const uint32_t mk[8] = {m0.x, m0.y, m0.z, m0.w, m1.x, m1.y, m1.z, m1.w};
+        // the next pass of this wave
+        const int np = pass + n_waves < last ? pass + n_waves : last;
+        bw = layout_load(oct_base + size_t(np) * kWave + lane);
+        m0 = layout_load(masks + size_t(np) * 128 + lane);
+        m1 = layout_load(masks + size_t(np) * 128 + 64 + lane);
+        const unsigned long long heads = __ballot((flagword & kOctNewSlot) != 0u);
+        const unsigned long long upto = heads & (~0ull >> (63 - lane));
+        const int start = 63 - __clzll(static_cast<long long>(upto));
+        const bool tail = lane == kWave - 1 || ((heads >> (lane + 1)) & 1ull) != 0ull;
+        const int slot = first_slot - slot_base + __popcll(upto) - 1;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const double dm[8] = {
+                __hiloint2double(int(q[u][0].y), int(q[u][0].x)),
+                __hiloint2double(int(q[u][0].w), int(q[u][0].z)),
+                __hiloint2double(int(q[u][1].y), int(q[u][1].x)),
+                __hiloint2double(int(q[u][1].w), int(q[u][1].z)),
+                __hiloint2double(int(q[u][2].y), int(q[u][2].x)),
+                __hiloint2double(int(q[u][2].w), int(q[u][2].z)),
+                __hiloint2double(int(q[u][3].y), int(q[u][3].x)),
+                __hiloint2double(int(q[u][3].w), int(q[u][3].z))};
+            double acc = 0.0;
+#pragma unroll
+            for (int sl = 0; sl < 8; ++sl) {
+                const uint32_t c8 = ((sl < 4 ? ch[u].x : ch[u].y) >> (8 * (sl & 3))) & 31u;
+                const uint32_t h = (mk[sl] >> c8) & 1u;
+                acc = __builtin_fma(dm[sl], static_cast<double>(h), acc);
+            }
+            acc = segmented_scan_f64(acc, start, lane);
+            if (tail) partial[u][slot] = acc;
+        }
+    }
+}
+
 // ---- phase B, tile part ---------------------------------------------------------------------
 // A work item is up to kTileRows pieces of one window: kTileIds consecutive commodity numbers
 // (ids, or sigma numbers).  Lane c owns column c, the commodities window + 8c .. + 7: it loads

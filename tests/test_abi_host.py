@@ -68,7 +68,7 @@ def test_create_rejects_malformed_input_before_any_device_call():
                                  case["n_paths"], case["lp"], case["pl"])
         assert st == B.NIMBLE_ERR_INVALID, (case, st, msg)
         assert msg
-    st, _ = _create_status(lib, 2, [1e9, 2e9], 1, [0, 2], 2, [0, 1, 2], [0, 1], flags=8)
+    st, _ = _create_status(lib, 2, [1e9, 2e9], 1, [0, 2], 2, [0, 1, 2], [0, 1], flags=8)   # unknown bit
     assert st == B.NIMBLE_ERR_INVALID
     # more than 127 candidates for one commodity is a documented limit
     n = 128

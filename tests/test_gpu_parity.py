@@ -118,9 +118,11 @@ def _batch_traffic(w, n):
                                  {"NIMBLE_TUNE_TILES": "1", "NIMBLE_TUNE_TILE_MIN_ITEMS": "24"},
                                  {"NIMBLE_TUNE_RECORD_DICT": "1"},
                                  {"NIMBLE_TUNE_RECORD_LANE_MAJOR": "0"},
-                                 {"NIMBLE_TUNE_NO_RECORDS": "1"}],
+                                 {"NIMBLE_TUNE_NO_RECORDS": "1"},
+                                 {"NIMBLE_TUNE_BATCH_KERNEL": "1"}],
                          ids=["default", "counters", "separate-update", "tiles", "dictionary",
-                              "record-major", "untiled"])
+                              "record-major", "untiled", "plan-by-plan-kernel"])
+# (one more variant below: the single-plan reduce + update kernel for every plan of a batch)
 def test_streamed_batch_shares_every_launch(oracle_mod, B, monkeypatch, env):
     """A batch of plans on a fabric that is streamed: with room reserved for them the plans of a
     batch run side by side in every kernel launch (one state block and one range of log rows
@@ -136,7 +138,10 @@ def test_streamed_batch_shares_every_launch(oracle_mod, B, monkeypatch, env):
         refs = [oracle_mod.solve(*t.csr(), tr[b], w.eps, iters, flags=flags) for b in range(n)]
         for group in (n, 2):
             print(f"[batch] cfg={cfg} n={n} group={group} env={env}", flush=True)
-            h = B.nimble_topo_create(*t.csr(), flags=flags)
+            # (the 16-node fabric, whole batch in one group: on a topology laid out for batches)
+            h = B.nimble_topo_create(*t.csr(),
+                                     flags=flags | (B.NIMBLE_LAYOUT_BATCH if group == n and cfg == 3
+                                                    else 0))
             try:
                 B.nimble_topo_set_regime(h, B.NIMBLE_REGIME_STREAM)
                 B.nimble_topo_reserve_batch(h, group, iters)
