@@ -63,6 +63,20 @@ nimble_status_t nimble_debug_barrier_probe(int32_t kind, int32_t blocks_per_cu, 
                                            int64_t work_bytes, int32_t *d_out, void *hip_stream);
 
 /*
+ * Test helpers for the allocation-failure paths.  nimble_debug_fail_allocation(n): of the
+ * device allocations the library makes from now on, the one after the next n fails as if the
+ * device were out of memory (n = 0: the very next one; -1 switches the hook off; it switches
+ * itself off after it has fired).  nimble_debug_fail_host_allocation(): the next
+ * nimble_topo_create fails in its host-side build as if the host were out of memory.
+ * nimble_debug_live_allocations(): device allocations of the library that have not been freed.
+ * A call that fails this way returns NIMBLE_ERR_ALLOC and leaves nothing allocated that was
+ * not allocated before it.
+ */
+nimble_status_t nimble_debug_fail_allocation(int32_t nth);
+void nimble_debug_fail_host_allocation(void);
+int64_t nimble_debug_live_allocations(void);
+
+/*
  * Test helper for the persistent regime: every grid-wide barrier of that kernel waits at most
  * `polls` polls of its arrival counter (default 2^22, about a second).  When a wait expires the
  * solve is abandoned -- every workgroup leaves the kernel at its next poll, d_splits is left

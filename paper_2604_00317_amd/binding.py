@@ -34,7 +34,8 @@ EXPORTS = [
     "nimble_host_build_reverse_streaming", "nimble_topo_resident_in_registers",
     "nimble_debug_stream_read", "nimble_topo_reserve", "nimble_host_resident_kernel",
     "nimble_plan_solve_static", "nimble_static_scratch_bytes", "nimble_debug_barrier_probe",
-    "nimble_topo_reserve_batch",
+    "nimble_topo_reserve_batch", "nimble_debug_fail_allocation",
+    "nimble_debug_fail_host_allocation", "nimble_debug_live_allocations",
 ]
 
 _lib = None
@@ -99,6 +100,12 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.nimble_debug_run_phase.argtypes = [vp, i32, i32, vp, vp]
     lib.nimble_debug_barrier_probe.restype = ctypes.c_int
     lib.nimble_debug_barrier_probe.argtypes = [i32, i32, i32, i32, u32, vp, i64, vp, vp]
+    lib.nimble_debug_fail_allocation.restype = ctypes.c_int
+    lib.nimble_debug_fail_allocation.argtypes = [i32]
+    lib.nimble_debug_fail_host_allocation.restype = None
+    lib.nimble_debug_fail_host_allocation.argtypes = []
+    lib.nimble_debug_live_allocations.restype = i64
+    lib.nimble_debug_live_allocations.argtypes = []
     lib.nimble_debug_stream_read.restype = ctypes.c_int
     lib.nimble_debug_stream_read.argtypes = [vp, i64, i32, vp, vp]
     lib.nimble_debug_set_spin_limit.restype = ctypes.c_int

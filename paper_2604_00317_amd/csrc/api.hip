@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <climits>
 #include <cmath>
 #include <cstdio>
@@ -45,6 +46,33 @@ nimble_status_t fail_hip(hipError_t e, const char *what)
 {
     g_last_error = std::string(what) + ": " + hipGetErrorString(e);
     return NIMBLE_ERR_HIP;
+}
+
+// Every device allocation of the library goes through these two, so that a test can make the
+// n-th one fail (nimble_debug_fail_allocation) and can count what is still allocated.
+std::atomic<int32_t> g_fail_alloc_in{-1};     // allocations until one fails; -1: none does
+std::atomic<int64_t> g_live_allocs{0};
+std::atomic<int32_t> g_fail_host_alloc{0};    // the next topology build throws std::bad_alloc
+
+hipError_t dev_malloc(void **p, size_t bytes)
+{
+    int32_t left = g_fail_alloc_in.load();
+    while (left >= 0 && !g_fail_alloc_in.compare_exchange_weak(left, left - 1)) {
+    }
+    if (left == 0) {
+        *p = nullptr;
+        return hipErrorOutOfMemory;
+    }
+    const hipError_t e = hipMalloc(p, bytes);
+    if (e == hipSuccess) g_live_allocs.fetch_add(1);
+    return e;
+}
+
+void dev_free(void *p)
+{
+    if (!p) return;
+    (void)hipFree(p);
+    g_live_allocs.fetch_sub(1);
 }
 
 // Device address of `scratch` on every device, resolved once per device with that device
@@ -109,7 +137,7 @@ template <typename T>
 hipError_t upload(nimble_topo *t, const T *host, size_t n, const T **dev)
 {
     void *p = nullptr;
-    hipError_t e = hipMalloc(&p, (n ? n : 1) * sizeof(T));
+    hipError_t e = dev_malloc(&p, (n ? n : 1) * sizeof(T));
     if (e != hipSuccess) return e;
     t->allocs.push_back(p);
     if (n) {
@@ -124,7 +152,7 @@ template <typename T>
 hipError_t allocate(nimble_topo *t, size_t n, T **dev)
 {
     void *p = nullptr;
-    hipError_t e = hipMalloc(&p, (n ? n : 1) * sizeof(T));
+    hipError_t e = dev_malloc(&p, (n ? n : 1) * sizeof(T));
     if (e != hipSuccess) return e;
     t->allocs.push_back(p);
     *dev = static_cast<T *>(p);
@@ -133,15 +161,15 @@ hipError_t allocate(nimble_topo *t, size_t n, T **dev)
 
 void release(nimble_topo *t)
 {
-    for (void *p : t->allocs) (void)hipFree(p);
+    for (void *p : t->allocs) dev_free(p);
     t->allocs.clear();
-    if (t->choice_log) (void)hipFree(t->choice_log);
+    if (t->choice_log) dev_free(t->choice_log);
     t->choice_log = nullptr;
     t->log_rows = 0;
-    if (t->state) (void)hipFree(t->state);
+    if (t->state) dev_free(t->state);
     t->state = nullptr;
     t->state_plans = 0;
-    if (t->ad.sigma_log) (void)hipFree(t->ad.sigma_log);
+    if (t->ad.sigma_log) dev_free(t->ad.sigma_log);
     t->ad.sigma_log = nullptr;
     t->ad_sigma_rows = 0;
 }
@@ -168,11 +196,11 @@ nimble_status_t grow_choice_log(nimble_topo *t, int32_t iters)
     const size_t bytes = stride * static_cast<size_t>(iters);
     if (bytes > kChoiceLogCap)
         return fail(NIMBLE_ERR_RANGE, "the choice log of that many iterations exceeds 1 GiB");
-    if (t->choice_log) (void)hipFree(t->choice_log);      // waits for work that still uses it
+    if (t->choice_log) dev_free(t->choice_log);      // waits for work that still uses it
     t->choice_log = nullptr;
     t->log_rows = 0;
     void *p = nullptr;
-    if (hipMalloc(&p, bytes) != hipSuccess) {
+    if (dev_malloc(&p, bytes) != hipSuccess) {
         (void)hipGetLastError();
         return fail(NIMBLE_ERR_ALLOC, "the choice log cannot be allocated");
     }
@@ -228,14 +256,14 @@ hipError_t ensure_state_plans(nimble_topo *t, int32_t plans)
     nimble::DeviceTopo &d = t->d;
     const StateLayout L = state_layout(d);
     void *p = nullptr;
-    hipError_t e = hipMalloc(&p, L.bytes * static_cast<size_t>(plans));
+    hipError_t e = dev_malloc(&p, L.bytes * static_cast<size_t>(plans));
     if (e != hipSuccess) return e;
     e = hipMemset(p, 0, L.bytes * static_cast<size_t>(plans));
     if (e != hipSuccess) {
-        (void)hipFree(p);
+        dev_free(p);
         return e;
     }
-    if (t->state) (void)hipFree(t->state);       // waits for work that still uses it
+    if (t->state) dev_free(t->state);       // waits for work that still uses it
     unsigned char *b = static_cast<unsigned char *>(p);
     t->state = b;
     t->state_plans = plans;
@@ -386,6 +414,7 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
         // choices and demands are fetched window by window, which is what bounds a launch that
         // covers many plans (a single plan of a mid-size fabric is faster with link blocks)
         if (flags & NIMBLE_LAYOUT_BATCH) h.tiles = 1;
+        if (g_fail_host_alloc.exchange(0) != 0) throw std::bad_alloc();      // test hook
         nimble::read_layout_options(h);
         nimble::build_host_topo(n_links, cap, n_comm, comm_path_ptr, n_paths, path_link_ptr,
                                 path_links, h);
@@ -918,7 +947,7 @@ nimble_status_t nimble_plan_solve_adaptive(nimble_topo_t *topo, const double *d_
         if (e == hipSuccess) e = allocate(topo, (static_cast<size_t>(d.E) + 255) / 256, &a.block_max_s);
         if (e != hipSuccess) {
             while (topo->allocs.size() > mark) {
-                (void)hipFree(topo->allocs.back());
+                dev_free(topo->allocs.back());
                 topo->allocs.pop_back();
             }
             (void)hipGetLastError();
@@ -928,11 +957,11 @@ nimble_status_t nimble_plan_solve_adaptive(nimble_topo_t *topo, const double *d_
         topo->ad_ready = true;
     }
     if (topo->ad_sigma_rows < max_iters) {
-        if (a.sigma_log) (void)hipFree(a.sigma_log);
+        if (a.sigma_log) dev_free(a.sigma_log);
         a.sigma_log = nullptr;
         topo->ad_sigma_rows = 0;
         void *p = nullptr;
-        if (hipMalloc(&p, sizeof(double) * static_cast<size_t>(max_iters)) != hipSuccess) {
+        if (dev_malloc(&p, sizeof(double) * static_cast<size_t>(max_iters)) != hipSuccess) {
             (void)hipGetLastError();
             return fail(NIMBLE_ERR_ALLOC, "step log of the adaptive solve");
         }
@@ -1062,6 +1091,18 @@ nimble_status_t nimble_debug_barrier_probe(int32_t kind, int32_t blocks_per_cu, 
     if (e != hipSuccess) return fail_hip(e, "cooperative launch (barrier probe)");
     return NIMBLE_OK;
 }
+
+nimble_status_t nimble_debug_fail_allocation(int32_t nth)
+{
+    g_last_error.clear();
+    if (nth < -1) return fail(NIMBLE_ERR_INVALID, "nth must be >= -1");
+    g_fail_alloc_in.store(nth);
+    return NIMBLE_OK;
+}
+
+void nimble_debug_fail_host_allocation(void) { g_fail_host_alloc.store(1); }
+
+int64_t nimble_debug_live_allocations(void) { return g_live_allocs.load(); }
 
 nimble_status_t nimble_debug_stream_read(const void *d_buf, int64_t bytes, int32_t reps,
                                          void *d_sink, void *hip_stream)

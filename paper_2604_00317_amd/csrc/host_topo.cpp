@@ -404,30 +404,13 @@ void build_forward_records(int32_t n_links, int32_t n_comm, const int32_t *comm_
                                path_links, false, t);
 }
 
-void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
-                     const int32_t *comm_path_ptr, int32_t n_paths,
-                     const int32_t *path_link_ptr, const int32_t *path_links,
-                     HostTopo &t)
+// ---- reverse CSR ---------------------------------------------------------------------------
+// The (commodity, window) pairs of every link by a stable counting sort (rev_ptr, rev_pair,
+// rev_rowlen, n_pairs): what the resident kernels walk, and the input of every other layout.
+static void build_reverse_pairs(int32_t n_links, int32_t n_comm, const int32_t *comm_path_ptr,
+                                const int32_t *path_link_ptr, const int32_t *path_links,
+                                HostTopo &t)
 {
-    t.E = n_links;
-    t.K = n_comm;
-    t.P = n_paths;
-    t.nnz = path_link_ptr[n_paths];
-    t.invcap.resize(n_links);
-    for (int32_t e = 0; e < n_links; ++e) t.invcap[e] = 1.0 / cap[e];
-
-    t.pmax = 0;
-    t.lmax = 0;
-    for (int32_t k = 0; k < n_comm; ++k) {
-        int32_t np = comm_path_ptr[k + 1] - comm_path_ptr[k];
-        if (np > t.pmax) t.pmax = np;
-    }
-    for (int32_t p = 0; p < n_paths; ++p) {
-        int32_t l = path_link_ptr[p + 1] - path_link_ptr[p];
-        if (l > t.lmax) t.lmax = l;
-    }
-
-    // ---- reverse CSR of (commodity, window) pairs: stable counting sort by link ---------
     // pass 1 counts the pairs of every link: a new pair starts when the commodity or the
     // window changes with respect to the link's previous incidence (incidences are visited in
     // ascending (commodity, path) order)
@@ -477,7 +460,17 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
             }
         }
 
-    // ---- streaming layout of the reverse rows: flat octets (two numberings) + single pairs --
+}
+
+// ---- streaming layouts of the reverse rows ---------------------------------------------------
+// From the pairs: the second commodity numbering sigma, tiles and strips where rows share
+// windows or octets, the flat octets with their partial-sum slots, chunked single pairs, and the
+// order of the rows (link blocks).  Needs build_reverse_pairs; reads t.tiles, t.tile_min_items,
+// t.tiles_dense_only and t.blk_passes as options.
+static void build_streaming_layout(int32_t n_links, int32_t n_comm, const int32_t *comm_path_ptr,
+                                const int32_t *path_link_ptr, const int32_t *path_links,
+                                HostTopo &t)
+{
     t.oct_base.clear();
     t.oct_mask.clear();
     t.pass_first_slot.clear();
@@ -1030,6 +1023,33 @@ void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
         }
     }
 
+}
+
+void build_host_topo(int32_t n_links, const double *cap, int32_t n_comm,
+                     const int32_t *comm_path_ptr, int32_t n_paths,
+                     const int32_t *path_link_ptr, const int32_t *path_links,
+                     HostTopo &t)
+{
+    t.E = n_links;
+    t.K = n_comm;
+    t.P = n_paths;
+    t.nnz = path_link_ptr[n_paths];
+    t.invcap.resize(n_links);
+    for (int32_t e = 0; e < n_links; ++e) t.invcap[e] = 1.0 / cap[e];
+
+    t.pmax = 0;
+    t.lmax = 0;
+    for (int32_t k = 0; k < n_comm; ++k) {
+        int32_t np = comm_path_ptr[k + 1] - comm_path_ptr[k];
+        if (np > t.pmax) t.pmax = np;
+    }
+    for (int32_t p = 0; p < n_paths; ++p) {
+        int32_t l = path_link_ptr[p + 1] - path_link_ptr[p];
+        if (l > t.lmax) t.lmax = l;
+    }
+
+    build_reverse_pairs(n_links, n_comm, comm_path_ptr, path_link_ptr, path_links, t);
+    build_streaming_layout(n_links, n_comm, comm_path_ptr, path_link_ptr, path_links, t);
     build_forward_records(n_links, n_comm, comm_path_ptr, n_paths, path_link_ptr, path_links, t);
 }
 

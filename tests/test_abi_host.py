@@ -295,3 +295,15 @@ def test_dictionary_of_record_bodies_on_a_large_product_fabric():
     links, path_rec, n_rec = B.nimble_host_records_roundtrip(*args)
     assert n_rec == st["records"] and np.array_equal(links, t.path_links)
     assert np.all(np.diff(path_rec) >= 0) and path_rec[-1] == n_rec - 1
+
+
+def test_host_allocation_failure_is_reported_before_any_device_call():
+    """A topology build that runs out of host memory returns NIMBLE_ERR_ALLOC (forced through the
+    test hook); the next create is unaffected (it fails later, for want of a GPU, or succeeds)."""
+    lib = B.load_library()
+    lib.nimble_debug_fail_host_allocation()
+    st, msg = _create_status(lib, 2, [1e9, 2e9], 1, [0, 2], 2, [0, 1, 2], [0, 1])
+    assert st == B.NIMBLE_ERR_ALLOC and "host" in msg
+    st, _ = _create_status(lib, 2, [1e9, 2e9], 1, [0, 2], 2, [0, 1, 2], [0, 1])
+    assert st in (B.NIMBLE_OK, B.NIMBLE_ERR_HIP)
+    assert lib.nimble_debug_fail_allocation(-2) == B.NIMBLE_ERR_INVALID

@@ -539,6 +539,63 @@ def test_solve_on_side_stream_and_reuse(oracle_mod, B):
         h.close()
 
 
+def test_device_allocation_failures_leave_nothing_behind(oracle_mod, B):
+    """Every device allocation of nimble_topo_create is made to fail in turn (test hook): the
+    call must return NIMBLE_ERR_ALLOC with nothing left allocated, and the first create that is
+    spared must work.  The same for the calls that grow the workspace later."""
+    import ctypes
+    import torch
+    lib = B.load_library()
+    w = W.make_config(1)
+    t = w.topo
+    base = lib.nimble_debug_live_allocations()
+    made = None
+    for n in range(400):
+        assert lib.nimble_debug_fail_allocation(n) == B.NIMBLE_OK
+        try:
+            made = B.nimble_topo_create(*t.csr())
+            break
+        except B.NimbleError as err:
+            assert err.status == B.NIMBLE_ERR_ALLOC, (n, str(err))
+            assert lib.nimble_debug_live_allocations() == base, n
+    lib.nimble_debug_fail_allocation(-1)
+    assert made is not None and n >= 20          # a create makes dozens of allocations
+    try:
+        ref = oracle_mod.solve(*t.csr(), w.traffic, w.eps, 50)
+        splits, lam = B.plan(made, w.traffic, w.eps, 50)
+        assert np.array_equal(splits, ref["splits"]) and lam == ref["lam"]
+        held = lib.nimble_debug_live_allocations()
+        # growing the log, the batch state and the adaptive workspace under failure
+        for call in (lambda: B.nimble_topo_reserve(made, 5000),
+                     lambda: B.nimble_topo_reserve_batch(made, 3, 100)):
+            lib.nimble_debug_fail_allocation(0)
+            with pytest.raises(B.NimbleError) as ei:
+                call()
+            assert ei.value.status == B.NIMBLE_ERR_ALLOC
+            assert lib.nimble_debug_live_allocations() <= held
+            lib.nimble_debug_fail_allocation(-1)
+        d = torch.as_tensor(w.traffic).to("cuda:0")
+        sp = torch.zeros(t.n_paths, dtype=torch.float64, device="cuda:0")
+        la = torch.zeros(1, dtype=torch.float64, device="cuda:0")
+        for n in range(3):
+            before = lib.nimble_debug_live_allocations()
+            lib.nimble_debug_fail_allocation(n)
+            with pytest.raises(B.NimbleError) as ei:
+                B.nimble_plan_solve_adaptive(made, d, w.eps, 200, 10, sp, la)
+            assert ei.value.status == B.NIMBLE_ERR_ALLOC
+            assert lib.nimble_debug_live_allocations() <= before
+            lib.nimble_debug_fail_allocation(-1)
+        # and everything still works afterwards
+        splits, lam = B.plan(made, w.traffic, w.eps, 50)
+        assert np.array_equal(splits, ref["splits"]) and lam == ref["lam"]
+        n_done, lb = B.nimble_plan_solve_adaptive(made, d, w.eps, 200, 10, sp, la)
+        assert n_done > 0
+    finally:
+        lib.nimble_debug_fail_allocation(-1)
+        made.close()
+    assert lib.nimble_debug_live_allocations() == base
+
+
 @pytest.mark.parametrize("kind", [0, 1, 2, 3, 4])
 def test_grid_barrier_probe(B, kind):
     """The barrier probe behind the benchmark's barrier figures: every design either lets the
