@@ -246,8 +246,11 @@ nimble_status_t nimble_plan_solve_warm(nimble_topo_t *topo, const double *d_traf
  *   iters_done   host out: iterations made (0 for all-zero traffic: every pair then stays on
  *                its first candidate)
  *   lower_bound  host out: best LB seen (0 if no check was made)
- * Unlike nimble_plan_solve this call synchronises hip_stream at every check and before it
- * returns.  Always runs the streaming regime; needs the per-iteration choice log of
+ * The stop decision is taken on the device; the host enqueues ahead and follows the device's
+ * progress through two words of pinned memory, so the stream is never synchronised during the
+ * solve (kernels enqueued after the stop return at once).  Unlike nimble_plan_solve the call
+ * waits for the stream before it returns, because iters_done and lower_bound are host outputs,
+ * and it cannot be captured into a graph.  Always runs the streaming regime; needs the per-iteration choice log of
  * max_iters rows and grows it when it is shorter (NIMBLE_ERR_ALLOC if it cannot be allocated,
  * NIMBLE_ERR_RANGE beyond 1 GiB), as well as a workspace of its own on the first call.
  * Bit-identical to the plain CPU definition for integer-valued demands.

@@ -5,6 +5,7 @@
 
 #include <algorithm>
 #include <atomic>
+#include <chrono>
 #include <climits>
 #include <cmath>
 #include <cstdio>
@@ -13,6 +14,7 @@
 #include <mutex>
 #include <new>
 #include <string>
+#include <thread>
 #include <vector>
 
 #include "../../include/nimble_plan.h"
@@ -169,6 +171,9 @@ void release(nimble_topo *t)
     if (t->state) dev_free(t->state);
     t->state = nullptr;
     t->state_plans = 0;
+    if (t->ad.host_words_host) (void)hipHostFree(t->ad.host_words_host);
+    t->ad.host_words_host = nullptr;
+    t->ad.host_words = nullptr;
     if (t->ad.sigma_log) dev_free(t->ad.sigma_log);
     t->ad.sigma_log = nullptr;
     t->ad_sigma_rows = 0;
@@ -943,7 +948,21 @@ nimble_status_t nimble_plan_solve_adaptive(nimble_topo_t *topo, const double *d_
         if (e == hipSuccess) e = allocate(topo, static_cast<size_t>(d.K), &a.term);
         if (e == hipSuccess) e = allocate(topo, n_chunks, &a.chunk);
         if (e == hipSuccess) e = allocate(topo, static_cast<size_t>(d.E), &a.u_pos);
-        if (e == hipSuccess) e = allocate(topo, (static_cast<size_t>(d.E) + 15) / 16, &a.block_max_u);
+        if (e == hipSuccess)
+            e = allocate(topo, std::max((static_cast<size_t>(d.E) + 15) / 16,
+                                        static_cast<size_t>(4) * static_cast<size_t>(d.n_blocks)),
+                         &a.block_max_u);
+        if (e == hipSuccess && !a.host_words_host) {
+            // two words of pinned host memory the device writes and the host polls
+            void *hp = nullptr;
+            e = hipHostMalloc(&hp, 4 * sizeof(int32_t), hipHostMallocMapped);
+            if (e == hipSuccess) {
+                a.host_words_host = static_cast<int32_t *>(hp);
+                void *dp = nullptr;
+                e = hipHostGetDevicePointer(&dp, hp, 0);
+                a.host_words = static_cast<int32_t *>(dp);
+            }
+        }
         if (e == hipSuccess) e = allocate(topo, (static_cast<size_t>(d.E) + 255) / 256, &a.block_max_s);
         if (e != hipSuccess) {
             while (topo->allocs.size() > mark) {
@@ -975,26 +994,56 @@ nimble_status_t nimble_plan_solve_adaptive(nimble_topo_t *topo, const double *d_
     if (st != NIMBLE_OK) return st;
     topo->last_regime = NIMBLE_REGIME_STREAM;
     const double gap = (1.0 + eps) * (1.0 + eps);
+    // The device takes the stop decision and publishes it, with the number of checks made, in
+    // pinned host memory.  The host enqueues ahead without ever synchronising the stream; it
+    // only keeps within kAhead checks of the device, so that after the stop little is left in
+    // the queue -- and what is left returns at once (every kernel of an iteration looks at the
+    // stop word first).
+    volatile int32_t *hw = a.host_words_host;
+    hw[0] = 0;
+    hw[1] = 0;
+    nimble::DeviceTopo dd = d;
+    dd.stop_flag = a.flags;
+    const int32_t ahead = std::max(4, 128 / check_every);
     nimble::launch_ad_reset(a, s);
-    nimble::launch_init(d, d_traffic, nullptr, s);
-    int32_t flags_host[2] = {0, 0};
+    nimble::launch_init(dd, d_traffic, nullptr, s);
+    int32_t checks = 0;
+    bool stalled = false;
     for (int32_t t = 0; t < max_iters; ++t) {
-        uint8_t *row = topo->choice_log + topo->log_stride * static_cast<size_t>(t);
-        nimble::launch_argmin(d, row, nullptr, s);
         const bool check = ((t + 1) % check_every) == 0 && !d.cost_max;
-        if (check) nimble::launch_ad_bound(d, a, row, d_traffic, s);
-        nimble::launch_load_reduce(d, row, d_traffic, s);
-        nimble::launch_ad_update(d, a, eps, s);
-        if (check) {
-            // the stop decision is taken on the device; the host looks at it here
-            nimble::launch_ad_lambda(d, a, gap, true, s);
-            e = hipMemcpyAsync(flags_host, a.flags, sizeof(flags_host), hipMemcpyDeviceToHost, s);
-            if (e == hipSuccess) e = hipStreamSynchronize(s);
-            if (e != hipSuccess) return fail_hip(e, "adaptive solve (stop test)");
-            if (flags_host[0]) break;
+        if (check && checks >= ahead) {
+            // wait (on the host only) until the device is within `ahead` checks
+            const auto t0 = std::chrono::steady_clock::now();
+            while (__atomic_load_n(&hw[1], __ATOMIC_ACQUIRE) < checks - ahead + 1 &&
+                   __atomic_load_n(&hw[0], __ATOMIC_ACQUIRE) == 0) {
+                if (std::chrono::steady_clock::now() - t0 > std::chrono::seconds(30)) {
+                    stalled = true;
+                    break;
+                }
+                std::this_thread::yield();
+            }
+            if (stalled) break;
         }
+        if (__atomic_load_n(&hw[0], __ATOMIC_ACQUIRE) != 0) break;       // the device has stopped
+        uint8_t *row = topo->choice_log + topo->log_stride * static_cast<size_t>(t);
+        nimble::launch_argmin(dd, row, nullptr, s);
+        if (check) nimble::launch_ad_bound(dd, a, row, d_traffic, s);
+        if (d.n_blocks > 0) {
+            // link blocks: normalised loads in one launch, then the step
+            const int n_u = nimble::launch_reduce_u(dd, row, a.u_pos, a.block_max_u, s);
+            nimble::launch_ad_apply(dd, a, eps, n_u, s);
+        } else {
+            nimble::launch_load_reduce(dd, row, d_traffic, s);
+            nimble::launch_ad_update(dd, a, eps, s);
+        }
+        if (check) nimble::launch_ad_lambda(dd, a, gap, ++checks, s);
     }
-    nimble::launch_ad_lambda(d, a, gap, false, s);
+    if (stalled) {
+        (void)hipStreamSynchronize(s);
+        return fail(NIMBLE_ERR_HIP, "adaptive solve: the device made no progress for 30 s");
+    }
+    int32_t flags_host[2] = {0, 0};
+    nimble::launch_ad_lambda(d, a, gap, 0, s);
     e = nimble::launch_ad_histogram(d, a, topo->choice_log, topo->log_stride, d_splits, d_lambda, s);
     if (e != hipSuccess) return fail_hip(e, "kernel launch (adaptive regime)");
     double ascal_host[4] = {0, 0, 0, 0};

@@ -93,6 +93,7 @@ struct DeviceTopo {
     // their state blocks and between their choice rows; 1 and anything for a single plan
     int32_t batch;
     size_t state_stride, row_stride;
+    const int32_t *stop_flag;  // adaptive solve: kernels return at once when this word is set
     int32_t batch_kernel;      // tuning: 0 four plans per workgroup in the fused reduce + update
                                // of a batch, 1 the single-plan kernel for every plan
     int32_t n_update_blocks;
@@ -165,6 +166,9 @@ struct AdaptiveState {
     double *block_max_s;       // [ceil(E/256)]
     double *sigma_log;         // [max_iters]
     const int32_t *pos_of_link;  // [E] position of every link in the flat order
+    int32_t *host_words;       // pinned host memory the device writes: [0] stopped, [1] checks
+                               // made (the device's address of it)
+    int32_t *host_words_host;  // the host's address of the same words
 };
 void launch_ad_reset(const AdaptiveState &a, hipStream_t s);
 // the weak-duality bound under the prices the choices in `choice` were made with
@@ -172,8 +176,15 @@ void launch_ad_bound(const DeviceTopo &t, const AdaptiveState &a, const uint8_t 
                      const double *demand, hipStream_t s);
 // u, sigma, S, len, price, W from the slot partials of the reduce
 void launch_ad_update(const DeviceTopo &t, const AdaptiveState &a, double eps, hipStream_t s);
-// lambda = max S / W; with `check` also the best bound and the stop test
-void launch_ad_lambda(const DeviceTopo &t, const AdaptiveState &a, double gap, bool check,
+// link-block fabrics: reduce to normalised loads in one launch (u by position and one maximum
+// per wave; returns the number of maxima), then the step from those
+int launch_reduce_u(const DeviceTopo &t, const uint8_t *choice, double *u_pos, double *block_max_u,
+                    hipStream_t s);
+void launch_ad_apply(const DeviceTopo &t, const AdaptiveState &a, double eps, int n_u_blocks,
+                     hipStream_t s);
+// lambda = max S / W; with `check` (the number of this check, from 1; 0: none) also the best
+// bound and the stop test, both published to a.host_words
+void launch_ad_lambda(const DeviceTopo &t, const AdaptiveState &a, double gap, int check,
                       hipStream_t s);
 hipError_t launch_ad_histogram(const DeviceTopo &t, const AdaptiveState &a, const uint8_t *log,
                                size_t stride, double *splits, double *lambda, hipStream_t s);

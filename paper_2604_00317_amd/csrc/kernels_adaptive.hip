@@ -181,10 +181,20 @@ __global__ __launch_bounds__(kAdBlock) void k_ad_lambda(int n_s_blocks,
                                                         const double *__restrict__ block_max_s,
                                                         double gap, int check,
                                                         int32_t *__restrict__ flags,
-                                                        double *__restrict__ ascal)
+                                                        double *__restrict__ ascal,
+                                                        int32_t *host_words)
 {
     __shared__ double red[16];
-    if (flags[0] && check) return;                    // already stopped (no traffic)
+    // what the host reads while it enqueues ahead: whether the solve has stopped and how many
+    // checks have been made (written to pinned host memory at system scope)
+    auto publish = [&]() {
+        __hip_atomic_store(host_words, flags[0], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        __hip_atomic_store(host_words + 1, check, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+    };
+    if (flags[0] && check) {                          // already stopped
+        if (threadIdx.x == 0) publish();
+        return;
+    }
     double m = 0.0;
     for (int b = threadIdx.x; b < n_s_blocks; b += kAdBlock) m = fmax(m, block_max_s[b]);
     const double smax = block_max(m, red);
@@ -196,6 +206,7 @@ __global__ __launch_bounds__(kAdBlock) void k_ad_lambda(int n_s_blocks,
         if (ascal[1] > ascal[2]) ascal[2] = ascal[1];
         const double bound = gap * ascal[2];
         if (lam <= bound) flags[0] = 1;
+        publish();
     }
 }
 
@@ -286,23 +297,29 @@ void launch_ad_update(const DeviceTopo &t, const AdaptiveState &a, double eps, h
     else
         hipLaunchKernelGGL(k_ad_u<16>, dim3(gu), dim3(kAdBlock), 0, s, t.E, t.pos_slot_ptr,
                            t.pos_xslot, t.partial, t.invcap_pos, a.flags, a.u_pos, a.block_max_u);
+    launch_ad_apply(t, a, eps, gu, s);
+}
+
+void launch_ad_apply(const DeviceTopo &t, const AdaptiveState &a, double eps, int n_u_blocks,
+                     hipStream_t s)
+{
     const int ga = (t.E + kAdBlock - 1) / kAdBlock;
     if (t.cost_max)
-        hipLaunchKernelGGL(k_ad_apply<true>, dim3(ga), dim3(kAdBlock), 0, s, t.E, eps, gu,
+        hipLaunchKernelGGL(k_ad_apply<true>, dim3(ga), dim3(kAdBlock), 0, s, t.E, eps, n_u_blocks,
                            a.block_max_u, a.u_pos, t.invcap_pos, t.pos_link, t.len, t.price, t.S,
                            a.flags, a.ascal, a.sigma_log, a.block_max_s);
     else
-        hipLaunchKernelGGL(k_ad_apply<false>, dim3(ga), dim3(kAdBlock), 0, s, t.E, eps, gu,
+        hipLaunchKernelGGL(k_ad_apply<false>, dim3(ga), dim3(kAdBlock), 0, s, t.E, eps, n_u_blocks,
                            a.block_max_u, a.u_pos, t.invcap_pos, t.pos_link, t.len, t.price, t.S,
                            a.flags, a.ascal, a.sigma_log, a.block_max_s);
 }
 
-void launch_ad_lambda(const DeviceTopo &t, const AdaptiveState &a, double gap, bool check,
+void launch_ad_lambda(const DeviceTopo &t, const AdaptiveState &a, double gap, int check,
                       hipStream_t s)
 {
     const int ga = (t.E + kAdBlock - 1) / kAdBlock;
-    hipLaunchKernelGGL(k_ad_lambda, dim3(1), dim3(kAdBlock), 0, s, ga, a.block_max_s, gap,
-                       check ? 1 : 0, a.flags, a.ascal);
+    hipLaunchKernelGGL(k_ad_lambda, dim3(1), dim3(kAdBlock), 0, s, ga, a.block_max_s, gap, check,
+                       a.flags, a.ascal, a.host_words);
 }
 
 hipError_t launch_ad_histogram(const DeviceTopo &t, const AdaptiveState &a, const uint8_t *log,

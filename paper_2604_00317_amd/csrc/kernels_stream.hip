@@ -86,6 +86,7 @@ __global__ __launch_bounds__(kBlock) void k_argmin(int K, const int32_t *__restr
                                                    const int32_t *__restrict__ sigma,
                                                    uint8_t *__restrict__ choice2, PlanStrides ps)
 {
+    if (stopped(ps)) return;
     price = of_plan(price, ps.state);
     choice = of_plan(choice, ps.row);
     count = of_plan(count, ps.state);
@@ -147,6 +148,7 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records,
                                                       uint8_t *__restrict__ choice2,
                                                       PlanStrides ps)
 {
+    if (stopped(ps)) return;
     price = of_plan(price, ps.state);
     choice = of_plan(choice, ps.row);
     count = of_plan(count, ps.state);
@@ -312,6 +314,7 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records,
 {
     static_assert(L >= 2 && L <= 16 && S <= kRecLaneSteps,
                   "lane-major records: 2 to 16 lanes per commodity, five steps");
+    if (stopped(ps)) return;
     price = of_plan(price, ps.state);
     choice = of_plan(choice, ps.row);
     count = of_plan(count, ps.state);
@@ -475,6 +478,7 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recd(int n_chunks, 
 {
     static_assert(L >= 2 && L <= 16 && S <= kRecLaneSteps,
                   "lane-major records: 2 to 16 lanes per commodity, five steps");
+    if (stopped(ps)) return;
     price = of_plan(price, ps.state);
     choice = of_plan(choice, ps.row);
     count = of_plan(count, ps.state);
@@ -621,6 +625,7 @@ struct ReduceArgs {
 template <int MODE>
 __global__ __launch_bounds__(kBlock) void k_load_reduce(ReduceArgs a)
 {
+    if (stopped(a.ps)) return;
     a.demand1n = of_plan(a.demand1n, a.ps.state);
     a.demand1t = of_plan(a.demand1t, a.ps.state);
     a.demand2t = of_plan(a.demand2t, a.ps.state);
@@ -672,6 +677,7 @@ struct FusedArgs {
     double eps;
     PlanStrides ps;
     int n_plans;
+    double *u_pos, *block_max_u;     // adaptive step only
 };
 
 struct LinkState {
@@ -679,10 +685,14 @@ struct LinkState {
     double ic, s, l;
 };
 
-template <bool MAXC>
+// ONLY_U (adaptive step): the update cannot be applied before the largest normalised load of
+// the whole fabric is known, so the kernel stops at u = load / cap (by position, to a.u_pos) and
+// leaves every wave's maximum of u in a.block_max_u for the kernel that applies the step.
+template <bool MAXC, bool ONLY_U = false>
 __global__ __launch_bounds__(kBlock) void k_reduce_update(FusedArgs a)
 {
     __shared__ double s_part[kBlkMaxSlots];
+    if (stopped(a.ps)) return;
     a.choice = of_plan(a.choice, a.ps.row);
     a.choice2 = of_plan(a.choice2, a.ps.state);
     a.demand1n = of_plan(a.demand1n, a.ps.state);
@@ -721,15 +731,20 @@ __global__ __launch_bounds__(kBlock) void k_reduce_update(FusedArgs a)
         const double load = row_partial_sum(st.c0, valid ? st.c1 : st.c0, l, s_part);
         if (valid && l == 0) {
             const double u = load * st.ic;
-            const double s_new = st.s + u;
-            a.S[i] = s_new;
-            const double g = u * invrho;
-            const double t1 = a.eps * g;
-            const double t2 = 1.0 + t1;
-            const double ln = st.l * t2;
-            a.len[i] = ln;
-            a.price[st.e] = MAXC ? ln : ln * st.ic;
-            smax = fmax(smax, s_new);
+            if constexpr (ONLY_U) {
+                a.u_pos[i] = u;
+                smax = fmax(smax, u);
+            } else {
+                const double s_new = st.s + u;
+                a.S[i] = s_new;
+                const double g = u * invrho;
+                const double t1 = a.eps * g;
+                const double t2 = 1.0 + t1;
+                const double ln = st.l * t2;
+                a.len[i] = ln;
+                a.price[st.e] = MAXC ? ln : ln * st.ic;
+                smax = fmax(smax, s_new);
+            }
         }
     };
     const LinkState st0 = fetch(i0 + row);
@@ -742,7 +757,10 @@ __global__ __launch_bounds__(kBlock) void k_reduce_update(FusedArgs a)
     for (int ibase = i0 + 2 * kRows; ibase < i1; ibase += kRows)         // block-uniform, rare
         apply(ibase + row, fetch(ibase + row));
     const double m = wave_max(smax);
-    if (lane == 0) a.scalars[1 + b * (kBlock / kWave) + wave] = m;
+    if (lane == 0) {
+        if constexpr (ONLY_U) a.block_max_u[b * (kBlock / kWave) + wave] = m;
+        else a.scalars[1 + b * (kBlock / kWave) + wave] = m;
+    }
 }
 
 // The same for batches, U plans per workgroup: the four waves split the passes of the block as
@@ -951,6 +969,7 @@ inline PlanStrides strides_of(const DeviceTopo &t)
     ps.row = t.row_stride;
     ps.demand = sizeof(double) * static_cast<size_t>(t.K);
     ps.splits = sizeof(double) * static_cast<size_t>(t.P);
+    ps.stop = t.stop_flag;
     return ps;
 }
 
@@ -1291,6 +1310,8 @@ void launch_reduce_update(const DeviceTopo &t, const uint8_t *choice, const doub
     a.eps = eps;
     a.ps = strides_of(t);
     a.n_plans = t.batch;
+    a.u_pos = nullptr;
+    a.block_max_u = nullptr;
     constexpr int kPlansPerBlock = 4;
     if (t.batch >= kPlansPerBlock && t.batch_kernel == 0) {
         // batches: four plans per workgroup, their loads in flight together
@@ -1308,6 +1329,34 @@ void launch_reduce_update(const DeviceTopo &t, const uint8_t *choice, const doub
     else
         hipLaunchKernelGGL(k_reduce_update<false>, dim3(t.n_blocks, t.batch), dim3(kBlock), 0, s,
                            a);
+}
+
+int launch_reduce_u(const DeviceTopo &t, const uint8_t *choice, double *u_pos,
+                    double *block_max_u, hipStream_t s)
+{
+    FusedArgs a;
+    a.blk_desc = t.blk_desc;
+    a.pass_first_slot = t.pass_first_slot;
+    a.oct_base = t.oct_base;
+    a.oct_mask = t.oct_mask;
+    a.pos_link = t.pos_link;
+    a.pos_slot_ptr = t.pos_slot_ptr;
+    a.choice = choice;
+    a.choice2 = t.choice2;
+    a.demand1n = t.demand1n;
+    a.demand2 = t.demand2;
+    a.invcap_pos = t.invcap_pos;
+    a.len = t.len;
+    a.price = t.price;
+    a.S = t.S;
+    a.scalars = t.scalars;
+    a.eps = 0.0;
+    a.ps = strides_of(t);
+    a.n_plans = 1;
+    a.u_pos = u_pos;
+    a.block_max_u = block_max_u;
+    hipLaunchKernelGGL((k_reduce_update<false, true>), dim3(t.n_blocks), dim3(kBlock), 0, s, a);
+    return t.n_blocks * (kBlock / kWave);
 }
 
 void launch_epilogue(const DeviceTopo &t, int32_t iters, const uint32_t *count, double *splits,

@@ -50,7 +50,15 @@ struct PlanStrides {
     size_t row;        // between the choice rows of one iteration
     size_t demand;     // between the caller's demand vectors
     size_t splits;     // between the caller's split vectors
+    // (not a stride: it rides along to every kernel of an iteration) when not null, a word that
+    // is non-zero once the solve has stopped; kernels launched after that return at once
+    const int32_t *stop;
 };
+
+__device__ __forceinline__ bool stopped(const PlanStrides &ps)
+{
+    return ps.stop != nullptr && *ps.stop != 0;
+}
 
 template <typename T>
 __device__ __forceinline__ T *of_plan_at(T *p, size_t stride, int plan)
