@@ -52,7 +52,9 @@ nimble_status_t nimble_debug_stream_read(const void *d_buf, int64_t bytes, int32
  * and a global one, all workgroups poll one generation word; 3 as 2, but only the last arriver
  * of an XCD polls the global word and releases the others through a word of their own XCD; 4 no
  * read-modify-write: every workgroup stores its round into its own word of a flag array and
- * its first wave reads the whole array until all words have arrived (at most 2048 workgroups).
+ * its first wave reads the whole array until all words have arrived (at most 2048 workgroups);
+ * 5 as 2 followed by an acquire fence at agent scope, the data written at agent scope and read
+ * with ordinary loads.
  * Every wait gives up after spin_limit polls.  d_work: device memory of work_bytes >= 16384 +
  * 128 per workgroup.  d_out: device int32 [32] out: [0] words that had not arrived, [1] 1 if a
  * wait expired, [2..17] workgroups that ran on XCC id 0..15, [18] rounds completed.  Timed with

@@ -1121,9 +1121,9 @@ nimble_status_t nimble_debug_barrier_probe(int32_t kind, int32_t blocks_per_cu, 
 {
     g_last_error.clear();
     if (!d_work || !d_out) return fail(NIMBLE_ERR_INVALID, "NULL argument");
-    if (kind < 0 || kind > 4 || blocks_per_cu < 1 || blocks_per_cu > 8 || rounds < 1 ||
+    if (kind < 0 || kind > 5 || blocks_per_cu < 1 || blocks_per_cu > 8 || rounds < 1 ||
         threads < 64 || threads > 1024 || threads % 64)
-        return fail(NIMBLE_ERR_INVALID, "kind 0..4, 1..8 blocks per CU, 64..1024 threads");
+        return fail(NIMBLE_ERR_INVALID, "kind 0..5, 1..8 blocks per CU, 64..1024 threads");
     int dev = -1, n_cu = 0;
     hipError_t e = hipGetDevice(&dev);
     if (e == hipSuccess)

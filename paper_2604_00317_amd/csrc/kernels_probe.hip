@@ -77,6 +77,8 @@ __device__ __forceinline__ bool wait_for(const unsigned int *p, unsigned int tar
 //           ordinary stores and loads may cross the barrier
 //   kind 2  two levels: the workgroups of an XCD arrive on their XCD's counter, the last of them
 //           on the global one, the last of those publishes the generation; all poll that word
+//   kind 5  as 2, followed by an acquire fence at agent scope: data stored at agent scope before
+//           the barrier may be read with ordinary (cached) loads after it
 //   kind 3  two levels with a local release: only the XCD's last arriver polls the global
 //           generation, the others poll a word of their own XCD at workgroup scope (it is
 //           written and read through that XCD's L2)
@@ -138,6 +140,13 @@ __device__ __forceinline__ bool probe_barrier(ProbeWords *w, unsigned int round,
         }
         if constexpr (KIND == 2) {
             return wait_for<false>(w->gen, round + 1u, w, spin_limit);
+        } else if constexpr (KIND == 5) {
+            // as 2, then an acquire fence at agent scope (it invalidates what the caches of this
+            // XCD hold of other XCDs' data; nothing is written back): data stored at agent scope
+            // before the barrier may be read with ordinary loads after it
+            const bool ok = wait_for<false>(w->gen, round + 1u, w, spin_limit);
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            return ok;
         } else {
             if (last_of_xcd) {
                 const bool ok = wait_for<false>(w->gen, round + 1u, w, spin_limit);
@@ -201,7 +210,7 @@ __global__ void k_barrier_probe(ProbeArgs a)
         round += 1u;
         if (threadIdx.x == 0) {
             unsigned int v;
-            if constexpr (KIND == 1) v = a.data[kLine * peer];
+            if constexpr (KIND == 1 || KIND == 5) v = a.data[kLine * peer];
             else v = ld_agent(&a.data[kLine * peer]);
             if (v != static_cast<unsigned int>(r + 1)) bad += 1;
         }
@@ -256,6 +265,7 @@ hipError_t launch_barrier_probe(int kind, int blocks, int threads, int rounds,
     case 1: fn = reinterpret_cast<const void *>(&k_barrier_probe<1>); break;
     case 2: fn = reinterpret_cast<const void *>(&k_barrier_probe<2>); break;
     case 3: fn = reinterpret_cast<const void *>(&k_barrier_probe<3>); break;
+    case 5: fn = reinterpret_cast<const void *>(&k_barrier_probe<5>); break;
     case 4:
         if (blocks > kMaxFlagBlocks) return hipErrorInvalidValue;
         fn = reinterpret_cast<const void *>(&k_barrier_probe<4>);

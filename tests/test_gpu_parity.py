@@ -596,7 +596,7 @@ def test_device_allocation_failures_leave_nothing_behind(oracle_mod, B):
     assert lib.nimble_debug_live_allocations() == base
 
 
-@pytest.mark.parametrize("kind", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("kind", [0, 1, 2, 3, 4, 5])
 def test_grid_barrier_probe(B, kind):
     """The barrier probe behind the benchmark's barrier figures: every design either lets the
     word written before a barrier arrive after it, on every round, or gives up within its
