@@ -8,11 +8,12 @@
 // problems does.  A thread keeps the link loads L_e and the remainders r_k of its problem in
 // LDS (entry-major, one column per thread: conflict-free; 64 problems per workgroup, fewer when
 // the topology is larger), reads the candidate CSR through
-// wave-uniform loads (all threads walk the same pairs, candidates and links), and follows
-// the steps of the listing: bottleneck cost max_e c_e with c_e = F(L_e) = L_e / cap_e, strict
+// wave-uniform loads (all threads walk the same pairs, candidates and links), and sweeps the
+// pairs as Algorithm 1 does: bottleneck cost max_e c_e with c_e = F(L_e) = L_e / cap_e, strict
 // `<` in candidate order, f = r if r < chi else chi * floor(r * phi / chi) (one chunk when that
 // is zero), immediate update of L_e, until no remainder is left.  Every floating-point
-// statement is one IEEE binary64 operation.
+// statement is one IEEE binary64 operation.  Both kernels are tested against the hand-worked
+// examples of the algorithm directly (tests/test_gpu_alg1.py), not only against the CPU oracle.
 #include <hip/hip_runtime.h>
 
 #include "kernels.hpp"

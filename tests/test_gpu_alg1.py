@@ -45,6 +45,66 @@ def check(oracle_mod, B, t, demands, phi, chi, max_sweeps=1 << 20):
     return flows, lam, sweeps
 
 
+def _parallel_links(caps, n_comm=1):
+    m = len(caps)
+    return W.Topology(n_links=m, cap=np.asarray(caps, dtype=np.float64), n_comm=n_comm,
+                      comm_path_ptr=np.arange(n_comm + 1, dtype=np.int32) * m, n_paths=n_comm * m,
+                      path_link_ptr=np.arange(n_comm * m + 1, dtype=np.int32),
+                      path_links=np.tile(np.arange(m, dtype=np.int32), n_comm),
+                      src=np.zeros(n_comm, dtype=np.int32), dst=np.zeros(n_comm, dtype=np.int32),
+                      meta=dict(kind="parallel"))
+
+
+def _gpu_alg1(B, t, demand, phi, chi):
+    h = make_topo(B, t)
+    try:
+        flows, lam, sweeps = B.plan_alg1(h, np.asarray(demand, dtype=np.float64), phi, chi)
+    finally:
+        B.nimble_topo_destroy(h)
+    return flows, lam, sweeps
+
+
+def test_hand_worked_examples_directly(B):
+    """Both kernels against the examples of Algorithm 1 worked by hand -- the same facts that pin
+    the CPU oracle (tests/golden/alg1_worked_example.txt, tests/test_alg1_pins.py) -- without
+    the oracle in between: the four-sweep example, the Gauss-Seidel schedule, bottleneck versus
+    additive cost, chunk multiples with the residual rule, and conservation on a benchmark
+    fabric."""
+    import os
+    golden = os.path.join(os.path.dirname(__file__), "golden", "alg1_worked_example.txt")
+    f0, f1, lam0, sw0 = [l for l in open(golden) if l[0] != "#"][0].split()
+    flows, lam, sweeps = _gpu_alg1(B, _parallel_links([100.0, 50.0]), [8.0], 0.5, 1.0)
+    assert flows.tolist() == [float(f0), float(f1)] and lam == float(lam0) and sweeps == int(sw0)
+    # the second pair already sees the first one's load (a Jacobi schedule would not)
+    flows, lam, sweeps = _gpu_alg1(B, _parallel_links([10.0, 10.0], 2), [4.0, 4.0], 1.0, 1.0)
+    assert flows.tolist() == [4.0, 0.0, 0.0, 4.0] and sweeps == 1 and lam == 0.4
+    # bottleneck cost max(0.3, 0.3) = 0.3 beats 0.5; an additive cost (0.6) would not
+    t = W.Topology(n_links=3, cap=np.full(3, 10.0), n_comm=3,
+                   comm_path_ptr=np.array([0, 1, 2, 4], dtype=np.int32), n_paths=4,
+                   path_link_ptr=np.array([0, 2, 3, 4, 6], dtype=np.int32),
+                   path_links=np.array([0, 1, 2, 2, 0, 1], dtype=np.int32),
+                   src=np.zeros(3, dtype=np.int32), dst=np.zeros(3, dtype=np.int32),
+                   meta=dict(kind="tiny"))
+    flows, lam, sweeps = _gpu_alg1(B, t, [3.0, 5.0, 1.0], 1.0, 1.0)
+    assert flows.tolist() == [3.0, 5.0, 0.0, 1.0] and lam == 0.5
+    # d = 10, phi = 0.5, chi = 4: 4, then one chunk of 4 (floor(3/4) = 0), then the residual 2
+    flows, lam, sweeps = _gpu_alg1(B, _parallel_links([1.0, 1.0]), [10.0], 0.5, 4.0)
+    assert flows.tolist() == [6.0, 4.0] and sweeps == 3
+    # conservation and whole chunks on the single node: flows of a pair add up to its demand,
+    # every flow but a pair's residual is a multiple of the chunk, lambda is the load maximum
+    w = W.make_config(0)
+    t, chi = w.topo, float(1 << 20)
+    flows, lam, sweeps = _gpu_alg1(B, t, w.traffic, 0.5, chi)
+    per_pair = np.add.reduceat(flows, t.comm_path_ptr[:-1])
+    assert np.array_equal(per_pair, w.traffic)
+    load = np.zeros(t.n_links)
+    for p in range(t.n_paths):
+        load[t.path_links[t.path_link_ptr[p]:t.path_link_ptr[p + 1]]] += flows[p]
+    assert lam == pytest.approx((load / t.cap).max(), rel=1e-14)
+    odd = np.add.reduceat((np.mod(flows, chi) != 0).astype(np.int64), t.comm_path_ptr[:-1])
+    assert np.all(odd <= 1)
+
+
 @pytest.mark.parametrize("phi,chi", [(0.5, float(1 << 20)), (0.25, 65536.0), (1.0, 4096.0)])
 def test_single_node_batch(oracle_mod, B, phi, chi):
     """The batched single-node workload: 67 problems span two workgroups with a ragged tail."""
