@@ -50,6 +50,40 @@ def check(oracle_mod, B, topo, traffic, eps, iters, regime=0, flags=0, exact=Tru
     return splits, lam
 
 
+def _parallel(caps):
+    m = len(caps)
+    return W.Topology(n_links=m, cap=np.asarray(caps, dtype=np.float64), n_comm=1,
+                      comm_path_ptr=np.array([0, m], dtype=np.int32), n_paths=m,
+                      path_link_ptr=np.arange(m + 1, dtype=np.int32),
+                      path_links=np.arange(m, dtype=np.int32), src=np.zeros(1, dtype=np.int32),
+                      dst=np.zeros(1, dtype=np.int32), meta=dict(kind="parallel"))
+
+
+@pytest.mark.parametrize("regime", [1, 2, 3])
+def test_hand_derived_trajectories_directly(B, regime):
+    """The HIP path against the facts that pin the oracle, without the oracle in between: the
+    hand-derived trajectories on two parallel links (sum cost: the slower link is first taken in
+    iteration 15; bottleneck cost: tests/golden/bottleneck_two_links.txt) and the exact round
+    robin over equal links."""
+    import os
+    def counts(t, T, flags=0):
+        splits, lam, _ = gpu_plan(B, t, [1e6], 0.1, T, regime, flags)
+        return np.rint(splits * T).astype(int).tolist(), lam
+    assert counts(_parallel([100e9, 50e9]), 15)[0] == [15, 0]
+    assert counts(_parallel([100e9, 50e9]), 16)[0] == [15, 1]
+    assert counts(_parallel([100e9, 50e9]), 17)[0] == [16, 1]
+    c, lam = counts(_parallel([50e9] * 4), 200)
+    assert c == [50] * 4 and lam == pytest.approx(1e6 / (4 * 50e9), rel=1e-14)
+    golden = os.path.join(os.path.dirname(__file__), "golden", "bottleneck_two_links.txt")
+    rows = {l.split()[0]: [int(float(x)) for x in l.split()[1:]]
+            for l in open(golden) if l.split() and l[0] != "#"}
+    for key, caps in (("fixed", [100e9, 50e9]), ("fixed_swapped", [50e9, 100e9])):
+        want = rows[key]
+        for T in (1, 2, 5, len(want)):
+            ones = sum(want[:T])
+            assert counts(_parallel(caps), T, flags=1)[0] == [T - ones, ones], (key, T)
+
+
 @pytest.mark.parametrize("regime", [1, 2, 3])
 @pytest.mark.parametrize("cfg", [0, 1])
 def test_small_configs_full_iterations(oracle_mod, B, cfg, regime):
