@@ -175,6 +175,11 @@ def main() -> int:
                     help="override the configuration's iteration count (profiling runs only)")
     ap.add_argument("--copy-calib", type=int, default=0,
                     help="also run N plain device copies of 1 GiB (counter calibration)")
+    ap.add_argument("--plans", type=int, default=0,
+                    help="run a batch of N plans of a single-plan configuration (profiling runs)")
+    ap.add_argument("--no-barrier-probe", action="store_true",
+                    help="skip the grid-barrier probe (its cooperative launch makes rocprofv3 "
+                         "crash when the traced process exits)")
     ap.add_argument("--no-also", action="store_true",
                     help="skip the extra configurations reported under 'also'")
     args = ap.parse_args()
@@ -192,14 +197,14 @@ def main() -> int:
     B.load_library(build_if_missing=True)
 
     r = run_config(B, W, torch, args.config, args.regime, args.steps, args.warmup, args.iters,
-                   args.batch, args.copy_calib)
+                   args.batch, args.copy_calib, plans=args.plans)
     w, topo, h, batch = r["w"], r["topo"], r["h"], r["batch"]
     elapsed, regime = r["elapsed"], r["regime"]
     ms_per_step = elapsed * 1e3 / args.steps
     iters_per_s = w.iters * batch * args.steps / elapsed
     plans_per_s = batch * args.steps / elapsed
     lam = r["d_lambda"].cpu().numpy()
-    workload = f"configs[{args.config}] {w.name}"
+    workload = f"configs[{args.config}] {w.name}" + (f" x{args.plans}" if args.plans else "")
 
     # ---- roofline of the dominant kernel ------------------------------------------------
     bytes_ = phase_bytes(h)
@@ -208,7 +213,8 @@ def main() -> int:
         for ph, name in enumerate(PHASES):
             if bytes_[name] == 0:        # the length update runs inside the reduce kernel
                 continue
-            sec = time_phase(B, torch, h, ph, 200, r["d_traffic"])
+            # (a batch: the launches of one plan, the first)
+            sec = time_phase(B, torch, h, ph, 200, r["d_traffic"][:topo.n_comm])
             if name == "load_reduce" and bytes_["update"] == 0:
                 name = "reduce_update"
             kernels[name] = dict(back_to_back_us=sec * 1e6, bytes=bytes_[PHASES[ph]])
@@ -442,7 +448,7 @@ def main() -> int:
 
     # ---- what a grid-wide barrier costs next to the kernel boundaries the plan uses -----------
     barrier = None
-    if not args.no_also:
+    if not args.no_also and not args.no_barrier_probe:
         work = torch.zeros(1 << 20, dtype=torch.uint8, device="cuda:0")
         res = torch.zeros(32, dtype=torch.int32, device="cuda:0")
         barrier = {}
