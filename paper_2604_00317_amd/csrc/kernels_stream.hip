@@ -76,7 +76,7 @@ __global__ __launch_bounds__(kBlock) void k_export_len(int E, const int32_t *__r
     if (i < E) len_out[pos_link[i]] = len[i];
 }
 
-template <int L, int LMAX, bool MAXC>
+template <int L, int LMAX, bool MAXC, bool EXT>
 __global__ __launch_bounds__(kBlock) void k_argmin(int K, const int32_t *__restrict__ cp,
                                                    const int32_t *__restrict__ lp,
                                                    const int32_t *__restrict__ pl,
@@ -86,11 +86,13 @@ __global__ __launch_bounds__(kBlock) void k_argmin(int K, const int32_t *__restr
                                                    const int32_t *__restrict__ sigma,
                                                    uint8_t *__restrict__ choice2, PlanStrides ps)
 {
-    if (stopped(ps)) return;
-    price = of_plan(price, ps.state);
-    choice = of_plan(choice, ps.row);
-    count = of_plan(count, ps.state);
-    choice2 = of_plan(choice2, ps.state);
+    if constexpr (EXT) {      // a batch (blockIdx.y is the plan) or a solve that may stop early
+        if (stopped(ps)) return;
+        price = of_plan(price, ps.state);
+        choice = of_plan(choice, ps.row);
+        count = of_plan(count, ps.state);
+        choice2 = of_plan(choice2, ps.state);
+    }
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
@@ -139,7 +141,7 @@ __device__ __forceinline__ void scan_quad(const double *s_price, const uint32_t 
     i4 = cst[0] == m4 ? 0 : (cst[1] == m4 ? 1 : (cst[2] == m4 ? 2 : 3));
 }
 
-template <int L, int S, bool MAXC, bool TWO>
+template <int L, int S, bool MAXC, bool TWO, bool EXT>
 __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records,
                                                       const uint8_t *__restrict__ records,
                                                       const double *__restrict__ price,
@@ -148,11 +150,13 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records,
                                                       uint8_t *__restrict__ choice2,
                                                       PlanStrides ps)
 {
-    if (stopped(ps)) return;
-    price = of_plan(price, ps.state);
-    choice = of_plan(choice, ps.row);
-    count = of_plan(count, ps.state);
-    choice2 = of_plan(choice2, ps.state);
+    if constexpr (EXT) {      // a batch (blockIdx.y is the plan) or a solve that may stop early
+        if (stopped(ps)) return;
+        price = of_plan(price, ps.state);
+        choice = of_plan(choice, ps.row);
+        count = of_plan(count, ps.state);
+        choice2 = of_plan(choice2, ps.state);
+    }
     // LDS, one private slice per wave: the body of the record (everything after the link
     // table) followed by the price table.  The waves of a workgroup never synchronise with
     // each other.
@@ -303,7 +307,7 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records,
 // commodity and the record), so the body never goes through LDS -- only the prices do.  The
 // price slots kRecZeroSlot / kRecInfSlot hold +0.0 / +inf for short paths and absent
 // candidates.  One scan round per record: a record has at most 64 / L commodities.
-template <int L, int S, bool MAXC, bool T16>
+template <int L, int S, bool MAXC, bool T16, bool EXT>
 __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records, int around_l2,
                                                        const uint8_t *__restrict__ records,
                                                        const double *__restrict__ price,
@@ -314,11 +318,13 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records,
 {
     static_assert(L >= 2 && L <= 16 && S <= kRecLaneSteps,
                   "lane-major records: 2 to 16 lanes per commodity, five steps");
-    if (stopped(ps)) return;
-    price = of_plan(price, ps.state);
-    choice = of_plan(choice, ps.row);
-    count = of_plan(count, ps.state);
-    choice2 = of_plan(choice2, ps.state);
+    if constexpr (EXT) {      // a batch (blockIdx.y is the plan) or a solve that may stop early
+        if (stopped(ps)) return;
+        price = of_plan(price, ps.state);
+        choice = of_plan(choice, ps.row);
+        count = of_plan(count, ps.state);
+        choice2 = of_plan(choice2, ps.state);
+    }
     // T16: the link table is 256 uint16 (8 bytes per lane) and the record 3.5 KiB
     constexpr int kTab = T16 ? kRecTable16 : kRecTable;
     constexpr int kRec = T16 ? kRecBytes16 : kRecBytes;
@@ -465,7 +471,7 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records,
 // link table entries, the lane's own word (sigma, or the record's first commodity / first
 // candidate) and the body number.  In flight while a record is scanned: the 16 bytes of the
 // record after the next and the prices of the next one.
-template <int L, int S, bool MAXC>
+template <int L, int S, bool MAXC, bool EXT>
 __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recd(int n_chunks, int around_l2,
                                                        const int4 *__restrict__ chunks,
                                                        const uint8_t *__restrict__ records,
@@ -478,11 +484,13 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recd(int n_chunks, 
 {
     static_assert(L >= 2 && L <= 16 && S <= kRecLaneSteps,
                   "lane-major records: 2 to 16 lanes per commodity, five steps");
-    if (stopped(ps)) return;
-    price = of_plan(price, ps.state);
-    choice = of_plan(choice, ps.row);
-    count = of_plan(count, ps.state);
-    choice2 = of_plan(choice2, ps.state);
+    if constexpr (EXT) {      // a batch (blockIdx.y is the plan) or a solve that may stop early
+        if (stopped(ps)) return;
+        price = of_plan(price, ps.state);
+        choice = of_plan(choice, ps.row);
+        count = of_plan(count, ps.state);
+        choice2 = of_plan(choice2, ps.state);
+    }
     __shared__ double s_all[kRecWaves * kRecPriceSlots];
     double *s_price = s_all + (threadIdx.x >> 6) * kRecPriceSlots;
     const int lane = threadIdx.x & (kWave - 1);
@@ -622,18 +630,20 @@ struct ReduceArgs {
     PlanStrides ps;
 };
 
-template <int MODE>
+template <int MODE, bool EXT>
 __global__ __launch_bounds__(kBlock) void k_load_reduce(ReduceArgs a)
 {
-    if (stopped(a.ps)) return;
-    a.demand1n = of_plan(a.demand1n, a.ps.state);
-    a.demand1t = of_plan(a.demand1t, a.ps.state);
-    a.demand2t = of_plan(a.demand2t, a.ps.state);
-    a.demand2 = of_plan(a.demand2, a.ps.state);
-    a.choice2 = of_plan(a.choice2, a.ps.state);
-    a.partial = of_plan(a.partial, a.ps.state);
-    a.choice = of_plan(a.choice, a.ps.row);
-    a.demand = of_plan(a.demand, a.ps.demand);
+    if constexpr (EXT) {      // a batch (blockIdx.y is the plan) or a solve that may stop early
+        if (stopped(a.ps)) return;
+        a.demand1n = of_plan(a.demand1n, a.ps.state);
+        a.demand1t = of_plan(a.demand1t, a.ps.state);
+        a.demand2t = of_plan(a.demand2t, a.ps.state);
+        a.demand2 = of_plan(a.demand2, a.ps.state);
+        a.choice2 = of_plan(a.choice2, a.ps.state);
+        a.partial = of_plan(a.partial, a.ps.state);
+        a.choice = of_plan(a.choice, a.ps.row);
+        a.demand = of_plan(a.demand, a.ps.demand);
+    }
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
@@ -688,19 +698,21 @@ struct LinkState {
 // ONLY_U (adaptive step): the update cannot be applied before the largest normalised load of
 // the whole fabric is known, so the kernel stops at u = load / cap (by position, to a.u_pos) and
 // leaves every wave's maximum of u in a.block_max_u for the kernel that applies the step.
-template <bool MAXC, bool ONLY_U = false>
+template <bool MAXC, bool ONLY_U, bool EXT>
 __global__ __launch_bounds__(kBlock) void k_reduce_update(FusedArgs a)
 {
     __shared__ double s_part[kBlkMaxSlots];
-    if (stopped(a.ps)) return;
-    a.choice = of_plan(a.choice, a.ps.row);
-    a.choice2 = of_plan(a.choice2, a.ps.state);
-    a.demand1n = of_plan(a.demand1n, a.ps.state);
-    a.demand2 = of_plan(a.demand2, a.ps.state);
-    a.len = of_plan(a.len, a.ps.state);
-    a.price = of_plan(a.price, a.ps.state);
-    a.S = of_plan(a.S, a.ps.state);
-    a.scalars = of_plan(a.scalars, a.ps.state);
+    if constexpr (EXT) {      // a batch (blockIdx.y is the plan) or a solve that may stop early
+        if (stopped(a.ps)) return;
+        a.choice = of_plan(a.choice, a.ps.row);
+        a.choice2 = of_plan(a.choice2, a.ps.state);
+        a.demand1n = of_plan(a.demand1n, a.ps.state);
+        a.demand2 = of_plan(a.demand2, a.ps.state);
+        a.len = of_plan(a.len, a.ps.state);
+        a.price = of_plan(a.price, a.ps.state);
+        a.S = of_plan(a.S, a.ps.state);
+        a.scalars = of_plan(a.scalars, a.ps.state);
+    }
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
     const int b = blockIdx.x;
@@ -880,7 +892,7 @@ __global__ __launch_bounds__(kBlock) void k_width_fold(int n_blocks, double *__r
 }
 
 // length update fused with the per-block maximum of the congestion sums (lambda = max / iters)
-template <bool MAXC, int RL>
+template <bool MAXC, int RL, bool EXT>
 __global__ __launch_bounds__(kBlock) void k_update(int E, double eps,
                                                    const int32_t *__restrict__ pos_link,
                                                    const int32_t *__restrict__ pos_slot_ptr,
@@ -893,11 +905,13 @@ __global__ __launch_bounds__(kBlock) void k_update(int E, double eps,
                                                    double *__restrict__ scalars, PlanStrides ps)
 {
     __shared__ double red[16];
-    partial = of_plan(partial, ps.state);
-    len = of_plan(len, ps.state);
-    price = of_plan(price, ps.state);
-    S = of_plan(S, ps.state);
-    scalars = of_plan(scalars, ps.state);
+    if constexpr (EXT) {
+        partial = of_plan(partial, ps.state);
+        len = of_plan(len, ps.state);
+        price = of_plan(price, ps.state);
+        S = of_plan(S, ps.state);
+        scalars = of_plan(scalars, ps.state);
+    }
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
     const int n_waves = (gridDim.x * blockDim.x) >> 6;
@@ -962,6 +976,10 @@ inline int blocks_for(int64_t threads, int block, int cap)
 }
 
 // byte distances between the plans of the batch a launch covers (t.batch plans, grid.y)
+// whether a launch needs the kernels that know about plans and the stop word; a single plan
+// that always runs to the end takes the plain ones, which do not even look
+inline bool extended(const DeviceTopo &t) { return t.batch > 1 || t.stop_flag != nullptr; }
+
 inline PlanStrides strides_of(const DeviceTopo &t)
 {
     PlanStrides ps;
@@ -998,11 +1016,18 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, uint8_t *choice, uint32_t
                     const int dgrid = (t.n_rec_chunks + kRecWaves - 1) / kRecWaves;
 #define NIMBLE_RECD_LAUNCH(SS)                                                                 \
     case SS:                                                                                   \
-        hipLaunchKernelGGL((k_argmin_recd<L, SS, MAXC>), dim3(dgrid, t.batch),                 \
-                           dim3(kWave * kRecWaves), 0, s, t.n_rec_chunks, around_l2,           \
-                           t.rec_chunks, t.records,                                            \
-                           reinterpret_cast<const u32x4 *>(t.rec_dict_words), t.price, choice, \
-                           count, t.choice2, strides_of(t));                                   \
+        if (extended(t))                                                                       \
+            hipLaunchKernelGGL((k_argmin_recd<L, SS, MAXC, true>), dim3(dgrid, t.batch),       \
+                               dim3(kWave * kRecWaves), 0, s, t.n_rec_chunks, around_l2,       \
+                               t.rec_chunks, t.records,                                        \
+                               reinterpret_cast<const u32x4 *>(t.rec_dict_words), t.price,     \
+                               choice, count, t.choice2, strides_of(t));                       \
+        else                                                                                   \
+            hipLaunchKernelGGL((k_argmin_recd<L, SS, MAXC, false>), dim3(dgrid),               \
+                               dim3(kWave * kRecWaves), 0, s, t.n_rec_chunks, around_l2,       \
+                               t.rec_chunks, t.records,                                        \
+                               reinterpret_cast<const u32x4 *>(t.rec_dict_words), t.price,     \
+                               choice, count, t.choice2, strides_of(t));                       \
         return;
                     switch (t.rec_stride) {
                         NIMBLE_RECD_LAUNCH(1)
@@ -1015,14 +1040,20 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, uint8_t *choice, uint32_t
                 }
 #define NIMBLE_RECL_LAUNCH(SS)                                                                 \
     case SS:                                                                                   \
-        if (t.rec_table16)                                                                     \
-            hipLaunchKernelGGL((k_argmin_recl<L, SS, MAXC, true>), dim3(rec_grid, t.batch),    \
+        if (t.rec_table16 && extended(t))                                                      \
+            hipLaunchKernelGGL((k_argmin_recl<L, SS, MAXC, true, true>),                       \
+                               dim3(rec_grid, t.batch), dim3(kWave * kRecWaves), 0, s,         \
+                               t.n_records, around_l2, t.records, t.price, choice, count,      \
+                               t.choice2, strides_of(t));                                      \
+        else if (t.rec_table16)                                                                \
+            hipLaunchKernelGGL((k_argmin_recl<L, SS, MAXC, true, false>), dim3(rec_grid),      \
                                dim3(kWave * kRecWaves), 0, s, t.n_records, around_l2,          \
                                t.records, t.price, choice, count, t.choice2, strides_of(t));   \
         else                                                                                   \
-            hipLaunchKernelGGL((k_argmin_recl<L, SS, MAXC, false>), dim3(rec_grid, t.batch),   \
-                               dim3(kWave * kRecWaves), 0, s, t.n_records, around_l2,          \
-                               t.records, t.price, choice, count, t.choice2, strides_of(t));   \
+            hipLaunchKernelGGL((k_argmin_recl<L, SS, MAXC, false, true>),                      \
+                               dim3(rec_grid, t.batch), dim3(kWave * kRecWaves), 0, s,         \
+                               t.n_records, around_l2, t.records, t.price, choice, count,      \
+                               t.choice2, strides_of(t));                                      \
         return;
                 switch (t.rec_stride) {
                     NIMBLE_RECL_LAUNCH(1)
@@ -1039,11 +1070,11 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, uint8_t *choice, uint32_t
 #define NIMBLE_REC_LAUNCH(SS)                                                                  \
     case SS:                                                                                   \
         if (two)                                                                               \
-            hipLaunchKernelGGL((k_argmin_rec<L, SS, MAXC, true>), dim3(rec_grid, t.batch),     \
+            hipLaunchKernelGGL((k_argmin_rec<L, SS, MAXC, true, true>), dim3(rec_grid, t.batch), \
                                dim3(kWave * kRecWaves), 0, s, t.n_records, t.records, t.price, \
                                choice, count, t.choice2, strides_of(t));                       \
         else                                                                                   \
-            hipLaunchKernelGGL((k_argmin_rec<L, SS, MAXC, false>), dim3(rec_grid, t.batch),    \
+            hipLaunchKernelGGL((k_argmin_rec<L, SS, MAXC, false, true>), dim3(rec_grid, t.batch), \
                                dim3(kWave * kRecWaves), 0, s, t.n_records, t.records, t.price, \
                                choice, count, t.choice2, strides_of(t));                       \
         return;
@@ -1060,7 +1091,7 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, uint8_t *choice, uint32_t
 #undef NIMBLE_REC_LAUNCH
     }
 #define NIMBLE_ARGMIN_LAUNCH(LM)                                                              \
-    hipLaunchKernelGGL((k_argmin<L, LM, MAXC>), dim3(grid, t.batch), dim3(kBlock), 0, s, t.K, \
+    hipLaunchKernelGGL((k_argmin<L, LM, MAXC, true>), dim3(grid, t.batch), dim3(kBlock), 0, s, t.K, \
                        t.comm_ptr, t.path_ptr, t.path_links, t.price, choice, count, t.sigma, \
                        t.choice2, strides_of(t))
     if (t.lmax <= 2) NIMBLE_ARGMIN_LAUNCH(2);
@@ -1153,7 +1184,10 @@ void launch_reduce_mode(const DeviceTopo &t, const uint8_t *choice, const double
     a.demand2 = t.demand2;
     a.partial = t.partial;
     a.ps = strides_of(t);
-    hipLaunchKernelGGL(k_load_reduce<MODE>, dim3(grid, t.batch), dim3(kBlock), 0, s, a);
+    if (extended(t) || MODE != 0)
+        hipLaunchKernelGGL((k_load_reduce<MODE, true>), dim3(grid, t.batch), dim3(kBlock), 0, s, a);
+    else
+        hipLaunchKernelGGL((k_load_reduce<0, false>), dim3(grid), dim3(kBlock), 0, s, a);
 }
 
 }  // namespace
@@ -1168,7 +1202,8 @@ int recd_blocks_per_cu(int stride)
 #define NIMBLE_RECD_OCC(SS)                                                                    \
     case SS:                                                                                   \
         e = hipOccupancyMaxActiveBlocksPerMultiprocessor(                                      \
-            &n, reinterpret_cast<const void *>(&k_argmin_recd<L, SS, MAXC>), kWave * kRecWaves, \
+            &n, reinterpret_cast<const void *>(&k_argmin_recd<L, SS, MAXC, false>),            \
+            kWave * kRecWaves,                                                                 \
             0);                                                                                \
         break;
     switch (stride) {
@@ -1275,9 +1310,18 @@ void launch_histogram(const DeviceTopo &t, const uint8_t *log, size_t stride, in
 void launch_update(const DeviceTopo &t, double eps, hipStream_t s)
 {
 #define NIMBLE_UPDATE_LAUNCH(MC, RL)                                                           \
-    hipLaunchKernelGGL((k_update<MC, RL>), dim3(t.n_update_blocks, t.batch), dim3(kBlock), 0,  \
-                       s, t.E, eps, t.pos_link, t.pos_slot_ptr, t.pos_xslot, t.partial,        \
-                       t.invcap_pos, t.len, t.price, t.S, t.scalars, strides_of(t))
+    do {                                                                                       \
+        if (extended(t))                                                                       \
+            hipLaunchKernelGGL((k_update<MC, RL, true>), dim3(t.n_update_blocks, t.batch),     \
+                               dim3(kBlock), 0, s, t.E, eps, t.pos_link, t.pos_slot_ptr,       \
+                               t.pos_xslot, t.partial, t.invcap_pos, t.len, t.price, t.S,      \
+                               t.scalars, strides_of(t));                                      \
+        else                                                                                   \
+            hipLaunchKernelGGL((k_update<MC, RL, false>), dim3(t.n_update_blocks),             \
+                               dim3(kBlock), 0, s, t.E, eps, t.pos_link, t.pos_slot_ptr,       \
+                               t.pos_xslot, t.partial, t.invcap_pos, t.len, t.price, t.S,      \
+                               t.scalars, strides_of(t));                                      \
+    } while (0)
     if (t.update_lanes == 4) {
         if (t.cost_max) NIMBLE_UPDATE_LAUNCH(true, 4);
         else NIMBLE_UPDATE_LAUNCH(false, 4);
@@ -1324,11 +1368,20 @@ void launch_reduce_update(const DeviceTopo &t, const uint8_t *choice, const doub
                                0, s, a);
         return;
     }
-    if (t.cost_max)
-        hipLaunchKernelGGL(k_reduce_update<true>, dim3(t.n_blocks, t.batch), dim3(kBlock), 0, s, a);
-    else
-        hipLaunchKernelGGL(k_reduce_update<false>, dim3(t.n_blocks, t.batch), dim3(kBlock), 0, s,
-                           a);
+    if (extended(t)) {
+        if (t.cost_max)
+            hipLaunchKernelGGL((k_reduce_update<true, false, true>), dim3(t.n_blocks, t.batch),
+                               dim3(kBlock), 0, s, a);
+        else
+            hipLaunchKernelGGL((k_reduce_update<false, false, true>), dim3(t.n_blocks, t.batch),
+                               dim3(kBlock), 0, s, a);
+    } else if (t.cost_max) {
+        hipLaunchKernelGGL((k_reduce_update<true, false, false>), dim3(t.n_blocks), dim3(kBlock),
+                           0, s, a);
+    } else {
+        hipLaunchKernelGGL((k_reduce_update<false, false, false>), dim3(t.n_blocks), dim3(kBlock),
+                           0, s, a);
+    }
 }
 
 int launch_reduce_u(const DeviceTopo &t, const uint8_t *choice, double *u_pos,
@@ -1355,7 +1408,8 @@ int launch_reduce_u(const DeviceTopo &t, const uint8_t *choice, double *u_pos,
     a.n_plans = 1;
     a.u_pos = u_pos;
     a.block_max_u = block_max_u;
-    hipLaunchKernelGGL((k_reduce_update<false, true>), dim3(t.n_blocks), dim3(kBlock), 0, s, a);
+    hipLaunchKernelGGL((k_reduce_update<false, true, true>), dim3(t.n_blocks), dim3(kBlock), 0, s,
+                       a);
     return t.n_blocks * (kBlock / kWave);
 }
 

@@ -6,6 +6,8 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <type_traits>
+
 #include "host_topo.hpp"
 #include "wave_ops.hpp"
 
@@ -64,7 +66,10 @@ template <typename T>
 __device__ __forceinline__ T *of_plan_at(T *p, size_t stride, int plan)
 {
     if (p == nullptr) return p;
-    return reinterpret_cast<T *>(reinterpret_cast<uintptr_t>(p) + stride * static_cast<size_t>(plan));
+    // (byte arithmetic on the pointer itself, not on an integer: the result stays derived from p,
+    // so what the compiler knows about p -- __restrict__ above all -- still holds)
+    using Byte = std::conditional_t<std::is_const<T>::value, const char, char>;
+    return reinterpret_cast<T *>(reinterpret_cast<Byte *>(p) + stride * static_cast<size_t>(plan));
 }
 
 template <typename T>
