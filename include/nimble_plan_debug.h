@@ -134,7 +134,7 @@ nimble_status_t nimble_host_records_roundtrip(int32_t n_links, int32_t n_comm,
 
 /*
  * Host-only helper (no device call): sizes of the device layout nimble_topo_create would build.
- * out is host int64 [18]: (commodity, window) pairs of the reverse CSR; octets (groups of 8
+ * out is host int64 [21]: (commodity, window) pairs of the reverse CSR; octets (groups of 8
  * consecutive commodity ids with one mask each); single pairs; octets numbered by the second
  * commodity numbering; single-pair chunks; partial-sum slots; forward records; indices per
  * candidate in a record; link blocks of the fused reduce + update kernel (0: not used); octets
@@ -143,7 +143,10 @@ nimble_status_t nimble_host_records_roundtrip(int32_t n_links, int32_t n_comm,
  * to 8 links that share them); links whose row lives in a strip; 1 if the bodies of the forward
  * records are laid out lane by lane (the record kernel then keeps them in registers), else 0;
  * 1 if those bodies are kept once each in a dictionary (records of 1 KiB that name their body),
- * else 0; the number of distinct bodies in that dictionary.
+ * else 0; the number of distinct bodies in that dictionary; blocks of link groups (tiled layouts
+ * whose links can be cut into groups with tile items, strip units and octets of their own: the
+ * reduce and the length update of a block then run in one workgroup; 0: none); the most
+ * partial-sum slots and the most work items of such a block.
  */
 nimble_status_t nimble_host_layout_stats(int32_t n_links, int32_t n_comm,
                                          const int32_t *comm_path_ptr, int32_t n_paths,

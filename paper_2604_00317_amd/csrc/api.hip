@@ -249,7 +249,8 @@ StateLayout state_layout(const nimble::DeviceTopo &d)
     L.partial = take(sizeof(double) * static_cast<size_t>(d.n_slots));
     // [0] = 1/rho, then one maximum of S per update block, or per wave of the link blocks
     L.scalars = take(sizeof(double) *
-                     (static_cast<size_t>(std::max(d.n_update_blocks, 4 * d.n_blocks)) + 1));
+                     (static_cast<size_t>(std::max({d.n_update_blocks, 4 * d.n_blocks,
+                                                    16 * d.n_gblocks})) + 1));
     L.bytes = at;
     return L;
 }
@@ -353,6 +354,8 @@ nimble_status_t solve_stream(nimble_topo *topo, const double *d_traffic, double 
         nimble::launch_argmin(d, row, logged ? nullptr : d.count, s);
         if (d.n_blocks > 0) {
             nimble::launch_reduce_update(d, row, d_traffic, eps, s);
+        } else if (d.n_gblocks > 0) {
+            nimble::launch_group_reduce_update(d, row, eps, s);
         } else {
             nimble::launch_load_reduce(d, row, d_traffic, s);
             nimble::launch_update(d, eps, s);
@@ -482,6 +485,16 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     }
     d.n_update_blocks = (h.E + 256 / d.update_lanes - 1) / (256 / d.update_lanes);
     d.n_blocks = std::getenv("NIMBLE_TUNE_NO_LINK_BLOCKS") ? 0 : h.n_blocks;
+    // blocks of link groups: a workgroup of 4, 8 or 16 waves, about two tasks per wave in the
+    // largest block
+    d.n_gblocks = h.n_gblocks;
+    d.gblk_max_slots = h.gblk_max_slots;
+    d.gblk_waves = 4;
+    while (d.gblk_waves < 16 && 2 * d.gblk_waves < h.gblk_max_tasks) d.gblk_waves *= 2;
+    if (const char *v = std::getenv("NIMBLE_TUNE_GROUP_WAVES")) {
+        const int x = std::atoi(v);
+        if (x == 4 || x == 8 || x == 16) d.gblk_waves = x;
+    }
 
 #define NIMBLE_TRY(call, what)                        \
     do {                                              \
@@ -528,6 +541,7 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     NIMBLE_TRY(upload(t, h.pos_slot_ptr.data(), h.pos_slot_ptr.size(), &d.pos_slot_ptr),
                "pos_slot_ptr");
     NIMBLE_TRY(upload(t, h.blk_desc.data(), h.blk_desc.size(), &d.blk_desc), "blk_desc");
+    NIMBLE_TRY(upload(t, h.gblk_desc.data(), h.gblk_desc.size(), &d.gblk_desc), "gblk_desc");
     NIMBLE_TRY(upload(t, h.tile_desc.data(), h.tile_desc.size(), &d.tile_desc), "tile_desc");
     NIMBLE_TRY(upload(t, h.tile_mask.data(), h.tile_mask.size(), &d.tile_mask), "tile_mask");
     NIMBLE_TRY(upload(t, h.tile_pres.data(), h.tile_pres.size(), &d.tile_pres), "tile_pres");
@@ -659,6 +673,12 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
         // one kernel: the slot partials stay in LDS; per block two table entries and one maximum
         t->bytes_reduce = 36LL * static_cast<int64_t>(h.oct_base.size()) + 4LL * d.n_passes +
                           8LL * h.E + 56LL * h.E + 64LL * d.n_blocks;
+        t->bytes_update = 0;
+    }
+    if (d.n_gblocks > 0) {
+        // one kernel: the slot partials stay in LDS; the links' tables and state, a descriptor
+        // and sixteen maxima per block
+        t->bytes_reduce += -8LL * d.n_slots + 16LL * h.E + 56LL * h.E + 192LL * d.n_gblocks;
         t->bytes_update = 0;
     }
     t->bytes_per_iter = t->bytes_argmin + t->bytes_reduce + t->bytes_update;
@@ -1095,7 +1115,7 @@ nimble_status_t nimble_debug_run_phase(nimble_topo_t *topo, int32_t phase, int32
     g_last_error.clear();
     if (!topo || !d_traffic) return fail(NIMBLE_ERR_INVALID, "NULL argument");
     if (phase < 0 || phase > 2 || reps < 1) return fail(NIMBLE_ERR_INVALID, "bad phase or reps");
-    if (phase == 2 && topo->d.n_blocks > 0)
+    if (phase == 2 && (topo->d.n_blocks > 0 || topo->d.n_gblocks > 0))
         return fail(NIMBLE_ERR_INVALID, "the length update is part of phase 1 on this topology");
     if (!topo->state_ready)
         return fail(NIMBLE_ERR_INVALID, "run a streaming-regime solve on this topology first");
@@ -1107,6 +1127,8 @@ nimble_status_t nimble_debug_run_phase(nimble_topo_t *topo, int32_t phase, int32
         if (phase == 0) nimble::launch_argmin(topo->d, row, topo->state_log ? nullptr : topo->d.count, s);
         else if (phase == 1 && topo->d.n_blocks > 0)
             nimble::launch_reduce_update(topo->d, row, d_traffic, 0.0, s);
+        else if (phase == 1 && topo->d.n_gblocks > 0)
+            nimble::launch_group_reduce_update(topo->d, row, 0.0, s);
         else if (phase == 1) nimble::launch_load_reduce(topo->d, row, d_traffic, s);
         else nimble::launch_update(topo->d, 0.0, s);   // eps 0: lengths stay as they are
     }

@@ -3,10 +3,13 @@
 #include <algorithm>
 #include <climits>
 #include <cmath>
+#include <cstdio>
 #include <cstdlib>
 #include <cstring>
 #include <functional>
+#include <map>
 #include <queue>
+#include <tuple>
 #include <string>
 #include <unordered_map>
 
@@ -94,6 +97,8 @@ void read_layout_options(HostTopo &t)
     number("NIMBLE_TUNE_BLOCK_PASSES", 1, 1024, t.blk_passes);
     number("NIMBLE_TUNE_TILES", 0, 1, t.tiles);
     number("NIMBLE_TUNE_TILE_MIN_ITEMS", 1, kTileIds, t.tile_min_items);
+    number("NIMBLE_TUNE_LINK_GROUPS", 0, 1, t.link_groups);
+    number("NIMBLE_TUNE_GROUP_BLOCKS", 1, 65536, t.grp_target);
     int32_t dense_only = 0;
     number("NIMBLE_TUNE_TILES_DENSE_ONLY", 0, 1, dense_only);
     t.tiles_dense_only = dense_only != 0;
@@ -477,8 +482,11 @@ static void build_streaming_layout(int32_t n_links, int32_t n_comm, const int32_
     t.single_pair.clear();
     t.n_single_pairs = 0;
     t.schunk_begin.clear(); t.schunk_end.clear(); t.schunk_slot.clear();
-    t.link_sslot_ptr.assign(n_links + 1, 0);
     t.sigma.assign(n_comm, -1);
+    t.n_gblocks = 0;
+    t.gblk_desc.clear();
+    t.gblk_max_slots = 0;
+    t.gblk_max_tasks = 0;
     const int32_t sgl_chunk = kRowLanesHost * kSinglesPerLane;
     auto one_window = [&](int32_t kk) { return comm_path_ptr[kk + 1] - comm_path_ptr[kk] <= 32; };
     struct Item { int32_t key; uint32_t a, b; };       // key: commodity id or sigma, -1: single
@@ -671,117 +679,10 @@ static void build_streaming_layout(int32_t n_links, int32_t n_comm, const int32_
         link_chunk_first[n_links] = static_cast<int32_t>(t.schunk_begin.size());
     }
 
-    // ---- strips: short rows that several links share ---------------------------------------
-    // Rows that are left with the very same octets (the same commodities: e.g. the rail links
-    // between two nodes) and one mask value each are taken out of the octet stream.  A UNIT is
-    // 8 columns (octets) x up to 8 such rows and occupies 8 lanes of a strip item; lane i of
-    // the unit gathers the choices and demands of column i once and uses them for all rows.
-    struct UnitRef { int32_t item, group, row; };
-    std::vector<std::vector<UnitRef>> link_units(n_links);
-    t.strip_base.clear(); t.strip_pres.clear(); t.strip_mask.clear(); t.strip_slot.clear();
-    t.n_strip_rows = 0;
-    if (tiles_on && !t.tiles_dense_only) {
-        std::vector<uint32_t> row_um(n_links, 0u);        // the row's one mask value, 0: none
-        std::unordered_map<uint64_t, std::vector<int32_t>> by_hash;
-        for (int32_t e = 0; e < n_links; ++e) {
-            const size_t n = row_base[e].size();
-            if (n < static_cast<size_t>(kStripMinCols) || n > static_cast<size_t>(kStripMaxCols))
-                continue;
-            uint32_t m = 0u;
-            bool uniform = true;
-            for (uint32_t v : row_mask[e]) {
-                if (v == 0u) continue;
-                if (m == 0u) m = v;
-                else if (m != v) { uniform = false; break; }
-            }
-            if (!uniform || m == 0u) continue;
-            row_um[e] = m;
-            uint64_t h = 1469598103934665603ull;
-            for (uint32_t v : row_base[e]) h = (h ^ v) * 1099511628211ull;
-            by_hash[h ^ (static_cast<uint64_t>(n) << 48)].push_back(e);
-        }
-        std::vector<std::vector<int32_t>> clusters;
-        for (auto &kv : by_hash) {
-            std::vector<int32_t> &cand = kv.second;         // ascending link ids
-            std::vector<bool> used(cand.size(), false);
-            for (size_t i = 0; i < cand.size(); ++i) {
-                if (used[i]) continue;
-                std::vector<int32_t> cl(1, cand[i]);
-                for (size_t j = i + 1; j < cand.size(); ++j)
-                    if (!used[j] && row_base[cand[j]] == row_base[cand[i]]) {
-                        used[j] = true;
-                        cl.push_back(cand[j]);
-                    }
-                if (static_cast<int32_t>(cl.size()) >= kStripMinRows) clusters.push_back(cl);
-            }
-        }
-        std::sort(clusters.begin(), clusters.end());        // by first link: a fixed order
-        int32_t n_units = 0;
-        for (const std::vector<int32_t> &cl : clusters) {
-            const std::vector<uint32_t> &bases = row_base[cl[0]];
-            const int32_t n_cols = static_cast<int32_t>(bases.size());
-            for (size_t r0 = 0; r0 < cl.size(); r0 += 8) {
-                const int32_t n_rows = static_cast<int32_t>(std::min<size_t>(8, cl.size() - r0));
-                for (int32_t c0 = 0; c0 < n_cols; c0 += 8) {
-                    const int32_t item = n_units / 8, group = n_units % 8;
-                    if (group == 0) {
-                        t.strip_base.resize(t.strip_base.size() + 64, 0u);
-                        t.strip_pres.resize(t.strip_pres.size() + 64, 0ull);
-                        t.strip_mask.resize(t.strip_mask.size() + 64, 0u);
-                        t.strip_slot.resize(t.strip_slot.size() + 64, -1);
-                    }
-                    const size_t at = static_cast<size_t>(item) * 64 + static_cast<size_t>(group) * 8;
-                    for (int32_t i = 0; i < 8 && c0 + i < n_cols; ++i) {
-                        t.strip_base[at + i] = bases[c0 + i];
-                        uint64_t pres = 0;
-                        for (int32_t r = 0; r < n_rows; ++r) {
-                            const std::vector<uint32_t> &mk = row_mask[cl[r0 + r]];
-                            for (int32_t s8 = 0; s8 < 8; ++s8)
-                                if (mk[static_cast<size_t>(c0 + i) * 8 + s8] != 0u)
-                                    pres |= 1ull << (8 * r + s8);
-                        }
-                        t.strip_pres[at + i] = pres;
-                    }
-                    for (int32_t r = 0; r < n_rows; ++r) {
-                        t.strip_mask[at + r] = row_um[cl[r0 + r]];
-                        link_units[cl[r0 + r]].push_back({item, group, r});
-                    }
-                    n_units += 1;
-                }
-            }
-            for (int32_t e : cl) {
-                t.n_strip_rows += 1;
-                row_base[e].clear(); row_base[e].shrink_to_fit();
-                row_mask[e].clear(); row_mask[e].shrink_to_fit();
-            }
-        }
-    }
-    t.n_strip_items = static_cast<int32_t>(t.strip_base.size() / 64);
-    t.strip_base.resize(t.strip_base.size() + 64, 0u);          // one spare item keeps the
-    t.strip_pres.resize(t.strip_pres.size() + 64, 0ull);        // arrays loadable
-    t.strip_mask.resize(t.strip_mask.size() + 64, 0u);
-    t.strip_slot.resize(t.strip_slot.size() + 64, -1);
-    for (int32_t e = 0; e < n_links; ++e) t.n_octets += static_cast<int64_t>(row_base[e].size());
-
-    // the link's slots outside the octet range: one per piece, per strip unit it has a row in,
-    // and per single-pair chunk, link by link
-    for (int32_t e = 0; e < n_links; ++e) {
-        t.link_sslot_ptr[e] = extra_slots;
-        for (size_t q = 0; q < link_pieces[e].size(); ++q) piece_extra.push_back(extra_slots++);
-        for (const UnitRef &u : link_units[e])
-            t.strip_slot[static_cast<size_t>(u.item) * 64 + static_cast<size_t>(u.group) * 8 + u.row] =
-                extra_slots++;
-        for (int32_t c = link_chunk_first[e]; c < link_chunk_first[e + 1]; ++c)
-            t.schunk_slot.push_back(extra_slots++);
-    }
+    // ---- uniform pieces -------------------------------------------------------------------
     // A piece whose non-zero masks are all equal (the usual case when the candidates of a
     // fabric are enumerated by a product rule) is UNIFORM: it is stored as that one mask plus a
-    // presence bit per commodity.  Work items: pieces sorted by (numbering, window, kind,
-    // covered commodities, link), up to kTileRows pieces of one window, one kind and (uniform
-    // pieces) one set of covered commodities per item: the rows of a uniform item have the same
-    // presence bits, so the kernel clears the demands of the commodities outside once per item.  Dense pieces keep their
-    // 512 masks, lane-contiguous like the masks of a pass; a uniform item stores, per column,
-    // one byte of presence bits for each of its rows.
+    // presence bit per commodity.
     t.n_pieces = static_cast<int32_t>(pieces.size());
     t.n_pieces_uniform = 0;
     std::vector<uint32_t> piece_umask(pieces.size(), 0u);     // 0: dense
@@ -805,6 +706,279 @@ static void build_streaming_layout(int32_t n_links, int32_t n_comm, const int32_
             t.n_pieces_uniform += 1;
         }
     }
+
+    // Tiled layouts cut the links into GROUPS whose tile items, strip units and octets belong
+    // to them alone, and deal the groups to blocks: one workgroup then reduces everything a
+    // block's links receive into LDS and applies their length update in the same launch.
+    const bool grouped = tiles_on && t.link_groups != 0 && t.n_single_pairs == 0;
+
+    // ---- strips: short rows that several links share ---------------------------------------
+    // Rows that are left with the very same octets (the same commodities: e.g. the rail links
+    // between two nodes) and one mask value each are taken out of the octet stream.  A UNIT is
+    // 8 columns (octets) x up to 8 such rows and occupies 8 lanes of a strip item; lane i of
+    // the unit gathers the choices and demands of column i once and uses them for all rows.
+    struct UnitRef { int32_t item, group, row; };
+    std::vector<std::vector<UnitRef>> link_units(n_links);
+    t.strip_base.clear(); t.strip_pres.clear(); t.strip_mask.clear(); t.strip_slot.clear();
+    t.n_strip_rows = 0;
+    std::vector<uint32_t> row_um(n_links, 0u);            // the row's one mask value, 0: none
+    std::vector<std::vector<int32_t>> clusters;
+    if (tiles_on && !t.tiles_dense_only) {
+        std::unordered_map<uint64_t, std::vector<int32_t>> by_hash;
+        for (int32_t e = 0; e < n_links; ++e) {
+            const size_t n = row_base[e].size();
+            if (n < static_cast<size_t>(kStripMinCols) || n > static_cast<size_t>(kStripMaxCols))
+                continue;
+            // (in a grouped layout a link with pieces belongs to the group of its pieces)
+            if (grouped && !link_pieces[e].empty()) continue;
+            uint32_t m = 0u;
+            bool uniform = true;
+            for (uint32_t v : row_mask[e]) {
+                if (v == 0u) continue;
+                if (m == 0u) m = v;
+                else if (m != v) { uniform = false; break; }
+            }
+            if (!uniform || m == 0u) continue;
+            row_um[e] = m;
+            uint64_t h = 1469598103934665603ull;
+            for (uint32_t v : row_base[e]) h = (h ^ v) * 1099511628211ull;
+            by_hash[h ^ (static_cast<uint64_t>(n) << 48)].push_back(e);
+        }
+        for (auto &kv : by_hash) {
+            std::vector<int32_t> &cand = kv.second;         // ascending link ids
+            std::vector<bool> used(cand.size(), false);
+            for (size_t i = 0; i < cand.size(); ++i) {
+                if (used[i]) continue;
+                std::vector<int32_t> cl(1, cand[i]);
+                for (size_t j = i + 1; j < cand.size(); ++j)
+                    if (!used[j] && row_base[cand[j]] == row_base[cand[i]]) {
+                        used[j] = true;
+                        cl.push_back(cand[j]);
+                    }
+                if (static_cast<int32_t>(cl.size()) >= kStripMinRows) clusters.push_back(cl);
+            }
+        }
+        std::sort(clusters.begin(), clusters.end());        // by first link: a fixed order
+    }
+    // a cluster is cut into chunks of up to 8 rows; the units of a chunk stay together
+    struct StripChunk { int32_t cluster, r0, n_rows, block; };
+    std::vector<StripChunk> strip_chunks;
+    for (size_t ci = 0; ci < clusters.size(); ++ci)
+        for (size_t r0 = 0; r0 < clusters[ci].size(); r0 += 8)
+            strip_chunks.push_back({static_cast<int32_t>(ci), static_cast<int32_t>(r0),
+                                    static_cast<int32_t>(std::min<size_t>(8, clusters[ci].size() - r0)),
+                                    0});
+
+    // ---- link groups and their blocks ------------------------------------------------------
+    // Links whose pieces lie in the same windows with the same cover (the same "classes") would
+    // share tile items, so they go into one group, up to 16 links; the links left over are
+    // joined where they share a class; a chunk of strip rows is a group; any other link is a
+    // group of its own.  The groups are dealt to blocks, heaviest first, each to the lightest
+    // block so far.  Any assignment is correct: items and units are formed inside a block.
+    std::vector<int32_t> link_block(n_links, 0);
+    int32_t n_gblocks = 0;
+    if (grouped) {
+        struct Group { std::vector<int32_t> links; int64_t weight; };
+        std::vector<Group> groups;
+        std::vector<bool> placed(n_links, false);
+        // classes of pieces
+        std::map<std::tuple<int32_t, int32_t, int32_t, uint64_t>, int32_t> class_id;
+        std::vector<int32_t> piece_class(pieces.size(), 0);
+        for (size_t i = 0; i < pieces.size(); ++i) {
+            const bool uni = piece_umask[i] != 0u;
+            auto key = std::make_tuple(pieces[i].sig, pieces[i].window, uni ? 1 : 0,
+                                       uni ? piece_phash[i] : 0ull);
+            auto f = class_id.find(key);
+            if (f == class_id.end())
+                f = class_id.emplace(key, static_cast<int32_t>(class_id.size())).first;
+            piece_class[i] = f->second;
+        }
+        auto tile_weight = [&](const std::vector<int32_t> &links) {
+            std::map<int32_t, int32_t> per_class;
+            int64_t octets = 0;
+            for (int32_t e : links) {
+                for (int32_t pi : link_pieces[e]) per_class[piece_class[pi]] += 1;
+                octets += static_cast<int64_t>(row_base[e].size());
+            }
+            int64_t tasks = (octets + 63) / 64;
+            for (const auto &kv : per_class) tasks += (kv.second + kTileRows - 1) / kTileRows;
+            return std::make_pair(tasks, 64 * tasks + static_cast<int64_t>(links.size()));
+        };
+        auto add_group = [&](const std::vector<int32_t> &links, int64_t weight) {
+            groups.push_back({links, weight});
+            for (int32_t e : links) placed[e] = true;
+        };
+        // links with the same classes
+        std::map<std::vector<int32_t>, std::vector<int32_t>> by_signature;
+        for (int32_t e = 0; e < n_links; ++e) {
+            if (link_pieces[e].empty()) continue;
+            std::vector<int32_t> sgn;
+            for (int32_t pi : link_pieces[e]) sgn.push_back(piece_class[pi]);
+            std::sort(sgn.begin(), sgn.end());
+            by_signature[sgn].push_back(e);
+        }
+        std::vector<int32_t> loners;
+        for (const auto &kv : by_signature) {
+            const std::vector<int32_t> &links = kv.second;
+            if (links.size() < 2) {
+                loners.push_back(links[0]);
+                continue;
+            }
+            const size_t nc = kv.first.size();
+            const size_t chunk = kTileRows * std::max<size_t>(1, 16 / nc);
+            for (size_t i = 0; i < links.size();) {
+                // (rows with many octets left: fewer links, so that no group outweighs a block)
+                size_t take = std::min(links.size() - i, chunk);
+                std::vector<int32_t> part(links.begin() + i, links.begin() + i + take);
+                while (take > 1 && tile_weight(part).first > 32) {
+                    take = (take + 1) / 2;
+                    part.resize(take);
+                }
+                add_group(part, tile_weight(part).second);
+                i += take;
+            }
+        }
+        // the others, joined where they share a class
+        {
+            std::sort(loners.begin(), loners.end());
+            std::vector<int32_t> parent(n_links);
+            for (int32_t e = 0; e < n_links; ++e) parent[e] = e;
+            auto find = [&](int32_t x) {
+                while (parent[x] != x) x = parent[x] = parent[parent[x]];
+                return x;
+            };
+            std::unordered_map<int32_t, int32_t> class_first;
+            for (int32_t e : loners)
+                for (int32_t pi : link_pieces[e]) {
+                    auto f = class_first.find(piece_class[pi]);
+                    if (f == class_first.end()) class_first.emplace(piece_class[pi], e);
+                    else {
+                        const int32_t a = find(f->second), b = find(e);
+                        if (a != b) parent[std::max(a, b)] = std::min(a, b);
+                    }
+                }
+            std::map<int32_t, std::vector<int32_t>> comps;
+            for (int32_t e : loners) comps[find(e)].push_back(e);
+            for (const auto &kv : comps) {
+                const std::vector<int32_t> &links = kv.second;       // ascending
+                const int64_t tasks = tile_weight(links).first;
+                const size_t parts = static_cast<size_t>((tasks + 31) / 32);
+                const size_t per = (links.size() + parts - 1) / std::max<size_t>(1, parts);
+                for (size_t i = 0; i < links.size(); i += per) {
+                    std::vector<int32_t> part(links.begin() + i,
+                                              links.begin() + std::min(links.size(), i + per));
+                    add_group(part, tile_weight(part).second);
+                }
+            }
+        }
+        // chunks of strip rows (group index remembered in the chunk)
+        std::vector<int32_t> chunk_group(strip_chunks.size(), -1);
+        for (size_t c = 0; c < strip_chunks.size(); ++c) {
+            const StripChunk &sc = strip_chunks[c];
+            const std::vector<int32_t> &cl = clusters[sc.cluster];
+            std::vector<int32_t> part(cl.begin() + sc.r0, cl.begin() + sc.r0 + sc.n_rows);
+            const int64_t units = (static_cast<int64_t>(row_base[cl[0]].size()) + 7) / 8;
+            chunk_group[c] = static_cast<int32_t>(groups.size());
+            add_group(part, 8 * units + sc.n_rows);
+        }
+        for (int32_t e = 0; e < n_links; ++e)
+            if (!placed[e])
+                add_group(std::vector<int32_t>(1, e),
+                          static_cast<int64_t>(row_base[e].size()) + 1);
+        // blocks
+        int64_t want = t.grp_target > 0 ? t.grp_target : 256;
+        if (want > static_cast<int64_t>(groups.size())) want = static_cast<int64_t>(groups.size());
+        n_gblocks = static_cast<int32_t>(want);
+        std::vector<int32_t> order(groups.size());
+        for (size_t i = 0; i < order.size(); ++i) order[i] = static_cast<int32_t>(i);
+        std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
+            return groups[x].weight > groups[y].weight;
+        });
+        using Load = std::pair<int64_t, int32_t>;         // (weight so far, block)
+        std::priority_queue<Load, std::vector<Load>, std::greater<Load>> lightest;
+        for (int32_t b = 0; b < n_gblocks; ++b) lightest.push({0, b});
+        std::vector<int32_t> group_block(groups.size(), 0);
+        for (int32_t gi : order) {
+            Load top = lightest.top();
+            lightest.pop();
+            group_block[gi] = top.second;
+            for (int32_t e : groups[gi].links) link_block[e] = top.second;
+            top.first += groups[gi].weight;
+            lightest.push(top);
+        }
+        for (size_t c = 0; c < strip_chunks.size(); ++c)
+            strip_chunks[c].block = group_block[chunk_group[c]];
+        std::stable_sort(strip_chunks.begin(), strip_chunks.end(),
+                         [](const StripChunk &x, const StripChunk &y) { return x.block < y.block; });
+    }
+
+    // the strip items, chunk after chunk (block after block: a block's units fill items of
+    // their own)
+    std::vector<int32_t> gblk_strip_ptr(static_cast<size_t>(n_gblocks) + 1, 0);
+    {
+        int32_t n_units = 0;
+        int32_t cur_block = 0;
+        for (const StripChunk &sc : strip_chunks) {
+            if (grouped && sc.block != cur_block) {
+                n_units = (n_units + 7) & ~7;             // the next block starts a new item
+                for (int32_t b = cur_block + 1; b <= sc.block; ++b) gblk_strip_ptr[b] = n_units / 8;
+                cur_block = sc.block;
+            }
+            const std::vector<int32_t> &cl = clusters[sc.cluster];
+            const std::vector<uint32_t> &bases = row_base[cl[0]];
+            const int32_t n_cols = static_cast<int32_t>(bases.size());
+            const int32_t r0 = sc.r0, n_rows = sc.n_rows;
+            for (int32_t c0 = 0; c0 < n_cols; c0 += 8) {
+                const int32_t item = n_units / 8, group = n_units % 8;
+                if (static_cast<size_t>(item) * 64 >= t.strip_base.size()) {
+                    t.strip_base.resize(t.strip_base.size() + 64, 0u);
+                    t.strip_pres.resize(t.strip_pres.size() + 64, 0ull);
+                    t.strip_mask.resize(t.strip_mask.size() + 64, 0u);
+                    t.strip_slot.resize(t.strip_slot.size() + 64, -1);
+                }
+                const size_t at = static_cast<size_t>(item) * 64 + static_cast<size_t>(group) * 8;
+                for (int32_t i = 0; i < 8 && c0 + i < n_cols; ++i) {
+                    t.strip_base[at + i] = bases[c0 + i];
+                    uint64_t pres = 0;
+                    for (int32_t r = 0; r < n_rows; ++r) {
+                        const std::vector<uint32_t> &mk = row_mask[cl[r0 + r]];
+                        for (int32_t s8 = 0; s8 < 8; ++s8)
+                            if (mk[static_cast<size_t>(c0 + i) * 8 + s8] != 0u)
+                                pres |= 1ull << (8 * r + s8);
+                    }
+                    t.strip_pres[at + i] = pres;
+                }
+                for (int32_t r = 0; r < n_rows; ++r) {
+                    t.strip_mask[at + r] = row_um[cl[r0 + r]];
+                    link_units[cl[r0 + r]].push_back({item, group, r});
+                }
+                n_units += 1;
+            }
+        }
+        if (grouped) {
+            n_units = (n_units + 7) & ~7;
+            for (int32_t b = cur_block + 1; b <= n_gblocks; ++b) gblk_strip_ptr[b] = n_units / 8;
+        }
+        for (const std::vector<int32_t> &cl : clusters)
+            for (int32_t e : cl) {
+                t.n_strip_rows += 1;
+                row_base[e].clear(); row_base[e].shrink_to_fit();
+                row_mask[e].clear(); row_mask[e].shrink_to_fit();
+            }
+    }
+    t.n_strip_items = static_cast<int32_t>(t.strip_base.size() / 64);
+    t.strip_base.resize(t.strip_base.size() + 64, 0u);          // one spare item keeps the
+    t.strip_pres.resize(t.strip_pres.size() + 64, 0ull);        // arrays loadable
+    t.strip_mask.resize(t.strip_mask.size() + 64, 0u);
+    t.strip_slot.resize(t.strip_slot.size() + 64, -1);
+    for (int32_t e = 0; e < n_links; ++e) t.n_octets += static_cast<int64_t>(row_base[e].size());
+
+    // Work items: pieces sorted by (block, numbering, window, kind, covered commodities, link),
+    // up to kTileRows pieces of one block, one window, one kind and (uniform pieces) one set of
+    // covered commodities per item: the rows of a uniform item have the same presence bits, so
+    // the kernel clears the demands of the commodities outside once per item.  Dense pieces
+    // keep their 512 masks, lane-contiguous like the masks of a pass; a uniform item stores,
+    // per column, one byte of presence bits that serves all its rows.
     std::vector<int32_t> item_piece;                      // [kTileRows * n_tile_items], -1: none
     {
         std::vector<int32_t> ord(pieces.size());
@@ -812,6 +986,8 @@ static void build_streaming_layout(int32_t n_links, int32_t n_comm, const int32_
         auto kind = [&](int32_t x) { return piece_umask[x] != 0u ? 1 : 0; };
         std::sort(ord.begin(), ord.end(), [&](int32_t x, int32_t y) {
             const Piece &px = pieces[x], &py = pieces[y];
+            if (link_block[px.link] != link_block[py.link])
+                return link_block[px.link] < link_block[py.link];
             if (px.sig != py.sig) return px.sig < py.sig;
             if (px.window != py.window) return px.window < py.window;
             if (kind(x) != kind(y)) return kind(x) < kind(y);
@@ -835,7 +1011,8 @@ static void build_streaming_layout(int32_t n_links, int32_t n_comm, const int32_
             const int32_t pi = ord[i];
             const Piece &pc = pieces[pi];
             const bool uni = kind(pi) == 1;
-            const bool fresh = i == 0 || pieces[ord[i - 1]].sig != pc.sig ||
+            const bool fresh = i == 0 || link_block[pieces[ord[i - 1]].link] != link_block[pc.link] ||
+                               pieces[ord[i - 1]].sig != pc.sig ||
                                pieces[ord[i - 1]].window != pc.window ||
                                kind(ord[i - 1]) != kind(pi) ||
                                (uni && !same_cover(ord[i - 1], pi)) ||
@@ -901,8 +1078,11 @@ static void build_streaming_layout(int32_t n_links, int32_t n_comm, const int32_
     if (n_blk < by_links) n_blk = by_links;
     if (n_blk < 1) n_blk = 1;
     if (n_blk > n_links) n_blk = n_links;
+    if (grouped) n_blk = n_gblocks;              // the blocks of the link groups instead
     std::vector<std::vector<int32_t>> blk_members(static_cast<size_t>(n_blk));
-    {
+    if (grouped) {
+        for (int32_t e = 0; e < n_links; ++e) blk_members[link_block[e]].push_back(e);
+    } else {
         std::vector<int32_t> by_size(n_links);
         for (int32_t e = 0; e < n_links; ++e) by_size[e] = e;
         std::stable_sort(by_size.begin(), by_size.end(), [&](int32_t x, int32_t y) {
@@ -984,19 +1164,25 @@ static void build_streaming_layout(int32_t n_links, int32_t n_comm, const int32_
                         t.oct_mask[(ps * 64 + ln) * 8 + w8];
         t.oct_mask.swap(tmp);
     }
-    // the extra slots follow the octet slots
+    // The link's slots outside the octet range follow the octet slots: one per piece, per strip
+    // unit it has a row in, and per single-pair chunk, link after link in the flat order of
+    // the rows (so that the slots of a block's links are one range).
     const int32_t extra_slot0 = t.n_oct_slots + pad_slots;
-    t.link_sslot_ptr[n_links] = extra_slots;
-    for (int32_t &v : t.schunk_slot) v += extra_slot0;
-    for (int32_t &v : t.strip_slot)
-        if (v >= 0) v += extra_slot0;
-    for (int32_t e = 0; e <= n_links; ++e) t.link_sslot_ptr[e] += extra_slot0;
-    t.n_slots = extra_slot0 + extra_slots;
+    piece_extra.assign(pieces.size(), -1);
+    t.schunk_slot.assign(t.schunk_begin.size(), -1);
     t.pos_xslot.resize(2 * static_cast<size_t>(n_links));
     for (int32_t i = 0; i < n_links; ++i) {
-        t.pos_xslot[2 * static_cast<size_t>(i)] = t.link_sslot_ptr[t.pos_link[i]];
-        t.pos_xslot[2 * static_cast<size_t>(i) + 1] = t.link_sslot_ptr[t.pos_link[i] + 1];
+        const int32_t e = t.pos_link[i];
+        t.pos_xslot[2 * static_cast<size_t>(i)] = extra_slot0 + extra_slots;
+        for (int32_t pi : link_pieces[e]) piece_extra[pi] = extra_slots++;
+        for (const UnitRef &u : link_units[e])
+            t.strip_slot[static_cast<size_t>(u.item) * 64 + static_cast<size_t>(u.group) * 8 + u.row] =
+                extra_slot0 + extra_slots++;
+        for (int32_t c = link_chunk_first[e]; c < link_chunk_first[e + 1]; ++c)
+            t.schunk_slot[c] = extra_slot0 + extra_slots++;
+        t.pos_xslot[2 * static_cast<size_t>(i) + 1] = extra_slot0 + extra_slots;
     }
+    t.n_slots = extra_slot0 + extra_slots;
     for (int32_t it = 0; it < t.n_tile_items; ++it) {
         int32_t *d = &t.tile_desc[static_cast<size_t>(it) * kTileDescInts];
         for (int32_t r = 0; r < kTileRows; ++r) {
@@ -1004,6 +1190,46 @@ static void build_streaming_layout(int32_t n_links, int32_t n_comm, const int32_
             d[8 + r] = pi >= 0 ? extra_slot0 + piece_extra[pi] : -1;
         }
     }
+    // what the workgroup of a block of link groups needs (kGblkDescInts int32 per block):
+    //   [0] first and [1] end position   [2] first and [3] end pass
+    //   [4] first octet slot, [5] octet slots   [6] first other slot, [7] other slots
+    //   [8] first and [9] end tile item  [10] first and [11] end strip item
+    if (grouped) {
+        std::vector<int32_t> gblk_tile_ptr(static_cast<size_t>(n_gblocks) + 1, t.n_tile_items);
+        {
+            int32_t b_seen = -1;
+            for (int32_t it = 0; it < t.n_tile_items; ++it) {
+                const int32_t b = link_block[pieces[item_piece[static_cast<size_t>(it) * kTileRows]].link];
+                for (int32_t q = b_seen + 1; q <= b; ++q) gblk_tile_ptr[q] = it;
+                b_seen = b;
+            }
+        }
+        bool fits = true;
+        t.gblk_desc.assign(static_cast<size_t>(kGblkDescInts) * n_gblocks, 0);
+        for (int32_t b = 0; b < n_gblocks; ++b) {
+            int32_t *d = &t.gblk_desc[static_cast<size_t>(kGblkDescInts) * b];
+            const int32_t i0 = t.blk_pos_ptr[b], i1 = t.blk_pos_ptr[b + 1];
+            d[0] = i0;
+            d[1] = i1;
+            d[2] = t.blk_pass_ptr[b];
+            d[3] = t.blk_pass_ptr[b + 1];
+            d[4] = t.pos_slot_ptr[i0];
+            d[5] = t.pos_slot_ptr[i1] - t.pos_slot_ptr[i0];
+            d[6] = i1 > i0 ? t.pos_xslot[2 * static_cast<size_t>(i0)] : extra_slot0;
+            d[7] = i1 > i0 ? t.pos_xslot[2 * static_cast<size_t>(i1 - 1) + 1] - d[6] : 0;
+            d[8] = gblk_tile_ptr[b];
+            d[9] = gblk_tile_ptr[b + 1];
+            d[10] = gblk_strip_ptr[b];
+            d[11] = gblk_strip_ptr[b + 1];
+            const int32_t tasks = (d[3] - d[2]) + (d[9] - d[8]) + (d[11] - d[10]);
+            t.gblk_max_slots = std::max(t.gblk_max_slots, d[5] + d[7]);
+            t.gblk_max_tasks = std::max(t.gblk_max_tasks, tasks);
+            if (d[5] + d[7] > kGblkMaxSlots || i1 <= i0) fits = false;
+        }
+        t.n_gblocks = fits ? n_gblocks : 0;
+        if (!fits) t.gblk_desc.clear();
+    }
+    if (t.gblk_desc.empty()) t.gblk_desc.assign(kGblkDescInts, 0);
     // the fused kernel covers topologies whose reverse rows are octets only
     t.n_blocks = (blocks_fit && t.n_single_pairs == 0)
                      ? static_cast<int32_t>(t.blk_pos_ptr.size()) - 1 : 0;
@@ -1279,6 +1505,9 @@ extern "C" nimble_status_t nimble_host_layout_stats(int32_t n_links, int32_t n_c
     out[15] = t.rec_lane_major;
     out[16] = t.rec_dict;
     out[17] = t.n_bodies;
+    out[18] = t.n_gblocks;
+    out[19] = t.gblk_max_slots;
+    out[20] = t.gblk_max_tasks;
     return NIMBLE_OK;
 }
 
@@ -1303,7 +1532,7 @@ extern "C" nimble_status_t nimble_host_build_reverse_streaming(int32_t n_links, 
                             path_links, t);
     // decode the streaming layout the way the reduce kernel walks it: flat octets with slot
     // flags (slot -> position -> link through pos_slot_ptr and pos_link), sigma octets through the inverse numbering,
-    // and chunked single pairs (chunk slot -> link through link_sslot_ptr)
+    // and chunked single pairs (chunk slot -> link through pos_xslot)
     std::vector<int32_t> inv_sigma(static_cast<size_t>(t.sigma_size), -1);
     for (int32_t k = 0; k < n_comm; ++k)
         if (t.sigma[k] >= 0) inv_sigma[t.sigma[k]] = k;
@@ -1321,8 +1550,12 @@ extern "C" nimble_status_t nimble_host_build_reverse_streaming(int32_t n_links, 
     for (int32_t i = 0; i < n_links; ++i)
         for (int32_t sl = t.pos_slot_ptr[i]; sl < t.pos_slot_ptr[i + 1]; ++sl)
             slot_link[sl] = t.pos_link[i];
-    for (int32_t e = 0; e < n_links; ++e)
-        for (int32_t sl = t.link_sslot_ptr[e]; sl < t.link_sslot_ptr[e + 1]; ++sl) slot_link[sl] = e;
+    for (int32_t i = 0; i < n_links; ++i)
+        for (int32_t sl = t.pos_xslot[2 * static_cast<size_t>(i)];
+             sl < t.pos_xslot[2 * static_cast<size_t>(i) + 1]; ++sl) {
+            if (sl < 0 || sl >= t.n_slots || slot_link[sl] >= 0) return NIMBLE_ERR_INVALID;
+            slot_link[sl] = t.pos_link[i];
+        }
     // link blocks: every pass of a block holds slots of the block's own links only, and the
     // block's slots and links fit its capacity
     std::vector<int32_t> pass_block(t.oct_base.size() / 64, -1);
@@ -1340,6 +1573,44 @@ extern "C" nimble_status_t nimble_host_build_reverse_streaming(int32_t n_links, 
          t.blk_pass_ptr[0] != 0 ||
          t.blk_pass_ptr[t.n_blocks] != static_cast<int32_t>(t.oct_base.size() / 64)))
         return NIMBLE_ERR_INVALID;
+    // blocks of link groups: positions, passes, tile items and strip items are cut into
+    // consecutive ranges that cover everything, and whatever a block's tasks write lies in the
+    // block's own slot ranges and belongs to its own links
+    std::vector<int32_t> pass_gblock(t.oct_base.size() / 64, -1);
+    std::vector<int32_t> item_gblock(static_cast<size_t>(t.n_tile_items), -1);
+    std::vector<int32_t> sitem_gblock(static_cast<size_t>(t.n_strip_items), -1);
+    auto gdesc = [&](int32_t b) { return &t.gblk_desc[static_cast<size_t>(nimble::kGblkDescInts) * b]; };
+    for (int32_t b = 0; b < t.n_gblocks; ++b) {
+        const int32_t *d = gdesc(b);
+        const int32_t *prev = b > 0 ? gdesc(b - 1) : nullptr;
+        if (d[0] != (prev ? prev[1] : 0) || d[1] <= d[0]) return NIMBLE_ERR_INVALID;
+        if (d[2] != (prev ? prev[3] : 0) || d[3] < d[2]) return NIMBLE_ERR_INVALID;
+        if (d[8] != (prev ? prev[9] : 0) || d[9] < d[8]) return NIMBLE_ERR_INVALID;
+        if (d[10] != (prev ? prev[11] : 0) || d[11] < d[10]) return NIMBLE_ERR_INVALID;
+        if (d[4] != t.pos_slot_ptr[d[0]] || d[5] != t.pos_slot_ptr[d[1]] - d[4]) return NIMBLE_ERR_INVALID;
+        if (d[5] + d[7] > nimble::kGblkMaxSlots || d[5] + d[7] > t.gblk_max_slots)
+            return NIMBLE_ERR_INVALID;
+        for (int32_t i = d[0]; i < d[1]; ++i)
+            if (t.pos_xslot[2 * static_cast<size_t>(i)] < d[6] ||
+                t.pos_xslot[2 * static_cast<size_t>(i) + 1] > d[6] + d[7])
+                return NIMBLE_ERR_INVALID;
+        for (int32_t ps = d[2]; ps < d[3]; ++ps) pass_gblock[ps] = b;
+        for (int32_t it = d[8]; it < d[9]; ++it) item_gblock[it] = b;
+        for (int32_t it = d[10]; it < d[11]; ++it) sitem_gblock[it] = b;
+    }
+    if (t.n_gblocks > 0) {
+        const int32_t *last = gdesc(t.n_gblocks - 1);
+        if (last[1] != n_links || last[9] != t.n_tile_items || last[11] != t.n_strip_items ||
+            (t.n_octets > 0 && last[3] != static_cast<int32_t>(t.oct_base.size() / 64)))
+            return NIMBLE_ERR_INVALID;
+    }
+    auto in_gblock = [&](int32_t b, int32_t e, int32_t sl, bool octet_slot) {
+        if (t.n_gblocks == 0) return true;
+        if (b < 0) return false;
+        const int32_t *d = gdesc(b);
+        if (link_pos[e] < d[0] || link_pos[e] >= d[1]) return false;
+        return octet_slot ? (sl >= d[4] && sl < d[4] + d[5]) : (sl >= d[6] && sl < d[6] + d[7]);
+    };
     std::vector<std::vector<int64_t>> rows(n_links);      // (commodity << 8 | path) per link
     const size_t n_flat = t.oct_base.size();
     int32_t slot = -1;
@@ -1353,6 +1624,8 @@ extern "C" nimble_status_t nimble_host_build_reverse_streaming(int32_t n_links, 
             if (b < 0 || link_pos[e] < t.blk_pos_ptr[b] || link_pos[e] >= t.blk_pos_ptr[b + 1])
                 return NIMBLE_ERR_INVALID;
         }
+        if (e >= 0 && t.n_octets > 0 && !in_gblock(pass_gblock[i / 64], e, slot, true))
+            return NIMBLE_ERR_INVALID;
         const int32_t base = static_cast<int32_t>(w & ~3u);
         for (int32_t s8 = 0; s8 < 8; ++s8) {
             const uint32_t m = t.oct_mask[(i / 64) * 512 + (s8 / 4) * 256 + (i % 64) * 4 + (s8 % 4)];
@@ -1372,6 +1645,7 @@ extern "C" nimble_status_t nimble_host_build_reverse_streaming(int32_t n_links, 
             const int32_t sl = d[8 + r];
             if (sl < 0 || sl >= t.n_slots || slot_link[sl] < 0) return NIMBLE_ERR_INVALID;
             const int32_t e = slot_link[sl];
+            if (!in_gblock(item_gblock[it], e, sl, false)) return NIMBLE_ERR_INVALID;
             const bool uni = (d[1] & 2) != 0;
             const size_t at = 512 * static_cast<size_t>(d[3] + r);      // dense piece
             for (int32_t c = 0; c < 64; ++c)
@@ -1404,6 +1678,7 @@ extern "C" nimble_status_t nimble_host_build_reverse_streaming(int32_t n_links, 
                 const int32_t sl = t.strip_slot[ur];
                 if (sl < 0 || sl >= t.n_slots || slot_link[sl] < 0) return NIMBLE_ERR_INVALID;
                 const int32_t e = slot_link[sl];
+                if (!in_gblock(sitem_gblock[it], e, sl, false)) return NIMBLE_ERR_INVALID;
                 const uint32_t m = t.strip_mask[ur];
                 if (!m) return NIMBLE_ERR_INVALID;
                 for (int32_t s8 = 0; s8 < 8; ++s8) {

@@ -96,6 +96,16 @@ constexpr int32_t kStripMinRows = 3;
 constexpr int32_t kBlkMaxSlots = 1024;
 constexpr int32_t kBlkMaxLinks = 512;
 
+// Link groups (tiled layouts).  The links are cut into groups whose tile items, strip units and
+// octets hold rows of the group's links only, and the groups are dealt to blocks of about equal
+// work; the rows, items, strips and passes of a block are contiguous in their arrays, and so
+// are its partial-sum slots (octet slots; piece and strip slots).  One workgroup can then
+// reduce everything its links receive into LDS and apply their length update.  A layout whose
+// largest block needs more than kGblkMaxSlots slots has no such blocks (n_gblocks = 0); the
+// arrays are the same either way, so the separate reduce and update kernels run on them too.
+constexpr int32_t kGblkDescInts = 16;
+constexpr int32_t kGblkMaxSlots = 4096;
+
 // ---- forward CSR records ------------------------------------------------------------------
 // The forward CSR is repacked into self-contained records of kRecBytes bytes, each holding a
 // run of consecutive commodities: a wave fetches one record with four 16-byte loads per lane
@@ -200,20 +210,26 @@ struct HostTopo {
     std::vector<int32_t> pos_link;       // [E] link of every position of the flat order
     std::vector<int32_t> pos_slot_ptr;   // [E+1] octet slots of a position
     std::vector<int32_t> pos_xslot;      // [2 * E] first and end of the link's other slots
-                                         // (link_sslot_ptr), by position
+                                         // (pieces, strip units, single-pair chunks), by
+                                         // position
     std::vector<int32_t> blk_pos_ptr;    // [n_blocks+1] first position of a block
     std::vector<int32_t> blk_pass_ptr;   // [n_blocks+1] first pass of a block
     std::vector<int32_t> blk_desc;       // [8 * n_blocks] what one workgroup of the fused kernel
                                          // needs: first and end position, first and end pass,
                                          // first slot, three zeros
+    int32_t link_groups = -1;            // option: 0 = no link groups, else build them where
+                                         // the layout is tiled
+    int32_t grp_target = 0;              // option: blocks to deal the groups to (0: 256)
+    int32_t n_gblocks = 0;               // blocks of link groups (0: none)
+    std::vector<int32_t> gblk_desc;      // [kGblkDescInts * n_gblocks], see host_topo.cpp
+    int32_t gblk_max_slots = 0;          // most partial-sum slots of a block
+    int32_t gblk_max_tasks = 0;          // most tile items + strip items + passes of a block
     int32_t n_oct_slots = 0;
     std::vector<int32_t> sigma;          // [K] second numbering, -1 = none
     int32_t sigma_size = 0;              // length of the sigma-ordered copies (multiple of 8)
     std::vector<uint32_t> single_pair;   // [2 * n_singles_padded], rows padded to 2 pairs
     int64_t n_single_pairs = 0;          // unpadded
     std::vector<int32_t> schunk_begin, schunk_end, schunk_slot;   // pair units
-    std::vector<int32_t> link_sslot_ptr; // [E+1] piece and single-chunk slots of a link (after
-                                         // all octet slots)
     int32_t n_slots = 0;                 // octet slots + single-chunk slots
     // forward records (n_records = 0 when the topology does not fit them: a path longer than
     // kRecMaxStride links, padding above 1.5x, or a commodity that alone overflows a record)

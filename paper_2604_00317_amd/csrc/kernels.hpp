@@ -54,6 +54,12 @@ struct DeviceTopo {
     int32_t n_blocks;
     const int32_t *blk_desc;          // [8 * n_blocks]: first position, end position, first
                                       // pass, end pass, first slot, 0, 0, 0
+    // blocks of link groups (tiled layouts; n_gblocks = 0: separate reduce and update kernels)
+    int32_t n_gblocks;
+    const int32_t *gblk_desc;         // [16 * n_gblocks]: positions, passes, octet slots, other
+                                      // slots, tile items, strip items (first and end each)
+    int32_t gblk_max_slots;           // most partial-sum slots of a block (LDS of the kernel)
+    int32_t gblk_waves;               // waves per workgroup of the kernel: 4, 8 or 16
     const uint32_t *single_pair;      // [2 * padded singles]
     const int32_t *schunk_begin, *schunk_end, *schunk_slot;   // [n_schunks], pair units
     const int2 *pos_xslot;            // [E] first and end of the piece, strip and single-chunk
@@ -122,6 +128,10 @@ void launch_load_reduce(const DeviceTopo &t, const uint8_t *choice, const double
 void launch_histogram(const DeviceTopo &t, const uint8_t *log, size_t stride, int32_t iters,
                       double *splits, hipStream_t s);
 void launch_update(const DeviceTopo &t, double eps, hipStream_t s);
+// reduce and update in one launch for tiled layouts cut into blocks of link groups
+// (t.n_gblocks > 0): every per-wave maximum of S goes to scalars[1 + block * gblk_waves + wave]
+void launch_group_reduce_update(const DeviceTopo &t, const uint8_t *choice, double eps,
+                                hipStream_t s);
 // reduce and update in one launch; only for topologies with link blocks (t.n_blocks > 0)
 void launch_reduce_update(const DeviceTopo &t, const uint8_t *choice, const double *demand,
                           double eps, hipStream_t s);

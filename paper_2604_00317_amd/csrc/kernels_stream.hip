@@ -775,6 +775,130 @@ __global__ __launch_bounds__(kBlock) void k_reduce_update(FusedArgs a)
     }
 }
 
+// The same for tiled layouts whose links are cut into groups: a workgroup owns a block of link
+// groups -- its tile items, strip items and octet passes hold rows of the block's links only --
+// reduces them into slot partials kept in LDS (a wave takes the block's tasks w, w + waves, ...
+// of each kind, the kinds starting at different waves), and then applies the length update of
+// exactly those links, RL lanes per link, with the additions of update_phase in the same order.
+// len, S and 1/cap are stored by position, so the state of the first round of links is
+// requested before the tasks are walked.  Every wave leaves its maximum of S in
+// scalars[1 + block * waves + wave].
+struct GroupArgs {
+    const int32_t *gblk_desc;
+    const int32_t *tile_desc;
+    const uint32_t *tile_mask;
+    const uint8_t *tile_pres;
+    const uint32_t *strip_base, *strip_mask;
+    const uint64_t *strip_pres;
+    const int32_t *strip_slot;
+    const int32_t *pass_first_slot;
+    const uint32_t *oct_base, *oct_mask;
+    const int32_t *pos_link, *pos_slot_ptr;
+    const int2 *pos_xslot;
+    const uint8_t *choice, *choice2;
+    const double *demand1n, *demand2;      // the library's padded copies, by id and by sigma
+    const double *demand1t, *demand2t;     // the same, window-transposed
+    const double *invcap_pos;
+    double *len, *price, *S, *scalars;
+    double eps;
+    PlanStrides ps;
+};
+
+template <bool MAXC, int RL, bool EXT>
+__global__ __launch_bounds__(1024) void k_group_reduce_update(GroupArgs a)
+{
+    extern __shared__ double s_slots[];
+    if constexpr (EXT) {      // a batch (blockIdx.y is the plan) or a solve that may stop early
+        if (stopped(a.ps)) return;
+        a.choice = of_plan(a.choice, a.ps.row);
+        a.choice2 = of_plan(a.choice2, a.ps.state);
+        a.demand1n = of_plan(a.demand1n, a.ps.state);
+        a.demand2 = of_plan(a.demand2, a.ps.state);
+        a.demand1t = of_plan(a.demand1t, a.ps.state);
+        a.demand2t = of_plan(a.demand2t, a.ps.state);
+        a.len = of_plan(a.len, a.ps.state);
+        a.price = of_plan(a.price, a.ps.state);
+        a.S = of_plan(a.S, a.ps.state);
+        a.scalars = of_plan(a.scalars, a.ps.state);
+    }
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n_waves = blockDim.x >> 6;
+    const int b = blockIdx.x;
+    const int4 *dsc = reinterpret_cast<const int4 *>(a.gblk_desc + 16 * b);
+    const int4 d0 = dsc[0], d1 = dsc[1], d2 = dsc[2];
+    const int i0 = d0.x, i1 = d0.y;             // positions of the block (at least one)
+    const int p0 = d0.z, p1 = d0.w;             // its passes
+    const int os0 = d1.x, n_os = d1.y;          // its octet slots: LDS 0 .. n_os - 1
+    const int xs0 = d1.z;                       // its other slots: LDS n_os ...
+    const int t0 = d2.x, t1 = d2.y;             // its tile items
+    const int s0 = d2.z, s1 = d2.w;             // its strip items
+    const int xbase = xs0 - n_os;               // other slot s sits at s - xbase
+    const double invrho = a.scalars[0];
+    const int row = threadIdx.x / RL;
+    const int l = threadIdx.x % RL;
+    const int rows = blockDim.x / RL;
+    struct Link {
+        int e, c0, c1, x0, x1;
+        double ic, s, l;
+    };
+    // positions past the end re-read the last one (so that every load is unconditional) and
+    // are masked out when the update is applied
+    auto fetch = [&](int i) {
+        const int ic = i < i1 ? i : i1 - 1;
+        Link st;
+        st.e = a.pos_link[ic];
+        st.c0 = a.pos_slot_ptr[ic] - os0;
+        st.c1 = a.pos_slot_ptr[ic + 1] - os0;
+        const int2 xs = a.pos_xslot[ic];
+        st.x0 = xs.x - xbase;
+        st.x1 = xs.y - xbase;
+        st.ic = a.invcap_pos[ic];
+        st.s = a.S[ic];
+        st.l = a.len[ic];
+        return st;
+    };
+    double smax = 0.0;
+    auto apply = [&](int i, const Link &st) {
+        const bool valid = i < i1;
+        const double load = row_partial_sum<RL>(st.c0, valid ? st.c1 : st.c0, l, s_slots) +
+                            row_partial_sum<RL>(st.x0, valid ? st.x1 : st.x0, l, s_slots);
+        if (valid && l == 0) {
+            const double u = load * st.ic;
+            const double s_new = st.s + u;
+            a.S[i] = s_new;
+            const double g = u * invrho;
+            const double t1e = a.eps * g;
+            const double t2e = 1.0 + t1e;
+            const double ln = st.l * t2e;
+            a.len[i] = ln;
+            a.price[st.e] = MAXC ? ln : ln * st.ic;
+            smax = fmax(smax, s_new);
+        }
+    };
+    const Link first = fetch(i0 + row);
+    // tile items from wave 0 on, strip items where those end, octet passes after them
+    const int nt = t1 - t0, ns = s1 - s0;
+    int w = wave;
+    reduce_tile_phase<0>(nt, a.tile_desc + size_t(t0) * kTileDescInts, a.tile_mask, a.tile_pres,
+                         a.choice, a.demand1t, a.choice2, a.demand2t, s_slots, w, n_waves, lane,
+                         xbase);
+    w = (wave + n_waves - nt % n_waves) % n_waves;
+    reduce_strip_phase<0>(ns, a.strip_base + size_t(s0) * kWave, a.strip_pres + size_t(s0) * kWave,
+                          a.strip_mask + size_t(s0) * kWave, a.strip_slot + size_t(s0) * kWave,
+                          a.choice, a.demand1n, a.choice2, a.demand2, s_slots, w, n_waves, lane,
+                          xbase);
+    w = (wave + 2 * n_waves - nt % n_waves - ns % n_waves) % n_waves;
+    reduce_flat_phase<0>(p0, p1, a.pass_first_slot, a.oct_base, a.oct_mask, a.choice, a.demand1n,
+                         a.choice2, a.demand2, s_slots, os0, w, n_waves, lane);
+    __syncthreads();
+    apply(i0 + row, first);
+    for (int ibase = i0 + rows; ibase < i1; ibase += rows)               // block-uniform
+        apply(ibase + row, fetch(ibase + row));
+    const double m = wave_max(smax);
+    if (lane == 0) a.scalars[1 + b * n_waves + wave] = m;
+}
+
 // The same for batches, U plans per workgroup: the four waves split the passes of the block as
 // in the single-plan kernel, and every wave sums its pass for all U plans at once
 // (reduce_flat_phase_multi), so that one trip to memory serves U plans.  A 16-lane row then
@@ -1332,6 +1456,58 @@ void launch_update(const DeviceTopo &t, double eps, hipStream_t s)
 #undef NIMBLE_UPDATE_LAUNCH
 }
 
+void launch_group_reduce_update(const DeviceTopo &t, const uint8_t *choice, double eps,
+                                hipStream_t s)
+{
+    GroupArgs a;
+    a.gblk_desc = t.gblk_desc;
+    a.tile_desc = t.tile_desc;
+    a.tile_mask = t.tile_mask;
+    a.tile_pres = t.tile_pres;
+    a.strip_base = t.strip_base;
+    a.strip_mask = t.strip_mask;
+    a.strip_pres = t.strip_pres;
+    a.strip_slot = t.strip_slot;
+    a.pass_first_slot = t.pass_first_slot;
+    a.oct_base = t.oct_base;
+    a.oct_mask = t.oct_mask;
+    a.pos_link = t.pos_link;
+    a.pos_slot_ptr = t.pos_slot_ptr;
+    a.pos_xslot = t.pos_xslot;
+    a.choice = choice;
+    a.choice2 = t.choice2;
+    a.demand1n = t.demand1n;
+    a.demand2 = t.demand2;
+    a.demand1t = t.demand1t;
+    a.demand2t = t.demand2t;
+    a.invcap_pos = t.invcap_pos;
+    a.len = t.len;
+    a.price = t.price;
+    a.S = t.S;
+    a.scalars = t.scalars;
+    a.eps = eps;
+    a.ps = strides_of(t);
+    const dim3 block(kWave * t.gblk_waves);
+    const size_t lds = sizeof(double) * static_cast<size_t>(t.gblk_max_slots > 0 ? t.gblk_max_slots : 1);
+#define NIMBLE_GROUP_LAUNCH(MC, RL)                                                            \
+    do {                                                                                       \
+        if (extended(t))                                                                       \
+            hipLaunchKernelGGL((k_group_reduce_update<MC, RL, true>),                          \
+                               dim3(t.n_gblocks, t.batch), block, lds, s, a);                  \
+        else                                                                                   \
+            hipLaunchKernelGGL((k_group_reduce_update<MC, RL, false>), dim3(t.n_gblocks),      \
+                               block, lds, s, a);                                              \
+    } while (0)
+    if (t.update_lanes == 4) {
+        if (t.cost_max) NIMBLE_GROUP_LAUNCH(true, 4);
+        else NIMBLE_GROUP_LAUNCH(false, 4);
+    } else {
+        if (t.cost_max) NIMBLE_GROUP_LAUNCH(true, 16);
+        else NIMBLE_GROUP_LAUNCH(false, 16);
+    }
+#undef NIMBLE_GROUP_LAUNCH
+}
+
 void launch_reduce_update(const DeviceTopo &t, const uint8_t *choice, const double *demand,
                           double eps, hipStream_t s)
 {
@@ -1416,9 +1592,11 @@ int launch_reduce_u(const DeviceTopo &t, const uint8_t *choice, double *u_pos,
 void launch_epilogue(const DeviceTopo &t, int32_t iters, const uint32_t *count, double *splits,
                      double *lambda, hipStream_t s)
 {
-    // the last length update left one maximum of S per block: link blocks when the fused
-    // kernel ran, update blocks otherwise
-    const int n_max = t.n_blocks > 0 ? t.n_blocks * (kBlock / kWave) : t.n_update_blocks;
+    // the last length update left one maximum of S per wave or block: of the link blocks or the
+    // blocks of link groups when a fused kernel ran, of the update blocks otherwise
+    const int n_max = t.n_blocks > 0    ? t.n_blocks * (kBlock / kWave)
+                      : t.n_gblocks > 0 ? t.n_gblocks * t.gblk_waves
+                                        : t.n_update_blocks;
     const int grid = count ? blocks_for(t.P, kBlock, 4096) : 1;
     hipLaunchKernelGGL(k_epilogue, dim3(grid, t.batch), dim3(kBlock), 0, s, t.P, iters, n_max,
                        count, t.scalars, splits, lambda, strides_of(t));

@@ -452,10 +452,11 @@ __device__ __forceinline__ void reduce_tile_phase(
     const uint8_t *__restrict__ tile_pres,
     const uint8_t *__restrict__ choice, const double *__restrict__ demand1t,
     const uint8_t *__restrict__ choice2, const double *__restrict__ demand2t,
-    double *__restrict__ partial, int wave, int n_waves, int lane)
+    double *__restrict__ partial, int wave, int n_waves, int lane, int slot_base = 0)
 {
     // demand1t / demand2t: the demands by id / by sigma number, window-transposed
-    // (tile_demand_index)
+    // (tile_demand_index); slot s goes to partial[s - slot_base] (global memory, or the LDS of
+    // a block of link groups)
     const u32x4 *masks = reinterpret_cast<const u32x4 *>(tile_mask);
     const int my_row = tile_row_of_lane(lane);
     // the item index lives in a scalar register, so the descriptor words that all lanes share
@@ -532,7 +533,7 @@ __device__ __forceinline__ void reduce_tile_phase(
             }
         }
         const double total = wave_sum8(acc, lane);
-        if (lane < 8 && my_row < n_rows) partial[my_slot] = total;
+        if (lane < 8 && my_row < n_rows) partial[my_slot - slot_base] = total;
     }
 }
 
@@ -549,7 +550,7 @@ __device__ __forceinline__ void reduce_strip_phase(
     const uint32_t *__restrict__ strip_mask, const int32_t *__restrict__ strip_slot,
     const uint8_t *__restrict__ choice, const double *__restrict__ demand1n,
     const uint8_t *__restrict__ choice2, const double *__restrict__ demand2,
-    double *__restrict__ partial, int wave, int n_waves, int lane)
+    double *__restrict__ partial, int wave, int n_waves, int lane, int slot_base = 0)
 {
     const int my_row = tile_row_of_lane(lane);
     const int unit0 = lane & ~7;
@@ -592,7 +593,7 @@ __device__ __forceinline__ void reduce_strip_phase(
             acc[r] = a;
         }
         const double total = group8_sum8(acc, lane);
-        if (my_slot >= 0) partial[my_slot] = total;
+        if (my_slot >= 0) partial[my_slot - slot_base] = total;
     }
 }
 

@@ -224,10 +224,45 @@ def test_tiled_reverse_layout_decodes_to_the_same_rows(monkeypatch, min_items):
         st = B.nimble_host_layout_stats(*args)
         assert st["link_blocks"] == 0                  # tiles and link blocks exclude each other
         assert (st["pieces"] + 7) // 8 <= st["tile_items"] <= st["pieces"]
+        # the links are cut into groups that own their items, strips and octets (the decoder
+        # above checks that nothing a block's tasks write belongs to another block's links)
+        # (commodities with more than 32 candidates leave single pairs: no groups then)
+        assert (1 if st["singles"] == 0 else 0) <= st["group_blocks"] <= min(256, t.n_links)
+        assert st["group_block_max_slots"] <= 4096 and st["group_block_max_tasks"] >= 0
     # the 16-node fabric has dense windows at every threshold tried here
     assert st["pieces"] >= 0 and B.nimble_host_layout_stats(
         *(lambda t: (t.n_links, t.n_comm, t.comm_path_ptr, t.n_paths, t.path_link_ptr,
                      t.path_links))(topos[2]))["pieces"] > 0
+
+
+@pytest.mark.parametrize("env", [{"NIMBLE_TUNE_LINK_GROUPS": "0"}, {"NIMBLE_TUNE_GROUP_BLOCKS": "1"},
+                                 {"NIMBLE_TUNE_GROUP_BLOCKS": "7"},
+                                 {"NIMBLE_TUNE_GROUP_BLOCKS": "5000"}],
+                         ids=["no-groups", "one-block", "seven-blocks", "a-block-per-group"])
+def test_link_groups_of_a_tiled_layout(monkeypatch, env):
+    """Tiled layouts deal their link groups to a chosen number of blocks; whatever the number,
+    and without groups at all, the layout decodes to the same rows."""
+    monkeypatch.setenv("NIMBLE_TUNE_TILES", "1")
+    monkeypatch.setenv("NIMBLE_TUNE_TILE_MIN_ITEMS", "24")
+    for name, value in env.items():
+        monkeypatch.setenv(name, value)
+    topos = [W.config_topology(c) for c in (1, 3)]
+    topos.append(W.random_topology(np.random.default_rng(12), 300, 700, 31, 2))
+    for t in topos:
+        args = (t.n_links, t.n_comm, t.comm_path_ptr, t.n_paths, t.path_link_ptr, t.path_links)
+        a = B.nimble_host_build_reverse(*args)
+        b = B.nimble_host_build_reverse(*args, streaming=True)
+        for x, y in zip(a, b):
+            assert np.array_equal(x, y)
+        st = B.nimble_host_layout_stats(*args)
+        if "NIMBLE_TUNE_LINK_GROUPS" in env:
+            assert st["group_blocks"] == 0
+        elif env["NIMBLE_TUNE_GROUP_BLOCKS"] == "1":
+            # (one block for everything overflows the slots a workgroup keeps on the 16-node
+            # fabric: then there are no blocks and the separate kernels run)
+            assert st["group_blocks"] in (0, 1)
+        else:
+            assert 1 <= st["group_blocks"] <= int(env["NIMBLE_TUNE_GROUP_BLOCKS"])
 
 
 def test_link_blocks_are_dropped_when_a_row_overflows_a_block():

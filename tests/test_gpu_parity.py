@@ -437,6 +437,32 @@ def test_tiled_reverse_layout(oracle_mod, B, monkeypatch, min_items):
         check(oracle_mod, B, t, d, 0.1, 40, regime=2)
 
 
+@pytest.mark.parametrize("env", [{"NIMBLE_TUNE_LINK_GROUPS": "0"}, {"NIMBLE_TUNE_GROUP_BLOCKS": "1"},
+                                 {"NIMBLE_TUNE_GROUP_BLOCKS": "7", "NIMBLE_TUNE_GROUP_WAVES": "4"},
+                                 {"NIMBLE_TUNE_GROUP_BLOCKS": "40", "NIMBLE_TUNE_GROUP_WAVES": "16"},
+                                 {"NIMBLE_TUNE_GROUP_BLOCKS": "5000", "NIMBLE_TUNE_GROUP_WAVES": "8"}],
+                         ids=["no-groups", "one-block", "seven-blocks-4-waves",
+                              "forty-blocks-16-waves", "a-block-per-group-8-waves"])
+def test_link_groups_reduce_and_update_in_one_launch(oracle_mod, B, monkeypatch, env):
+    """A tiled layout whose links are cut into groups runs the link-load reduce and the length
+    update of a block of groups in one workgroup (partial sums in LDS).  Any number of blocks
+    and any workgroup size must give the oracle's plan, and so must the same layout without
+    groups (two kernels)."""
+    monkeypatch.setenv("NIMBLE_TUNE_TILES", "1")
+    monkeypatch.setenv("NIMBLE_TUNE_TILE_MIN_ITEMS", "24")
+    for name, value in env.items():
+        monkeypatch.setenv(name, value)
+    for cfg, iters in ((1, 300), (3, 60)):
+        w = W.make_config(cfg)
+        print(f"[groups] cfg={cfg} env={env}", flush=True)
+        check(oracle_mod, B, w.topo, w.traffic, w.eps, iters, regime=2)
+        check(oracle_mod, B, w.topo, w.traffic, w.eps, iters, regime=2, flags=1)
+    rng = np.random.default_rng(12)
+    t = W.random_topology(rng, 300, 700, 31, 2)
+    d = rng.integers(0, 1 << 30, size=t.n_comm).astype(np.float64)
+    check(oracle_mod, B, t, d, 0.1, 40, regime=2)
+
+
 def test_row_too_long_for_a_link_block(oracle_mod, B):
     """600 000 single-path commodities on one link: the row needs more partial-sum slots than a
     link block holds, so the streaming regime runs the separate reduce and update kernels."""
