@@ -45,8 +45,9 @@ enum {
                              rule of Sec. IV-B (intra-node 2-hop and inter-node path costs) */
     NIMBLE_LAYOUT_BATCH = 2u /* the topology will mostly solve batches of plans in the streaming
                              regime (nimble_topo_reserve_batch): lay the reverse CSR out for
-                             launches that cover many plans, at the price of slower single
-                             plans on mid-size fabrics.  Results do not depend on it. */
+                             launches that cover many plans (tuned for batches of about 16),
+                             at the price of slower single plans on mid-size fabrics.
+                             Results do not depend on it. */
 };
 
 /* kernel regimes, for nimble_topo_set_regime (testing and benchmarking) */

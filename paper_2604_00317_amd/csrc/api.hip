@@ -421,7 +421,13 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
         // a topology meant for batches takes the tiled reverse layout whatever its size: its
         // choices and demands are fetched window by window, which is what bounds a launch that
         // covers many plans (a single plan of a mid-size fabric is faster with link blocks)
-        if (flags & NIMBLE_LAYOUT_BATCH) h.tiles = 1;
+        // (and few, large blocks of link groups: 16 blocks x 16 plans put one workgroup of the
+        // fused reduce + update kernel on every compute unit; pieces from 64 commodities on)
+        if (flags & NIMBLE_LAYOUT_BATCH) {
+            h.tiles = 1;
+            h.grp_target = 16;
+            h.tile_min_items = 64;
+        }
         if (g_fail_host_alloc.exchange(0) != 0) throw std::bad_alloc();      // test hook
         nimble::read_layout_options(h);
         nimble::build_host_topo(n_links, cap, n_comm, comm_path_ptr, n_paths, path_link_ptr,

@@ -493,10 +493,10 @@ __device__ __forceinline__ void reduce_tile_phase(
             for (int sl = 0; sl < 8; ++sl) dz[sl] = ((p0 >> sl) & 1u) != 0u ? dm[sl] : 0.0;
 #pragma unroll
             for (int r = 0; r < kTileRows; ++r) {
-                // rows past the last piece carry an empty mask
-                const uint32_t mr = r < n_rows ? static_cast<uint32_t>(
-                                                     __builtin_amdgcn_readfirstlane(d[16 + r]))
-                                               : 0u;
+                acc[r] = 0.0;
+                if (r >= n_rows) continue;          // wave-uniform: rows past the last piece
+                const uint32_t mr =
+                    static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(d[16 + r]));
                 double a = 0.0;
 #pragma unroll
                 for (int sl = 0; sl < 8; ++sl) {
