@@ -975,8 +975,9 @@ nimble_status_t nimble_plan_solve_adaptive(nimble_topo_t *topo, const double *d_
         if (e == hipSuccess) e = allocate(topo, n_chunks, &a.chunk);
         if (e == hipSuccess) e = allocate(topo, static_cast<size_t>(d.E), &a.u_pos);
         if (e == hipSuccess)
-            e = allocate(topo, std::max((static_cast<size_t>(d.E) + 15) / 16,
-                                        static_cast<size_t>(4) * static_cast<size_t>(d.n_blocks)),
+            e = allocate(topo, std::max({(static_cast<size_t>(d.E) + 15) / 16,
+                                         static_cast<size_t>(4) * static_cast<size_t>(d.n_blocks),
+                                         static_cast<size_t>(16) * static_cast<size_t>(d.n_gblocks)}),
                          &a.block_max_u);
         if (e == hipSuccess && !a.host_words_host) {
             // two words of pinned host memory the device writes and the host polls
@@ -1057,6 +1058,10 @@ nimble_status_t nimble_plan_solve_adaptive(nimble_topo_t *topo, const double *d_
         if (d.n_blocks > 0) {
             // link blocks: normalised loads in one launch, then the step
             const int n_u = nimble::launch_reduce_u(dd, row, a.u_pos, a.block_max_u, s);
+            nimble::launch_ad_apply(dd, a, eps, n_u, s);
+        } else if (d.n_gblocks > 0) {
+            // blocks of link groups: the same with the tiled layout's kernel
+            const int n_u = nimble::launch_group_reduce_u(dd, row, a.u_pos, a.block_max_u, s);
             nimble::launch_ad_apply(dd, a, eps, n_u, s);
         } else {
             nimble::launch_load_reduce(dd, row, d_traffic, s);

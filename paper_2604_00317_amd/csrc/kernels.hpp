@@ -132,6 +132,10 @@ void launch_update(const DeviceTopo &t, double eps, hipStream_t s);
 // (t.n_gblocks > 0): every per-wave maximum of S goes to scalars[1 + block * gblk_waves + wave]
 void launch_group_reduce_update(const DeviceTopo &t, const uint8_t *choice, double eps,
                                 hipStream_t s);
+// the same up to the normalised loads (adaptive step): u by position and one maximum of u per
+// wave; returns the number of maxima written
+int launch_group_reduce_u(const DeviceTopo &t, const uint8_t *choice, double *u_pos,
+                          double *block_max_u, hipStream_t s);
 // reduce and update in one launch; only for topologies with link blocks (t.n_blocks > 0)
 void launch_reduce_update(const DeviceTopo &t, const uint8_t *choice, const double *demand,
                           double eps, hipStream_t s);

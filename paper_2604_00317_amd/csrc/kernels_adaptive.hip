@@ -143,26 +143,35 @@ __global__ __launch_bounds__(kAdBlock) void k_ad_apply(
     double *__restrict__ sigma_log, double *__restrict__ block_max_s)
 {
     __shared__ double red[16];
-    if (flags[0]) return;
+    // the stop word, the link's own state and the maxima are requested together (threads past
+    // the last link re-read it), so that one trip to memory serves all three
+    const int32_t stop_now = *static_cast<const volatile int32_t *>(flags);
+    const int i = blockIdx.x * kAdBlock + threadIdx.x;
+    const int ic = i < E ? i : E - 1;
+    const double u_i = u_pos[ic];
+    const double s_old = S[ic];
+    const double l_old = len[ic];
+    const double cap_i = invcap_pos[ic];
+    const int e_i = pos_link[ic];
     double m = 0.0;
     for (int b = threadIdx.x; b < n_u_blocks; b += kAdBlock) m = fmax(m, block_max_u[b]);
+    if (stop_now != 0) return;
     const double umax = block_max(m, red);
     if (!(umax > 0.0)) {                               // no traffic at all: the solve ends here
         if (blockIdx.x == 0 && threadIdx.x == 0) flags[0] = 1;
         return;
     }
     const double sigma = 1.0 / umax;
-    const int i = blockIdx.x * kAdBlock + threadIdx.x;
     double s_new = 0.0;
     if (i < E) {
-        const double su = sigma * u_pos[i];
-        s_new = S[i] + su;
+        const double su = sigma * u_i;
+        s_new = s_old + su;
         S[i] = s_new;
         const double t1 = eps * su;
         const double t2 = 1.0 + t1;
-        const double ln = len[i] * t2;
+        const double ln = l_old * t2;
         len[i] = ln;
-        price[pos_link[i]] = MAXC ? ln : ln * invcap_pos[i];
+        price[e_i] = MAXC ? ln : ln * cap_i;
     }
     __syncthreads();
     const double sm = block_max(s_new, red);

@@ -318,8 +318,9 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records,
 {
     static_assert(L >= 2 && L <= 16 && S <= kRecLaneSteps,
                   "lane-major records: 2 to 16 lanes per commodity, five steps");
+    int32_t stop_now = 0;
     if constexpr (EXT) {      // a batch (blockIdx.y is the plan) or a solve that may stop early
-        if (stopped(ps)) return;
+        stop_now = stop_word(ps);            // tested below, once the first loads are under way
         price = of_plan(price, ps.state);
         choice = of_plan(choice, ps.row);
         count = of_plan(count, ps.state);
@@ -410,6 +411,8 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records,
     pr[3] = price[tab.d];
     if (rec + n_waves < n_records) tab = table_of(rec + n_waves);
     body_of(rec, body);
+    if constexpr (EXT)
+        if (stop_now != 0) return;                      // nothing has been written yet
     for (; rec < n_records; rec += n_waves) {           // wave-uniform
         wave_lds_sync();                                // the previous record is done with LDS
 #pragma unroll
@@ -484,8 +487,9 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recd(int n_chunks, 
 {
     static_assert(L >= 2 && L <= 16 && S <= kRecLaneSteps,
                   "lane-major records: 2 to 16 lanes per commodity, five steps");
+    int32_t stop_now = 0;
     if constexpr (EXT) {      // a batch (blockIdx.y is the plan) or a solve that may stop early
-        if (stopped(ps)) return;
+        stop_now = stop_word(ps);            // tested below, once the first loads are under way
         price = of_plan(price, ps.state);
         choice = of_plan(choice, ps.row);
         count = of_plan(count, ps.state);
@@ -526,6 +530,8 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recd(int n_chunks, 
     pr[3] = price[head.y >> 16];
     int32_t own_next = static_cast<int32_t>(head.z);
     if (rec + 1 < end) head = head_of(rec + 1);
+    if constexpr (EXT)
+        if (stop_now != 0) return;                      // nothing has been written yet
     for (; rec < end; ++rec) {                          // wave-uniform
         wave_lds_sync();                                // the previous record is done with LDS
 #pragma unroll
@@ -769,9 +775,18 @@ __global__ __launch_bounds__(kBlock) void k_reduce_update(FusedArgs a)
     for (int ibase = i0 + 2 * kRows; ibase < i1; ibase += kRows)         // block-uniform, rare
         apply(ibase + row, fetch(ibase + row));
     const double m = wave_max(smax);
-    if (lane == 0) {
-        if constexpr (ONLY_U) a.block_max_u[b * (kBlock / kWave) + wave] = m;
-        else a.scalars[1 + b * (kBlock / kWave) + wave] = m;
+    if constexpr (ONLY_U) {
+        // one maximum per block: the kernel that applies the step folds them all
+        __syncthreads();                                // the slots are free again
+        if (lane == 0) s_part[wave] = m;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            double mm = 0.0;
+            for (int q = 0; q < kBlock / kWave; ++q) mm = fmax(mm, s_part[q]);
+            a.block_max_u[b] = mm;
+        }
+    } else if (lane == 0) {
+        a.scalars[1 + b * (kBlock / kWave) + wave] = m;
     }
 }
 
@@ -802,9 +817,12 @@ struct GroupArgs {
     double *len, *price, *S, *scalars;
     double eps;
     PlanStrides ps;
+    double *u_pos, *block_max_u;     // adaptive step only
 };
 
-template <bool MAXC, int RL, bool EXT>
+// ONLY_U (adaptive step): stops at u = load / cap (by position, to a.u_pos) and leaves every
+// wave's maximum of u in a.block_max_u, as k_reduce_update does.
+template <bool MAXC, int RL, bool EXT, bool ONLY_U = false>
 __global__ __launch_bounds__(1024) void k_group_reduce_update(GroupArgs a)
 {
     extern __shared__ double s_slots[];
@@ -865,15 +883,20 @@ __global__ __launch_bounds__(1024) void k_group_reduce_update(GroupArgs a)
                             row_partial_sum<RL>(st.x0, valid ? st.x1 : st.x0, l, s_slots);
         if (valid && l == 0) {
             const double u = load * st.ic;
-            const double s_new = st.s + u;
-            a.S[i] = s_new;
-            const double g = u * invrho;
-            const double t1e = a.eps * g;
-            const double t2e = 1.0 + t1e;
-            const double ln = st.l * t2e;
-            a.len[i] = ln;
-            a.price[st.e] = MAXC ? ln : ln * st.ic;
-            smax = fmax(smax, s_new);
+            if constexpr (ONLY_U) {
+                a.u_pos[i] = u;
+                smax = fmax(smax, u);
+            } else {
+                const double s_new = st.s + u;
+                a.S[i] = s_new;
+                const double g = u * invrho;
+                const double t1e = a.eps * g;
+                const double t2e = 1.0 + t1e;
+                const double ln = st.l * t2e;
+                a.len[i] = ln;
+                a.price[st.e] = MAXC ? ln : ln * st.ic;
+                smax = fmax(smax, s_new);
+            }
         }
     };
     const Link first = fetch(i0 + row);
@@ -896,7 +919,19 @@ __global__ __launch_bounds__(1024) void k_group_reduce_update(GroupArgs a)
     for (int ibase = i0 + rows; ibase < i1; ibase += rows)               // block-uniform
         apply(ibase + row, fetch(ibase + row));
     const double m = wave_max(smax);
-    if (lane == 0) a.scalars[1 + b * n_waves + wave] = m;
+    if constexpr (ONLY_U) {
+        // one maximum per block: the kernel that applies the step folds them all
+        __syncthreads();                                // the slots are free again
+        if (lane == 0) s_slots[wave] = m;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            double mm = 0.0;
+            for (int q = 0; q < n_waves; ++q) mm = fmax(mm, s_slots[q]);
+            a.block_max_u[b] = mm;
+        }
+    } else if (lane == 0) {
+        a.scalars[1 + b * n_waves + wave] = m;
+    }
 }
 
 // The same for batches, U plans per workgroup: the four waves split the passes of the block as
@@ -1456,8 +1491,7 @@ void launch_update(const DeviceTopo &t, double eps, hipStream_t s)
 #undef NIMBLE_UPDATE_LAUNCH
 }
 
-void launch_group_reduce_update(const DeviceTopo &t, const uint8_t *choice, double eps,
-                                hipStream_t s)
+static GroupArgs group_args(const DeviceTopo &t, const uint8_t *choice, double eps)
 {
     GroupArgs a;
     a.gblk_desc = t.gblk_desc;
@@ -1487,6 +1521,32 @@ void launch_group_reduce_update(const DeviceTopo &t, const uint8_t *choice, doub
     a.scalars = t.scalars;
     a.eps = eps;
     a.ps = strides_of(t);
+    a.u_pos = nullptr;
+    a.block_max_u = nullptr;
+    return a;
+}
+
+int launch_group_reduce_u(const DeviceTopo &t, const uint8_t *choice, double *u_pos,
+                          double *block_max_u, hipStream_t s)
+{
+    GroupArgs a = group_args(t, choice, 0.0);
+    a.u_pos = u_pos;
+    a.block_max_u = block_max_u;
+    const dim3 block(kWave * t.gblk_waves);
+    const size_t lds = sizeof(double) * static_cast<size_t>(t.gblk_max_slots > 16 ? t.gblk_max_slots : 16);
+    if (t.update_lanes == 4)
+        hipLaunchKernelGGL((k_group_reduce_update<false, 4, true, true>), dim3(t.n_gblocks), block,
+                           lds, s, a);
+    else
+        hipLaunchKernelGGL((k_group_reduce_update<false, 16, true, true>), dim3(t.n_gblocks),
+                           block, lds, s, a);
+    return t.n_gblocks;
+}
+
+void launch_group_reduce_update(const DeviceTopo &t, const uint8_t *choice, double eps,
+                                hipStream_t s)
+{
+    const GroupArgs a = group_args(t, choice, eps);
     const dim3 block(kWave * t.gblk_waves);
     const size_t lds = sizeof(double) * static_cast<size_t>(t.gblk_max_slots > 0 ? t.gblk_max_slots : 1);
 #define NIMBLE_GROUP_LAUNCH(MC, RL)                                                            \
@@ -1586,7 +1646,7 @@ int launch_reduce_u(const DeviceTopo &t, const uint8_t *choice, double *u_pos,
     a.block_max_u = block_max_u;
     hipLaunchKernelGGL((k_reduce_update<false, true, true>), dim3(t.n_blocks), dim3(kBlock), 0, s,
                        a);
-    return t.n_blocks * (kBlock / kWave);
+    return t.n_blocks;
 }
 
 void launch_epilogue(const DeviceTopo &t, int32_t iters, const uint32_t *count, double *splits,

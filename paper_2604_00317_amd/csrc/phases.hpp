@@ -57,6 +57,14 @@ struct PlanStrides {
     const int32_t *stop;
 };
 
+// The stop word itself, requested here and now (a volatile load the compiler leaves in place):
+// a kernel that has other loads to issue first tests the value after them, so that the trip to
+// memory for this word overlaps with theirs instead of preceding everything.
+__device__ __forceinline__ int32_t stop_word(const PlanStrides &ps)
+{
+    return ps.stop != nullptr ? *static_cast<const volatile int32_t *>(ps.stop) : 0;
+}
+
 __device__ __forceinline__ bool stopped(const PlanStrides &ps)
 {
     return ps.stop != nullptr && *ps.stop != 0;
