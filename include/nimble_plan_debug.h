@@ -134,7 +134,7 @@ nimble_status_t nimble_host_records_roundtrip(int32_t n_links, int32_t n_comm,
 
 /*
  * Host-only helper (no device call): sizes of the device layout nimble_topo_create would build.
- * out is host int64 [21]: (commodity, window) pairs of the reverse CSR; octets (groups of 8
+ * out is host int64 [22]: (commodity, window) pairs of the reverse CSR; octets (groups of 8
  * consecutive commodity ids with one mask each); single pairs; octets numbered by the second
  * commodity numbering; single-pair chunks; partial-sum slots; forward records; indices per
  * candidate in a record; link blocks of the fused reduce + update kernel (0: not used); octets
@@ -146,7 +146,8 @@ nimble_status_t nimble_host_records_roundtrip(int32_t n_links, int32_t n_comm,
  * else 0; the number of distinct bodies in that dictionary; blocks of link groups (tiled layouts
  * whose links can be cut into groups with tile items, strip units and octets of their own: the
  * reduce and the length update of a block then run in one workgroup; 0: none); the most
- * partial-sum slots and the most work items of such a block.
+ * partial-sum slots and the most work items of such a block; the bodies of the dictionary whose
+ * quads all have the two-by-two product shape (nine price reads per quad instead of twenty).
  */
 nimble_status_t nimble_host_layout_stats(int32_t n_links, int32_t n_comm,
                                          const int32_t *comm_path_ptr, int32_t n_paths,

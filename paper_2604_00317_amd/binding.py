@@ -407,7 +407,7 @@ def nimble_host_layout_stats(n_links, n_comm, comm_path_ptr, n_paths, path_link_
     cp = _host(comm_path_ptr, np.int32)
     lp = _host(path_link_ptr, np.int32)
     pl = _host(path_links, np.int32)
-    out = np.zeros(21, dtype=np.int64)
+    out = np.zeros(22, dtype=np.int64)
     st = load_library().nimble_host_layout_stats(n_links, n_comm, _hp(cp), n_paths, _hp(lp),
                                                  _hp(pl), _hp(out))
     if st != NIMBLE_OK:
@@ -415,7 +415,8 @@ def nimble_host_layout_stats(n_links, n_comm, comm_path_ptr, n_paths, path_link_
     keys = ["pairs", "octets", "singles", "octets_sigma", "single_chunks", "slots", "records",
             "record_stride", "link_blocks", "octets_padded", "pieces", "tile_items",
             "pieces_uniform", "strip_items", "strip_rows", "records_lane_major", "records_dict",
-            "record_bodies", "group_blocks", "group_block_max_slots", "group_block_max_tasks"]
+            "record_bodies", "group_blocks", "group_block_max_slots", "group_block_max_tasks",
+            "record_bodies_product"]
     return dict(zip(keys, (int(v) for v in out)))
 
 

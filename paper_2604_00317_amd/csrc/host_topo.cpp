@@ -94,6 +94,7 @@ void read_layout_options(HostTopo &t)
     number("NIMBLE_TUNE_RECORD_LANE_MAJOR", 0, 1, t.rec_lane_major);
     number("NIMBLE_TUNE_RECORD_TABLE16", 0, 1, t.rec_table16);
     number("NIMBLE_TUNE_RECORD_DICT", 0, 1, t.rec_dict);
+    number("NIMBLE_TUNE_RECORD_PRODUCT_QUADS", 0, 1, t.rec_product_quads);
     number("NIMBLE_TUNE_BLOCK_PASSES", 1, 1024, t.blk_passes);
     number("NIMBLE_TUNE_TILES", 0, 1, t.tiles);
     number("NIMBLE_TUNE_TILE_MIN_ITEMS", 1, kTileIds, t.tile_min_items);
@@ -102,6 +103,93 @@ void read_layout_options(HostTopo &t)
     int32_t dense_only = 0;
     number("NIMBLE_TUNE_TILES_DENSE_ONLY", 0, 1, dense_only);
     t.tiles_dense_only = dense_only != 0;
+}
+
+// ---- quads of a two-by-two product ---------------------------------------------------------
+// Candidate lists built by a product rule (rail x egress GPU x ingress GPU, two GPUs per rail)
+// put four candidates into a quad that differ only in (egress, ingress): their first two links
+// depend on the egress alone, the middle link on neither, the last two on the ingress alone.
+// Adding +0.0 is exact wherever it happens in the left-to-right sum of a path, so the padding
+// of a short path may sit anywhere among its steps: this tries to shift the links of every
+// candidate of a quad (keeping their order) so that, step by step, the quad reads
+//   step 0: x x y y   step 1: x x y y   step 2: x x x x   step 3: x y x y   step 4: x y x y
+// The record kernel then fetches 9 prices for the quad instead of 20 and shares the partial
+// sums.  q5[c][i] is the table index of step i of candidate c (kRecZeroSlot = padding); on
+// success the shifted indices are written back.  Absent candidates (first index kRecInfSlot)
+// are never shifted.
+static bool align_product_quad(uint8_t (&q5)[4][kRecLaneSteps])
+{
+    int32_t len[4];
+    uint8_t links[4][kRecLaneSteps];
+    bool absent[4];
+    for (int32_t c = 0; c < 4; ++c) {
+        len[c] = 0;
+        absent[c] = q5[c][0] == kRecInfSlot;
+        for (int32_t i = 0; i < kRecLaneSteps; ++i)
+            if (q5[c][i] != kRecZeroSlot) links[c][len[c]++] = q5[c][i];
+        if (len[c] == 0) return false;
+    }
+    uint8_t out[4][kRecLaneSteps];
+    auto place = [&](int32_t c, int32_t shift) {
+        for (int32_t i = 0; i < kRecLaneSteps; ++i) out[c][i] = static_cast<uint8_t>(kRecZeroSlot);
+        for (int32_t i = 0; i < len[c]; ++i) out[c][shift + i] = links[c][i];
+    };
+    auto fits = [&]() {
+        for (int32_t i = 0; i < kRecLaneSteps; ++i) {
+            const uint8_t a = out[0][i], b = out[1][i], c = out[2][i], d = out[3][i];
+            const bool ok = i < 2 ? (a == b && c == d) : i == 2 ? (a == b && b == c && c == d)
+                                                                : (a == c && b == d);
+            if (!ok) return false;
+        }
+        return true;
+    };
+    int32_t hi[4];
+    for (int32_t c = 0; c < 4; ++c) hi[c] = absent[c] ? 0 : kRecLaneSteps - len[c];
+    for (int32_t s0 = 0; s0 <= hi[0]; ++s0)
+        for (int32_t s1 = 0; s1 <= hi[1]; ++s1)
+            for (int32_t s2 = 0; s2 <= hi[2]; ++s2)
+                for (int32_t s3 = 0; s3 <= hi[3]; ++s3) {
+                    place(0, s0);
+                    place(1, s1);
+                    place(2, s2);
+                    place(3, s3);
+                    if (!fits()) continue;
+                    for (int32_t c = 0; c < 4; ++c)
+                        for (int32_t i = 0; i < kRecLaneSteps; ++i) q5[c][i] = out[c][i];
+                    return true;
+                }
+    return false;
+}
+
+// Brings the A quads (bit 0 of the result) and the B quads (bit 1) of all 64 lanes of a
+// lane-major body into the product shape where every lane allows it; `words` holds
+// kRecLaneWords words per lane and is rewritten for the quads that succeed.
+static uint32_t align_product_body(std::vector<uint32_t> &words)
+{
+    uint32_t product = 0u;
+    for (int32_t q = 0; q < 2; ++q) {
+        std::vector<uint32_t> trial(words);
+        bool all = true;
+        for (int32_t lane = 0; lane < 64 && all; ++lane) {
+            uint32_t *w = &trial[static_cast<size_t>(lane) * kRecLaneWords +
+                                 static_cast<size_t>(q) * kRecLaneSteps];
+            uint8_t q5[4][kRecLaneSteps];
+            for (int32_t c4 = 0; c4 < 4; ++c4)
+                for (int32_t i = 0; i < kRecLaneSteps; ++i)
+                    q5[c4][i] = static_cast<uint8_t>((w[i] >> (8 * c4)) & 0xFFu);
+            all = align_product_quad(q5);
+            for (int32_t i = 0; i < kRecLaneSteps && all; ++i) {
+                w[i] = 0u;
+                for (int32_t c4 = 0; c4 < 4; ++c4)
+                    w[i] |= static_cast<uint32_t>(q5[c4][i]) << (8 * c4);
+            }
+        }
+        if (all) {
+            words.swap(trial);
+            product |= 1u << q;
+        }
+    }
+    return product;
 }
 
 // ---- forward records ----------------------------------------------------------------------
@@ -118,6 +206,7 @@ static void build_forward_records_once(int32_t n_links, int32_t n_comm,
     t.records.clear();
     t.rec_stride = t.lmax;
     t.n_bodies = 0;
+    t.n_bodies_product = 0;
     t.rec_dict_words.clear();
     t.rec_body.clear();
     bool dict = false;
@@ -308,12 +397,21 @@ static void build_forward_records_once(int32_t n_links, int32_t n_comm,
                         body_ids.emplace(std::move(key), id);
                         const size_t at = t.rec_dict_words.size();
                         t.rec_dict_words.resize(at + 3 * 64 * 4, 0u);
+                        // quads of a two-by-two product: where the A quads (or the B quads) of
+                        // all 64 lanes can be brought into that shape, the body stores them so
+                        // and says it in word 11 (bit 0: A quads, bit 1: B quads), the same in
+                        // every lane
+                        std::vector<uint32_t> stored(words);
+                        const uint32_t product = (t.rec_product_quads != 0 && S == kRecLaneSteps)
+                                                     ? align_product_body(stored) : 0u;
                         for (int32_t lane = 0; lane < 64; ++lane)
                             for (int32_t it = 0; it < 3; ++it)
                                 for (int32_t q = 0; q < 4; ++q)
-                                    if (4 * it + q < 11)
-                                        t.rec_dict_words[at + (static_cast<size_t>(it) * 64 + lane) * 4 + q] =
-                                            words[static_cast<size_t>(lane) * kRecLaneWords + 4 * it + q];
+                                    t.rec_dict_words[at + (static_cast<size_t>(it) * 64 + lane) * 4 + q] =
+                                        4 * it + q < 11
+                                            ? stored[static_cast<size_t>(lane) * kRecLaneWords + 4 * it + q]
+                                            : product;
+                        if (product == 3u) t.n_bodies_product += 1;
                     } else {
                         id = found->second;
                     }
@@ -327,6 +425,12 @@ static void build_forward_records_once(int32_t n_links, int32_t n_comm,
                     if (nl > t.rec_max_links) t.rec_max_links = nl;
                     continue;
                 }
+                // bodies kept in the record: the same product shape where the quads allow it; the
+                // two bits go to word 11 of lane 2L + 1 (slot 2, second lane: no sigma, not one
+                // of the record's own words)
+                if (t.rec_product_quads != 0 && S == kRecLaneSteps)
+                    words[static_cast<size_t>(2 * L + 1) * kRecLaneWords + 11] =
+                        align_product_body(words);
                 for (int32_t lane = 0; lane < 64; ++lane)
                     for (int32_t it = 0; it < 3; ++it)
                         std::memcpy(body + 1024 * it + 16 * lane,
@@ -1399,6 +1503,34 @@ extern "C" nimble_status_t nimble_host_records_roundtrip(int32_t n_links, int32_
             if (k0 != next_comm || nk < 1 || nk > 64 / L || p0 != comm_path_ptr[k0])
                 return NIMBLE_ERR_INVALID;
             next_comm = k0 + nk;
+            // quads flagged as two-by-two products must have that shape in every lane: the
+            // record kernel reads nine of their twenty indices and takes the rest as equal
+            {
+                uint32_t product = 0u;
+                if (t.rec_dict)
+                    product = t.rec_dict_words[(static_cast<size_t>(t.rec_body[ri]) * 3 + 2) * 256 + 3];
+                else if (t.rec_stride == nimble::kRecLaneSteps)
+                    product = word(2 * L + 1, 11);
+                if (product > 3u) return NIMBLE_ERR_INVALID;
+                for (int32_t lane = 0; lane < 64; ++lane) {
+                    if (t.rec_dict &&
+                        t.rec_dict_words[(static_cast<size_t>(t.rec_body[ri]) * 3 + 2) * 256 +
+                                         4 * lane + 3] != product)
+                        return NIMBLE_ERR_INVALID;
+                    for (int32_t q = 0; q < 2; ++q) {
+                        if (!((product >> q) & 1u)) continue;
+                        for (int32_t i = 0; i < nimble::kRecLaneSteps; ++i) {
+                            const uint32_t v = word(lane, q * nimble::kRecLaneSteps + i);
+                            const uint32_t a = v & 0xFFu, b = (v >> 8) & 0xFFu,
+                                           c = (v >> 16) & 0xFFu, d = v >> 24;
+                            const bool ok = i < 2 ? (a == b && c == d)
+                                                  : i == 2 ? (a == b && b == c && c == d)
+                                                           : (a == c && b == d);
+                            if (!ok) return NIMBLE_ERR_INVALID;
+                        }
+                    }
+                }
+            }
             for (int32_t g = 0; g < 64 / L; ++g) {
                 const uint32_t meta = word(g * L, 10);
                 for (int32_t j = 1; j < L; ++j)
@@ -1505,6 +1637,7 @@ extern "C" nimble_status_t nimble_host_layout_stats(int32_t n_links, int32_t n_c
     out[15] = t.rec_lane_major;
     out[16] = t.rec_dict;
     out[17] = t.n_bodies;
+    out[21] = t.n_bodies_product;
     out[18] = t.n_gblocks;
     out[19] = t.gblk_max_slots;
     out[20] = t.gblk_max_tasks;

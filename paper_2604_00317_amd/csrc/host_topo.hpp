@@ -137,7 +137,9 @@ constexpr int32_t kGblkMaxSlots = 4096;
 //   word 10              candidates of the commodity (low byte) | its first candidate relative
 //                        to p0, shifted left by 8; 0 for an empty slot
 //   word 11              lane 0 of a slot: sigma of the commodity; lane 1 of slot 0:
-//                        k0 | nk << 24; lane 1 of slot 1: p0
+//                        k0 | nk << 24; lane 1 of slot 1: p0; lane 1 of slot 2: bit 0 = the A
+//                        quads of all lanes have the two-by-two product shape, bit 1 = the B
+//                        quads (see align_product_quad in host_topo.cpp)
 // Load `it` of lane l sits at byte kRecTable + 1024*it + 16*l.  Short paths are padded with
 // the index kRecZeroSlot and absent candidates start with kRecInfSlot (their price slots hold
 // +0.0 and +inf), so a record has at most kRecMaxLinks table entries in use.
@@ -147,7 +149,10 @@ constexpr int32_t kGblkMaxSlots = 4096;
 // candidates of the record index its link table, not which commodities or links they are, so
 // on fabrics built by a product rule (rail x egress x ingress) thousands of records share a few
 // dozen bodies.  The bodies then live once in a dictionary (kRecBodyBytes each: load `it` of
-// lane l at 1024*it + 16*l as above, word 11 zero) that stays in the L2, and a record shrinks
+// lane l at 1024*it + 16*l as above; word 11, the same in all lanes, says whether the A quads
+// (bit 0) and the B quads (bit 1) of the body have the two-by-two product shape, in which the
+// record kernel fetches 9 prices per quad instead of 20) that stays in the L2, and a record
+// shrinks
 // to kRecBytesDict: 16 bytes per lane -- its four 16-bit table entries, its word 11, and the
 // number of the record's body (the same in all lanes).  Records are stored sorted by body, so
 // a wave that walks a run of records of one body fetches the body once.
@@ -243,7 +248,10 @@ struct HostTopo {
     int32_t rec_dict = -1;               // option in (-1: when it pays, 0: never, 1: whenever
                                          // the format allows), layout out (0 / 1): bodies in a
                                          // dictionary, records of kRecBytesDict
+    int32_t rec_product_quads = 1;       // option: 0 = never store quads in the two-by-two
+                                         // product shape (see align_product_quad)
     int32_t n_bodies = 0;                // distinct bodies
+    int32_t n_bodies_product = 0;        // of which with all quads in the product shape
     std::vector<uint32_t> rec_dict_words; // [n_bodies * kRecBodyBytes / 4]
     std::vector<int32_t> rec_body;       // [n_records] body of every record (ascending)
     int32_t rec_bytes = 0;               // bytes of a record: kRecBytes, kRecBytes16 or

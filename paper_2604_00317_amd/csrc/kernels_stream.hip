@@ -141,6 +141,34 @@ __device__ __forceinline__ void scan_quad(const double *s_price, const uint32_t 
     i4 = cst[0] == m4 ? 0 : (cst[1] == m4 ? 1 : (cst[2] == m4 ? 2 : 3));
 }
 
+// The same for a quad in the two-by-two product shape (step 0 and 1: candidates 0, 1 and 2, 3
+// read the same slot; step 2: all four; step 3 and 4: candidates 0, 2 and 1, 3): nine prices
+// instead of twenty, and the partial sums the candidates share are formed once.  Every
+// candidate's cost is still ((((p0 + p1) + p2) + p3) + p4 in that order.
+template <bool MAXC>
+__device__ __forceinline__ void scan_quad_product(const double *s_price, const uint32_t *w,
+                                                  double &m4, int &i4)
+{
+    auto op = [](double acc, double pe) {
+        if constexpr (MAXC) return (pe > acc) ? pe : acc;
+        else return acc + pe;
+    };
+    const double a0 = s_price[w[0] & 0xFFu], a2 = s_price[(w[0] >> 16) & 0xFFu];
+    const double b0 = s_price[w[1] & 0xFFu], b2 = s_price[(w[1] >> 16) & 0xFFu];
+    const double c = s_price[w[2] & 0xFFu];
+    const double d0 = s_price[w[3] & 0xFFu], d1 = s_price[(w[3] >> 8) & 0xFFu];
+    const double e0 = s_price[w[4] & 0xFFu], e1 = s_price[(w[4] >> 8) & 0xFFu];
+    const double t0 = op(op(a0, b0), c);
+    const double t2 = op(op(a2, b2), c);
+    double cst[4];
+    cst[0] = op(op(t0, d0), e0);
+    cst[1] = op(op(t0, d1), e1);
+    cst[2] = op(op(t2, d0), e0);
+    cst[3] = op(op(t2, d1), e1);
+    m4 = fast_min_f64(fast_min_f64(cst[0], cst[1]), fast_min_f64(cst[2], cst[3]));
+    i4 = cst[0] == m4 ? 0 : (cst[1] == m4 ? 1 : (cst[2] == m4 ? 2 : 3));
+}
+
 template <int L, int S, bool MAXC, bool TWO, bool EXT>
 __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records,
                                                       const uint8_t *__restrict__ records,
@@ -440,8 +468,13 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records,
         const int ja = 4 * j, jb = 4 * j + 4 * L;
         double ma, mb;
         int ia, ib;
-        scan_quad<S, MAXC>(s_price, w, ma, ia);
-        scan_quad<S, MAXC>(s_price, w + kRecLaneSteps, mb, ib);
+        // which quads of the record have the two-by-two product shape: lane 1 of slot 2
+        const uint32_t product =
+            S == kRecLaneSteps ? static_cast<uint32_t>(__builtin_amdgcn_readlane(own, 2 * L + 1)) : 0u;
+        if (product & 1u) scan_quad_product<MAXC>(s_price, w, ma, ia);            // wave-uniform
+        else scan_quad<S, MAXC>(s_price, w, ma, ia);
+        if (product & 2u) scan_quad_product<MAXC>(s_price, w + kRecLaneSteps, mb, ib);
+        else scan_quad<S, MAXC>(s_price, w + kRecLaneSteps, mb, ib);
         // the strict `<` scan in candidate order: quad A first; absent candidates cost +inf
         double best = __builtin_inf();
         int bj = ja < np ? ja : 0x7FFFFFFF;
@@ -520,6 +553,8 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recd(int n_chunks, 
     const u32x4 b0 = bsrc[0], b1 = bsrc[kWave], b2 = bsrc[2 * kWave];
     const uint32_t w[10] = {b0.x, b0.y, b0.z, b0.w, b1.x, b1.y, b1.z, b1.w, b2.x, b2.y};
     const uint32_t meta = b2.z;
+    // which quads of the body have the two-by-two product shape (the same word in all lanes)
+    const uint32_t product = S == kRecLaneSteps ? __builtin_amdgcn_readfirstlane(b2.w) : 0u;
     const int np = static_cast<int>(meta & 0xFFu);
     const int p_lo = static_cast<int>(meta >> 8);
     const int ja = 4 * j, jb = 4 * j + 4 * L;
@@ -552,8 +587,10 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recd(int n_chunks, 
         wave_lds_sync();
         double ma, mb;
         int ia, ib;
-        scan_quad<S, MAXC>(s_price, w, ma, ia);
-        scan_quad<S, MAXC>(s_price, w + kRecLaneSteps, mb, ib);
+        if (product & 1u) scan_quad_product<MAXC>(s_price, w, ma, ia);            // wave-uniform
+        else scan_quad<S, MAXC>(s_price, w, ma, ia);
+        if (product & 2u) scan_quad_product<MAXC>(s_price, w + kRecLaneSteps, mb, ib);
+        else scan_quad<S, MAXC>(s_price, w + kRecLaneSteps, mb, ib);
         // the strict `<` scan in candidate order: quad A first; absent candidates cost +inf
         double best = __builtin_inf();
         int bj = ja < np ? ja : 0x7FFFFFFF;

@@ -68,7 +68,7 @@ int main(int argc, char **argv)
         std::fprintf(stderr, "the forward records do not read back the incidences\n");
         return 7;
     }
-    int64_t stats[21] = {0};
+    int64_t stats[22] = {0};
     if (nimble_host_layout_stats(E, K, cp.data(), P, lp.data(), pl.data(), stats) != NIMBLE_OK)
         return 8;
     std::printf("OK records %d pairs %lld octets %lld pieces %lld blocks %lld bodies %lld groups %lld\n", n_rec,

@@ -124,6 +124,9 @@ RECORD_FORMATS = {
     "default": {},
     "lane-major, 32-bit table": {"NIMBLE_TUNE_RECORD_TABLE16": "0"},
     "record-major": {"NIMBLE_TUNE_RECORD_LANE_MAJOR": "0"},
+    "lane-major, no product quads": {"NIMBLE_TUNE_RECORD_PRODUCT_QUADS": "0"},
+    "lane-major, no product quads, bodies in a dictionary": {
+        "NIMBLE_TUNE_RECORD_PRODUCT_QUADS": "0", "NIMBLE_TUNE_RECORD_DICT": "1"},
 }
 
 
@@ -141,6 +144,14 @@ def test_forward_records_round_trip(cfg, fmt, monkeypatch):
     assert st["records_lane_major"] == int(lane_major)
     if "dictionary" in fmt and lane_major:
         assert st["records_dict"] == 1 and 1 <= st["record_bodies"] <= n_rec
+        # rail x egress x ingress: most quads are two-by-two products, and the bodies whose
+        # quads all are say so (the decoder above checks every flagged quad, lane by lane)
+        if "no product" in fmt:
+            assert st["record_bodies_product"] == 0
+        else:
+            # (on the two-node fabric every record also holds pairs inside a node, whose
+            # candidates are no product)
+            assert (1 if cfg == 3 else 0) <= st["record_bodies_product"] <= st["record_bodies"]
     if fmt == "default":
         # three records per body on the 16-node fabric: not enough for the dictionary to pay
         assert st["records_dict"] == 0

@@ -362,13 +362,17 @@ def test_edge_cases(oracle_mod, B, regime):
                                  {"NIMBLE_TUNE_RECORD_DICT": "1",
                                   "NIMBLE_TUNE_NO_CHOICE_LOG": "1"},
                                  {"NIMBLE_TUNE_RECORD_DICT": "1",
-                                  "NIMBLE_TUNE_RECORDS_PER_WAVE": "3"}],
+                                  "NIMBLE_TUNE_RECORDS_PER_WAVE": "3"},
+                                 {"NIMBLE_TUNE_RECORD_PRODUCT_QUADS": "0"},
+                                 {"NIMBLE_TUNE_RECORD_PRODUCT_QUADS": "0",
+                                  "NIMBLE_TUNE_RECORD_DICT": "1"}],
                          ids=["lane-major-32", "record-major", "record-major-counters",
                               "lane-major-16-counters", "lane-major-16-around-l2",
                               "lane-major-32-around-l2", "lane-major-16-inline",
                               "lane-major-16-inline-around-l2", "dictionary",
                               "dictionary-around-l2", "dictionary-counters",
-                              "dictionary-runs-of-3"])
+                              "dictionary-runs-of-3", "inline-twenty-reads-per-quad",
+                              "dictionary-twenty-reads-per-quad"])
 def test_every_forward_record_format(oracle_mod, B, monkeypatch, env, flags):
     """The default on these fabrics is lane-major record bodies with 16-bit link tables, kept
     once each in a dictionary where records share them (the 16-node fabric) and inline otherwise;
@@ -376,7 +380,10 @@ def test_every_forward_record_format(oracle_mod, B, monkeypatch, env, flags):
     body.  The 32-bit table (fabrics of more than 65535 links) and the record-major body (more than five
     links per path, or fewer than nine candidates per commodity) must give the same plans, with
     the choice log and with per-path counters.  Records that exceed the L2 are fetched with
-    loads that bypass it; the switch forces those loads on fabrics of any size."""
+    loads that bypass it; the switch forces those loads on fabrics of any size.  Quads of four
+    candidates that differ only in (egress, ingress) are stored in a shape of which the kernel
+    reads 9 prices instead of 20 (the default on these fabrics); the last two cases switch that
+    off."""
     for name, value in env.items():
         monkeypatch.setenv(name, value)
     for cfg, iters in ((1, 120), (3, 60)):
