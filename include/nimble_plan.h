@@ -306,8 +306,9 @@ int64_t nimble_topo_bytes_per_iter(const nimble_topo_t *topo);
  * the forward CSR, 1: link-load reduce over the reverse CSR, 2: length update).  On topologies
  * whose reduce and update run as one kernel, phase 1 covers both and phase 2 is 0.  Phase 3 is
  * not memory traffic: the bytes the path-cost kernel reads from LDS per launch (one 8-byte
- * price per candidate step), 0 for the kernels that do not keep the prices of a record in LDS
- * lane by lane. */
+ * price per candidate step, or nine per four candidates that share their first and last
+ * links pairwise), 0 for the kernels that do not keep the prices of a record in LDS lane by
+ * lane. */
 int64_t nimble_topo_phase_bytes(const nimble_topo_t *topo, int32_t phase);
 
 /* Force a kernel regime (NIMBLE_REGIME_*) for later solves; NIMBLE_ERR_RANGE if the topology

@@ -688,10 +688,10 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
         t->bytes_update = 0;
     }
     t->bytes_per_iter = t->bytes_argmin + t->bytes_reduce + t->bytes_update;
-    // lane-major record kernels: every lane reads, per record, one 8-byte price from LDS for
-    // every step of the 8 candidates of its two quads (padding steps included)
-    if (d.n_records > 0 && d.rec_lane_major)
-        t->bytes_lds_argmin = static_cast<int64_t>(d.n_records) * 64 * 8 * 8 * d.rec_stride;
+    // lane-major record kernels: every lane reads 8-byte prices from LDS, per record one for
+    // every step of the 8 candidates of its two quads (padding steps included), or 9 for a
+    // quad in the product shape
+    if (d.n_records > 0 && d.rec_lane_major) t->bytes_lds_argmin = 64 * 8 * h.rec_price_reads;
     *out = t;
     return NIMBLE_OK;
 }

@@ -207,6 +207,7 @@ static void build_forward_records_once(int32_t n_links, int32_t n_comm,
     t.rec_stride = t.lmax;
     t.n_bodies = 0;
     t.n_bodies_product = 0;
+    t.rec_price_reads = 0;
     t.rec_dict_words.clear();
     t.rec_body.clear();
     bool dict = false;
@@ -420,6 +421,11 @@ static void build_forward_records_once(int32_t n_links, int32_t n_comm,
                         r32[4 * lane + 2] = words[static_cast<size_t>(lane) * kRecLaneWords + 11];
                         r32[4 * lane + 3] = static_cast<uint32_t>(id);
                     }
+                    {
+                        const uint32_t pb = t.rec_dict_words[(static_cast<size_t>(id) * 3 + 2) * 256 + 3];
+                        t.rec_price_reads += ((pb & 1u) ? 9 : 4 * kRecLaneSteps) +
+                                             ((pb & 2u) ? 9 : 4 * kRecLaneSteps);
+                    }
                     t.rec_body.push_back(id);
                     t.n_records += 1;
                     if (nl > t.rec_max_links) t.rec_max_links = nl;
@@ -431,6 +437,11 @@ static void build_forward_records_once(int32_t n_links, int32_t n_comm,
                 if (t.rec_product_quads != 0 && S == kRecLaneSteps)
                     words[static_cast<size_t>(2 * L + 1) * kRecLaneWords + 11] =
                         align_product_body(words);
+                {
+                    const uint32_t pb = S == kRecLaneSteps
+                                            ? words[static_cast<size_t>(2 * L + 1) * kRecLaneWords + 11] : 0u;
+                    t.rec_price_reads += ((pb & 1u) ? 9 : 4 * S) + ((pb & 2u) ? 9 : 4 * S);
+                }
                 for (int32_t lane = 0; lane < 64; ++lane)
                     for (int32_t it = 0; it < 3; ++it)
                         std::memcpy(body + 1024 * it + 16 * lane,

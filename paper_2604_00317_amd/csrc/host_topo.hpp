@@ -252,6 +252,8 @@ struct HostTopo {
                                          // product shape (see align_product_quad)
     int32_t n_bodies = 0;                // distinct bodies
     int32_t n_bodies_product = 0;        // of which with all quads in the product shape
+    int64_t rec_price_reads = 0;         // lane-major records: price reads per lane, summed
+                                         // over the records (9 or 4 * stride per quad)
     std::vector<uint32_t> rec_dict_words; // [n_bodies * kRecBodyBytes / 4]
     std::vector<int32_t> rec_body;       // [n_records] body of every record (ascending)
     int32_t rec_bytes = 0;               // bytes of a record: kRecBytes, kRecBytes16 or
