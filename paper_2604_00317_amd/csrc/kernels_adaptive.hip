@@ -47,8 +47,26 @@ __global__ __launch_bounds__(kAdBlock) void k_ad_terms(int K, const int32_t *__r
 // null) redirects term i to x[index[i]].  A workgroup owns kAdChunksPerBlock chunks: all its
 // threads fetch the terms side by side (coalesced) into LDS, a padded row per chunk so that
 // the rows start in different banks, and one thread per chunk then adds its row in order.
-constexpr int kAdChunksPerBlock = 16;
+constexpr int kAdChunksPerBlock = 4;
 constexpr int kAdRow = kAdChunk + 1;
+
+// x[0] + x[1] + ... + x[n-1] added strictly in that order by one thread.  The additions form
+// one dependent chain whatever is done; what can be avoided is waiting for every term in turn:
+// sixteen terms are fetched side by side, then added one after the other.
+__device__ __forceinline__ double ordered_sum(const double *x, int n)
+{
+    double s = 0.0;
+    int i = 0;
+    for (; i + 16 <= n; i += 16) {
+        double v[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) v[j] = x[i + j];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) s = s + v[j];
+    }
+    for (; i < n; ++i) s = s + x[i];
+    return s;
+}
 
 __global__ __launch_bounds__(kAdBlock) void k_ad_chunks(int n, const double *__restrict__ x,
                                                         const int32_t *__restrict__ index,
@@ -59,20 +77,25 @@ __global__ __launch_bounds__(kAdBlock) void k_ad_chunks(int n, const double *__r
     if (flags[0]) return;
     const int c0 = blockIdx.x * kAdChunksPerBlock;
     const int first = c0 * kAdChunk;
-    for (int q = threadIdx.x; q < kAdChunksPerBlock * kAdChunk; q += kAdBlock) {
-        const int i = first + q;
-        double v = 0.0;
-        if (i < n) v = x[index ? index[i] : i];
-        s_terms[(q / kAdChunk) * kAdRow + (q % kAdChunk)] = v;
+    // (all terms of the workgroup are requested before the first is stored)
+    constexpr int kPer = kAdChunksPerBlock * kAdChunk / kAdBlock;
+    double v[kPer];
+#pragma unroll
+    for (int r = 0; r < kPer; ++r) {
+        const int i = first + r * kAdBlock + static_cast<int>(threadIdx.x);
+        v[r] = 0.0;
+        if (i < n) v[r] = x[index ? index[i] : i];
+    }
+#pragma unroll
+    for (int r = 0; r < kPer; ++r) {
+        const int q = r * kAdBlock + static_cast<int>(threadIdx.x);
+        s_terms[(q / kAdChunk) * kAdRow + (q % kAdChunk)] = v[r];
     }
     __syncthreads();
     const int c = c0 + threadIdx.x;
     if (threadIdx.x < kAdChunksPerBlock && c * kAdChunk < n) {
         const int len = n - c * kAdChunk < kAdChunk ? n - c * kAdChunk : kAdChunk;
-        const double *row = s_terms + threadIdx.x * kAdRow;
-        double s = 0.0;
-        for (int i = 0; i < len; ++i) s = s + row[i];
-        chunk[c] = s;
+        chunk[c] = ordered_sum(s_terms + threadIdx.x * kAdRow, len);
     }
 }
 
@@ -92,11 +115,12 @@ __global__ __launch_bounds__(kAdBlock) void k_ad_lb(int n_alpha, const double *c
         chunk_alpha = s_chunks;
         chunk_d = s_chunks + n_alpha;
     }
-    if (threadIdx.x != 0) return;
-    double alpha = 0.0, D = 0.0;
-    for (int i = 0; i < n_alpha; ++i) alpha = alpha + chunk_alpha[i];
-    for (int i = 0; i < n_d; ++i) D = D + chunk_d[i];
-    ascal[1] = alpha / D;
+    // two threads, one sum each
+    __shared__ double s_sum[2];
+    if (threadIdx.x == 0) s_sum[0] = ordered_sum(chunk_alpha, n_alpha);
+    if (threadIdx.x == kWave) s_sum[1] = ordered_sum(chunk_d, n_d);
+    __syncthreads();
+    if (threadIdx.x == 0) ascal[1] = s_sum[0] / s_sum[1];
 }
 
 // normalised loads u = load / cap by position, and the maximum of every block; RL lanes per link
