@@ -210,12 +210,17 @@ hipError_t launch_one(const PersistentArgs &a, int n_cu, hipStream_t s, int *gri
         &per_cu, reinterpret_cast<const void *>(&k_persistent<L, LMAX, MAXC>), kPBlock, 0);
     if (e != hipSuccess) return e;
     if (per_cu < 1) return hipErrorLaunchOutOfResources;
-    // one 1024-thread workgroup per CU: co-residency of the whole grid then only needs the
-    // kernel to fit a CU at all, whatever else the occupancy query assumes
+    // One 1024-thread workgroup per CU, launched cooperatively: the runtime then checks that the
+    // whole grid is resident at once (with this kernel's real register and LDS needs) and
+    // refuses the launch otherwise, instead of leaving the grid barrier to find out.  A plain
+    // launch gives no such promise: with two workgroups per CU, as the occupancy query allows,
+    // the barrier's bounded wait has expired on this part.
     const int grid = n_cu;
     if (grid_out) *grid_out = grid;
-    hipLaunchKernelGGL((k_persistent<L, LMAX, MAXC>), dim3(grid), dim3(kPBlock), 0, s, a);
-    return hipGetLastError();
+    PersistentArgs copy = a;
+    void *params[] = {&copy};
+    return hipLaunchCooperativeKernel(reinterpret_cast<const void *>(&k_persistent<L, LMAX, MAXC>),
+                                      dim3(grid), dim3(kPBlock), params, 0, s);
 }
 
 template <int L, bool MAXC>
