@@ -493,11 +493,38 @@ def test_non_integer_demands(oracle_mod, B):
     d = w.traffic * (1.0 + np.random.default_rng(0).random(w.topo.n_comm))
     check(oracle_mod, B, w.topo, d, w.eps, 100, regime=1, exact=True)
     ref = oracle_mod.solve(*w.topo.csr(), d, w.eps, 100)
+    t = w.topo
     for regime in (2, 3):
-        a = gpu_plan(B, w.topo, d, w.eps, 100, regime=regime)
-        b = gpu_plan(B, w.topo, d, w.eps, 100, regime=regime)
+        a = gpu_plan(B, t, d, w.eps, 100, regime=regime)
+        b = gpu_plan(B, t, d, w.eps, 100, regime=regime)
         assert np.array_equal(a[0], b[0]) and a[1] == b[1]
         assert abs(a[1] - ref["lam"]) <= 1e-6 * ref["lam"]
+        # whatever the rounding of the load sums did to a choice here or there, the plan is a
+        # plan: whole iterations per candidate, fractions of a commodity adding up to one, and
+        # lambda the congestion of these very fractions
+        counts = np.round(a[0] * 100)
+        assert np.array_equal(a[0], counts / 100.0)
+        per_comm = np.add.reduceat(a[0], t.comm_path_ptr[:-1])
+        np.testing.assert_allclose(per_comm, 1.0, rtol=0, atol=1e-12)
+        load = np.zeros(t.n_links)
+        flow = a[0] * np.repeat(d, np.diff(t.comm_path_ptr))
+        np.add.at(load, t.path_links, np.repeat(flow, np.diff(t.path_link_ptr)))
+        assert abs((load / t.cap).max() - a[1]) <= 1e-9 * a[1]
+        # (few commodities may have chosen differently from the oracle in some iteration)
+        assert np.mean(a[0] != ref["splits"]) < 0.05
+
+
+@pytest.mark.parametrize("scale", [2.0 ** -10, 2.0 ** -40, 3.0 * 2.0 ** 20])
+def test_demands_on_a_power_of_two_grid_are_exact_in_every_regime(oracle_mod, B, scale):
+    """Load sums are exact, in any order, whenever all demands are whole multiples of one power
+    of two and their total stays below 2^53 of those units: fractional byte counts on a binary
+    grid (and counts in other units) are therefore bit-identical to the oracle in the regimes
+    that add in a tree as well."""
+    for cfg, iters in ((1, 120), (3, 40)):
+        w = W.make_config(cfg)
+        d = np.floor(w.traffic / 7.0) * scale
+        for regime in ((1, 2, 3) if cfg == 1 else (2,)):
+            check(oracle_mod, B, w.topo, d, w.eps, iters, regime=regime, exact=True)
 
 
 def test_argument_errors_on_device(B):
