@@ -1197,7 +1197,10 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, uint8_t *choice, uint32_t
         // wave walks records rec, rec + n_waves, ..., the next one prefetched while one is
         // scanned
         int rec_grid = (t.n_records + kRecWaves - 1) / kRecWaves;
-        if (rec_grid > t.rec_blocks) rec_grid = t.rec_blocks;
+        // (the plans of a batch share the chip: each gets its part of what is resident)
+        int resident = t.rec_blocks / (t.batch > 1 ? t.batch : 1);
+        if (resident < 1) resident = 1;
+        if (rec_grid > resident) rec_grid = resident;
         if (t.rec_per_wave > 0)
             rec_grid = (t.n_records + kRecWaves * t.rec_per_wave - 1) / (kRecWaves * t.rec_per_wave);
         if constexpr (L >= 2 && L <= 16) {      // (a slot's lanes 1 and L + 1 hold record words)
