@@ -363,6 +363,7 @@ def main() -> int:
         dt = time.perf_counter() - t1
         lam_ad = float(r["d_lambda"].item())
         adaptive = dict(iterations=n_done, ms_per_plan=dt * 1e3, iterations_per_s=n_done / dt,
+                        us_per_iteration=dt * 1e6 / n_done,
                         check_every=check_every, lambda_=lam_ad, lower_bound=lb,
                         gap=lam_ad / lb if lb > 0 else None, target_gap=(1 + w.eps) ** 2,
                         lambda_fixed_step=lam_fixed, fixed_step_iters=w.iters,
@@ -403,6 +404,19 @@ def main() -> int:
                         ks["reduce_update" if ph == 1 and not b3["update"] else name] = dict(
                             back_to_back_us=sec * 1e6, bytes=b3[name])
                 entry["kernels"] = ks
+                # the adaptive step on the same fabric (three launches per iteration)
+                ws = q["w"]
+                for _ in range(2):
+                    torch.cuda.synchronize()
+                    t1 = time.perf_counter()
+                    n_ad, lb_ad = B.nimble_plan_solve_adaptive(
+                        q["h"], q["d_traffic"], ws.eps, 4 * ws.iters, 25, q["d_splits"],
+                        q["d_lambda"])
+                    dt_ad = time.perf_counter() - t1
+                entry["adaptive_step"] = dict(iterations=n_ad, ms_per_plan=dt_ad * 1e3,
+                                              us_per_iteration=dt_ad * 1e6 / n_ad, check_every=25,
+                                              lower_bound=lb_ad,
+                                              lambda_=float(q["d_lambda"].item()))
             if cfg == 3 and plans and single_c3:
                 entry["speedup_over_one_plan_at_a_time"] = entry["plans_per_s"] / single_c3
             if cfg == 2:
