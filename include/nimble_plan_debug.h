@@ -155,13 +155,17 @@ nimble_status_t nimble_host_layout_stats(int32_t n_links, int32_t n_comm,
                                          const int32_t *path_links, int64_t *out);
 
 /*
- * Host-only helper (no device call): which kernel the resident regime would run for this
- * topology.  kernel_out receives 0 when the per-plan state does not fit the LDS of a compute
- * unit (the resident regime is refused), 1 for the kernel that keeps candidate lists and
- * reverse rows in LDS and lets a thread stride over commodities and links, 2 for the kernel
+ * Host-only helper (no device call): which kernel the resident regime would run for one plan
+ * of this topology.  kernel_out receives 0 when the per-plan state does not fit the LDS of a
+ * compute unit (the resident regime is refused), 1 for the kernel that keeps candidate lists
+ * and reverse rows in LDS and lets a thread stride over commodities and links, 2 for the kernel
  * that gives every thread exactly one commodity and one link and keeps their lists in
  * registers (at most 8 candidates of at most 2 links, at most 16 pairs per link, and no more
- * commodities or links than the 1024 threads of a workgroup).
+ * commodities or links than the 1024 threads of a workgroup), 3 for the kernel that gives the
+ * plan a whole workgroup whose lanes share commodities (a candidate each) and links (16 lanes
+ * per reverse row), 4 for that kernel with the lanes' lists in registers (paths of at most 5
+ * links, at most 64 pairs per link, at most 256 links and 4096 / lanes-per-commodity
+ * commodities).
  */
 nimble_status_t nimble_host_resident_kernel(int32_t n_links, int32_t n_comm,
                                             const int32_t *comm_path_ptr, int32_t n_paths,

@@ -313,20 +313,17 @@ nimble_status_t check_device(const nimble_topo *topo)
     return NIMBLE_OK;
 }
 
-// The regime of a solve of `batch` plans.  The resident regime runs the plans side by side,
-// one thread group each, for the price of one; but the thread of its LDS kernel walks a
-// commodity's candidates and a link's reverse row alone (about 0.04 us per LDS access, measured
-// on the two-node fabric), while a streaming-regime iteration costs about two short kernels
-// (6.5 us) however wide the rows are.  A few plans of a fabric with long rows are therefore
-// streamed one after the other.
+// The regime of a solve of `batch` plans.  The resident regime runs the plans side by side for
+// the price of one -- how long that is depends on the kernel the fabric and the batch allow
+// (resident_iteration_us) -- while a streaming-regime iteration costs about two short kernels
+// (6.5 us) per plan however wide the rows are.
 int32_t pick_regime(const nimble_topo *topo, int32_t batch)
 {
     if (topo->forced_regime != NIMBLE_REGIME_AUTO) return topo->forced_regime;
     const nimble::DeviceTopo &d = topo->d;
     if (!nimble::resident_fits(d)) return NIMBLE_REGIME_STREAM;
     if (nimble::resident_in_registers(d)) return NIMBLE_REGIME_RESIDENT;
-    const double accesses = 2.0 * d.pmax * d.lmax + 3.0 * d.rev_row_max;
-    const double resident_us = 0.04 * accesses * ((batch + 255) / 256);
+    const double resident_us = nimble::resident_iteration_us(d, batch);
     const double stream_us = 6.5 * batch;
     return resident_us < stream_us ? NIMBLE_REGIME_RESIDENT : NIMBLE_REGIME_STREAM;
 }
@@ -900,7 +897,7 @@ nimble_status_t nimble_host_resident_kernel(int32_t n_links, int32_t n_comm,
     d.rev_pairs = static_cast<int64_t>(h.rev_pair.size() / 2);
     for (int32_t len : h.rev_rowlen) d.rev_row_max = std::max(d.rev_row_max, len);
     d.resident_generic = std::getenv("NIMBLE_TUNE_RESIDENT_GENERIC") ? 1 : 0;
-    *kernel_out = !nimble::resident_fits(d) ? 0 : (nimble::resident_in_registers(d) ? 2 : 1);
+    *kernel_out = nimble::resident_kernel_kind(d, 1);
     return NIMBLE_OK;
 }
 

@@ -148,6 +148,12 @@ size_t resident_state_bytes(const DeviceTopo &t);
 size_t resident_topo_bytes(const DeviceTopo &t);
 bool resident_fits(const DeviceTopo &t);
 bool resident_in_registers(const DeviceTopo &t);   // the resident regime keeps the topology in registers
+// which kernel the resident regime runs for `batch` plans: 0 none (does not fit), 1 a thread per
+// commodity and per link with the lists in LDS, 2 the same with the lists in registers, 3 lanes
+// sharing commodities and links (one plan per workgroup), 4 the same with the lists in registers
+int resident_kernel_kind(const DeviceTopo &t, int batch);
+// rough time of one iteration of the resident regime for `batch` plans, in microseconds
+double resident_iteration_us(const DeviceTopo &t, int batch);
 hipError_t launch_resident(const DeviceTopo &t, int32_t batch, const double *demand, double eps,
                            int32_t iters, double *splits, double *lambda, hipStream_t s);
 

@@ -8,6 +8,14 @@
 // ascending (commodity, path) order -- the sequential order of Algorithm 1's L_e += f -- and
 // applies the multiplicative length update.  Reverse rows hold (commodity, window | mask) pairs,
 // ascending by commodity, of which at most one per commodity can hit.  Two workgroup barriers per iteration.
+//
+// One plan, or a few, leave most of such a group idle and its busy threads with long loops.
+// The kernel therefore has a cooperative form (CL > 0) for them: the plan gets all 1024 threads,
+// CL lanes share a commodity (one candidate each, the (cost, index) minimum by DPP: lowest index
+// among equal costs, the strict `<` of the sequential scan) and 16 lanes share a link's reverse
+// row (pairs l, l + 16, ... each, the 16 partial sums added by a fixed butterfly).  Path costs
+// are the same sums as before; link loads are added in that fixed tree instead of the
+// sequential order, which is the same number for demands on a power-of-two grid (byte counts).
 #include "host_topo.hpp"
 #include "kernels.hpp"
 #include "wave_ops.hpp"
@@ -46,7 +54,7 @@ __host__ __device__ inline ResidentLayout make_layout(int E, int K, int P, int64
     return l;
 }
 
-template <bool MAXC, bool TOPO_LDS>
+template <bool MAXC, bool TOPO_LDS, int CL>
 __global__ __launch_bounds__(1024) void k_resident(
     int E, int K, int P, int nnz, int rev_len, int batch, int nt, int plans_per_block,
     double eps, int iters,
@@ -136,6 +144,67 @@ __global__ __launch_bounds__(1024) void k_resident(
     const double invrho = s_invrho[slot];
 
     for (int it = 0; it < iters; ++it) {
+        if constexpr (CL > 0) {
+            // CL lanes per commodity, one candidate each
+            const int j = t % CL, per = nt / CL;
+            for (int k0 = 0; k0 < K; k0 += per) {                     // uniform over the group
+                const int k = k0 + t / CL;
+                double c = __builtin_inf();
+                int cand = 0x7FFFFFFF, p0 = 0;
+                if (k < K) {
+                    p0 = cp[k];
+                    if (j < cp[k + 1] - p0) {
+                        cand = j;
+                        c = 0.0;
+                        const int b = lp[p0 + j + 1];
+                        for (int i = lp[p0 + j]; i < b; ++i) {
+                            const double pe = price[pl[i]];
+                            if constexpr (MAXC) c = (pe > c) ? pe : c;
+                            else c = c + pe;
+                        }
+                    }
+                }
+                const int bj = group_argmin_two_pass<(CL > 0 ? CL : 1)>(c, cand);
+                if (k < K && j == 0) {
+                    choice[k] = static_cast<uint8_t>(bj);
+                    count[p0 + bj] += 1u;
+                }
+            }
+            __syncthreads();
+            // 16 lanes per link
+            const int l = t & 15, rows = nt >> 4;
+            for (int e0 = 0; e0 < E; e0 += rows) {                    // uniform over the group
+                const int e = e0 + (t >> 4);
+                double load = 0.0;
+                if (e < E) {
+                    const int end = rp[e + 1];
+                    for (int i = rp[e] + l; i < end; i += 16) {
+                        const uint32_t wa = rev[2 * i], wb = rev[2 * i + 1];
+                        const uint32_t k = wa & kCommMask;
+                        const uint32_t ch = choice[k];
+                        if ((ch >> 5) == ((wa >> kWindowShift) & 3u) && ((wb >> (ch & 31u)) & 1u))
+                            load = load + demand[k];
+                    }
+                }
+                load = load + partner_f64<1>(load);
+                load = load + partner_f64<2>(load);
+                load = load + partner_f64<4>(load);
+                load = load + partner_f64<8>(load);
+                if (e < E && l == 0) {
+                    const double ic = invcap[e];
+                    const double u = load * ic;
+                    S[e] = S[e] + u;
+                    const double g = u * invrho;
+                    const double t1 = eps * g;
+                    const double t2 = 1.0 + t1;
+                    const double ln = len[e] * t2;
+                    len[e] = ln;
+                    price[e] = MAXC ? ln : ln * ic;
+                }
+            }
+            __syncthreads();
+            continue;
+        }
         for (int k = t; k < K; k += nt) {
             const int p0 = cp[k];
             const int np = cp[k + 1] - p0;
@@ -201,6 +270,212 @@ __global__ __launch_bounds__(1024) void k_resident(
     }
 }
 
+
+// ---- one plan per workgroup, lanes sharing commodities and links, lists in registers ----------
+// The cooperative form above for fabrics small enough that a thread can keep its share of the
+// lists in registers for the whole solve (as k_resident_reg does for a single node): CL lanes
+// per commodity, lane j holding the LDS addresses of the prices of candidate j's steps (at most
+// kCoopSteps; short paths point at a +0.0 slot, absent candidates at a +inf slot) for up to
+// kCoopRounds commodities; 16 lanes per link, lane l holding the pairs l, l + 16, l + 32, l + 48
+// of the row for up to kCoopRounds links.  LDS then carries only what threads exchange --
+// prices, choices -- and the demands, lengths, congestion sums and counts.  Same additions in
+// the same order as the cooperative form of k_resident, hence the same bits.
+constexpr int kCoopRounds = 4;     // commodities per lane group, links per 16-lane row
+constexpr int kCoopSteps = 5;      // longest path
+constexpr int kCoopPairs = 4;      // pairs per lane: rows of at most 64 pairs
+
+struct CoopLayout {
+    size_t price, len, S, invcap, demand, count, choice, bytes;
+};
+
+__host__ __device__ inline CoopLayout coop_layout(int E, int K, int P)
+{
+    CoopLayout l;
+    size_t o = 0;
+    l.price = o;  o += sizeof(double) * (E + 2);      // [E] = +0.0, [E + 1] = +inf
+    l.len = o;    o += sizeof(double) * E;
+    l.S = o;      o += sizeof(double) * E;
+    l.invcap = o; o += sizeof(double) * E;
+    l.demand = o; o += sizeof(double) * (K + 1);      // [K] = 0.0: the pair that is not there
+    l.count = o;  o += align8(sizeof(uint32_t) * P);
+    l.choice = o; o += align8(K + 1);
+    l.bytes = o;
+    return l;
+}
+
+template <bool MAXC, int CL>
+__global__ __launch_bounds__(1024) void k_resident_coop(
+    int E, int K, int P, int batch, double eps, int iters, const int32_t *__restrict__ g_cp,
+    const int32_t *__restrict__ g_lp, const int32_t *__restrict__ g_pl,
+    const int32_t *__restrict__ g_rp, const uint32_t *__restrict__ g_rev,
+    const double *__restrict__ g_invcap, const double *__restrict__ demand_all,
+    double *__restrict__ splits_all, double *__restrict__ lambda_all)
+{
+    extern __shared__ __align__(16) unsigned char lds[];
+    __shared__ double red[16];
+    __shared__ double s_invrho;
+    constexpr int NT = 1024;
+    const CoopLayout lay = coop_layout(E, K, P);
+    double *price = reinterpret_cast<double *>(lds + lay.price);
+    double *len = reinterpret_cast<double *>(lds + lay.len);
+    double *S = reinterpret_cast<double *>(lds + lay.S);
+    double *invcap = reinterpret_cast<double *>(lds + lay.invcap);
+    double *demand = reinterpret_cast<double *>(lds + lay.demand);
+    uint32_t *count = reinterpret_cast<uint32_t *>(lds + lay.count);
+    uint8_t *choice = lds + lay.choice;
+    const int t = threadIdx.x;
+    const int plan = blockIdx.x;                  // grid = batch
+
+    const double *d_in = demand_all + static_cast<size_t>(plan) * K;
+    for (int k = t; k < K; k += NT) demand[k] = d_in[k];
+    for (int p = t; p < P; p += NT) count[p] = 0u;
+    for (int e = t; e < E; e += NT) invcap[e] = g_invcap[e];
+    if (t == 0) {
+        demand[K] = 0.0;
+        choice[K] = 0u;
+        price[E] = 0.0;
+        price[E + 1] = __builtin_inf();
+    }
+    __syncthreads();
+
+    // width rho: every commodity that can reach a link counts once (first-of-commodity flag)
+    double wmax = 0.0;
+    for (int e = t; e < E; e += NT) {
+        double reach = 0.0;
+        for (int i = g_rp[e]; i < g_rp[e + 1]; ++i) {
+            const uint32_t wa = g_rev[2 * i];
+            if (wa & kFirstFlag) reach = reach + demand[wa & kCommMask];
+        }
+        const double ic = invcap[e];
+        wmax = fmax(wmax, reach * ic);
+        len[e] = 1.0;
+        price[e] = MAXC ? 1.0 : ic;
+        S[e] = 0.0;
+    }
+    {
+        const double wm = wave_max(wmax);
+        if ((t & (kWave - 1)) == 0) red[t >> 6] = wm;
+        __syncthreads();
+        if (t == 0) {
+            double m = 0.0;
+            for (int w = 0; w < NT / kWave; ++w) m = fmax(m, red[w]);
+            s_invrho = (m > 0.0) ? 1.0 / m : 0.0;
+        }
+        __syncthreads();
+    }
+    const double invrho = s_invrho;
+
+    // this lane's share of the lists, for the whole solve
+    const int j = t % CL, per = NT / CL;
+    int addr[kCoopRounds][kCoopSteps];            // price slots of candidate j of commodity r
+    int cand[kCoopRounds], first_path[kCoopRounds];
+#pragma unroll
+    for (int r = 0; r < kCoopRounds; ++r) {
+        const int k = r * per + t / CL;
+        cand[r] = 0x7FFFFFFF;
+        first_path[r] = 0;
+        addr[r][0] = E + 1;
+#pragma unroll
+        for (int i = 1; i < kCoopSteps; ++i) addr[r][i] = E;
+        if (k < K) {
+            const int p0 = g_cp[k];
+            first_path[r] = p0;
+            if (j < g_cp[k + 1] - p0) {
+                cand[r] = j;
+                const int a = g_lp[p0 + j], n = g_lp[p0 + j + 1] - a;
+#pragma unroll
+                for (int i = 0; i < kCoopSteps; ++i) addr[r][i] = i < n ? g_pl[a + i] : E;
+            }
+        }
+    }
+    const int l = t & 15, rows = NT >> 4;
+    uint32_t pair_k[kCoopRounds][kCoopPairs];     // commodity | window << 24, K: no pair
+    uint32_t pair_m[kCoopRounds][kCoopPairs];     // candidate mask of the window
+#pragma unroll
+    for (int r = 0; r < kCoopRounds; ++r) {
+        const int e = r * rows + (t >> 4);
+#pragma unroll
+        for (int q = 0; q < kCoopPairs; ++q) {
+            pair_k[r][q] = static_cast<uint32_t>(K);
+            pair_m[r][q] = 0u;
+            if (e < E) {
+                const int i = g_rp[e] + l + 16 * q;
+                if (i < g_rp[e + 1]) {
+                    const uint32_t wa = g_rev[2 * i];
+                    pair_k[r][q] = (wa & kCommMask) | (((wa >> kWindowShift) & 3u) << 24);
+                    pair_m[r][q] = g_rev[2 * i + 1];
+                }
+            }
+        }
+    }
+
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int r = 0; r < kCoopRounds; ++r) {
+            if (r * per >= K) break;                                  // uniform
+            double c = price[addr[r][0]];
+#pragma unroll
+            for (int i = 1; i < kCoopSteps; ++i) {
+                const double pe = price[addr[r][i]];
+                if constexpr (MAXC) c = (pe > c) ? pe : c;
+                else c = c + pe;
+            }
+            const int bj = group_argmin_two_pass<CL>(c, cand[r]);
+            const int k = r * per + t / CL;
+            if (k < K && j == 0) {
+                choice[k] = static_cast<uint8_t>(bj);
+                count[first_path[r] + bj] += 1u;
+            }
+        }
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < kCoopRounds; ++r) {
+            if (r * rows >= E) break;                                 // uniform
+            const int e = r * rows + (t >> 4);
+            double load = 0.0;
+#pragma unroll
+            for (int q = 0; q < kCoopPairs; ++q) {
+                const uint32_t k = pair_k[r][q] & kCommMask;
+                const uint32_t ch = choice[k];
+                const bool hit = (ch >> 5) == (pair_k[r][q] >> 24) &&
+                                 ((pair_m[r][q] >> (ch & 31u)) & 1u) != 0u;
+                const double d = demand[k];
+                load = load + (hit ? d : 0.0);
+            }
+            load = load + partner_f64<1>(load);
+            load = load + partner_f64<2>(load);
+            load = load + partner_f64<4>(load);
+            load = load + partner_f64<8>(load);
+            if (e < E && l == 0) {
+                const double ic = invcap[e];
+                const double u = load * ic;
+                S[e] = S[e] + u;
+                const double g = u * invrho;
+                const double t1 = eps * g;
+                const double t2 = 1.0 + t1;
+                const double ln = len[e] * t2;
+                len[e] = ln;
+                price[e] = MAXC ? ln : ln * ic;
+            }
+        }
+        __syncthreads();
+    }
+
+    const double T = static_cast<double>(iters);
+    double *out = splits_all + static_cast<size_t>(plan) * P;
+    for (int p = t; p < P; p += NT) out[p] = static_cast<double>(count[p]) / T;
+    double smax = 0.0;
+    for (int e = t; e < E; e += NT) smax = fmax(smax, S[e]);
+    const double sm = wave_max(smax);
+    __syncthreads();
+    if ((t & (kWave - 1)) == 0) red[t >> 6] = sm;
+    __syncthreads();
+    if (t == 0) {
+        double m = 0.0;
+        for (int w = 0; w < NT / kWave; ++w) m = fmax(m, red[w]);
+        lambda_all[plan] = m / T;
+    }
+}
 
 __host__ __device__ inline size_t reg_plan_bytes(int E, int K, int nt, int maxp)
 {
@@ -426,8 +701,12 @@ struct ResidentPlan {
     int nt, plans_per_block;
     bool topo_lds;
     bool in_registers;     // k_resident_reg: one commodity and one link per thread
+    int coop_lanes;        // > 0: the cooperative form of k_resident, that many lanes per commodity
+    bool coop_registers;   // k_resident_coop: that form with the lists in registers
     size_t lds_bytes;
 };
+
+constexpr int kCoopMaxPlans = 256;   // beyond that many plans a thread per commodity serves better
 
 bool plan_resident(const DeviceTopo &t, int batch, ResidentPlan &rp)
 {
@@ -453,6 +732,27 @@ bool plan_resident(const DeviceTopo &t, int batch, ResidentPlan &rp)
     rp.in_registers = !t.resident_generic && t.pmax <= kRegMaxPaths && t.lmax <= kRegMaxLen &&
                       t.rev_row_max <= kRegMaxRow && need <= nt;
     if (rp.in_registers) rp.lds_bytes = reg_plan_bytes(t.E, t.K, nt, kRegMaxPaths) * ppb;
+    // a few plans: all 1024 threads of a workgroup for each, lanes sharing commodities and links
+    rp.coop_lanes = 0;
+    rp.coop_registers = false;
+    if (!rp.in_registers && !t.resident_generic && batch <= kCoopMaxPlans && t.pmax <= kWave) {
+        int cl = 2;
+        while (cl < t.pmax) cl <<= 1;
+        rp.coop_lanes = cl;
+        rp.nt = 1024;
+        rp.plans_per_block = 1;
+        rp.topo_lds = lay.plan_bytes + lay.topo_bytes + 256 <= kLdsBudgetMax;
+        rp.lds_bytes = lay.plan_bytes + (rp.topo_lds ? lay.topo_bytes : 0);
+        // lists in registers: at most kCoopRounds commodities per lane group and links per row
+        // of 16 lanes, paths of at most kCoopSteps links, rows of at most 16 x kCoopPairs pairs
+        // (rows are padded to an even number of pairs)
+        const int row_padded = (t.rev_row_max + 1) & ~1;
+        const CoopLayout cl_lay = coop_layout(t.E, t.K, t.P);
+        rp.coop_registers = t.lmax <= kCoopSteps && t.K <= kCoopRounds * (1024 / cl) &&
+                            t.E <= kCoopRounds * (1024 / 16) &&
+                            row_padded <= 16 * kCoopPairs && cl_lay.bytes + 256 <= kLdsBudget;
+        if (rp.coop_registers) rp.lds_bytes = cl_lay.bytes;
+    }
     return true;
 }
 
@@ -480,6 +780,35 @@ bool resident_in_registers(const DeviceTopo &t)
     return plan_resident(t, 1, rp) && rp.in_registers;
 }
 
+int resident_kernel_kind(const DeviceTopo &t, int batch)
+{
+    ResidentPlan rp;
+    if (!plan_resident(t, batch, rp)) return 0;
+    if (rp.in_registers) return 2;
+    if (rp.coop_registers) return 4;
+    if (rp.coop_lanes > 0) return 3;
+    return 1;
+}
+
+double resident_iteration_us(const DeviceTopo &t, int batch)
+{
+    // measured on the two-node fabric (240 commodities of up to 16 candidates, 152 links, rows
+    // of up to 64 pairs): 18.6 us per iteration with a thread per commodity and per link (one
+    // dependent LDS access after the other, about 0.04 us each), 5.0 us with lanes sharing
+    // them, 2.7 us with the lists in registers; the kernels with a thread per commodity run
+    // 256 plans side by side for that price, the others one plan per workgroup
+    ResidentPlan rp;
+    if (!plan_resident(t, batch, rp)) return 1e30;
+    const double rounds = (batch + 255) / 256;
+    if (rp.coop_registers) return 2.7 * rounds;
+    if (rp.coop_lanes > 0) {
+        const double fwd = ((static_cast<double>(t.K) * rp.coop_lanes + 1023) / 1024) * (4 + 2 * t.lmax);
+        const double rev = ((t.E + 63) / 64) * (2 + 3 * ((t.rev_row_max + 15) / 16));
+        return 0.05 * (fwd + rev) * rounds;
+    }
+    return 0.04 * (2.0 * t.pmax * t.lmax + 3.0 * t.rev_row_max) * rounds;
+}
+
 hipError_t launch_resident(const DeviceTopo &t, int32_t batch, const double *demand, double eps,
                            int32_t iters, double *splits, double *lambda, hipStream_t s)
 {
@@ -487,19 +816,31 @@ hipError_t launch_resident(const DeviceTopo &t, int32_t batch, const double *dem
     if (!plan_resident(t, batch, rp)) return hipErrorInvalidValue;
     const int grid = (batch + rp.plans_per_block - 1) / rp.plans_per_block;
     const int block = rp.nt * rp.plans_per_block;
-#define NIMBLE_RES_LAUNCH(MAXC, TL)                                                            \
+#define NIMBLE_RES_LAUNCH_CL(MAXC, TL, CLN)                                                    \
     do {                                                                                       \
         if (rp.lds_bytes + 256 > kLdsBudget) {                                                 \
             hipError_t ea = hipFuncSetAttribute(                                               \
-                reinterpret_cast<const void *>(&k_resident<MAXC, TL>),                         \
+                reinterpret_cast<const void *>(&k_resident<MAXC, TL, CLN>),                    \
                 hipFuncAttributeMaxDynamicSharedMemorySize, static_cast<int>(rp.lds_bytes));   \
             if (ea != hipSuccess) return ea;                                                   \
         }                                                                                      \
-        hipLaunchKernelGGL((k_resident<MAXC, TL>), dim3(grid), dim3(block), rp.lds_bytes, s,   \
-                           t.E, t.K, t.P, static_cast<int>(t.nnz),                             \
+        hipLaunchKernelGGL((k_resident<MAXC, TL, CLN>), dim3(grid), dim3(block), rp.lds_bytes, \
+                           s, t.E, t.K, t.P, static_cast<int>(t.nnz),                          \
                            static_cast<int>(t.rev_pairs), batch, rp.nt, rp.plans_per_block,    \
                            eps, iters, t.comm_ptr, t.path_ptr, t.path_links, t.rev_ptr,        \
                            t.rev_pair, t.invcap, demand, splits, lambda);                      \
+    } while (0)
+#define NIMBLE_RES_LAUNCH(MAXC, TL)                                                            \
+    do {                                                                                       \
+        switch (rp.coop_lanes) {                                                               \
+        case 2: NIMBLE_RES_LAUNCH_CL(MAXC, TL, 2); break;                                      \
+        case 4: NIMBLE_RES_LAUNCH_CL(MAXC, TL, 4); break;                                      \
+        case 8: NIMBLE_RES_LAUNCH_CL(MAXC, TL, 8); break;                                      \
+        case 16: NIMBLE_RES_LAUNCH_CL(MAXC, TL, 16); break;                                    \
+        case 32: NIMBLE_RES_LAUNCH_CL(MAXC, TL, 32); break;                                    \
+        case 64: NIMBLE_RES_LAUNCH_CL(MAXC, TL, 64); break;                                    \
+        default: NIMBLE_RES_LAUNCH_CL(MAXC, TL, 0); break;                                     \
+        }                                                                                      \
     } while (0)
     if (rp.in_registers) {
 #define NIMBLE_REG_LAUNCH(MAXC, ONEW)                                                          \
@@ -518,6 +859,29 @@ hipError_t launch_resident(const DeviceTopo &t, int32_t batch, const double *dem
 #undef NIMBLE_REG_LAUNCH
         return hipGetLastError();
     }
+    if (rp.coop_registers) {
+#define NIMBLE_COOP_LAUNCH(MAXC, CLN)                                                          \
+    hipLaunchKernelGGL((k_resident_coop<MAXC, CLN>), dim3(batch), dim3(1024), rp.lds_bytes, s, \
+                       t.E, t.K, t.P, batch, eps, iters, t.comm_ptr, t.path_ptr, t.path_links, \
+                       t.rev_ptr, t.rev_pair, t.invcap, demand, splits, lambda)
+#define NIMBLE_COOP_LANES(MAXC)                                                                \
+    switch (rp.coop_lanes) {                                                                   \
+    case 2: NIMBLE_COOP_LAUNCH(MAXC, 2); break;                                                \
+    case 4: NIMBLE_COOP_LAUNCH(MAXC, 4); break;                                                \
+    case 8: NIMBLE_COOP_LAUNCH(MAXC, 8); break;                                                \
+    case 16: NIMBLE_COOP_LAUNCH(MAXC, 16); break;                                              \
+    case 32: NIMBLE_COOP_LAUNCH(MAXC, 32); break;                                              \
+    default: NIMBLE_COOP_LAUNCH(MAXC, 64); break;                                              \
+    }
+        if (t.cost_max) {
+            NIMBLE_COOP_LANES(true)
+        } else {
+            NIMBLE_COOP_LANES(false)
+        }
+#undef NIMBLE_COOP_LANES
+#undef NIMBLE_COOP_LAUNCH
+        return hipGetLastError();
+    }
     if (t.cost_max) {
         if (rp.topo_lds) NIMBLE_RES_LAUNCH(true, true);
         else NIMBLE_RES_LAUNCH(true, false);
@@ -526,6 +890,7 @@ hipError_t launch_resident(const DeviceTopo &t, int32_t batch, const double *dem
         else NIMBLE_RES_LAUNCH(false, false);
     }
 #undef NIMBLE_RES_LAUNCH
+#undef NIMBLE_RES_LAUNCH_CL
     return hipGetLastError();
 }
 

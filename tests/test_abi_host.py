@@ -313,8 +313,11 @@ def test_streaming_reverse_layout_random(seed, E, K, pm, lm):
 def test_register_kernel_only_when_a_thread_per_commodity_and_link_exists():
     """The register kernel of the resident regime has no striding: one commodity and one link
     per thread of a workgroup of at most 1024.  A fabric with short lists but more commodities
-    or links than that must take the LDS kernel (kernel 1), not the register kernel (2)."""
-    for G, want in ((9, 2), (31, 2), (33, 1), (35, 1)):
+    or links than that must take a kernel whose threads stride (3: lanes share commodities and
+    links, lists in LDS), not the register kernel (2).  The two-node fabric, with up to 16
+    candidates of up to 5 links and rows of 64 pairs, takes the cooperative kernel with its
+    lists in registers (4), and the thread-per-commodity LDS kernel (1) when that is forced."""
+    for G, want in ((9, 2), (31, 2), (33, 3), (35, 3)):
         t = W.two_candidate_mesh(G)
         assert t.n_comm == G * (G - 1)
         got = B.nimble_host_resident_kernel(t.n_links, t.n_comm, t.comm_path_ptr, t.n_paths,
@@ -324,10 +327,22 @@ def test_register_kernel_only_when_a_thread_per_commodity_and_link_exists():
     t = w.topo
     assert B.nimble_host_resident_kernel(t.n_links, t.n_comm, t.comm_path_ptr, t.n_paths,
                                          t.path_link_ptr, t.path_links) == 2
+    w = W.make_config(1)
+    t = w.topo
+    assert B.nimble_host_resident_kernel(t.n_links, t.n_comm, t.comm_path_ptr, t.n_paths,
+                                         t.path_link_ptr, t.path_links) == 4
     w = W.make_config(3)
     t = w.topo
     assert B.nimble_host_resident_kernel(t.n_links, t.n_comm, t.comm_path_ptr, t.n_paths,
                                          t.path_link_ptr, t.path_links) == 0
+
+
+def test_forced_thread_per_commodity_kernel(monkeypatch):
+    monkeypatch.setenv("NIMBLE_TUNE_RESIDENT_GENERIC", "1")
+    for cfg in (0, 1):
+        t = W.make_config(cfg).topo
+        assert B.nimble_host_resident_kernel(t.n_links, t.n_comm, t.comm_path_ptr, t.n_paths,
+                                             t.path_link_ptr, t.path_links) == 1
 
 
 def test_dictionary_of_record_bodies_on_a_large_product_fabric():

@@ -253,28 +253,54 @@ def test_resident_regime_with_more_commodities_and_links_than_threads(oracle_mod
         check(oracle_mod, B, t, d, 0.07, 40, 0, flags)     # whatever the library picks itself
 
 
-def test_regime_chosen_from_batch_size_and_row_lengths(oracle_mod, B):
-    """The two-node fabric fits the resident regime, but its rail links carry 64 pairs each: one
-    plan is streamed (two short kernels per iteration beat one thread walking such a row), a
-    batch of plans runs side by side in the resident regime.  Same bits either way."""
+def test_regime_chosen_from_batch_size_and_row_lengths(oracle_mod, B, monkeypatch):
+    """The two-node fabric fits the resident regime: one plan, or a few, get a workgroup each
+    whose lanes share commodities and links; same bits as the oracle, one plan or four.  With
+    only the thread-per-commodity kernel to choose from (its rail links carry 64 pairs each: one
+    thread walking such a row is slower than two short kernels per iteration) one plan is
+    streamed and a batch runs side by side in the resident regime."""
     w = W.make_config(1)
     t = w.topo
     iters = 50
     tr = np.stack([w.traffic, np.floor(w.traffic / 2), np.floor(w.traffic / 5),
                    np.zeros_like(w.traffic)])
     refs = [oracle_mod.solve(*t.csr(), tr[b], w.eps, iters) for b in range(4)]
-    h = B.nimble_topo_create(*t.csr())
-    try:
-        splits, lam = B.plan(h, tr[0], w.eps, iters)
-        assert h.regime == B.NIMBLE_REGIME_STREAM
-        assert np.array_equal(splits, refs[0]["splits"]) and lam == refs[0]["lam"]
-        splits, lam = B.plan(h, tr, w.eps, iters)
-        assert h.regime == B.NIMBLE_REGIME_RESIDENT
-        for b in range(4):
-            assert np.array_equal(splits[b], refs[b]["splits"]), b
-            assert lam[b] == refs[b]["lam"], b
-    finally:
-        h.close()
+    for generic, single in ((False, B.NIMBLE_REGIME_RESIDENT), (True, B.NIMBLE_REGIME_STREAM)):
+        if generic:
+            monkeypatch.setenv("NIMBLE_TUNE_RESIDENT_GENERIC", "1")
+        h = B.nimble_topo_create(*t.csr())
+        try:
+            splits, lam = B.plan(h, tr[0], w.eps, iters)
+            assert h.regime == single
+            assert np.array_equal(splits, refs[0]["splits"]) and lam == refs[0]["lam"]
+            splits, lam = B.plan(h, tr, w.eps, iters)
+            assert h.regime == B.NIMBLE_REGIME_RESIDENT
+            for b in range(4):
+                assert np.array_equal(splits[b], refs[b]["splits"]), b
+                assert lam[b] == refs[b]["lam"], b
+        finally:
+            h.close()
+
+
+def test_resident_kernels_on_either_side_of_the_cooperative_limit(oracle_mod, B):
+    """Up to 256 plans of the two-node fabric get a workgroup each (lanes share commodities and
+    links); one plan more and all of them run on the thread-per-commodity kernel, several to a
+    workgroup.  Both must give the oracle's plans."""
+    w = W.make_config(1)
+    t = w.topo
+    iters = 30
+    for n in (256, 257):
+        tr = np.stack([np.floor(w.traffic / (1 + b % 7)) for b in range(n)])
+        h = B.nimble_topo_create(*t.csr())
+        try:
+            splits, lam = B.plan(h, tr, w.eps, iters)
+            assert h.regime == B.NIMBLE_REGIME_RESIDENT
+        finally:
+            h.close()
+        for b in (0, 1, 6, n - 1):
+            ref = oracle_mod.solve(*t.csr(), tr[b], w.eps, iters)
+            assert np.array_equal(splits[b], ref["splits"]), (n, b)
+            assert lam[b] == ref["lam"], (n, b)
 
 
 def test_batched_single_node_with_the_lds_kernel(oracle_mod, B, monkeypatch):
@@ -485,16 +511,19 @@ def test_row_too_long_for_a_link_block(oracle_mod, B):
     check(oracle_mod, B, topo, d, 0.1, 5, regime=2)
 
 
-def test_non_integer_demands(oracle_mod, B):
-    """The resident regime adds loads in the sequential order, so it is exact for any demands;
-    the streaming regime sums in a fixed tree: run-to-run identical, equal to the oracle up to
-    the rounding of the load sums."""
+def test_non_integer_demands(oracle_mod, B, monkeypatch):
+    """The resident kernel that gives a thread a whole link adds loads in the sequential order,
+    so it is exact for any demands; the cooperative resident kernel (a few plans: 16 lanes per
+    link) and the streaming regimes sum in a fixed tree: run-to-run identical, equal to the
+    oracle up to the rounding of the load sums."""
     w = W.make_config(1)
     d = w.traffic * (1.0 + np.random.default_rng(0).random(w.topo.n_comm))
+    monkeypatch.setenv("NIMBLE_TUNE_RESIDENT_GENERIC", "1")
     check(oracle_mod, B, w.topo, d, w.eps, 100, regime=1, exact=True)
+    monkeypatch.delenv("NIMBLE_TUNE_RESIDENT_GENERIC")
     ref = oracle_mod.solve(*w.topo.csr(), d, w.eps, 100)
     t = w.topo
-    for regime in (2, 3):
+    for regime in (1, 2, 3):
         a = gpu_plan(B, t, d, w.eps, 100, regime=regime)
         b = gpu_plan(B, t, d, w.eps, 100, regime=regime)
         assert np.array_equal(a[0], b[0]) and a[1] == b[1]
