@@ -23,10 +23,9 @@ __device__ __forceinline__ T stream_load(const T *p)
     return __builtin_nontemporal_load(p);
 }
 
-// Loads of the reverse layouts (octets, masks, strip words): ordinary cached loads.  On fabrics
-// whose reverse layout fits the L2 (27 MB on the 64-node configuration) it is found there again
-// in the next iteration, now that the records are read around the L2; a non-temporal hint here
-// cost 0.3 us per iteration.
+// Loads of the reverse layouts (octets, masks, strip words): ordinary cached loads.  A
+// non-temporal hint here cost 0.3 to 0.7 us per iteration on the 64-node configuration, whether
+// the forward records were read through the L2 or around it.
 template <typename T>
 __device__ __forceinline__ T layout_load(const T *p)
 {
