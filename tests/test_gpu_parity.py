@@ -282,6 +282,34 @@ def test_regime_chosen_from_batch_size_and_row_lengths(oracle_mod, B, monkeypatc
             h.close()
 
 
+@pytest.mark.parametrize("flags", [0, 1])
+@pytest.mark.parametrize("seed,E,K,pm,lm,kind", [(41, 200, 60, 2, 5, 4), (42, 200, 60, 5, 5, 4),
+                                                 (43, 250, 60, 12, 4, 4), (44, 256, 100, 30, 3, 4),
+                                                 (45, 256, 60, 60, 2, 4), (46, 257, 60, 12, 4, 3),
+                                                 (47, 200, 60, 12, 6, 3), (48, 40, 600, 12, 3, 3)])
+def test_cooperative_resident_kernels(oracle_mod, B, seed, E, K, pm, lm, kind, flags):
+    """One plan, and a batch of three, on the kernels whose lanes share commodities and links:
+    with the lists in registers (kind 4: paths of at most 5 links, at most 256 links, rows of
+    at most 64 pairs, few enough commodities) for 2 to 64 lanes per commodity, and with the
+    lists in LDS (kind 3) one link, one step or one long row beyond that."""
+    rng = np.random.default_rng(seed)
+    t = W.random_topology(rng, E, K, pm, lm)
+    assert B.nimble_host_resident_kernel(t.n_links, t.n_comm, t.comm_path_ptr, t.n_paths,
+                                         t.path_link_ptr, t.path_links) == kind
+    d = np.floor(rng.pareto(1.1, (3, K)) * 1e6)
+    d[1, ::5] = 0.0
+    check(oracle_mod, B, t, d[0], 0.07, 50, 1, flags)
+    h = B.nimble_topo_create(*t.csr(), flags=flags)
+    try:
+        B.nimble_topo_set_regime(h, 1)
+        splits, lam = B.plan(h, d, 0.07, 30)
+    finally:
+        h.close()
+    for b in range(3):
+        ref = oracle_mod.solve(*t.csr(), d[b], 0.07, 30, flags=flags)
+        assert np.array_equal(splits[b], ref["splits"]) and lam[b] == ref["lam"], b
+
+
 def test_resident_kernels_on_either_side_of_the_cooperative_limit(oracle_mod, B):
     """Up to 256 plans of the two-node fabric get a workgroup each (lanes share commodities and
     links); one plan more and all of them run on the thread-per-commodity kernel, several to a
