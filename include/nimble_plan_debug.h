@@ -14,6 +14,13 @@
 extern "C" {
 #endif
 
+/* 1 if nimble_plan_solve_adaptive applies the step of an iteration inside the record kernel of
+ * the next one on this topology (two launches per iteration; the prices of the scan are formed
+ * from the lengths before the step, the loads and the step, with the operations of the step
+ * itself), 0 if in a launch of its own (three), -1 for a NULL handle.  Both give the same
+ * bits. */
+int32_t nimble_topo_adaptive_folds(const nimble_topo_t *topo);
+
 /* 1 if the resident regime would run this topology with one commodity and one link per thread,
  * their candidate lists and reverse rows held in registers (at most 8 candidates of at most 2
  * links per commodity, at most 16 (commodity, mask) pairs per link); 0 if it keeps everything

@@ -32,6 +32,7 @@ EXPORTS = [
     "nimble_plan_solve_adaptive",
     "nimble_host_records_roundtrip", "nimble_host_layout_stats",
     "nimble_host_build_reverse_streaming", "nimble_topo_resident_in_registers",
+    "nimble_topo_adaptive_folds",
     "nimble_debug_stream_read", "nimble_topo_reserve", "nimble_host_resident_kernel",
     "nimble_plan_solve_static", "nimble_static_scratch_bytes", "nimble_debug_barrier_probe",
     "nimble_topo_reserve_batch", "nimble_debug_fail_allocation",
@@ -86,7 +87,8 @@ def load_library(build_if_missing: bool = True) -> ctypes.CDLL:
     lib.nimble_last_error.restype = ctypes.c_char_p
     lib.nimble_last_error.argtypes = []
     for name in ("nimble_topo_num_links", "nimble_topo_num_comm", "nimble_topo_num_paths",
-                 "nimble_topo_regime", "nimble_topo_resident_in_registers"):
+                 "nimble_topo_regime", "nimble_topo_resident_in_registers",
+                 "nimble_topo_adaptive_folds"):
         getattr(lib, name).restype = i32
         getattr(lib, name).argtypes = [vp]
     for name in ("nimble_topo_nnz", "nimble_topo_bytes_per_iter"):
@@ -196,6 +198,10 @@ class Topo:
     @property
     def regime(self) -> int:
         return load_library().nimble_topo_regime(self.handle)
+
+    @property
+    def adaptive_folds(self) -> bool:
+        return load_library().nimble_topo_adaptive_folds(self.handle) == 1
 
     @property
     def resident_in_registers(self) -> bool:

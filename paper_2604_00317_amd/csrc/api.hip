@@ -120,6 +120,9 @@ struct nimble_topo {
     int64_t log_rows = 0;
     size_t log_stride = 0;
     bool no_choice_log = false;  // tuning switch read at create: keep per-path counters instead
+    int ad_fold = -1;            // tuning switch read at create: 0 the adaptive solve applies
+                                 // every step in a launch of its own, 1 inside the next record
+                                 // kernel whenever that kernel can, -1 where that is faster
     // workspace of the adaptive-step variant; the sigma log grows with max_iters
     nimble::AdaptiveState ad{};
     bool ad_ready = false;
@@ -388,6 +391,13 @@ nimble_status_t solve_persistent(nimble_topo *topo, const double *d_traffic, dou
 
 }  // namespace
 
+// whether nimble_plan_solve_adaptive applies a step inside the next iteration's record kernel
+static bool adaptive_folds(const nimble_topo_t *t)
+{
+    if (t->ad_fold == 0 || (t->d.n_blocks <= 0 && t->d.n_gblocks <= 0)) return false;
+    return nimble::record_kernel_folds(t->d, t->ad_fold == 1);
+}
+
 extern "C" {
 
 const char *nimble_last_error(void) { return g_last_error.c_str(); }
@@ -449,6 +459,7 @@ nimble_status_t nimble_topo_create(int32_t n_links, const double *cap, int32_t n
     d.rev_row_max = 0;
     for (int32_t len : h.rev_rowlen) d.rev_row_max = std::max(d.rev_row_max, len);
     t->no_choice_log = std::getenv("NIMBLE_TUNE_NO_CHOICE_LOG") != nullptr;
+    if (const char *v = std::getenv("NIMBLE_TUNE_ADAPTIVE_FOLD")) t->ad_fold = std::atoi(v) != 0;
     d.resident_generic = std::getenv("NIMBLE_TUNE_RESIDENT_GENERIC") ? 1 : 0;
     d.alg1_thread_per_problem = std::getenv("NIMBLE_TUNE_ALG1_THREAD_PER_PROBLEM") ? 1 : 0;
     d.n_records = h.n_records;
@@ -706,6 +717,11 @@ int32_t nimble_topo_num_paths(const nimble_topo_t *t) { return t ? t->d.P : -1; 
 int64_t nimble_topo_nnz(const nimble_topo_t *t) { return t ? t->d.nnz : -1; }
 int64_t nimble_topo_bytes_per_iter(const nimble_topo_t *t) { return t ? t->bytes_per_iter : -1; }
 int32_t nimble_topo_regime(const nimble_topo_t *t) { return t ? t->last_regime : -1; }
+int32_t nimble_topo_adaptive_folds(const nimble_topo_t *t)
+{
+    return t ? (adaptive_folds(t) ? 1 : 0) : -1;
+}
+
 int32_t nimble_topo_resident_in_registers(const nimble_topo_t *t)
 {
     return t ? (nimble::resident_in_registers(t->d) ? 1 : 0) : -1;
@@ -968,9 +984,11 @@ nimble_status_t nimble_plan_solve_adaptive(nimble_topo_t *topo, const double *d_
         const size_t mark = topo->allocs.size();
         e = allocate(topo, 2, &a.flags);
         if (e == hipSuccess) e = allocate(topo, 4, &a.ascal);
-        if (e == hipSuccess) e = allocate(topo, static_cast<size_t>(d.K), &a.term);
         if (e == hipSuccess) e = allocate(topo, n_chunks, &a.chunk);
         if (e == hipSuccess) e = allocate(topo, static_cast<size_t>(d.E), &a.u_pos);
+        if (e == hipSuccess) e = allocate(topo, static_cast<size_t>(d.E), &a.u_id);
+        if (e == hipSuccess) e = allocate(topo, static_cast<size_t>(d.E), &a.len_id[0]);
+        if (e == hipSuccess) e = allocate(topo, static_cast<size_t>(d.E), &a.len_id[1]);
         if (e == hipSuccess)
             e = allocate(topo, std::max({(static_cast<size_t>(d.E) + 15) / 16,
                                          static_cast<size_t>(4) * static_cast<size_t>(d.n_blocks),
@@ -1031,6 +1049,20 @@ nimble_status_t nimble_plan_solve_adaptive(nimble_topo_t *topo, const double *d_
     const int32_t ahead = std::max(4, 128 / check_every);
     nimble::launch_ad_reset(a, s);
     nimble::launch_init(dd, d_traffic, nullptr, s);
+    // Where the record kernel can, the step of an iteration is applied inside the record kernel
+    // of the next one (two launches per iteration instead of three): the scan forms its prices
+    // from the lengths before the step (by link id, a.len_id[cur]) while further workgroups of
+    // that launch bring the stored state up to date and write the new lengths to the other
+    // buffer.  The stop test of an iteration with a check wants lambda after that iteration's
+    // step, so it follows the next record kernel (whose scan is then wasted if the solve stops:
+    // its row of the choice log lies beyond the iterations made).
+    const bool folding = adaptive_folds(topo);
+    int cur = 0;                 // a.len_id[cur] holds the lengths of every step applied so far
+    bool pending = false;        // the last iteration's step has not been applied yet
+    bool lambda_due = false;     // ... and its stop test has not been made yet
+    int n_u = 0;
+    nimble::FoldArgs fold;
+    if (folding) nimble::launch_ad_len_id(dd, a.len_id[0], s);
     int32_t checks = 0;
     bool stalled = false;
     for (int32_t t = 0; t < max_iters; ++t) {
@@ -1050,21 +1082,49 @@ nimble_status_t nimble_plan_solve_adaptive(nimble_topo_t *topo, const double *d_
         }
         if (__atomic_load_n(&hw[0], __ATOMIC_ACQUIRE) != 0) break;       // the device has stopped
         uint8_t *row = topo->choice_log + topo->log_stride * static_cast<size_t>(t);
-        nimble::launch_argmin(dd, row, nullptr, s);
+        if (pending) {
+            fold.ap = nimble::ad_apply_args(dd, a, eps, n_u, a.len_id[cur ^ 1]);
+            fold.len_id = a.len_id[cur];
+            fold.u_id = a.u_id;
+            fold.invcap = d.invcap;
+            fold.apply_blocks = 0;                   // (the launch fills it in)
+            dd.fold = &fold;
+            nimble::launch_argmin(dd, row, nullptr, s);
+            dd.fold = nullptr;
+            cur ^= 1;
+            pending = false;
+        } else {
+            nimble::launch_argmin(dd, row, nullptr, s);
+        }
+        if (lambda_due) nimble::launch_ad_lambda(dd, a, gap, ++checks, s);
+        lambda_due = false;
         if (check) nimble::launch_ad_bound(dd, a, row, d_traffic, s);
-        if (d.n_blocks > 0) {
-            // link blocks: normalised loads in one launch, then the step
-            const int n_u = nimble::launch_reduce_u(dd, row, a.u_pos, a.block_max_u, s);
-            nimble::launch_ad_apply(dd, a, eps, n_u, s);
-        } else if (d.n_gblocks > 0) {
-            // blocks of link groups: the same with the tiled layout's kernel
-            const int n_u = nimble::launch_group_reduce_u(dd, row, a.u_pos, a.block_max_u, s);
-            nimble::launch_ad_apply(dd, a, eps, n_u, s);
+        if (d.n_blocks > 0 || d.n_gblocks > 0) {
+            // link blocks or blocks of link groups: normalised loads in one launch, then the
+            // step -- now, or inside the next record kernel
+            n_u = d.n_blocks > 0
+                      ? nimble::launch_reduce_u(dd, row, a.u_pos, a.u_id, a.block_max_u, s)
+                      : nimble::launch_group_reduce_u(dd, row, a.u_pos, a.u_id, a.block_max_u, s);
+            if (folding && t + 1 < max_iters) {
+                pending = true;
+                lambda_due = check;
+            } else {
+                nimble::launch_ad_apply(dd, a, eps, n_u, a.len_id[cur ^ 1], s);
+                cur ^= 1;
+                if (check) nimble::launch_ad_lambda(dd, a, gap, ++checks, s);
+            }
         } else {
             nimble::launch_load_reduce(dd, row, d_traffic, s);
             nimble::launch_ad_update(dd, a, eps, s);
+            if (check) nimble::launch_ad_lambda(dd, a, gap, ++checks, s);
         }
-        if (check) nimble::launch_ad_lambda(dd, a, gap, ++checks, s);
+    }
+    if (pending) {
+        // the loop was left with a step outstanding (the device has stopped, so these return at
+        // once, or the host gave up waiting)
+        nimble::launch_ad_apply(dd, a, eps, n_u, a.len_id[cur ^ 1], s);
+        cur ^= 1;
+        if (lambda_due) nimble::launch_ad_lambda(dd, a, gap, ++checks, s);
     }
     if (stalled) {
         (void)hipStreamSynchronize(s);

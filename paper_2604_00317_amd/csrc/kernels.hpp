@@ -7,6 +7,35 @@
 namespace nimble {
 
 // Device-side view of one topology plus the workspace of one solve.
+// One step of the adaptive solve (sigma = 1 / max u; S += sigma u; len *= 1 + eps sigma u; the
+// prices; W += sigma), a thread per link position.
+struct AdApplyArgs {
+    int E;
+    double eps;
+    int n_u_blocks;                 // maxima in block_max_u
+    const double *block_max_u, *u_pos, *invcap_pos;
+    const int32_t *pos_link;
+    double *len, *price, *S;
+    int32_t *flags;
+    double *ascal, *sigma_log, *block_max_s;
+    double *len_id_new;             // the new lengths once more, by link id
+};
+
+// A record kernel that runs while the step of the iteration before is still pending: its
+// scanning workgroups compute every price they need from the lengths before that step, the
+// normalised loads and the step (all by link id), with the very operations of the step; further
+// workgroups of the same launch (its first apply_blocks) apply the step to the stored state.
+struct FoldArgs {
+    AdApplyArgs ap;
+    const double *len_id;           // lengths by link id before the pending step
+    const double *u_id;             // normalised loads by link id
+    const double *invcap;           // 1 / capacity by link id
+    int apply_blocks;               // the first workgroups of the launch apply the step
+};
+struct NoFold {
+    int unused;
+};
+
 struct DeviceTopo {
     int32_t E, K, P;
     int64_t nnz;
@@ -100,6 +129,8 @@ struct DeviceTopo {
     int32_t batch;
     size_t state_stride, row_stride;
     const int32_t *stop_flag;  // adaptive solve: kernels return at once when this word is set
+    const FoldArgs *fold;         // adaptive solve: when not null, the record kernel applies the
+                                  // step of the iteration before on the fly (see FoldArgs)
     int32_t batch_kernel;      // tuning: 0 four plans per workgroup in the fused reduce + update
                                // of a batch, 1 the single-plan kernel for every plan
     int32_t n_update_blocks;
@@ -134,7 +165,7 @@ void launch_group_reduce_update(const DeviceTopo &t, const uint8_t *choice, doub
                                 hipStream_t s);
 // the same up to the normalised loads (adaptive step): u by position and one maximum of u per
 // wave; returns the number of maxima written
-int launch_group_reduce_u(const DeviceTopo &t, const uint8_t *choice, double *u_pos,
+int launch_group_reduce_u(const DeviceTopo &t, const uint8_t *choice, double *u_pos, double *u_id,
                           double *block_max_u, hipStream_t s);
 // reduce and update in one launch; only for topologies with link blocks (t.n_blocks > 0)
 void launch_reduce_update(const DeviceTopo &t, const uint8_t *choice, const double *demand,
@@ -179,9 +210,10 @@ struct AdaptiveState {
     int32_t *flags;            // [0] stop flag, [1] iterations made
     double *ascal;             // [0] W = sum of sigma, [1] bound of this check, [2] best bound,
                                // [3] lambda
-    double *term;              // [K] d_k * cheapest cost_k
     double *chunk;             // [ceil(K/256) + ceil(E/256)] chunk sums of alpha and D
     double *u_pos;             // [E] normalised loads by position
+    double *u_id;              // [E] the same by link id
+    double *len_id[2];         // [E] each: lengths by link id, written in turn by the steps
     double *block_max_u;       // [ceil(E/16)]
     double *block_max_s;       // [ceil(E/256)]
     double *sigma_log;         // [max_iters]
@@ -198,10 +230,18 @@ void launch_ad_bound(const DeviceTopo &t, const AdaptiveState &a, const uint8_t 
 void launch_ad_update(const DeviceTopo &t, const AdaptiveState &a, double eps, hipStream_t s);
 // link-block fabrics: reduce to normalised loads in one launch (u by position and one maximum
 // per wave; returns the number of maxima), then the step from those
-int launch_reduce_u(const DeviceTopo &t, const uint8_t *choice, double *u_pos, double *block_max_u,
-                    hipStream_t s);
+int launch_reduce_u(const DeviceTopo &t, const uint8_t *choice, double *u_pos, double *u_id,
+                    double *block_max_u, hipStream_t s);
+// (the lengths by link id go to len_id_new)
 void launch_ad_apply(const DeviceTopo &t, const AdaptiveState &a, double eps, int n_u_blocks,
-                     hipStream_t s);
+                     double *len_id_new, hipStream_t s);
+// The step applied inside the next iteration's record kernel instead: the arguments of that
+// step, and whether this topology's record kernel can take them.
+AdApplyArgs ad_apply_args(const DeviceTopo &t, const AdaptiveState &a, double eps, int n_u_blocks,
+                          double *len_id_new);
+bool record_kernel_folds(const DeviceTopo &t, bool whenever_possible);
+// lengths by link id from the lengths by position
+void launch_ad_len_id(const DeviceTopo &t, double *len_id, hipStream_t s);
 // lambda = max S / W; with `check` (the number of this check, from 1; 0: none) also the best
 // bound and the stop test, both published to a.host_words
 void launch_ad_lambda(const DeviceTopo &t, const AdaptiveState &a, double gap, int check,

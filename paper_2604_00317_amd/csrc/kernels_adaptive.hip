@@ -18,36 +18,15 @@ namespace {
 constexpr int kAdBlock = 256;
 constexpr int kAdChunk = 256;
 
-// d_k times the cost of the candidate commodity k has just chosen (= its cheapest: the sum
-// is taken link by link in path order, exactly as the scan took it)
-template <bool MAXC>
-__global__ __launch_bounds__(kAdBlock) void k_ad_terms(int K, const int32_t *__restrict__ cp,
-                                                       const int32_t *__restrict__ lp,
-                                                       const int32_t *__restrict__ pl,
-                                                       const double *__restrict__ price,
-                                                       const uint8_t *__restrict__ choice,
-                                                       const double *__restrict__ demand,
-                                                       const int32_t *__restrict__ flags,
-                                                       double *__restrict__ term)
-{
-    if (flags[0]) return;
-    const int k = blockIdx.x * kAdBlock + threadIdx.x;
-    if (k >= K) return;
-    const int p = cp[k] + choice[k];
-    double c = 0.0;
-    for (int i = lp[p]; i < lp[p + 1]; ++i) {
-        const double pe = price[pl[i]];
-        if constexpr (MAXC) c = (pe > c) ? pe : c;
-        else c = c + pe;
-    }
-    term[k] = demand[k] * c;
-}
-
-// chunk sums: chunk c is the sum of the terms 256c .. 256c + 255 added in order; `index` (may be
-// null) redirects term i to x[index[i]].  A workgroup owns kAdChunksPerBlock chunks: all its
-// threads fetch the terms side by side (coalesced) into LDS, a padded row per chunk so that
-// the rows start in different banks, and one thread per chunk then adds its row in order.
+// The two sums of the bound as chunk sums, in one launch.  Chunk c of a sum is its terms
+// 256c .. 256c + 255 added in order.  A workgroup owns kAdChunksPerBlock chunks of one sum, a
+// thread per term: the first blocks_alpha workgroups those of alpha (term k is d_k times the cost
+// of the candidate commodity k has just chosen -- its cheapest; the cost is taken link by link
+// in path order, exactly as the scan took it), the others those of D (term i is the length of
+// link i).  The terms go to LDS, a padded row per chunk so that the rows start in different
+// banks, and one thread per chunk then adds its row in order.
 constexpr int kAdChunksPerBlock = 4;
+constexpr int kAdSumBlock = kAdChunksPerBlock * kAdChunk;
 constexpr int kAdRow = kAdChunk + 1;
 
 // x[0] + x[1] + ... + x[n-1] added strictly in that order by one thread.  The additions form
@@ -68,59 +47,44 @@ __device__ __forceinline__ double ordered_sum(const double *x, int n)
     return s;
 }
 
-__global__ __launch_bounds__(kAdBlock) void k_ad_chunks(int n, const double *__restrict__ x,
-                                                        const int32_t *__restrict__ index,
-                                                        const int32_t *__restrict__ flags,
-                                                        double *__restrict__ chunk)
+template <bool MAXC>
+__global__ __launch_bounds__(kAdSumBlock) void k_ad_bound_sums(
+    int K, int E, int blocks_alpha, const int32_t *__restrict__ cp, const int32_t *__restrict__ lp,
+    const int32_t *__restrict__ pl, const double *__restrict__ price,
+    const uint8_t *__restrict__ choice, const double *__restrict__ demand,
+    const double *__restrict__ len, const int32_t *__restrict__ pos_of_link,
+    const int32_t *__restrict__ flags, double *__restrict__ chunk_alpha,
+    double *__restrict__ chunk_d)
 {
     __shared__ double s_terms[kAdChunksPerBlock * kAdRow];
     if (flags[0]) return;
-    const int c0 = blockIdx.x * kAdChunksPerBlock;
-    const int first = c0 * kAdChunk;
-    // (all terms of the workgroup are requested before the first is stored)
-    constexpr int kPer = kAdChunksPerBlock * kAdChunk / kAdBlock;
-    double v[kPer];
-#pragma unroll
-    for (int r = 0; r < kPer; ++r) {
-        const int i = first + r * kAdBlock + static_cast<int>(threadIdx.x);
-        v[r] = 0.0;
-        if (i < n) v[r] = x[index ? index[i] : i];
+    const int tid = threadIdx.x;
+    const bool alpha = static_cast<int>(blockIdx.x) < blocks_alpha;          // block-uniform
+    const int blk = alpha ? blockIdx.x : blockIdx.x - blocks_alpha;
+    const int n = alpha ? K : E;
+    const int i = blk * kAdSumBlock + tid;
+    double v = 0.0;
+    if (alpha) {
+        if (i < K) {
+            const int p = cp[i] + choice[i];
+            double c = 0.0;
+            for (int q = lp[p]; q < lp[p + 1]; ++q) {
+                const double pe = price[pl[q]];
+                if constexpr (MAXC) c = (pe > c) ? pe : c;
+                else c = c + pe;
+            }
+            v = demand[i] * c;
+        }
+    } else if (i < E) {
+        v = len[pos_of_link[i]];
     }
-#pragma unroll
-    for (int r = 0; r < kPer; ++r) {
-        const int q = r * kAdBlock + static_cast<int>(threadIdx.x);
-        s_terms[(q / kAdChunk) * kAdRow + (q % kAdChunk)] = v[r];
-    }
+    s_terms[(tid / kAdChunk) * kAdRow + (tid % kAdChunk)] = v;
     __syncthreads();
-    const int c = c0 + threadIdx.x;
-    if (threadIdx.x < kAdChunksPerBlock && c * kAdChunk < n) {
-        const int len = n - c * kAdChunk < kAdChunk ? n - c * kAdChunk : kAdChunk;
-        chunk[c] = ordered_sum(s_terms + threadIdx.x * kAdRow, len);
+    const int c = blk * kAdChunksPerBlock + tid;
+    if (tid < kAdChunksPerBlock && c * kAdChunk < n) {
+        const int cnt = n - c * kAdChunk < kAdChunk ? n - c * kAdChunk : kAdChunk;
+        (alpha ? chunk_alpha : chunk_d)[c] = ordered_sum(s_terms + tid * kAdRow, cnt);
     }
-}
-
-// ascal: [0] W, [1] bound of this check, [2] best bound, [3] lambda.  The chunk sums are added
-// in order by one thread, from LDS.
-__global__ __launch_bounds__(kAdBlock) void k_ad_lb(int n_alpha, const double *chunk_alpha,
-                                                    int n_d, const double *chunk_d,
-                                                    const int32_t *__restrict__ flags,
-                                                    double *__restrict__ ascal, bool staged)
-{
-    extern __shared__ double s_chunks[];
-    if (flags[0]) return;
-    if (staged) {
-        for (int i = threadIdx.x; i < n_alpha; i += kAdBlock) s_chunks[i] = chunk_alpha[i];
-        for (int i = threadIdx.x; i < n_d; i += kAdBlock) s_chunks[n_alpha + i] = chunk_d[i];
-        __syncthreads();
-        chunk_alpha = s_chunks;
-        chunk_d = s_chunks + n_alpha;
-    }
-    // two threads, one sum each
-    __shared__ double s_sum[2];
-    if (threadIdx.x == 0) s_sum[0] = ordered_sum(chunk_alpha, n_alpha);
-    if (threadIdx.x == kWave) s_sum[1] = ordered_sum(chunk_d, n_d);
-    __syncthreads();
-    if (threadIdx.x == 0) ascal[1] = s_sum[0] / s_sum[1];
 }
 
 // normalised loads u = load / cap by position, and the maximum of every block; RL lanes per link
@@ -159,65 +123,37 @@ __global__ __launch_bounds__(kAdBlock) void k_ad_u(int E, const int32_t *__restr
 
 // sigma = 1 / max u; S += sigma * u; len *= 1 + eps * sigma * u; price; W += sigma
 template <bool MAXC>
-__global__ __launch_bounds__(kAdBlock) void k_ad_apply(
-    int E, double eps, int n_u_blocks, const double *__restrict__ block_max_u,
-    const double *__restrict__ u_pos, const double *__restrict__ invcap_pos,
-    const int32_t *__restrict__ pos_link, double *__restrict__ len, double *__restrict__ price,
-    double *__restrict__ S, int32_t *__restrict__ flags, double *__restrict__ ascal,
-    double *__restrict__ sigma_log, double *__restrict__ block_max_s)
+__global__ __launch_bounds__(kAdBlock) void k_ad_apply(AdApplyArgs a)
 {
     __shared__ double red[16];
-    // the stop word, the link's own state and the maxima are requested together (threads past
-    // the last link re-read it), so that one trip to memory serves all three
-    const int32_t stop_now = *static_cast<const volatile int32_t *>(flags);
-    const int i = blockIdx.x * kAdBlock + threadIdx.x;
-    const int ic = i < E ? i : E - 1;
-    const double u_i = u_pos[ic];
-    const double s_old = S[ic];
-    const double l_old = len[ic];
-    const double cap_i = invcap_pos[ic];
-    const int e_i = pos_link[ic];
-    double m = 0.0;
-    for (int b = threadIdx.x; b < n_u_blocks; b += kAdBlock) m = fmax(m, block_max_u[b]);
-    if (stop_now != 0) return;
-    const double umax = block_max(m, red);
-    if (!(umax > 0.0)) {                               // no traffic at all: the solve ends here
-        if (blockIdx.x == 0 && threadIdx.x == 0) flags[0] = 1;
-        return;
-    }
-    const double sigma = 1.0 / umax;
-    double s_new = 0.0;
-    if (i < E) {
-        const double su = sigma * u_i;
-        s_new = s_old + su;
-        S[i] = s_new;
-        const double t1 = eps * su;
-        const double t2 = 1.0 + t1;
-        const double ln = l_old * t2;
-        len[i] = ln;
-        price[e_i] = MAXC ? ln : ln * cap_i;
-    }
-    __syncthreads();
-    const double sm = block_max(s_new, red);
-    if (threadIdx.x == 0) {
-        block_max_s[blockIdx.x] = sm;
-        if (blockIdx.x == 0) {
-            ascal[0] = ascal[0] + sigma;
-            sigma_log[flags[1]] = sigma;
-            flags[1] = flags[1] + 1;
-        }
-    }
+    ad_apply_block<MAXC>(a, blockIdx.x, red);
 }
 
-// lambda = max S / W; at a check the best bound is updated and the stop test made
+// lengths by link id from the lengths by position
+__global__ __launch_bounds__(kAdBlock) void k_ad_len_id(int E, const int32_t *__restrict__ pos_link,
+                                                        const double *__restrict__ len,
+                                                        double *__restrict__ len_id)
+{
+    const int i = blockIdx.x * kAdBlock + threadIdx.x;
+    if (i < E) len_id[pos_link[i]] = len[i];
+}
+
+// lambda = max S / W.  At a check, first the bound of this check -- alpha / D, each the sum of
+// its chunk sums added in order by one thread (from LDS when `staged`) -- then the best bound
+// is updated and the stop test made.  ascal: [0] W, [1] bound of this check, [2] best bound,
+// [3] lambda.
 __global__ __launch_bounds__(kAdBlock) void k_ad_lambda(int n_s_blocks,
                                                         const double *__restrict__ block_max_s,
-                                                        double gap, int check,
+                                                        double gap, int check, int n_alpha,
+                                                        const double *chunk_alpha, int n_d,
+                                                        const double *chunk_d, bool staged,
                                                         int32_t *__restrict__ flags,
                                                         double *__restrict__ ascal,
                                                         int32_t *host_words)
 {
+    extern __shared__ double s_chunks[];
     __shared__ double red[16];
+    __shared__ double s_sum[2];
     // what the host reads while it enqueues ahead: whether the solve has stopped and how many
     // checks have been made (written to pinned host memory at system scope)
     auto publish = [&]() {
@@ -230,13 +166,27 @@ __global__ __launch_bounds__(kAdBlock) void k_ad_lambda(int n_s_blocks,
     }
     double m = 0.0;
     for (int b = threadIdx.x; b < n_s_blocks; b += kAdBlock) m = fmax(m, block_max_s[b]);
-    const double smax = block_max(m, red);
+    if (check) {
+        if (staged) {
+            for (int i = threadIdx.x; i < n_alpha; i += kAdBlock) s_chunks[i] = chunk_alpha[i];
+            for (int i = threadIdx.x; i < n_d; i += kAdBlock) s_chunks[n_alpha + i] = chunk_d[i];
+            __syncthreads();
+            chunk_alpha = s_chunks;
+            chunk_d = s_chunks + n_alpha;
+        }
+        // two threads, one sum each
+        if (threadIdx.x == 0) s_sum[0] = ordered_sum(chunk_alpha, n_alpha);
+        if (threadIdx.x == kWave) s_sum[1] = ordered_sum(chunk_d, n_d);
+    }
+    const double smax = block_max(m, red);            // (its barriers also publish s_sum)
     if (threadIdx.x != 0) return;
     const double W = ascal[0];
     const double lam = W > 0.0 ? smax / W : 0.0;
     ascal[3] = lam;
     if (check) {
-        if (ascal[1] > ascal[2]) ascal[2] = ascal[1];
+        const double lb = s_sum[0] / s_sum[1];
+        ascal[1] = lb;
+        if (lb > ascal[2]) ascal[2] = lb;
         const double bound = gap * ascal[2];
         if (lam <= bound) flags[0] = 1;
         publish();
@@ -297,25 +247,16 @@ void launch_ad_reset(const AdaptiveState &a, hipStream_t s)
 void launch_ad_bound(const DeviceTopo &t, const AdaptiveState &a, const uint8_t *choice,
                      const double *demand, hipStream_t s)
 {
-    const int gk = (t.K + kAdBlock - 1) / kAdBlock;
+    const int n_alpha = (t.K + kAdChunk - 1) / kAdChunk;
+    const int ba = (t.K + kAdSumBlock - 1) / kAdSumBlock, bd = (t.E + kAdSumBlock - 1) / kAdSumBlock;
     if (t.cost_max)
-        hipLaunchKernelGGL(k_ad_terms<true>, dim3(gk), dim3(kAdBlock), 0, s, t.K, t.comm_ptr,
-                           t.path_ptr, t.path_links, t.price, choice, demand, a.flags, a.term);
+        hipLaunchKernelGGL(k_ad_bound_sums<true>, dim3(ba + bd), dim3(kAdSumBlock), 0, s, t.K, t.E,
+                           ba, t.comm_ptr, t.path_ptr, t.path_links, t.price, choice, demand,
+                           t.len, a.pos_of_link, a.flags, a.chunk, a.chunk + n_alpha);
     else
-        hipLaunchKernelGGL(k_ad_terms<false>, dim3(gk), dim3(kAdBlock), 0, s, t.K, t.comm_ptr,
-                           t.path_ptr, t.path_links, t.price, choice, demand, a.flags, a.term);
-    const int n_alpha = (t.K + kAdChunk - 1) / kAdChunk, n_d = (t.E + kAdChunk - 1) / kAdChunk;
-    hipLaunchKernelGGL(k_ad_chunks,
-                       dim3((n_alpha + kAdChunksPerBlock - 1) / kAdChunksPerBlock), dim3(kAdBlock),
-                       0, s, t.K, a.term, static_cast<const int32_t *>(nullptr), a.flags, a.chunk);
-    hipLaunchKernelGGL(k_ad_chunks, dim3((n_d + kAdChunksPerBlock - 1) / kAdChunksPerBlock),
-                       dim3(kAdBlock), 0, s, t.E, t.len, a.pos_of_link, a.flags,
-                       a.chunk + n_alpha);
-    // the chunk sums go through LDS while they fit (32 KB: about a million commodities)
-    const size_t lb_lds = sizeof(double) * (static_cast<size_t>(n_alpha) + n_d);
-    const bool staged = lb_lds <= 32 * 1024;
-    hipLaunchKernelGGL(k_ad_lb, dim3(1), dim3(kAdBlock), staged ? lb_lds : 0, s, n_alpha, a.chunk,
-                       n_d, a.chunk + n_alpha, a.flags, a.ascal, staged);
+        hipLaunchKernelGGL(k_ad_bound_sums<false>, dim3(ba + bd), dim3(kAdSumBlock), 0, s, t.K, t.E,
+                           ba, t.comm_ptr, t.path_ptr, t.path_links, t.price, choice, demand,
+                           t.len, a.pos_of_link, a.flags, a.chunk, a.chunk + n_alpha);
 }
 
 void launch_ad_update(const DeviceTopo &t, const AdaptiveState &a, double eps, hipStream_t s)
@@ -330,28 +271,57 @@ void launch_ad_update(const DeviceTopo &t, const AdaptiveState &a, double eps, h
     else
         hipLaunchKernelGGL(k_ad_u<16>, dim3(gu), dim3(kAdBlock), 0, s, t.E, t.pos_slot_ptr,
                            t.pos_xslot, t.partial, t.invcap_pos, a.flags, a.u_pos, a.block_max_u);
-    launch_ad_apply(t, a, eps, gu, s);
+    launch_ad_apply(t, a, eps, gu, a.len_id[0], s);   // (no record kernel reads these here)
+}
+
+AdApplyArgs ad_apply_args(const DeviceTopo &t, const AdaptiveState &a, double eps, int n_u_blocks,
+                          double *len_id_new)
+{
+    AdApplyArgs p;
+    p.E = t.E;
+    p.eps = eps;
+    p.n_u_blocks = n_u_blocks;
+    p.block_max_u = a.block_max_u;
+    p.u_pos = a.u_pos;
+    p.invcap_pos = t.invcap_pos;
+    p.pos_link = t.pos_link;
+    p.len = t.len;
+    p.price = t.price;
+    p.S = t.S;
+    p.flags = a.flags;
+    p.ascal = a.ascal;
+    p.sigma_log = a.sigma_log;
+    p.block_max_s = a.block_max_s;
+    p.len_id_new = len_id_new;
+    return p;
 }
 
 void launch_ad_apply(const DeviceTopo &t, const AdaptiveState &a, double eps, int n_u_blocks,
-                     hipStream_t s)
+                     double *len_id_new, hipStream_t s)
 {
     const int ga = (t.E + kAdBlock - 1) / kAdBlock;
-    if (t.cost_max)
-        hipLaunchKernelGGL(k_ad_apply<true>, dim3(ga), dim3(kAdBlock), 0, s, t.E, eps, n_u_blocks,
-                           a.block_max_u, a.u_pos, t.invcap_pos, t.pos_link, t.len, t.price, t.S,
-                           a.flags, a.ascal, a.sigma_log, a.block_max_s);
-    else
-        hipLaunchKernelGGL(k_ad_apply<false>, dim3(ga), dim3(kAdBlock), 0, s, t.E, eps, n_u_blocks,
-                           a.block_max_u, a.u_pos, t.invcap_pos, t.pos_link, t.len, t.price, t.S,
-                           a.flags, a.ascal, a.sigma_log, a.block_max_s);
+    const AdApplyArgs p = ad_apply_args(t, a, eps, n_u_blocks, len_id_new);
+    if (t.cost_max) hipLaunchKernelGGL(k_ad_apply<true>, dim3(ga), dim3(kAdBlock), 0, s, p);
+    else hipLaunchKernelGGL(k_ad_apply<false>, dim3(ga), dim3(kAdBlock), 0, s, p);
+}
+
+void launch_ad_len_id(const DeviceTopo &t, double *len_id, hipStream_t s)
+{
+    hipLaunchKernelGGL(k_ad_len_id, dim3((t.E + kAdBlock - 1) / kAdBlock), dim3(kAdBlock), 0, s,
+                       t.E, t.pos_link, t.len, len_id);
 }
 
 void launch_ad_lambda(const DeviceTopo &t, const AdaptiveState &a, double gap, int check,
                       hipStream_t s)
 {
     const int ga = (t.E + kAdBlock - 1) / kAdBlock;
-    hipLaunchKernelGGL(k_ad_lambda, dim3(1), dim3(kAdBlock), 0, s, ga, a.block_max_s, gap, check,
+    const int n_alpha = (t.K + kAdChunk - 1) / kAdChunk, n_d = (t.E + kAdChunk - 1) / kAdChunk;
+    // the chunk sums of a check go through LDS while they fit (32 KB: about a million
+    // commodities)
+    const size_t lb_lds = sizeof(double) * (static_cast<size_t>(n_alpha) + n_d);
+    const bool staged = check != 0 && lb_lds <= 32 * 1024;
+    hipLaunchKernelGGL(k_ad_lambda, dim3(1), dim3(kAdBlock), staged ? lb_lds : 0, s, ga,
+                       a.block_max_s, gap, check, n_alpha, a.chunk, n_d, a.chunk + n_alpha, staged,
                        a.flags, a.ascal, a.host_words);
 }
 

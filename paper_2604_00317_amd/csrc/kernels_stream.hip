@@ -330,29 +330,96 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_rec(int n_records,
     }
 }
 
+// FOLD (adaptive step): the step of the iteration before has not been applied to the stored
+// state when this launch starts.  The scanning workgroups take, for every link of a record's
+// table, the length before that step, the normalised load and 1/capacity (all by link id) and
+// form the price with the operations of the step itself, in the same order -- the same bits the
+// step writes; the first f.apply_blocks workgroups apply the step to the stored state meanwhile
+// (nothing they write is read by this launch).
+template <bool FOLD>
+struct FoldParam {
+    typedef NoFold type;
+};
+template <>
+struct FoldParam<true> {
+    typedef FoldArgs type;
+};
+
+// the largest normalised load of the fabric from the maxima of the blocks; 0 when there was no
+// traffic (the step then ends the solve, and every price stays what it was)
+__device__ __forceinline__ double fold_sigma(const AdApplyArgs &ap, int lane)
+{
+    const double umax = wave_max(max_of_strided<kWave>(ap.block_max_u, ap.n_u_blocks, lane));
+    return umax > 0.0 ? 1.0 / umax : 0.0;
+}
+
+// what a price is made of: plain, the price itself; folded, length, load and 1/capacity
+template <bool FOLD, bool MAXC>
+struct PriceTerms {
+    double v[4];
+    __device__ __forceinline__ void fetch(int q, uint32_t id, const double *price, const NoFold &)
+    {
+        v[q] = price[id];
+    }
+    __device__ __forceinline__ double priced(int q, double, double) const { return v[q]; }
+};
+template <bool MAXC>
+struct PriceTerms<true, MAXC> {
+    double v[4], u[4], c[4];
+    __device__ __forceinline__ void fetch(int q, uint32_t id, const double *, const FoldArgs &f)
+    {
+        v[q] = f.len_id[id];
+        u[q] = f.u_id[id];
+        if constexpr (!MAXC) c[q] = f.invcap[id];
+    }
+    __device__ __forceinline__ double priced(int q, double sigma, double eps) const
+    {
+        const double su = sigma * u[q];
+        const double t1 = eps * su;
+        const double t2 = 1.0 + t1;
+        const double ln = v[q] * t2;
+        if constexpr (MAXC) return ln;
+        else return ln * c[q];
+    }
+};
+
 // The same for records with a lane-major body: the three 16-byte loads of a lane return its own
 // twelve words (the table indices of its two quads, five steps each, and two words about its
 // commodity and the record), so the body never goes through LDS -- only the prices do.  The
 // price slots kRecZeroSlot / kRecInfSlot hold +0.0 / +inf for short paths and absent
 // candidates.  One scan round per record: a record has at most 64 / L commodities.
-template <int L, int S, bool MAXC, bool T16, bool EXT>
+template <int L, int S, bool MAXC, bool T16, bool EXT, bool FOLD = false>
 __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records, int around_l2,
                                                        const uint8_t *__restrict__ records,
                                                        const double *__restrict__ price,
                                                        uint8_t *__restrict__ choice,
                                                        uint32_t *__restrict__ count,
                                                        uint8_t *__restrict__ choice2,
-                                                       PlanStrides ps)
+                                                       PlanStrides ps,
+                                                       typename FoldParam<FOLD>::type f)
 {
     static_assert(L >= 2 && L <= 16 && S <= kRecLaneSteps,
                   "lane-major records: 2 to 16 lanes per commodity, five steps");
+    static_assert(!FOLD || EXT, "the folded step belongs to a solve that may stop early");
+    int bx = blockIdx.x, scan_blocks = gridDim.x;
+    if constexpr (FOLD) {
+        if (bx < f.apply_blocks) {                               // block-uniform
+            __shared__ double red[16];
+            ad_apply_block<MAXC>(f.ap, bx, red);
+            return;
+        }
+        bx -= f.apply_blocks;
+        scan_blocks -= f.apply_blocks;
+    }
     int32_t stop_now = 0;
     if constexpr (EXT) {      // a batch (blockIdx.y is the plan) or a solve that may stop early
         stop_now = stop_word(ps);            // tested below, once the first loads are under way
-        price = of_plan(price, ps.state);
-        choice = of_plan(choice, ps.row);
-        count = of_plan(count, ps.state);
-        choice2 = of_plan(choice2, ps.state);
+        if constexpr (!FOLD) {               // (a folded step belongs to a single plan)
+            price = of_plan(price, ps.state);
+            choice = of_plan(choice, ps.row);
+            count = of_plan(count, ps.state);
+            choice2 = of_plan(choice2, ps.state);
+        }
     }
     // T16: the link table is 256 uint16 (8 bytes per lane) and the record 3.5 KiB
     constexpr int kTab = T16 ? kRecTable16 : kRecTable;
@@ -362,8 +429,8 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records,
     const int lane = threadIdx.x & (kWave - 1);
     const int g = lane / L;
     const int j = lane % L;
-    const int n_waves = gridDim.x * kRecWaves;
-    int rec = __builtin_amdgcn_readfirstlane(blockIdx.x * kRecWaves + (threadIdx.x >> 6));
+    const int n_waves = scan_blocks * kRecWaves;
+    int rec = __builtin_amdgcn_readfirstlane(bx * kRecWaves + (threadIdx.x >> 6));
     if (rec >= n_records) return;
     // in flight while a record is scanned: the table of the record after the next, the prices
     // and the body of the next one; nothing is requested past the wave's last record
@@ -431,12 +498,17 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records,
         }
     };
     Ids tab = table_of(rec);
+    [[maybe_unused]] double sigma = 0.0, eps = 0.0;
+    if constexpr (FOLD) {                    // (the maxima travel together with the table)
+        sigma = fold_sigma(f.ap, lane);
+        eps = f.ap.eps;
+    }
     u32x4 body[3];
-    double pr[4];
-    pr[0] = price[tab.a];
-    pr[1] = price[tab.b];
-    pr[2] = price[tab.c];
-    pr[3] = price[tab.d];
+    PriceTerms<FOLD, MAXC> pr;
+    pr.fetch(0, tab.a, price, f);
+    pr.fetch(1, tab.b, price, f);
+    pr.fetch(2, tab.c, price, f);
+    pr.fetch(3, tab.d, price, f);
     if (rec + n_waves < n_records) tab = table_of(rec + n_waves);
     body_of(rec, body);
     if constexpr (EXT)
@@ -444,7 +516,7 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records,
     for (; rec < n_records; rec += n_waves) {           // wave-uniform
         wave_lds_sync();                                // the previous record is done with LDS
 #pragma unroll
-        for (int q = 0; q < 4; ++q) s_price[lane + q * kWave] = pr[q];
+        for (int q = 0; q < 4; ++q) s_price[lane + q * kWave] = pr.priced(q, sigma, eps);
         if (lane == 0) {                             // after the table prices, in LDS order
             s_price[kRecZeroSlot] = 0.0;             // pads short paths
             s_price[kRecInfSlot] = __builtin_inf();  // first step of absent candidates
@@ -455,10 +527,10 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records,
         const uint32_t meta = body[2].z;
         const int32_t own = static_cast<int32_t>(body[2].w);
         if (rec + n_waves < n_records) {
-            pr[0] = price[tab.a];
-            pr[1] = price[tab.b];
-            pr[2] = price[tab.c];
-            pr[3] = price[tab.d];
+            pr.fetch(0, tab.a, price, f);
+            pr.fetch(1, tab.b, price, f);
+            pr.fetch(2, tab.c, price, f);
+            pr.fetch(3, tab.d, price, f);
             if (rec + 2 * n_waves < n_records) tab = table_of(rec + 2 * n_waves);
             body_of(rec + n_waves, body);
         }
@@ -507,7 +579,7 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recl(int n_records,
 // link table entries, the lane's own word (sigma, or the record's first commodity / first
 // candidate) and the body number.  In flight while a record is scanned: the 16 bytes of the
 // record after the next and the prices of the next one.
-template <int L, int S, bool MAXC, bool EXT>
+template <int L, int S, bool MAXC, bool EXT, bool FOLD = false>
 __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recd(int n_chunks, int around_l2,
                                                        const int4 *__restrict__ chunks,
                                                        const uint8_t *__restrict__ records,
@@ -516,24 +588,37 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recd(int n_chunks, 
                                                        uint8_t *__restrict__ choice,
                                                        uint32_t *__restrict__ count,
                                                        uint8_t *__restrict__ choice2,
-                                                       PlanStrides ps)
+                                                       PlanStrides ps,
+                                                       typename FoldParam<FOLD>::type f)
 {
     static_assert(L >= 2 && L <= 16 && S <= kRecLaneSteps,
                   "lane-major records: 2 to 16 lanes per commodity, five steps");
+    static_assert(!FOLD || EXT, "the folded step belongs to a solve that may stop early");
+    int bx = blockIdx.x;
+    if constexpr (FOLD) {
+        if (bx < f.apply_blocks) {                               // block-uniform
+            __shared__ double red[16];
+            ad_apply_block<MAXC>(f.ap, bx, red);
+            return;
+        }
+        bx -= f.apply_blocks;
+    }
     int32_t stop_now = 0;
     if constexpr (EXT) {      // a batch (blockIdx.y is the plan) or a solve that may stop early
         stop_now = stop_word(ps);            // tested below, once the first loads are under way
-        price = of_plan(price, ps.state);
-        choice = of_plan(choice, ps.row);
-        count = of_plan(count, ps.state);
-        choice2 = of_plan(choice2, ps.state);
+        if constexpr (!FOLD) {               // (a folded step belongs to a single plan)
+            price = of_plan(price, ps.state);
+            choice = of_plan(choice, ps.row);
+            count = of_plan(count, ps.state);
+            choice2 = of_plan(choice2, ps.state);
+        }
     }
     __shared__ double s_all[kRecWaves * kRecPriceSlots];
     double *s_price = s_all + (threadIdx.x >> 6) * kRecPriceSlots;
     const int lane = threadIdx.x & (kWave - 1);
     const int g = lane / L;
     const int j = lane % L;
-    const int chunk = __builtin_amdgcn_readfirstlane(blockIdx.x * kRecWaves + (threadIdx.x >> 6));
+    const int chunk = __builtin_amdgcn_readfirstlane(bx * kRecWaves + (threadIdx.x >> 6));
     if (chunk >= n_chunks) return;
     const int4 ck = chunks[chunk];
     int rec = __builtin_amdgcn_readfirstlane(ck.x);
@@ -558,11 +643,16 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recd(int n_chunks, 
     const int np = static_cast<int>(meta & 0xFFu);
     const int p_lo = static_cast<int>(meta >> 8);
     const int ja = 4 * j, jb = 4 * j + 4 * L;
-    double pr[4];
-    pr[0] = price[head.x & 0xFFFFu];
-    pr[1] = price[head.x >> 16];
-    pr[2] = price[head.y & 0xFFFFu];
-    pr[3] = price[head.y >> 16];
+    [[maybe_unused]] double sigma = 0.0, eps = 0.0;
+    if constexpr (FOLD) {                    // (the maxima travel together with head and body)
+        sigma = fold_sigma(f.ap, lane);
+        eps = f.ap.eps;
+    }
+    PriceTerms<FOLD, MAXC> pr;
+    pr.fetch(0, head.x & 0xFFFFu, price, f);
+    pr.fetch(1, head.x >> 16, price, f);
+    pr.fetch(2, head.y & 0xFFFFu, price, f);
+    pr.fetch(3, head.y >> 16, price, f);
     int32_t own_next = static_cast<int32_t>(head.z);
     if (rec + 1 < end) head = head_of(rec + 1);
     if constexpr (EXT)
@@ -570,17 +660,17 @@ __global__ __launch_bounds__(kWave *kRecWaves) void k_argmin_recd(int n_chunks, 
     for (; rec < end; ++rec) {                          // wave-uniform
         wave_lds_sync();                                // the previous record is done with LDS
 #pragma unroll
-        for (int q = 0; q < 4; ++q) s_price[lane + q * kWave] = pr[q];
+        for (int q = 0; q < 4; ++q) s_price[lane + q * kWave] = pr.priced(q, sigma, eps);
         if (lane == 0) {                             // after the table prices, in LDS order
             s_price[kRecZeroSlot] = 0.0;             // pads short paths
             s_price[kRecInfSlot] = __builtin_inf();  // first step of absent candidates
         }
         const int32_t own = own_next;
         if (rec + 1 < end) {
-            pr[0] = price[head.x & 0xFFFFu];
-            pr[1] = price[head.x >> 16];
-            pr[2] = price[head.y & 0xFFFFu];
-            pr[3] = price[head.y >> 16];
+            pr.fetch(0, head.x & 0xFFFFu, price, f);
+            pr.fetch(1, head.x >> 16, price, f);
+            pr.fetch(2, head.y & 0xFFFFu, price, f);
+            pr.fetch(3, head.y >> 16, price, f);
             own_next = static_cast<int32_t>(head.z);
             if (rec + 2 < end) head = head_of(rec + 2);
         }
@@ -730,7 +820,7 @@ struct FusedArgs {
     double eps;
     PlanStrides ps;
     int n_plans;
-    double *u_pos, *block_max_u;     // adaptive step only
+    double *u_pos, *u_id, *block_max_u;     // adaptive step only (u by position and by id)
 };
 
 struct LinkState {
@@ -745,16 +835,19 @@ template <bool MAXC, bool ONLY_U, bool EXT>
 __global__ __launch_bounds__(kBlock) void k_reduce_update(FusedArgs a)
 {
     __shared__ double s_part[kBlkMaxSlots];
+    int32_t stop_now = 0;
     if constexpr (EXT) {      // a batch (blockIdx.y is the plan) or a solve that may stop early
-        if (stopped(a.ps)) return;
-        a.choice = of_plan(a.choice, a.ps.row);
-        a.choice2 = of_plan(a.choice2, a.ps.state);
-        a.demand1n = of_plan(a.demand1n, a.ps.state);
-        a.demand2 = of_plan(a.demand2, a.ps.state);
-        a.len = of_plan(a.len, a.ps.state);
-        a.price = of_plan(a.price, a.ps.state);
-        a.S = of_plan(a.S, a.ps.state);
-        a.scalars = of_plan(a.scalars, a.ps.state);
+        stop_now = stop_word(a.ps);          // tested below, once the first loads are under way
+        if constexpr (!ONLY_U) {             // (the adaptive step belongs to a single plan)
+            a.choice = of_plan(a.choice, a.ps.row);
+            a.choice2 = of_plan(a.choice2, a.ps.state);
+            a.demand1n = of_plan(a.demand1n, a.ps.state);
+            a.demand2 = of_plan(a.demand2, a.ps.state);
+            a.len = of_plan(a.len, a.ps.state);
+            a.price = of_plan(a.price, a.ps.state);
+            a.S = of_plan(a.S, a.ps.state);
+            a.scalars = of_plan(a.scalars, a.ps.state);
+        }
     }
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = threadIdx.x >> 6;
@@ -788,6 +881,7 @@ __global__ __launch_bounds__(kBlock) void k_reduce_update(FusedArgs a)
             const double u = load * st.ic;
             if constexpr (ONLY_U) {
                 a.u_pos[i] = u;
+                a.u_id[st.e] = u;
                 smax = fmax(smax, u);
             } else {
                 const double s_new = st.s + u;
@@ -804,6 +898,8 @@ __global__ __launch_bounds__(kBlock) void k_reduce_update(FusedArgs a)
     };
     const LinkState st0 = fetch(i0 + row);
     const LinkState st1 = fetch(i0 + row + kRows);
+    if constexpr (EXT)
+        if (stop_now != 0) return;           // (the same in every thread; nothing written yet)
     reduce_flat_phase<0>(p0, p1, a.pass_first_slot, a.oct_base, a.oct_mask, a.choice, a.demand1n,
                          a.choice2, a.demand2, s_part, slot0, wave, kBlock / kWave, lane);
     __syncthreads();
@@ -854,7 +950,7 @@ struct GroupArgs {
     double *len, *price, *S, *scalars;
     double eps;
     PlanStrides ps;
-    double *u_pos, *block_max_u;     // adaptive step only
+    double *u_pos, *u_id, *block_max_u;     // adaptive step only (u by position and by id)
 };
 
 // ONLY_U (adaptive step): stops at u = load / cap (by position, to a.u_pos) and leaves every
@@ -863,18 +959,21 @@ template <bool MAXC, int RL, bool EXT, bool ONLY_U = false>
 __global__ __launch_bounds__(1024) void k_group_reduce_update(GroupArgs a)
 {
     extern __shared__ double s_slots[];
+    int32_t stop_now = 0;
     if constexpr (EXT) {      // a batch (blockIdx.y is the plan) or a solve that may stop early
-        if (stopped(a.ps)) return;
-        a.choice = of_plan(a.choice, a.ps.row);
-        a.choice2 = of_plan(a.choice2, a.ps.state);
-        a.demand1n = of_plan(a.demand1n, a.ps.state);
-        a.demand2 = of_plan(a.demand2, a.ps.state);
-        a.demand1t = of_plan(a.demand1t, a.ps.state);
-        a.demand2t = of_plan(a.demand2t, a.ps.state);
-        a.len = of_plan(a.len, a.ps.state);
-        a.price = of_plan(a.price, a.ps.state);
-        a.S = of_plan(a.S, a.ps.state);
-        a.scalars = of_plan(a.scalars, a.ps.state);
+        stop_now = stop_word(a.ps);          // tested below, once the first loads are under way
+        if constexpr (!ONLY_U) {             // (the adaptive step belongs to a single plan)
+            a.choice = of_plan(a.choice, a.ps.row);
+            a.choice2 = of_plan(a.choice2, a.ps.state);
+            a.demand1n = of_plan(a.demand1n, a.ps.state);
+            a.demand2 = of_plan(a.demand2, a.ps.state);
+            a.demand1t = of_plan(a.demand1t, a.ps.state);
+            a.demand2t = of_plan(a.demand2t, a.ps.state);
+            a.len = of_plan(a.len, a.ps.state);
+            a.price = of_plan(a.price, a.ps.state);
+            a.S = of_plan(a.S, a.ps.state);
+            a.scalars = of_plan(a.scalars, a.ps.state);
+        }
     }
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -922,6 +1021,7 @@ __global__ __launch_bounds__(1024) void k_group_reduce_update(GroupArgs a)
             const double u = load * st.ic;
             if constexpr (ONLY_U) {
                 a.u_pos[i] = u;
+                a.u_id[st.e] = u;
                 smax = fmax(smax, u);
             } else {
                 const double s_new = st.s + u;
@@ -937,6 +1037,8 @@ __global__ __launch_bounds__(1024) void k_group_reduce_update(GroupArgs a)
         }
     };
     const Link first = fetch(i0 + row);
+    if constexpr (EXT)
+        if (stop_now != 0) return;           // (the same in every thread; nothing written yet)
     // tile items from wave 0 on, strip items where those end, octet passes after them
     const int nt = t1 - t0, ns = s1 - s0;
     int w = wave;
@@ -1187,6 +1289,19 @@ inline PlanStrides strides_of(const DeviceTopo &t)
     return ps;
 }
 
+// workgroups that apply the pending step (one thread per link position; the first ones of the
+// grid, so that they run beside the scan and not after it), and the arguments of a folded launch
+static int fold_blocks(const DeviceTopo &t)
+{
+    return (t.E + kWave * kRecWaves - 1) / (kWave * kRecWaves);
+}
+static FoldArgs fold_of(const DeviceTopo &t)
+{
+    FoldArgs f = *t.fold;
+    f.apply_blocks = fold_blocks(t);
+    return f;
+}
+
 template <int L, bool MAXC>
 void launch_argmin_lmax(const DeviceTopo &t, int grid, uint8_t *choice, uint32_t *count,
                         hipStream_t s)
@@ -1215,18 +1330,24 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, uint8_t *choice, uint32_t
                     const int dgrid = (t.n_rec_chunks + kRecWaves - 1) / kRecWaves;
 #define NIMBLE_RECD_LAUNCH(SS)                                                                 \
     case SS:                                                                                   \
-        if (extended(t))                                                                       \
+        if (t.fold != nullptr)                                                                 \
+            hipLaunchKernelGGL((k_argmin_recd<L, SS, MAXC, true, true>),                       \
+                               dim3(dgrid + fold_blocks(t)), dim3(kWave * kRecWaves), 0, s,    \
+                               t.n_rec_chunks, around_l2, t.rec_chunks, t.records,             \
+                               reinterpret_cast<const u32x4 *>(t.rec_dict_words), t.price,     \
+                               choice, count, t.choice2, strides_of(t), fold_of(t));           \
+        else if (extended(t))                                                                  \
             hipLaunchKernelGGL((k_argmin_recd<L, SS, MAXC, true>), dim3(dgrid, t.batch),       \
                                dim3(kWave * kRecWaves), 0, s, t.n_rec_chunks, around_l2,       \
                                t.rec_chunks, t.records,                                        \
                                reinterpret_cast<const u32x4 *>(t.rec_dict_words), t.price,     \
-                               choice, count, t.choice2, strides_of(t));                       \
+                               choice, count, t.choice2, strides_of(t), NoFold{0});            \
         else                                                                                   \
             hipLaunchKernelGGL((k_argmin_recd<L, SS, MAXC, false>), dim3(dgrid),               \
                                dim3(kWave * kRecWaves), 0, s, t.n_rec_chunks, around_l2,       \
                                t.rec_chunks, t.records,                                        \
                                reinterpret_cast<const u32x4 *>(t.rec_dict_words), t.price,     \
-                               choice, count, t.choice2, strides_of(t));                       \
+                               choice, count, t.choice2, strides_of(t), NoFold{0});            \
         return;
                     switch (t.rec_stride) {
                         NIMBLE_RECD_LAUNCH(1)
@@ -1239,20 +1360,26 @@ void launch_argmin_lmax(const DeviceTopo &t, int grid, uint8_t *choice, uint32_t
                 }
 #define NIMBLE_RECL_LAUNCH(SS)                                                                 \
     case SS:                                                                                   \
-        if (t.rec_table16 && extended(t))                                                      \
+        if (t.rec_table16 && t.fold != nullptr)                                                \
+            hipLaunchKernelGGL((k_argmin_recl<L, SS, MAXC, true, true, true>),                 \
+                               dim3(rec_grid + fold_blocks(t)), dim3(kWave * kRecWaves), 0, s, \
+                               t.n_records, around_l2, t.records, t.price, choice, count,      \
+                               t.choice2, strides_of(t), fold_of(t));                          \
+        else if (t.rec_table16 && extended(t))                                                 \
             hipLaunchKernelGGL((k_argmin_recl<L, SS, MAXC, true, true>),                       \
                                dim3(rec_grid, t.batch), dim3(kWave * kRecWaves), 0, s,         \
                                t.n_records, around_l2, t.records, t.price, choice, count,      \
-                               t.choice2, strides_of(t));                                      \
+                               t.choice2, strides_of(t), NoFold{0});                           \
         else if (t.rec_table16)                                                                \
             hipLaunchKernelGGL((k_argmin_recl<L, SS, MAXC, true, false>), dim3(rec_grid),      \
                                dim3(kWave * kRecWaves), 0, s, t.n_records, around_l2,          \
-                               t.records, t.price, choice, count, t.choice2, strides_of(t));   \
+                               t.records, t.price, choice, count, t.choice2, strides_of(t),    \
+                               NoFold{0});                                                     \
         else                                                                                   \
             hipLaunchKernelGGL((k_argmin_recl<L, SS, MAXC, false, true>),                      \
                                dim3(rec_grid, t.batch), dim3(kWave * kRecWaves), 0, s,         \
                                t.n_records, around_l2, t.records, t.price, choice, count,      \
-                               t.choice2, strides_of(t));                                      \
+                               t.choice2, strides_of(t), NoFold{0});                           \
         return;
                 switch (t.rec_stride) {
                     NIMBLE_RECL_LAUNCH(1)
@@ -1492,6 +1619,25 @@ void launch_argmin(const DeviceTopo &t, uint8_t *choice, uint32_t *count, hipStr
     else launch_argmin_l<false>(t, choice, count, s);
 }
 
+// The kernels that take a folded step are the lane-major record kernels (16-bit tables or a
+// dictionary); launch_argmin_l and launch_argmin_lmax choose them under these conditions.
+// Folding pays while the scan waits rather than works: three gathers per table entry instead
+// of one cost about 0.1 us for every record a compute unit scans, a launch saved about 2 us
+// (64-node fabric, 64 records per compute unit: 4 us per iteration slower; 16-node fabric, 3
+// records per compute unit: 2 us faster).  Hence only while all records are scanned at once.
+bool record_kernel_folds(const DeviceTopo &t, bool whenever_possible)
+{
+    if (t.n_records <= 0 || !t.rec_lane_major || t.batch > 1) return false;
+    if (!whenever_possible && t.n_records > t.rec_blocks * kRecWaves) return false;
+    if (!t.rec_dict && !t.rec_table16) return false;
+    const int quads = (t.pmax + 3) / 4;
+    int L = 1;
+    while (2 * L < quads && L < kWave) L <<= 1;
+    if (t.rec_lanes > 0) L = t.rec_lanes;
+    if (L < 2 || L > 16) return false;
+    return t.rec_stride >= 1 && t.rec_stride <= 5;
+}
+
 void launch_load_reduce(const DeviceTopo &t, const uint8_t *choice, const double *demand,
                         hipStream_t s)
 {
@@ -1562,15 +1708,17 @@ static GroupArgs group_args(const DeviceTopo &t, const uint8_t *choice, double e
     a.eps = eps;
     a.ps = strides_of(t);
     a.u_pos = nullptr;
+    a.u_id = nullptr;
     a.block_max_u = nullptr;
     return a;
 }
 
-int launch_group_reduce_u(const DeviceTopo &t, const uint8_t *choice, double *u_pos,
+int launch_group_reduce_u(const DeviceTopo &t, const uint8_t *choice, double *u_pos, double *u_id,
                           double *block_max_u, hipStream_t s)
 {
     GroupArgs a = group_args(t, choice, 0.0);
     a.u_pos = u_pos;
+    a.u_id = u_id;
     a.block_max_u = block_max_u;
     const dim3 block(kWave * t.gblk_waves);
     const size_t lds = sizeof(double) * static_cast<size_t>(t.gblk_max_slots > 16 ? t.gblk_max_slots : 16);
@@ -1631,6 +1779,7 @@ void launch_reduce_update(const DeviceTopo &t, const uint8_t *choice, const doub
     a.ps = strides_of(t);
     a.n_plans = t.batch;
     a.u_pos = nullptr;
+    a.u_id = nullptr;
     a.block_max_u = nullptr;
     constexpr int kPlansPerBlock = 4;
     if (t.batch >= kPlansPerBlock && t.batch_kernel == 0) {
@@ -1660,7 +1809,7 @@ void launch_reduce_update(const DeviceTopo &t, const uint8_t *choice, const doub
     }
 }
 
-int launch_reduce_u(const DeviceTopo &t, const uint8_t *choice, double *u_pos,
+int launch_reduce_u(const DeviceTopo &t, const uint8_t *choice, double *u_pos, double *u_id,
                     double *block_max_u, hipStream_t s)
 {
     FusedArgs a;
@@ -1683,6 +1832,7 @@ int launch_reduce_u(const DeviceTopo &t, const uint8_t *choice, double *u_pos,
     a.ps = strides_of(t);
     a.n_plans = 1;
     a.u_pos = u_pos;
+    a.u_id = u_id;
     a.block_max_u = block_max_u;
     hipLaunchKernelGGL((k_reduce_update<false, true, true>), dim3(t.n_blocks), dim3(kBlock), 0, s,
                        a);

@@ -9,6 +9,7 @@
 #include <type_traits>
 
 #include "host_topo.hpp"
+#include "kernels.hpp"
 #include "wave_ops.hpp"
 
 namespace nimble {
@@ -703,6 +704,55 @@ __device__ __forceinline__ double width_phase(int E,
         if (i < E) m = fmax(m, reach * invcap_pos[i]);
     }
     return m;
+}
+
+// One workgroup's share of a step of the adaptive solve (Sec. IV-B with the step sigma = 1 /
+// max_e u_e): thread i of block `block` owns link position block * 256 + i (workgroups of 256
+// threads).  `red` is shared scratch of 16 doubles.  Every block folds all the maxima of u
+// itself.
+template <bool MAXC>
+__device__ __forceinline__ void ad_apply_block(const AdApplyArgs &a, int block, double *red)
+{
+    // the stop word, the link's own state and the maxima are requested together (threads past
+    // the last link re-read it), so that one trip to memory serves all three
+    const int32_t stop_now = *static_cast<const volatile int32_t *>(a.flags);
+    const int i = block * 256 + static_cast<int>(threadIdx.x);
+    const int ic = i < a.E ? i : a.E - 1;
+    const double u_i = a.u_pos[ic];
+    const double s_old = a.S[ic];
+    const double l_old = a.len[ic];
+    const double cap_i = a.invcap_pos[ic];
+    const int e_i = a.pos_link[ic];
+    const double m = max_of_strided<256>(a.block_max_u, a.n_u_blocks, threadIdx.x);
+    if (stop_now != 0) return;
+    const double umax = block_max(m, red);
+    if (!(umax > 0.0)) {                               // no traffic at all: the solve ends here
+        if (block == 0 && threadIdx.x == 0) a.flags[0] = 1;
+        return;
+    }
+    const double sigma = 1.0 / umax;
+    double s_new = 0.0;
+    if (i < a.E) {
+        const double su = sigma * u_i;
+        s_new = s_old + su;
+        a.S[i] = s_new;
+        const double t1 = a.eps * su;
+        const double t2 = 1.0 + t1;
+        const double ln = l_old * t2;
+        a.len[i] = ln;
+        a.len_id_new[e_i] = ln;
+        a.price[e_i] = MAXC ? ln : ln * cap_i;
+    }
+    __syncthreads();
+    const double sm = block_max(s_new, red);
+    if (threadIdx.x == 0) {
+        a.block_max_s[block] = sm;
+        if (block == 0) {
+            a.ascal[0] = a.ascal[0] + sigma;
+            a.sigma_log[a.flags[1]] = sigma;
+            a.flags[1] = a.flags[1] + 1;
+        }
+    }
 }
 
 }  // namespace nimble

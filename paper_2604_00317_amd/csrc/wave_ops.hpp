@@ -221,6 +221,26 @@ __device__ __forceinline__ double wave_max(double v)
     return v;
 }
 
+// max(x[first], x[first + STRIDE], ...) over the entries below n (0 when there is none; the
+// entries are not negative): eight loads are requested side by side, so that the count of trips
+// to memory is an eighth of the count of entries.
+template <int STRIDE>
+__device__ __forceinline__ double max_of_strided(const double *x, int n, int first)
+{
+    double m = 0.0;
+    for (int base = first; base < n; base += 8 * STRIDE) {
+        double v[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int b = base + q * STRIDE;
+            v[q] = x[b < n ? b : n - 1];
+        }
+#pragma unroll
+        for (int q = 0; q < 8; ++q) m = fmax(m, v[q]);
+    }
+    return m;
+}
+
 // Block-wide max for blocks of up to 1024 threads; `red` is shared scratch of >= 16 doubles.
 // Returns the maximum in every thread.
 __device__ __forceinline__ double block_max(double v, double *red)

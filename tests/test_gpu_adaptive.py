@@ -16,11 +16,13 @@ def B():
     return binding
 
 
-def gpu_adaptive(B, topo, demand, eps, max_iters, check_every, flags=0):
+def gpu_adaptive(B, topo, demand, eps, max_iters, check_every, flags=0, folds=None):
     import torch
     h = B.nimble_topo_create(topo.n_links, topo.cap, topo.n_comm, topo.comm_path_ptr,
                              topo.n_paths, topo.path_link_ptr, topo.path_links, flags)
     try:
+        if folds is not None:
+            assert h.adaptive_folds == folds
         d = torch.as_tensor(np.ascontiguousarray(demand, dtype=np.float64)).to("cuda:0")
         splits = torch.full((topo.n_paths,), float("nan"), dtype=torch.float64, device="cuda:0")
         lam = torch.full((1,), float("nan"), dtype=torch.float64, device="cuda:0")
@@ -30,9 +32,10 @@ def gpu_adaptive(B, topo, demand, eps, max_iters, check_every, flags=0):
         h.close()
 
 
-def check(oracle_mod, B, topo, demand, eps, max_iters, check_every, flags=0):
+def check(oracle_mod, B, topo, demand, eps, max_iters, check_every, flags=0, folds=None):
     ref = oracle_mod.solve_adaptive(*topo.csr(), demand, eps, max_iters, check_every, flags=flags)
-    splits, lam, iters, lb = gpu_adaptive(B, topo, demand, eps, max_iters, check_every, flags)
+    splits, lam, iters, lb = gpu_adaptive(B, topo, demand, eps, max_iters, check_every, flags,
+                                          folds)
     assert iters == ref["iters"]
     assert lb == ref["lb"]
     assert lam == ref["lam"]
@@ -67,6 +70,46 @@ def test_random_topologies(oracle_mod, B, seed):
     t = W.random_topology(rng, 60, 300, 20, 4)
     d = rng.integers(0, 1 << 24, size=t.n_comm).astype(np.float64)
     check(oracle_mod, B, t, d, 0.1, 400, 5)
+
+
+@pytest.mark.parametrize("fold", [0, 1])
+def test_step_applied_inside_the_next_record_kernel_or_on_its_own(oracle_mod, B, monkeypatch, fold):
+    """Where the record kernel can, the step of an iteration is applied inside the record kernel
+    of the next one, its prices formed on the fly; a switch read at create forces either way.
+    Both must give the oracle's bits: every check period from 1 (a stop test after every
+    iteration) up, limits of 1, 2 and 3 iterations, the limit reached on a check and between two
+    checks, both cost rules, inline and dictionary records (configuration 4: 30 iterations)."""
+    monkeypatch.setenv("NIMBLE_TUNE_ADAPTIVE_FOLD", str(fold))
+    w = W.make_config(3)
+    for max_iters, check_every in ((1, 1), (2, 1), (3, 2), (40, 1), (40, 7), (50, 25), (60, 100)):
+        print(f"[adaptive fold={fold}] config 3 max_iters={max_iters} check_every={check_every}",
+              flush=True)
+        check(oracle_mod, B, w.topo, w.traffic, w.eps, max_iters, check_every, folds=bool(fold))
+    print(f"[adaptive fold={fold}] config 3 to the stop", flush=True)
+    ref = check(oracle_mod, B, w.topo, w.traffic, w.eps, 5000, 3, folds=bool(fold))
+    assert ref["iters"] < 5000
+    print(f"[adaptive fold={fold}] config 3, bottleneck cost", flush=True)
+    check(oracle_mod, B, w.topo, w.traffic, w.eps, 30, 10, flags=1, folds=bool(fold))
+    w = W.make_config(4)
+    print(f"[adaptive fold={fold}] config 4, 30 iterations", flush=True)
+    check(oracle_mod, B, w.topo, w.traffic, w.eps, 30, 10, folds=bool(fold))
+    rng = np.random.default_rng(11)
+    t = W.random_topology(rng, 60, 300, 20, 4)
+    d = rng.integers(0, 1 << 24, size=t.n_comm).astype(np.float64)
+    print(f"[adaptive fold={fold}] random topology", flush=True)
+    check(oracle_mod, B, t, d, 0.1, 200, 4)
+
+
+def test_default_choice_of_where_the_step_is_applied(B):
+    """Folding pays while every record is scanned at once: the 16-node fabric folds, the 64-node
+    one (64 records per compute unit) does not."""
+    for cfg, folds in ((3, True), (4, False)):
+        w = W.make_config(cfg)
+        h = B.nimble_topo_create(*w.topo.csr())
+        try:
+            assert h.adaptive_folds == folds
+        finally:
+            h.close()
 
 
 def test_zero_traffic(oracle_mod, B):
