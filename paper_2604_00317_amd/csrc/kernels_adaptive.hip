@@ -67,13 +67,28 @@ __global__ __launch_bounds__(kAdSumBlock) void k_ad_bound_sums(
     if (alpha) {
         if (i < K) {
             const int p = cp[i] + choice[i];
+            const int q0 = lp[p], q1 = lp[p + 1];
+            const double dm = demand[i];
             double c = 0.0;
-            for (int q = lp[p]; q < lp[p + 1]; ++q) {
-                const double pe = price[pl[q]];
-                if constexpr (MAXC) c = (pe > c) ? pe : c;
-                else c = c + pe;
+            // eight links at a time: their ids are requested side by side, then their prices,
+            // and only then are the prices added in path order (two trips to memory for a path
+            // of up to eight links instead of two per link)
+            for (int base = q0; base < q1; base += 8) {
+                int id[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) id[j] = pl[base + j < q1 ? base + j : q1 - 1];
+                double pe[8];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) pe[j] = price[id[j]];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    if (base + j < q1) {
+                        if constexpr (MAXC) c = (pe[j] > c) ? pe[j] : c;
+                        else c = c + pe[j];
+                    }
+                }
             }
-            v = demand[i] * c;
+            v = dm * c;
         }
     } else if (i < E) {
         v = len[pos_of_link[i]];
