@@ -727,15 +727,22 @@ __global__ __launch_bounds__(kWave) void k_histogram(int K, int iters, int pmax,
     for (int j = 0; j < pmax; ++j) mine[j] = 0u;
     if (k < K) {
         const uint8_t *col = log + k;
+        // counts are whole numbers, so their order is free: the choices of sixteen iterations
+        // are requested side by side and counted with LDS additions that return nothing (no
+        // read-modify-write chain from one iteration to the next)
+        auto bump = [&](int c) {
+            (void)__hip_atomic_fetch_add(mine + c, 1u, __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_WORKGROUP);
+        };
         int t = 0;
-        for (; t + 8 <= iters; t += 8) {
-            uint8_t c[8];
+        for (; t + 16 <= iters; t += 16) {
+            uint8_t c[16];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) c[u] = col[size_t(t + u) * stride];
+            for (int u = 0; u < 16; ++u) c[u] = col[size_t(t + u) * stride];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) mine[c[u]] += 1u;
+            for (int u = 0; u < 16; ++u) bump(c[u]);
         }
-        for (; t < iters; ++t) mine[col[size_t(t) * stride]] += 1u;
+        for (; t < iters; ++t) bump(col[size_t(t) * stride]);
         const int p0 = cp[k], np = cp[k + 1] - p0;
         const double T = static_cast<double>(iters);
         for (int j = 0; j < np; ++j) splits[p0 + j] = static_cast<double>(mine[j]) / T;
