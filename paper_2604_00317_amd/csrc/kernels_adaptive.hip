@@ -236,9 +236,10 @@ __global__ __launch_bounds__(kWave) void k_ad_histogram(int K, int pmax, size_t 
     const int k = blockIdx.x * kWave + lane;
     const int iters = flags[1];
     const double W = ascal[0];
-    const int row = pmax | 1;                      // odd row length: conflict-free columns
-    double *mine = s_w + lane * row;
-    for (int j = 0; j < pmax; ++j) mine[j] = 0.0;
+    // weight j of this lane's commodity is entry j * 64 + lane: whatever the lanes choose, they
+    // spread evenly over the banks
+    double *mine = s_w + lane;
+    for (int j = 0; j < pmax; ++j) mine[j * kWave] = 0.0;
     if (k < K) {
         const uint8_t *col = log + k;
         // the choices of sixteen iterations are requested side by side; the additions stay in
@@ -249,15 +250,16 @@ __global__ __launch_bounds__(kWave) void k_ad_histogram(int K, int pmax, size_t 
 #pragma unroll
             for (int j = 0; j < 16; ++j) c[j] = col[size_t(t + j) * stride];
 #pragma unroll
-            for (int j = 0; j < 16; ++j) mine[c[j]] = mine[c[j]] + sigma_log[t + j];
+            for (int j = 0; j < 16; ++j)
+                mine[c[j] * kWave] = mine[c[j] * kWave] + sigma_log[t + j];
         }
         for (; t < iters; ++t) {
             const int c = col[size_t(t) * stride];
-            mine[c] = mine[c] + sigma_log[t];
+            mine[c * kWave] = mine[c * kWave] + sigma_log[t];
         }
         const int p0 = cp[k], np = cp[k + 1] - p0;
         for (int j = 0; j < np; ++j)
-            splits[p0 + j] = W > 0.0 ? mine[j] / W : (j == 0 ? 1.0 : 0.0);
+            splits[p0 + j] = W > 0.0 ? mine[j * kWave] / W : (j == 0 ? 1.0 : 0.0);
     }
     if (blockIdx.x == 0 && lane == 0) lambda[0] = ascal[3];
 }

@@ -722,16 +722,17 @@ __global__ __launch_bounds__(kWave) void k_histogram(int K, int iters, int pmax,
     extern __shared__ uint32_t s_cnt[];
     const int lane = threadIdx.x;
     const int k = blockIdx.x * kWave + lane;
-    const int row = pmax | 1;                      // odd row length: conflict-free columns
-    uint32_t *mine = s_cnt + lane * row;
-    for (int j = 0; j < pmax; ++j) mine[j] = 0u;
+    // counter j of this lane's commodity is word j * 64 + lane: whatever the lanes choose,
+    // lanes l and l + 32 share a bank and nobody else does
+    uint32_t *mine = s_cnt + lane;
+    for (int j = 0; j < pmax; ++j) mine[j * kWave] = 0u;
     if (k < K) {
         const uint8_t *col = log + k;
         // counts are whole numbers, so their order is free: the choices of sixteen iterations
         // are requested side by side and counted with LDS additions that return nothing (no
         // read-modify-write chain from one iteration to the next)
         auto bump = [&](int c) {
-            (void)__hip_atomic_fetch_add(mine + c, 1u, __ATOMIC_RELAXED,
+            (void)__hip_atomic_fetch_add(mine + c * kWave, 1u, __ATOMIC_RELAXED,
                                          __HIP_MEMORY_SCOPE_WORKGROUP);
         };
         int t = 0;
@@ -745,7 +746,7 @@ __global__ __launch_bounds__(kWave) void k_histogram(int K, int iters, int pmax,
         for (; t < iters; ++t) bump(col[size_t(t) * stride]);
         const int p0 = cp[k], np = cp[k + 1] - p0;
         const double T = static_cast<double>(iters);
-        for (int j = 0; j < np; ++j) splits[p0 + j] = static_cast<double>(mine[j]) / T;
+        for (int j = 0; j < np; ++j) splits[p0 + j] = static_cast<double>(mine[j * kWave]) / T;
     }
 }
 
