@@ -367,7 +367,8 @@ def main() -> int:
                         check_every=check_every, lambda_=lam_ad, lower_bound=lb,
                         gap=lam_ad / lb if lb > 0 else None, target_gap=(1 + w.eps) ** 2,
                         lambda_fixed_step=lam_fixed, fixed_step_iters=w.iters,
-                        fixed_step_ms=ms_per_step)
+                        fixed_step_ms=ms_per_step,
+                        launches_per_iteration=2 if h.adaptive_folds else 3)
     h.close()
     del r
 
@@ -404,7 +405,8 @@ def main() -> int:
                         ks["reduce_update" if ph == 1 and not b3["update"] else name] = dict(
                             back_to_back_us=sec * 1e6, bytes=b3[name])
                 entry["kernels"] = ks
-                # the adaptive step on the same fabric (three launches per iteration)
+                # the adaptive step on the same fabric (two launches per iteration where the
+                # step is applied inside the next record kernel, else three)
                 ws = q["w"]
                 for _ in range(2):
                     torch.cuda.synchronize()
@@ -416,7 +418,9 @@ def main() -> int:
                 entry["adaptive_step"] = dict(iterations=n_ad, ms_per_plan=dt_ad * 1e3,
                                               us_per_iteration=dt_ad * 1e6 / n_ad, check_every=25,
                                               lower_bound=lb_ad,
-                                              lambda_=float(q["d_lambda"].item()))
+                                              lambda_=float(q["d_lambda"].item()),
+                                              launches_per_iteration=2 if q["h"].adaptive_folds
+                                              else 3)
             if cfg == 3 and plans and single_c3:
                 entry["speedup_over_one_plan_at_a_time"] = entry["plans_per_s"] / single_c3
             if cfg == 2:
